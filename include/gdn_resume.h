@@ -1,0 +1,170 @@
+/*
+ * gdn_resume — resume-from-checkpoint GatedDeltaNet prefill with sparse checkpoint emission,
+ * for one MI355X (gfx950).  C ABI: plain pointers and sizes, no framework types.
+ *
+ * The operation (Sec. 3 and Remark 1 of the paper, "Sparse Prefix Caching for Hybrid and
+ * Recurrent LLM Serving"): a cached prefix of length N keeps exact recurrent states at a
+ * sparse set of checkpoint positions C = {c_1 < ... < c_M}.  A request that overlaps the
+ * prefix up to depth t loads the state of the deepest checkpoint l(t;C) = max({0} u {c <= t}),
+ * replays only the tokens after it, and may store the exact states it passes at further
+ * checkpoint positions.  The state "at position c" is the state after consuming tokens 1..c;
+ * position 0 is the zero state.
+ *
+ * The recurrent update replayed is the gated delta rule of a GatedDeltaNet layer, per value
+ * head, with state S (d_v x d_k, fp32, row-major [d_v][d_k]):
+ *     S~ = a_t S_{t-1};  u_t = b_t (v_t - S~ k_t);  S_t = S~ + u_t k_t^T;  o_t = scale * S_t q_t.
+ *
+ * Conventions common to every entry point
+ *   - "host" pointers are read during the call and may be freed on return; "device" pointers
+ *     are HIP device memory owned by the caller and must stay valid until the work enqueued
+ *     on `stream` has finished.  `stream` is a hipStream_t passed as void* (NULL = default).
+ *   - No entry point allocates or frees device memory and none synchronises the stream,
+ *     except that gdn_resume_prefill may wait (on the host) for its previous call's plan
+ *     upload to leave a small pinned staging buffer the library owns.
+ *   - Every argument is validated on the host before anything is enqueued; on error nothing
+ *     is enqueued and a negative code is returned.  HIP failures return GDN_ERR_HIP - hipError.
+ *   - A checkpoint slot holds the states of all layers and value heads of one position:
+ *     [L][H_v][d_v][d_k] fp32, contiguous; a pool is slots at a fixed stride (in floats).
+ */
+#ifndef GDN_RESUME_H
+#define GDN_RESUME_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    GDN_OK = 0,
+    GDN_ERR_NULL = -1,        /* a required pointer is NULL */
+    GDN_ERR_ALIGN = -2,       /* a device pointer or stride is not 16-byte aligned */
+    GDN_ERR_SHAPE = -3,       /* unsupported head size / dtype, H_v not a multiple of H_qk, ... */
+    GDN_ERR_SEQLENS = -4,     /* cu_seqlens not starting at 0, decreasing, or beyond T_alloc */
+    GDN_ERR_SLOT_RANGE = -5,  /* a slot id outside its pool (sources may be -1) */
+    GDN_ERR_SLOT_DUP = -6,    /* two states written to the same destination slot */
+    GDN_ERR_SLOT_HAZARD = -7, /* a destination slot is another request's source slot in the same pool */
+    GDN_ERR_EMIT = -8,        /* emit positions not strictly increasing inside (start, end] */
+    GDN_ERR_WORKSPACE = -9,   /* workspace NULL, misaligned or too small */
+    GDN_ERR_START = -10,      /* negative start position, or positions overflowing int32 */
+    GDN_ERR_COUNT = -11,      /* a negative count */
+    GDN_ERR_HIP = -1000       /* GDN_ERR_HIP - (int)hipError_t */
+};
+
+enum { GDN_F32 = 0, GDN_BF16 = 1 };
+
+/* Number of tokens one chunk of the kernels covers (kernel-internal granularity; positions
+ * need not be aligned to it). */
+#define GDN_CHUNK 64
+
+typedef struct gdn_shape {
+    int32_t L;         /* stacked recurrent layers, independent problems with their own inputs */
+    int32_t H_qk;      /* query/key heads */
+    int32_t H_v;       /* value heads, a multiple of H_qk; value head h uses q/k head h / (H_v/H_qk) */
+    int32_t d_k;       /* 64 or 128 */
+    int32_t d_v;       /* 64 or 128 */
+    int32_t in_dtype;  /* GDN_F32 or GDN_BF16: type of q, k, v, beta, gate */
+    int32_t o_dtype;   /* GDN_F32 or GDN_BF16: type of o */
+    float scale;       /* o_t = scale * S_t q_t; 1.0 for the plain definition */
+    int64_t T_alloc;   /* tokens per layer plane of the token tensors (>= total tokens) */
+} gdn_shape;
+
+/*
+ * Sec. 3, l(t;C): index i of the deepest checkpoint pos[i] <= t, or -1 when there is none
+ * (resume from the zero state at position 0).  pos: host, M strictly increasing positions.
+ * Pure host function.  Returns GDN_ERR_NULL (-1 cannot be told apart, so M > 0 with a NULL
+ * pos returns -1 as well: "no checkpoint").
+ */
+int32_t gdn_deepest_ckpt(const int32_t *pos, int32_t M, int32_t t);
+
+/*
+ * Host-only chunk planner (exposed for tests; gdn_resume_prefill runs the same code).
+ * Splits every request's token range at its emit positions and then into pieces of at most
+ * GDN_CHUNK tokens.  Outputs (host arrays of `capacity` entries, req_chunk_cu of n_req+1):
+ *   chunk_tok0[c]  first packed token of chunk c      chunk_len[c]  1..GDN_CHUNK tokens
+ *   chunk_emit[c]  flat index into emit_pos of the emission at the end of chunk c, or -1
+ *   req_chunk_cu   request r owns chunks [req_chunk_cu[r], req_chunk_cu[r+1])
+ * Returns the number of chunks, GDN_ERR_WORKSPACE when capacity is too small, or the
+ * validation error of the index arrays (GDN_ERR_SEQLENS / _START / _EMIT / _NULL / _COUNT).
+ */
+int32_t gdn_plan_chunks(int32_t n_req, const int32_t *cu_seqlens, const int32_t *start_pos,
+                        const int32_t *emit_cu, const int32_t *emit_pos,
+                        int32_t *chunk_tok0, int32_t *chunk_len, int32_t *chunk_emit,
+                        int32_t *req_chunk_cu, int32_t capacity);
+
+/*
+ * Upper bound, in bytes, of the workspace gdn_resume_prefill needs for a call with this
+ * shape, n_req requests, total_tokens packed tokens and n_emit emissions.  Negative on error.
+ */
+int64_t gdn_workspace_bytes(const gdn_shape *shape, int32_t n_req, int64_t total_tokens,
+                            int32_t n_emit);
+
+/*
+ * Checkpoint load (Sec. 6, overhead decomposition, item (i): loading the stored checkpoint),
+ * here from a pool in HBM:  dst[i] = pool[slot_ids[i]] for i < n, zeros when slot_ids[i] == -1.
+ *   pool      device, fp32, n_slots slots at slot_stride floats
+ *   slot_ids  host, n ids in [-1, n_slots)
+ *   dst       device, n states at dst_stride floats;  state_elems floats are copied per state
+ * state_elems and both strides must be multiples of 4, pointers 16-byte aligned,
+ * strides >= state_elems.  Bit-exact copy.  dst must not overlap the pool.
+ */
+int32_t ckpt_gather(const float *pool, int64_t slot_stride, int32_t n_slots,
+                    const int32_t *slot_ids, int32_t n,
+                    float *dst, int64_t dst_stride, int64_t state_elems, void *stream);
+
+/*
+ * Checkpoint store: pool[slot_ids[i]] = src[i] for i < n.  Same argument rules as
+ * ckpt_gather; ids in [0, n_slots); a repeated id is GDN_ERR_SLOT_DUP.  Bit-exact copy.
+ */
+int32_t ckpt_scatter(float *pool, int64_t slot_stride, int32_t n_slots,
+                     const int32_t *slot_ids, int32_t n,
+                     const float *src, int64_t src_stride, int64_t state_elems, void *stream);
+
+/*
+ * The resumed prefill (Sec. 3: replay of tokens l+1..t from the state at l; Remark 1: the
+ * result equals a full replay; Sec. 5 "Capturing checkpoints": states at checkpoint positions
+ * are captured, here inside the same pass).
+ *
+ * Token tensors (device) are packed over requests, token-major, one plane per layer:
+ *   q, k        [L][T_alloc][H_qk][d_k]        v, o   [L][T_alloc][H_v][d_v]
+ *   beta, gate  [L][T_alloc][H_v]              gate is a_t in (0,1], not its logarithm
+ * Request r owns packed tokens [cu_seqlens[r], cu_seqlens[r+1]); they are the tokens at
+ * absolute positions start_pos[r]+1 .. of its sequence.  A zero-length request is legal and
+ * does nothing.  bf16 inputs must be finite and below 65504 in magnitude (they are widened
+ * exactly to fp16 for the matrix cores).
+ *
+ *   cu_seqlens  host int32 [n_req+1], cu_seqlens[0] == 0, non-decreasing, last <= T_alloc
+ *   start_pos   host int32 [n_req], >= 0: position l_r of the loaded state
+ *   state_src   device fp32 pool read for start states (may be NULL when every src_slot is -1)
+ *   src_slot    host int32 [n_req] in [-1, src_n_slots): slot of the start state, -1 = zeros
+ *   emit_cu     host int32 [n_req+1]; request r stores emissions [emit_cu[r], emit_cu[r+1])
+ *   emit_pos    host int32 [n_emit]: absolute positions, strictly increasing per request,
+ *               inside (start_pos[r], start_pos[r] + len_r]
+ *   state_dst   device fp32 pool written with the emitted states (may equal state_src)
+ *   emit_slot   host int32 [n_emit] in [0, dst_n_slots), all distinct; when state_dst and
+ *               state_src are the same pool, a destination may not be the source slot of a
+ *               different request of this call
+ *   o           device, written for every packed token
+ *   workspace   device, 256-byte aligned, at least gdn_workspace_bytes(...) bytes; contents
+ *               are scratch, nothing is carried between calls
+ * Outputs: o within the stated tolerance of the token-by-token definition, emitted states
+ * likewise, slot indexing exact.  Calls that share a workspace must be ordered on one stream.
+ */
+int32_t gdn_resume_prefill(const gdn_shape *shape,
+                           const void *q, const void *k, const void *v,
+                           const void *beta, const void *gate,
+                           int32_t n_req, const int32_t *cu_seqlens, const int32_t *start_pos,
+                           const float *state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                           const int32_t *src_slot,
+                           const int32_t *emit_cu, const int32_t *emit_pos,
+                           float *state_dst, int64_t dst_slot_stride, int32_t dst_n_slots,
+                           const int32_t *emit_slot,
+                           void *o, void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Version of the library (major * 100 + minor). */
+int32_t gdn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GDN_RESUME_H */

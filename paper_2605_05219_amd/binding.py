@@ -1,0 +1,174 @@
+"""Thin ctypes binding of the C ABI in include/gdn_resume.h: argument marshalling only.
+
+Device buffers are torch tensors (torch is used for device memory and streams, nothing
+else); index arrays are host numpy int32.  Every step of the path runs inside the library.
+The library must be present: there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libgdn_resume.so")
+
+GDN_F32, GDN_BF16 = 0, 1
+GDN_CHUNK = 64
+
+ERRORS = {
+    -1: "GDN_ERR_NULL", -2: "GDN_ERR_ALIGN", -3: "GDN_ERR_SHAPE", -4: "GDN_ERR_SEQLENS",
+    -5: "GDN_ERR_SLOT_RANGE", -6: "GDN_ERR_SLOT_DUP", -7: "GDN_ERR_SLOT_HAZARD", -8: "GDN_ERR_EMIT",
+    -9: "GDN_ERR_WORKSPACE", -10: "GDN_ERR_START", -11: "GDN_ERR_COUNT",
+}
+
+
+class GdnError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = int(code)
+        name = ERRORS.get(self.code, f"GDN_ERR_HIP(hipError {-1000 - self.code})" if self.code <= -1000 else "?")
+        super().__init__(f"{where} failed: {self.code} {name}")
+
+
+class gdn_shape(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int32), ("H_qk", ctypes.c_int32), ("H_v", ctypes.c_int32),
+                ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32), ("in_dtype", ctypes.c_int32),
+                ("o_dtype", ctypes.c_int32), ("scale", ctypes.c_float), ("T_alloc", ctypes.c_int64)]
+
+
+_lib = None
+_vp, _i32, _i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+
+
+def lib():
+    """The loaded library; raises when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2605_05219_amd.build)")
+        L = ctypes.CDLL(LIB_PATH)
+        L.gdn_version.restype = _i32
+        L.gdn_deepest_ckpt.restype = _i32
+        L.gdn_deepest_ckpt.argtypes = [_vp, _i32, _i32]
+        L.gdn_plan_chunks.restype = _i32
+        L.gdn_plan_chunks.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32]
+        L.gdn_workspace_bytes.restype = _i64
+        L.gdn_workspace_bytes.argtypes = [ctypes.POINTER(gdn_shape), _i32, _i64, _i32]
+        L.ckpt_gather.restype = _i32
+        L.ckpt_gather.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
+        L.ckpt_scatter.restype = _i32
+        L.ckpt_scatter.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
+        L.gdn_resume_prefill.restype = _i32
+        L.gdn_resume_prefill.argtypes = ([ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _vp]
+                                         + [_vp, _i64, _i32, _vp] + [_vp, _vp]
+                                         + [_vp, _i64, _i32, _vp] + [_vp, _vp, _i64, _vp])
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["gdn_version", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+           "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill"]
+
+
+def _h32(x) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x, dtype=np.int32))
+
+
+def _hp(a: Optional[np.ndarray]):
+    return _vp(a.ctypes.data) if a is not None and a.size else _vp(0)
+
+
+def _dp(t):
+    return _vp(t.data_ptr()) if t is not None else _vp(0)
+
+
+def _stream_ptr(stream=None):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return _vp(s.cuda_stream)
+
+
+def _check(rc: int, where: str) -> int:
+    if rc < 0:
+        raise GdnError(rc, where)
+    return rc
+
+
+def make_shape(L, H_qk, H_v, d_k, d_v, in_dtype, o_dtype, T_alloc, scale=1.0) -> gdn_shape:
+    code = {"f32": GDN_F32, "bf16": GDN_BF16, GDN_F32: GDN_F32, GDN_BF16: GDN_BF16}
+    return gdn_shape(L, H_qk, H_v, d_k, d_v, code[in_dtype], code[o_dtype], float(scale), int(T_alloc))
+
+
+# ----------------------------------------------------------------------------- host-only entry points
+def gdn_version() -> int:
+    return int(lib().gdn_version())
+
+
+def gdn_deepest_ckpt(pos: Sequence[int], t: int) -> int:
+    p = _h32(pos)
+    return int(lib().gdn_deepest_ckpt(_hp(p), int(p.size), int(t)))
+
+
+def gdn_plan_chunks(cu_seqlens, start_pos, emit_cu, emit_pos, capacity: Optional[int] = None):
+    cu, sp, ecu, epos = _h32(cu_seqlens), _h32(start_pos), _h32(emit_cu), _h32(emit_pos)
+    n_req = int(sp.size)
+    if capacity is None:
+        capacity = int(cu[-1]) // GDN_CHUNK + n_req + int(epos.size) + 1 if cu.size else 1
+    tok0 = np.zeros(max(capacity, 1), np.int32)
+    ln = np.zeros_like(tok0)
+    em = np.zeros_like(tok0)
+    rcu = np.zeros(n_req + 1, np.int32)
+    nc = _check(lib().gdn_plan_chunks(n_req, _hp(cu), _hp(sp), _hp(ecu), _hp(epos), _hp(tok0), _hp(ln),
+                                      _hp(em), _vp(rcu.ctypes.data), int(capacity)), "gdn_plan_chunks")
+    return tok0[:nc].copy(), ln[:nc].copy(), em[:nc].copy(), rcu
+
+
+def gdn_workspace_bytes(shape: gdn_shape, n_req: int, total_tokens: int, n_emit: int) -> int:
+    return _check(lib().gdn_workspace_bytes(ctypes.byref(shape), int(n_req), int(total_tokens), int(n_emit)),
+                  "gdn_workspace_bytes")
+
+
+# ----------------------------------------------------------------------------- device entry points
+def ckpt_gather(pool, slot_ids, dst, state_elems: Optional[int] = None, stream=None) -> None:
+    """dst[i] = pool[slot_ids[i]] (zeros for -1).  pool: [n_slots, ...] fp32, dst: [n, ...] fp32."""
+    ids = _h32(slot_ids)
+    n_slots, sstride = int(pool.shape[0]), int(pool.stride(0))
+    dstride = int(dst.stride(0)) if dst.dim() > 0 and dst.shape[0] > 0 else sstride
+    elems = int(state_elems if state_elems is not None else pool[0].numel())
+    _check(lib().ckpt_gather(_dp(pool), sstride, n_slots, _hp(ids), int(ids.size), _dp(dst), dstride, elems,
+                             _stream_ptr(stream)), "ckpt_gather")
+
+
+def ckpt_scatter(pool, slot_ids, src, state_elems: Optional[int] = None, stream=None) -> None:
+    """pool[slot_ids[i]] = src[i]."""
+    ids = _h32(slot_ids)
+    n_slots, sstride = int(pool.shape[0]), int(pool.stride(0))
+    srcstride = int(src.stride(0)) if src.dim() > 0 and src.shape[0] > 0 else sstride
+    elems = int(state_elems if state_elems is not None else pool[0].numel())
+    _check(lib().ckpt_scatter(_dp(pool), sstride, n_slots, _hp(ids), int(ids.size), _dp(src), srcstride, elems,
+                              _stream_ptr(stream)), "ckpt_scatter")
+
+
+def gdn_resume_prefill(shape: gdn_shape, q, k, v, beta, gate, cu_seqlens, start_pos,
+                       state_src, src_slot, emit_cu, emit_pos, state_dst, emit_slot,
+                       o, workspace, stream=None) -> None:
+    """See include/gdn_resume.h.  q..gate, o, state pools and workspace are device tensors;
+    the index arrays are host sequences."""
+    cu, sp, ss = _h32(cu_seqlens), _h32(start_pos), _h32(src_slot)
+    ecu, epos, eslot = _h32(emit_cu), _h32(emit_pos), _h32(emit_slot)
+    n_req = int(sp.size)
+    if cu.size != n_req + 1 or ecu.size != n_req + 1 or ss.size != n_req or eslot.size != epos.size:
+        raise ValueError("index arrays have inconsistent lengths")
+    src_stride = int(state_src.stride(0)) if state_src is not None else 0
+    src_n = int(state_src.shape[0]) if state_src is not None else 0
+    dst_stride = int(state_dst.stride(0)) if state_dst is not None else 0
+    dst_n = int(state_dst.shape[0]) if state_dst is not None else 0
+    ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    _check(lib().gdn_resume_prefill(ctypes.byref(shape), _dp(q), _dp(k), _dp(v), _dp(beta), _dp(gate),
+                                    n_req, _hp(cu), _hp(sp),
+                                    _dp(state_src), src_stride, src_n, _hp(ss), _hp(ecu), _hp(epos),
+                                    _dp(state_dst), dst_stride, dst_n, _hp(eslot),
+                                    _dp(o), _dp(workspace), ws_bytes, _stream_ptr(stream)),
+           "gdn_resume_prefill")

@@ -1,0 +1,117 @@
+// Matrix-core building blocks for gfx950 (wave64), shared by the prep and recurrence kernels.
+//
+// Every contraction here is D[m][n] += sum_k X[m][k] * Y[n][k] on a 32x32 output tile per wave,
+// with both operands read row-wise along k.  Lane l supplies row (l & 31) of X as the MFMA's A
+// operand and row (l & 31) of Y as its B operand; its half-wave index g = l >> 5 selects which
+// k-slots of the step it carries.  The hardware only pairs slot with slot, so the order in
+// which contraction indices are assigned to slots is free as long as A and B agree.  The
+// order used everywhere is the one the accumulator layout induces: accumulator register
+// 4b+e of lane (n, g) holds output row 8b+4g+e of column n.  With it, an accumulator tile
+// whose ROWS are the next contraction's index can be fed back as a B operand straight from
+// registers, with no shuffle and no trip through LDS:
+//   fp16: step s of a 32-row tile uses registers 8s..8s+7, i.e. rows 16s+4g+{0..3} and
+//         16s+8+4g+{0..3}; an operand read from memory loads exactly those two 4-element runs.
+//   fp32: step 4b+e uses register 4b+e, i.e. row 8b+4g+e.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gdn {
+
+typedef _Float16 half_t;
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Output row (within a 32x32 tile) held by accumulator register idx of half-wave g.
+__device__ __forceinline__ int acc_row(int idx, int g) { return 8 * (idx >> 2) + 4 * g + (idx & 3); }
+
+template <typename E> struct Elem;
+
+template <> struct Elem<half_t> {
+    typedef uint16_t In;               // bf16 bits in global memory
+    typedef half8 Frag;
+    static constexpr int PAD = 4;      // row padding (elements) of LDS tiles: 2 dwords, keeps 8-byte alignment
+    static constexpr int KSTEP = 16;   // contraction indices per MFMA
+    static constexpr int STEPS_PER_TILE = 2;  // MFMA steps that consume one 32-row accumulator tile
+
+    static __device__ __forceinline__ Frag load(const half_t* row, int s, int g) {
+        const half4 lo = *reinterpret_cast<const half4*>(row + 16 * s + 4 * g);
+        const half4 hi = *reinterpret_cast<const half4*>(row + 16 * s + 8 + 4 * g);
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ Frag from_acc(const f32x16& acc, int sub) {
+        Frag f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (half_t)acc[8 * sub + e];
+        return f;
+    }
+    static __device__ __forceinline__ void store4(half_t* p, float a, float b, float c, float d) {
+        half4 h;
+        h[0] = (half_t)a; h[1] = (half_t)b; h[2] = (half_t)c; h[3] = (half_t)d;
+        *reinterpret_cast<half4*>(p) = h;
+    }
+    // 8 consecutive input elements -> float
+    static __device__ __forceinline__ void load8(const In* p, float out[8]) {
+        const uint4 raw = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ float load1(const In* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+};
+
+template <> struct Elem<float> {
+    typedef float In;
+    typedef float Frag;
+    static constexpr int PAD = 1;
+    static constexpr int KSTEP = 2;
+    static constexpr int STEPS_PER_TILE = 16;
+
+    static __device__ __forceinline__ Frag load(const float* row, int s, int g) {
+        const int w = s & 15;
+        return row[32 * (s >> 4) + 8 * (w >> 2) + 4 * g + (w & 3)];
+    }
+    static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ Frag from_acc(const f32x16& acc, int sub) { return acc[sub]; }
+    static __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
+        p[0] = a; p[1] = b; p[2] = c; p[3] = d;
+    }
+    static __device__ __forceinline__ void load8(const In* p, float out[8]) {
+        const float4 a = *reinterpret_cast<const float4*>(p);
+        const float4 b = *reinterpret_cast<const float4*>(p + 4);
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    }
+    static __device__ __forceinline__ float load1(const In* p) { return *p; }
+};
+
+// Byte layout of one (chunk, layer, value head) unit of the workspace.  The first
+// `staged_bytes` are an image of the LDS tiles the recurrence kernel stages with one linear
+// copy; the accumulator-ordered U~ follows.
+template <typename E, int DK, int DV> struct UnitLayout {
+    static constexpr int C = 64;
+    static constexpr int PAD = Elem<E>::PAD;
+    static constexpr int W_LD = DK + PAD;    // W   [C][DK]  row = token, along d_k
+    static constexpr int KT_LD = C + PAD;    // K^T [DK][C]  row = d_k index, along tokens
+    static constexpr int P_LD = C + PAD;     // P   [C][C]   row = query token, along key tokens
+    static constexpr int W_OFF = 0;
+    static constexpr int KT_OFF = W_OFF + C * W_LD * (int)sizeof(E);
+    static constexpr int P_OFF = KT_OFF + DK * KT_LD * (int)sizeof(E);
+    static constexpr int AUX_OFF = P_OFF + C * P_LD * (int)sizeof(E);   // gam[C], dec[C] floats
+    static constexpr int STAGED_BYTES = AUX_OFF + 2 * C * (int)sizeof(float);
+    static constexpr int UT_OFF = STAGED_BYTES;                          // U~ fragments, fp32
+    static constexpr int UNIT_BYTES = UT_OFF + C * DV * (int)sizeof(float);
+    static_assert(KT_OFF % 16 == 0 && P_OFF % 16 == 0 && AUX_OFF % 16 == 0 && STAGED_BYTES % 16 == 0, "16-byte pieces");
+};
+
+}  // namespace gdn

@@ -1,0 +1,377 @@
+// Chunk preparation kernel: everything of a 64-token chunk that does not depend on the
+// recurrent state.  One workgroup (4 waves) per (chunk, layer, value head).
+//
+// With g_i the running sum of log a inside the chunk, gam_i = exp(g_i), and the chunk-local
+// form of the gated delta rule
+//     S_i = gam_i S_0 + sum_{j<=i} exp(g_i-g_j) u_j k_j^T ,   (I + L) U = diag(b)(V - diag(gam) K S_0^T)
+//     L_ij = b_i exp(g_i-g_j) (k_i.k_j)  for j < i,
+// it produces, with T = (I+L)^-1 (fp32):
+//     W  = -T diag(b gam) K          [C][d_k]   (so that U = U~ + W S_0^T)
+//     U~ =  T diag(b) V              [C][d_v]   fp32, in the recurrence kernel's accumulator order
+//     P_ij = scale * exp(g_i-g_j) (q_i.k_j), j <= i   [C][C]
+//     K^T, gam_i, dec_i = exp(g_C - g_i)
+// Tokens past the chunk's valid length are identity tokens (a = 1, b = 0, k = q = v = 0), which
+// leave the state untouched, so a short chunk needs no special arithmetic.
+#pragma once
+#include "gdn_mma.h"
+
+namespace gdn {
+
+struct PrepArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const void* beta;
+    const void* gate;
+    const int32_t* chunk_tok0;
+    const int32_t* chunk_len;
+    char* ws_units;       // unit (c, l, h) at ((c * L + l) * H_v + h) * UNIT_BYTES
+    int32_t L, H_qk, H_v;
+    int64_t T_alloc;
+    float scale;
+};
+
+// D(16x16) += A(16x16) * B(16x16), fp32 MFMA 16x16x4.  Lane (m = l & 15, g4 = l >> 4).
+// A and B are blocks of the fp32 matrix Lf (leading dimension LD) in LDS.
+template <int LD>
+__device__ __forceinline__ f32x4 mm16_ll(f32x4 acc, const float* A, const float* B, int m, int g4) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(A[m * LD + 4 * s + g4], B[(4 * s + g4) * LD + m], acc, 0, 0, 0);
+    return acc;
+}
+// Same with B taken from an accumulator tile (rows 4*g4+e are the contraction index).
+template <int LD>
+__device__ __forceinline__ f32x4 mm16_lr(f32x4 acc, const float* A, const f32x4& B, int m, int g4) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(A[m * LD + 4 * g4 + e], B[e], acc, 0, 0, 0);
+    return acc;
+}
+
+template <typename E, int DK, int DV>
+struct PrepSmem {
+    typedef UnitLayout<E, DK, DV> U;
+    static constexpr int C = 64;
+    static constexpr int PAD = Elem<E>::PAD;
+    static constexpr int LF_LD = C + 1;
+    static constexpr int T_LD = C + PAD;  // Tb / Tbg rows
+    static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
+    // region A: K [C][DK+PAD], later the P image, later the W image
+    static constexpr int A_OFF = 0;
+    static constexpr int A_BYTES = a16(C * (DK + PAD) * (int)sizeof(E));
+    // region B: Q [C][DK+PAD], later Tb and Tbg
+    static constexpr int B_OFF = A_OFF + A_BYTES;
+    static constexpr int TB_BYTES = a16(C * T_LD * (int)sizeof(E));
+    static constexpr int B_BYTES = (A_BYTES > 2 * TB_BYTES) ? A_BYTES : 2 * TB_BYTES;
+    static constexpr int KT_OFF = B_OFF + B_BYTES;
+    static constexpr int KT_BYTES = a16(DK * U::KT_LD * (int)sizeof(E));
+    static constexpr int VT_OFF = KT_OFF + KT_BYTES;
+    static constexpr int VT_BYTES = a16(DV * (C + PAD) * (int)sizeof(E));
+    static constexpr int LF_OFF = VT_OFF + VT_BYTES;
+    static constexpr int LF_BYTES = a16(C * LF_LD * (int)sizeof(float));
+    static constexpr int SM_OFF = LF_OFF + LF_BYTES;  // g[C], b[C], gam[C], dec[C]
+    static constexpr int BYTES = SM_OFF + 4 * C * (int)sizeof(float);
+};
+
+template <typename E, int DK, int DV>
+__global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
+    typedef Elem<E> EL;
+    typedef typename EL::In In;
+    typedef typename EL::Frag Frag;
+    typedef UnitLayout<E, DK, DV> U;
+    typedef PrepSmem<E, DK, DV> SM;
+    constexpr int C = 64;
+    constexpr int PAD = EL::PAD;
+    constexpr int K_LD = DK + PAD;
+    constexpr int KT_LD = U::KT_LD;
+    constexpr int VT_LD = C + PAD;
+    constexpr int LF_LD = SM::LF_LD;
+    constexpr int T_LD = SM::T_LD;
+
+    extern __shared__ __align__(16) char smem[];
+    E* Ks = reinterpret_cast<E*>(smem + SM::A_OFF);
+    E* Qs = reinterpret_cast<E*>(smem + SM::B_OFF);
+    E* KTs = reinterpret_cast<E*>(smem + SM::KT_OFF);
+    E* VTs = reinterpret_cast<E*>(smem + SM::VT_OFF);
+    float* Lf = reinterpret_cast<float*>(smem + SM::LF_OFF);
+    float* gS = reinterpret_cast<float*>(smem + SM::SM_OFF);
+    float* bS = gS + C;
+    float* gamS = bS + C;
+    float* decS = gamS + C;
+    E* Pt = Ks;                                           // after the first products
+    E* Wt = Ks;                                           // after P has been copied out
+    E* Tb = Qs;                                           // after the first products
+    E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int lr = lane & 31;
+    const int g = lane >> 5;
+
+    const int c = blockIdx.x;
+    const int lh = blockIdx.y;
+    const int l = lh / a.H_v;
+    const int hv = lh % a.H_v;
+    const int hq = hv / (a.H_v / a.H_qk);
+    const int tok0 = a.chunk_tok0[c];
+    const int n = a.chunk_len[c];
+    const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
+    char* unit = a.ws_units + ((int64_t)(c * a.L + l) * a.H_v + hv) * U::UNIT_BYTES;
+
+    // ---- gates: g_i = inclusive running sum of log a (wave 0), b_i; identity beyond n
+    if (wave == 0) {
+        float la = 0.f, b = 0.f;
+        if (lane < n) {
+            const int64_t gi = (row0 + lane) * a.H_v + hv;
+            la = fmaxf(__logf(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
+            b = EL::load1(reinterpret_cast<const In*>(a.beta) + gi);
+        }
+        float s = la;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float t = __shfl_up(s, d, 64);
+            if (lane >= d) s += t;
+        }
+        const float g_last = __shfl(s, 63, 64);
+        gS[lane] = s;
+        bS[lane] = b;
+        gamS[lane] = __expf(s);
+        decS[lane] = __expf(g_last - s);
+    }
+    // ---- zero the fp32 triangular matrix (its untouched upper blocks must read as 0)
+    for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
+
+    // ---- stage K, Q (row-major) and K^T, V^T (token-contiguous), converted to E
+    {
+        const In* qg = reinterpret_cast<const In*>(a.q);
+        const In* kg = reinterpret_cast<const In*>(a.k);
+        constexpr int VPR = DK / 8;  // 8-element vectors per row
+        for (int u = tid; u < C * VPR; u += 256) {
+            const int i = u / VPR, d0 = (u % VPR) * 8;
+            float kv[8], qv[8];
+            if (i < n) {
+                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
+                EL::load8(kg + off, kv);
+                EL::load8(qg + off, qv);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { kv[e] = 0.f; qv[e] = 0.f; }
+            }
+            EL::store4(Ks + i * K_LD + d0, kv[0], kv[1], kv[2], kv[3]);
+            EL::store4(Ks + i * K_LD + d0 + 4, kv[4], kv[5], kv[6], kv[7]);
+            EL::store4(Qs + i * K_LD + d0, qv[0], qv[1], qv[2], qv[3]);
+            EL::store4(Qs + i * K_LD + d0 + 4, qv[4], qv[5], qv[6], qv[7]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) KTs[(d0 + e) * KT_LD + i] = (E)kv[e];
+        }
+        const In* vg = reinterpret_cast<const In*>(a.v);
+        constexpr int VPRV = DV / 8;
+        for (int u = tid; u < C * VPRV; u += 256) {
+            const int i = u / VPRV, d0 = (u % VPRV) * 8;
+            float vv[8];
+            if (i < n) {
+                EL::load8(vg + ((row0 + i) * a.H_v + hv) * DV + d0, vv);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vv[e] = 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) VTs[(d0 + e) * VT_LD + i] = (E)vv[e];
+        }
+    }
+    __syncthreads();
+
+    // ---- K K^T -> L (fp32) and K Q^T -> P (kept in registers until K is dead)
+    //      wave 0: KK(0,0) KQ(0,0)   wave 1: KK(1,0)   wave 2: KK(1,1) KQ(1,1)   wave 3: KQ(0,1)
+    constexpr int NKD = DK / EL::KSTEP;
+    f32x16 accP;
+    int p_mj = -1, p_ni = -1;
+    {
+        int kk_mi = -1, kk_nj = -1;
+        if (wave == 0) { kk_mi = 0; kk_nj = 0; p_mj = 0; p_ni = 0; }
+        if (wave == 1) { kk_mi = 1; kk_nj = 0; }
+        if (wave == 2) { kk_mi = 1; kk_nj = 1; p_mj = 1; p_ni = 1; }
+        if (wave == 3) { p_mj = 0; p_ni = 1; }
+        if (kk_mi >= 0) {
+            f32x16 acc = {0};
+            const E* ar = Ks + (32 * kk_mi + lr) * K_LD;
+            const E* br = Ks + (32 * kk_nj + lr) * K_LD;
+#pragma unroll
+            for (int s = 0; s < NKD; ++s) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+            const int j = 32 * kk_nj + lr;
+            const float gj = gS[j];
+#pragma unroll
+            for (int idx = 0; idx < 16; ++idx) {
+                const int i = 32 * kk_mi + acc_row(idx, g);
+                const float val = bS[i] * __expf(fminf(gS[i] - gj, 0.f)) * acc[idx];
+                Lf[i * LF_LD + j] = (j < i) ? val : 0.f;
+            }
+        }
+        if (p_mj >= 0) {
+            f32x16 acc = {0};
+            const E* ar = Ks + (32 * p_mj + lr) * K_LD;   // rows: key token j
+            const E* br = Qs + (32 * p_ni + lr) * K_LD;   // rows: query token i
+#pragma unroll
+            for (int s = 0; s < NKD; ++s) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+            const int i = 32 * p_ni + lr;
+            const float gi = gS[i];
+#pragma unroll
+            for (int idx = 0; idx < 16; ++idx) {
+                const int j = 32 * p_mj + acc_row(idx, g);
+                const float val = a.scale * __expf(fminf(gi - gS[j], 0.f)) * acc[idx];
+                acc[idx] = (j <= i) ? val : 0.f;
+            }
+            accP = acc;
+        }
+    }
+    __syncthreads();  // K, Q in LDS are dead; L is complete
+
+    // ---- P image into region A; wave 1 clears the all-zero quadrant (i < 32, j >= 32)
+    if (p_mj >= 0) {
+        const int i = 32 * p_ni + lr;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            EL::store4(Pt + i * U::P_LD + 32 * p_mj + 8 * b + 4 * g, accP[4 * b], accP[4 * b + 1], accP[4 * b + 2], accP[4 * b + 3]);
+    } else {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) EL::store4(Pt + lr * U::P_LD + 32 + 8 * b + 4 * g, 0.f, 0.f, 0.f, 0.f);
+    }
+
+    // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks by forward
+    //      substitution, one per wave, column (lane & 15) of the inverse in registers.
+    {
+        const int base = 16 * wave, cc = lane & 15;
+        float x[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float s = (r == cc) ? 1.f : 0.f;
+#pragma unroll
+            for (int j = 0; j < r; ++j) s -= Lf[(base + r) * LF_LD + base + j] * x[j];
+            x[r] = s;
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Lf[(base + r) * LF_LD + base + cc] = x[r];
+        }
+    }
+    __syncthreads();  // diagonal blocks of T in place; P image complete
+
+    // copy the P image out while the inversion goes on (region A is not touched until W)
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(Pt);
+        uint4* dst = reinterpret_cast<uint4*>(unit + U::P_OFF);
+        constexpr int N16 = C * U::P_LD * (int)sizeof(E) / 16;
+        for (int i = tid; i < N16; i += 256) dst[i] = src[i];
+    }
+
+    const int m16 = lane & 15, g4 = lane >> 4;
+    auto blk = [&](int br, int bc) -> const float* { return Lf + (16 * br) * LF_LD + 16 * bc; };
+    // Stage 2: T_10 = -T_11 (L_10 T_00) on wave 0, T_32 = -T_33 (L_32 T_22) on wave 1.
+    if (wave < 2) {
+        const int ra = 2 * wave + 1, rb = 2 * wave;
+        f32x4 m = {0, 0, 0, 0};
+        m = mm16_ll<LF_LD>(m, blk(ra, rb), blk(rb, rb), m16, g4);
+        f32x4 r = {0, 0, 0, 0};
+        r = mm16_lr<LF_LD>(r, blk(ra, ra), m, m16, g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Lf[(16 * ra + 4 * g4 + e) * LF_LD + 16 * rb + m16] = -r[e];
+    }
+    __syncthreads();
+    // Stage 3: the 32x32 block below the diagonal.  Wave w owns T_ab, a = 2 + w/2, b = w%2:
+    //   X_cb = L_c0 T_0b + L_c1 T_1b (c = 2, 3);  T_2b = -T_22 X_2b;  T_3b = -(T_32 X_2b + T_33 X_3b).
+    {
+        const int ra = 2 + (wave >> 1), rb = wave & 1;
+        f32x4 x2 = {0, 0, 0, 0};
+        if (rb == 0) x2 = mm16_ll<LF_LD>(x2, blk(2, 0), blk(0, 0), m16, g4);
+        x2 = mm16_ll<LF_LD>(x2, blk(2, 1), blk(1, rb), m16, g4);
+        f32x4 r = {0, 0, 0, 0};
+        r = mm16_lr<LF_LD>(r, blk(ra, 2), x2, m16, g4);
+        if (ra == 3) {
+            f32x4 x3 = {0, 0, 0, 0};
+            if (rb == 0) x3 = mm16_ll<LF_LD>(x3, blk(3, 0), blk(0, 0), m16, g4);
+            x3 = mm16_ll<LF_LD>(x3, blk(3, 1), blk(1, rb), m16, g4);
+            r = mm16_lr<LF_LD>(r, blk(3, 3), x3, m16, g4);
+        }
+        __syncthreads();  // every wave has read the L blocks it needs before any is overwritten
+#pragma unroll
+        for (int e = 0; e < 4; ++e) Lf[(16 * ra + 4 * g4 + e) * LF_LD + 16 * rb + m16] = -r[e];
+    }
+    __syncthreads();  // T complete in Lf
+
+    // ---- Tb = T diag(b), Tbg = -T diag(b gam), converted to E (region B; Q is dead)
+    {
+        const int i = tid >> 2, j0 = (tid & 3) * 16;
+#pragma unroll
+        for (int jj = 0; jj < 16; jj += 4) {
+            float tb[4], tg[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = j0 + jj + e;
+                const float t = Lf[i * LF_LD + j] * bS[j];
+                tb[e] = t;
+                tg[e] = -t * gamS[j];
+            }
+            EL::store4(Tb + i * T_LD + j0 + jj, tb[0], tb[1], tb[2], tb[3]);
+            EL::store4(Tbg + i * T_LD + j0 + jj, tg[0], tg[1], tg[2], tg[3]);
+        }
+    }
+    __syncthreads();
+
+    // ---- W^T tile (mt, nt): D[d_k][token i] = sum_j K^T[d_k][j] Tbg[i][j]   -> W image [i][d_k]
+    //      T is lower triangular: token tile 0 only contracts over j < 32.
+    constexpr int NKC = C / EL::KSTEP;
+    for (int t = wave; t < (DK / 32) * 2; t += 4) {
+        const int mt = t >> 1, nt = t & 1;
+        f32x16 acc = {0};
+        const E* ar = KTs + (32 * mt + lr) * KT_LD;
+        const E* br = Tbg + (32 * nt + lr) * T_LD;
+        const int ns = (nt == 0) ? NKC / 2 : NKC;
+#pragma unroll
+        for (int s = 0; s < NKC; ++s)
+            if (s < ns) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+        const int i = 32 * nt + lr;
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+            EL::store4(Wt + i * U::W_LD + 32 * mt + 8 * b + 4 * g, acc[4 * b], acc[4 * b + 1], acc[4 * b + 2], acc[4 * b + 3]);
+    }
+    // ---- U~ tile (slice sl, token tile rt): D[token][d_v] = sum_j Tb[token][j] V^T[d_v][j]
+    //      stored as the recurrence kernel's accumulators: [sl][rt][b][lane] float4
+    {
+        f32x4* ut = reinterpret_cast<f32x4*>(unit + U::UT_OFF);
+        for (int p = wave; p < (DV / 32) * 2; p += 4) {
+            const int sl = p >> 1, rt = p & 1;
+            f32x16 acc = {0};
+            const E* ar = Tb + (32 * rt + lr) * T_LD;
+            const E* br = VTs + (32 * sl + lr) * VT_LD;
+            const int ns = (rt == 0) ? NKC / 2 : NKC;
+#pragma unroll
+            for (int s = 0; s < NKC; ++s)
+                if (s < ns) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                f32x4 o4 = {acc[4 * b], acc[4 * b + 1], acc[4 * b + 2], acc[4 * b + 3]};
+                ut[((sl * 2 + rt) * 4 + b) * 64 + lane] = o4;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- copy the W and K^T images and the per-token scale factors out
+    {
+        const uint4* src = reinterpret_cast<const uint4*>(Wt);
+        uint4* dst = reinterpret_cast<uint4*>(unit + U::W_OFF);
+        constexpr int NW16 = C * U::W_LD * (int)sizeof(E) / 16;
+        for (int i = tid; i < NW16; i += 256) dst[i] = src[i];
+        const uint4* src2 = reinterpret_cast<const uint4*>(KTs);
+        uint4* dst2 = reinterpret_cast<uint4*>(unit + U::KT_OFF);
+        constexpr int NK16 = DK * U::KT_LD * (int)sizeof(E) / 16;
+        for (int i = tid; i < NK16; i += 256) dst2[i] = src2[i];
+        float* aux = reinterpret_cast<float*>(unit + U::AUX_OFF);
+        if (tid < C) aux[tid] = gamS[tid];
+        else if (tid < 2 * C) aux[tid] = decS[tid - C];
+    }
+}
+
+}  // namespace gdn

@@ -1,0 +1,367 @@
+// C ABI of the library: argument validation, planning, plan upload and kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "gdn_plan.h"
+#include "gdn_prep_kernel.h"
+#include "gdn_recur_kernel.h"
+#include "gdn_resume.h"
+
+namespace gdn {
+namespace {
+
+inline int32_t hip_err(hipError_t e) { return e == hipSuccess ? GDN_OK : GDN_ERR_HIP - (int32_t)e; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ------------------------------------------------------------------ checkpoint pool copies
+constexpr int COPY_IDS = 256;   // slot ids carried by value per launch
+constexpr int COPY_THREADS = 256;
+constexpr int COPY_UNROLL = 4;  // float4 loads in flight per thread
+
+struct CopyIds {
+    int32_t id[COPY_IDS];
+};
+
+// blockIdx.y = state within the batch, blockIdx.x strides over its float4 elements.
+// GATHER: dst[y] = pool[id[y]] (zeros for id -1);  else pool[id[y]] = src[y].
+template <bool GATHER>
+__global__ void __launch_bounds__(COPY_THREADS) ckpt_copy_kernel(const float4* __restrict__ from, float4* __restrict__ to,
+                                                                 int64_t from_stride4, int64_t to_stride4,
+                                                                 int64_t n4, CopyIds ids) {
+    const int y = blockIdx.y;
+    const int32_t id = ids.id[y];
+    const float4* src = GATHER ? from + (int64_t)id * from_stride4 : from + (int64_t)y * from_stride4;
+    float4* dst = GATHER ? to + (int64_t)y * to_stride4 : to + (int64_t)id * to_stride4;
+    const int64_t step = (int64_t)gridDim.x * COPY_THREADS;
+    int64_t i = (int64_t)blockIdx.x * COPY_THREADS + threadIdx.x;
+    if (GATHER && id < 0) {
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (; i < n4; i += step) dst[i] = z;
+        return;
+    }
+    for (; i + (COPY_UNROLL - 1) * step < n4; i += COPY_UNROLL * step) {
+        float4 x[COPY_UNROLL];
+#pragma unroll
+        for (int u = 0; u < COPY_UNROLL; ++u) x[u] = src[i + u * step];
+#pragma unroll
+        for (int u = 0; u < COPY_UNROLL; ++u) dst[i + u * step] = x[u];
+    }
+    for (; i < n4; i += step) dst[i] = src[i];
+}
+
+int32_t check_copy_args(const void* pool, int64_t slot_stride, int32_t n_slots, const int32_t* ids, int32_t n,
+                        const void* other, int64_t other_stride, int64_t state_elems, bool allow_minus_one) {
+    if (n < 0 || n_slots < 0 || state_elems < 0) return GDN_ERR_COUNT;
+    if (n == 0 || state_elems == 0) return GDN_OK;
+    if (!pool || !ids || !other) return GDN_ERR_NULL;
+    if (!aligned16(pool) || !aligned16(other)) return GDN_ERR_ALIGN;
+    if ((state_elems & 3) || (slot_stride & 3) || (other_stride & 3)) return GDN_ERR_ALIGN;
+    if (slot_stride < state_elems || other_stride < state_elems) return GDN_ERR_SHAPE;
+    for (int32_t i = 0; i < n; ++i) {
+        if (ids[i] >= n_slots) return GDN_ERR_SLOT_RANGE;
+        if (ids[i] < (allow_minus_one ? -1 : 0)) return GDN_ERR_SLOT_RANGE;
+    }
+    return GDN_OK;
+}
+
+template <bool GATHER>
+int32_t launch_copy(const float* from, float* to, int64_t from_stride, int64_t to_stride, int64_t state_elems,
+                    const int32_t* ids, int32_t n, hipStream_t stream) {
+    const int64_t n4 = state_elems / 4;
+    // enough workgroups to fill 256 CUs several times over, but no more than the state has work for
+    const int64_t per_state = std::max<int64_t>(1, std::min<int64_t>((n4 + COPY_THREADS * COPY_UNROLL - 1) / (COPY_THREADS * COPY_UNROLL), 1024));
+    for (int32_t base = 0; base < n; base += COPY_IDS) {
+        const int32_t m = std::min(COPY_IDS, n - base);
+        CopyIds batch;
+        std::memset(&batch, 0, sizeof batch);
+        std::memcpy(batch.id, ids + base, sizeof(int32_t) * m);
+        const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(per_state, (8192 + m - 1) / m));
+        const dim3 grid((unsigned)gx, (unsigned)m);
+        const float4* f = reinterpret_cast<const float4*>(from) + (GATHER ? 0 : (int64_t)base * (from_stride / 4));
+        float4* t = reinterpret_cast<float4*>(to) + (GATHER ? (int64_t)base * (to_stride / 4) : 0);
+        hipLaunchKernelGGL(ckpt_copy_kernel<GATHER>, grid, dim3(COPY_THREADS), 0, stream, f, t, from_stride / 4,
+                           to_stride / 4, n4, batch);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_err(e);
+    }
+    return GDN_OK;
+}
+
+// ------------------------------------------------------------------ plan staging (pinned host memory)
+struct Staging {
+    std::mutex mu;
+    void* host = nullptr;
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool pending = false;
+};
+Staging g_staging;
+
+// Copies `bytes` from `src` into pinned memory and enqueues its upload to `dst`.
+int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream) {
+    std::lock_guard<std::mutex> lock(g_staging.mu);
+    Staging& s = g_staging;
+    if (!s.done) {
+        const hipError_t e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_err(e);
+    }
+    if (s.pending) {  // the previous upload must have left the buffer
+        const hipError_t e = hipEventSynchronize(s.done);
+        if (e != hipSuccess) return hip_err(e);
+        s.pending = false;
+    }
+    if (s.bytes < bytes) {
+        if (s.host) (void)hipHostFree(s.host);
+        s.host = nullptr;
+        s.bytes = 0;
+        const size_t want = std::max<size_t>(bytes * 2, 1 << 16);
+        const hipError_t e = hipHostMalloc(&s.host, want, hipHostMallocDefault);
+        if (e != hipSuccess) return hip_err(e);
+        s.bytes = want;
+    }
+    std::memcpy(s.host, src, bytes);
+    hipError_t e = hipMemcpyAsync(dst, s.host, bytes, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return hip_err(e);
+    e = hipEventRecord(s.done, stream);
+    if (e != hipSuccess) return hip_err(e);
+    s.pending = true;
+    return GDN_OK;
+}
+
+// ------------------------------------------------------------------ kernel dispatch
+struct DevicePlan {
+    const int32_t *chunk_tok0, *chunk_len, *chunk_emit_slot, *req_chunk_cu, *req_src_slot, *req_order;
+};
+
+template <typename E, int DK, int DV>
+int64_t unit_bytes_of() { return UnitLayout<E, DK, DV>::UNIT_BYTES; }
+
+int64_t unit_bytes(const gdn_shape& s) {
+    if (s.in_dtype == GDN_F32) return unit_bytes_of<float, 64, 64>();
+    return s.d_k == 64 ? unit_bytes_of<half_t, 64, 64>() : unit_bytes_of<half_t, 128, 128>();
+}
+
+int recur_waves_override() {
+    static const int v = [] {
+        const char* e = std::getenv("GDN_RECUR_WAVES");
+        return e ? std::atoi(e) : 0;
+    }();
+    return v;
+}
+
+template <typename E, int DK, int DV, int NW>
+hipError_t launch_recur_nw(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
+    constexpr int SG = (DV / 32) / NW;
+    constexpr int smem = recur_smem_bytes<E, DK, DV>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
+    return hipGetLastError();
+}
+
+template <typename E, int DK, int DV>
+int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, int32_t n_chunks, int32_t n_req,
+                   hipStream_t stream) {
+    typedef PrepSmem<E, DK, DV> SM;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_prep_kernel<E, DK, DV>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+        if (e != hipSuccess) return hip_err(e);
+        attr_set = true;
+    }
+    const int units = s.L * s.H_v;
+    hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)n_chunks, (unsigned)units), dim3(256), SM::BYTES, stream, pa);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_err(e);
+
+    // Waves (d_v slices) per workgroup of the recurrence: as many as still leave the chip full;
+    // few chains -> one wave per workgroup so that the slices spread over more compute units.
+    const int64_t n_chains = (int64_t)n_req * units;
+    constexpr int NS = DV / 32;
+    int nw = NS;
+    while (nw > 1 && n_chains * (NS / nw) < 512) nw >>= 1;
+    if (const int o = recur_waves_override()) {
+        if (o == 1 || o == 2 || (o == 4 && NS == 4)) nw = o;
+    }
+    if (nw == 1) e = launch_recur_nw<E, DK, DV, 1>(ra, n_chains, stream);
+    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
+    else e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
+    return hip_err(e);
+}
+
+}  // namespace
+}  // namespace gdn
+
+using namespace gdn;
+
+extern "C" {
+
+int32_t gdn_version(void) { return 100; }
+
+int32_t gdn_deepest_ckpt(const int32_t* pos, int32_t M, int32_t t) {
+    if (!pos || M <= 0) return -1;
+    // largest i with pos[i] <= t (pos strictly increasing)
+    const int32_t* it = std::upper_bound(pos, pos + M, t);
+    return (int32_t)(it - pos) - 1;
+}
+
+int32_t gdn_plan_chunks(int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos, const int32_t* emit_cu,
+                        const int32_t* emit_pos, int32_t* chunk_tok0, int32_t* chunk_len, int32_t* chunk_emit,
+                        int32_t* req_chunk_cu, int32_t capacity) {
+    ChunkPlan plan;
+    const int32_t rc = plan_chunks(n_req, cu_seqlens, start_pos, emit_cu, emit_pos, &plan);
+    if (rc != GDN_OK) return rc;
+    const int32_t nc = (int32_t)plan.chunk_tok0.size();
+    if (nc > capacity) return GDN_ERR_WORKSPACE;
+    if (nc > 0 && (!chunk_tok0 || !chunk_len || !chunk_emit)) return GDN_ERR_NULL;
+    if (!req_chunk_cu) return GDN_ERR_NULL;
+    if (nc > 0) {
+        std::memcpy(chunk_tok0, plan.chunk_tok0.data(), sizeof(int32_t) * nc);
+        std::memcpy(chunk_len, plan.chunk_len.data(), sizeof(int32_t) * nc);
+        std::memcpy(chunk_emit, plan.chunk_emit.data(), sizeof(int32_t) * nc);
+    }
+    std::memcpy(req_chunk_cu, plan.req_chunk_cu.data(), sizeof(int32_t) * (n_req + 1));
+    return nc;
+}
+
+static int64_t plan_bytes(int64_t n_chunks, int64_t n_req) {
+    return align_up((3 * n_chunks + 3 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
+}
+
+int64_t gdn_workspace_bytes(const gdn_shape* shape, int32_t n_req, int64_t total_tokens, int32_t n_emit) {
+    const int32_t rc = check_shape(shape);
+    if (rc != GDN_OK) return rc;
+    if (n_req < 0 || total_tokens < 0 || n_emit < 0) return GDN_ERR_COUNT;
+    const int64_t max_chunks = total_tokens / GDN_CHUNK + n_req + n_emit + 1;
+    return plan_bytes(max_chunks, n_req) + max_chunks * shape->L * shape->H_v * unit_bytes(*shape);
+}
+
+int32_t ckpt_gather(const float* pool, int64_t slot_stride, int32_t n_slots, const int32_t* slot_ids, int32_t n,
+                    float* dst, int64_t dst_stride, int64_t state_elems, void* stream) {
+    const int32_t rc = check_copy_args(pool, slot_stride, n_slots, slot_ids, n, dst, dst_stride, state_elems, true);
+    if (rc != GDN_OK || n == 0 || state_elems == 0) return rc;
+    return launch_copy<true>(pool, dst, slot_stride, dst_stride, state_elems, slot_ids, n, (hipStream_t)stream);
+}
+
+int32_t ckpt_scatter(float* pool, int64_t slot_stride, int32_t n_slots, const int32_t* slot_ids, int32_t n,
+                     const float* src, int64_t src_stride, int64_t state_elems, void* stream) {
+    const int32_t rc = check_copy_args(pool, slot_stride, n_slots, slot_ids, n, src, src_stride, state_elems, false);
+    if (rc != GDN_OK || n == 0 || state_elems == 0) return rc;
+    std::vector<int32_t> sorted(slot_ids, slot_ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return GDN_ERR_SLOT_DUP;
+    return launch_copy<false>(src, pool, src_stride, slot_stride, state_elems, slot_ids, n, (hipStream_t)stream);
+}
+
+int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                           const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
+                           const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                           const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
+                           float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
+                           void* o, void* workspace, int64_t workspace_bytes, void* stream_v) {
+    hipStream_t stream = (hipStream_t)stream_v;
+    int32_t rc = check_shape(shape);
+    if (rc != GDN_OK) return rc;
+    const gdn_shape& s = *shape;
+
+    ChunkPlan plan;
+    rc = plan_chunks(n_req, cu_seqlens, start_pos, emit_cu, emit_pos, &plan);
+    if (rc != GDN_OK) return rc;
+    const int64_t total_tokens = cu_seqlens[n_req];
+    if (total_tokens > s.T_alloc) return GDN_ERR_SEQLENS;
+    const int32_t n_emit = emit_cu[n_req];
+    rc = check_slots(n_req, src_slot, src_n_slots, emit_cu, emit_slot, dst_n_slots,
+                     state_src != nullptr && (const void*)state_src == (const void*)state_dst);
+    if (rc != GDN_OK) return rc;
+
+    const int64_t slot_elems = (int64_t)s.L * s.H_v * s.d_v * s.d_k;
+    bool any_src = false;
+    for (int32_t r = 0; r < n_req; ++r) any_src |= src_slot[r] >= 0;
+    if (any_src) {
+        if (!state_src) return GDN_ERR_NULL;
+        if (!aligned16(state_src) || (src_slot_stride & 3)) return GDN_ERR_ALIGN;
+        if (src_slot_stride < slot_elems) return GDN_ERR_SHAPE;
+    }
+    if (n_emit > 0) {
+        if (!state_dst) return GDN_ERR_NULL;
+        if (!aligned16(state_dst) || (dst_slot_stride & 3)) return GDN_ERR_ALIGN;
+        if (dst_slot_stride < slot_elems) return GDN_ERR_SHAPE;
+    }
+    const int32_t n_chunks = (int32_t)plan.chunk_tok0.size();
+    if (n_chunks == 0) return GDN_OK;  // nothing to replay
+    if (!q || !k || !v || !beta || !gate || !o) return GDN_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return GDN_ERR_ALIGN;
+    const int64_t esz = s.in_dtype == GDN_F32 ? 4 : 2;
+    if (((int64_t)s.H_v * esz) & 1) return GDN_ERR_ALIGN;
+
+    const int64_t ub = unit_bytes(s);
+    const int64_t pb = plan_bytes(n_chunks, n_req);
+    const int64_t need = pb + (int64_t)n_chunks * s.L * s.H_v * ub;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GDN_ERR_WORKSPACE;
+    if (workspace_bytes < need) return GDN_ERR_WORKSPACE;
+
+    // ---- plan image: [tok0 | len | emit slot] per chunk, [chunk_cu | src slot | order] per request
+    std::vector<int32_t> img((size_t)(3 * (int64_t)n_chunks + 3 * (int64_t)n_req + 1));
+    int32_t* p_tok0 = img.data();
+    int32_t* p_len = p_tok0 + n_chunks;
+    int32_t* p_eslot = p_len + n_chunks;
+    int32_t* p_cu = p_eslot + n_chunks;
+    int32_t* p_src = p_cu + (n_req + 1);
+    int32_t* p_order = p_src + n_req;
+    for (int32_t c = 0; c < n_chunks; ++c) {
+        p_tok0[c] = plan.chunk_tok0[c];
+        p_len[c] = plan.chunk_len[c];
+        p_eslot[c] = plan.chunk_emit[c] >= 0 ? emit_slot[plan.chunk_emit[c]] : -1;
+    }
+    std::memcpy(p_cu, plan.req_chunk_cu.data(), sizeof(int32_t) * (n_req + 1));
+    std::memcpy(p_src, src_slot, sizeof(int32_t) * n_req);
+    const std::vector<int32_t> order = longest_first(plan, n_req);
+    std::memcpy(p_order, order.data(), sizeof(int32_t) * n_req);
+
+    rc = upload_plan(img.data(), img.size() * sizeof(int32_t), workspace, stream);
+    if (rc != GDN_OK) return rc;
+
+    const int32_t* d = reinterpret_cast<const int32_t*>(workspace);
+    char* ws_units = reinterpret_cast<char*>(workspace) + pb;
+
+    PrepArgs pa;
+    pa.q = q; pa.k = k; pa.v = v; pa.beta = beta; pa.gate = gate;
+    pa.chunk_tok0 = d;
+    pa.chunk_len = d + n_chunks;
+    pa.ws_units = ws_units;
+    pa.L = s.L; pa.H_qk = s.H_qk; pa.H_v = s.H_v;
+    pa.T_alloc = s.T_alloc;
+    pa.scale = s.scale;
+
+    RecurArgs ra;
+    ra.q = q; ra.o = o; ra.ws_units = ws_units;
+    ra.chunk_tok0 = d;
+    ra.chunk_len = d + n_chunks;
+    ra.chunk_emit_slot = d + 2 * (int64_t)n_chunks;
+    ra.req_chunk_cu = d + 3 * (int64_t)n_chunks;
+    ra.req_src_slot = ra.req_chunk_cu + (n_req + 1);
+    ra.req_order = ra.req_src_slot + n_req;
+    ra.state_src = state_src; ra.state_dst = state_dst;
+    ra.src_slot_stride = src_slot_stride; ra.dst_slot_stride = dst_slot_stride;
+    ra.L = s.L; ra.H_qk = s.H_qk; ra.H_v = s.H_v;
+    ra.T_alloc = s.T_alloc;
+    ra.scale = s.scale;
+    ra.o_bf16 = s.o_dtype == GDN_BF16;
+
+    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
+    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
+    return launch_all<half_t, 128, 128>(s, pa, ra, n_chunks, n_req, stream);
+}
+
+}  // extern "C"
