@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         float la = 0.f, b = 0.f;
         if (lane < n) {
             const int64_t gi = (row0 + lane) * a.H_v + hv;
-            la = fmaxf(__logf(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
+            la = fmaxf(logf(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
             b = EL::load1(reinterpret_cast<const In*>(a.beta) + gi);
         }
         float s = la;
@@ -137,8 +137,8 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         const float g_last = __shfl(s, 63, 64);
         gS[lane] = s;
         bS[lane] = b;
-        gamS[lane] = __expf(s);
-        decS[lane] = __expf(g_last - s);
+        gamS[lane] = expf(s);
+        decS[lane] = expf(g_last - s);
     }
     // ---- zero the fp32 triangular matrix (its untouched upper blocks must read as 0)
     for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
@@ -205,7 +205,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
                 const int i = 32 * kk_mi + acc_row(idx, g);
-                const float val = bS[i] * __expf(fminf(gS[i] - gj, 0.f)) * acc[idx];
+                const float val = bS[i] * expf(fminf(gS[i] - gj, 0.f)) * acc[idx];
                 Lf[i * LF_LD + j] = (j < i) ? val : 0.f;
             }
         }
@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
                 const int j = 32 * p_mj + acc_row(idx, g);
-                const float val = a.scale * __expf(fminf(gi - gS[j], 0.f)) * acc[idx];
+                const float val = a.scale * expf(fminf(gi - gS[j], 0.f)) * acc[idx];
                 acc[idx] = (j <= i) ? val : 0.f;
             }
             accP = acc;
