@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the resume + checkpoint-emit prefill on one MI355X.
+
+Workload (configs[1]): one GatedDeltaNet layer, batch 1, 16 heads, d_k = d_v = 128, bf16 inputs,
+fp32 state and outputs, cached prefix N = 8192 with M = 16 uniformly spaced checkpoints.  A
+step is one request: its overlap depth t is a seeded draw from U[0, N); it loads the state of
+the deepest checkpoint at or below t straight from the HBM pool, replays tokens l+1..N and
+stores every downstream checkpoint state to fresh pool slots.  Steps cycle through a fixed
+list of seeded draws.  Inputs are resident in HBM before the timed region; the timed region
+covers the whole call per step (host planning, plan upload, both kernels).
+
+Prints ONE JSON line; see the design doc for the roofline accounting.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+N_PREFIX, M_CKPT, HEADS, D = 8192, 16, 16, 128
+N_DRAWS = 16
+SEED = 1001
+C = 64
+# algorithmic flops per token.head (dense tiles, chunk 64): chunk preparation and recurrence
+FLOP_PREP = C * (6 * D + 2 * D)             # K K^T, K Q^T, W (each 2 C d_k) + U~ (2 C d_v)
+FLOP_RECUR = 6 * D * D + 2 * C * D          # W S^T, Q S^T, state update (2 d_k d_v each) + P U (2 C d_v)
+# algorithmic HBM bytes per token.head: q, k, v in bf16, beta, gate, o in fp32
+BYTES_TOKEN_HEAD = (2 * D + D) * 2 + 2 * 2 + D * 4
+PEAK_MFMA_TFLOPS = 2500.0                   # dense fp16/bf16 MFMA, MI355X
+PEAK_HBM_GBS = 8000.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not record per-kernel HIP events in the timed region (no roofline object)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_05219_amd import binding as B, workloads as wl
+    from tests.harness import GpuCall
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---- the cache entry and the requests (host side, seeded)
+    sc = wl.config1(B.gdn_deepest_ckpt, seed=SEED, n_draws=N_DRAWS, N=N_PREFIX, M=M_CKPT, H=HEADS, d=D)
+    n_slots = M_CKPT + M_CKPT + 1
+    pool = torch.zeros((n_slots, 1, HEADS, D, D), dtype=torch.float32, device=dev)
+    build = GpuCall(sc.build, pool)
+    build.run()                       # fills slots 0..M-1 with the prefix checkpoints (untimed set-up)
+    torch.cuda.synchronize()
+
+    # one call object per draw (its own packed suffix tokens, resident in HBM)
+    r = sc.resume
+    calls = []
+    for i in range(N_DRAWS):
+        lo, hi = int(r.cu_seqlens[i]), int(r.cu_seqlens[i + 1])
+        e0, e1 = int(r.emit_cu[i]), int(r.emit_cu[i + 1])
+        one = wl.pack_call(1, HEADS, HEADS, D, D, "bf16", [r.streams.slice(lo, hi)], [r.start_pos[i]],
+                           [r.src_slot[i]], [list(r.emit_pos[e0:e1])],
+                           [list(range(M_CKPT, M_CKPT + e1 - e0))], n_slots)
+        calls.append(GpuCall(one, pool))
+    suffix = [c.call.total_tokens for c in calls]
+
+    def step(i):
+        calls[i % N_DRAWS].run()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    if not args.no_kernel_events:
+        B.gdn_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prep_ms = recur_ms = 0.0
+    if not args.no_kernel_events:
+        prep_ms, recur_ms, n_prof = B.gdn_profile_collect()
+        B.gdn_profile_enable(False)
+        assert n_prof == args.steps
+
+    tokens = sum(suffix[i % N_DRAWS] for i in range(args.steps))
+    wall = t1 - t0
+    value = tokens / wall
+    token_heads = tokens * HEADS
+
+    out = {
+        "metric": "recomputed suffix tokens/sec/GPU (resume+ckpt emit)",
+        "value": value,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": 1e3 * wall / args.steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1]: 1 layer, batch 1, 16 heads, d_k=d_v=128, N=8192, M=16 checkpoints at 512 i, "
+                        "depth ~ U[0,N), bf16 inputs, fp32 state and outputs",
+            "draws": N_DRAWS, "seed": SEED,
+            "depths": [int(x) for x in r.meta["depths"]],
+            "suffix_tokens": suffix,
+            "mean_suffix_tokens": float(np.mean(suffix)),
+            "emits_per_step": float(np.mean([int(r.emit_cu[i + 1] - r.emit_cu[i]) for i in range(N_DRAWS)])),
+            "chunk": C,
+        },
+    }
+
+    if not args.no_kernel_events:
+        dom = "gdn_recur_kernel" if recur_ms >= prep_ms else "gdn_prep_kernel"
+        dom_ms = max(recur_ms, prep_ms)
+        dom_flop = FLOP_RECUR if recur_ms >= prep_ms else FLOP_PREP
+        achieved = token_heads * dom_flop / (dom_ms * 1e-3) / 1e12
+        out["roofline"] = {
+            "bound": "mfma", "kernel": dom,
+            "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_MFMA_TFLOPS,
+            "traffic": None,
+            "avg_launch_ms": dom_ms / args.steps,
+            "flop_per_token_head": dom_flop,
+        }
+        out["kernels"] = {
+            "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps,
+                                "tflops": token_heads * FLOP_PREP / (prep_ms * 1e-3) / 1e12},
+            "gdn_recur_kernel": {"avg_ms": recur_ms / args.steps,
+                                 "tflops": token_heads * FLOP_RECUR / (recur_ms * 1e-3) / 1e12},
+            "both_kernels_hbm_gbs_algorithmic": token_heads * BYTES_TOKEN_HEAD / ((prep_ms + recur_ms) * 1e-3) / 1e9,
+            "host_overhead_ms_per_step": 1e3 * wall / args.steps - (prep_ms + recur_ms) / args.steps,
+        }
+
+    # ---- standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB each way
+    try:
+        n_copy, elems = 256, HEADS * D * D
+        big = torch.randn((n_copy * 2, elems), dtype=torch.float32, device=dev)
+        stage = torch.empty((n_copy, elems), dtype=torch.float32, device=dev)
+        ids = np.random.default_rng(SEED).permutation(n_copy * 2)[:n_copy].astype(np.int32)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for _ in range(3):
+            B.ckpt_gather(big, ids, stage)
+            B.ckpt_scatter(big, ids, stage)
+        reps = 20
+        ev[0].record()
+        for _ in range(reps):
+            B.ckpt_gather(big, ids, stage)
+        ev[1].record()
+        for _ in range(reps):
+            B.ckpt_scatter(big, ids, stage)
+        ev[2].record()
+        torch.cuda.synchronize()
+        nbytes = 2.0 * n_copy * elems * 4
+        out["ckpt_copy"] = {
+            "states": n_copy, "state_bytes": elems * 4,
+            "gather_gbs": nbytes * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
+            "scatter_gbs": nbytes * reps / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9,
+            "peak_gbs": PEAK_HBM_GBS,
+        }
+        del big, stage
+    except Exception as exc:  # the copies are a side measurement; never lose the main line
+        out["ckpt_copy"] = {"error": str(exc)}
+
+    # ---- the oracle on the host cores, same workload (all draws once)
+    if not args.no_cpu_baseline:
+        from oracle import gdn_oracle as orc
+        pool_host = pool.cpu().numpy()
+        s0 = calls[0].call
+        orc.resume_prefill(*s0.streams.slice(0, 64).fields(), [0, 64], [0], [-1], [0, 0], [])  # load + warm
+        tc0 = time.perf_counter()
+        cpu_tokens = 0
+        for c in calls:
+            cc = c.call
+            orc.resume_prefill(*cc.streams.fields(), cc.cu_seqlens, cc.start_pos, cc.src_slot, cc.emit_cu,
+                               cc.emit_pos, state_src=pool_host)
+            cpu_tokens += cc.total_tokens
+        tc1 = time.perf_counter()
+        out["cpu_baseline"] = {
+            "value": cpu_tokens / (tc1 - tc0), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"all {N_DRAWS} draws of the same workload once ({cpu_tokens} suffix tokens x {HEADS} heads), "
+                      f"fp64 token loop, one (layer, head) chain per thread",
+            "seconds": tc1 - tc0,
+        }
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

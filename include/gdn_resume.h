@@ -161,6 +161,17 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
                            const int32_t *emit_slot,
                            void *o, void *workspace, int64_t workspace_bytes, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks (not a step of the method).  While enabled, every
+ * gdn_resume_prefill call records HIP events on its stream around its two kernels (chunk
+ * preparation, chunk recurrence).  gdn_profile_enable(1) clears the totals and starts
+ * recording, gdn_profile_enable(0) stops.  gdn_profile_collect waits (on the host) for the
+ * recorded events and returns the summed kernel intervals in milliseconds and the number of
+ * calls since recording started; any output pointer may be NULL.
+ */
+int32_t gdn_profile_enable(int32_t on);
+int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls);
+
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);
 

@@ -50,6 +50,10 @@ def lib():
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2605_05219_amd.build)")
         L = ctypes.CDLL(LIB_PATH)
         L.gdn_version.restype = _i32
+        L.gdn_profile_enable.restype = _i32
+        L.gdn_profile_enable.argtypes = [_i32]
+        L.gdn_profile_collect.restype = _i32
+        L.gdn_profile_collect.argtypes = [_vp, _vp, _vp]
         L.gdn_deepest_ckpt.restype = _i32
         L.gdn_deepest_ckpt.argtypes = [_vp, _i32, _i32]
         L.gdn_plan_chunks.restype = _i32
@@ -68,7 +72,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["gdn_version", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+EXPORTS = ["gdn_version", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill"]
 
 
@@ -104,6 +108,17 @@ def make_shape(L, H_qk, H_v, d_k, d_v, in_dtype, o_dtype, T_alloc, scale=1.0) ->
 # ----------------------------------------------------------------------------- host-only entry points
 def gdn_version() -> int:
     return int(lib().gdn_version())
+
+
+def gdn_profile_enable(on: bool) -> None:
+    _check(lib().gdn_profile_enable(1 if on else 0), "gdn_profile_enable")
+
+
+def gdn_profile_collect():
+    """(prep kernel ms, recurrence kernel ms, calls) summed since profiling was enabled."""
+    a, b, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int64(0)
+    _check(lib().gdn_profile_collect(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)), "gdn_profile_collect")
+    return a.value, b.value, n.value
 
 
 def gdn_deepest_ckpt(pos: Sequence[int], t: int) -> int:

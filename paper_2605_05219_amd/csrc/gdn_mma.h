@@ -23,6 +23,7 @@ typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // Output row (within a 32x32 tile) held by accumulator register idx of half-wave g.
 __device__ __forceinline__ int acc_row(int idx, int g) { return 8 * (idx >> 2) + 4 * g + (idx & 3); }
@@ -95,23 +96,30 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ float load1(const In* p) { return *p; }
 };
 
-// Byte layout of one (chunk, layer, value head) unit of the workspace.  The first
-// `staged_bytes` are an image of the LDS tiles the recurrence kernel stages with one linear
-// copy; the accumulator-ordered U~ follows.
+// Byte layout of one (chunk, layer, value head) unit of the workspace.
+//
+// The chunk operands the recurrence kernel multiplies from the left (W, Q, K^T, P) are stored
+// "fragment-major": fragment f of an operand is the 64-lane vector of MFMA A operands of one
+// step, at [f][lane], so a wave fetches a step's operand with one fully coalesced vector load
+// (from global memory, or from an LDS copy of the image without bank conflicts).  Fragment
+// numbering: (row tile rt, step s) -> rt * steps + s, a row tile being 32 rows of the operand.
+// The first STAGED_BYTES are what the recurrence kernel may copy to LDS in one linear pass;
+// the accumulator-ordered U~ (fp32) follows.
 template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int C = 64;
-    static constexpr int PAD = Elem<E>::PAD;
-    static constexpr int W_LD = DK + PAD;    // W   [C][DK]  row = token, along d_k
-    static constexpr int KT_LD = C + PAD;    // K^T [DK][C]  row = d_k index, along tokens
-    static constexpr int P_LD = C + PAD;     // P   [C][C]   row = query token, along key tokens
-    static constexpr int W_OFF = 0;
-    static constexpr int KT_OFF = W_OFF + C * W_LD * (int)sizeof(E);
-    static constexpr int P_OFF = KT_OFF + DK * KT_LD * (int)sizeof(E);
-    static constexpr int AUX_OFF = P_OFF + C * P_LD * (int)sizeof(E);   // gam[C], dec[C] floats
+    typedef typename Elem<E>::Frag Frag;
+    static constexpr int FRAG_BYTES = 64 * (int)sizeof(Frag);            // one step of one wave
+    static constexpr int NKD = DK / Elem<E>::KSTEP;                       // steps over d_k
+    static constexpr int NKC = C / Elem<E>::KSTEP;                        // steps over the chunk's tokens
+    static constexpr int W_OFF = 0;                                       // W   [C][DK]: 2 row tiles x NKD
+    static constexpr int Q_OFF = W_OFF + 2 * NKD * FRAG_BYTES;            // Q   [C][DK]: 2 row tiles x NKD
+    static constexpr int KT_OFF = Q_OFF + 2 * NKD * FRAG_BYTES;           // K^T [DK][C]: DK/32 row tiles x NKC
+    static constexpr int P_OFF = KT_OFF + (DK / 32) * NKC * FRAG_BYTES;   // P   [C][C]:  2 row tiles x NKC
+    static constexpr int AUX_OFF = P_OFF + 2 * NKC * FRAG_BYTES;          // gam[C], dec[C] floats
     static constexpr int STAGED_BYTES = AUX_OFF + 2 * C * (int)sizeof(float);
-    static constexpr int UT_OFF = STAGED_BYTES;                          // U~ fragments, fp32
+    static constexpr int UT_OFF = STAGED_BYTES;                           // U~ accumulators, fp32
     static constexpr int UNIT_BYTES = UT_OFF + C * DV * (int)sizeof(float);
-    static_assert(KT_OFF % 16 == 0 && P_OFF % 16 == 0 && AUX_OFF % 16 == 0 && STAGED_BYTES % 16 == 0, "16-byte pieces");
+    static_assert(STAGED_BYTES % 16 == 0 && UNIT_BYTES % 256 == 0, "vector-copy granularity");
 };
 
 }  // namespace gdn

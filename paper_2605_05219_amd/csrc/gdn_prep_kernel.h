@@ -9,7 +9,11 @@
 //     W  = -T diag(b gam) K          [C][d_k]   (so that U = U~ + W S_0^T)
 //     U~ =  T diag(b) V              [C][d_v]   fp32, in the recurrence kernel's accumulator order
 //     P_ij = scale * exp(g_i-g_j) (q_i.k_j), j <= i   [C][C]
-//     K^T, gam_i, dec_i = exp(g_C - g_i)
+//     Q, K^T (converted), gam_i, dec_i = exp(g_C - g_i)
+// W, Q, K^T and P leave in fragment-major order (see UnitLayout).  A product's accumulator tile
+// already holds, lane for lane, the fragments of its transpose, so W and P go from the
+// accumulators to global memory with coalesced stores; Q and K^T fragments are the operands
+// this kernel loaded for its own products.
 // Tokens past the chunk's valid length are identity tokens (a = 1, b = 0, k = q = v = 0), which
 // leave the state untouched, so a short chunk needs no special arithmetic.
 #pragma once
@@ -57,7 +61,7 @@ struct PrepSmem {
     static constexpr int LF_LD = C + 1;
     static constexpr int T_LD = C + PAD;  // Tb / Tbg rows
     static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
-    // region A: K [C][DK+PAD], later the P image, later the W image
+    // region A: K [C][DK+PAD]
     static constexpr int A_OFF = 0;
     static constexpr int A_BYTES = a16(C * (DK + PAD) * (int)sizeof(E));
     // region B: Q [C][DK+PAD], later Tb and Tbg
@@ -65,7 +69,8 @@ struct PrepSmem {
     static constexpr int TB_BYTES = a16(C * T_LD * (int)sizeof(E));
     static constexpr int B_BYTES = (A_BYTES > 2 * TB_BYTES) ? A_BYTES : 2 * TB_BYTES;
     static constexpr int KT_OFF = B_OFF + B_BYTES;
-    static constexpr int KT_BYTES = a16(DK * U::KT_LD * (int)sizeof(E));
+    static constexpr int KT_LD = C + PAD;
+    static constexpr int KT_BYTES = a16(DK * KT_LD * (int)sizeof(E));
     static constexpr int VT_OFF = KT_OFF + KT_BYTES;
     static constexpr int VT_BYTES = a16(DV * (C + PAD) * (int)sizeof(E));
     static constexpr int LF_OFF = VT_OFF + VT_BYTES;
@@ -84,7 +89,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     constexpr int C = 64;
     constexpr int PAD = EL::PAD;
     constexpr int K_LD = DK + PAD;
-    constexpr int KT_LD = U::KT_LD;
+    constexpr int KT_LD = SM::KT_LD;
     constexpr int VT_LD = C + PAD;
     constexpr int LF_LD = SM::LF_LD;
     constexpr int T_LD = SM::T_LD;
@@ -99,8 +104,6 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     float* bS = gS + C;
     float* gamS = bS + C;
     float* decS = gamS + C;
-    E* Pt = Ks;                                           // after the first products
-    E* Wt = Ks;                                           // after P has been copied out
     E* Tb = Qs;                                           // after the first products
     E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
 
@@ -119,6 +122,11 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     const int n = a.chunk_len[c];
     const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
     char* unit = a.ws_units + ((int64_t)(c * a.L + l) * a.H_v + hv) * U::UNIT_BYTES;
+    Frag* w_img = reinterpret_cast<Frag*>(unit + U::W_OFF);
+    Frag* q_img = reinterpret_cast<Frag*>(unit + U::Q_OFF);
+    Frag* kt_img = reinterpret_cast<Frag*>(unit + U::KT_OFF);
+    Frag* p_img = reinterpret_cast<Frag*>(unit + U::P_OFF);
+    constexpr int SPT = EL::STEPS_PER_TILE;
 
     // ---- gates: g_i = inclusive running sum of log a (wave 0), b_i; identity beyond n
     if (wave == 0) {
@@ -183,13 +191,11 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     }
     __syncthreads();
 
-    // ---- K K^T -> L (fp32) and K Q^T -> P (kept in registers until K is dead)
+    // ---- K K^T -> L (fp32) and K Q^T -> P fragments
     //      wave 0: KK(0,0) KQ(0,0)   wave 1: KK(1,0)   wave 2: KK(1,1) KQ(1,1)   wave 3: KQ(0,1)
     constexpr int NKD = DK / EL::KSTEP;
-    f32x16 accP;
-    int p_mj = -1, p_ni = -1;
     {
-        int kk_mi = -1, kk_nj = -1;
+        int kk_mi = -1, kk_nj = -1, p_mj = -1, p_ni = -1;
         if (wave == 0) { kk_mi = 0; kk_nj = 0; p_mj = 0; p_ni = 0; }
         if (wave == 1) { kk_mi = 1; kk_nj = 0; }
         if (wave == 2) { kk_mi = 1; kk_nj = 1; p_mj = 1; p_ni = 1; }
@@ -210,11 +216,18 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
             }
         }
         if (p_mj >= 0) {
+            // D[key j][query i]: the accumulators of lane (i, g) are row i of P at the key
+            // positions that lane carries as an A operand, i.e. P's fragments (row tile p_ni).
             f32x16 acc = {0};
             const E* ar = Ks + (32 * p_mj + lr) * K_LD;   // rows: key token j
             const E* br = Qs + (32 * p_ni + lr) * K_LD;   // rows: query token i
+            const bool write_q = (p_mj == p_ni);          // waves 0 and 2 also emit Q's fragments
 #pragma unroll
-            for (int s = 0; s < NKD; ++s) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+            for (int s = 0; s < NKD; ++s) {
+                const Frag qf = EL::load(br, s, g);
+                if (write_q) q_img[(p_ni * NKD + s) * 64 + lane] = qf;
+                acc = EL::mma(EL::load(ar, s, g), qf, acc);
+            }
             const int i = 32 * p_ni + lr;
             const float gi = gS[i];
 #pragma unroll
@@ -223,21 +236,12 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
                 const float val = a.scale * expf(fminf(gi - gS[j], 0.f)) * acc[idx];
                 acc[idx] = (j <= i) ? val : 0.f;
             }
-            accP = acc;
+#pragma unroll
+            for (int sub = 0; sub < SPT; ++sub)
+                p_img[(p_ni * U::NKC + p_mj * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
         }
     }
-    __syncthreads();  // K, Q in LDS are dead; L is complete
-
-    // ---- P image into region A; wave 1 clears the all-zero quadrant (i < 32, j >= 32)
-    if (p_mj >= 0) {
-        const int i = 32 * p_ni + lr;
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-            EL::store4(Pt + i * U::P_LD + 32 * p_mj + 8 * b + 4 * g, accP[4 * b], accP[4 * b + 1], accP[4 * b + 2], accP[4 * b + 3]);
-    } else {
-#pragma unroll
-        for (int b = 0; b < 4; ++b) EL::store4(Pt + lr * U::P_LD + 32 + 8 * b + 4 * g, 0.f, 0.f, 0.f, 0.f);
-    }
+    __syncthreads();  // L is complete; K, Q in LDS are dead
 
     // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks by forward
     //      substitution, one per wave, column (lane & 15) of the inverse in registers.
@@ -256,15 +260,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
             for (int r = 0; r < 16; ++r) Lf[(base + r) * LF_LD + base + cc] = x[r];
         }
     }
-    __syncthreads();  // diagonal blocks of T in place; P image complete
-
-    // copy the P image out while the inversion goes on (region A is not touched until W)
-    {
-        const uint4* src = reinterpret_cast<const uint4*>(Pt);
-        uint4* dst = reinterpret_cast<uint4*>(unit + U::P_OFF);
-        constexpr int N16 = C * U::P_LD * (int)sizeof(E) / 16;
-        for (int i = tid; i < N16; i += 256) dst[i] = src[i];
-    }
+    __syncthreads();  // diagonal blocks of T in place
 
     const int m16 = lane & 15, g4 = lane >> 4;
     auto blk = [&](int br, int bc) -> const float* { return Lf + (16 * br) * LF_LD + 16 * bc; };
@@ -319,8 +315,9 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     }
     __syncthreads();
 
-    // ---- W^T tile (mt, nt): D[d_k][token i] = sum_j K^T[d_k][j] Tbg[i][j]   -> W image [i][d_k]
-    //      T is lower triangular: token tile 0 only contracts over j < 32.
+    // ---- W^T tile (mt, nt): D[d_k][token i] = sum_j K^T[d_k][j] Tbg[i][j].  The accumulators of
+    //      lane (i, g) are W's fragments of row tile nt, steps SPT*mt ..; the A operands are
+    //      K^T's fragments.  T is lower triangular: token tile 0 only contracts over j < 32.
     constexpr int NKC = C / EL::KSTEP;
     for (int t = wave; t < (DK / 32) * 2; t += 4) {
         const int mt = t >> 1, nt = t & 1;
@@ -330,11 +327,14 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         const int ns = (nt == 0) ? NKC / 2 : NKC;
 #pragma unroll
         for (int s = 0; s < NKC; ++s)
-            if (s < ns) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
-        const int i = 32 * nt + lr;
+            if (s < ns) {
+                const Frag kf = EL::load(ar, s, g);
+                if (nt == 1) kt_img[(mt * NKC + s) * 64 + lane] = kf;
+                acc = EL::mma(kf, EL::load(br, s, g), acc);
+            }
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-            EL::store4(Wt + i * U::W_LD + 32 * mt + 8 * b + 4 * g, acc[4 * b], acc[4 * b + 1], acc[4 * b + 2], acc[4 * b + 3]);
+        for (int sub = 0; sub < SPT; ++sub)
+            w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
     }
     // ---- U~ tile (slice sl, token tile rt): D[token][d_v] = sum_j Tb[token][j] V^T[d_v][j]
     //      stored as the recurrence kernel's accumulators: [sl][rt][b][lane] float4
@@ -356,18 +356,8 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
             }
         }
     }
-    __syncthreads();
-
-    // ---- copy the W and K^T images and the per-token scale factors out
+    // ---- per-token scale factors
     {
-        const uint4* src = reinterpret_cast<const uint4*>(Wt);
-        uint4* dst = reinterpret_cast<uint4*>(unit + U::W_OFF);
-        constexpr int NW16 = C * U::W_LD * (int)sizeof(E) / 16;
-        for (int i = tid; i < NW16; i += 256) dst[i] = src[i];
-        const uint4* src2 = reinterpret_cast<const uint4*>(KTs);
-        uint4* dst2 = reinterpret_cast<uint4*>(unit + U::KT_OFF);
-        constexpr int NK16 = DK * U::KT_LD * (int)sizeof(E) / 16;
-        for (int i = tid; i < NK16; i += 256) dst2[i] = src2[i];
         float* aux = reinterpret_cast<float*>(unit + U::AUX_OFF);
         if (tid < C) aux[tid] = gamS[tid];
         else if (tid < 2 * C) aux[tid] = decS[tid - C];

@@ -133,11 +133,52 @@ int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream
     return GDN_OK;
 }
 
-// ------------------------------------------------------------------ kernel dispatch
-struct DevicePlan {
-    const int32_t *chunk_tok0, *chunk_len, *chunk_emit_slot, *req_chunk_cu, *req_src_slot, *req_order;
+// ------------------------------------------------------------------ optional per-kernel timing
+// When switched on, every prefill call records three events on its stream (before the prep
+// kernel, between the kernels, after the recurrence kernel); collect() waits for them and sums
+// the two intervals.  Off by default: nothing is recorded.
+struct Profiler {
+    std::mutex mu;
+    bool on = false;
+    std::vector<hipEvent_t> spare;
+    std::vector<hipEvent_t> pending;  // triples
+    double prep_ms = 0.0, recur_ms = 0.0;
+    int64_t calls = 0;
+
+    hipEvent_t get() {
+        if (!spare.empty()) {
+            hipEvent_t e = spare.back();
+            spare.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+Profiler g_prof;
+
+struct ProfScope {
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    bool active = false;
+    hipStream_t stream;
+    explicit ProfScope(hipStream_t s) : stream(s) {
+        std::lock_guard<std::mutex> lock(g_prof.mu);
+        if (!g_prof.on) return;
+        for (auto& e : ev) e = g_prof.get();
+        active = ev[0] && ev[1] && ev[2];
+    }
+    void mark(int i) {
+        if (active) (void)hipEventRecord(ev[i], stream);
+    }
+    ~ProfScope() {
+        if (!active) return;
+        std::lock_guard<std::mutex> lock(g_prof.mu);
+        for (auto e : ev) g_prof.pending.push_back(e);
+    }
 };
 
+// ------------------------------------------------------------------ kernel dispatch
 template <typename E, int DK, int DV>
 int64_t unit_bytes_of() { return UnitLayout<E, DK, DV>::UNIT_BYTES; }
 
@@ -154,18 +195,18 @@ int recur_waves_override() {
     return v;
 }
 
-template <typename E, int DK, int DV, int NW>
+template <typename E, int DK, int DV, int NW, bool STAGED>
 hipError_t launch_recur_nw(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
     constexpr int SG = (DV / 32) / NW;
-    constexpr int smem = recur_smem_bytes<E, DK, DV>();
+    constexpr int smem = recur_smem_bytes<E, DK, DV>(STAGED);
     static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW>),
+    if (!attr_set && smem > 0) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW, STAGED>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
+    hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW, STAGED>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
     return hipGetLastError();
 }
 
@@ -181,9 +222,12 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
         attr_set = true;
     }
     const int units = s.L * s.H_v;
+    ProfScope prof(stream);
+    prof.mark(0);
     hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)n_chunks, (unsigned)units), dim3(256), SM::BYTES, stream, pa);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_err(e);
+    prof.mark(1);
 
     // Waves (d_v slices) per workgroup of the recurrence: as many as still leave the chip full;
     // few chains -> one wave per workgroup so that the slices spread over more compute units.
@@ -194,9 +238,10 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && NS == 4)) nw = o;
     }
-    if (nw == 1) e = launch_recur_nw<E, DK, DV, 1>(ra, n_chains, stream);
-    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
-    else e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
+    if (nw == 1) e = launch_recur_nw<E, DK, DV, 1, false>(ra, n_chains, stream);
+    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2, true>(ra, n_chains, stream);
+    else e = launch_recur_nw<E, DK, DV, NS, true>(ra, n_chains, stream);
+    prof.mark(2);
     return hip_err(e);
 }
 
@@ -208,6 +253,41 @@ using namespace gdn;
 extern "C" {
 
 int32_t gdn_version(void) { return 100; }
+
+int32_t gdn_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    g_prof.on = on != 0;
+    if (on) {
+        for (auto e : g_prof.pending) g_prof.spare.push_back(e);
+        g_prof.pending.clear();
+        g_prof.prep_ms = g_prof.recur_ms = 0.0;
+        g_prof.calls = 0;
+    }
+    return GDN_OK;
+}
+
+int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls) {
+    std::lock_guard<std::mutex> lock(g_prof.mu);
+    for (size_t i = 0; i + 2 < g_prof.pending.size(); i += 3) {
+        hipEvent_t* ev = &g_prof.pending[i];
+        hipError_t e = hipEventSynchronize(ev[2]);
+        if (e != hipSuccess) return hip_err(e);
+        float a = 0.f, b = 0.f;
+        e = hipEventElapsedTime(&a, ev[0], ev[1]);
+        if (e != hipSuccess) return hip_err(e);
+        e = hipEventElapsedTime(&b, ev[1], ev[2]);
+        if (e != hipSuccess) return hip_err(e);
+        g_prof.prep_ms += a;
+        g_prof.recur_ms += b;
+        g_prof.calls += 1;
+    }
+    for (auto e : g_prof.pending) g_prof.spare.push_back(e);
+    g_prof.pending.clear();
+    if (prep_ms) *prep_ms = g_prof.prep_ms;
+    if (recur_ms) *recur_ms = g_prof.recur_ms;
+    if (calls) *calls = g_prof.calls;
+    return GDN_OK;
+}
 
 int32_t gdn_deepest_ckpt(const int32_t* pos, int32_t M, int32_t t) {
     if (!pos || M <= 0) return -1;
@@ -345,7 +425,7 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     pa.scale = s.scale;
 
     RecurArgs ra;
-    ra.q = q; ra.o = o; ra.ws_units = ws_units;
+    ra.o = o; ra.ws_units = ws_units;
     ra.chunk_tok0 = d;
     ra.chunk_len = d + n_chunks;
     ra.chunk_emit_slot = d + 2 * (int64_t)n_chunks;
