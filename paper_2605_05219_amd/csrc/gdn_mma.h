@@ -111,14 +111,23 @@ template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int FRAG_BYTES = 64 * (int)sizeof(Frag);            // one step of one wave
     static constexpr int NKD = DK / Elem<E>::KSTEP;                       // steps over d_k
     static constexpr int NKC = C / Elem<E>::KSTEP;                        // steps over the chunk's tokens
-    static constexpr int W_OFF = 0;                                       // W   [C][DK]: 2 row tiles x NKD
-    static constexpr int Q_OFF = W_OFF + 2 * NKD * FRAG_BYTES;            // Q   [C][DK]: 2 row tiles x NKD
-    static constexpr int KT_OFF = Q_OFF + 2 * NKD * FRAG_BYTES;           // K^T [DK][C]: DK/32 row tiles x NKC
-    static constexpr int P_OFF = KT_OFF + (DK / 32) * NKC * FRAG_BYTES;   // P   [C][C]:  2 row tiles x NKC
-    static constexpr int AUX_OFF = P_OFF + 2 * NKC * FRAG_BYTES;          // gam[C], dec[C] floats
-    static constexpr int STAGED_BYTES = AUX_OFF + 2 * C * (int)sizeof(float);
+    static constexpr int W_BYTES = 2 * NKD * FRAG_BYTES;                  // W   [C][DK]: 2 row tiles x NKD
+    static constexpr int KT_BYTES = (DK / 32) * NKC * FRAG_BYTES;         // K^T [DK][C]: DK/32 row tiles x NKC
+    static constexpr int AUX_BYTES = 1024;                                // gam[C], dec[C] floats, padded
+    static constexpr int Q_BYTES = 2 * NKD * FRAG_BYTES;                  // Q   [C][DK]: 2 row tiles x NKD
+    static constexpr int P_BYTES = 2 * NKC * FRAG_BYTES;                  // P   [C][C]:  2 row tiles x NKC
+    // what the state-dependent chain needs first (W, K^T, scale factors) is one contiguous run
+    static constexpr int W_OFF = 0;
+    static constexpr int KT_OFF = W_OFF + W_BYTES;
+    static constexpr int AUX_OFF = KT_OFF + KT_BYTES;
+    static constexpr int CHAIN_BYTES = AUX_OFF + AUX_BYTES;
+    static constexpr int Q_OFF = CHAIN_BYTES;
+    static constexpr int P_OFF = Q_OFF + Q_BYTES;
+    static constexpr int STAGED_BYTES = P_OFF + P_BYTES;
     static constexpr int UT_OFF = STAGED_BYTES;                           // U~ accumulators, fp32
+    static constexpr int UT_SLICE_BYTES = C * 32 * (int)sizeof(float);    // one 32-column slice
     static constexpr int UNIT_BYTES = UT_OFF + C * DV * (int)sizeof(float);
+    static_assert(CHAIN_BYTES % 1024 == 0 && UT_OFF % 1024 == 0, "1 KiB pieces for wave-wide 16-byte copies");
     static_assert(STAGED_BYTES % 16 == 0 && UNIT_BYTES % 256 == 0, "vector-copy granularity");
 };
 

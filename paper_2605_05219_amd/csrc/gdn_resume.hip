@@ -195,18 +195,32 @@ int recur_waves_override() {
     return v;
 }
 
-template <typename E, int DK, int DV, int NW, bool STAGED>
+template <typename E, int DK, int DV, int NW>
 hipError_t launch_recur_nw(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
     constexpr int SG = (DV / 32) / NW;
-    constexpr int smem = recur_smem_bytes<E, DK, DV>(STAGED);
+    constexpr int smem = recur_smem_bytes<E, DK, DV>();
     static bool attr_set = false;
-    if (!attr_set && smem > 0) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW, STAGED>),
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW, STAGED>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
+    hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
+    return hipGetLastError();
+}
+
+template <typename E, int DK, int DV>
+hipError_t launch_recur_trio(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
+    constexpr int smem = TrioSmem<E, DK, DV>::BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_trio_kernel<E, DK, DV>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gdn_recur_trio_kernel<E, DK, DV>), dim3((unsigned)(n_chains * (DV / 32))), dim3(192), smem, stream, ra);
     return hipGetLastError();
 }
 
@@ -229,8 +243,10 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
     if (e != hipSuccess) return hip_err(e);
     prof.mark(1);
 
-    // Waves (d_v slices) per workgroup of the recurrence: as many as still leave the chip full;
-    // few chains -> one wave per workgroup so that the slices spread over more compute units.
+    // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain share
+    // one workgroup and one LDS copy of the chunk operands; with fewer, two slices per workgroup;
+    // with too few to occupy every compute unit, the latency variant (chain, output and
+    // loader waves per slice).
     const int64_t n_chains = (int64_t)n_req * units;
     constexpr int NS = DV / 32;
     int nw = NS;
@@ -238,9 +254,9 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && NS == 4)) nw = o;
     }
-    if (nw == 1) e = launch_recur_nw<E, DK, DV, 1, false>(ra, n_chains, stream);
-    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2, true>(ra, n_chains, stream);
-    else e = launch_recur_nw<E, DK, DV, NS, true>(ra, n_chains, stream);
+    if (nw == 1) e = launch_recur_trio<E, DK, DV>(ra, n_chains, stream);
+    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
+    else e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
     prof.mark(2);
     return hip_err(e);
 }
@@ -438,6 +454,8 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     ra.T_alloc = s.T_alloc;
     ra.scale = s.scale;
     ra.o_bf16 = s.o_dtype == GDN_BF16;
+    ra.debug_same_unit = std::getenv("GDN_DEBUG_SAME_UNIT") != nullptr;
+
 
     if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
     if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
