@@ -96,6 +96,9 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ float load1(const In* p) { return *p; }
 };
 
+// Words that follow gam[64], dec[64] in a unit's aux block (int32).
+enum { AUX_EMIT_SLOT = 0, AUX_TOK0 = 1, AUX_LEN = 2 };
+
 // Byte layout of one (chunk, layer, value head) unit of the workspace.
 //
 // The chunk operands the recurrence kernel multiplies from the left (W, Q, K^T, P) are stored
@@ -113,7 +116,7 @@ template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int NKC = C / Elem<E>::KSTEP;                        // steps over the chunk's tokens
     static constexpr int W_BYTES = 2 * NKD * FRAG_BYTES;                  // W   [C][DK]: 2 row tiles x NKD
     static constexpr int KT_BYTES = (DK / 32) * NKC * FRAG_BYTES;         // K^T [DK][C]: DK/32 row tiles x NKC
-    static constexpr int AUX_BYTES = 1024;                                // gam[C], dec[C] floats, padded
+    static constexpr int AUX_BYTES = 1024;                                // gam[C], dec[C] floats, bookkeeping words, padded
     static constexpr int Q_BYTES = 2 * NKD * FRAG_BYTES;                  // Q   [C][DK]: 2 row tiles x NKD
     static constexpr int P_BYTES = 2 * NKC * FRAG_BYTES;                  // P   [C][C]:  2 row tiles x NKC
     // what the state-dependent chain needs first (W, K^T, scale factors) is one contiguous run

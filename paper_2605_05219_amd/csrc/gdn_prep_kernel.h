@@ -9,7 +9,7 @@
 //     W  = -T diag(b gam) K          [C][d_k]   (so that U = U~ + W S_0^T)
 //     U~ =  T diag(b) V              [C][d_v]   fp32, in the recurrence kernel's accumulator order
 //     P_ij = scale * exp(g_i-g_j) (q_i.k_j), j <= i   [C][C]
-//     Q, K^T (converted), gam_i, dec_i = exp(g_C - g_i)
+//     Q, K^T (converted), gam_i, dec_i = exp(g_C - g_i), and the chunk's bookkeeping words
 // W, Q, K^T and P leave in fragment-major order (see UnitLayout).  A product's accumulator tile
 // already holds, lane for lane, the fragments of its transpose, so W and P go from the
 // accumulators to global memory with coalesced stores; Q and K^T fragments are the operands
@@ -29,6 +29,7 @@ struct PrepArgs {
     const void* gate;
     const int32_t* chunk_tok0;
     const int32_t* chunk_len;
+    const int32_t* chunk_emit_slot;
     char* ws_units;       // unit (c, l, h) at ((c * L + l) * H_v + h) * UNIT_BYTES
     int32_t L, H_qk, H_v;
     int64_t T_alloc;
@@ -109,7 +110,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
     const int g = lane >> 5;
 
@@ -361,6 +362,13 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         float* aux = reinterpret_cast<float*>(unit + U::AUX_OFF);
         if (tid < C) aux[tid] = gamS[tid];
         else if (tid < 2 * C) aux[tid] = decS[tid - C];
+        else if (tid == 2 * C) {
+            // the chunk's bookkeeping rides along, so the recurrence never waits on a lookup
+            int32_t* meta = reinterpret_cast<int32_t*>(aux + 2 * C);
+            meta[AUX_EMIT_SLOT] = a.chunk_emit_slot[c];
+            meta[AUX_TOK0] = tok0;
+            meta[AUX_LEN] = n;
+        }
     }
 }
 

@@ -1,15 +1,14 @@
-// Recurrence kernel: the state-dependent part, sequential over the chunks of one chain
+// Recurrence kernels: the state-dependent part, sequential over the chunks of one chain
 // (request, layer, value head).  Each wave owns a 32-column slice of d_v for the whole chain:
 // the slice of the state (as S^T, d_k x 32, fp32 accumulators), of U and of O.  Rows of the
-// state are independent given the chunk's W, Q, K^T and P, so waves never exchange data; a
-// workgroup is NW waves (slices) of one chain sharing the staged tiles in LDS.
+// state are independent given the chunk's W, Q, K^T and P, so slices never exchange data.
 //
 // Per chunk, with S the state at the chunk start (all products on the matrix cores, the
-// left operands read as ready-made fragments, the state-derived right operands fed from
+// chunk operands read as ready-made fragments, the state-derived operands fed from
 // registers):
-//     U  = U~ + W S^T                      [C][32]
-//     O  = diag(gam) (Q S^T) + P U         [C][32]   (scale already folded into gam, P)
-//     S^T <- gam_C S^T + K^T-contraction:  S^T[d_k][d_v] += sum_j K[j][d_k] dec_j U[j][d_v]
+//     U   = U~ + W S^T                        [C][32]
+//     O^T = (S Q^T) diag(gam) + U^T P^T       [32][C]   (scale already folded into P)
+//     S^T <- gam_C S^T + K^T-contraction:     S^T[d_k][d_v] += sum_j K[j][d_k] dec_j U[j][d_v]
 // and, when the chunk ends at a checkpoint position, S is stored to its pool slot.
 #pragma once
 #include "gdn_mma.h"
@@ -19,9 +18,6 @@ namespace gdn {
 struct RecurArgs {
     void* o;
     const char* ws_units;
-    const int32_t* chunk_tok0;
-    const int32_t* chunk_len;
-    const int32_t* chunk_emit_slot;  // destination slot after the chunk, or -1
     const int32_t* req_chunk_cu;
     const int32_t* req_src_slot;
     const int32_t* req_order;        // requests, longest chain first
@@ -32,8 +28,37 @@ struct RecurArgs {
     int64_t T_alloc;
     float scale;
     int32_t o_bf16;
-    int32_t debug_same_unit;  // timing experiment: every chunk reads the first unit (wrong results)
 };
+
+// Keeps a value's computation where it is written: the empty statement is opaque to the
+// optimiser and ordered with the scheduling fences, so pure arithmetic cannot drift away from
+// the matrix instruction it is meant to hide under.
+template <typename T>
+__device__ __forceinline__ void pin(T& x) { asm volatile("" : "+v"(x)); }
+
+// S^T tiles of one slice <-> the [d_v][d_k] fp32 state in a pool slot: register 4b+e of tile mt
+// holds S[32 sl + lr][32 mt + 8b + 4g + e], i.e. 16-byte runs along d_k.
+template <int MT>
+__device__ __forceinline__ void load_state(f32x16 (&accS)[MT], const float* src, int g) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const f32x4 x = *reinterpret_cast<const f32x4*>(src + 32 * mt + 8 * b + 4 * g);
+            accS[mt][4 * b] = x[0]; accS[mt][4 * b + 1] = x[1];
+            accS[mt][4 * b + 2] = x[2]; accS[mt][4 * b + 3] = x[3];
+        }
+}
+template <int MT>
+__device__ __forceinline__ void store_state(const f32x16 (&accS)[MT], float* dst, int g) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const f32x4 x = {accS[mt][4 * b], accS[mt][4 * b + 1], accS[mt][4 * b + 2], accS[mt][4 * b + 3]};
+            *reinterpret_cast<f32x4*>(dst + 32 * mt + 8 * b + 4 * g) = x;
+        }
+}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
     uint32_t u = __float_as_uint(x);
@@ -49,31 +74,34 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 // per-token factors gam_i and the "token < n" predicate are per-lane scalars.
 // ot[tt]: tile of token tile tt (lane = token 32 tt + lr, register 4b+e = d_v 32 sl + 8b + 4g + e).
 template <int DV>
-__device__ __forceinline__ void store_o_t(const RecurArgs& a, int64_t row0, int hv, int sl, int lr, int g, int n,
-                                          const f32x16 (&ot)[2]) {
+__device__ __forceinline__ void store_o_tile(const RecurArgs& a, int64_t row0, int hv, int sl, int lr, int g, int n,
+                                             int tt, const f32x16& ot) {
+    const int tok = 32 * tt + lr;
+    if (tok < n) {
+        const int64_t off = ((row0 + tok) * a.H_v + hv) * DV + 32 * sl + 4 * g;
+        if (a.o_bf16) {
+            uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        const int tok = 32 * tt + lr;
-        if (tok < n) {
-            const int64_t off = ((row0 + tok) * a.H_v + hv) * DV + 32 * sl + 4 * g;
-            if (a.o_bf16) {
-                uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t lo = f32_to_bf16_rne(ot[4 * b]) | ((uint32_t)f32_to_bf16_rne(ot[4 * b + 1]) << 16);
+                const uint32_t hi = f32_to_bf16_rne(ot[4 * b + 2]) | ((uint32_t)f32_to_bf16_rne(ot[4 * b + 3]) << 16);
+                *reinterpret_cast<uint2*>(p + 8 * b) = make_uint2(lo, hi);
+            }
+        } else {
+            float* p = reinterpret_cast<float*>(a.o) + off;
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t lo = f32_to_bf16_rne(ot[tt][4 * b]) | ((uint32_t)f32_to_bf16_rne(ot[tt][4 * b + 1]) << 16);
-                    const uint32_t hi = f32_to_bf16_rne(ot[tt][4 * b + 2]) | ((uint32_t)f32_to_bf16_rne(ot[tt][4 * b + 3]) << 16);
-                    *reinterpret_cast<uint2*>(p + 8 * b) = make_uint2(lo, hi);
-                }
-            } else {
-                float* p = reinterpret_cast<float*>(a.o) + off;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 x = {ot[tt][4 * b], ot[tt][4 * b + 1], ot[tt][4 * b + 2], ot[tt][4 * b + 3]};
-                    *reinterpret_cast<f32x4*>(p + 8 * b) = x;
-                }
+            for (int b = 0; b < 4; ++b) {
+                const f32x4 x = {ot[4 * b], ot[4 * b + 1], ot[4 * b + 2], ot[4 * b + 3]};
+                *reinterpret_cast<f32x4*>(p + 8 * b) = x;
             }
         }
     }
+}
+template <int DV>
+__device__ __forceinline__ void store_o_t(const RecurArgs& a, int64_t row0, int hv, int sl, int lr, int g, int n,
+                                          const f32x16 (&ot)[2]) {
+    store_o_tile<DV>(a, row0, hv, sl, lr, g, n, 0, ot[0]);
+    store_o_tile<DV>(a, row0, hv, sl, lr, g, n, 1, ot[1]);
 }
 
 // Throughput variant.  The workgroup copies the unit's fragment image to LDS once per chunk and
@@ -99,7 +127,7 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
     const int g = lane >> 5;
 
@@ -114,21 +142,13 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
     const int c_begin = a.req_chunk_cu[r], c_end = a.req_chunk_cu[r + 1];
     if (c_begin == c_end) return;
 
-    // ---- start state: S^T tiles, register 4b+e of tile mt <-> S[32 sl + lr][32 mt + 8b + 4g + e]
+    // ---- start state
     f32x16 accS[MT];
     const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK + (int64_t)(32 * sl + lr) * DK;
     {
         const int slot = a.req_src_slot[r];
         if (slot >= 0) {
-            const float* src = a.state_src + slot * a.src_slot_stride + head_off;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 x = *reinterpret_cast<const f32x4*>(src + 32 * mt + 8 * b + 4 * g);
-                    accS[mt][4 * b] = x[0]; accS[mt][4 * b + 1] = x[1];
-                    accS[mt][4 * b + 2] = x[2]; accS[mt][4 * b + 3] = x[3];
-                }
+            load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
         } else {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
@@ -155,10 +175,6 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
     if (STAGED) GDN_PREFETCH_IMAGE(unit)
 
     for (int c = c_begin; c < c_end; ++c, unit += unit_stride) {
-        const int tok0 = a.chunk_tok0[c];
-        const int n = a.chunk_len[c];
-        const int eslot = a.chunk_emit_slot[c];
-        const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
 
         const char* img;
         {
@@ -178,6 +194,10 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         const Frag* p_img = reinterpret_cast<const Frag*>(img + U::P_OFF) + lane;
         const float* gamS = reinterpret_cast<const float*>(img + U::AUX_OFF);
         const float* decS = gamS + C;
+        const int32_t* meta = reinterpret_cast<const int32_t*>(gamS + 2 * C);
+        const int eslot = meta[AUX_EMIT_SLOT];
+        const int n = meta[AUX_LEN];
+        const int64_t row0 = (int64_t)l * a.T_alloc + meta[AUX_TOK0];
 
         // U~ (this slice), already in accumulator order
         f32x16 accU[2];
@@ -233,16 +253,7 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         }
 
         // checkpoint emission: exact state after the last token of this chunk
-        if (eslot >= 0) {
-            float* dst = a.state_dst + eslot * a.dst_slot_stride + head_off;
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 x = {accS[mt][4 * b], accS[mt][4 * b + 1], accS[mt][4 * b + 2], accS[mt][4 * b + 3]};
-                    *reinterpret_cast<f32x4*>(dst + 32 * mt + 8 * b + 4 * g) = x;
-                }
-        }
+        if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
 
         // O^T = (S Q^T) diag(gam) + U^T P^T with the state of the chunk start (sf), off the chain
         f32x16 ot[2];
@@ -271,21 +282,24 @@ constexpr int recur_smem_bytes() {
 }
 
 // Latency variant, for calls with too few chains to fill the chip: the per-chunk dependent
-// chain bounds the run time, so it is cut to the minimum and memory latency is taken off it.
-// One workgroup per (chain, d_v slice) with three waves:
-//   wave 0 ("chain")  keeps the state and runs only the dependent part, U = U~ + W S^T and the
-//                     state update, reading W, K^T, U~ and the scale factors from an LDS ring;
-//   wave 1 ("output") computes O = diag(gam) Q S^T + P U one chunk behind, from the state and U
-//                     fragments wave 0 leaves in LDS (double buffered), with Q and P fetched
-//                     into registers a chunk ahead;
-//   wave 2 ("loader") fills the ring two chunks ahead with 16-byte global->LDS loads (lane l of
-//                     an instruction lands at base + 16 l, so 1 KiB of the fragment-major image
-//                     per instruction, no registers).
+// chain bounds the run time, so everything else is taken off it.  One workgroup per
+// (chain, d_v slice) with four waves, one per SIMD:
+//   wave 0 ("chain")      keeps the state and runs only the dependent part, U = U~ + W S^T and
+//                         the state update, reading W, K^T, U~ and the scale factors from an LDS
+//                         ring; its matrix instructions issue back to back, conversions, the
+//                         decay of the state and LDS traffic ride in their shadow;
+//   waves 1, 2 ("output") compute O one chunk behind, one token tile each, from the state and U
+//                         fragments wave 0 leaves in LDS (double buffered), with Q and P fetched
+//                         from global memory into registers three chunks ahead;
+//   wave 3 ("loader")     fills the ring two chunks ahead with 16-byte global->LDS loads (lane l
+//                         of an instruction lands at base + 16 l, so 1 KiB of the fragment-major
+//                         image per instruction, no registers).
 // Ring stage s holds chunk i with i % 3 == s.  Every wave passes one barrier before the first
-// chunk and one after each chunk; the loader reaches the barrier after chunk i only when
-// chunk i+1 has landed, and refills the stage chunk i-1 used right after it.
+// chunk and one per chunk.  The chain wave reaches chunk i's barrier once it has read all it
+// needs of chunk i's stage and has published chunk i's fragments; the loader reaches it only
+// when chunk i+1 has landed, and refills the released stage with chunk i+3 right after it.
 template <typename E, int DK, int DV>
-struct TrioSmem {
+struct QuadSmem {
     typedef UnitLayout<E, DK, DV> U;
     static constexpr int STAGES = 3;
     static constexpr int UT_OFF = U::CHAIN_BYTES;                     // stage: [W | K^T | aux | U~ slice]
@@ -294,7 +308,6 @@ struct TrioSmem {
     static constexpr int XCH_FRAGS = U::NKD + U::NKC;                 // state fragments, then U fragments
     static constexpr int BYTES = XCH_OFF + 2 * XCH_FRAGS * U::FRAG_BYTES;
     static constexpr int DMA_PER_STAGE = STAGE_BYTES / 1024;
-    static_assert(DMA_PER_STAGE < 60, "outstanding-load counter");
     static_assert(BYTES <= 160 * 1024, "LDS");
 };
 
@@ -304,15 +317,18 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
 }
 
+#define GDN_FENCE() __builtin_amdgcn_sched_barrier(0)   // nothing is scheduled across this point
+
 template <typename E, int DK, int DV>
-__global__ void __launch_bounds__(192) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_recur_trio_kernel(RecurArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_recur_quad_kernel(RecurArgs a) {
     typedef Elem<E> EL;
     typedef typename EL::Frag Frag;
     typedef UnitLayout<E, DK, DV> U;
-    typedef TrioSmem<E, DK, DV> SM;
+    typedef QuadSmem<E, DK, DV> SM;
     constexpr int C = 64;
     constexpr int NS = DV / 32;
     constexpr int SPT = EL::STEPS_PER_TILE;
+    constexpr int RPS = 16 / SPT;            // accumulator registers one step consumes as operand
     constexpr int NKD = U::NKD;
     constexpr int NKC = U::NKC;
     constexpr int MT = DK / 32;
@@ -321,7 +337,7 @@ __global__ void __launch_bounds__(192) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
     const int g = lane >> 5;
 
@@ -336,36 +352,51 @@ __global__ void __launch_bounds__(192) __attribute__((amdgpu_waves_per_eu(2, 2))
     if (c_begin == c_end) return;
     const int n_chunks = c_end - c_begin;
 
-    const int64_t unit_stride = a.debug_same_unit ? 0 : (int64_t)units * U::UNIT_BYTES;
+    const int64_t unit_stride = (int64_t)units * U::UNIT_BYTES;
     const char* unit0 = a.ws_units + ((int64_t)c_begin * units + lh) * U::UNIT_BYTES;
 
-    if (wave == 2) {
+    if (wave == 3) {
         // ------------------------------------------------------------ loader wave
-        auto issue = [&](int i, int stage) {
+        // Two stages' loads are in flight in steady state, more than the 6-bit outstanding-load
+        // counter holds, so a stage is issued in two parts with a wait in between that keeps
+        // the count at 63 or below.
+        constexpr int NP = SM::DMA_PER_STAGE;
+        constexpr int NA = 2 * NP <= 63 ? NP : 63 - NP, NB = NP - NA;   // first part, second part
+        constexpr int NCHAIN = U::CHAIN_BYTES / 1024;
+        static_assert(NP <= 62 && NA > 0 && NB >= 0, "stage size vs outstanding-load counter");
+        auto issue = [&](int i, int stage, int k0, int k1) {
             const int ii = i < n_chunks ? i : n_chunks - 1;   // past the end: harmless re-read
             const char* u = unit0 + ii * unit_stride;
             const char* g_chain = u + lane * 16;
             const char* g_ut = u + U::UT_OFF + sl * U::UT_SLICE_BYTES + lane * 16;
             char* dst = smem + stage * SM::STAGE_BYTES;
 #pragma unroll
-            for (int k = 0; k < U::CHAIN_BYTES / 1024; ++k)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g_chain + k * 1024),
+            for (int k = 0; k < NP; ++k) {
+                if (k < k0 || k >= k1) continue;
+                const char* src = k < NCHAIN ? g_chain + k * 1024 : g_ut + (k - NCHAIN) * 1024;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                                  (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
-#pragma unroll
-            for (int k = 0; k < U::UT_SLICE_BYTES / 1024; ++k)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g_ut + k * 1024),
-                                                 (__attribute__((address_space(3))) void*)(dst + SM::UT_OFF + k * 1024), 16, 0, 0);
+            }
         };
-        issue(0, 0);
-        issue(1, 1);
-        wait_vmcnt<SM::DMA_PER_STAGE>();        // chunk 0 has landed
+        // issue_stage: with at most NP loads outstanding on entry, at most 63 at any time
+        auto issue_stage = [&](int i, int stage) {
+            issue(i, stage, 0, NA);
+            if (NB > 0) {
+                wait_vmcnt<63 - NB>();
+                issue(i, stage, NA, NP);
+            }
+        };
+        issue(0, 0, 0, NP);
+        issue_stage(1, 1);
+        wait_vmcnt<NP>();                       // chunk 0 has landed
+        issue_stage(2, 2);
         __builtin_amdgcn_s_barrier();
-        int stage = 2;
+        int stage = 0;
         for (int i = 0; i < n_chunks; ++i) {
-            issue(i + 2, stage);                // the stage chunk i-1 has just released
+            wait_vmcnt<NP>();                   // chunk i+1 has landed (chunk i+2 may be in flight)
+            __builtin_amdgcn_s_barrier();       // the chain wave is done with chunk i's stage
+            issue_stage(i + 3, stage);
             stage = stage == 2 ? 0 : stage + 1;
-            wait_vmcnt<SM::DMA_PER_STAGE>();    // chunk i+1 has landed
-            __builtin_amdgcn_s_barrier();
         }
         wait_vmcnt<0>();
     } else if (wave == 0) {
@@ -375,15 +406,7 @@ __global__ void __launch_bounds__(192) __attribute__((amdgpu_waves_per_eu(2, 2))
         {
             const int slot = a.req_src_slot[r];
             if (slot >= 0) {
-                const float* src = a.state_src + slot * a.src_slot_stride + head_off;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const f32x4 x = *reinterpret_cast<const f32x4*>(src + 32 * mt + 8 * b + 4 * g);
-                        accS[mt][4 * b] = x[0]; accS[mt][4 * b + 1] = x[1];
-                        accS[mt][4 * b + 2] = x[2]; accS[mt][4 * b + 3] = x[3];
-                    }
+                load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
             } else {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
@@ -392,159 +415,219 @@ __global__ void __launch_bounds__(192) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         }
         __syncthreads();   // chunk 0 is in the ring
+        Frag* const xch0 = reinterpret_cast<Frag*>(smem + SM::XCH_OFF) + lane;
+        // W fragments and U~ accumulators of the chunk about to be processed
+        Frag wf[2 * NKD];
+        f32x16 accU[2];
+        {
+            const Frag* w_ = reinterpret_cast<const Frag*>(smem + U::W_OFF) + lane;
+            const f32x4* ut_ = reinterpret_cast<const f32x4*>(smem + SM::UT_OFF) + lane;
+#pragma unroll
+            for (int k = 0; k < 2 * NKD; ++k) wf[k] = w_[k * 64];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const f32x4 x = ut_[k * 64];
+                accU[k >> 2][4 * (k & 3)] = x[0]; accU[k >> 2][4 * (k & 3) + 1] = x[1];
+                accU[k >> 2][4 * (k & 3) + 2] = x[2]; accU[k >> 2][4 * (k & 3) + 3] = x[3];
+            }
+        }
         int stage = 0;
         for (int i = 0; i < n_chunks; ++i) {
-            const int eslot = a.chunk_emit_slot[c_begin + i];
             const char* st = smem + stage * SM::STAGE_BYTES;
             stage = stage == 2 ? 0 : stage + 1;
-            const Frag* w_img = reinterpret_cast<const Frag*>(st + U::W_OFF) + lane;
+            const char* st_next = smem + stage * SM::STAGE_BYTES;
             const Frag* kt_img = reinterpret_cast<const Frag*>(st + U::KT_OFF) + lane;
             const float* gamS = reinterpret_cast<const float*>(st + U::AUX_OFF);
             const float* decS = gamS + C;
-            const f32x4* ut = reinterpret_cast<const f32x4*>(st + SM::UT_OFF) + lane;
-            Frag* xch = reinterpret_cast<Frag*>(smem + SM::XCH_OFF) + (i & 1) * SM::XCH_FRAGS * 64 + lane;
-            // [A] this chunk's W fragments and U~ accumulators: LDS reads in flight during [B]
-            Frag wf[2 * NKD];
-#pragma unroll
-            for (int k = 0; k < 2 * NKD; ++k) wf[k] = w_img[k * 64];
-            f32x16 accU[2];
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 x = ut[(rt * 4 + b) * 64];
-                    accU[rt][4 * b] = x[0]; accU[rt][4 * b + 1] = x[1];
-                    accU[rt][4 * b + 2] = x[2]; accU[rt][4 * b + 3] = x[3];
-                }
+            Frag* xch = xch0 + (i & 1) * SM::XCH_FRAGS * 64;
             const float gam_last = gamS[C - 1];
-            __builtin_amdgcn_sched_barrier(0);
-            // [B] state -> B fragments, shared with the output wave
-            Frag sf[NKD];
+            const int eslot = reinterpret_cast<const int32_t*>(gamS + 2 * C)[AUX_EMIT_SLOT];
+
+            // Everything below is laid out as short groups, one matrix instruction plus what is
+            // meant to execute in its shadow, separated by scheduling fences.
+            Frag sf[NKD], kf[MT * NKC], ud[NKC];
+            f32x4 dc[8];
+            sf[0] = EL::from_acc(accS[0], 0);
+            pin(sf[0]);
+            GDN_FENCE();
+            // ---- U token tile 0: state -> B fragments just ahead of their use, published to the
+            //      output wave; first half of the state's decay
 #pragma unroll
-            for (int s = 0; s < NKD; ++s) {
-                sf[s] = EL::from_acc(accS[s / SPT], s % SPT);
-                xch[s * 64] = sf[s];
+            for (int k = 0; k < NKD; ++k) {
+                accU[0] = EL::mma(wf[k], sf[k], accU[0]);
+                if (k + 1 < NKD) {
+                    sf[k + 1] = EL::from_acc(accS[(k + 1) / SPT], (k + 1) % SPT);
+                    pin(sf[k + 1]);
+                }
+                xch[k * 64] = sf[k];
+#pragma unroll
+                for (int e = 0; e < RPS / 2; ++e) {
+                    float x = accS[k / SPT][(k % SPT) * RPS + e] * gam_last;
+                    pin(x);
+                    accS[k / SPT][(k % SPT) * RPS + e] = x;
+                }
+                GDN_FENCE();
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // [C] U = U~ + W S^T.  Independent accumulators alternate, so consecutive MFMAs never
-            //     wait on each other; the decay of the old state (gam_C S) rides in their shadow.
+            // ---- U token tile 1: rest of the decay; K^T fragments and decay factors are read;
+            //      tile 0 of U is converted as soon as its last product has drained
 #pragma unroll
-            for (int s = 0; s < NKD; ++s)
+            for (int k = 0; k < NKD; ++k) {
+                accU[1] = EL::mma(wf[NKD + k], sf[k], accU[1]);
 #pragma unroll
-                for (int rt = 0; rt < 2; ++rt) accU[rt] = EL::mma(wf[rt * NKD + s], sf[s], accU[rt]);
+                for (int e = RPS / 2; e < RPS; ++e) {
+                    float x = accS[k / SPT][(k % SPT) * RPS + e] * gam_last;
+                    pin(x);
+                    accS[k / SPT][(k % SPT) * RPS + e] = x;
+                }
+                if (k == 0) {
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int k = 0; k < 16; ++k) {
-                    accS[mt][k] *= gam_last;
-                    asm volatile("" : "+v"(accS[mt][k]));   // keep the multiply here, not where its result is used
+                    for (int j = 0; j < 8; ++j) dc[j] = *reinterpret_cast<const f32x4*>(decS + 8 * j + 4 * g);
                 }
 #pragma unroll
-            for (int k = 0; k < 2 * NKD; ++k) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                    // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, (16 * MT) / (2 * NKD), 0); // a share of the multiplies
+                for (int j = 0; j < (MT * NKC) / NKD; ++j) kf[k * ((MT * NKC) / NKD) + j] = kt_img[(k * ((MT * NKC) / NKD) + j) * 64];
+                // conversion piece p of tile 0 at step 2 + p * stride (late enough for the data)
+                constexpr int stride = (NKD - 2) / SPT > 0 ? (NKD - 2) / SPT : 1;
+                if (k >= 2 && (k - 2) % stride == 0 && (k - 2) / stride < SPT) {
+                    const int p = (k - 2) / stride;
+                    f32x16 d = accU[0];
+#pragma unroll
+                    for (int e = 0; e < RPS; ++e) d[p * RPS + e] *= dc[(p * RPS + e) >> 2][(p * RPS + e) & 3];
+                    ud[p] = EL::from_acc(d, p);
+                    pin(ud[p]);
+                    xch[(NKD + p) * 64] = EL::from_acc(accU[0], p);
+                }
+                GDN_FENCE();
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // [D] K^T fragments and decay factors: in flight while U is converted
-            Frag kf[MT * NKC];
+            // (steps of tile 0's conversion that did not fit into the loop above)
+            {
+                constexpr int stride = (NKD - 2) / SPT > 0 ? (NKD - 2) / SPT : 1;
+                constexpr int done = (NKD - 2 + stride - 1) / stride < SPT ? ((NKD - 2 + stride - 1) / stride > 0 ? (NKD - 2 + stride - 1) / stride : 0) : SPT;
 #pragma unroll
-            for (int k = 0; k < MT * NKC; ++k) kf[k] = kt_img[k * 64];
-            f32x4 dc[8];
+                for (int p = done; p < SPT; ++p) {
+                    f32x16 d = accU[0];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) dc[k] = *reinterpret_cast<const f32x4*>(decS + 8 * k + 4 * g);
-            __builtin_amdgcn_sched_barrier(0);
-            // [E] U decayed to the chunk end, as B operand of the state update
-            Frag ud[NKC];
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-                f32x16 d = accU[rt];
-#pragma unroll
-                for (int b = 0; b < 4; ++b)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) d[4 * b + e] *= dc[rt * 4 + b][e];
-#pragma unroll
-                for (int s = 0; s < SPT; ++s) ud[rt * SPT + s] = EL::from_acc(d, s);
+                    for (int e = 0; e < RPS; ++e) d[p * RPS + e] *= dc[(p * RPS + e) >> 2][(p * RPS + e) & 3];
+                    ud[p] = EL::from_acc(d, p);
+                    pin(ud[p]);
+                    xch[(NKD + p) * 64] = EL::from_acc(accU[0], p);
+                }
+                GDN_FENCE();
             }
-            __builtin_amdgcn_sched_barrier(0);
-            // [G] state update S^T += K^T-contraction, with [H] (plain U for the output wave)
-            //     converted and written in the MFMAs' shadow
+            // ---- state update over the tokens of tile 0 (steps 0..SPT-1), with tile 1 of U
+            //      converted in its shadow
 #pragma unroll
-            for (int s = 0; s < NKC; ++s)
+            for (int s = 0; s < SPT; ++s) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) accS[mt] = EL::mma(kf[mt * NKC + s], ud[s], accS[mt]);
+                for (int mt = 0; mt < MT; ++mt) {
+                    accS[mt] = EL::mma(kf[mt * NKC + s], ud[s], accS[mt]);
+                    if (mt == 0) {
+                        f32x16 d = accU[1];
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int s = 0; s < SPT; ++s) xch[(NKD + rt * SPT + s) * 64] = EL::from_acc(accU[rt], s);
-            __builtin_amdgcn_sched_barrier(0);
-            if (eslot >= 0) {
-                float* dst = a.state_dst + eslot * a.dst_slot_stride + head_off;
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const f32x4 x = {accS[mt][4 * b], accS[mt][4 * b + 1], accS[mt][4 * b + 2], accS[mt][4 * b + 3]};
-                        *reinterpret_cast<f32x4*>(dst + 32 * mt + 8 * b + 4 * g) = x;
+                        for (int e = 0; e < RPS; ++e) d[s * RPS + e] *= dc[4 + ((s * RPS + e) >> 2)][(s * RPS + e) & 3];
+                        ud[SPT + s] = EL::from_acc(d, s);
+                        pin(ud[SPT + s]);
+                        xch[(NKD + SPT + s) * 64] = EL::from_acc(accU[1], s);
                     }
+                    GDN_FENCE();
+                }
             }
-            __syncthreads();   // this chunk's fragments are in LDS; its ring stage is free
+            __syncthreads();   // this chunk's fragments are published, its ring stage is released,
+                               // the next chunk's stage has landed
+            // ---- state update over the tokens of tile 1, the next chunk's W fragments and U~
+            //      being read in its shadow
+            {
+                const Frag* w_ = reinterpret_cast<const Frag*>(st_next + U::W_OFF) + lane;
+                const f32x4* ut_ = reinterpret_cast<const f32x4*>(st_next + SM::UT_OFF) + lane;
+                constexpr int NM = SPT * MT;                      // matrix instructions left
+                constexpr int WPM = (2 * NKD + NM - 1) / NM;      // W fragments read per instruction
+                int m = 0;
+#pragma unroll
+                for (int s = SPT; s < 2 * SPT; ++s)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt, ++m) {
+                        accS[mt] = EL::mma(kf[mt * NKC + s], ud[s], accS[mt]);
+#pragma unroll
+                        for (int j = 0; j < WPM; ++j)
+                            if (m * WPM + j < 2 * NKD) wf[m * WPM + j] = w_[(m * WPM + j) * 64];
+                        if (m < 8) {
+                            const f32x4 x = ut_[m * 64];
+                            accU[m >> 2][4 * (m & 3)] = x[0]; accU[m >> 2][4 * (m & 3) + 1] = x[1];
+                            accU[m >> 2][4 * (m & 3) + 2] = x[2]; accU[m >> 2][4 * (m & 3) + 3] = x[3];
+                        }
+                        GDN_FENCE();
+                    }
+                // (U~ pieces beyond the number of matrix instructions)
+#pragma unroll
+                for (int k = NM; k < 8; ++k) {
+                    const f32x4 x = ut_[k * 64];
+                    accU[k >> 2][4 * (k & 3)] = x[0]; accU[k >> 2][4 * (k & 3) + 1] = x[1];
+                    accU[k >> 2][4 * (k & 3) + 2] = x[2]; accU[k >> 2][4 * (k & 3) + 3] = x[3];
+                }
+            }
+            // checkpoint emission: exact state after the last token of this chunk
+            if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
         }
     } else {
-        // ------------------------------------------------------------ output wave
-        // Left operands of chunk i+1 are requested before chunk i's results are stored, so that
-        // their memory latency is covered by a chunk of work.
-        const char* unit = unit0;
-        Frag qf[2 * NKD], pf[2 * NKC];
-        float gm[2];
-#define GDN_LOAD_QP(u_)                                                                       \
-    {                                                                                         \
-        const Frag* q_ = reinterpret_cast<const Frag*>((u_) + U::Q_OFF) + lane;               \
-        const Frag* p_ = reinterpret_cast<const Frag*>((u_) + U::P_OFF) + lane;               \
-        const float* g_ = reinterpret_cast<const float*>((u_) + U::AUX_OFF) + lr;             \
-        _Pragma("unroll") for (int i_ = 0; i_ < 2 * NKD; ++i_) qf[i_] = q_[i_ * 64];          \
-        _Pragma("unroll") for (int i_ = 0; i_ < SPT; ++i_) pf[i_] = p_[i_ * 64];              \
-        _Pragma("unroll") for (int i_ = 0; i_ < NKC; ++i_) pf[NKC + i_] = p_[(NKC + i_) * 64]; \
-        gm[0] = g_[0]; gm[1] = g_[32];                                                        \
-    }
-        GDN_LOAD_QP(unit)
-        __syncthreads();   // matches the barrier before the first chunk
-        for (int i = 0; i < n_chunks; ++i) {
-            const int tok0 = a.chunk_tok0[c_begin + i];
-            const int n = a.chunk_len[c_begin + i];
-            const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
-            const char* nxt = (i + 1 < n_chunks) ? unit + unit_stride : unit;
-
-            __syncthreads();   // the chain wave has left this chunk's state and U fragments
-            const Frag* xch = reinterpret_cast<const Frag*>(smem + SM::XCH_OFF) + (i & 1) * SM::XCH_FRAGS * 64 + lane;
+        // ------------------------------------------------------------ output waves
+        // Wave 1 owns token tile 0, wave 2 token tile 1.  Three register sets of Q/P fragments
+        // rotate: the set a chunk has just used is refilled with the chunk three ahead, so a
+        // load has three chunk times to arrive.
+        const int tt = wave - 1;
+        const int np = (tt + 1) * SPT;           // P is lower triangular: tile 0 only sees key tile 0
+        Frag qf0[NKD], qf1[NKD], qf2[NKD], pf0[NKC], pf1[NKC], pf2[NKC];
+        float gm0, gm1, gm2;
+        int t00, t01, t02, n0, n1, n2;
+        auto load_set = [&](int j, Frag (&qf)[NKD], Frag (&pf)[NKC], float& gm, int& tok0, int& nn) {
+            const int jj = j < n_chunks ? j : n_chunks - 1;   // past the end: harmless re-read
+            const char* u = unit0 + jj * unit_stride;
+            const Frag* q_ = reinterpret_cast<const Frag*>(u + U::Q_OFF) + tt * NKD * 64 + lane;
+            const Frag* p_ = reinterpret_cast<const Frag*>(u + U::P_OFF) + tt * NKC * 64 + lane;
+            const float* g_ = reinterpret_cast<const float*>(u + U::AUX_OFF);
+            const int32_t* m_ = reinterpret_cast<const int32_t*>(g_ + 2 * C);
+#pragma unroll
+            for (int k = 0; k < NKD; ++k) qf[k] = q_[k * 64];
+#pragma unroll
+            for (int k = 0; k < NKC; ++k)
+                if (k < np) pf[k] = p_[k * 64];
+            gm = g_[32 * tt + lr];
+            tok0 = m_[AUX_TOK0];
+            nn = m_[AUX_LEN];
+        };
+        auto step = [&](int j, Frag (&qf)[NKD], Frag (&pf)[NKC], float& gm, int& tok0, int& nn) {
+            __syncthreads();   // the chain wave has left chunk j's state and U fragments
+            const Frag* xch = reinterpret_cast<const Frag*>(smem + SM::XCH_OFF) + (j & 1) * SM::XCH_FRAGS * 64 + lane;
             Frag sf[NKD], uf[NKC];
 #pragma unroll
-            for (int s = 0; s < NKD; ++s) sf[s] = xch[s * 64];
+            for (int k = 0; k < NKD; ++k) sf[k] = xch[k * 64];
 #pragma unroll
-            for (int s = 0; s < NKC; ++s) uf[s] = xch[(NKD + s) * 64];
-
-            // O^T tiles of the two token tiles, their MFMA chains interleaved
-            f32x16 ot[2] = {{0}, {0}};
+            for (int k = 0; k < NKC; ++k)
+                if (k < np) uf[k] = xch[(NKD + k) * 64];
+            f32x16 acc = {0};
 #pragma unroll
-            for (int s = 0; s < NKD; ++s)
+            for (int k = 0; k < NKD; ++k) acc = EL::mma(sf[k], qf[k], acc);
+            const float sc = gm * a.scale;
 #pragma unroll
-                for (int tt = 0; tt < 2; ++tt) ot[tt] = EL::mma(sf[s], qf[tt * NKD + s], ot[tt]);
+            for (int k = 0; k < 16; ++k) acc[k] *= sc;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                const float sc = gm[tt] * a.scale;
-#pragma unroll
-                for (int k = 0; k < 16; ++k) ot[tt][k] *= sc;
-            }
-#pragma unroll
-            for (int s = 0; s < NKC; ++s)
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
-                    if (s < (tt + 1) * SPT) ot[tt] = EL::mma(uf[s], pf[tt * NKC + s], ot[tt]);
-            GDN_LOAD_QP(nxt)   // next chunk's operands into the registers just freed
-            unit = nxt;
-            store_o_t<DV>(a, row0, hv, sl, lr, g, n, ot);
+            for (int k = 0; k < NKC; ++k)
+                if (k < np) acc = EL::mma(uf[k], pf[k], acc);
+            const int n = nn;
+            const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
+            load_set(j + 3, qf, pf, gm, tok0, nn);   // refill the set just used
+            store_o_tile<DV>(a, row0, hv, sl, lr, g, n, tt, acc);
+        };
+        load_set(0, qf0, pf0, gm0, t00, n0);
+        load_set(1, qf1, pf1, gm1, t01, n1);
+        load_set(2, qf2, pf2, gm2, t02, n2);
+        __syncthreads();   // matches the barrier before the first chunk
+        for (int i = 0; i < n_chunks; i += 3) {
+            step(i, qf0, pf0, gm0, t00, n0);
+            if (i + 1 < n_chunks) step(i + 1, qf1, pf1, gm1, t01, n1);
+            if (i + 2 < n_chunks) step(i + 2, qf2, pf2, gm2, t02, n2);
         }
-#undef GDN_LOAD_QP
     }
 }
+
+#undef GDN_FENCE
 
 }  // namespace gdn

@@ -211,16 +211,16 @@ hipError_t launch_recur_nw(const RecurArgs& ra, int64_t n_chains, hipStream_t st
 }
 
 template <typename E, int DK, int DV>
-hipError_t launch_recur_trio(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
-    constexpr int smem = TrioSmem<E, DK, DV>::BYTES;
+hipError_t launch_recur_quad(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
+    constexpr int smem = QuadSmem<E, DK, DV>::BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_trio_kernel<E, DK, DV>),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_quad_kernel<E, DK, DV>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gdn_recur_trio_kernel<E, DK, DV>), dim3((unsigned)(n_chains * (DV / 32))), dim3(192), smem, stream, ra);
+    hipLaunchKernelGGL((gdn_recur_quad_kernel<E, DK, DV>), dim3((unsigned)(n_chains * (DV / 32))), dim3(256), smem, stream, ra);
     return hipGetLastError();
 }
 
@@ -246,7 +246,7 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
     // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain share
     // one workgroup and one LDS copy of the chunk operands; with fewer, two slices per workgroup;
     // with too few to occupy every compute unit, the latency variant (chain, output and
-    // loader waves per slice).
+    // two loader waves per slice).
     const int64_t n_chains = (int64_t)n_req * units;
     constexpr int NS = DV / 32;
     int nw = NS;
@@ -254,8 +254,15 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && NS == 4)) nw = o;
     }
-    if (nw == 1) e = launch_recur_trio<E, DK, DV>(ra, n_chains, stream);
-    else if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
+    if constexpr (sizeof(typename Elem<E>::Frag) == 16) {
+        if (nw == 1) {
+            e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
+            prof.mark(2);
+            return hip_err(e);
+        }
+    }
+    // (fp32 operands: the latency variant's register budget is sized for 16-byte fragments)
+    if (nw <= 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
     else e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
     prof.mark(2);
     return hip_err(e);
@@ -435,6 +442,7 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     pa.q = q; pa.k = k; pa.v = v; pa.beta = beta; pa.gate = gate;
     pa.chunk_tok0 = d;
     pa.chunk_len = d + n_chunks;
+    pa.chunk_emit_slot = d + 2 * (int64_t)n_chunks;
     pa.ws_units = ws_units;
     pa.L = s.L; pa.H_qk = s.H_qk; pa.H_v = s.H_v;
     pa.T_alloc = s.T_alloc;
@@ -442,9 +450,6 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
 
     RecurArgs ra;
     ra.o = o; ra.ws_units = ws_units;
-    ra.chunk_tok0 = d;
-    ra.chunk_len = d + n_chunks;
-    ra.chunk_emit_slot = d + 2 * (int64_t)n_chunks;
     ra.req_chunk_cu = d + 3 * (int64_t)n_chunks;
     ra.req_src_slot = ra.req_chunk_cu + (n_req + 1);
     ra.req_order = ra.req_src_slot + n_req;
@@ -454,7 +459,6 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     ra.T_alloc = s.T_alloc;
     ra.scale = s.scale;
     ra.o_bf16 = s.o_dtype == GDN_BF16;
-    ra.debug_same_unit = std::getenv("GDN_DEBUG_SAME_UNIT") != nullptr;
 
 
     if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
