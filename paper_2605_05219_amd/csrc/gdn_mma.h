@@ -67,6 +67,9 @@ template <> struct Elem<half_t> {
         }
     }
     static __device__ __forceinline__ float load1(const In* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+    // hardware exp2/log2 based: relative error ~1e-6 |x|, far inside the fp16 operand rounding
+    static __device__ __forceinline__ float exp_(float x) { return __expf(x); }
+    static __device__ __forceinline__ float log_(float x) { return __logf(x); }
 };
 
 template <> struct Elem<float> {
@@ -94,6 +97,8 @@ template <> struct Elem<float> {
         out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
     }
     static __device__ __forceinline__ float load1(const In* p) { return *p; }
+    static __device__ __forceinline__ float exp_(float x) { return expf(x); }
+    static __device__ __forceinline__ float log_(float x) { return logf(x); }
 };
 
 // Words that follow gam[64], dec[64] in a unit's aux block (int32).

@@ -59,22 +59,22 @@ struct PrepSmem {
     typedef UnitLayout<E, DK, DV> U;
     static constexpr int C = 64;
     static constexpr int PAD = Elem<E>::PAD;
-    static constexpr int LF_LD = C + 1;
+    static constexpr int LF_LD = C + 4;   // rows 16-byte aligned
     static constexpr int T_LD = C + PAD;  // Tb / Tbg rows
     static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
-    // region A: K [C][DK+PAD]
+    static constexpr int KT_LD = C + PAD;
+    static constexpr int VT_LD = C + PAD;
+    static constexpr int cmax(int x, int y) { return x > y ? x : y; }
+    // region A: K [C][DK+PAD]; once the first products are done, V^T [DV][C+PAD]
     static constexpr int A_OFF = 0;
-    static constexpr int A_BYTES = a16(C * (DK + PAD) * (int)sizeof(E));
+    static constexpr int A_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), a16(DV * VT_LD * (int)sizeof(E)));
     // region B: Q [C][DK+PAD], later Tb and Tbg
     static constexpr int B_OFF = A_OFF + A_BYTES;
     static constexpr int TB_BYTES = a16(C * T_LD * (int)sizeof(E));
-    static constexpr int B_BYTES = (A_BYTES > 2 * TB_BYTES) ? A_BYTES : 2 * TB_BYTES;
+    static constexpr int B_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), 2 * TB_BYTES);
     static constexpr int KT_OFF = B_OFF + B_BYTES;
-    static constexpr int KT_LD = C + PAD;
     static constexpr int KT_BYTES = a16(DK * KT_LD * (int)sizeof(E));
-    static constexpr int VT_OFF = KT_OFF + KT_BYTES;
-    static constexpr int VT_BYTES = a16(DV * (C + PAD) * (int)sizeof(E));
-    static constexpr int LF_OFF = VT_OFF + VT_BYTES;
+    static constexpr int LF_OFF = KT_OFF + KT_BYTES;
     static constexpr int LF_BYTES = a16(C * LF_LD * (int)sizeof(float));
     static constexpr int SM_OFF = LF_OFF + LF_BYTES;  // g[C], b[C], gam[C], dec[C]
     static constexpr int BYTES = SM_OFF + 4 * C * (int)sizeof(float);
@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     constexpr int PAD = EL::PAD;
     constexpr int K_LD = DK + PAD;
     constexpr int KT_LD = SM::KT_LD;
-    constexpr int VT_LD = C + PAD;
+    constexpr int VT_LD = SM::VT_LD;
     constexpr int LF_LD = SM::LF_LD;
     constexpr int T_LD = SM::T_LD;
 
@@ -99,7 +99,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     E* Ks = reinterpret_cast<E*>(smem + SM::A_OFF);
     E* Qs = reinterpret_cast<E*>(smem + SM::B_OFF);
     E* KTs = reinterpret_cast<E*>(smem + SM::KT_OFF);
-    E* VTs = reinterpret_cast<E*>(smem + SM::VT_OFF);
+    E* VTs = reinterpret_cast<E*>(smem + SM::A_OFF);       // after the first products
     float* Lf = reinterpret_cast<float*>(smem + SM::LF_OFF);
     float* gS = reinterpret_cast<float*>(smem + SM::SM_OFF);
     float* bS = gS + C;
@@ -134,7 +134,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         float la = 0.f, b = 0.f;
         if (lane < n) {
             const int64_t gi = (row0 + lane) * a.H_v + hv;
-            la = fmaxf(logf(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
+            la = fmaxf(EL::log_(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
             b = EL::load1(reinterpret_cast<const In*>(a.beta) + gi);
         }
         float s = la;
@@ -146,48 +146,57 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         const float g_last = __shfl(s, 63, 64);
         gS[lane] = s;
         bS[lane] = b;
-        gamS[lane] = expf(s);
-        decS[lane] = expf(g_last - s);
+        gamS[lane] = EL::exp_(s);
+        decS[lane] = EL::exp_(g_last - s);
     }
     // ---- zero the fp32 triangular matrix (its untouched upper blocks must read as 0)
     for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
 
-    // ---- stage K, Q (row-major) and K^T, V^T (token-contiguous), converted to E
+    // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E.  A thread owns
+    //      4-token x 8-column blocks: every global load is issued before the first LDS store,
+    //      and the transposed copy goes out as 4-token runs.  V is fetched now and kept in
+    //      registers; its transposed tile takes K's place once K is dead.
+    constexpr int KB = (C / 4) * (DK / 8), VB = (C / 4) * (DV / 8);   // blocks of K (and Q), of V
+    static_assert(KB <= 256 && VB <= 256, "one block per thread at most");
+    float vv[4][8];
     {
         const In* qg = reinterpret_cast<const In*>(a.q);
         const In* kg = reinterpret_cast<const In*>(a.k);
-        constexpr int VPR = DK / 8;  // 8-element vectors per row
-        for (int u = tid; u < C * VPR; u += 256) {
-            const int i = u / VPR, d0 = (u % VPR) * 8;
-            float kv[8], qv[8];
-            if (i < n) {
-                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
-                EL::load8(kg + off, kv);
-                EL::load8(qg + off, qv);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { kv[e] = 0.f; qv[e] = 0.f; }
-            }
-            EL::store4(Ks + i * K_LD + d0, kv[0], kv[1], kv[2], kv[3]);
-            EL::store4(Ks + i * K_LD + d0 + 4, kv[4], kv[5], kv[6], kv[7]);
-            EL::store4(Qs + i * K_LD + d0, qv[0], qv[1], qv[2], qv[3]);
-            EL::store4(Qs + i * K_LD + d0 + 4, qv[4], qv[5], qv[6], qv[7]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) KTs[(d0 + e) * KT_LD + i] = (E)kv[e];
-        }
         const In* vg = reinterpret_cast<const In*>(a.v);
-        constexpr int VPRV = DV / 8;
-        for (int u = tid; u < C * VPRV; u += 256) {
-            const int i = u / VPRV, d0 = (u % VPRV) * 8;
-            float vv[8];
-            if (i < n) {
-                EL::load8(vg + ((row0 + i) * a.H_v + hv) * DV + d0, vv);
+        float kv[4][8], qv[4][8];
+        const int tg = tid / (DK / 8), d0 = (tid % (DK / 8)) * 8;
+        const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 4 * tg + r;
+            if (tid < KB && i < n) {
+                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
+                EL::load8(kg + off, kv[r]);
+                EL::load8(qg + off, qv[r]);
             } else {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vv[e] = 0.f;
+                for (int e = 0; e < 8; ++e) { kv[r][e] = 0.f; qv[r][e] = 0.f; }
+            }
+            const int iv = 4 * tgv + r;
+            if (tid < VB && iv < n) {
+                EL::load8(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v, vv[r]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vv[r][e] = 0.f;
+            }
+        }
+        if (tid < KB) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = 4 * tg + r;
+                EL::store4(Ks + i * K_LD + d0, kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
+                EL::store4(Ks + i * K_LD + d0 + 4, kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
+                EL::store4(Qs + i * K_LD + d0, qv[r][0], qv[r][1], qv[r][2], qv[r][3]);
+                EL::store4(Qs + i * K_LD + d0 + 4, qv[r][4], qv[r][5], qv[r][6], qv[r][7]);
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) VTs[(d0 + e) * VT_LD + i] = (E)vv[e];
+            for (int e = 0; e < 8; ++e)
+                EL::store4(KTs + (d0 + e) * KT_LD + 4 * tg, kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
         }
     }
     __syncthreads();
@@ -212,7 +221,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
                 const int i = 32 * kk_mi + acc_row(idx, g);
-                const float val = bS[i] * expf(fminf(gS[i] - gj, 0.f)) * acc[idx];
+                const float val = bS[i] * EL::exp_(fminf(gS[i] - gj, 0.f)) * acc[idx];
                 Lf[i * LF_LD + j] = (j < i) ? val : 0.f;
             }
         }
@@ -234,7 +243,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 #pragma unroll
             for (int idx = 0; idx < 16; ++idx) {
                 const int j = 32 * p_mj + acc_row(idx, g);
-                const float val = a.scale * expf(fminf(gi - gS[j], 0.f)) * acc[idx];
+                const float val = a.scale * EL::exp_(fminf(gi - gS[j], 0.f)) * acc[idx];
                 acc[idx] = (j <= i) ? val : 0.f;
             }
 #pragma unroll
@@ -244,16 +253,31 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     }
     __syncthreads();  // L is complete; K, Q in LDS are dead
 
+    // ---- V^T into K's place (read by the last product, several barriers from here)
+    if (tid < VB) {
+        const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            EL::store4(VTs + (d0v + e) * VT_LD + 4 * tgv, vv[0][e], vv[1][e], vv[2][e], vv[3][e]);
+    }
+
     // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks by forward
     //      substitution, one per wave, column (lane & 15) of the inverse in registers.
     {
         const int base = 16 * wave, cc = lane & 15;
         float x[16];
+        // the block's rows, fetched up front as 16-byte pieces (same address in every lane)
+        f32x4 lrow[16][4];
+#pragma unroll
+        for (int r = 1; r < 16; ++r)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                if (4 * q4 < r) lrow[r][q4] = *reinterpret_cast<const f32x4*>(Lf + (base + r) * LF_LD + base + 4 * q4);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             float s = (r == cc) ? 1.f : 0.f;
 #pragma unroll
-            for (int j = 0; j < r; ++j) s -= Lf[(base + r) * LF_LD + base + j] * x[j];
+            for (int j = 0; j < r; ++j) s -= lrow[r][j >> 2][j & 3] * x[j];
             x[r] = s;
         }
         if (lane < 16) {
