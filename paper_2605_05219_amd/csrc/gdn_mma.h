@@ -45,6 +45,18 @@ template <> struct Elem<half_t> {
     static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
+    // f[slot] * vec[index that slot carries]  (vec indexed like a row handed to load())
+    static __device__ __forceinline__ Frag scale(Frag f, const float* vec, int s, int g) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(vec + 16 * s + 4 * g);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(vec + 16 * s + 8 + 4 * g);
+        Frag r;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            r[e] = (half_t)((float)f[e] * lo[e]);
+            r[4 + e] = (half_t)((float)f[4 + e] * hi[e]);
+        }
+        return r;
+    }
     static __device__ __forceinline__ Frag from_acc(const f32x16& acc, int sub) {
         Frag f;
 #pragma unroll
@@ -86,6 +98,10 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
     }
+    static __device__ __forceinline__ Frag scale(Frag f, const float* vec, int s, int g) {
+        const int w = s & 15;
+        return f * vec[32 * (s >> 4) + 8 * (w >> 2) + 4 * g + (w & 3)];
+    }
     static __device__ __forceinline__ Frag from_acc(const f32x16& acc, int sub) { return acc[sub]; }
     static __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
         p[0] = a; p[1] = b; p[2] = c; p[3] = d;
@@ -120,7 +136,7 @@ template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int NKD = DK / Elem<E>::KSTEP;                       // steps over d_k
     static constexpr int NKC = C / Elem<E>::KSTEP;                        // steps over the chunk's tokens
     static constexpr int W_BYTES = 2 * NKD * FRAG_BYTES;                  // W   [C][DK]: 2 row tiles x NKD
-    static constexpr int KT_BYTES = (DK / 32) * NKC * FRAG_BYTES;         // K^T [DK][C]: DK/32 row tiles x NKC
+    static constexpr int KT_BYTES = (DK / 32) * NKC * FRAG_BYTES;         // K^T diag(dec) [DK][C]: DK/32 row tiles x NKC
     static constexpr int AUX_BYTES = 1024;                                // gam[C], dec[C] floats, bookkeeping words, padded
     static constexpr int Q_BYTES = 2 * NKD * FRAG_BYTES;                  // Q   [C][DK]: 2 row tiles x NKD
     static constexpr int P_BYTES = 2 * NKC * FRAG_BYTES;                  // P   [C][C]:  2 row tiles x NKC

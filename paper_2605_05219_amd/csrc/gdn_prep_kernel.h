@@ -9,7 +9,8 @@
 //     W  = -T diag(b gam) K          [C][d_k]   (so that U = U~ + W S_0^T)
 //     U~ =  T diag(b) V              [C][d_v]   fp32, in the recurrence kernel's accumulator order
 //     P_ij = scale * exp(g_i-g_j) (q_i.k_j), j <= i   [C][C]
-//     Q, K^T (converted), gam_i, dec_i = exp(g_C - g_i), and the chunk's bookkeeping words
+//     Q, K^T diag(dec) with dec_i = exp(g_C - g_i) (the decay to the chunk end rides on K, so
+//     the recurrence uses one conversion of U for both of its uses), gam_i, bookkeeping words
 // W, Q, K^T and P leave in fragment-major order (see UnitLayout).  A product's accumulator tile
 // already holds, lane for lane, the fragments of its transpose, so W and P go from the
 // accumulators to global memory with coalesced stores; Q and K^T fragments are the operands
@@ -354,7 +355,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
         for (int s = 0; s < NKC; ++s)
             if (s < ns) {
                 const Frag kf = EL::load(ar, s, g);
-                if (nt == 1) kt_img[(mt * NKC + s) * 64 + lane] = kf;
+                if (nt == 1) kt_img[(mt * NKC + s) * 64 + lane] = EL::scale(kf, decS, s, g);   // decayed to the chunk end
                 acc = EL::mma(kf, EL::load(br, s, g), acc);
             }
 #pragma unroll

@@ -8,7 +8,7 @@
 // registers):
 //     U   = U~ + W S^T                        [C][32]
 //     O^T = (S Q^T) diag(gam) + U^T P^T       [32][C]   (scale already folded into P)
-//     S^T <- gam_C S^T + K^T-contraction:     S^T[d_k][d_v] += sum_j K[j][d_k] dec_j U[j][d_v]
+//     S^T <- gam_C S^T + K^T-contraction:     S^T[d_k][d_v] += sum_j (dec_j K[j][d_k]) U[j][d_v]
 // and, when the chunk ends at a checkpoint position, S is stored to its pool slot.
 #pragma once
 #include "gdn_mma.h"
@@ -193,7 +193,6 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         const Frag* kt_img = reinterpret_cast<const Frag*>(img + U::KT_OFF) + lane;
         const Frag* p_img = reinterpret_cast<const Frag*>(img + U::P_OFF) + lane;
         const float* gamS = reinterpret_cast<const float*>(img + U::AUX_OFF);
-        const float* decS = gamS + C;
         const int32_t* meta = reinterpret_cast<const int32_t*>(gamS + 2 * C);
         const int eslot = meta[AUX_EMIT_SLOT];
         const int n = meta[AUX_LEN];
@@ -224,32 +223,21 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
 #pragma unroll
             for (int s = 0; s < NKD; ++s) accU[rt] = EL::mma(w_img[(rt * NKD + s) * 64], sf[s], accU[rt]);
 
-        // U as B operand: plain for O += P U, decayed to the chunk end for the state update
-        Frag uf[2 * SPT], ud[2 * SPT];
+        // U as the register operand of both O += P U and the state update
+        Frag uf[2 * SPT];
 #pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-            f32x16 d = accU[rt];
+        for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 32 * rt + 8 * b + 4 * g);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) d[4 * b + e] *= dc[e];
-            }
-#pragma unroll
-            for (int s = 0; s < SPT; ++s) {
-                uf[rt * SPT + s] = EL::from_acc(accU[rt], s);
-                ud[rt * SPT + s] = EL::from_acc(d, s);
-            }
-        }
+            for (int s = 0; s < SPT; ++s) uf[rt * SPT + s] = EL::from_acc(accU[rt], s);
 
-        // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.])
+        // state update: S^T = gam_C S^T + sum_j (dec_j K^T[.][j]) U[j][.]
         const float gam_last = gamS[C - 1];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) accS[mt][i] *= gam_last;
 #pragma unroll
-            for (int s = 0; s < NKC; ++s) accS[mt] = EL::mma(kt_img[(mt * NKC + s) * 64], ud[s], accS[mt]);
+            for (int s = 0; s < NKC; ++s) accS[mt] = EL::mma(kt_img[(mt * NKC + s) * 64], uf[s], accS[mt]);
         }
 
         // checkpoint emission: exact state after the last token of this chunk
@@ -438,15 +426,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const char* st_next = smem + stage * SM::STAGE_BYTES;
             const Frag* kt_img = reinterpret_cast<const Frag*>(st + U::KT_OFF) + lane;
             const float* gamS = reinterpret_cast<const float*>(st + U::AUX_OFF);
-            const float* decS = gamS + C;
             Frag* xch = xch0 + (i & 1) * SM::XCH_FRAGS * 64;
             const float gam_last = gamS[C - 1];
             const int eslot = reinterpret_cast<const int32_t*>(gamS + 2 * C)[AUX_EMIT_SLOT];
 
             // Everything below is laid out as short groups, one matrix instruction plus what is
             // meant to execute in its shadow, separated by scheduling fences.
-            Frag sf[NKD], kf[MT * NKC], ud[NKC];
-            f32x4 dc[8];
+            Frag sf[NKD], kf[MT * NKC], uf[NKC];
             sf[0] = EL::from_acc(accS[0], 0);
             pin(sf[0]);
             GDN_FENCE();
@@ -468,7 +454,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 GDN_FENCE();
             }
-            // ---- U token tile 1: rest of the decay; K^T fragments and decay factors are read;
+            // ---- U token tile 1: rest of the decay; K^T fragments are read;
             //      tile 0 of U is converted as soon as its last product has drained
 #pragma unroll
             for (int k = 0; k < NKD; ++k) {
@@ -479,22 +465,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     pin(x);
                     accS[k / SPT][(k % SPT) * RPS + e] = x;
                 }
-                if (k == 0) {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) dc[j] = *reinterpret_cast<const f32x4*>(decS + 8 * j + 4 * g);
-                }
 #pragma unroll
                 for (int j = 0; j < (MT * NKC) / NKD; ++j) kf[k * ((MT * NKC) / NKD) + j] = kt_img[(k * ((MT * NKC) / NKD) + j) * 64];
                 // conversion piece p of tile 0 at step 2 + p * stride (late enough for the data)
                 constexpr int stride = (NKD - 2) / SPT > 0 ? (NKD - 2) / SPT : 1;
                 if (k >= 2 && (k - 2) % stride == 0 && (k - 2) / stride < SPT) {
                     const int p = (k - 2) / stride;
-                    f32x16 d = accU[0];
-#pragma unroll
-                    for (int e = 0; e < RPS; ++e) d[p * RPS + e] *= dc[(p * RPS + e) >> 2][(p * RPS + e) & 3];
-                    ud[p] = EL::from_acc(d, p);
-                    pin(ud[p]);
-                    xch[(NKD + p) * 64] = EL::from_acc(accU[0], p);
+                    uf[p] = EL::from_acc(accU[0], p);
+                    pin(uf[p]);
+                    xch[(NKD + p) * 64] = uf[p];
                 }
                 GDN_FENCE();
             }
@@ -504,12 +483,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 constexpr int done = (NKD - 2 + stride - 1) / stride < SPT ? ((NKD - 2 + stride - 1) / stride > 0 ? (NKD - 2 + stride - 1) / stride : 0) : SPT;
 #pragma unroll
                 for (int p = done; p < SPT; ++p) {
-                    f32x16 d = accU[0];
-#pragma unroll
-                    for (int e = 0; e < RPS; ++e) d[p * RPS + e] *= dc[(p * RPS + e) >> 2][(p * RPS + e) & 3];
-                    ud[p] = EL::from_acc(d, p);
-                    pin(ud[p]);
-                    xch[(NKD + p) * 64] = EL::from_acc(accU[0], p);
+                    uf[p] = EL::from_acc(accU[0], p);
+                    pin(uf[p]);
+                    xch[(NKD + p) * 64] = uf[p];
                 }
                 GDN_FENCE();
             }
@@ -519,14 +495,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int s = 0; s < SPT; ++s) {
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    accS[mt] = EL::mma(kf[mt * NKC + s], ud[s], accS[mt]);
+                    accS[mt] = EL::mma(kf[mt * NKC + s], uf[s], accS[mt]);
                     if (mt == 0) {
-                        f32x16 d = accU[1];
-#pragma unroll
-                        for (int e = 0; e < RPS; ++e) d[s * RPS + e] *= dc[4 + ((s * RPS + e) >> 2)][(s * RPS + e) & 3];
-                        ud[SPT + s] = EL::from_acc(d, s);
-                        pin(ud[SPT + s]);
-                        xch[(NKD + SPT + s) * 64] = EL::from_acc(accU[1], s);
+                        uf[SPT + s] = EL::from_acc(accU[1], s);
+                        pin(uf[SPT + s]);
+                        xch[(NKD + SPT + s) * 64] = uf[SPT + s];
                     }
                     GDN_FENCE();
                 }
@@ -545,7 +518,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int s = SPT; s < 2 * SPT; ++s)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt, ++m) {
-                        accS[mt] = EL::mma(kf[mt * NKC + s], ud[s], accS[mt]);
+                        accS[mt] = EL::mma(kf[mt * NKC + s], uf[s], accS[mt]);
 #pragma unroll
                         for (int j = 0; j < WPM; ++j)
                             if (m * WPM + j < 2 * NKD) wf[m * WPM + j] = w_[(m * WPM + j) * 64];
