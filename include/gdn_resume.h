@@ -95,6 +95,10 @@ int32_t gdn_plan_chunks(int32_t n_req, const int32_t *cu_seqlens, const int32_t 
 /*
  * Upper bound, in bytes, of the workspace gdn_resume_prefill needs for a call with this
  * shape, n_req requests, total_tokens packed tokens and n_emit emissions.  Negative on error.
+ * The per-chunk intermediates are produced and consumed slab by slab (a bounded number of
+ * chunks of every request at a time), so beyond one slab the bound does not grow with the
+ * sequence length: it holds the chunk plan, one carried state per (request, layer, head) and
+ * one slab.
  */
 int64_t gdn_workspace_bytes(const gdn_shape *shape, int32_t n_req, int64_t total_tokens,
                             int32_t n_emit);

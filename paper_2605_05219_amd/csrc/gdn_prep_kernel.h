@@ -1,5 +1,6 @@
 // Chunk preparation kernel: everything of a 64-token chunk that does not depend on the
-// recurrent state.  One workgroup (4 waves) per (chunk, layer, value head).
+// recurrent state.  One workgroup (4 waves) per (chunk, layer, value head); a launch covers one
+// slab, i.e. up to R consecutive chunks of every request.
 //
 // With g_i the running sum of log a inside the chunk, gam_i = exp(g_i), and the chunk-local
 // form of the gated delta rule
@@ -31,7 +32,10 @@ struct PrepArgs {
     const int32_t* chunk_tok0;
     const int32_t* chunk_len;
     const int32_t* chunk_emit_slot;
-    char* ws_units;       // unit (c, l, h) at ((c * L + l) * H_v + h) * UNIT_BYTES
+    const int32_t* req_chunk_cu;
+    char* ws_units;       // this slab's units: (request r, round j, l, h) at (((r * R + j) * L + l) * H_v + h) * UNIT_BYTES
+    int32_t slab_begin;   // first chunk round of the slab (rounds are counted per request)
+    int32_t R;            // chunk rounds per slab
     int32_t L, H_qk, H_v;
     int64_t T_alloc;
     float scale;
@@ -115,7 +119,10 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     const int lr = lane & 31;
     const int g = lane >> 5;
 
-    const int c = blockIdx.x;
+    // workgroup (r * R + j, unit): chunk round slab_begin + j of request r, if it has that many
+    const int r = blockIdx.x / a.R;
+    const int c = a.req_chunk_cu[r] + a.slab_begin + (int)(blockIdx.x % a.R);
+    if (c >= a.req_chunk_cu[r + 1]) return;
     const int lh = blockIdx.y;
     const int l = lh / a.H_v;
     const int hv = lh % a.H_v;
@@ -123,7 +130,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     const int tok0 = a.chunk_tok0[c];
     const int n = a.chunk_len[c];
     const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
-    char* unit = a.ws_units + ((int64_t)(c * a.L + l) * a.H_v + hv) * U::UNIT_BYTES;
+    char* unit = a.ws_units + ((int64_t)blockIdx.x * a.L * a.H_v + lh) * U::UNIT_BYTES;
     Frag* w_img = reinterpret_cast<Frag*>(unit + U::W_OFF);
     Frag* q_img = reinterpret_cast<Frag*>(unit + U::Q_OFF);
     Frag* kt_img = reinterpret_cast<Frag*>(unit + U::KT_OFF);

@@ -10,6 +10,8 @@
 //     O^T = (S Q^T) diag(gam) + U^T P^T       [32][C]   (scale already folded into P)
 //     S^T <- gam_C S^T + K^T-contraction:     S^T[d_k][d_v] += sum_j (dec_j K[j][d_k]) U[j][d_v]
 // and, when the chunk ends at a checkpoint position, S is stored to its pool slot.
+// A launch covers one slab (up to R consecutive chunks of every request); a chain that goes on
+// in the next slab leaves its state in the carry buffer and picks it up there.
 #pragma once
 #include "gdn_mma.h"
 
@@ -23,7 +25,10 @@ struct RecurArgs {
     const int32_t* req_order;        // requests, longest chain first
     const float* state_src;
     float* state_dst;
+    float* carry;                    // [request][L][H_v][d_v][d_k]: state handed from one slab to the next
     int64_t src_slot_stride, dst_slot_stride;
+    int32_t slab_begin;              // first chunk round of this launch's slab
+    int32_t R;                       // chunk rounds per slab
     int32_t L, H_qk, H_v;
     int64_t T_alloc;
     float scale;
@@ -139,15 +144,20 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
     const int l = lh / a.H_v;
     const int hv = lh % a.H_v;
     const int sl = sg * NW + wave;           // this wave's d_v slice
-    const int c_begin = a.req_chunk_cu[r], c_end = a.req_chunk_cu[r + 1];
-    if (c_begin == c_end) return;
+    const int c_last = a.req_chunk_cu[r + 1];
+    const int c_begin = a.req_chunk_cu[r] + a.slab_begin;
+    if (c_begin >= c_last) return;
+    const int c_end = min(c_last, c_begin + a.R);
 
-    // ---- start state
+    // ---- start state: the pool slot (or zeros) in the first slab, the carried state afterwards
     f32x16 accS[MT];
     const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK + (int64_t)(32 * sl + lr) * DK;
+    float* const carry = a.carry + (int64_t)r * units * DV * DK + head_off;
     {
         const int slot = a.req_src_slot[r];
-        if (slot >= 0) {
+        if (a.slab_begin > 0) {
+            load_state<MT>(accS, carry, g);
+        } else if (slot >= 0) {
             load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
         } else {
 #pragma unroll
@@ -158,7 +168,7 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
     }
 
     const int64_t unit_stride = (int64_t)units * U::UNIT_BYTES;   // from one chunk to the next
-    const char* unit = a.ws_units + ((int64_t)c_begin * units + lh) * U::UNIT_BYTES;
+    const char* unit = a.ws_units + ((int64_t)r * a.R * units + lh) * U::UNIT_BYTES;
 
     // image prefetch registers of the staged variant: NFULL vectors per thread plus a tail
     constexpr int NVEC = U::STAGED_BYTES / 16;
@@ -260,6 +270,7 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         }
         store_o_t<DV>(a, row0, hv, sl, lr, g, n, ot);
     }
+    if (c_end < c_last) store_state<MT>(accS, carry, g);
 }
 
 #undef GDN_PREFETCH_IMAGE
@@ -329,19 +340,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int lr = lane & 31;
     const int g = lane >> 5;
 
+    // Workgroups are handed to the eight XCDs round robin, and each XCD has its own L2.  The NS
+    // slices of a chain read the same W, K^T, Q and P, so consecutive work items are given to
+    // workgroups of the same XCD: item = (position of this XCD's first workgroup in a by-XCD
+    // ordering) + (index of this workgroup within its XCD).
+    int item;
+    {
+        const int nb = gridDim.x, x = blockIdx.x & 7, q = nb >> 3, rem = nb & 7;
+        item = (x < rem ? x * (q + 1) : rem * (q + 1) + (x - rem) * q) + (blockIdx.x >> 3);
+    }
     const int units = a.L * a.H_v;
-    const int sl = blockIdx.x % NS;
-    const int chain = blockIdx.x / NS;
+    const int sl = item % NS;
+    const int chain = item / NS;
     const int r = a.req_order[chain / units];
     const int lh = chain % units;
     const int l = lh / a.H_v;
     const int hv = lh % a.H_v;
-    const int c_begin = a.req_chunk_cu[r], c_end = a.req_chunk_cu[r + 1];
-    if (c_begin == c_end) return;
-    const int n_chunks = c_end - c_begin;
+    const int c_last = a.req_chunk_cu[r + 1];
+    const int c_begin = a.req_chunk_cu[r] + a.slab_begin;
+    if (c_begin >= c_last) return;
+    const int n_chunks = min(c_last - c_begin, a.R);
 
     const int64_t unit_stride = (int64_t)units * U::UNIT_BYTES;
-    const char* unit0 = a.ws_units + ((int64_t)c_begin * units + lh) * U::UNIT_BYTES;
+    const char* unit0 = a.ws_units + ((int64_t)r * a.R * units + lh) * U::UNIT_BYTES;
 
     if (wave == 3) {
         // ------------------------------------------------------------ loader wave
@@ -391,9 +412,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         // ------------------------------------------------------------ chain wave
         f32x16 accS[MT];
         const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK + (int64_t)(32 * sl + lr) * DK;
+        float* const carry = a.carry + (int64_t)r * units * DV * DK + head_off;
         {
             const int slot = a.req_src_slot[r];
-            if (slot >= 0) {
+            if (a.slab_begin > 0) {
+                load_state<MT>(accS, carry, g);
+            } else if (slot >= 0) {
                 load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
             } else {
 #pragma unroll
@@ -540,6 +564,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             // checkpoint emission: exact state after the last token of this chunk
             if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
         }
+        if (c_begin + n_chunks < c_last) store_state<MT>(accS, carry, g);
     } else {
         // ------------------------------------------------------------ output waves
         // Wave 1 owns token tile 0, wave 2 token tile 1.  Three register sets of Q/P fragments

@@ -134,15 +134,16 @@ int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream
 }
 
 // ------------------------------------------------------------------ optional per-kernel timing
-// When switched on, every prefill call records three events on its stream (before the prep
-// kernel, between the kernels, after the recurrence kernel); collect() waits for them and sums
-// the two intervals.  Off by default: nothing is recorded.
+// When switched on, the kernel launches of a prefill call are separated by events on the
+// caller's stream (one before the first launch, one after each); collect() waits for them and
+// sums the intervals per kernel kind.  Off by default: nothing is recorded.
 struct Profiler {
+    struct Mark { hipEvent_t ev; int kind; };   // kind of the launch that ENDS at ev; -1: a chain starts
     std::mutex mu;
     bool on = false;
     std::vector<hipEvent_t> spare;
-    std::vector<hipEvent_t> pending;  // triples
-    double prep_ms = 0.0, recur_ms = 0.0;
+    std::vector<Mark> marks;
+    double ms[2] = {0.0, 0.0};   // 0: preparation, 1: recurrence
     int64_t calls = 0;
 
     hipEvent_t get() {
@@ -155,26 +156,33 @@ struct Profiler {
         if (hipEventCreate(&e) != hipSuccess) return nullptr;
         return e;
     }
+    void recycle() {
+        for (auto& m : marks) spare.push_back(m.ev);
+        marks.clear();
+    }
 };
 Profiler g_prof;
 
-struct ProfScope {
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    bool active = false;
+// One call's chain of marks.
+struct ProfChain {
     hipStream_t stream;
-    explicit ProfScope(hipStream_t s) : stream(s) {
+    bool on;
+    explicit ProfChain(hipStream_t s) : stream(s) {
         std::lock_guard<std::mutex> lock(g_prof.mu);
-        if (!g_prof.on) return;
-        for (auto& e : ev) e = g_prof.get();
-        active = ev[0] && ev[1] && ev[2];
+        on = g_prof.on;
+        if (on) mark_locked(-1);
     }
-    void mark(int i) {
-        if (active) (void)hipEventRecord(ev[i], stream);
-    }
-    ~ProfScope() {
-        if (!active) return;
+    void mark(int kind) {
+        if (!on) return;
         std::lock_guard<std::mutex> lock(g_prof.mu);
-        for (auto e : ev) g_prof.pending.push_back(e);
+        mark_locked(kind);
+    }
+private:
+    void mark_locked(int kind) {
+        hipEvent_t e = g_prof.get();
+        if (!e) { on = false; return; }
+        (void)hipEventRecord(e, stream);
+        g_prof.marks.push_back({e, kind});
     }
 };
 
@@ -224,9 +232,41 @@ hipError_t launch_recur_quad(const RecurArgs& ra, int64_t n_chains, hipStream_t 
     return hipGetLastError();
 }
 
+// Which recurrence variant a call gets: 1 = latency variant (few chains), else the number of
+// d_v slices (waves) per workgroup of the throughput variant.
+inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
+    int nw = ns;
+    while (nw > 1 && n_chains * (ns / nw) < 512) nw >>= 1;
+    if (const int o = recur_waves_override()) {
+        if (o == 1 || o == 2 || (o == 4 && ns == 4)) nw = o;
+    }
+    if (nw == 1 && !frag16) nw = 2;   // fp32 operands: the latency variant's registers are sized for 16-byte fragments
+    return nw;
+}
+
+// Chunk rounds per slab.  The latency variant wants a slab's operand images to stay in the
+// last-level caches between the kernel that writes them and the one that reads them; the
+// throughput variant only bounds the workspace.
+// Chunk rounds per slab.  The slab should stay cache resident between the preparation launch
+// that writes it and the recurrence launch that reads it back (budget), and a preparation
+// launch should fill the chip a whole number of times (512 = two of its workgroups on each of
+// the 256 compute units).  GDN_SLAB_ROUNDS overrides the choice.
+inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
+    static const int32_t forced = [] {
+        const char* e = std::getenv("GDN_SLAB_ROUNDS");
+        return e ? std::atoi(e) : 0;
+    }();
+    if (forced > 0) return forced;
+    const int64_t budget = nw == 1 ? (int64_t)96 << 20 : (int64_t)1 << 30;
+    int64_t r = std::max<int64_t>(1, budget / std::max<int64_t>(1, n_chains * unit_bytes));
+    const int64_t q = std::max<int64_t>(1, 512 / std::max<int64_t>(1, n_chains));
+    r = std::max(q, r / q * q);
+    return (int32_t)std::min<int64_t>(r, 1 << 16);
+}
+
 template <typename E, int DK, int DV>
-int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, int32_t n_chunks, int32_t n_req,
-                   hipStream_t stream) {
+int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req, int32_t max_chunks_per_req,
+                   char* slab_base, hipStream_t stream) {
     typedef PrepSmem<E, DK, DV> SM;
     static bool attr_set = false;
     if (!attr_set) {
@@ -236,36 +276,41 @@ int32_t launch_all(const gdn_shape& s, const PrepArgs& pa, const RecurArgs& ra, 
         attr_set = true;
     }
     const int units = s.L * s.H_v;
-    ProfScope prof(stream);
-    prof.mark(0);
-    hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)n_chunks, (unsigned)units), dim3(256), SM::BYTES, stream, pa);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_err(e);
-    prof.mark(1);
-
-    // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain share
-    // one workgroup and one LDS copy of the chunk operands; with fewer, two slices per workgroup;
-    // with too few to occupy every compute unit, the latency variant (chain, output and
-    // two loader waves per slice).
     const int64_t n_chains = (int64_t)n_req * units;
     constexpr int NS = DV / 32;
-    int nw = NS;
-    while (nw > 1 && n_chains * (NS / nw) < 512) nw >>= 1;
-    if (const int o = recur_waves_override()) {
-        if (o == 1 || o == 2 || (o == 4 && NS == 4)) nw = o;
-    }
-    if constexpr (sizeof(typename Elem<E>::Frag) == 16) {
-        if (nw == 1) {
-            e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
-            prof.mark(2);
-            return hip_err(e);
+    const int nw = pick_waves(n_chains, NS, sizeof(typename Elem<E>::Frag) == 16);
+    const int32_t R = pa.R;
+    const int32_t n_slabs = (max_chunks_per_req + R - 1) / R;
+
+    // Slab after slab on the caller's stream: the units one preparation launch writes are read
+    // back by the recurrence launch right behind it while they are still in the caches.
+    ProfChain prof(stream);
+    pa.ws_units = slab_base;
+    ra.ws_units = slab_base;
+    for (int32_t sb = 0; sb < n_slabs; ++sb) {
+        pa.slab_begin = sb * R;
+        ra.slab_begin = sb * R;
+        hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)(n_req * R), (unsigned)units), dim3(256), SM::BYTES,
+                           stream, pa);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_err(e);
+        prof.mark(0);
+        // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain
+        // share one workgroup and one LDS copy of the chunk operands; with fewer, two slices per
+        // workgroup; with too few to occupy every compute unit, the latency variant.
+        if constexpr (sizeof(typename Elem<E>::Frag) == 16) {
+            if (nw == 1) e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
         }
+        if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
+        else if (nw > 2) e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
+        if (e != hipSuccess) return hip_err(e);
+        prof.mark(1);
     }
-    // (fp32 operands: the latency variant's register budget is sized for 16-byte fragments)
-    if (nw <= 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
-    else e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
-    prof.mark(2);
-    return hip_err(e);
+    {
+        std::lock_guard<std::mutex> lock(g_prof.mu);
+        if (g_prof.on) g_prof.calls += 1;
+    }
+    return GDN_OK;
 }
 
 }  // namespace
@@ -281,9 +326,8 @@ int32_t gdn_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lock(g_prof.mu);
     g_prof.on = on != 0;
     if (on) {
-        for (auto e : g_prof.pending) g_prof.spare.push_back(e);
-        g_prof.pending.clear();
-        g_prof.prep_ms = g_prof.recur_ms = 0.0;
+        g_prof.recycle();
+        g_prof.ms[0] = g_prof.ms[1] = 0.0;
         g_prof.calls = 0;
     }
     return GDN_OK;
@@ -291,23 +335,19 @@ int32_t gdn_profile_enable(int32_t on) {
 
 int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls) {
     std::lock_guard<std::mutex> lock(g_prof.mu);
-    for (size_t i = 0; i + 2 < g_prof.pending.size(); i += 3) {
-        hipEvent_t* ev = &g_prof.pending[i];
-        hipError_t e = hipEventSynchronize(ev[2]);
+    for (size_t i = 0; i < g_prof.marks.size(); ++i) {
+        const Profiler::Mark& m = g_prof.marks[i];
+        if (m.kind < 0) continue;
+        hipError_t e = hipEventSynchronize(m.ev);
         if (e != hipSuccess) return hip_err(e);
-        float a = 0.f, b = 0.f;
-        e = hipEventElapsedTime(&a, ev[0], ev[1]);
+        float t = 0.f;
+        e = hipEventElapsedTime(&t, g_prof.marks[i - 1].ev, m.ev);
         if (e != hipSuccess) return hip_err(e);
-        e = hipEventElapsedTime(&b, ev[1], ev[2]);
-        if (e != hipSuccess) return hip_err(e);
-        g_prof.prep_ms += a;
-        g_prof.recur_ms += b;
-        g_prof.calls += 1;
+        g_prof.ms[m.kind] += t;
     }
-    for (auto e : g_prof.pending) g_prof.spare.push_back(e);
-    g_prof.pending.clear();
-    if (prep_ms) *prep_ms = g_prof.prep_ms;
-    if (recur_ms) *recur_ms = g_prof.recur_ms;
+    g_prof.recycle();
+    if (prep_ms) *prep_ms = g_prof.ms[0];
+    if (recur_ms) *recur_ms = g_prof.ms[1];
     if (calls) *calls = g_prof.calls;
     return GDN_OK;
 }
@@ -342,12 +382,31 @@ static int64_t plan_bytes(int64_t n_chunks, int64_t n_req) {
     return align_up((3 * n_chunks + 3 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
 }
 
+// Workspace = [plan | carried states | slab].  The slab holds the units of R chunk rounds of
+// every chain; slabs are processed one after the other and reuse it.
+struct WsLayout {
+    int32_t R;
+    int64_t plan, carry, slab, total;
+};
+// n_chunks: chunks of the whole call; max_rounds: chunks of its longest request (or a bound)
+static WsLayout ws_layout(const gdn_shape& s, int64_t n_chunks, int64_t max_rounds, int32_t n_req) {
+    const int64_t units = (int64_t)s.L * s.H_v, n_chains = units * n_req, ub = unit_bytes(s);
+    const int nw = pick_waves(n_chains, s.d_v / 32, s.in_dtype != GDN_F32);
+    WsLayout w;
+    w.R = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slab_rounds(n_chains, ub, nw), max_rounds));
+    w.plan = plan_bytes(n_chunks, n_req);
+    w.carry = align_up(n_chains * s.d_v * s.d_k * (int64_t)sizeof(float), 256);
+    w.slab = n_chains * w.R * ub;
+    w.total = w.plan + w.carry + w.slab;
+    return w;
+}
+
 int64_t gdn_workspace_bytes(const gdn_shape* shape, int32_t n_req, int64_t total_tokens, int32_t n_emit) {
     const int32_t rc = check_shape(shape);
     if (rc != GDN_OK) return rc;
     if (n_req < 0 || total_tokens < 0 || n_emit < 0) return GDN_ERR_COUNT;
     const int64_t max_chunks = total_tokens / GDN_CHUNK + n_req + n_emit + 1;
-    return plan_bytes(max_chunks, n_req) + max_chunks * shape->L * shape->H_v * unit_bytes(*shape);
+    return ws_layout(*shape, max_chunks, max_chunks, n_req).total;
 }
 
 int32_t ckpt_gather(const float* pool, int64_t slot_stride, int32_t n_slots, const int32_t* slot_ids, int32_t n,
@@ -408,9 +467,9 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     const int64_t esz = s.in_dtype == GDN_F32 ? 4 : 2;
     if (((int64_t)s.H_v * esz) & 1) return GDN_ERR_ALIGN;
 
-    const int64_t ub = unit_bytes(s);
-    const int64_t pb = plan_bytes(n_chunks, n_req);
-    const int64_t need = pb + (int64_t)n_chunks * s.L * s.H_v * ub;
+    const WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
+    const int64_t pb = wl.plan;
+    const int64_t need = wl.total;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GDN_ERR_WORKSPACE;
     if (workspace_bytes < need) return GDN_ERR_WORKSPACE;
 
@@ -436,20 +495,26 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     if (rc != GDN_OK) return rc;
 
     const int32_t* d = reinterpret_cast<const int32_t*>(workspace);
-    char* ws_units = reinterpret_cast<char*>(workspace) + pb;
+    char* slab_base = reinterpret_cast<char*>(workspace) + wl.plan + wl.carry;
 
     PrepArgs pa;
     pa.q = q; pa.k = k; pa.v = v; pa.beta = beta; pa.gate = gate;
     pa.chunk_tok0 = d;
     pa.chunk_len = d + n_chunks;
     pa.chunk_emit_slot = d + 2 * (int64_t)n_chunks;
-    pa.ws_units = ws_units;
+    pa.req_chunk_cu = d + 3 * (int64_t)n_chunks;
+    pa.ws_units = nullptr;   // set per slab
+    pa.slab_begin = 0;
+    pa.R = wl.R;
     pa.L = s.L; pa.H_qk = s.H_qk; pa.H_v = s.H_v;
     pa.T_alloc = s.T_alloc;
     pa.scale = s.scale;
 
     RecurArgs ra;
-    ra.o = o; ra.ws_units = ws_units;
+    ra.o = o; ra.ws_units = nullptr;
+    ra.carry = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + wl.plan);
+    ra.slab_begin = 0;
+    ra.R = wl.R;
     ra.req_chunk_cu = d + 3 * (int64_t)n_chunks;
     ra.req_src_slot = ra.req_chunk_cu + (n_req + 1);
     ra.req_order = ra.req_src_slot + n_req;
@@ -461,9 +526,10 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     ra.o_bf16 = s.o_dtype == GDN_BF16;
 
 
-    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
-    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_chunks, n_req, stream);
-    return launch_all<half_t, 128, 128>(s, pa, ra, n_chunks, n_req, stream);
+    const int32_t mc = plan.max_chunks_per_req;
+    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
+    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
+    return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, stream);
 }
 
 }  // extern "C"
