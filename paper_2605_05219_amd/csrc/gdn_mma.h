@@ -68,17 +68,19 @@ template <> struct Elem<half_t> {
         h[0] = (half_t)a; h[1] = (half_t)b; h[2] = (half_t)c; h[3] = (half_t)d;
         *reinterpret_cast<half4*>(p) = h;
     }
-    // 8 consecutive input elements -> float
-    static __device__ __forceinline__ void load8(const In* p, float out[8]) {
-        const uint4 raw = *reinterpret_cast<const uint4*>(p);
-        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    // 8 consecutive input elements as they come from memory (so that a fetch can be issued long
+    // before its first use), and their widening to float
+    typedef u32x4 Raw8;
+    static __device__ __forceinline__ Raw8 load_raw(const In* p) { return *reinterpret_cast<const u32x4*>(p); }
+    static __device__ __forceinline__ Raw8 zero_raw() { return Raw8{0u, 0u, 0u, 0u}; }
+    static __device__ __forceinline__ void unpack(const Raw8& raw, float out[8]) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            out[2 * i] = __uint_as_float(w[i] << 16);
-            out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+            out[2 * i] = __uint_as_float(raw[i] << 16);
+            out[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
         }
     }
-    static __device__ __forceinline__ float load1(const In* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+    static __device__ __forceinline__ float widen(In x) { return __uint_as_float((uint32_t)x << 16); }
     // hardware exp2/log2 based: relative error ~1e-6 |x|, far inside the fp16 operand rounding
     static __device__ __forceinline__ float exp_(float x) { return __expf(x); }
     static __device__ __forceinline__ float log_(float x) { return __logf(x); }
@@ -106,13 +108,16 @@ template <> struct Elem<float> {
     static __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
         p[0] = a; p[1] = b; p[2] = c; p[3] = d;
     }
-    static __device__ __forceinline__ void load8(const In* p, float out[8]) {
-        const float4 a = *reinterpret_cast<const float4*>(p);
-        const float4 b = *reinterpret_cast<const float4*>(p + 4);
-        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    struct Raw8 { f32x4 a, b; };
+    static __device__ __forceinline__ Raw8 load_raw(const In* p) {
+        return Raw8{*reinterpret_cast<const f32x4*>(p), *reinterpret_cast<const f32x4*>(p + 4)};
     }
-    static __device__ __forceinline__ float load1(const In* p) { return *p; }
+    static __device__ __forceinline__ Raw8 zero_raw() { return Raw8{f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}}; }
+    static __device__ __forceinline__ void unpack(const Raw8& raw, float out[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { out[i] = raw.a[i]; out[4 + i] = raw.b[i]; }
+    }
+    static __device__ __forceinline__ float widen(In x) { return x; }
     static __device__ __forceinline__ float exp_(float x) { return expf(x); }
     static __device__ __forceinline__ float log_(float x) { return logf(x); }
 };

@@ -1,6 +1,7 @@
 // Chunk preparation kernel: everything of a 64-token chunk that does not depend on the
-// recurrent state.  One workgroup (4 waves) per (chunk, layer, value head); a launch covers one
-// slab, i.e. up to R consecutive chunks of every request.
+// recurrent state.  A workgroup (4 waves) handles one (chunk, layer, value head) at a time; a
+// launch covers one slab, i.e. up to R consecutive chunks of every request, with as many
+// workgroups as the chip holds at once, each looping over its share of the slab.
 //
 // With g_i the running sum of log a inside the chunk, gam_i = exp(g_i), and the chunk-local
 // form of the gated delta rule
@@ -36,6 +37,7 @@ struct PrepArgs {
     char* ws_units;       // this slab's units: (request r, round j, l, h) at (((r * R + j) * L + l) * H_v + h) * UNIT_BYTES
     int32_t slab_begin;   // first chunk round of the slab (rounds are counted per request)
     int32_t R;            // chunk rounds per slab
+    int32_t n_req;
     int32_t L, H_qk, H_v;
     int64_t T_alloc;
     float scale;
@@ -86,7 +88,7 @@ struct PrepSmem {
 };
 
 template <typename E, int DK, int DV>
-__global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_prep_kernel(PrepArgs a) {
     typedef Elem<E> EL;
     typedef typename EL::In In;
     typedef typename EL::Frag Frag;
@@ -118,32 +120,99 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
     const int g = lane >> 5;
+    constexpr int SPT = EL::STEPS_PER_TILE;
+    const In* const qg = reinterpret_cast<const In*>(a.q);
+    const In* const kg = reinterpret_cast<const In*>(a.k);
+    const In* const vg = reinterpret_cast<const In*>(a.v);
 
-    // workgroup (r * R + j, unit): chunk round slab_begin + j of request r, if it has that many
-    const int r = blockIdx.x / a.R;
-    const int c = a.req_chunk_cu[r] + a.slab_begin + (int)(blockIdx.x % a.R);
-    if (c >= a.req_chunk_cu[r + 1]) return;
-    const int lh = blockIdx.y;
-    const int l = lh / a.H_v;
-    const int hv = lh % a.H_v;
-    const int hq = hv / (a.H_v / a.H_qk);
-    const int tok0 = a.chunk_tok0[c];
-    const int n = a.chunk_len[c];
-    const int64_t row0 = (int64_t)l * a.T_alloc + tok0;
-    char* unit = a.ws_units + ((int64_t)blockIdx.x * a.L * a.H_v + lh) * U::UNIT_BYTES;
+    // Work items of the launch: u = x * units + lh with x = r * R + j (chunk round slab_begin + j
+    // of request r, skipped if the request has no such round).  The workgroup takes items
+    // blockIdx.x, blockIdx.x + gridDim.x, ... and fetches the inputs of its next item while it
+    // works on the current one.
+    const int units = a.L * a.H_v;
+    const int total = a.n_req * a.R * units;
+    struct Item { int u, c, lh, x, tok0, n; };
+    auto locate = [&](int u) -> Item {
+        Item it;
+        it.c = -1; it.lh = 0; it.x = 0; it.tok0 = 0; it.n = 0;
+        for (;; u += (int)gridDim.x) {
+            it.u = u;
+            if (u >= total) return it;
+            it.x = u / units;
+            it.lh = u - it.x * units;
+            const int r = it.x / a.R;
+            it.c = a.req_chunk_cu[r] + a.slab_begin + (it.x - r * a.R);
+            if (it.c < a.req_chunk_cu[r + 1]) break;
+        }
+        it.tok0 = a.chunk_tok0[it.c];
+        it.n = a.chunk_len[it.c];
+        return it;
+    };
+    // A thread owns 4-token x 8-column blocks of K, Q and V.
+    constexpr int KB = (C / 4) * (DK / 8), VB = (C / 4) * (DV / 8);   // blocks of K (and Q), of V
+    static_assert(KB <= 256 && VB <= 256, "one block per thread at most");
+    const int tg = tid / (DK / 8), d0 = (tid % (DK / 8)) * 8;
+    const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+    typedef typename EL::Raw8 Raw8;
+    // (16-bit inputs only: the fp32 fetch registers would not fit next to the working set)
+    constexpr bool PREFETCH = sizeof(In) == 2;
+    Raw8 kraw[4], qraw[4], vraw[4];
+    In graw = In(), braw = In();
+    auto fetch_kq = [&](const Item& it) {
+        const int l = it.lh / a.H_v, hq = (it.lh % a.H_v) / (a.H_v / a.H_qk);
+        const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 4 * tg + r;
+            if (tid < KB && i < it.n) {
+                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
+                kraw[r] = EL::load_raw(kg + off);
+                qraw[r] = EL::load_raw(qg + off);
+            } else {
+                kraw[r] = EL::zero_raw();
+                qraw[r] = EL::zero_raw();
+            }
+        }
+    };
+    auto fetch_v = [&](const Item& it) {
+        const int l = it.lh / a.H_v, hv = it.lh % a.H_v;
+        const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int iv = 4 * tgv + r;
+            if (tid < VB && iv < it.n) vraw[r] = EL::load_raw(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v);
+            else vraw[r] = EL::zero_raw();
+        }
+        if (wave == 0 && lane < it.n) {
+            const int64_t gi = (row0 + lane) * a.H_v + hv;
+            graw = reinterpret_cast<const In*>(a.gate)[gi];
+            braw = reinterpret_cast<const In*>(a.beta)[gi];
+        }
+    };
+
+    Item cur = locate((int)blockIdx.x);
+    if (cur.u >= total) return;
+    fetch_kq(cur);
+    fetch_v(cur);
+    Item nxt = locate(cur.u + (int)gridDim.x);
+
+  for (;;) {
+    const int c = cur.c;
+    const int lh = cur.lh;
+    const int tok0 = cur.tok0;
+    const int n = cur.n;
+    char* unit = a.ws_units + ((int64_t)cur.x * units + lh) * U::UNIT_BYTES;
     Frag* w_img = reinterpret_cast<Frag*>(unit + U::W_OFF);
     Frag* q_img = reinterpret_cast<Frag*>(unit + U::Q_OFF);
     Frag* kt_img = reinterpret_cast<Frag*>(unit + U::KT_OFF);
     Frag* p_img = reinterpret_cast<Frag*>(unit + U::P_OFF);
-    constexpr int SPT = EL::STEPS_PER_TILE;
 
     // ---- gates: g_i = inclusive running sum of log a (wave 0), b_i; identity beyond n
     if (wave == 0) {
         float la = 0.f, b = 0.f;
         if (lane < n) {
-            const int64_t gi = (row0 + lane) * a.H_v + hv;
-            la = fmaxf(EL::log_(EL::load1(reinterpret_cast<const In*>(a.gate) + gi)), -88.f);
-            b = EL::load1(reinterpret_cast<const In*>(a.beta) + gi);
+            la = fmaxf(EL::log_(EL::widen(graw)), -88.f);
+            b = EL::widen(braw);
         }
         float s = la;
 #pragma unroll
@@ -160,53 +229,27 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     // ---- zero the fp32 triangular matrix (its untouched upper blocks must read as 0)
     for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
 
-    // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E.  A thread owns
-    //      4-token x 8-column blocks: every global load is issued before the first LDS store,
-    //      and the transposed copy goes out as 4-token runs.  V is fetched now and kept in
-    //      registers; its transposed tile takes K's place once K is dead.
-    constexpr int KB = (C / 4) * (DK / 8), VB = (C / 4) * (DV / 8);   // blocks of K (and Q), of V
-    static_assert(KB <= 256 && VB <= 256, "one block per thread at most");
-    float vv[4][8];
-    {
-        const In* qg = reinterpret_cast<const In*>(a.q);
-        const In* kg = reinterpret_cast<const In*>(a.k);
-        const In* vg = reinterpret_cast<const In*>(a.v);
-        float kv[4][8], qv[4][8];
-        const int tg = tid / (DK / 8), d0 = (tid % (DK / 8)) * 8;
-        const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+    // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E; the transposed
+    //      copy goes out as 4-token runs.  V stays in registers; its transposed tile takes K's
+    //      place once K is dead.
+    if (tid < KB) {
+        float kv[4][8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * tg + r;
-            if (tid < KB && i < n) {
-                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
-                EL::load8(kg + off, kv[r]);
-                EL::load8(qg + off, qv[r]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { kv[r][e] = 0.f; qv[r][e] = 0.f; }
-            }
-            const int iv = 4 * tgv + r;
-            if (tid < VB && iv < n) {
-                EL::load8(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v, vv[r]);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) vv[r][e] = 0.f;
-            }
+            float qv[8];
+            EL::unpack(kraw[r], kv[r]);
+            EL::unpack(qraw[r], qv);
+            EL::store4(Ks + i * K_LD + d0, kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
+            EL::store4(Ks + i * K_LD + d0 + 4, kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
+            EL::store4(Qs + i * K_LD + d0, qv[0], qv[1], qv[2], qv[3]);
+            EL::store4(Qs + i * K_LD + d0 + 4, qv[4], qv[5], qv[6], qv[7]);
         }
-        if (tid < KB) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = 4 * tg + r;
-                EL::store4(Ks + i * K_LD + d0, kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
-                EL::store4(Ks + i * K_LD + d0 + 4, kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
-                EL::store4(Qs + i * K_LD + d0, qv[r][0], qv[r][1], qv[r][2], qv[r][3]);
-                EL::store4(Qs + i * K_LD + d0 + 4, qv[r][4], qv[r][5], qv[r][6], qv[r][7]);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                EL::store4(KTs + (d0 + e) * KT_LD + 4 * tg, kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
-        }
+        for (int e = 0; e < 8; ++e)
+            EL::store4(KTs + (d0 + e) * KT_LD + 4 * tg, kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
     }
+    if (PREFETCH && nxt.u < total) fetch_kq(nxt);   // K and Q of the next item travel during the rest of this one
     __syncthreads();
 
     // ---- K K^T -> L (fp32) and K Q^T -> P fragments
@@ -263,11 +306,14 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
 
     // ---- V^T into K's place (read by the last product, several barriers from here)
     if (tid < VB) {
-        const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+        float vv[4][8];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) EL::unpack(vraw[r], vv[r]);
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             EL::store4(VTs + (d0v + e) * VT_LD + 4 * tgv, vv[0][e], vv[1][e], vv[2][e], vv[3][e]);
     }
+    if (PREFETCH && nxt.u < total) fetch_v(nxt);    // V and the gates of the next item
 
     // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks by forward
     //      substitution, one per wave, column (lane & 15) of the inverse in registers.
@@ -353,7 +399,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     //      K^T's fragments.  T is lower triangular: token tile 0 only contracts over j < 32.
     constexpr int NKC = C / EL::KSTEP;
     for (int t = wave; t < (DK / 32) * 2; t += 4) {
-        const int mt = t >> 1, nt = t & 1;
+        const int mt = t % (DK / 32), nt = t / (DK / 32);   // a wave's tiles: one of each token tile where possible
         f32x16 acc = {0};
         const E* ar = KTs + (32 * mt + lr) * KT_LD;
         const E* br = Tbg + (32 * nt + lr) * T_LD;
@@ -374,7 +420,7 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
     {
         f32x4* ut = reinterpret_cast<f32x4*>(unit + U::UT_OFF);
         for (int p = wave; p < (DV / 32) * 2; p += 4) {
-            const int sl = p >> 1, rt = p & 1;
+            const int sl = p % (DV / 32), rt = p / (DV / 32);
             f32x16 acc = {0};
             const E* ar = Tb + (32 * rt + lr) * T_LD;
             const E* br = VTs + (32 * sl + lr) * VT_LD;
@@ -402,6 +448,15 @@ __global__ void __launch_bounds__(256) gdn_prep_kernel(PrepArgs a) {
             meta[AUX_LEN] = n;
         }
     }
+    if (nxt.u >= total) break;
+    cur = nxt;
+    nxt = locate(cur.u + (int)gridDim.x);
+    if (!PREFETCH) {
+        fetch_kq(cur);
+        fetch_v(cur);
+    }
+    __syncthreads();   // every wave is done with this item's LDS tiles
+  }
 }
 
 }  // namespace gdn

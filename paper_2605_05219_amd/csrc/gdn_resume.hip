@@ -268,12 +268,19 @@ template <typename E, int DK, int DV>
 int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req, int32_t max_chunks_per_req,
                    char* slab_base, hipStream_t stream) {
     typedef PrepSmem<E, DK, DV> SM;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_prep_kernel<E, DK, DV>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+    // workgroups of the preparation kernel the chip holds at once (per kernel instance)
+    static int prep_slots = 0;
+    if (prep_slots == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_prep_kernel<E, DK, DV>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
         if (e != hipSuccess) return hip_err(e);
-        attr_set = true;
+        int dev = 0, cus = 0, per_cu = 0;
+        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_prep_kernel<E, DK, DV>, 256, SM::BYTES);
+        if (e != hipSuccess) return hip_err(e);
+        prep_slots = std::max(1, cus * per_cu);
     }
     const int units = s.L * s.H_v;
     const int64_t n_chains = (int64_t)n_req * units;
@@ -290,8 +297,10 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
     for (int32_t sb = 0; sb < n_slabs; ++sb) {
         pa.slab_begin = sb * R;
         ra.slab_begin = sb * R;
-        hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)(n_req * R), (unsigned)units), dim3(256), SM::BYTES,
-                           stream, pa);
+        const int64_t items = (int64_t)n_req * R * units;
+        if (items > INT32_MAX) return GDN_ERR_COUNT;
+        hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)std::min<int64_t>(items, prep_slots)), dim3(256),
+                           SM::BYTES, stream, pa);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_err(e);
         prof.mark(0);
@@ -506,6 +515,7 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     pa.ws_units = nullptr;   // set per slab
     pa.slab_begin = 0;
     pa.R = wl.R;
+    pa.n_req = n_req;
     pa.L = s.L; pa.H_qk = s.H_qk; pa.H_v = s.H_v;
     pa.T_alloc = s.T_alloc;
     pa.scale = s.scale;
