@@ -37,6 +37,9 @@ template <> struct Elem<half_t> {
     static constexpr int KSTEP = 16;   // contraction indices per MFMA
     static constexpr int STEPS_PER_TILE = 2;  // MFMA steps that consume one 32-row accumulator tile
 
+    // slot4: where the 4-aligned run of contraction indices starting at c is stored in an LDS row
+    // (the identity: rows are kept in index order and a step's operand is two 8-byte reads)
+    static __device__ __forceinline__ int slot4(int c) { return c; }
     static __device__ __forceinline__ Frag load(const half_t* row, int s, int g) {
         const half4 lo = *reinterpret_cast<const half4*>(row + 16 * s + 4 * g);
         const half4 hi = *reinterpret_cast<const half4*>(row + 16 * s + 8 + 4 * g);
@@ -93,6 +96,7 @@ template <> struct Elem<float> {
     static constexpr int KSTEP = 2;
     static constexpr int STEPS_PER_TILE = 16;
 
+    static __device__ __forceinline__ int slot4(int c) { return c; }
     static __device__ __forceinline__ Frag load(const float* row, int s, int g) {
         const int w = s & 15;
         return row[32 * (s >> 4) + 8 * (w >> 2) + 4 * g + (w & 3)];

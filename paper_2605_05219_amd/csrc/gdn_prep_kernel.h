@@ -54,7 +54,7 @@ __device__ __forceinline__ f32x4 mm16_ll(f32x4 acc, const float* A, const float*
 }
 // Same with B taken from an accumulator tile (rows 4*g4+e are the contraction index).
 template <int LD>
-__device__ __forceinline__ f32x4 mm16_lr(f32x4 acc, const float* A, const f32x4& B, int m, int g4) {
+__device__ __forceinline__ f32x4 mm16_lr(f32x4 acc, const float* A, const f32x4 B, int m, int g4) {
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(A[m * LD + 4 * g4 + e], B[e], acc, 0, 0, 0);
@@ -192,6 +192,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     Item cur = locate((int)blockIdx.x);
     if (cur.u >= total) return;
+    // The fp32 triangular matrix: its upper right 32x32 tile is never written and must read as 0
+    // (every other entry on or above the diagonal is rewritten with an exact 0 for each item).
+    for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
     fetch_kq(cur);
     fetch_v(cur);
     Item nxt = locate(cur.u + (int)gridDim.x);
@@ -226,8 +229,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         gamS[lane] = EL::exp_(s);
         decS[lane] = EL::exp_(g_last - s);
     }
-    // ---- zero the fp32 triangular matrix (its untouched upper blocks must read as 0)
-    for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
 
     // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E; the transposed
     //      copy goes out as 4-token runs.  V stays in registers; its transposed tile takes K's
@@ -240,14 +241,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             float qv[8];
             EL::unpack(kraw[r], kv[r]);
             EL::unpack(qraw[r], qv);
-            EL::store4(Ks + i * K_LD + d0, kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
-            EL::store4(Ks + i * K_LD + d0 + 4, kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
-            EL::store4(Qs + i * K_LD + d0, qv[0], qv[1], qv[2], qv[3]);
-            EL::store4(Qs + i * K_LD + d0 + 4, qv[4], qv[5], qv[6], qv[7]);
+            EL::store4(Ks + i * K_LD + EL::slot4(d0), kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
+            EL::store4(Ks + i * K_LD + EL::slot4(d0 + 4), kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
+            EL::store4(Qs + i * K_LD + EL::slot4(d0), qv[0], qv[1], qv[2], qv[3]);
+            EL::store4(Qs + i * K_LD + EL::slot4(d0 + 4), qv[4], qv[5], qv[6], qv[7]);
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            EL::store4(KTs + (d0 + e) * KT_LD + 4 * tg, kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
+            EL::store4(KTs + (d0 + e) * KT_LD + EL::slot4(4 * tg), kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
     }
     if (PREFETCH && nxt.u < total) fetch_kq(nxt);   // K and Q of the next item travel during the rest of this one
     __syncthreads();
@@ -311,37 +312,52 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int r = 0; r < 4; ++r) EL::unpack(vraw[r], vv[r]);
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            EL::store4(VTs + (d0v + e) * VT_LD + 4 * tgv, vv[0][e], vv[1][e], vv[2][e], vv[3][e]);
+            EL::store4(VTs + (d0v + e) * VT_LD + EL::slot4(4 * tgv), vv[0][e], vv[1][e], vv[2][e], vv[3][e]);
     }
     if (PREFETCH && nxt.u < total) fetch_v(nxt);    // V and the gates of the next item
 
-    // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks by forward
-    //      substitution, one per wave, column (lane & 15) of the inverse in registers.
+    // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks, one per
+    //      wave.  A strictly lower triangular 16x16 block D has D^16 = 0, so
+    //          (I + D)^-1 = (I + D^8)(I + D^4)(I + D^2)(I - D)
+    //      exactly: three squarings and three products on the matrix cores instead of a
+    //      sixteen-step substitution.  The running product stays in accumulators (it is always
+    //      the right operand); the powers pass through a wave-private LDS buffer (Q's region is
+    //      dead) to become left operands.
+    const int m16 = lane & 15, g4 = lane >> 4;
     {
-        const int base = 16 * wave, cc = lane & 15;
-        float x[16];
-        // the block's rows, fetched up front as 16-byte pieces (same address in every lane)
-        f32x4 lrow[16][4];
+        constexpr int PLD = 20;   // 16-byte aligned rows, no bank conflict between the four row groups
+        static_assert(4 * 3 * 16 * PLD * (int)sizeof(float) <= SM::B_BYTES, "power buffers fit in Q's region");
+        float* const D = Lf + (16 * wave) * LF_LD + 16 * wave;
+        float* const P2 = reinterpret_cast<float*>(smem + SM::B_OFF) + wave * 3 * 16 * PLD;
+        float* const P4 = P2 + 16 * PLD;
+        float* const P8 = P4 + 16 * PLD;
+        const f32x4 zero = {0, 0, 0, 0};
+        f32x4 d1, y;
 #pragma unroll
-        for (int r = 1; r < 16; ++r)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4)
-                if (4 * q4 < r) lrow[r][q4] = *reinterpret_cast<const f32x4*>(Lf + (base + r) * LF_LD + base + 4 * q4);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float s = (r == cc) ? 1.f : 0.f;
-#pragma unroll
-            for (int j = 0; j < r; ++j) s -= lrow[r][j >> 2][j & 3] * x[j];
-            x[r] = s;
+        for (int e = 0; e < 4; ++e) {
+            d1[e] = D[(4 * g4 + e) * LF_LD + m16];
+            y[e] = ((4 * g4 + e) == m16 ? 1.f : 0.f) - d1[e];
         }
-        if (lane < 16) {
+        const f32x4 d2 = mm16_lr<LF_LD>(zero, D, d1, m16, g4);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) Lf[(base + r) * LF_LD + base + cc] = x[r];
-        }
+        for (int e = 0; e < 4; ++e) P2[(4 * g4 + e) * PLD + m16] = d2[e];
+        __builtin_amdgcn_wave_barrier();
+        y = mm16_lr<PLD>(y, P2, y, m16, g4);
+        const f32x4 d4 = mm16_lr<PLD>(zero, P2, d2, m16, g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) P4[(4 * g4 + e) * PLD + m16] = d4[e];
+        __builtin_amdgcn_wave_barrier();
+        y = mm16_lr<PLD>(y, P4, y, m16, g4);
+        const f32x4 d8 = mm16_lr<PLD>(zero, P4, d4, m16, g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) P8[(4 * g4 + e) * PLD + m16] = d8[e];
+        __builtin_amdgcn_wave_barrier();
+        y = mm16_lr<PLD>(y, P8, y, m16, g4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[(4 * g4 + e) * LF_LD + m16] = y[e];
     }
     __syncthreads();  // diagonal blocks of T in place
 
-    const int m16 = lane & 15, g4 = lane >> 4;
     auto blk = [&](int br, int bc) -> const float* { return Lf + (16 * br) * LF_LD + 16 * bc; };
     // Stage 2: T_10 = -T_11 (L_10 T_00) on wave 0, T_32 = -T_33 (L_32 T_22) on wave 1.
     if (wave < 2) {
@@ -380,16 +396,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int i = tid >> 2, j0 = (tid & 3) * 16;
 #pragma unroll
         for (int jj = 0; jj < 16; jj += 4) {
-            float tb[4], tg[4];
+            float tb[4], tn[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int j = j0 + jj + e;
                 const float t = Lf[i * LF_LD + j] * bS[j];
                 tb[e] = t;
-                tg[e] = -t * gamS[j];
+                tn[e] = -t * gamS[j];
             }
-            EL::store4(Tb + i * T_LD + j0 + jj, tb[0], tb[1], tb[2], tb[3]);
-            EL::store4(Tbg + i * T_LD + j0 + jj, tg[0], tg[1], tg[2], tg[3]);
+            EL::store4(Tb + i * T_LD + EL::slot4(j0 + jj), tb[0], tb[1], tb[2], tb[3]);
+            EL::store4(Tbg + i * T_LD + EL::slot4(j0 + jj), tn[0], tn[1], tn[2], tn[3]);
         }
     }
     __syncthreads();
