@@ -176,6 +176,17 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
 int32_t gdn_profile_enable(int32_t on);
 int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls);
 
+/*
+ * Tuning knob (not a step of the method).  gdn_resume_prefill works through a call slab by
+ * slab: up to `rounds` consecutive 64-token chunks of every request are prepared, then
+ * consumed by the recurrence, then the next slab follows, the states carried in the workspace.
+ * rounds > 0 fixes the slab length for later gdn_workspace_bytes / gdn_resume_prefill calls
+ * (query the workspace size after setting it); rounds <= 0 restores the automatic choice.
+ * Results do not depend on it beyond rounding-order-free bookkeeping: outputs are bitwise
+ * the same for every setting.  Returns the previous setting (0 = automatic).
+ */
+int32_t gdn_tune_slab_rounds(int32_t rounds);
+
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);
 

@@ -50,6 +50,8 @@ def lib():
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2605_05219_amd.build)")
         L = ctypes.CDLL(LIB_PATH)
         L.gdn_version.restype = _i32
+        L.gdn_tune_slab_rounds.restype = _i32
+        L.gdn_tune_slab_rounds.argtypes = [_i32]
         L.gdn_profile_enable.restype = _i32
         L.gdn_profile_enable.argtypes = [_i32]
         L.gdn_profile_collect.restype = _i32
@@ -72,7 +74,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["gdn_version", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill"]
 
 
@@ -108,6 +110,11 @@ def make_shape(L, H_qk, H_v, d_k, d_v, in_dtype, o_dtype, T_alloc, scale=1.0) ->
 # ----------------------------------------------------------------------------- host-only entry points
 def gdn_version() -> int:
     return int(lib().gdn_version())
+
+
+def gdn_tune_slab_rounds(rounds: int) -> int:
+    """Fixes the slab length in chunk rounds (<= 0: automatic); returns the previous setting."""
+    return int(lib().gdn_tune_slab_rounds(int(rounds)))
 
 
 def gdn_profile_enable(on: bool) -> None:

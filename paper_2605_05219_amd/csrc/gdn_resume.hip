@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <mutex>
@@ -250,12 +251,10 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
 // Chunk rounds per slab.  The slab should stay cache resident between the preparation launch
 // that writes it and the recurrence launch that reads it back (budget), and a preparation
 // launch should fill the chip a whole number of times (512 = two of its workgroups on each of
-// the 256 compute units).  GDN_SLAB_ROUNDS overrides the choice.
+// the 256 compute units).  gdn_tune_slab_rounds overrides the choice.
+std::atomic<int32_t> g_forced_rounds{0};
 inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
-    static const int32_t forced = [] {
-        const char* e = std::getenv("GDN_SLAB_ROUNDS");
-        return e ? std::atoi(e) : 0;
-    }();
+    const int32_t forced = g_forced_rounds.load();
     if (forced > 0) return forced;
     const int64_t budget = nw == 1 ? (int64_t)96 << 20 : (int64_t)1 << 30;
     int64_t r = std::max<int64_t>(1, budget / std::max<int64_t>(1, n_chains * unit_bytes));
@@ -330,6 +329,10 @@ using namespace gdn;
 extern "C" {
 
 int32_t gdn_version(void) { return 100; }
+
+int32_t gdn_tune_slab_rounds(int32_t rounds) {
+    return g_forced_rounds.exchange(rounds > 0 ? rounds : 0);
+}
 
 int32_t gdn_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lock(g_prof.mu);

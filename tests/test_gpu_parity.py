@@ -153,6 +153,40 @@ def test_batch_sizes_cover_every_launch_shape(n_req):
     check_call(sc.resume, pool, TOL["bf16"])
 
 
+@pytest.mark.parametrize("n_req,dtype", [(1, "bf16"), (4, "bf16"), (32, "bf16"), (3, "f32")])
+@pytest.mark.parametrize("rounds", [1, 3])
+def test_short_slabs_carry_the_state_bitwise(n_req, dtype, rounds):
+    """Slabs of 1 or 3 chunk rounds: every recurrence variant hands its state from slab to slab
+    through the workspace; outputs and emitted states equal the automatic setting's bit for bit
+    (and so meet the oracle tolerance, checked on the forced run)."""
+    from paper_2605_05219_amd import binding as B
+    d = 128 if dtype == "bf16" else 64
+    H = 16 if dtype == "bf16" else 2
+    rng = np.random.default_rng(300 + n_req)
+    lens = [int(x) for x in rng.integers(1, 400, size=n_req)]
+    lens[0] = 333
+    starts = [int(x) for x in rng.integers(0, 50, size=n_req)]
+    n_slots = 2 * n_req + 2
+    pool = (rng.standard_normal((n_slots, 1, H, d, d)) * 0.5).astype(np.float32)
+    src = [(-1 if r % 3 == 0 else r % 2) for r in range(n_req)]
+    emits = [[starts[r] + lens[r]] if r % 2 == 0 else [] for r in range(n_req)]
+    emits[0] = [starts[0] + 100, starts[0] + 333]
+    per = [wl.token_streams(rng, 1, n, H, H, d, d, dtype, "slow") for n in lens]
+    slots, nxt = [], 2
+    for e in emits:
+        slots.append(list(range(nxt, nxt + len(e)))); nxt += len(e)
+    call = wl.pack_call(1, H, H, d, d, dtype, per, starts, src, emits, slots, n_slots)
+    o_auto, pool_auto = run_call_gpu(call, pool)
+    prev = B.gdn_tune_slab_rounds(rounds)
+    try:
+        o_forced, pool_forced = run_call_gpu(call, pool)
+        check_call(call, pool, TOL[dtype])
+    finally:
+        B.gdn_tune_slab_rounds(prev)
+    assert np.array_equal(o_auto, o_forced)
+    assert np.array_equal(pool_auto, pool_forced)
+
+
 def test_bf16_output_and_scale():
     sc = wl.config1(orc.deepest_ckpt, seed=5, n_draws=2, N=1024, M=4, H=4, d=128)
     pool, _, _ = fill_pool_from_oracle(sc)

@@ -220,3 +220,18 @@ def test_copy_argument_errors(monkeypatch, fn):
             f(pool, [-1, 1], other, 64)
         assert ei.value.code == -5
     f(pool, [], other, 64)                    # nothing to copy: fine, nothing enqueued
+
+
+def test_slab_rounds_knob_bounds_the_workspace():
+    """A shorter slab needs a smaller workspace; the knob returns the previous setting."""
+    shape = B.make_shape(1, 16, 16, 128, 128, "bf16", "f32", 8192)
+    auto = B.gdn_workspace_bytes(shape, 1, 8192, 16)
+    assert B.gdn_tune_slab_rounds(4) == 0
+    try:
+        small = B.gdn_workspace_bytes(shape, 1, 8192, 16)
+        assert B.gdn_tune_slab_rounds(8) == 4
+        mid = B.gdn_workspace_bytes(shape, 1, 8192, 16)
+    finally:
+        B.gdn_tune_slab_rounds(0)
+    assert 0 < small < mid < auto
+    assert B.gdn_workspace_bytes(shape, 1, 8192, 16) == auto
