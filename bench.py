@@ -34,6 +34,9 @@ FLOP_PREP = C * (6 * D + 2 * D)             # K K^T, K Q^T, W (each 2 C d_k) + U
 FLOP_RECUR = 6 * D * D + 2 * C * D          # W S^T, Q S^T, state update (2 d_k d_v each) + P U (2 C d_v)
 # algorithmic HBM bytes per token.head: q, k, v in bf16, beta, gate, o in fp32
 BYTES_TOKEN_HEAD = (2 * D + D) * 2 + 2 * 2 + D * 4
+# measured HBM bytes per token.head of each kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/)
+TRAFFIC_PREP = 805 + 1384      # read + written
+TRAFFIC_RECUR = 1416 + 647
 PEAK_MFMA_TFLOPS = 2500.0                   # dense fp16/bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
 
@@ -100,24 +103,24 @@ def main() -> int:
         torch.cuda.synchronize()
         tb = time.perf_counter()
         if not events:
-            return tb - ta, 0.0, 0.0
-        p_ms, r_ms, n_prof = B.gdn_profile_collect()
+            return tb - ta, 0.0, 0.0, 0, 0
+        p_ms, r_ms, n_prof, p_n, r_n = B.gdn_profile_collect()
         B.gdn_profile_enable(False)
         assert n_prof == args.steps
-        return tb - ta, p_ms, r_ms
+        return tb - ta, p_ms, r_ms, p_n, r_n
 
     # The timed region; the per-kernel durations come from HIP events the library records on the
     # launch stream between its kernels, by default in an immediate repeat of the same steps so
     # that the events' own cost stays out of `value`.
     events_wall = None
     if args.no_kernel_events:
-        wall_s, prep_ms, recur_ms = timed(False)
+        wall_s, prep_ms, recur_ms, prep_n, recur_n = timed(False)
     elif args.events_in_timed_region:
-        wall_s, prep_ms, recur_ms = timed(True)
+        wall_s, prep_ms, recur_ms, prep_n, recur_n = timed(True)
         events_wall = wall_s
     else:
-        wall_s, _, _ = timed(False)
-        events_wall, prep_ms, recur_ms = timed(True)
+        wall_s = timed(False)[0]
+        events_wall, prep_ms, recur_ms, prep_n, recur_n = timed(True)
 
     tokens = sum(suffix[i % N_DRAWS] for i in range(args.steps))
     wall = wall_s
@@ -150,22 +153,32 @@ def main() -> int:
     }
 
     if not args.no_kernel_events:
-        dom = "gdn_recur_kernel" if recur_ms >= prep_ms else "gdn_prep_kernel"
-        dom_ms = max(recur_ms, prep_ms)
-        dom_flop = FLOP_RECUR if recur_ms >= prep_ms else FLOP_PREP
-        achieved = token_heads * dom_flop / (dom_ms * 1e-3) / 1e12
+        # A step launches each kernel once per slab (64 chunk rounds here), so 1 to 3 times.
+        rec_dom = recur_ms >= prep_ms
+        dom = "gdn_recur_kernel" if rec_dom else "gdn_prep_kernel"
+        dom_ms, dom_n = (recur_ms, recur_n) if rec_dom else (prep_ms, prep_n)
+        dom_flop = FLOP_RECUR if rec_dom else FLOP_PREP
+        dom_traffic = TRAFFIC_RECUR if rec_dom else TRAFFIC_PREP
+        units_per_launch = token_heads / dom_n
+        achieved = units_per_launch * dom_flop / (dom_ms / dom_n * 1e-3) / 1e12
         out["roofline"] = {
             "bound": "mfma", "kernel": dom,
             "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / PEAK_MFMA_TFLOPS,
-            "traffic": None,
-            "avg_launch_ms": dom_ms / args.steps,
+            # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE per token.head of this build
+            # (profiles/, scaled by the copy-kernel calibration) x the token.heads of one launch
+            "traffic": None if dom_traffic is None else dom_traffic * units_per_launch,
+            "avg_launch_ms": dom_ms / dom_n,
+            "launches": dom_n,
+            "token_heads_per_launch": units_per_launch,
             "flop_per_token_head": dom_flop,
         }
         out["kernels"] = {
-            "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps,
+            "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps, "launches": prep_n,
+                                "avg_launch_ms": prep_ms / max(prep_n, 1),
                                 "tflops": token_heads * FLOP_PREP / (prep_ms * 1e-3) / 1e12},
-            "gdn_recur_kernel": {"avg_ms": recur_ms / args.steps,
+            "gdn_recur_kernel": {"avg_ms": recur_ms / args.steps, "launches": recur_n,
+                                 "avg_launch_ms": recur_ms / max(recur_n, 1),
                                  "tflops": token_heads * FLOP_RECUR / (recur_ms * 1e-3) / 1e12},
             "both_kernels_hbm_gbs_algorithmic": token_heads * BYTES_TOKEN_HEAD / ((prep_ms + recur_ms) * 1e-3) / 1e9,
             "events": "same steps, inside the timed region" if args.events_in_timed_region
@@ -211,17 +224,18 @@ def main() -> int:
         s0 = calls[0].call
         orc.resume_prefill(*s0.streams.slice(0, 64).fields(), [0, 64], [0], [-1], [0, 0], [])  # load + warm
         tc0 = time.perf_counter()
-        cpu_tokens = 0
-        for c in calls:
-            cc = c.call
+        cpu_tokens = cpu_calls = 0
+        while time.perf_counter() - tc0 < 10.0:      # about 10 s of CPU work, whole draws only
+            cc = calls[cpu_calls % N_DRAWS].call
             orc.resume_prefill(*cc.streams.fields(), cc.cu_seqlens, cc.start_pos, cc.src_slot, cc.emit_cu,
                                cc.emit_pos, state_src=pool_host)
             cpu_tokens += cc.total_tokens
+            cpu_calls += 1
         tc1 = time.perf_counter()
         out["cpu_baseline"] = {
             "value": cpu_tokens / (tc1 - tc0), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"all {N_DRAWS} draws of the same workload once ({cpu_tokens} suffix tokens x {HEADS} heads), "
-                      f"fp64 token loop, one (layer, head) chain per thread",
+            "sample": f"the same {N_DRAWS} draws cycled for about 10 s: {cpu_calls} requests, {cpu_tokens} suffix tokens "
+                      f"x {HEADS} heads; fp64 token loop, one (layer, head) chain per thread",
             "seconds": tc1 - tc0,
         }
 

@@ -167,14 +167,16 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
 
 /*
  * Per-kernel timing for benchmarks (not a step of the method).  While enabled, every
- * gdn_resume_prefill call records HIP events on its stream around its two kernels (chunk
- * preparation, chunk recurrence).  gdn_profile_enable(1) clears the totals and starts
- * recording, gdn_profile_enable(0) stops.  gdn_profile_collect waits (on the host) for the
- * recorded events and returns the summed kernel intervals in milliseconds and the number of
- * calls since recording started; any output pointer may be NULL.
+ * gdn_resume_prefill call records HIP events on its stream between its kernel launches (one
+ * chunk preparation and one chunk recurrence launch per slab).  gdn_profile_enable(1) clears
+ * the totals and starts recording, gdn_profile_enable(0) stops.  gdn_profile_collect waits (on
+ * the host) for the recorded events and returns, since recording started: the summed
+ * intervals per kernel in milliseconds, the number of calls, and the number of launches of
+ * each kernel; any output pointer may be NULL.
  */
 int32_t gdn_profile_enable(int32_t on);
-int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls);
+int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls,
+                            int64_t *prep_launches, int64_t *recur_launches);
 
 /*
  * Tuning knob (not a step of the method).  gdn_resume_prefill works through a call slab by

@@ -55,7 +55,7 @@ def lib():
         L.gdn_profile_enable.restype = _i32
         L.gdn_profile_enable.argtypes = [_i32]
         L.gdn_profile_collect.restype = _i32
-        L.gdn_profile_collect.argtypes = [_vp, _vp, _vp]
+        L.gdn_profile_collect.argtypes = [_vp, _vp, _vp, _vp, _vp]
         L.gdn_deepest_ckpt.restype = _i32
         L.gdn_deepest_ckpt.argtypes = [_vp, _i32, _i32]
         L.gdn_plan_chunks.restype = _i32
@@ -122,10 +122,12 @@ def gdn_profile_enable(on: bool) -> None:
 
 
 def gdn_profile_collect():
-    """(prep kernel ms, recurrence kernel ms, calls) summed since profiling was enabled."""
+    """(prep kernel ms, recurrence kernel ms, calls, prep launches, recurrence launches) since profiling was enabled."""
     a, b, n = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_int64(0)
-    _check(lib().gdn_profile_collect(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n)), "gdn_profile_collect")
-    return a.value, b.value, n.value
+    pl, rl = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().gdn_profile_collect(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n), ctypes.byref(pl), ctypes.byref(rl)),
+           "gdn_profile_collect")
+    return a.value, b.value, n.value, pl.value, rl.value
 
 
 def gdn_deepest_ckpt(pos: Sequence[int], t: int) -> int:

@@ -145,6 +145,7 @@ struct Profiler {
     std::vector<hipEvent_t> spare;
     std::vector<Mark> marks;
     double ms[2] = {0.0, 0.0};   // 0: preparation, 1: recurrence
+    int64_t launches[2] = {0, 0};
     int64_t calls = 0;
 
     hipEvent_t get() {
@@ -340,12 +341,14 @@ int32_t gdn_profile_enable(int32_t on) {
     if (on) {
         g_prof.recycle();
         g_prof.ms[0] = g_prof.ms[1] = 0.0;
+        g_prof.launches[0] = g_prof.launches[1] = 0;
         g_prof.calls = 0;
     }
     return GDN_OK;
 }
 
-int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls) {
+int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls, int64_t* prep_launches,
+                            int64_t* recur_launches) {
     std::lock_guard<std::mutex> lock(g_prof.mu);
     for (size_t i = 0; i < g_prof.marks.size(); ++i) {
         const Profiler::Mark& m = g_prof.marks[i];
@@ -356,11 +359,14 @@ int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls) {
         e = hipEventElapsedTime(&t, g_prof.marks[i - 1].ev, m.ev);
         if (e != hipSuccess) return hip_err(e);
         g_prof.ms[m.kind] += t;
+        g_prof.launches[m.kind] += 1;
     }
     g_prof.recycle();
     if (prep_ms) *prep_ms = g_prof.ms[0];
     if (recur_ms) *recur_ms = g_prof.ms[1];
     if (calls) *calls = g_prof.calls;
+    if (prep_launches) *prep_launches = g_prof.launches[0];
+    if (recur_launches) *recur_launches = g_prof.launches[1];
     return GDN_OK;
 }
 
