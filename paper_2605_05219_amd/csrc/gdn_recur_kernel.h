@@ -455,13 +455,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int eslot = reinterpret_cast<const int32_t*>(gamS + 2 * C)[AUX_EMIT_SLOT];
 
             // Everything below is laid out as short groups, one matrix instruction plus what is
-            // meant to execute in its shadow, separated by scheduling fences.
+            // meant to execute in its shadow, separated by scheduling fences.  The vector work
+            // (conversions, the decay of the state) is spread so that no group carries more than
+            // six such instructions.
             Frag sf[NKD], kf[MT * NKC], uf[NKC];
+            auto decay = [&](int mt, int r0, int r1) {
+#pragma unroll
+                for (int e = r0; e < r1; ++e) {
+                    float x = accS[mt][e] * gam_last;
+                    pin(x);
+                    accS[mt][e] = x;
+                }
+            };
             sf[0] = EL::from_acc(accS[0], 0);
             pin(sf[0]);
             GDN_FENCE();
             // ---- U token tile 0: state -> B fragments just ahead of their use, published to the
-            //      output wave; first half of the state's decay
+            //      output waves; decay of the first state tile (its fragments were taken first)
 #pragma unroll
             for (int k = 0; k < NKD; ++k) {
                 accU[0] = EL::mma(wf[k], sf[k], accU[0]);
@@ -470,25 +480,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     pin(sf[k + 1]);
                 }
                 xch[k * 64] = sf[k];
-#pragma unroll
-                for (int e = 0; e < RPS / 2; ++e) {
-                    float x = accS[k / SPT][(k % SPT) * RPS + e] * gam_last;
-                    pin(x);
-                    accS[k / SPT][(k % SPT) * RPS + e] = x;
-                }
+                decay(0, k * (16 / NKD), (k + 1) * (16 / NKD));
                 GDN_FENCE();
             }
-            // ---- U token tile 1: rest of the decay; K^T fragments are read;
+            // ---- U token tile 1: decay of the second state tile; K^T fragments are read;
             //      tile 0 of U is converted as soon as its last product has drained
 #pragma unroll
             for (int k = 0; k < NKD; ++k) {
                 accU[1] = EL::mma(wf[NKD + k], sf[k], accU[1]);
-#pragma unroll
-                for (int e = RPS / 2; e < RPS; ++e) {
-                    float x = accS[k / SPT][(k % SPT) * RPS + e] * gam_last;
-                    pin(x);
-                    accS[k / SPT][(k % SPT) * RPS + e] = x;
-                }
+                decay(1, k * (16 / NKD), (k + 1) * (16 / NKD));
 #pragma unroll
                 for (int j = 0; j < (MT * NKC) / NKD; ++j) kf[k * ((MT * NKC) / NKD) + j] = kt_img[(k * ((MT * NKC) / NKD) + j) * 64];
                 // conversion piece p of tile 0 at step 2 + p * stride (late enough for the data)
@@ -513,36 +513,39 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
                 GDN_FENCE();
             }
-            // ---- state update over the tokens of tile 0 (steps 0..SPT-1), with tile 1 of U
-            //      converted in its shadow
+            // ---- state update, one state tile after the other (all token steps of a tile back
+            //      to back).  First half of the tiles: tile 1 of U is converted under the first
+            //      products, the state tiles two further on are decayed.
 #pragma unroll
-            for (int s = 0; s < SPT; ++s) {
+            for (int mt = 0; mt < MT / 2; ++mt) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
+                for (int s = 0; s < NKC; ++s) {
                     accS[mt] = EL::mma(kf[mt * NKC + s], uf[s], accS[mt]);
-                    if (mt == 0) {
+                    if (mt == 0 && s < SPT) {
                         uf[SPT + s] = EL::from_acc(accU[1], s);
                         pin(uf[SPT + s]);
                         xch[(NKD + SPT + s) * 64] = uf[SPT + s];
                     }
+                    if (mt + 2 < MT) decay(mt + 2, s * (16 / NKC), (s + 1) * (16 / NKC));
                     GDN_FENCE();
                 }
             }
             __syncthreads();   // this chunk's fragments are published, its ring stage is released,
                                // the next chunk's stage has landed
-            // ---- state update over the tokens of tile 1, the next chunk's W fragments and U~
-            //      being read in its shadow
+            // ---- second half of the state tiles, the next chunk's W fragments and U~ being read
+            //      in their shadow
             {
                 const Frag* w_ = reinterpret_cast<const Frag*>(st_next + U::W_OFF) + lane;
                 const f32x4* ut_ = reinterpret_cast<const f32x4*>(st_next + SM::UT_OFF) + lane;
-                constexpr int NM = SPT * MT;                      // matrix instructions left
+                constexpr int NM = (MT - MT / 2) * NKC;           // matrix instructions left
                 constexpr int WPM = (2 * NKD + NM - 1) / NM;      // W fragments read per instruction
                 int m = 0;
 #pragma unroll
-                for (int s = SPT; s < 2 * SPT; ++s)
+                for (int mt = MT / 2; mt < MT; ++mt)
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt, ++m) {
+                    for (int s = 0; s < NKC; ++s, ++m) {
                         accS[mt] = EL::mma(kf[mt * NKC + s], uf[s], accS[mt]);
+                        if (mt + 2 < MT) decay(mt + 2, s * (16 / NKC), (s + 1) * (16 / NKC));
 #pragma unroll
                         for (int j = 0; j < WPM; ++j)
                             if (m * WPM + j < 2 * NKD) wf[m * WPM + j] = w_[(m * WPM + j) * 64];
