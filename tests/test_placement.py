@@ -1,0 +1,153 @@
+"""The placement layer of the library (include/ckpt_place.h) against the placement oracle.
+Integer outputs (positions of the fixed strategies, clipping) bit-exact; the dynamic program's
+minimum within 1e-12 of the oracle's O(N^2 M) recurrence, its positions checked for validity and
+for attaining that minimum (several sets can be optimal).  CPU only."""
+import ctypes
+import math
+import os
+import re
+import time
+
+import numpy as np
+import pytest
+
+from oracle import placement_oracle as po
+from paper_2605_05219_amd import binding as B, placement as P
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+ERR = {name: code for code, name in B.ERRORS.items()}
+
+
+def test_library_exports_every_symbol_the_placement_header_declares():
+    header = open(os.path.join(ROOT, "include", "ckpt_place.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ckpt_\w+)\s*\(", header))
+    assert declared == set(P.EXPORTS)
+    L = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+@pytest.mark.parametrize("N,M,Bk", [(1, 1, 1), (10, 3, 4), (512, 3, 128), (8192, 16, 128), (1000, 7, 64), (33000, 12, 128)])
+def test_fixed_strategies_bit_exact(N, M, Bk):
+    assert P.ckpt_place_balanced(N, M) == po.balanced(N, M)
+    assert P.ckpt_place_block(N, Bk) == po.block(N, Bk)
+    assert P.ckpt_place_sqrt(N) == po.sqrt_spaced(N)
+    assert P.ckpt_place_log(N, Bk, M) == po.logarithmic(N, Bk, M)
+    assert P.ckpt_place_log(N, 1, 40) == po.logarithmic(N, 1, 40)
+    raw = sorted(set(np.random.default_rng(N).integers(1, N + 1, size=M).tolist()))
+    assert P.ckpt_clip_to_blocks(raw, Bk) == po.clip_to_blocks(raw, Bk)
+    assert P.ckpt_clip_to_blocks(po.balanced(N, M), Bk) == po.clip_to_blocks(po.balanced(N, M), Bk)
+
+
+def depth_laws(rng, N):
+    """Overlap laws shaped like the paper's workloads: uniform, a spike near the full length,
+    a concentrated non-uniform mixture, sparse support (many zero masses)."""
+    t = np.arange(1, N + 1)
+    spike = np.exp(-(N - t) / max(N / 20, 1.0))
+    mix = 0.5 * (t > 0.73 * N) / max((t > 0.73 * N).sum(), 1) + 0.5 / N
+    sparse = np.zeros(N); sparse[rng.choice(N, size=max(N // 6, 1), replace=False)] = rng.random(max(N // 6, 1))
+    return {"uniform": np.full(N, 1.0 / N), "spike": spike / spike.sum(), "mixture": mix / mix.sum(),
+            "sparse": sparse / sparse.sum(), "random": (lambda x: x / x.sum())(rng.random(N) ** 4)}
+
+
+@pytest.mark.parametrize("N,M", [(1, 1), (7, 2), (40, 3), (150, 8), (150, 0), (9, 9), (60, 70)])
+def test_dp_and_metrics_match_the_oracle(N, M):
+    rng = np.random.default_rng(N * 100 + M)
+    for name, p in depth_laws(rng, N).items():
+        ref_cost, _ = po.dp_optimal(p, min(M, N))
+        cost, pos = P.ckpt_place_dp(p, M)
+        scale = max(po.no_cache_cost(p), 1e-300)
+        assert abs(cost - ref_cost) <= 1e-12 * scale, (name, cost, ref_cost)
+        assert len(pos) <= M and pos == sorted(set(pos)) and all(1 <= c <= N for c in pos)
+        assert abs(po.expected_recompute(p, pos) - ref_cost) <= 1e-12 * scale, name   # the set attains the minimum
+        e, rnc, sav, red = P.ckpt_expected_recompute(p, pos)
+        assert e == pytest.approx(po.expected_recompute(p, pos), rel=1e-13, abs=1e-15)
+        assert rnc == pytest.approx(po.no_cache_cost(p), rel=1e-13)
+        assert sav == pytest.approx(1.0 - e / rnc, rel=1e-13, abs=1e-15)
+        assert red == (math.inf if e == 0.0 else pytest.approx(rnc / e, rel=1e-13))
+        for base in (po.balanced(N, min(M, N)), po.sqrt_spaced(N)[:M]):
+            assert cost <= po.expected_recompute(p, base) + 1e-12 * scale
+
+
+def test_dp_at_full_size_hits_theorem1_and_runs_in_linear_time_per_layer():
+    N, M = 32768, 32
+    p = np.full(N, 1.0 / N)
+    t0 = time.perf_counter()
+    cost, pos = P.ckpt_place_dp(p, M)
+    dt = time.perf_counter() - t0
+    K = M + 1
+    q, rho = divmod(N + 1, K)
+    closed = ((K - rho) * q * (q - 1) / 2 + rho * q * (q + 1) / 2) / N       # Theorem 1
+    assert cost == pytest.approx(closed, rel=1e-10)
+    gaps = np.diff([0] + pos + [N + 1])
+    assert len(pos) == M and gaps.max() - gaps.min() <= 1                    # optimal iff balanced
+    assert dt < 2.0                                                          # O(N M): about a million line operations
+
+
+def test_argument_errors():
+    p = np.full(8, 0.125)
+    for call, code in ((lambda: P.ckpt_place_balanced(4, 5), ERR["GDN_ERR_COUNT"]),
+                       (lambda: P.ckpt_place_block(0, 4), ERR["GDN_ERR_COUNT"]),
+                       (lambda: P.ckpt_expected_recompute(p, [3, 3]), ERR["GDN_ERR_EMIT"]),
+                       (lambda: P.ckpt_expected_recompute(p, [9]), ERR["GDN_ERR_EMIT"]),
+                       (lambda: P.ckpt_place_dp(-p, 2), ERR["GDN_ERR_COUNT"]),
+                       (lambda: P.ckpt_clip_to_blocks([4, 2], 2), ERR["GDN_ERR_EMIT"])):
+        with pytest.raises(B.GdnError) as e:
+            call()
+        assert e.value.code == code
+    with pytest.raises(ValueError):
+        P.OverlapHistogram(0)
+    with pytest.raises(ValueError):
+        P.OverlapHistogram(8, 1.5)
+
+
+@pytest.mark.parametrize("gamma", [1.0, 0.99, 0.5])
+def test_exponentially_weighted_histogram_is_the_formula(gamma):
+    """p^ = (1-g)/(1-g^n) sum_s g^(n-s) e_{T_s} (Theorem 4's estimator), written out."""
+    rng = np.random.default_rng(5)
+    N, n = 50, 3000
+    obs = rng.integers(1, N + 1, size=n)
+    h = P.OverlapHistogram(N, gamma)
+    assert np.all(h.get() == 0.0)
+    for i, t in enumerate(obs):
+        assert h.observe(int(t)) == i + 1
+    w = gamma ** np.arange(n - 1, -1, -1, dtype=np.float64)
+    ref = np.zeros(N)
+    np.add.at(ref, obs - 1, w)
+    ref /= w.sum()
+    got = h.get()
+    assert np.allclose(got, ref, rtol=1e-10, atol=1e-300)
+    assert got.sum() == pytest.approx(1.0, rel=1e-12)
+    cost, pos = h.solve(4)
+    ref_cost, _ = po.dp_optimal(ref, 4)
+    assert cost == pytest.approx(ref_cost, rel=1e-9)
+    _, clipped = h.solve(4, 8)
+    assert clipped == po.clip_to_blocks(pos, 8)
+    h.close()
+
+
+def test_histogram_tracks_a_drifting_law_and_the_schedule_follows():
+    """Stationary then shifted overlap law: with gamma = 0.99 and a re-solve every 10 requests
+    (the paper's setting) the schedule's cost under the CURRENT law comes close to that law's
+    optimum again a few hundred requests after the shift, while the plain empirical histogram
+    keeps serving the old law; the plug-in cost never exceeds the stability bound."""
+    rng = np.random.default_rng(11)
+    N, M = 256, 6
+    t = np.arange(1, N + 1)
+    law_a = np.exp(-0.5 * ((t - 60) / 12.0) ** 2); law_a /= law_a.sum()
+    law_b = np.exp(-0.5 * ((t - 200) / 12.0) ** 2); law_b /= law_b.sum()
+    ew, emp = P.OverlapHistogram(N, 0.99), P.OverlapHistogram(N, 1.0)
+    pos_ew = pos_emp = []
+    for i in range(2000):
+        law = law_a if i < 1200 else law_b
+        d = int(rng.choice(t, p=law))
+        ew.observe(d); emp.observe(d)
+        if (i + 1) % 10 == 0:
+            pos_ew, pos_emp = ew.solve(M)[1], emp.solve(M)[1]
+    best = po.dp_optimal(law_b, M)[0]
+    cost_ew = po.expected_recompute(law_b, pos_ew)
+    cost_emp = po.expected_recompute(law_b, pos_emp)
+    assert cost_ew <= best + 2 * N * np.abs(ew.get() - law_b).sum() + 1e-9      # Lemma 1 applied twice
+    assert cost_ew < 2.0 * best + 1.0
+    assert cost_emp > cost_ew                                                  # the unweighted estimate lags
