@@ -217,6 +217,36 @@ def main() -> int:
     except Exception as exc:  # the copies are a side measurement; never lose the main line
         out["ckpt_copy"] = {"error": str(exc)}
 
+    # ---- decode step (one token per request, states updated in place): 1024 requests x 16 heads, HBM bound
+    try:
+        n_dec = 1024                # 1 GiB of states: four times the memory-side cache
+        dpool = torch.randn((n_dec, 1, HEADS, D, D), dtype=torch.float32, device=dev) * 0.1
+        dshape = B.make_shape(1, HEADS, HEADS, D, D, "bf16", "f32", n_dec)
+        dq = torch.nn.functional.normalize(torch.randn((1, n_dec, HEADS, D), device=dev), dim=-1).bfloat16()
+        dk = torch.nn.functional.normalize(torch.randn((1, n_dec, HEADS, D), device=dev), dim=-1).bfloat16()
+        dv = torch.randn((1, n_dec, HEADS, D), device=dev).bfloat16()
+        db = torch.sigmoid(torch.randn((1, n_dec, HEADS), device=dev)).bfloat16()
+        dg = torch.exp(-torch.nn.functional.softplus(torch.randn((1, n_dec, HEADS), device=dev))).bfloat16()
+        do = torch.empty((1, n_dec, HEADS, D), dtype=torch.float32, device=dev)
+        dslots = np.arange(n_dec, dtype=np.int32)
+        for _ in range(3):
+            B.gdn_decode_step(dshape, dq, dk, dv, db, dg, dpool, dslots, do)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = 20
+        ev[0].record()
+        for _ in range(reps):
+            B.gdn_decode_step(dshape, dq, dk, dv, db, dg, dpool, dslots, do)
+        ev[1].record()
+        torch.cuda.synchronize()
+        dbytes = 2.0 * n_dec * HEADS * D * D * 4
+        dms = ev[0].elapsed_time(ev[1]) / reps
+        out["decode_step"] = {"requests": n_dec, "state_bytes_read_and_written": dbytes, "ms": dms,
+                              "gbs": dbytes / (dms * 1e-3) / 1e9, "peak_gbs": PEAK_HBM_GBS,
+                              "tokens_per_s": n_dec / (dms * 1e-3)}
+        del dpool
+    except Exception as exc:
+        out["decode_step"] = {"error": str(exc)}
+
     # ---- the oracle on the host cores, same workload (all draws once)
     if not args.no_cpu_baseline:
         from oracle import gdn_oracle as orc

@@ -166,6 +166,27 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
                            void *o, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * Decode step: one new token per request, the recurrent state updated IN PLACE in its pool
+ * slot (same state layout as gdn_resume_prefill; the update is the one-token case of the same
+ * recurrence, Sec. 1: a recurrent layer needs only its latest state to go on):
+ *     S~ = a S;  u = b (v - S~ k);  S = S~ + u k^T;  o = scale * S q     per (request, layer, value head)
+ *   shape       as for gdn_resume_prefill; T_alloc = token rows allocated per layer (>= n_req)
+ *   q, k        device [L][T_alloc][H_qk][d_k];  v device [L][T_alloc][H_v][d_v]
+ *   beta, gate  device [L][T_alloc][H_v];  row r of every tensor is request r's token
+ *   pool        device fp32, slot s at pool + s * slot_stride (floats), read and written
+ *   slot        host int32 [n_req] in [0, n_slots), all distinct (two requests may not share a state)
+ *   o           device [L][T_alloc][H_v][d_v] in shape->o_dtype, rows 0..n_req-1 written
+ * All arithmetic is fp32 on the exactly widened inputs.  Errors as for gdn_resume_prefill
+ * (GDN_ERR_SLOT_RANGE, GDN_ERR_SLOT_DUP, GDN_ERR_SEQLENS when n_req > T_alloc, ...); nothing is
+ * enqueued when an error is returned.
+ */
+int32_t gdn_decode_step(const gdn_shape *shape,
+                        const void *q, const void *k, const void *v,
+                        const void *beta, const void *gate, int32_t n_req,
+                        float *pool, int64_t slot_stride, int32_t n_slots, const int32_t *slot,
+                        void *o, void *stream);
+
+/*
  * Per-kernel timing for benchmarks (not a step of the method).  While enabled, every
  * gdn_resume_prefill call records HIP events on its stream between its kernel launches (one
  * chunk preparation and one chunk recurrence launch per slab).  gdn_profile_enable(1) clears

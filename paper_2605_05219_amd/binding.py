@@ -66,6 +66,8 @@ def lib():
         L.ckpt_gather.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
         L.ckpt_scatter.restype = _i32
         L.ckpt_scatter.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
+        L.gdn_decode_step.restype = _i32
+        L.gdn_decode_step.argtypes = [ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _i64, _i32, _vp, _vp, _vp]
         L.gdn_resume_prefill.restype = _i32
         L.gdn_resume_prefill.argtypes = ([ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _vp]
                                          + [_vp, _i64, _i32, _vp] + [_vp, _vp]
@@ -75,7 +77,7 @@ def lib():
 
 
 EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
-           "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill"]
+           "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step"]
 
 
 def _h32(x) -> np.ndarray:
@@ -196,3 +198,13 @@ def gdn_resume_prefill(shape: gdn_shape, q, k, v, beta, gate, cu_seqlens, start_
                                     _dp(state_dst), dst_stride, dst_n, _hp(eslot),
                                     _dp(o), _dp(workspace), ws_bytes, _stream_ptr(stream)),
            "gdn_resume_prefill")
+
+
+def gdn_decode_step(shape: gdn_shape, q, k, v, beta, gate, pool, slot, o, stream=None) -> None:
+    """See include/gdn_resume.h: one token per request, states updated in place in their pool slots."""
+    sl = _h32(slot)
+    n_req = int(sl.size)
+    _check(lib().gdn_decode_step(ctypes.byref(shape), _dp(q), _dp(k), _dp(v), _dp(beta), _dp(gate), n_req,
+                                 _dp(pool), int(pool.stride(0)) if pool is not None else 0,
+                                 int(pool.shape[0]) if pool is not None else 0, _hp(sl), _dp(o), _stream_ptr(stream)),
+           "gdn_decode_step")

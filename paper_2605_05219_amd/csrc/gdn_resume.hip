@@ -10,6 +10,7 @@
 
 #include "gdn_plan.h"
 #include "gdn_prep_kernel.h"
+#include "gdn_decode_kernel.h"
 #include "gdn_recur_kernel.h"
 #include "gdn_resume.h"
 
@@ -549,6 +550,50 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
     if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
     return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, stream);
+}
+
+int32_t gdn_decode_step(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                        const void* gate, int32_t n_req, float* pool, int64_t slot_stride, int32_t n_slots,
+                        const int32_t* slot, void* o, void* stream_) {
+    int32_t rc = check_shape(shape);
+    if (rc != GDN_OK) return rc;
+    const gdn_shape& s = *shape;
+    if (n_req < 0 || n_slots < 0) return GDN_ERR_COUNT;
+    if (n_req == 0) return GDN_OK;
+    if (n_req > s.T_alloc) return GDN_ERR_SEQLENS;
+    if (!q || !k || !v || !beta || !gate || !pool || !slot || !o) return GDN_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(pool) || (slot_stride & 3))
+        return GDN_ERR_ALIGN;
+    const int64_t slot_elems = (int64_t)s.L * s.H_v * s.d_v * s.d_k;
+    if (slot_stride < slot_elems) return GDN_ERR_SHAPE;
+    {
+        std::vector<int32_t> sorted(slot, slot + n_req);
+        std::sort(sorted.begin(), sorted.end());
+        if (sorted.front() < 0 || sorted.back() >= n_slots) return GDN_ERR_SLOT_RANGE;
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return GDN_ERR_SLOT_DUP;
+    }
+    hipStream_t stream = (hipStream_t)stream_;
+    DecodeArgs a;
+    a.q = q; a.k = k; a.v = v; a.beta = beta; a.gate = gate;
+    a.pool = pool; a.o = o;
+    a.slot_stride = slot_stride; a.T_alloc = s.T_alloc;
+    a.L = s.L; a.H_qk = s.H_qk; a.H_v = s.H_v;
+    a.scale = s.scale;
+    a.o_bf16 = s.o_dtype == GDN_BF16;
+    for (int32_t base = 0; base < n_req; base += DECODE_IDS) {
+        const int32_t m = std::min(DECODE_IDS, n_req - base);
+        DecodeIds ids;
+        std::memset(&ids, 0, sizeof ids);
+        std::memcpy(ids.slot, slot + base, sizeof(int32_t) * m);
+        a.req_base = base;
+        const dim3 grid((unsigned)(s.d_v / 32), (unsigned)(s.L * s.H_v), (unsigned)m);
+        if (s.in_dtype == GDN_F32) hipLaunchKernelGGL((gdn_decode_kernel<float, 64, 64>), grid, dim3(256), 0, stream, a, ids);
+        else if (s.d_k == 64) hipLaunchKernelGGL((gdn_decode_kernel<half_t, 64, 64>), grid, dim3(256), 0, stream, a, ids);
+        else hipLaunchKernelGGL((gdn_decode_kernel<half_t, 128, 128>), grid, dim3(256), 0, stream, a, ids);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_err(e);
+    }
+    return GDN_OK;
 }
 
 }  // extern "C"

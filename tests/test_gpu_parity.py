@@ -266,3 +266,56 @@ def test_config4_shape_reduced_layer_group():
     call = wl.config4_call(n_req=24, L=3, H=4, n_slots=160, lo=64, hi=1500, emit_step=512)
     pool = (rng.standard_normal((call.n_slots,) + call.slot_shape) * 0.5).astype(np.float32)
     check_call(call, pool, TOL["bf16"])
+
+
+# ------------------------------------------------------------------ decode step
+def decode_streams(rng, L, n_req, H_qk, H_v, d, dtype, gate_mode):
+    return wl.token_streams(rng, L, n_req, H_qk, H_v, d, d, dtype, gate_mode)
+
+
+@pytest.mark.parametrize("d,H_qk,H_v,L,dtype,n_req", [
+    (128, 2, 2, 1, "bf16", 1), (128, 2, 2, 1, "bf16", 5), (128, 2, 2, 1, "bf16", 300),      # 300: two launches
+    (64, 2, 4, 2, "bf16", 1), (64, 2, 4, 2, "bf16", 5), (64, 2, 4, 2, "bf16", 300),
+    (64, 2, 2, 1, "f32", 1), (64, 2, 2, 1, "f32", 5), (64, 2, 2, 1, "f32", 300),
+    (128, 4, 8, 1, "bf16", 1), (128, 4, 8, 1, "bf16", 5)])
+def test_decode_step_matches_the_token_loop(d, H_qk, H_v, L, dtype, n_req):
+    """Two decode steps in a row (the second reads the states the first wrote in place) against
+    the oracle's token loop run over both tokens; fp32 arithmetic on exactly widened inputs,
+    so the fp32 tolerance holds for bf16 inputs too.  Slots not named are untouched."""
+    import torch
+    from paper_2605_05219_amd import binding as B
+    from tests.harness import to_device
+    rng = np.random.default_rng(900 + d + H_v + n_req)
+    n_slots = n_req + 3
+    pool = (rng.standard_normal((n_slots, L, H_v, d, d)) * 0.5).astype(np.float32)
+    slots = rng.permutation(n_slots)[:n_req].astype(np.int32)
+    steps = [decode_streams(rng, L, n_req, H_qk, H_v, d, dtype, "slow") for _ in range(2)]
+    # oracle: request r = tokens (step 0, step 1) of row r, starting from its slot, state emitted after both
+    per = []
+    for r in range(n_req):
+        a, b = steps[0].slice(r, r + 1), steps[1].slice(r, r + 1)
+        per.append(wl.concat_streams([a, b]))
+    call = wl.pack_call(L, H_qk, H_v, d, d, dtype, per, [0] * n_req, [int(s) for s in slots],
+                        [[2]] * n_req, [[int(s)] for s in slots], n_slots)
+    o_ref, st_ref = orc.resume_prefill(*call.streams.fields(), call.cu_seqlens, call.start_pos, call.src_slot,
+                                       call.emit_cu, call.emit_pos, state_src=pool, scale=0.5)
+    dpool = torch.from_numpy(pool.copy()).cuda()
+    shape = B.make_shape(L, H_qk, H_v, d, d, dtype, "f32", n_req, 0.5)
+    outs = []
+    for st in steps:
+        q, k, v, beta, gate = (to_device(np.ascontiguousarray(x)) for x in st.fields())
+        o = torch.full((L, n_req, H_v, d), float("nan"), dtype=torch.float32, device="cuda")
+        B.gdn_decode_step(shape, q, k, v, beta, gate, dpool, slots, o)
+        torch.cuda.synchronize()
+        outs.append(o.cpu().numpy())
+    after = dpool.cpu().numpy()
+    o_ref = o_ref[:, :2 * n_req].reshape(L, n_req, 2, H_v, d)
+    for t in range(2):
+        assert not np.isnan(outs[t]).any()
+        assert max_norm_err(outs[t], o_ref[:, :, t]) <= TOL["f32"]
+    named = set(int(s) for s in slots)
+    for e, s in enumerate(call.emit_slot):
+        assert max_norm_err(after[s], st_ref[e]) <= TOL["f32"]
+    for s in range(n_slots):
+        if s not in named:
+            assert np.array_equal(after[s], pool[s])

@@ -235,3 +235,26 @@ def test_slab_rounds_knob_bounds_the_workspace():
         B.gdn_tune_slab_rounds(0)
     assert 0 < small < mid < auto
     assert B.gdn_workspace_bytes(shape, 1, 8192, 16) == auto
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(slot=[0, 0]), -6),                                   # two requests share a state
+    (dict(slot=[0, 8]), -5),
+    (dict(slot=[-1, 1]), -5),
+    (dict(q=FakeDev(ptr=0)), -1),
+    (dict(o=FakeDev(ptr=0x10004)), -2),
+    (dict(pool=FakeDev(stride0=2 * 64 * 64 - 4)), -3),
+    (dict(pool=FakeDev(stride0=2 * 64 * 64 + 2)), -2),
+    (dict(slot=[0, 1, 2], T_alloc=2), -4),                      # more requests than token rows
+])
+def test_decode_argument_errors(monkeypatch, over, code):
+    """Every check of gdn_decode_step fires on the host, before anything is enqueued."""
+    monkeypatch.setattr(B, "_stream_ptr", lambda s=None: ctypes.c_void_p(0))
+    d = FakeDev()
+    args = dict(q=d, k=d, v=d, beta=d, gate=d, pool=FakeDev(), slot=[0, 1], o=d, T_alloc=4)
+    args.update(over)
+    shape = B.make_shape(1, 2, 2, 64, 64, "f32", "f32", args.pop("T_alloc"))
+    with pytest.raises(B.GdnError) as ei:
+        B.gdn_decode_step(shape, args["q"], args["k"], args["v"], args["beta"], args["gate"], args["pool"], args["slot"],
+                          args["o"], ctypes.c_void_p(0))
+    assert ei.value.code == code
