@@ -187,6 +187,30 @@ def main() -> int:
             "other_ms_per_step_with_events": 1e3 * events_wall / args.steps - (prep_ms + recur_ms) / args.steps,
         }
 
+    # ---- latency against suffix length (Sec. 6, overhead decomposition: the resume cost is a small constant
+    #      for loading the checkpoint plus a term linear in the replayed suffix): every draw timed on its own
+    try:
+        per_draw = []
+        for i in range(N_DRAWS):
+            for _ in range(2):
+                step(i)
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            for _ in range(8):
+                step(i)
+            torch.cuda.synchronize()
+            per_draw.append((suffix[i], 1e3 * (time.perf_counter() - ta) / 8))
+        xs = np.array([p_[0] / C for p_ in per_draw], dtype=np.float64)
+        ys = np.array([p_[1] for p_ in per_draw], dtype=np.float64)
+        slope, offset = np.polyfit(xs, ys, 1)
+        out["latency_vs_suffix"] = {
+            "suffix_tokens_ms": sorted(set((int(a), round(float(b), 5)) for a, b in per_draw)),
+            "fit_ms": {"per_chunk_step": float(slope), "offset": float(offset)},
+            "note": "whole call (planning, upload, every launch), 8 back-to-back calls per draw; chunk step = 64 tokens",
+        }
+    except Exception as exc:
+        out["latency_vs_suffix"] = {"error": str(exc)}
+
     # ---- standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB each way
     try:
         n_copy, elems = 256, HEADS * D * D
