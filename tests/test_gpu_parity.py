@@ -319,3 +319,60 @@ def test_decode_step_matches_the_token_loop(d, H_qk, H_v, L, dtype, n_req):
     for s in range(n_slots):
         if s not in named:
             assert np.array_equal(after[s], pool[s])
+
+
+# ------------------------------------------------------------------ full-size configs, sampled requests
+def check_call_sampled(call, pool, tol, sample):
+    """GPU runs the whole call; the oracle replays only the sampled requests (same tokens, start
+    states and emit lists) and those requests' outputs and emitted states are compared."""
+    o, pool_after = run_call_gpu(call, pool)
+    assert not np.isnan(o[:, :call.total_tokens]).any(), "an output row was never written"
+    for r in sample:
+        lo, hi = int(call.cu_seqlens[r]), int(call.cu_seqlens[r + 1])
+        e0, e1 = int(call.emit_cu[r]), int(call.emit_cu[r + 1])
+        sub = wl.pack_call(call.L, call.H_qk, call.H_v, call.d_k, call.d_v, call.dtype, [call.streams.slice(lo, hi)],
+                           [int(call.start_pos[r])], [int(call.src_slot[r])], [list(call.emit_pos[e0:e1])],
+                           [list(call.emit_slot[e0:e1])], pool.shape[0])
+        o_ref, st_ref = orc.resume_prefill(*sub.streams.fields(), sub.cu_seqlens, sub.start_pos, sub.src_slot,
+                                           sub.emit_cu, sub.emit_pos, state_src=pool)
+        if hi > lo:
+            err = max_norm_err(o[:, lo:hi], o_ref[:, :hi - lo])
+            assert err <= tol, f"request {r} ({hi - lo} tokens): o error {err:.3e} > {tol}"
+        for e in range(e1 - e0):
+            s = int(call.emit_slot[e0 + e])
+            err = max_norm_err(pool_after[s], st_ref[e])
+            assert err <= tol, f"request {r}: emitted state {e} (slot {s}) error {err:.3e} > {tol}"
+    dst = set(int(s) for s in call.emit_slot)
+    for s in range(pool.shape[0]):
+        if s not in dst:
+            assert np.array_equal(pool_after[s], pool[s]), f"slot {s} changed but was not a destination"
+
+
+def sample_requests(call, k, rng):
+    lens = np.diff(call.cu_seqlens)
+    picks = {int(np.argmax(lens)), int(np.argmin(lens))}
+    picks.update(int(x) for x in rng.choice(call.n_req, size=min(k, call.n_req), replace=False))
+    return sorted(picks)
+
+
+def test_config2_full_size_sampled_requests():
+    """configs[2] as specified (64 requests, N = 16384, M = 12, 16 heads, d = 128): 1024 chains,
+    several slabs in the throughput variant.  Start states are seeded random states (any state
+    is a valid resume point); six requests, the longest and the shortest among them, are
+    checked element by element."""
+    rng = np.random.default_rng(2002)
+    sc = wl.config2(orc.deepest_ckpt)
+    pool = (rng.standard_normal((sc.n_slots,) + sc.build.slot_shape) * 0.3).astype(np.float32)
+    check_call_sampled(sc.resume, pool, TOL["bf16"], sample_requests(sc.resume, 4, rng))
+
+
+def test_config3_full_shape_sampled_requests():
+    """configs[3]'s shape (N = 32768, 16 query/key heads shared by 32 value heads, M = 8) at half
+    its batch (16 requests; generating the inputs on the host dominates the test's time):
+    heavily imbalanced chain lengths, the longest and the shortest requests are checked."""
+    rng = np.random.default_rng(2003)
+    sc = wl.config3(orc.deepest_ckpt, n_req=16)
+    pool = (rng.standard_normal((sc.n_slots,) + sc.build.slot_shape) * 0.3).astype(np.float32)
+    lens = np.diff(sc.resume.cu_seqlens)
+    short = [int(i) for i in np.argsort(lens)[:3]]
+    check_call_sampled(sc.resume, pool, TOL["bf16"], sorted(set(short + [int(np.argmax(lens))])))
