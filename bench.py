@@ -241,6 +241,49 @@ def main() -> int:
     except Exception as exc:  # the copies are a side measurement; never lose the main line
         out["ckpt_copy"] = {"error": str(exc)}
 
+    # ---- host tier (Sec. 6: loading the stored checkpoint from host memory is overhead (i) of a hit): the same
+    #      draws with the checkpoint pool in pinned host memory, and the raw host -> HBM state copy rate
+    try:
+        host_pool = pool.cpu().pin_memory()
+        ws_host = torch.empty(max(B.gdn_workspace_bytes_host(c.shape, 1, c.call.total_tokens, int(c.call.emit_pos.size))
+                                  for c in calls), dtype=torch.uint8, device=dev)
+
+        def host_step(i):
+            c = calls[i % N_DRAWS]
+            cc = c.call
+            B.gdn_resume_prefill_host(c.shape, c.q, c.k, c.v, c.beta, c.gate, cc.cu_seqlens, cc.start_pos, host_pool,
+                                      cc.src_slot, cc.emit_cu, cc.emit_pos, pool, cc.emit_slot, c.o, ws_host)
+        for i in range(N_DRAWS):
+            host_step(i)
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for i in range(args.steps):
+            host_step(i)
+        torch.cuda.synchronize()
+        host_ms = 1e3 * (time.perf_counter() - ta) / args.steps
+        n_f = 64
+        stage_f = torch.empty((n_f,) + tuple(pool.shape[1:]), dtype=torch.float32, device=dev)
+        big_host = torch.randn((n_f,) + tuple(pool.shape[1:]), dtype=torch.float32).pin_memory()
+        ids_f = np.arange(n_f, dtype=np.int32)
+        B.ckpt_fetch_host(big_host, ids_f, stage_f, ids_f)
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for _ in range(4):
+            B.ckpt_fetch_host(big_host, ids_f, stage_f, ids_f)
+        torch.cuda.synchronize()
+        f_s = (time.perf_counter() - ta) / 4
+        out["host_tier"] = {
+            "ms_per_step_pool_in_pinned_host_memory": host_ms,
+            "ms_per_step_pool_in_hbm": 1e3 * wall / args.steps,
+            "state_bytes": int(pool[0].numel() * 4),
+            "fetch_gbs": n_f * pool[0].numel() * 4 / f_s / 1e9,
+            "draws_that_load_a_state": int(sum(int(c.call.src_slot[0]) >= 0 for c in calls)),
+            "note": "start state fetched from pinned host memory by workgroups appended to the first preparation launch",
+        }
+        del stage_f, big_host, ws_host
+    except Exception as exc:
+        out["host_tier"] = {"error": str(exc)}
+
     # ---- decode step (one token per request, states updated in place): 1024 requests x 16 heads, HBM bound
     try:
         n_dec = 1024                # 1 GiB of states: four times the memory-side cache

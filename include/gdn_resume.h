@@ -166,6 +166,46 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
                            void *o, void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * Host tier (Sec. 5, implementation details: the prototype keeps checkpoints in CPU RAM;
+ * Sec. 6: loading the stored checkpoint is the first component of the overhead of a hit).
+ * Checkpoint states may live in a pinned host pool (allocate it with hipHostMalloc or an
+ * equivalent; pageable memory works but the copies then block the host) with the same slot
+ * layout as the device pool.
+ *
+ * ckpt_fetch_host: dev_pool[dev_ids[i]] = host_pool[host_ids[i]], i < n, as asynchronous
+ * copies on `stream`; dev_ids distinct.  ckpt_spill_host: the reverse; host_ids distinct.
+ * Strides in floats, multiples of 4; ids inside their pools (no -1).  Bit-exact.
+ *
+ * gdn_resume_prefill_host: gdn_resume_prefill with the start states read from a pinned HOST
+ * pool (host_state_src, host pointer; src_slot indexes it; -1 = zero state as before).  The
+ * states are copied to a staging area of the workspace on a stream of the library's own while
+ * the first preparation launch runs on the caller's stream; only the recurrence waits for
+ * them.  The workspace must hold gdn_workspace_bytes_host(...) bytes.  Outputs are bitwise
+ * those of gdn_resume_prefill on a device copy of the pool.  Calls are serialised inside the
+ * library while their work is being enqueued.
+ */
+int32_t ckpt_fetch_host(const float *host_pool, int64_t host_slot_stride, int32_t host_n_slots,
+                        const int32_t *host_ids,
+                        float *dev_pool, int64_t dev_slot_stride, int32_t dev_n_slots,
+                        const int32_t *dev_ids, int32_t n, int64_t state_elems, void *stream);
+int32_t ckpt_spill_host(float *host_pool, int64_t host_slot_stride, int32_t host_n_slots,
+                        const int32_t *host_ids,
+                        const float *dev_pool, int64_t dev_slot_stride, int32_t dev_n_slots,
+                        const int32_t *dev_ids, int32_t n, int64_t state_elems, void *stream);
+int64_t gdn_workspace_bytes_host(const gdn_shape *shape, int32_t n_req, int64_t total_tokens,
+                                 int32_t n_emit);
+int32_t gdn_resume_prefill_host(const gdn_shape *shape,
+                                const void *q, const void *k, const void *v,
+                                const void *beta, const void *gate,
+                                int32_t n_req, const int32_t *cu_seqlens, const int32_t *start_pos,
+                                const float *host_state_src, int64_t src_slot_stride,
+                                int32_t src_n_slots, const int32_t *src_slot,
+                                const int32_t *emit_cu, const int32_t *emit_pos,
+                                float *state_dst, int64_t dst_slot_stride, int32_t dst_n_slots,
+                                const int32_t *emit_slot,
+                                void *o, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
  * Decode step: one new token per request, the recurrent state updated IN PLACE in its pool
  * slot (same state layout as gdn_resume_prefill; the update is the one-token case of the same
  * recurrence, Sec. 1: a recurrent layer needs only its latest state to go on):

@@ -66,6 +66,14 @@ def lib():
         L.ckpt_gather.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
         L.ckpt_scatter.restype = _i32
         L.ckpt_scatter.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
+        L.gdn_resume_prefill_host.restype = _i32
+        L.gdn_resume_prefill_host.argtypes = ([ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _vp]
+                                              + [_vp, _i64, _i32, _vp, _vp, _vp] + [_vp, _i64, _i32, _vp] + [_vp, _vp, _i64, _vp])
+        L.gdn_workspace_bytes_host.restype = _i64
+        L.gdn_workspace_bytes_host.argtypes = [ctypes.POINTER(gdn_shape), _i32, _i64, _i32]
+        for f in (L.ckpt_fetch_host, L.ckpt_spill_host):
+            f.restype = _i32
+            f.argtypes = [_vp, _i64, _i32, _vp, _vp, _i64, _i32, _vp, _i32, _i64, _vp]
         L.gdn_decode_step.restype = _i32
         L.gdn_decode_step.argtypes = [ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _i64, _i32, _vp, _vp, _vp]
         L.gdn_resume_prefill.restype = _i32
@@ -77,7 +85,8 @@ def lib():
 
 
 EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
-           "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step"]
+           "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
+           "gdn_workspace_bytes_host", "gdn_resume_prefill_host"]
 
 
 def _h32(x) -> np.ndarray:
@@ -208,3 +217,50 @@ def gdn_decode_step(shape: gdn_shape, q, k, v, beta, gate, pool, slot, o, stream
                                  _dp(pool), int(pool.stride(0)) if pool is not None else 0,
                                  int(pool.shape[0]) if pool is not None else 0, _hp(sl), _dp(o), _stream_ptr(stream)),
            "gdn_decode_step")
+
+
+def gdn_workspace_bytes_host(shape: gdn_shape, n_req: int, total_tokens: int, n_emit: int) -> int:
+    return _check(int(lib().gdn_workspace_bytes_host(ctypes.byref(shape), n_req, total_tokens, n_emit)),
+                  "gdn_workspace_bytes_host")
+
+
+def _tier(fn, host_pool, host_ids, dev_pool, dev_ids, state_elems, stream):
+    hi, di = _h32(host_ids), _h32(dev_ids)
+    if hi.size != di.size:
+        raise ValueError("host_ids and dev_ids differ in length")
+    elems = int(state_elems if state_elems is not None else host_pool[0].numel())
+    _check(getattr(lib(), fn)(_dp(host_pool), int(host_pool.stride(0)), int(host_pool.shape[0]), _hp(hi),
+                              _dp(dev_pool), int(dev_pool.stride(0)), int(dev_pool.shape[0]), _hp(di), int(hi.size),
+                              elems, _stream_ptr(stream)), fn)
+
+
+def ckpt_fetch_host(host_pool, host_ids, dev_pool, dev_ids, state_elems=None, stream=None) -> None:
+    """dev_pool[dev_ids[i]] = host_pool[host_ids[i]] (host_pool: pinned host tensor)."""
+    _tier("ckpt_fetch_host", host_pool, host_ids, dev_pool, dev_ids, state_elems, stream)
+
+
+def ckpt_spill_host(host_pool, host_ids, dev_pool, dev_ids, state_elems=None, stream=None) -> None:
+    """host_pool[host_ids[i]] = dev_pool[dev_ids[i]]."""
+    _tier("ckpt_spill_host", host_pool, host_ids, dev_pool, dev_ids, state_elems, stream)
+
+
+def gdn_resume_prefill_host(shape: gdn_shape, q, k, v, beta, gate, cu_seqlens, start_pos,
+                            host_state_src, src_slot, emit_cu, emit_pos, state_dst, emit_slot,
+                            o, workspace, stream=None) -> None:
+    """gdn_resume_prefill with the start states in a pinned host pool (see include/gdn_resume.h)."""
+    cu, sp, ss = _h32(cu_seqlens), _h32(start_pos), _h32(src_slot)
+    ecu, epos, eslot = _h32(emit_cu), _h32(emit_pos), _h32(emit_slot)
+    n_req = int(sp.size)
+    if cu.size != n_req + 1 or ecu.size != n_req + 1 or ss.size != n_req or eslot.size != epos.size:
+        raise ValueError("index arrays have inconsistent lengths")
+    src_stride = int(host_state_src.stride(0)) if host_state_src is not None else 0
+    src_n = int(host_state_src.shape[0]) if host_state_src is not None else 0
+    dst_stride = int(state_dst.stride(0)) if state_dst is not None else 0
+    dst_n = int(state_dst.shape[0]) if state_dst is not None else 0
+    ws_bytes = int(workspace.numel() * workspace.element_size()) if workspace is not None else 0
+    _check(lib().gdn_resume_prefill_host(ctypes.byref(shape), _dp(q), _dp(k), _dp(v), _dp(beta), _dp(gate),
+                                         n_req, _hp(cu), _hp(sp),
+                                         _dp(host_state_src), src_stride, src_n, _hp(ss), _hp(ecu), _hp(epos),
+                                         _dp(state_dst), dst_stride, dst_n, _hp(eslot),
+                                         _dp(o), _dp(workspace), ws_bytes, _stream_ptr(stream)),
+           "gdn_resume_prefill_host")

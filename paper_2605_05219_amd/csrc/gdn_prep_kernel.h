@@ -41,6 +41,16 @@ struct PrepArgs {
     int32_t L, H_qk, H_v;
     int64_t T_alloc;
     float scale;
+    // Host tier (first launch of a call only, else n_copy_wgs = 0): the last n_copy_wgs workgroups
+    // of the grid copy the start states from device-accessible pinned host memory to the staging
+    // area, so the transfer rides under this launch.
+    const float* host_pool;          // device-side address of the pinned host pool
+    int64_t host_slot_stride;        // floats
+    const int32_t* staged_slot;      // [n_staged] host slot of the i-th staged state
+    float* staging;                  // [n_staged][slot_elems]
+    int64_t slot_elems;
+    int32_t n_staged;
+    int32_t n_copy_wgs;
 };
 
 // D(16x16) += A(16x16) * B(16x16), fp32 MFMA 16x16x4.  Lane (m = l & 15, g4 = l >> 4).
@@ -116,6 +126,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
 
     const int tid = threadIdx.x;
+    const int n_prep_wgs = (int)gridDim.x - a.n_copy_wgs;
+    if ((int)blockIdx.x >= n_prep_wgs) {
+        // ---- copy role: 16-byte loads over PCIe, four in flight per thread
+        const int64_t n4 = a.slot_elems / 4;
+        const int64_t step = (int64_t)a.n_copy_wgs * 256;
+        for (int st = 0; st < a.n_staged; ++st) {
+            const f32x4* src = reinterpret_cast<const f32x4*>(a.host_pool + (int64_t)a.staged_slot[st] * a.host_slot_stride);
+            f32x4* dst = reinterpret_cast<f32x4*>(a.staging + (int64_t)st * a.slot_elems);
+            int64_t i = (int64_t)((int)blockIdx.x - n_prep_wgs) * 256 + tid;
+            for (; i + 3 * step < n4; i += 4 * step) {
+                const f32x4 x0 = src[i], x1 = src[i + step], x2 = src[i + 2 * step], x3 = src[i + 3 * step];
+                dst[i] = x0; dst[i + step] = x1; dst[i + 2 * step] = x2; dst[i + 3 * step] = x3;
+            }
+            for (; i < n4; i += step) dst[i] = src[i];
+        }
+        return;
+    }
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
@@ -135,7 +162,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     auto locate = [&](int u) -> Item {
         Item it;
         it.c = -1; it.lh = 0; it.x = 0; it.tok0 = 0; it.n = 0;
-        for (;; u += (int)gridDim.x) {
+        for (;; u += n_prep_wgs) {
             it.u = u;
             if (u >= total) return it;
             it.x = u / units;
@@ -197,7 +224,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     for (int i = tid; i < C * LF_LD; i += 256) Lf[i] = 0.f;
     fetch_kq(cur);
     fetch_v(cur);
-    Item nxt = locate(cur.u + (int)gridDim.x);
+    Item nxt = locate(cur.u + n_prep_wgs);
 
   for (;;) {
     const int c = cur.c;
@@ -466,7 +493,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
     if (nxt.u >= total) break;
     cur = nxt;
-    nxt = locate(cur.u + (int)gridDim.x);
+    nxt = locate(cur.u + n_prep_wgs);
     if (!PREFETCH) {
         fetch_kq(cur);
         fetch_v(cur);

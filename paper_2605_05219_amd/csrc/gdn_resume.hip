@@ -189,6 +189,37 @@ private:
     }
 };
 
+// ------------------------------------------------------------------ host tier
+// Copies between a pinned host pool and device memory run on a stream of the library's own
+// (default priority), ordered against the caller's stream with two events.
+struct HostTier {
+    std::mutex mu;
+    hipStream_t stream = nullptr;
+    hipEvent_t start = nullptr, ready = nullptr;
+    hipError_t init() {
+        if (stream) return hipSuccess;
+        hipError_t e = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&start, hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ready, hipEventDisableTiming);
+        return e;
+    }
+};
+HostTier g_tier;
+
+int32_t check_tier_args(const void* host_pool, int64_t host_stride, int32_t host_n, const int32_t* host_ids,
+                        const void* dev_pool, int64_t dev_stride, int32_t dev_n, const int32_t* dev_ids, int32_t n,
+                        int64_t state_elems) {
+    if (n < 0 || host_n < 0 || dev_n < 0 || state_elems < 0) return GDN_ERR_COUNT;
+    if (n == 0 || state_elems == 0) return GDN_OK;
+    if (!host_pool || !dev_pool || !host_ids || !dev_ids) return GDN_ERR_NULL;
+    if (!aligned16(host_pool) || !aligned16(dev_pool)) return GDN_ERR_ALIGN;
+    if ((state_elems & 3) || (host_stride & 3) || (dev_stride & 3)) return GDN_ERR_ALIGN;
+    if (host_stride < state_elems || dev_stride < state_elems) return GDN_ERR_SHAPE;
+    for (int32_t i = 0; i < n; ++i)
+        if (host_ids[i] < 0 || host_ids[i] >= host_n || dev_ids[i] < 0 || dev_ids[i] >= dev_n) return GDN_ERR_SLOT_RANGE;
+    return GDN_OK;
+}
+
 // ------------------------------------------------------------------ kernel dispatch
 template <typename E, int DK, int DV>
 int64_t unit_bytes_of() { return UnitLayout<E, DK, DV>::UNIT_BYTES; }
@@ -267,7 +298,7 @@ inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
 
 template <typename E, int DK, int DV>
 int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req, int32_t max_chunks_per_req,
-                   char* slab_base, hipStream_t stream) {
+                   char* slab_base, hipStream_t stream, hipEvent_t state_ready = nullptr) {
     typedef PrepSmem<E, DK, DV> SM;
     // workgroups of the preparation kernel the chip holds at once (per kernel instance)
     static int prep_slots = 0;
@@ -300,11 +331,17 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
         ra.slab_begin = sb * R;
         const int64_t items = (int64_t)n_req * R * units;
         if (items > INT32_MAX) return GDN_ERR_COUNT;
-        hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>), dim3((unsigned)std::min<int64_t>(items, prep_slots)), dim3(256),
-                           SM::BYTES, stream, pa);
+        PrepArgs pl = pa;
+        if (sb > 0) pl.n_copy_wgs = 0;   // the start states travel with the first launch only
+        hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>),
+                           dim3((unsigned)(std::min<int64_t>(items, prep_slots) + pl.n_copy_wgs)), dim3(256), SM::BYTES, stream, pl);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_err(e);
         prof.mark(0);
+        if (sb == 0 && state_ready) {   // start states still on their way from the host tier: only the recurrence needs them
+            e = hipStreamWaitEvent(stream, state_ready, 0);
+            if (e != hipSuccess) return hip_err(e);
+        }
         // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain
         // share one workgroup and one LDS copy of the chunk operands; with fewer, two slices per
         // workgroup; with too few to occupy every compute unit, the latency variant.
@@ -398,7 +435,7 @@ int32_t gdn_plan_chunks(int32_t n_req, const int32_t* cu_seqlens, const int32_t*
 }
 
 static int64_t plan_bytes(int64_t n_chunks, int64_t n_req) {
-    return align_up((3 * n_chunks + 3 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
+    return align_up((3 * n_chunks + 4 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
 }
 
 // Workspace = [plan | carried states | slab].  The slab holds the units of R chunk rounds of
@@ -445,12 +482,14 @@ int32_t ckpt_scatter(float* pool, int64_t slot_stride, int32_t n_slots, const in
     return launch_copy<false>(src, pool, src_stride, slot_stride, state_elems, slot_ids, n, (hipStream_t)stream);
 }
 
-int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
-                           const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
-                           const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
-                           const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
-                           float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
-                           void* o, void* workspace, int64_t workspace_bytes, void* stream_v) {
+// The body of gdn_resume_prefill; with src_on_host the start states live in a pinned host pool
+// and are first copied to a staging area behind the workspace proper.
+static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                            const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
+                            const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                            const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
+                            float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
+                            void* o, void* workspace, int64_t workspace_bytes, void* stream_v, bool src_on_host) {
     hipStream_t stream = (hipStream_t)stream_v;
     int32_t rc = check_shape(shape);
     if (rc != GDN_OK) return rc;
@@ -463,7 +502,7 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     if (total_tokens > s.T_alloc) return GDN_ERR_SEQLENS;
     const int32_t n_emit = emit_cu[n_req];
     rc = check_slots(n_req, src_slot, src_n_slots, emit_cu, emit_slot, dst_n_slots,
-                     state_src != nullptr && (const void*)state_src == (const void*)state_dst);
+                     !src_on_host && state_src != nullptr && (const void*)state_src == (const void*)state_dst);
     if (rc != GDN_OK) return rc;
 
     const int64_t slot_elems = (int64_t)s.L * s.H_v * s.d_v * s.d_k;
@@ -488,12 +527,16 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
 
     const WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
     const int64_t pb = wl.plan;
-    const int64_t need = wl.total;
+    int32_t n_staged = 0;
+    if (src_on_host)
+        for (int32_t r = 0; r < n_req; ++r) n_staged += src_slot[r] >= 0;
+    const int64_t staging_off = align_up(wl.total, 256);
+    const int64_t need = src_on_host ? staging_off + (int64_t)n_staged * slot_elems * (int64_t)sizeof(float) : wl.total;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GDN_ERR_WORKSPACE;
     if (workspace_bytes < need) return GDN_ERR_WORKSPACE;
 
     // ---- plan image: [tok0 | len | emit slot] per chunk, [chunk_cu | src slot | order] per request
-    std::vector<int32_t> img((size_t)(3 * (int64_t)n_chunks + 3 * (int64_t)n_req + 1));
+    std::vector<int32_t> img((size_t)(3 * (int64_t)n_chunks + 4 * (int64_t)n_req + 1));   // + staged host slots
     int32_t* p_tok0 = img.data();
     int32_t* p_len = p_tok0 + n_chunks;
     int32_t* p_eslot = p_len + n_chunks;
@@ -507,6 +550,14 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     }
     std::memcpy(p_cu, plan.req_chunk_cu.data(), sizeof(int32_t) * (n_req + 1));
     std::memcpy(p_src, src_slot, sizeof(int32_t) * n_req);
+    if (src_on_host) {   // the recurrence reads request r's start state from its place in the staging area
+        int32_t* p_staged = p_order + n_req;
+        int32_t at = 0;
+        for (int32_t r = 0; r < n_req; ++r) {
+            if (src_slot[r] >= 0) p_staged[at] = src_slot[r];
+            p_src[r] = src_slot[r] >= 0 ? at++ : -1;
+        }
+    }
     const std::vector<int32_t> order = longest_first(plan, n_req);
     std::memcpy(p_order, order.data(), sizeof(int32_t) * n_req);
 
@@ -529,6 +580,8 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     pa.L = s.L; pa.H_qk = s.H_qk; pa.H_v = s.H_v;
     pa.T_alloc = s.T_alloc;
     pa.scale = s.scale;
+    pa.host_pool = nullptr; pa.host_slot_stride = 0; pa.staged_slot = nullptr; pa.staging = nullptr;
+    pa.slot_elems = 0; pa.n_staged = 0; pa.n_copy_wgs = 0;
 
     RecurArgs ra;
     ra.o = o; ra.ws_units = nullptr;
@@ -546,10 +599,112 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
     ra.o_bf16 = s.o_dtype == GDN_BF16;
 
 
+    // ---- host tier: the start states go to the staging area.  If the pool is device-accessible
+    //      pinned memory, workgroups appended to the first preparation launch fetch them over
+    //      PCIe while that launch computes (only the recurrence needs them); otherwise they are
+    //      copied on the caller's stream ahead of the first launch.  (Sending them over a second
+    //      stream was measured: the two cross-stream event waits cost more than the 27 us copy
+    //      of a 1 MiB state they hide.)
+    hipEvent_t state_ready = nullptr;
+    if (src_on_host && n_staged > 0) {
+        float* staging = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + staging_off);
+        hipPointerAttribute_t attr;
+        std::memset(&attr, 0, sizeof attr);
+        const bool mapped = hipPointerGetAttributes(&attr, state_src) == hipSuccess && attr.type == hipMemoryTypeHost &&
+                            attr.devicePointer != nullptr;
+        if (!mapped) (void)hipGetLastError();   // an unregistered pointer is not an error here
+        if (mapped) {
+            pa.host_pool = static_cast<const float*>(attr.devicePointer);
+            pa.host_slot_stride = src_slot_stride;
+            pa.staged_slot = ra.req_order + n_req;
+            pa.staging = staging;
+            pa.slot_elems = slot_elems;
+            pa.n_staged = n_staged;
+            pa.n_copy_wgs = 32;
+        } else {
+            int32_t at = 0;
+            for (int32_t r = 0; r < n_req; ++r) {
+                if (src_slot[r] < 0) continue;
+                const hipError_t e = hipMemcpyAsync(staging + (int64_t)at * slot_elems,
+                                                    state_src + (int64_t)src_slot[r] * src_slot_stride,
+                                                    (size_t)slot_elems * sizeof(float), hipMemcpyHostToDevice, stream);
+                if (e != hipSuccess) return hip_err(e);
+                ++at;
+            }
+        }
+        ra.state_src = staging;
+        ra.src_slot_stride = slot_elems;
+    }
+
     const int32_t mc = plan.max_chunks_per_req;
-    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
-    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream);
-    return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, stream);
+    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
+    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
+    return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
+}
+
+int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                           const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
+                           const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                           const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
+                           float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
+                           void* o, void* workspace, int64_t workspace_bytes, void* stream) {
+    return prefill_impl(shape, q, k, v, beta, gate, n_req, cu_seqlens, start_pos, state_src, src_slot_stride, src_n_slots,
+                        src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o, workspace,
+                        workspace_bytes, stream, false);
+}
+
+int32_t gdn_resume_prefill_host(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                                const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
+                                const float* host_state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                                const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
+                                float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
+                                void* o, void* workspace, int64_t workspace_bytes, void* stream) {
+    return prefill_impl(shape, q, k, v, beta, gate, n_req, cu_seqlens, start_pos, host_state_src, src_slot_stride,
+                        src_n_slots, src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o,
+                        workspace, workspace_bytes, stream, true);
+}
+
+int64_t gdn_workspace_bytes_host(const gdn_shape* shape, int32_t n_req, int64_t total_tokens, int32_t n_emit) {
+    const int64_t base = gdn_workspace_bytes(shape, n_req, total_tokens, n_emit);
+    if (base < 0) return base;
+    const int64_t slot_bytes = (int64_t)shape->L * shape->H_v * shape->d_v * shape->d_k * (int64_t)sizeof(float);
+    return align_up(base, 256) + (int64_t)n_req * slot_bytes;
+}
+
+int32_t ckpt_fetch_host(const float* host_pool, int64_t host_slot_stride, int32_t host_n_slots, const int32_t* host_ids,
+                        float* dev_pool, int64_t dev_slot_stride, int32_t dev_n_slots, const int32_t* dev_ids, int32_t n,
+                        int64_t state_elems, void* stream) {
+    const int32_t rc = check_tier_args(host_pool, host_slot_stride, host_n_slots, host_ids, dev_pool, dev_slot_stride,
+                                       dev_n_slots, dev_ids, n, state_elems);
+    if (rc != GDN_OK || n == 0 || state_elems == 0) return rc;
+    std::vector<int32_t> sorted(dev_ids, dev_ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return GDN_ERR_SLOT_DUP;
+    for (int32_t i = 0; i < n; ++i) {
+        const hipError_t e = hipMemcpyAsync(dev_pool + (int64_t)dev_ids[i] * dev_slot_stride,
+                                            host_pool + (int64_t)host_ids[i] * host_slot_stride,
+                                            (size_t)state_elems * sizeof(float), hipMemcpyHostToDevice, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_err(e);
+    }
+    return GDN_OK;
+}
+
+int32_t ckpt_spill_host(float* host_pool, int64_t host_slot_stride, int32_t host_n_slots, const int32_t* host_ids,
+                        const float* dev_pool, int64_t dev_slot_stride, int32_t dev_n_slots, const int32_t* dev_ids, int32_t n,
+                        int64_t state_elems, void* stream) {
+    const int32_t rc = check_tier_args(host_pool, host_slot_stride, host_n_slots, host_ids, dev_pool, dev_slot_stride,
+                                       dev_n_slots, dev_ids, n, state_elems);
+    if (rc != GDN_OK || n == 0 || state_elems == 0) return rc;
+    std::vector<int32_t> sorted(host_ids, host_ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return GDN_ERR_SLOT_DUP;
+    for (int32_t i = 0; i < n; ++i) {
+        const hipError_t e = hipMemcpyAsync(host_pool + (int64_t)host_ids[i] * host_slot_stride,
+                                            dev_pool + (int64_t)dev_ids[i] * dev_slot_stride,
+                                            (size_t)state_elems * sizeof(float), hipMemcpyDeviceToHost, (hipStream_t)stream);
+        if (e != hipSuccess) return hip_err(e);
+    }
+    return GDN_OK;
 }
 
 int32_t gdn_decode_step(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,

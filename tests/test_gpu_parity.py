@@ -376,3 +376,72 @@ def test_config3_full_shape_sampled_requests():
     lens = np.diff(sc.resume.cu_seqlens)
     short = [int(i) for i in np.argsort(lens)[:3]]
     check_call_sampled(sc.resume, pool, TOL["bf16"], sorted(set(short + [int(np.argmax(lens))])))
+
+
+# ------------------------------------------------------------------ host tier
+def test_host_tier_fetch_and_spill_bit_exact():
+    import torch
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(77)
+    elems = 2 * 64 * 64
+    host = torch.from_numpy(rng.standard_normal((9, elems)).astype(np.float32)).pin_memory()
+    dev = torch.zeros((12, elems + 8), dtype=torch.float32, device="cuda")[:, :elems]     # padded stride
+    before = dev.cpu().numpy().copy()
+    h_ids, d_ids = [8, 0, 3, 3], [1, 11, 5, 6]
+    B.ckpt_fetch_host(host, h_ids, dev, d_ids, elems)
+    torch.cuda.synchronize()
+    after = dev.cpu().numpy()
+    for h, d in zip(h_ids, d_ids):
+        assert np.array_equal(after[d], host[h].numpy())
+    for d in set(range(12)) - set(d_ids):
+        assert np.array_equal(after[d], before[d])
+    back = torch.zeros((5, elems), dtype=torch.float32).pin_memory()
+    B.ckpt_spill_host(back, [4, 0], dev, [11, 5], elems)
+    torch.cuda.synchronize()
+    assert np.array_equal(back[4].numpy(), host[0].numpy()) and np.array_equal(back[0].numpy(), host[3].numpy())
+    assert not back[1:4].numpy().any()
+
+
+@pytest.mark.parametrize("n_req,pinned", [(1, True), (6, True), (6, False)])
+def test_prefill_from_host_pool_equals_prefill_from_device_pool(n_req, pinned):
+    """Start states in a host pool: pinned memory is fetched by workgroups riding under the first
+    preparation launch, pageable memory is copied on the stream first; outputs and emitted
+    states bitwise those of the device-pool call, and within tolerance of the oracle.  Called
+    twice (the staging area is reused)."""
+    import torch
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(60 + n_req)
+    d, H, L = 128, 4, 1
+    lens = [int(x) for x in rng.integers(40, 700, size=n_req)]
+    starts = [int(x) for x in rng.integers(0, 90, size=n_req)]
+    n_src, n_dst = 5, 2 * n_req
+    src_pool = (rng.standard_normal((n_src, L, H, d, d)) * 0.4).astype(np.float32)
+    src = [(-1 if r == 2 else int(rng.integers(0, n_src))) for r in range(n_req)]
+    emits = [[starts[r] + lens[r] // 2, starts[r] + lens[r]] for r in range(n_req)]
+    slots = [[2 * r, 2 * r + 1] for r in range(n_req)]
+    per = [wl.token_streams(rng, L, n, H, H, d, d, "bf16", "slow") for n in lens]
+    call = wl.pack_call(L, H, H, d, d, "bf16", per, starts, src, emits, slots, max(n_src, n_dst))
+    o_ref, st_ref = orc.resume_prefill(*call.streams.fields(), call.cu_seqlens, call.start_pos, call.src_slot,
+                                       call.emit_cu, call.emit_pos, state_src=src_pool)
+    # device-pool run (source and destination pools kept apart so that both runs see the same inputs)
+    dst_dev = torch.zeros((n_dst, L, H, d, d), dtype=torch.float32, device="cuda")
+    g = GpuCall(call, torch.from_numpy(src_pool).cuda(), dst_pool=dst_dev)
+    g.run(); torch.cuda.synchronize()
+    o_dev, st_dev = g.o[:, :call.total_tokens].cpu().numpy(), dst_dev.cpu().numpy()
+    # host-pool run
+    host_pool = torch.from_numpy(src_pool.copy())
+    if pinned:
+        host_pool = host_pool.pin_memory()
+    dst_host = torch.zeros_like(dst_dev)
+    ws = torch.empty(B.gdn_workspace_bytes_host(g.shape, call.n_req, call.total_tokens, int(call.emit_pos.size)),
+                     dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        g.o.fill_(float("nan")); dst_host.zero_()
+        B.gdn_resume_prefill_host(g.shape, g.q, g.k, g.v, g.beta, g.gate, call.cu_seqlens, call.start_pos, host_pool,
+                                  call.src_slot, call.emit_cu, call.emit_pos, dst_host, call.emit_slot, g.o, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(g.o[:, :call.total_tokens].cpu().numpy(), o_dev)
+        assert np.array_equal(dst_host.cpu().numpy(), st_dev)
+    assert max_norm_err(o_dev, o_ref[:, :call.total_tokens]) <= TOL["bf16"]
+    for e, s in enumerate(call.emit_slot):
+        assert max_norm_err(st_dev[s], st_ref[e]) <= TOL["bf16"]

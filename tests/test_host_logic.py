@@ -258,3 +258,33 @@ def test_decode_argument_errors(monkeypatch, over, code):
         B.gdn_decode_step(shape, args["q"], args["k"], args["v"], args["beta"], args["gate"], args["pool"], args["slot"],
                           args["o"], ctypes.c_void_p(0))
     assert ei.value.code == code
+
+
+@pytest.mark.parametrize("fn", ["ckpt_fetch_host", "ckpt_spill_host"])
+def test_host_tier_copy_argument_errors(monkeypatch, fn):
+    monkeypatch.setattr(B, "_stream_ptr", lambda s=None: ctypes.c_void_p(0))
+    f = getattr(B, fn)
+    host, dev = FakeDev(ptr=0x20000, n0=4, stride0=64), FakeDev(ptr=0x30000, n0=6, stride0=64)
+    cases = [
+        (dict(host_ids=[0, 4], dev_ids=[0, 1]), -5),
+        (dict(host_ids=[0, 1], dev_ids=[0, 6]), -5),
+        (dict(host_ids=[-1, 1], dev_ids=[0, 1]), -5),
+        (dict(host_ids=[0, 1], dev_ids=[2, 2]) if fn == "ckpt_fetch_host" else dict(host_ids=[1, 1], dev_ids=[0, 2]), -6),
+        (dict(host=FakeDev(ptr=0)), -1),
+        (dict(dev=FakeDev(ptr=0x30004, n0=6, stride0=64)), -2),
+        (dict(elems=66), -2),
+        (dict(host=FakeDev(ptr=0x20000, n0=4, stride0=32)), -3),
+    ]
+    for over, code in cases:
+        a = dict(host=host, dev=dev, host_ids=[0, 1], dev_ids=[0, 1], elems=64)
+        a.update(over)
+        with pytest.raises(B.GdnError) as ei:
+            f(a["host"], a["host_ids"], a["dev"], a["dev_ids"], a["elems"], ctypes.c_void_p(0))
+        assert ei.value.code == code, (over, ei.value.code)
+    f(host, [], dev, [], 64, ctypes.c_void_p(0))                       # empty: nothing to do
+
+
+def test_host_tier_workspace_is_the_device_one_plus_staging():
+    shape = B.make_shape(1, 16, 16, 128, 128, "bf16", "f32", 8192)
+    base = B.gdn_workspace_bytes(shape, 3, 8192, 16)
+    assert B.gdn_workspace_bytes_host(shape, 3, 8192, 16) == (base + 255) // 256 * 256 + 3 * 16 * 128 * 128 * 4
