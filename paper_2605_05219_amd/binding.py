@@ -48,6 +48,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2605_05219_amd.build)")
+        # PyTorch ships its own HIP runtime; it must be in the process before this library is loaded so
+        # that both resolve to the same one (device pointers of one runtime mean nothing to another).
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         L.gdn_version.restype = _i32
         L.gdn_tune_slab_rounds.restype = _i32

@@ -97,8 +97,9 @@ struct PrepSmem {
     static constexpr int BYTES = SM_OFF + 4 * C * (int)sizeof(float);
 };
 
+// The work of one preparation workgroup: workgroup `wg` of `n_prep_wgs` that share a launch's items.
 template <typename E, int DK, int DV>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_prep_kernel(PrepArgs a) {
+__device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const int n_prep_wgs) {
     typedef Elem<E> EL;
     typedef typename EL::In In;
     typedef typename EL::Frag Frag;
@@ -126,23 +127,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
 
     const int tid = threadIdx.x;
-    const int n_prep_wgs = (int)gridDim.x - a.n_copy_wgs;
-    if ((int)blockIdx.x >= n_prep_wgs) {
-        // ---- copy role: 16-byte loads over PCIe, four in flight per thread
-        const int64_t n4 = a.slot_elems / 4;
-        const int64_t step = (int64_t)a.n_copy_wgs * 256;
-        for (int st = 0; st < a.n_staged; ++st) {
-            const f32x4* src = reinterpret_cast<const f32x4*>(a.host_pool + (int64_t)a.staged_slot[st] * a.host_slot_stride);
-            f32x4* dst = reinterpret_cast<f32x4*>(a.staging + (int64_t)st * a.slot_elems);
-            int64_t i = (int64_t)((int)blockIdx.x - n_prep_wgs) * 256 + tid;
-            for (; i + 3 * step < n4; i += 4 * step) {
-                const f32x4 x0 = src[i], x1 = src[i + step], x2 = src[i + 2 * step], x3 = src[i + 3 * step];
-                dst[i] = x0; dst[i + step] = x1; dst[i + 2 * step] = x2; dst[i + 3 * step] = x3;
-            }
-            for (; i < n4; i += step) dst[i] = src[i];
-        }
-        return;
-    }
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
     const int lr = lane & 31;
@@ -154,7 +138,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // Work items of the launch: u = x * units + lh with x = r * R + j (chunk round slab_begin + j
     // of request r, skipped if the request has no such round).  The workgroup takes items
-    // blockIdx.x, blockIdx.x + gridDim.x, ... and fetches the inputs of its next item while it
+    // wg, wg + n_prep_wgs, ... and fetches the inputs of its next item while it
     // works on the current one.
     const int units = a.L * a.H_v;
     const int total = a.n_req * a.R * units;
@@ -217,7 +201,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
     };
 
-    Item cur = locate((int)blockIdx.x);
+    Item cur = locate(wg);
     if (cur.u >= total) return;
     // The fp32 triangular matrix: its upper right 32x32 tile is never written and must read as 0
     // (every other entry on or above the diagonal is rewritten with an exact 0 for each item).
@@ -500,6 +484,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     }
     __syncthreads();   // every wave is done with this item's LDS tiles
   }
+}
+
+template <typename E, int DK, int DV>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_prep_kernel(PrepArgs a) {
+    const int tid = threadIdx.x;
+    const int n_prep_wgs = (int)gridDim.x - a.n_copy_wgs;
+    if ((int)blockIdx.x >= n_prep_wgs) {
+        // ---- copy role: 16-byte loads over PCIe, four in flight per thread
+        const int64_t n4 = a.slot_elems / 4;
+        const int64_t step = (int64_t)a.n_copy_wgs * 256;
+        for (int st = 0; st < a.n_staged; ++st) {
+            const f32x4* src = reinterpret_cast<const f32x4*>(a.host_pool + (int64_t)a.staged_slot[st] * a.host_slot_stride);
+            f32x4* dst = reinterpret_cast<f32x4*>(a.staging + (int64_t)st * a.slot_elems);
+            int64_t i = (int64_t)((int)blockIdx.x - n_prep_wgs) * 256 + tid;
+            for (; i + 3 * step < n4; i += 4 * step) {
+                const f32x4 x0 = src[i], x1 = src[i + step], x2 = src[i + 2 * step], x3 = src[i + 3 * step];
+                dst[i] = x0; dst[i + step] = x1; dst[i + 2 * step] = x2; dst[i + 3 * step] = x3;
+            }
+            for (; i < n4; i += step) dst[i] = src[i];
+        }
+        return;
+    }
+    prep_body<E, DK, DV>(a, (int)blockIdx.x, n_prep_wgs);
 }
 
 }  // namespace gdn

@@ -318,8 +318,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 
 #define GDN_FENCE() __builtin_amdgcn_sched_barrier(0)   // nothing is scheduled across this point
 
+// The work of one latency-variant workgroup: workgroup `wg` of the `nb` that cover the chains' slices.
 template <typename E, int DK, int DV>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_recur_quad_kernel(RecurArgs a) {
+__device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg, const int nb) {
     typedef Elem<E> EL;
     typedef typename EL::Frag Frag;
     typedef UnitLayout<E, DK, DV> U;
@@ -346,8 +347,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // ordering) + (index of this workgroup within its XCD).
     int item;
     {
-        const int nb = gridDim.x, x = blockIdx.x & 7, q = nb >> 3, rem = nb & 7;
-        item = (x < rem ? x * (q + 1) : rem * (q + 1) + (x - rem) * q) + (blockIdx.x >> 3);
+        const int x = wg & 7, q = nb >> 3, rem = nb & 7;
+        item = (x < rem ? x * (q + 1) : rem * (q + 1) + (x - rem) * q) + (wg >> 3);
     }
     const int units = a.L * a.H_v;
     const int sl = item % NS;
@@ -630,5 +631,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 }
 
 #undef GDN_FENCE
+
+template <typename E, int DK, int DV>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_recur_quad_kernel(RecurArgs a) {
+    recur_quad_body<E, DK, DV>(a, (int)blockIdx.x, (int)gridDim.x);
+}
 
 }  // namespace gdn

@@ -266,6 +266,38 @@ hipError_t launch_recur_quad(const RecurArgs& ra, int64_t n_chains, hipStream_t 
     return hipGetLastError();
 }
 
+// Latency variant with several slabs: the recurrence over slab s and the preparation of slab s+1
+// are independent, so they share one launch, the recurrence workgroups first (they are
+// dispatched first and each takes a whole compute unit), the preparation workgroups on the
+// compute units that are left.  No synchronisation between the two roles: the dependences
+// (slab s prepared before its recurrence, states carried from slab to slab) run from launch to
+// launch.
+template <typename E, int DK, int DV>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_quad_overlap_kernel(RecurArgs ra, PrepArgs pa,
+                                                                                                         int n_recur) {
+    if ((int)blockIdx.x < n_recur) recur_quad_body<E, DK, DV>(ra, (int)blockIdx.x, n_recur);
+    else prep_body<E, DK, DV>(pa, (int)blockIdx.x - n_recur, (int)gridDim.x - n_recur);
+}
+
+template <typename E, int DK, int DV>
+hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t n_chains, int64_t prep_items, int cus,
+                               hipStream_t stream) {
+    constexpr int smem = QuadSmem<E, DK, DV>::BYTES > PrepSmem<E, DK, DV>::BYTES ? QuadSmem<E, DK, DV>::BYTES
+                                                                               : PrepSmem<E, DK, DV>::BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_quad_overlap_kernel<E, DK, DV>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int n_recur = (int)(n_chains * (DV / 32));
+    const int n_prep = (int)std::min<int64_t>(prep_items, std::max(cus - n_recur, 16));   // one workgroup per compute unit
+    hipLaunchKernelGGL((gdn_quad_overlap_kernel<E, DK, DV>), dim3((unsigned)(n_recur + n_prep)), dim3(256), smem, stream, ra, pa,
+                       n_recur);
+    return hipGetLastError();
+}
+
 // Which recurrence variant a call gets: 1 = latency variant (few chains), else the number of
 // d_v slices (waves) per workgroup of the throughput variant.
 inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
@@ -289,7 +321,7 @@ std::atomic<int32_t> g_forced_rounds{0};
 inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
     const int32_t forced = g_forced_rounds.load();
     if (forced > 0) return forced;
-    const int64_t budget = nw == 1 ? (int64_t)96 << 20 : (int64_t)1 << 30;
+    const int64_t budget = nw == 1 ? (int64_t)48 << 20 : (int64_t)1 << 30;
     int64_t r = std::max<int64_t>(1, budget / std::max<int64_t>(1, n_chains * unit_bytes));
     const int64_t q = std::max<int64_t>(1, 512 / std::max<int64_t>(1, n_chains));
     r = std::max(q, r / q * q);
@@ -298,10 +330,10 @@ inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
 
 template <typename E, int DK, int DV>
 int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req, int32_t max_chunks_per_req,
-                   char* slab_base, hipStream_t stream, hipEvent_t state_ready = nullptr) {
+                   char* slab_base, int64_t slab_bytes, int32_t n_bufs, hipStream_t stream) {
     typedef PrepSmem<E, DK, DV> SM;
     // workgroups of the preparation kernel the chip holds at once (per kernel instance)
-    static int prep_slots = 0;
+    static int prep_slots = 0, n_cus = 0;
     if (prep_slots == 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_prep_kernel<E, DK, DV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
@@ -313,6 +345,7 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
             e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_prep_kernel<E, DK, DV>, 256, SM::BYTES);
         if (e != hipSuccess) return hip_err(e);
         prep_slots = std::max(1, cus * per_cu);
+        n_cus = cus;
     }
     const int units = s.L * s.H_v;
     const int64_t n_chains = (int64_t)n_req * units;
@@ -322,31 +355,47 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
     const int32_t n_slabs = (max_chunks_per_req + R - 1) / R;
 
     // Slab after slab on the caller's stream: the units one preparation launch writes are read
-    // back by the recurrence launch right behind it while they are still in the caches.
+    // back by the recurrence launch right behind it while they are still in the caches.  With two
+    // slab buffers (latency variant) the preparation of the next slab shares the recurrence's launch.
     ProfChain prof(stream);
-    pa.ws_units = slab_base;
-    ra.ws_units = slab_base;
-    for (int32_t sb = 0; sb < n_slabs; ++sb) {
-        pa.slab_begin = sb * R;
-        ra.slab_begin = sb * R;
-        const int64_t items = (int64_t)n_req * R * units;
-        if (items > INT32_MAX) return GDN_ERR_COUNT;
+    static const bool no_overlap = std::getenv("GDN_NO_OVERLAP") != nullptr;
+    const bool overlap = nw == 1 && n_bufs >= 2 && n_slabs > 1 && !no_overlap && sizeof(typename Elem<E>::Frag) == 16;
+    const int64_t items = (int64_t)n_req * R * units;
+    if (items > INT32_MAX) return GDN_ERR_COUNT;
+    auto launch_prep = [&](int32_t sb, char* buf, bool with_copies) -> hipError_t {
         PrepArgs pl = pa;
-        if (sb > 0) pl.n_copy_wgs = 0;   // the start states travel with the first launch only
+        pl.ws_units = buf;
+        pl.slab_begin = sb * R;
+        if (!with_copies) pl.n_copy_wgs = 0;   // the start states travel with the first launch only
         hipLaunchKernelGGL((gdn_prep_kernel<E, DK, DV>),
                            dim3((unsigned)(std::min<int64_t>(items, prep_slots) + pl.n_copy_wgs)), dim3(256), SM::BYTES, stream, pl);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_err(e);
-        prof.mark(0);
-        if (sb == 0 && state_ready) {   // start states still on their way from the host tier: only the recurrence needs them
-            e = hipStreamWaitEvent(stream, state_ready, 0);
+        return hipGetLastError();
+    };
+    for (int32_t sb = 0; sb < n_slabs; ++sb) {
+        char* buf = slab_base + (overlap ? (sb & 1) * slab_bytes : 0);
+        hipError_t e = hipSuccess;
+        if (!overlap || sb == 0) {
+            e = launch_prep(sb, buf, sb == 0);
             if (e != hipSuccess) return hip_err(e);
+            prof.mark(0);
         }
+        ra.ws_units = buf;
+        ra.slab_begin = sb * R;
         // Recurrence variant: with enough chains to fill the chip, NS slices (waves) of a chain
         // share one workgroup and one LDS copy of the chunk operands; with fewer, two slices per
         // workgroup; with too few to occupy every compute unit, the latency variant.
         if constexpr (sizeof(typename Elem<E>::Frag) == 16) {
-            if (nw == 1) e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
+            if (nw == 1) {
+                if (overlap && sb + 1 < n_slabs) {
+                    PrepArgs pl = pa;
+                    pl.ws_units = slab_base + ((sb + 1) & 1) * slab_bytes;
+                    pl.slab_begin = (sb + 1) * R;
+                    pl.n_copy_wgs = 0;
+                    e = launch_quad_overlap<E, DK, DV>(ra, pl, n_chains, items, n_cus, stream);
+                } else {
+                    e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
+                }
+            }
         }
         if (nw == 2) e = launch_recur_nw<E, DK, DV, 2>(ra, n_chains, stream);
         else if (nw > 2) e = launch_recur_nw<E, DK, DV, NS>(ra, n_chains, stream);
@@ -438,10 +487,12 @@ static int64_t plan_bytes(int64_t n_chunks, int64_t n_req) {
     return align_up((3 * n_chunks + 4 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
 }
 
-// Workspace = [plan | carried states | slab].  The slab holds the units of R chunk rounds of
-// every chain; slabs are processed one after the other and reuse it.
+// Workspace = [plan | carried states | slab buffers].  A slab buffer holds the units of R chunk
+// rounds of every chain; slabs are processed one after the other.  The throughput variants
+// reuse one buffer; the latency variant alternates between two, so that the next slab can be
+// prepared while the current one is consumed.
 struct WsLayout {
-    int32_t R;
+    int32_t R, n_bufs;
     int64_t plan, carry, slab, total;
 };
 // n_chunks: chunks of the whole call; max_rounds: chunks of its longest request (or a bound)
@@ -453,7 +504,8 @@ static WsLayout ws_layout(const gdn_shape& s, int64_t n_chunks, int64_t max_roun
     w.plan = plan_bytes(n_chunks, n_req);
     w.carry = align_up(n_chains * s.d_v * s.d_k * (int64_t)sizeof(float), 256);
     w.slab = n_chains * w.R * ub;
-    w.total = w.plan + w.carry + w.slab;
+    w.n_bufs = nw == 1 ? 2 : 1;   // latency variant: the next slab is prepared while this one is consumed
+    w.total = w.plan + w.carry + w.n_bufs * w.slab;
     return w;
 }
 
@@ -605,7 +657,6 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     //      copied on the caller's stream ahead of the first launch.  (Sending them over a second
     //      stream was measured: the two cross-stream event waits cost more than the 27 us copy
     //      of a 1 MiB state they hide.)
-    hipEvent_t state_ready = nullptr;
     if (src_on_host && n_staged > 0) {
         float* staging = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + staging_off);
         hipPointerAttribute_t attr;
@@ -637,9 +688,9 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     }
 
     const int32_t mc = plan.max_chunks_per_req;
-    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
-    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
-    return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, stream, state_ready);
+    if (s.in_dtype == GDN_F32) return launch_all<float, 64, 64>(s, pa, ra, n_req, mc, slab_base, wl.slab, wl.n_bufs, stream);
+    if (s.d_k == 64) return launch_all<half_t, 64, 64>(s, pa, ra, n_req, mc, slab_base, wl.slab, wl.n_bufs, stream);
+    return launch_all<half_t, 128, 128>(s, pa, ra, n_req, mc, slab_base, wl.slab, wl.n_bufs, stream);
 }
 
 int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
