@@ -34,9 +34,10 @@ FLOP_PREP = C * (6 * D + 2 * D)             # K K^T, K Q^T, W (each 2 C d_k) + U
 FLOP_RECUR = 6 * D * D + 2 * C * D          # W S^T, Q S^T, state update (2 d_k d_v each) + P U (2 C d_v)
 # algorithmic HBM bytes per token.head: q, k, v in bf16, beta, gate, o in fp32
 BYTES_TOKEN_HEAD = (2 * D + D) * 2 + 2 * 2 + D * 4
-# measured HBM bytes per token.head of each kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/)
-TRAFFIC_PREP = 805 + 1384      # read + written
-TRAFFIC_RECUR = 1416 + 647
+# measured HBM bytes per token.head of a call (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/), by launch
+# kind: the first slab's preparation launch; the recurrence launches, which also prepare every later slab
+TRAFFIC_PREP = 319 + 545       # read + written
+TRAFFIC_RECUR = 1927 + 1503
 PEAK_MFMA_TFLOPS = 2500.0                   # dense fp16/bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
 
@@ -47,6 +48,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed steps and their event pass (no latency sweep, pool copies, host tier, decode, "
+                         "CPU baseline): what the profiler runs use")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP event pass (no roofline object)")
     ap.add_argument("--events-in-timed-region", action="store_true",
@@ -153,7 +157,9 @@ def main() -> int:
     }
 
     if not args.no_kernel_events:
-        # A step launches each kernel once per slab (64 chunk rounds here), so 1 to 3 times.
+        # A step prepares its first slab (32 chunk rounds) in a launch of its own; every recurrence launch
+        # but the last also prepares the next slab (gdn_quad_overlap_kernel).  The roofline object prices the
+        # recurrence launches at the recurrence's flops alone (the preparation they carry is not counted).
         rec_dom = recur_ms >= prep_ms
         dom = "gdn_recur_kernel" if rec_dom else "gdn_prep_kernel"
         dom_ms, dom_n = (recur_ms, recur_n) if rec_dom else (prep_ms, prep_n)
@@ -186,6 +192,10 @@ def main() -> int:
             "ms_per_step_with_events": 1e3 * events_wall / args.steps,
             "other_ms_per_step_with_events": 1e3 * events_wall / args.steps - (prep_ms + recur_ms) / args.steps,
         }
+
+    if args.main_only:
+        print(json.dumps(out))
+        return 0
 
     # ---- latency against suffix length (Sec. 6, overhead decomposition: the resume cost is a small constant
     #      for loading the checkpoint plus a term linear in the replayed suffix): every draw timed on its own
