@@ -84,6 +84,15 @@ template <> struct Elem<half_t> {
         }
     }
     static __device__ __forceinline__ float widen(In x) { return __uint_as_float((uint32_t)x << 16); }
+    // U~ travels in E: a 32x32 accumulator tile as UT_PIECES 16-byte pieces per lane, piece p = registers
+    // UT_REGS p .. UT_REGS p + UT_REGS - 1 (its rounding is of the size of the operand rounding of U itself)
+    typedef half8 UtVec;
+    static constexpr int UT_PIECES = 2, UT_REGS = 8;
+    static __device__ __forceinline__ UtVec ut_pack(const f32x16& acc, int p) { return from_acc(acc, p); }
+    static __device__ __forceinline__ void ut_unpack(const UtVec& x, f32x16& acc, int p) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[8 * p + e] = (float)x[e];
+    }
     // hardware exp2/log2 based: relative error ~1e-6 |x|, far inside the fp16 operand rounding
     static __device__ __forceinline__ float exp_(float x) { return __expf(x); }
     static __device__ __forceinline__ float log_(float x) { return __logf(x); }
@@ -122,6 +131,15 @@ template <> struct Elem<float> {
         for (int i = 0; i < 4; ++i) { out[i] = raw.a[i]; out[4 + i] = raw.b[i]; }
     }
     static __device__ __forceinline__ float widen(In x) { return x; }
+    typedef f32x4 UtVec;
+    static constexpr int UT_PIECES = 4, UT_REGS = 4;
+    static __device__ __forceinline__ UtVec ut_pack(const f32x16& acc, int p) {
+        return UtVec{acc[4 * p], acc[4 * p + 1], acc[4 * p + 2], acc[4 * p + 3]};
+    }
+    static __device__ __forceinline__ void ut_unpack(const UtVec& x, f32x16& acc, int p) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[4 * p + e] = x[e];
+    }
     static __device__ __forceinline__ float exp_(float x) { return expf(x); }
     static __device__ __forceinline__ float log_(float x) { return logf(x); }
 };
@@ -137,7 +155,7 @@ enum { AUX_EMIT_SLOT = 0, AUX_TOK0 = 1, AUX_LEN = 2 };
 // (from global memory, or from an LDS copy of the image without bank conflicts).  Fragment
 // numbering: (row tile rt, step s) -> rt * steps + s, a row tile being 32 rows of the operand.
 // The first STAGED_BYTES are what the recurrence kernel may copy to LDS in one linear pass;
-// the accumulator-ordered U~ (fp32) follows.
+// the accumulator-ordered U~ follows.
 template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int C = 64;
     typedef typename Elem<E>::Frag Frag;
@@ -157,9 +175,9 @@ template <typename E, int DK, int DV> struct UnitLayout {
     static constexpr int Q_OFF = CHAIN_BYTES;
     static constexpr int P_OFF = Q_OFF + Q_BYTES;
     static constexpr int STAGED_BYTES = P_OFF + P_BYTES;
-    static constexpr int UT_OFF = STAGED_BYTES;                           // U~ accumulators, fp32
-    static constexpr int UT_SLICE_BYTES = C * 32 * (int)sizeof(float);    // one 32-column slice
-    static constexpr int UNIT_BYTES = UT_OFF + C * DV * (int)sizeof(float);
+    static constexpr int UT_OFF = STAGED_BYTES;                           // U~ in accumulator order, element type E
+    static constexpr int UT_SLICE_BYTES = 2 * Elem<E>::UT_PIECES * 64 * (int)sizeof(typename Elem<E>::UtVec);   // one 32-column slice
+    static constexpr int UNIT_BYTES = UT_OFF + (DV / 32) * UT_SLICE_BYTES;
     static_assert(CHAIN_BYTES % 1024 == 0 && UT_OFF % 1024 == 0, "1 KiB pieces for wave-wide 16-byte copies");
     static_assert(STAGED_BYTES % 16 == 0 && UNIT_BYTES % 256 == 0, "vector-copy granularity");
 };

@@ -443,9 +443,10 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
             w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
     }
     // ---- U~ tile (slice sl, token tile rt): D[token][d_v] = sum_j Tb[token][j] V^T[d_v][j]
-    //      stored as the recurrence kernel's accumulators: [sl][rt][b][lane] float4
+    //      stored in the recurrence kernel's accumulator order: [sl][rt][piece][lane], 16 bytes each
     {
-        f32x4* ut = reinterpret_cast<f32x4*>(unit + U::UT_OFF);
+        typedef typename EL::UtVec UtVec;
+        UtVec* ut = reinterpret_cast<UtVec*>(unit + U::UT_OFF);
         for (int p = wave; p < (DV / 32) * 2; p += 4) {
             const int sl = p % (DV / 32), rt = p / (DV / 32);
             f32x16 acc = {0};
@@ -456,10 +457,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
             for (int s = 0; s < NKC; ++s)
                 if (s < ns) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                f32x4 o4 = {acc[4 * b], acc[4 * b + 1], acc[4 * b + 2], acc[4 * b + 3]};
-                ut[((sl * 2 + rt) * 4 + b) * 64 + lane] = o4;
-            }
+            for (int pc = 0; pc < EL::UT_PIECES; ++pc) ut[((sl * 2 + rt) * EL::UT_PIECES + pc) * 64 + lane] = EL::ut_pack(acc, pc);
         }
     }
     // ---- per-token scale factors

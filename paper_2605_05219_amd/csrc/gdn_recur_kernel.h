@@ -211,15 +211,13 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         // U~ (this slice), already in accumulator order
         f32x16 accU[2];
         {
-            const f32x4* ut = reinterpret_cast<const f32x4*>(unit + U::UT_OFF);
+            typedef typename EL::UtVec UtVec;
+            const UtVec* ut = reinterpret_cast<const UtVec*>(unit + U::UT_OFF);
 #pragma unroll
             for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 x = ut[((sl * 2 + rt) * 4 + b) * 64 + lane];
-                    accU[rt][4 * b] = x[0]; accU[rt][4 * b + 1] = x[1];
-                    accU[rt][4 * b + 2] = x[2]; accU[rt][4 * b + 3] = x[3];
-                }
+                for (int pc = 0; pc < EL::UT_PIECES; ++pc)
+                    EL::ut_unpack(ut[((sl * 2 + rt) * EL::UT_PIECES + pc) * 64 + lane], accU[rt], pc);
         }
 
         // state as the B operand of the two products that contract over d_k
@@ -332,6 +330,8 @@ __device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg
     constexpr int NKD = U::NKD;
     constexpr int NKC = U::NKC;
     constexpr int MT = DK / 32;
+    typedef typename EL::UtVec UtVec;
+    constexpr int NUT = 2 * EL::UT_PIECES;   // 16-byte pieces of a slice's U~ per lane
 
     extern __shared__ __align__(16) char smem[];
 
@@ -434,15 +434,11 @@ __device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg
         f32x16 accU[2];
         {
             const Frag* w_ = reinterpret_cast<const Frag*>(smem + U::W_OFF) + lane;
-            const f32x4* ut_ = reinterpret_cast<const f32x4*>(smem + SM::UT_OFF) + lane;
+            const UtVec* ut_ = reinterpret_cast<const UtVec*>(smem + SM::UT_OFF) + lane;
 #pragma unroll
             for (int k = 0; k < 2 * NKD; ++k) wf[k] = w_[k * 64];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const f32x4 x = ut_[k * 64];
-                accU[k >> 2][4 * (k & 3)] = x[0]; accU[k >> 2][4 * (k & 3) + 1] = x[1];
-                accU[k >> 2][4 * (k & 3) + 2] = x[2]; accU[k >> 2][4 * (k & 3) + 3] = x[3];
-            }
+            for (int k = 0; k < NUT; ++k) EL::ut_unpack(ut_[k * 64], accU[k / EL::UT_PIECES], k % EL::UT_PIECES);
         }
         int stage = 0;
         for (int i = 0; i < n_chunks; ++i) {
@@ -537,7 +533,7 @@ __device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg
             //      in their shadow
             {
                 const Frag* w_ = reinterpret_cast<const Frag*>(st_next + U::W_OFF) + lane;
-                const f32x4* ut_ = reinterpret_cast<const f32x4*>(st_next + SM::UT_OFF) + lane;
+                const UtVec* ut_ = reinterpret_cast<const UtVec*>(st_next + SM::UT_OFF) + lane;
                 constexpr int NM = (MT - MT / 2) * NKC;           // matrix instructions left
                 constexpr int WPM = (2 * NKD + NM - 1) / NM;      // W fragments read per instruction
                 int m = 0;
@@ -550,20 +546,12 @@ __device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg
 #pragma unroll
                         for (int j = 0; j < WPM; ++j)
                             if (m * WPM + j < 2 * NKD) wf[m * WPM + j] = w_[(m * WPM + j) * 64];
-                        if (m < 8) {
-                            const f32x4 x = ut_[m * 64];
-                            accU[m >> 2][4 * (m & 3)] = x[0]; accU[m >> 2][4 * (m & 3) + 1] = x[1];
-                            accU[m >> 2][4 * (m & 3) + 2] = x[2]; accU[m >> 2][4 * (m & 3) + 3] = x[3];
-                        }
+                        if (m < NUT) EL::ut_unpack(ut_[m * 64], accU[m / EL::UT_PIECES], m % EL::UT_PIECES);
                         GDN_FENCE();
                     }
                 // (U~ pieces beyond the number of matrix instructions)
 #pragma unroll
-                for (int k = NM; k < 8; ++k) {
-                    const f32x4 x = ut_[k * 64];
-                    accU[k >> 2][4 * (k & 3)] = x[0]; accU[k >> 2][4 * (k & 3) + 1] = x[1];
-                    accU[k >> 2][4 * (k & 3) + 2] = x[2]; accU[k >> 2][4 * (k & 3) + 3] = x[3];
-                }
+                for (int k = NM; k < NUT; ++k) EL::ut_unpack(ut_[k * 64], accU[k / EL::UT_PIECES], k % EL::UT_PIECES);
             }
             // checkpoint emission: exact state after the last token of this chunk
             if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
