@@ -36,8 +36,9 @@ FLOP_RECUR = 6 * D * D + 2 * C * D          # W S^T, Q S^T, state update (2 d_k 
 BYTES_TOKEN_HEAD = (2 * D + D) * 2 + 2 * 2 + D * 4
 # measured HBM bytes per token.head of a call (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/), by launch
 # kind: the first slab's preparation launch; the recurrence launches, which also prepare every later slab
-TRAFFIC_PREP = 319 + 545       # read + written
-TRAFFIC_RECUR = 1927 + 1503
+TRAFFIC_PREP = 319 + 444       # read + written
+TRAFFIC_RECUR = 1671 + 1347
+SLAB_TOKENS = 32 * C           # the latency variant's slab at 16 chains (checked against the launch count below)
 PEAK_MFMA_TFLOPS = 2500.0                   # dense fp16/bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
 
@@ -158,15 +159,21 @@ def main() -> int:
 
     if not args.no_kernel_events:
         # A step prepares its first slab (32 chunk rounds) in a launch of its own; every recurrence launch
-        # but the last also prepares the next slab (gdn_quad_overlap_kernel).  The roofline object prices the
-        # recurrence launches at the recurrence's flops alone (the preparation they carry is not counted).
+        # but the last also prepares the next slab (gdn_quad_overlap_kernel).  The recurrence launches are
+        # therefore priced at the recurrence's flops of every token plus the preparation's flops of the
+        # tokens beyond the first slab; the preparation launches at the first slab's preparation flops.
+        step_suffix = [suffix[i % N_DRAWS] for i in range(args.steps)]
+        slabs_ok = recur_n == sum(-(-t // SLAB_TOKENS) for t in step_suffix) and prep_n == args.steps
+        later = sum(max(0, t - SLAB_TOKENS) for t in step_suffix) * HEADS if slabs_ok else 0
+        first = token_heads - later
         rec_dom = recur_ms >= prep_ms
-        dom = "gdn_recur_kernel" if rec_dom else "gdn_prep_kernel"
+        dom = "recurrence launches (gdn_quad_overlap_kernel, gdn_recur_quad_kernel)" if rec_dom else "gdn_prep_kernel"
         dom_ms, dom_n = (recur_ms, recur_n) if rec_dom else (prep_ms, prep_n)
-        dom_flop = FLOP_RECUR if rec_dom else FLOP_PREP
+        dom_flops_total = token_heads * FLOP_RECUR + later * FLOP_PREP if rec_dom else first * FLOP_PREP
+        dom_flop = dom_flops_total / token_heads
         dom_traffic = TRAFFIC_RECUR if rec_dom else TRAFFIC_PREP
         units_per_launch = token_heads / dom_n
-        achieved = units_per_launch * dom_flop / (dom_ms / dom_n * 1e-3) / 1e12
+        achieved = dom_flops_total / (dom_ms * 1e-3) / 1e12
         out["roofline"] = {
             "bound": "mfma", "kernel": dom,
             "achieved": achieved, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
@@ -182,10 +189,11 @@ def main() -> int:
         out["kernels"] = {
             "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps, "launches": prep_n,
                                 "avg_launch_ms": prep_ms / max(prep_n, 1),
-                                "tflops": token_heads * FLOP_PREP / (prep_ms * 1e-3) / 1e12},
+                                "tflops": first * FLOP_PREP / (prep_ms * 1e-3) / 1e12},
             "gdn_recur_kernel": {"avg_ms": recur_ms / args.steps, "launches": recur_n,
                                  "avg_launch_ms": recur_ms / max(recur_n, 1),
-                                 "tflops": token_heads * FLOP_RECUR / (recur_ms * 1e-3) / 1e12},
+                                 "tflops": (token_heads * FLOP_RECUR + later * FLOP_PREP) / (recur_ms * 1e-3) / 1e12},
+            "token_heads_prepared_in_recurrence_launches": later,
             "both_kernels_hbm_gbs_algorithmic": token_heads * BYTES_TOKEN_HEAD / ((prep_ms + recur_ms) * 1e-3) / 1e9,
             "events": "same steps, inside the timed region" if args.events_in_timed_region
                       else "immediate repeat of the timed steps",
