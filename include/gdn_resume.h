@@ -250,6 +250,16 @@ int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls,
  */
 int32_t gdn_tune_slab_rounds(int32_t rounds);
 
+/*
+ * Tuning knob (not a step of the method).  Calls with bf16 inputs, d_k = d_v = 128 and many
+ * chains are served by one fused kernel (preparation and recurrence of a chain in one
+ * workgroup, no operand image in memory) when the library estimates it to be faster than the
+ * two-kernel path.  mode 1 forces the fused kernel wherever it applies, mode 0 forbids it,
+ * mode < 0 restores the automatic choice.  Both paths meet the same tolerance; their outputs
+ * differ in rounding.  Returns the previous setting (-1 = automatic).
+ */
+int32_t gdn_tune_fused(int32_t mode);
+
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);
 

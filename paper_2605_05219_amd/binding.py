@@ -55,6 +55,8 @@ def lib():
         L.gdn_version.restype = _i32
         L.gdn_tune_slab_rounds.restype = _i32
         L.gdn_tune_slab_rounds.argtypes = [_i32]
+        L.gdn_tune_fused.restype = _i32
+        L.gdn_tune_fused.argtypes = [_i32]
         L.gdn_profile_enable.restype = _i32
         L.gdn_profile_enable.argtypes = [_i32]
         L.gdn_profile_collect.restype = _i32
@@ -87,7 +89,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
            "gdn_workspace_bytes_host", "gdn_resume_prefill_host"]
 
@@ -129,6 +131,11 @@ def gdn_version() -> int:
 def gdn_tune_slab_rounds(rounds: int) -> int:
     """Fixes the slab length in chunk rounds (<= 0: automatic); returns the previous setting."""
     return int(lib().gdn_tune_slab_rounds(int(rounds)))
+
+
+def gdn_tune_fused(mode: int) -> int:
+    """1: always the fused kernel where it applies, 0: never, < 0: automatic; returns the previous setting."""
+    return int(lib().gdn_tune_fused(int(mode)))
 
 
 def gdn_profile_enable(on: bool) -> None:

@@ -78,8 +78,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 // four consecutive d_v values, which go out as 16-byte (fp32) or 8-byte (bf16) stores, and the
 // per-token factors gam_i and the "token < n" predicate are per-lane scalars.
 // ot[tt]: tile of token tile tt (lane = token 32 tt + lr, register 4b+e = d_v 32 sl + 8b + 4g + e).
-template <int DV>
-__device__ __forceinline__ void store_o_tile(const RecurArgs& a, int64_t row0, int hv, int sl, int lr, int g, int n,
+template <int DV, typename Args>
+__device__ __forceinline__ void store_o_tile(const Args& a, int64_t row0, int hv, int sl, int lr, int g, int n,
                                              int tt, const f32x16& ot) {
     const int tok = 32 * tt + lr;
     if (tok < n) {

@@ -11,6 +11,7 @@
 #include "gdn_plan.h"
 #include "gdn_prep_kernel.h"
 #include "gdn_decode_kernel.h"
+#include "gdn_fused_kernel.h"
 #include "gdn_recur_kernel.h"
 #include "gdn_resume.h"
 
@@ -298,6 +299,49 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
     return hipGetLastError();
 }
 
+// Fused throughput kernel (bf16 inputs, d = 128): see gdn_fused_kernel.h.
+hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
+    typedef FusedSmem<128, 128> SM;
+    static int slots = 0;
+    if (slots == 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<128, 128>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+        if (e != hipSuccess) return e;
+        int dev = 0, cus = 0, per_cu = 0;
+        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<128, 128>, 256, SM::BYTES);
+        if (e != hipSuccess) return e;
+        slots = std::max(1, cus * per_cu);
+    }
+    hipLaunchKernelGGL((gdn_fused_kernel<128, 128>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
+                       stream, fa);
+    return hipGetLastError();
+}
+
+// The fused kernel serialises a chain's preparation along the chain; it pays when chains are
+// plentiful (the chip stays full: two workgroups on each of 256 compute units) and the longest
+// chain does not outlast the whole two-kernel run.  Figures measured on MI355X (bf16, d = 128):
+// 12.8 us per chunk of one chain and 0.029 us per (chunk, chain) unit of a large call in the
+// fused kernel, 0.056 us per unit in the two-kernel path; with 512 chains or fewer the
+// two-kernel path wins (0.62 against 0.79 ms at 512 chains), from 1024 chains on the fused one
+// (0.90 against 1.03 ms at 1024 chains, 26 against 45 ms at 32768).  gdn_tune_fused (or GDN_FUSED=0/1
+// in the environment) forces the choice.
+std::atomic<int32_t> g_forced_fused{-1};
+inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
+    if (s.in_dtype != GDN_BF16 || s.d_k != 128 || s.d_v != 128) return false;
+    static const int env_forced = [] {
+        const char* e = std::getenv("GDN_FUSED");
+        return e ? std::atoi(e) : -1;
+    }();
+    const int forced = g_forced_fused.load() >= 0 ? g_forced_fused.load() : env_forced;
+    if (forced >= 0) return forced != 0;
+    if (n_chains < 1024) return false;
+    const double t_two = 0.056 * (double)total_units;
+    const double t_fused = std::max(0.029 * (double)total_units, 12.8 * (double)longest_chain_chunks);
+    return t_fused < t_two;
+}
+
 // Which recurrence variant a call gets: 1 = latency variant (few chains), else the number of
 // d_v slices (waves) per workgroup of the throughput variant.
 inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
@@ -321,8 +365,10 @@ std::atomic<int32_t> g_forced_rounds{0};
 inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
     const int32_t forced = g_forced_rounds.load();
     if (forced > 0) return forced;
+    // Throughput variants: the states are carried through memory from slab to slab (d_v d_k floats per
+    // chain each way), so a slab is at least 8 rounds long whatever the budget says.
     const int64_t budget = nw == 1 ? (int64_t)48 << 20 : (int64_t)1 << 30;
-    int64_t r = std::max<int64_t>(1, budget / std::max<int64_t>(1, n_chains * unit_bytes));
+    int64_t r = std::max<int64_t>(nw == 1 ? 1 : 8, budget / std::max<int64_t>(1, n_chains * unit_bytes));
     const int64_t q = std::max<int64_t>(1, 512 / std::max<int64_t>(1, n_chains));
     r = std::max(q, r / q * q);
     return (int32_t)std::min<int64_t>(r, 1 << 16);
@@ -417,6 +463,10 @@ using namespace gdn;
 extern "C" {
 
 int32_t gdn_version(void) { return 100; }
+
+int32_t gdn_tune_fused(int32_t mode) {
+    return g_forced_fused.exchange(mode < 0 ? -1 : (mode != 0));
+}
 
 int32_t gdn_tune_slab_rounds(int32_t rounds) {
     return g_forced_rounds.exchange(rounds > 0 ? rounds : 0);
@@ -651,6 +701,8 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     ra.o_bf16 = s.o_dtype == GDN_BF16;
 
 
+    const bool use_fused = choose_fused(s, (int64_t)n_req * s.L * s.H_v, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
+
     // ---- host tier: the start states go to the staging area.  If the pool is device-accessible
     //      pinned memory, workgroups appended to the first preparation launch fetch them over
     //      PCIe while that launch computes (only the recurrence needs them); otherwise they are
@@ -664,7 +716,7 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         const bool mapped = hipPointerGetAttributes(&attr, state_src) == hipSuccess && attr.type == hipMemoryTypeHost &&
                             attr.devicePointer != nullptr;
         if (!mapped) (void)hipGetLastError();   // an unregistered pointer is not an error here
-        if (mapped) {
+        if (mapped && !use_fused) {
             pa.host_pool = static_cast<const float*>(attr.devicePointer);
             pa.host_slot_stride = src_slot_stride;
             pa.staged_slot = ra.req_order + n_req;
@@ -685,6 +737,28 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         }
         ra.state_src = staging;
         ra.src_slot_stride = slot_elems;
+    }
+
+    // ---- many chains: preparation and recurrence fused, no operand image in memory
+    if (use_fused) {
+        FusedArgs fa;
+        fa.q = q; fa.k = k; fa.v = v; fa.beta = beta; fa.gate = gate; fa.o = o;
+        fa.chunk_tok0 = pa.chunk_tok0; fa.chunk_len = pa.chunk_len; fa.chunk_emit_slot = pa.chunk_emit_slot;
+        fa.req_chunk_cu = ra.req_chunk_cu; fa.req_src_slot = ra.req_src_slot; fa.req_order = ra.req_order;
+        fa.state_src = ra.state_src; fa.state_dst = state_dst;   // (the staging area when the pool is on the host)
+        fa.src_slot_stride = ra.src_slot_stride; fa.dst_slot_stride = dst_slot_stride;
+        fa.n_chains = (int32_t)((int64_t)n_req * s.L * s.H_v);
+        fa.L = s.L; fa.H_qk = s.H_qk; fa.H_v = s.H_v;
+        fa.T_alloc = s.T_alloc;
+        fa.scale = s.scale;
+        fa.o_bf16 = s.o_dtype == GDN_BF16;
+        ProfChain prof(stream);
+        const hipError_t e = launch_fused(fa, stream);
+        if (e != hipSuccess) return hip_err(e);
+        prof.mark(1);
+        std::lock_guard<std::mutex> lock(g_prof.mu);
+        if (g_prof.on) g_prof.calls += 1;
+        return GDN_OK;
     }
 
     const int32_t mc = plan.max_chunks_per_req;

@@ -187,6 +187,33 @@ def test_short_slabs_carry_the_state_bitwise(n_req, dtype, rounds):
     assert np.array_equal(pool_auto, pool_forced)
 
 
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("H_qk,H_v,L,o_dtype", [(2, 2, 1, "f32"), (2, 4, 2, "bf16")])
+def test_fused_and_two_kernel_paths_both_meet_the_oracle(mode, H_qk, H_v, L, o_dtype):
+    """The fused kernel (one workgroup per chain, operands stay in LDS) and the two-kernel path,
+    each forced in turn, on ragged requests with unaligned starts and emits, grouped value
+    heads, stacked layers, an empty request and both output types."""
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(500 + H_v + L)
+    d = 128
+    lens = [333, 0, 65, 1, 130, 64, 700, 47]
+    starts = [0, 77, 513, 9, 128, 1000, 5, 64]
+    n_slots = 30
+    pool = (rng.standard_normal((n_slots, L, H_v, d, d)) * 0.5).astype(np.float32)
+    src = [-1, 3, 5, 5, -1, 7, 2, 1]
+    emits = [[64, 100, 333], [], [513 + 65], [10], [128 + 64, 128 + 128, 128 + 130], [], [5 + 700], [64 + 47]]
+    per = [wl.token_streams(rng, L, n, H_qk, H_v, d, d, "bf16", "slow") for n in lens]
+    slots, nxt = [], 10
+    for e in emits:
+        slots.append(list(range(nxt, nxt + len(e)))); nxt += len(e)
+    call = wl.pack_call(L, H_qk, H_v, d, d, "bf16", per, starts, src, emits, slots, n_slots)
+    prev = B.gdn_tune_fused(mode)
+    try:
+        check_call(call, pool, TOL["bf16"], o_dtype=o_dtype, scale=0.5)
+    finally:
+        B.gdn_tune_fused(prev)
+
+
 def test_bf16_output_and_scale():
     sc = wl.config1(orc.deepest_ckpt, seed=5, n_draws=2, N=1024, M=4, H=4, d=128)
     pool, _, _ = fill_pool_from_oracle(sc)
