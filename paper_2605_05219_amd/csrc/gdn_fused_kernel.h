@@ -183,11 +183,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
     };
 
-    // Fetching the next item's K and Q (or K, Q and V) while the current one is processed was
-    // measured: the fetch registers push the kernel over 256 registers and the spills cost more
-    // (32 ms and 39 ms on a 900 k-unit call) than the exposed loads do with a second workgroup on
-    // the compute unit to cover them (26 ms).  Modes kept for reference: 0 none, 1 K, Q, V, 2 K, Q.
-    constexpr int GDN_FUSED_PREFETCH = 0;
+    // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is
+    // processed: 25.0 against 25.8 ms on a 900 k-unit call, 0.84 against 0.91 ms on a 15 k-unit one.
+    // This only pays without spills (with 15 to 116 spilled registers the same fetch cost 32 to
+    // 39 ms): see the note on opaque lane coordinates in the item loop.  Modes: 0 none, 1 K, Q, V, 2 K, Q.
+    constexpr int GDN_FUSED_PREFETCH = 1;
     Item cur = open_chain((int)blockIdx.x);
     if (cur.chain < 0) return;
     if (GDN_FUSED_PREFETCH) fetch_kq(cur);
@@ -199,9 +199,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     bool first = true;
 
     for (;;) {
-        // The lane's coordinates are made opaque once per item: otherwise every address of the
-        // unrolled tile accesses below is hoisted out of this loop and held in a register of its
-        // own for the whole kernel (hundreds of them), which spills.
+        // The lane's coordinates are made opaque once per item (and the thread index where it is
+        // used): otherwise every address of the unrolled tile accesses below is hoisted out of
+        // this loop and held in a register of its own for the whole kernel, which spills (116
+        // registers, 2.4 times slower).
         int lane = lane_, lr = lr_, g = g_, m16 = m16_, g4 = g4_, tg = tg_, d0 = d0_, tgv = tgv_, d0v = d0v_;
         pin(lane); pin(lr); pin(g); pin(m16); pin(g4); pin(tg); pin(d0); pin(tgv); pin(d0v);
         const int c = cur.c;
@@ -395,7 +396,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         //      from (a row of 68 floats holds both 64-element fp16 rows); the tile above the
         //      diagonal tiles is never written and is taken as zero here.  P's fragments go to X.
         {
-            const int i = tid >> 2, j0 = (tid & 3) * 16;
+            int tid_p = tid;
+            pin(tid_p);
+            const int i = tid_p >> 2, j0 = (tid_p & 3) * 16;
             float tb[16], tn[16];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
