@@ -25,6 +25,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Makes a value opaque to the optimiser at this point (an empty statement that "modifies" it).
+// Two uses: pure arithmetic stays where it is written, next to the matrix instruction it is
+// meant to hide under (the statement is ordered with the scheduling fences); and addresses
+// derived from an opaque coordinate cannot be hoisted out of a loop into registers of their own.
+template <typename T>
+__device__ __forceinline__ void pin(T& x) { asm volatile("" : "+v"(x)); }
+
 // Output row (within a 32x32 tile) held by accumulator register idx of half-wave g.
 __device__ __forceinline__ int acc_row(int idx, int g) { return 8 * (idx >> 2) + 4 * g + (idx & 3); }
 

@@ -127,10 +127,10 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63;
+    const int lane_ = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
-    const int lr = lane & 31;
-    const int g = lane >> 5;
+    const int lr_ = lane_ & 31;
+    const int g_ = lane_ >> 5;
     constexpr int SPT = EL::STEPS_PER_TILE;
     const In* const qg = reinterpret_cast<const In*>(a.q);
     const In* const kg = reinterpret_cast<const In*>(a.k);
@@ -162,8 +162,8 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     // A thread owns 4-token x 8-column blocks of K, Q and V.
     constexpr int KB = (C / 4) * (DK / 8), VB = (C / 4) * (DV / 8);   // blocks of K (and Q), of V
     static_assert(KB <= 256 && VB <= 256, "one block per thread at most");
-    const int tg = tid / (DK / 8), d0 = (tid % (DK / 8)) * 8;
-    const int tgv = tid / (DV / 8), d0v = (tid % (DV / 8)) * 8;
+    const int tg_ = tid / (DK / 8), d0_ = (tid % (DK / 8)) * 8;
+    const int tgv_ = tid / (DV / 8), d0v_ = (tid % (DV / 8)) * 8;
     typedef typename EL::Raw8 Raw8;
     // (16-bit inputs only: the fp32 fetch registers would not fit next to the working set)
     constexpr bool PREFETCH = sizeof(In) == 2;
@@ -174,9 +174,9 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int i = 4 * tg + r;
+            const int i = 4 * tg_ + r;
             if (tid < KB && i < it.n) {
-                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0;
+                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0_;
                 kraw[r] = EL::load_raw(kg + off);
                 qraw[r] = EL::load_raw(qg + off);
             } else {
@@ -190,12 +190,12 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int iv = 4 * tgv + r;
-            if (tid < VB && iv < it.n) vraw[r] = EL::load_raw(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v);
+            const int iv = 4 * tgv_ + r;
+            if (tid < VB && iv < it.n) vraw[r] = EL::load_raw(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v_);
             else vraw[r] = EL::zero_raw();
         }
-        if (wave == 0 && lane < it.n) {
-            const int64_t gi = (row0 + lane) * a.H_v + hv;
+        if (wave == 0 && lane_ < it.n) {
+            const int64_t gi = (row0 + lane_) * a.H_v + hv;
             graw = reinterpret_cast<const In*>(a.gate)[gi];
             braw = reinterpret_cast<const In*>(a.beta)[gi];
         }
@@ -211,6 +211,11 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     Item nxt = locate(cur.u + n_prep_wgs);
 
   for (;;) {
+    // The thread's coordinates are made opaque once per item: otherwise every address of the
+    // unrolled tile accesses below is hoisted out of this loop and held in a register of its
+    // own for the whole kernel.
+    int tid_p = tid, lane = lane_, lr = lr_, g = g_, tg = tg_, d0 = d0_, tgv = tgv_, d0v = d0v_;
+    pin(tid_p); pin(lane); pin(lr); pin(g); pin(tg); pin(d0); pin(tgv); pin(d0v);
     const int c = cur.c;
     const int lh = cur.lh;
     const int tok0 = cur.tok0;
@@ -244,7 +249,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E; the transposed
     //      copy goes out as 4-token runs.  V stays in registers; its transposed tile takes K's
     //      place once K is dead.
-    if (tid < KB) {
+    if (tid_p < KB) {
         float kv[4][8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -317,7 +322,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     __syncthreads();  // L is complete; K, Q in LDS are dead
 
     // ---- V^T into K's place (read by the last product, several barriers from here)
-    if (tid < VB) {
+    if (tid_p < VB) {
         float vv[4][8];
 #pragma unroll
         for (int r = 0; r < 4; ++r) EL::unpack(vraw[r], vv[r]);
@@ -404,7 +409,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
 
     // ---- Tb = T diag(b), Tbg = -T diag(b gam), converted to E (region B; Q is dead)
     {
-        const int i = tid >> 2, j0 = (tid & 3) * 16;
+        const int i = tid_p >> 2, j0 = (tid_p & 3) * 16;
 #pragma unroll
         for (int jj = 0; jj < 16; jj += 4) {
             float tb[4], tn[4];
@@ -463,9 +468,9 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     // ---- per-token scale factors
     {
         float* aux = reinterpret_cast<float*>(unit + U::AUX_OFF);
-        if (tid < C) aux[tid] = gamS[tid];
-        else if (tid < 2 * C) aux[tid] = decS[tid - C];
-        else if (tid == 2 * C) {
+        if (tid_p < C) aux[tid_p] = gamS[tid_p];
+        else if (tid_p < 2 * C) aux[tid_p] = decS[tid_p - C];
+        else if (tid_p == 2 * C) {
             // the chunk's bookkeeping rides along, so the recurrence never waits on a lookup
             int32_t* meta = reinterpret_cast<int32_t*>(aux + 2 * C);
             meta[AUX_EMIT_SLOT] = a.chunk_emit_slot[c];

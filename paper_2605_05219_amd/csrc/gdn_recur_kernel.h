@@ -35,11 +35,6 @@ struct RecurArgs {
     int32_t o_bf16;
 };
 
-// Keeps a value's computation where it is written: the empty statement is opaque to the
-// optimiser and ordered with the scheduling fences, so pure arithmetic cannot drift away from
-// the matrix instruction it is meant to hide under.
-template <typename T>
-__device__ __forceinline__ void pin(T& x) { asm volatile("" : "+v"(x)); }
 
 // S^T tiles of one slice <-> the [d_v][d_k] fp32 state in a pool slot: register 4b+e of tile mt
 // holds S[32 sl + lr][32 mt + 8b + 4g + e], i.e. 16-byte runs along d_k.
