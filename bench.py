@@ -9,7 +9,8 @@ stores every downstream checkpoint state to fresh pool slots.  Steps cycle throu
 list of seeded draws.  Inputs are resident in HBM before the timed region; the timed region
 covers the whole call per step (host planning, plan upload, both kernels).
 
-Prints ONE JSON line; see the design doc for the roofline accounting.
+Prints ONE JSON line.  Roofline accounting: algorithmic flops (dense tiles of the chunked form) of the launches
+that run the recurrence, over their HIP-event time, against the fp16 MFMA peak.
 """
 from __future__ import annotations
 
