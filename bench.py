@@ -333,6 +333,17 @@ def main() -> int:
     except Exception as exc:
         out["decode_step"] = {"error": str(exc)}
 
+    # ---- side measurement: what this chip delivers (fp16 matrix-instruction loop, plain 1 GiB copy), as context
+    #      for the data-sheet peaks the roofline is priced against
+    try:
+        scratch = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+        tf, gbs = B.gdn_probe_ceilings(scratch)
+        out["ceilings"] = {"mfma_f16_TFLOPs": tf, "copy_GBs": gbs, "copy_bytes_each_way": scratch.numel() // 2,
+                           "note": "measured by gdn_probe_ceilings on this device; data-sheet: 2500 TFLOP/s, 8000 GB/s"}
+        del scratch
+    except Exception as exc:
+        out["ceilings"] = {"error": str(exc)}
+
     # ---- the oracle on the host cores, same workload (all draws once)
     if not args.no_cpu_baseline:
         from oracle import gdn_oracle as orc

@@ -240,6 +240,18 @@ int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls,
                             int64_t *prep_launches, int64_t *recur_launches);
 
 /*
+ * Machine ceilings for benchmarks (not a step of the method), measured on the current device:
+ * the rate of a loop of fp16 matrix instructions (v_mfma_f32_32x32x16_f16, two workgroups of
+ * four waves per compute unit) in TFLOP/s, and of a plain 16-byte copy of scratch_bytes / 2
+ * bytes from the first half of `scratch` to the second in GB/s (bytes read + written).
+ * scratch: device memory, 16-byte aligned, at least 1 MiB, overwritten; a copy figure that
+ * means memory bandwidth needs a scratch far larger than the caches (GiB).  Blocks the host
+ * until the measurement is done; either output pointer may be NULL.
+ */
+int32_t gdn_probe_ceilings(void *scratch, int64_t scratch_bytes, double *mfma_f16_tflops,
+                           double *copy_gbs, void *stream);
+
+/*
  * Tuning knob (not a step of the method).  gdn_resume_prefill works through a call slab by
  * slab: up to `rounds` consecutive 64-token chunks of every request are prepared, then
  * consumed by the recurrence, then the next slab follows, the states carried in the workspace.

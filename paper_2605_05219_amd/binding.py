@@ -61,6 +61,8 @@ def lib():
         L.gdn_profile_enable.argtypes = [_i32]
         L.gdn_profile_collect.restype = _i32
         L.gdn_profile_collect.argtypes = [_vp, _vp, _vp, _vp, _vp]
+        L.gdn_probe_ceilings.restype = _i32
+        L.gdn_probe_ceilings.argtypes = [_vp, _i64, _vp, _vp, _vp]
         L.gdn_deepest_ckpt.restype = _i32
         L.gdn_deepest_ckpt.argtypes = [_vp, _i32, _i32]
         L.gdn_plan_chunks.restype = _i32
@@ -89,7 +91,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_profile_enable", "gdn_profile_collect", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_profile_enable", "gdn_profile_collect", "gdn_probe_ceilings", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
            "gdn_workspace_bytes_host", "gdn_resume_prefill_host"]
 
@@ -149,6 +151,14 @@ def gdn_profile_collect():
     _check(lib().gdn_profile_collect(ctypes.byref(a), ctypes.byref(b), ctypes.byref(n), ctypes.byref(pl), ctypes.byref(rl)),
            "gdn_profile_collect")
     return a.value, b.value, n.value, pl.value, rl.value
+
+
+def gdn_probe_ceilings(scratch, stream=None):
+    """(fp16 matrix-instruction TFLOP/s, plain copy GB/s over half of `scratch`) measured on the current device."""
+    a, b = ctypes.c_double(0), ctypes.c_double(0)
+    _check(lib().gdn_probe_ceilings(_dp(scratch), int(scratch.numel() * scratch.element_size()), ctypes.byref(a), ctypes.byref(b),
+                                    _stream_ptr(stream)), "gdn_probe_ceilings")
+    return a.value, b.value
 
 
 def gdn_deepest_ckpt(pos: Sequence[int], t: int) -> int:

@@ -12,6 +12,7 @@
 #include "gdn_prep_kernel.h"
 #include "gdn_decode_kernel.h"
 #include "gdn_fused_kernel.h"
+#include "gdn_probe_kernel.h"
 #include "gdn_recur_kernel.h"
 #include "gdn_resume.h"
 
@@ -505,6 +506,54 @@ int32_t gdn_profile_collect(double* prep_ms, double* recur_ms, int64_t* calls, i
     if (prep_launches) *prep_launches = g_prof.launches[0];
     if (recur_launches) *recur_launches = g_prof.launches[1];
     return GDN_OK;
+}
+
+int32_t gdn_probe_ceilings(void* scratch, int64_t scratch_bytes, double* mfma_f16_tflops, double* copy_gbs,
+                           void* stream_v) {
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (!scratch) return GDN_ERR_NULL;
+    if (!aligned16(scratch)) return GDN_ERR_ALIGN;
+    if (scratch_bytes < (1 << 20)) return GDN_ERR_WORKSPACE;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_err(e);
+    const int blocks = std::max(1, cus) * 2;   // two workgroups of four waves per compute unit
+    if (scratch_bytes < (int64_t)blocks * PROBE_THREADS * (int64_t)sizeof(float)) return GDN_ERR_WORKSPACE;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    for (auto& x : ev)
+        if ((e = hipEventCreate(&x)) != hipSuccess) return hip_err(e);
+    auto timed = [&](auto&& launch, int reps, double* ms) -> hipError_t {
+        launch();   // warm-up
+        hipError_t r = hipEventRecord(ev[0], stream);
+        if (r != hipSuccess) return r;
+        for (int i = 0; i < reps; ++i) launch();
+        if ((r = hipGetLastError()) != hipSuccess) return r;
+        if ((r = hipEventRecord(ev[1], stream)) != hipSuccess) return r;
+        if ((r = hipEventSynchronize(ev[1])) != hipSuccess) return r;
+        float t = 0.f;
+        r = hipEventElapsedTime(&t, ev[0], ev[1]);
+        *ms = (double)t / reps;
+        return r;
+    };
+    double ms = 0.0;
+    const int iters = 4096;
+    e = timed([&] { hipLaunchKernelGGL(probe_mfma_kernel, dim3(blocks), dim3(PROBE_THREADS), 0, stream,
+                                       reinterpret_cast<float*>(scratch), iters); }, 3, &ms);
+    if (e == hipSuccess && mfma_f16_tflops) {
+        const double flop = (double)blocks * (PROBE_THREADS / 64) * iters * PROBE_MFMA_PER_ITER * (2.0 * 32 * 32 * 16);
+        *mfma_f16_tflops = flop / (ms * 1e-3) / 1e12;
+    }
+    if (e == hipSuccess) {
+        const int64_t half = scratch_bytes / 2 / 16 * 16;
+        const float4* src = reinterpret_cast<const float4*>(scratch);
+        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<char*>(scratch) + half);
+        e = timed([&] { hipLaunchKernelGGL(probe_copy_kernel, dim3(8192), dim3(PROBE_THREADS), 0, stream, src, dst, half / 16); },
+                  5, &ms);
+        if (e == hipSuccess && copy_gbs) *copy_gbs = 2.0 * (double)half / (ms * 1e-3) / 1e9;
+    }
+    for (auto& x : ev) (void)hipEventDestroy(x);
+    return e == hipSuccess ? GDN_OK : hip_err(e);
 }
 
 int32_t gdn_deepest_ckpt(const int32_t* pos, int32_t M, int32_t t) {

@@ -472,3 +472,14 @@ def test_prefill_from_host_pool_equals_prefill_from_device_pool(n_req, pinned):
     assert max_norm_err(o_dev, o_ref[:, :call.total_tokens]) <= TOL["bf16"]
     for e, s in enumerate(call.emit_slot):
         assert max_norm_err(st_dev[s], st_ref[e]) <= TOL["bf16"]
+
+
+@pytest.mark.gpu
+def test_probe_ceilings_reports_plausible_machine_rates():
+    """The probe's figures lie between a fifth of the data-sheet peaks and the peaks themselves."""
+    import torch
+    from paper_2605_05219_amd import binding as B
+    scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    tf, gbs = B.gdn_probe_ceilings(scratch)
+    assert 500.0 < tf < 2600.0, tf
+    assert 1600.0 < gbs < 8100.0, gbs

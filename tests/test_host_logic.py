@@ -288,3 +288,12 @@ def test_host_tier_workspace_is_the_device_one_plus_staging():
     shape = B.make_shape(1, 16, 16, 128, 128, "bf16", "f32", 8192)
     base = B.gdn_workspace_bytes(shape, 3, 8192, 16)
     assert B.gdn_workspace_bytes_host(shape, 3, 8192, 16) == (base + 255) // 256 * 256 + 3 * 16 * 128 * 128 * 4
+
+
+@pytest.mark.parametrize("dev,code", [(FakeDev(ptr=0), -1), (FakeDev(ptr=0x10004), -2), (FakeDev(nbytes=1 << 19), -9)])
+def test_probe_ceilings_argument_errors(monkeypatch, dev, code):
+    """The machine-ceiling probe rejects a null, misaligned or too small scratch before touching the device."""
+    monkeypatch.setattr(B, "_stream_ptr", lambda s=None: ctypes.c_void_p(0))
+    with pytest.raises(B.GdnError) as ei:
+        B.gdn_probe_ceilings(dev)
+    assert ei.value.code == code
