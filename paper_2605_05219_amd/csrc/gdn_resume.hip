@@ -8,6 +8,7 @@
 #include <mutex>
 #include <vector>
 
+#include "gdn_host.h"
 #include "gdn_plan.h"
 #include "gdn_prep_kernel.h"
 #include "gdn_decode_kernel.h"
@@ -106,7 +107,10 @@ struct Staging {
 };
 Staging g_staging;
 
-// Copies `bytes` from `src` into pinned memory and enqueues its upload to `dst`.
+}  // namespace
+
+// Copies `bytes` from `src` into pinned memory and enqueues its upload to `dst` (declared in gdn_host.h:
+// the layer front end uploads its index arrays the same way).
 int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(g_staging.mu);
     Staging& s = g_staging;
@@ -136,6 +140,8 @@ int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream
     s.pending = true;
     return GDN_OK;
 }
+
+namespace {
 
 // ------------------------------------------------------------------ optional per-kernel timing
 // When switched on, the kernel launches of a prefill call are separated by events on the

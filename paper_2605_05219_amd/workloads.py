@@ -388,3 +388,73 @@ def config4_call(seed: int = 1004, n_req: int = 256, L: int = 8, H: int = 16, d:
     assert nxt <= n_slots, "pool too small"
     return pack_call(L, H, H, d, d, dtype, per_req, starts, src, elists, eslots, n_slots,
                      {"kind": "serving", "config": "config4", "lens": [int(x) for x in lens]})
+
+
+# ----------------------------------------------------------------------------- layer front/back end inputs
+@dataclass
+class LayerCase:
+    """Seeded inputs of the layer's elementwise front and back ends for a packed batch of resumed
+    requests (storage dtype for activations and convolution states, fp32 parameters).  Draws only:
+    pre-activations ~ N(0,1), taps ~ N(0, 0.5^2), small biases, A_log ~ U(log 0.5, log 4),
+    dt_bias ~ N(0, 0.5^2), norm weight 1 + 0.1 N(0,1); they stand in for the projections of the
+    model the paper measures (Sec. 5, runtime experiment), whose weights are not available."""
+    H_qk: int
+    H_v: int
+    d_k: int
+    d_v: int
+    K: int
+    dtype: str
+    x_qkv: np.ndarray        # [T][C]
+    conv_w: np.ndarray       # fp32 [C][K]
+    conv_b: np.ndarray       # fp32 [C]
+    a_pre: np.ndarray        # [T][H_v]
+    b_pre: np.ndarray
+    A_log: np.ndarray        # fp32 [H_v]
+    dt_bias: np.ndarray
+    z: np.ndarray            # [T][H_v][d_v]
+    o: np.ndarray            # fp32 [T][H_v][d_v]: stands in for the recurrence output
+    norm_w: np.ndarray       # fp32 [d_v]
+    conv_pool: np.ndarray    # [n_slots][K-1][C]: stored convolution states (random rows: any rows are legal inputs)
+    cu_seqlens: np.ndarray
+    start_pos: np.ndarray
+    src_slot: np.ndarray
+    emit_cu: np.ndarray
+    emit_pos: np.ndarray
+    emit_slot: np.ndarray
+
+    @property
+    def C(self) -> int:
+        return 2 * self.H_qk * self.d_k + self.H_v * self.d_v
+
+    @property
+    def T(self) -> int:
+        return int(self.cu_seqlens[-1])
+
+
+def layer_case(seed: int, H_qk: int, H_v: int, d_k: int, d_v: int, K: int, dtype: str, lens: Sequence[int],
+               starts: Sequence[int], emits: Sequence[Sequence[int]], n_src_slots: int = 4) -> LayerCase:
+    """lens[r] tokens from position starts[r]; starts[r] == 0 resumes from nothing (slot -1), otherwise from a
+    random source slot; emits[r] are absolute positions in (starts[r], starts[r] + lens[r]]; destination slots
+    are fresh ids after the source slots."""
+    rng = np.random.default_rng(seed)
+    C = 2 * H_qk * d_k + H_v * d_v
+    T = int(sum(lens))
+
+    def normal(*shape, s=1.0):
+        return (rng.standard_normal(shape, dtype=np.float32) * np.float32(s)).astype(np.float32)
+
+    cu = np.zeros(len(lens) + 1, np.int32)
+    cu[1:] = np.cumsum(lens)
+    ecu = np.zeros(len(lens) + 1, np.int32)
+    ecu[1:] = np.cumsum([len(e) for e in emits])
+    epos = np.asarray([p for e in emits for p in e], np.int32)
+    src = np.asarray([-1 if s == 0 else int(rng.integers(0, n_src_slots)) for s in starts], np.int32)
+    eslot = (n_src_slots + rng.permutation(max(int(epos.size), 1))[:epos.size]).astype(np.int32)
+    return LayerCase(
+        H_qk, H_v, d_k, d_v, K, dtype,
+        to_storage(normal(T, C), dtype), normal(C, K, s=0.5), normal(C, s=0.1),
+        to_storage(normal(T, H_v), dtype), to_storage(normal(T, H_v), dtype),
+        rng.uniform(np.log(0.5), np.log(4.0), H_v).astype(np.float32), normal(H_v, s=0.5),
+        to_storage(normal(T, H_v, d_v), dtype), normal(T, H_v, d_v), (1.0 + normal(d_v, s=0.1)).astype(np.float32),
+        to_storage(normal(n_src_slots + max(int(epos.size), 1), K - 1, C), dtype),
+        cu, np.asarray(starts, np.int32), src, ecu, epos, eslot)
