@@ -333,6 +333,53 @@ def main() -> int:
     except Exception as exc:
         out["decode_step"] = {"error": str(exc)}
 
+    # ---- layer front end (short convolution + SiLU + q/k norm + gates, resumed from stored convolution states) and
+    #      back end (gated output norm): memory bound; 32 requests x 2048 tokens of this layer shape, bf16
+    try:
+        from paper_2605_05219_amd import layer as LY
+        n_rq, ln = 32, 2048
+        Tl, Cl = n_rq * ln, 3 * HEADS * D
+        lsh = LY.make_layer_shape(HEADS, HEADS, D, D, 4, "bf16", "bf16", "f32")
+        bf = lambda *sh: torch.randn(sh, device=dev).bfloat16()
+        xq, ap, bp, zz = bf(Tl, Cl), bf(Tl, HEADS), bf(Tl, HEADS), bf(Tl, HEADS, D)
+        cw, cb = torch.randn((Cl, 4), device=dev) * 0.5, torch.randn(Cl, device=dev) * 0.1
+        Al, dtb, nw = torch.zeros(HEADS, device=dev), torch.zeros(HEADS, device=dev), torch.ones(D, device=dev)
+        cpool = bf(2 * n_rq, 3, Cl)
+        lq, lk, lv = (torch.empty((Tl, HEADS, D), dtype=torch.bfloat16, device=dev) for _ in range(3))
+        lb, lg = (torch.empty((Tl, HEADS), dtype=torch.bfloat16, device=dev) for _ in range(2))
+        lo_ = torch.randn((Tl, HEADS, D), device=dev)
+        ly = torch.empty((Tl, HEADS, D), dtype=torch.bfloat16, device=dev)
+        lcu = np.arange(n_rq + 1, dtype=np.int32) * ln
+        lst = np.full(n_rq, 4096, np.int32)
+        lws = torch.empty(LY.gdn_layer_workspace_bytes(n_rq, n_rq), dtype=torch.uint8, device=dev)
+
+        def front():
+            LY.gdn_layer_inputs(lsh, xq, cw, cb, ap, bp, Al, dtb, lcu, lst, cpool, np.arange(n_rq, dtype=np.int32),
+                                np.arange(n_rq + 1, dtype=np.int32), lst + ln, cpool, n_rq + np.arange(n_rq, dtype=np.int32),
+                                lq, lk, lv, lb, lg, lws)
+
+        def back():
+            LY.gdn_layer_output(lsh, lo_, zz, nw, ly, Tl)
+
+        res = {}
+        for name, fn, nbytes in (("inputs", front, Tl * (2 * Cl * 2 + 4 * HEADS * 2)), ("output", back, Tl * HEADS * D * (4 + 2 + 2))):
+            for _ in range(3):
+                fn()
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            reps = 20
+            ev[0].record()
+            for _ in range(reps):
+                fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / reps
+            res[name] = {"ms": ms, "bytes_read_and_written": nbytes, "gbs": nbytes / (ms * 1e-3) / 1e9}
+        out["layer_io"] = {"tokens": Tl, "requests": n_rq, "channels": Cl, "peak_gbs": PEAK_HBM_GBS, **res,
+                           "note": "gdn_layer_inputs / gdn_layer_output, bf16 activations, fp32 o; algorithmic bytes"}
+        del xq, zz, lq, lk, lv, lo_, ly, cpool
+    except Exception as exc:
+        out["layer_io"] = {"error": str(exc)}
+
     # ---- side measurement: what this chip delivers (fp16 matrix-instruction loop, plain 1 GiB copy), as context
     #      for the data-sheet peaks the roofline is priced against
     try:

@@ -62,15 +62,17 @@ __device__ __forceinline__ F8 load8(const float* p) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
     return F8{{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
 }
-__device__ __forceinline__ uint32_t bf16_rne(float x) {   // round to nearest even; inputs are finite
-    const uint32_t u = __float_as_uint(x);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, b);
 }
 __device__ __forceinline__ void store8(uint16_t* p, const F8& v) {
-    uint32_t u[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) u[i] = bf16_rne(v.f[2 * i]) | (bf16_rne(v.f[2 * i + 1]) << 16);
-    *reinterpret_cast<uint4*>(p) = make_uint4(u[0], u[1], u[2], u[3]);
+    *reinterpret_cast<uint4*>(p) = make_uint4(pack_bf16(v.f[0], v.f[1]), pack_bf16(v.f[2], v.f[3]), pack_bf16(v.f[4], v.f[5]),
+                                              pack_bf16(v.f[6], v.f[7]));
 }
 __device__ __forceinline__ void store8(float* p, const F8& v) {
     reinterpret_cast<float4*>(p)[0] = make_float4(v.f[0], v.f[1], v.f[2], v.f[3]);
@@ -78,17 +80,45 @@ __device__ __forceinline__ void store8(float* p, const F8& v) {
 }
 __device__ __forceinline__ float load1(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
 __device__ __forceinline__ float load1(const float* p) { return *p; }
-__device__ __forceinline__ void store1(uint16_t* p, float x) { *p = (uint16_t)bf16_rne(x); }
+__device__ __forceinline__ void store1(uint16_t* p, float x) { *p = (uint16_t)(pack_bf16(x, 0.f) & 0xffffu); }
 __device__ __forceinline__ void store1(float* p, float x) { *p = x; }
 
 __device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 
-// Sum over the d/8 adjacent lanes that hold one head (8 lanes for d = 64, 16 for d = 128).
+// Raw 16-byte-granular loads of 8 elements, widened to fp32 when they are used.
+struct Raw16 { uint4 r; };
+struct Raw32 { uint4 r[2]; };
+__device__ __forceinline__ Raw16 load_raw8(const uint16_t* p) { return Raw16{*reinterpret_cast<const uint4*>(p)}; }
+__device__ __forceinline__ Raw32 load_raw8(const float* p) {
+    return Raw32{{reinterpret_cast<const uint4*>(p)[0], reinterpret_cast<const uint4*>(p)[1]}};
+}
+__device__ __forceinline__ F8 widen8(const Raw16& x) {
+    const uint32_t u[4] = {x.r.x, x.r.y, x.r.z, x.r.w};
+    F8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o.f[2 * i] = __uint_as_float(u[i] << 16);
+        o.f[2 * i + 1] = __uint_as_float(u[i] & 0xffff0000u);
+    }
+    return o;
+}
+__device__ __forceinline__ F8 widen8(const Raw32& x) {
+    return F8{{__uint_as_float(x.r[0].x), __uint_as_float(x.r[0].y), __uint_as_float(x.r[0].z), __uint_as_float(x.r[0].w),
+               __uint_as_float(x.r[1].x), __uint_as_float(x.r[1].y), __uint_as_float(x.r[1].z), __uint_as_float(x.r[1].w)}};
+}
+
+// Sum over the d/8 adjacent lanes that hold one head (8 lanes for d = 64, 16 for d = 128), every
+// lane receiving the total: four cross-lane adds inside a 16-lane row (lane ^ 1, lane ^ 2, then
+// the mirror image inside 8 lanes and inside 16 lanes), no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float s) {
+    return s + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, s), CTRL, 0xF, 0xF, true));
+}
 __device__ __forceinline__ float head_sum(float s, int d) {
-    s += __shfl_xor(s, 1, 64);
-    s += __shfl_xor(s, 2, 64);
-    s += __shfl_xor(s, 4, 64);
-    if (d == 128) s += __shfl_xor(s, 8, 64);
+    s = dpp_add<0xB1>(s);    // quad_perm [1,0,3,2]
+    s = dpp_add<0x4E>(s);    // quad_perm [2,3,0,1]
+    s = dpp_add<0x141>(s);   // row_half_mirror: lane i <-> 7 - i of each 8
+    if (d == 128) s = dpp_add<0x140>(s);   // row_mirror: lane i <-> 15 - i of each 16
     return s;
 }
 
@@ -149,14 +179,22 @@ __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_inputs_kernel(LayerAr
         const int width = is_v ? a.C - 2 * a.nq : a.nq;
         Out* const dst = reinterpret_cast<Out*>(ch < a.nq ? a.q : (is_v ? a.v : a.k)) + (ch - base);
         const In* src = x + (row0 + t_first) * a.C + ch;
-        for (int t0 = 0; t0 < n; t0 += 4) {
-            F8 cur[4];
+        // four rows at a time; the next four are fetched (raw) while these are worked on
+        decltype(load_raw8(src)) nxt[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (t0 + u < n) cur[u] = load8(src + (int64_t)(t0 + u) * a.C);
+        for (int u = 0; u < 4; ++u) nxt[u] = load_raw8(src + (int64_t)min(u, n - 1) * a.C);
+        for (int t0 = 0; t0 < n; t0 += 4) {
+            decltype(load_raw8(src)) cur[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            if (t0 + 4 < n) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) nxt[u] = load_raw8(src + (int64_t)min(t0 + 4 + u, n - 1) * a.C);
+            }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 if (t0 + u >= n) break;   // uniform over the lanes of a head (same run)
+                const F8 xc = widen8(cur[u]);
                 F8 y;
                 float ss = 0.f;
 #pragma unroll
@@ -165,16 +203,15 @@ __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_inputs_kernel(LayerAr
                     acc = fmaf(w4[c][0], win[0].f[c], acc);
                     acc = fmaf(w4[c][1], win[1].f[c], acc);
                     acc = fmaf(w4[c][2], win[2].f[c], acc);
-                    acc = fmaf(w4[c][3], cur[u].f[c], acc);
+                    acc = fmaf(w4[c][3], xc.f[c], acc);
                     y.f[c] = silu_f(acc);
                     ss = fmaf(y.f[c], y.f[c], ss);
                 }
                 win[0] = win[1];
                 win[1] = win[2];
-                win[2] = cur[u];
-                ss = head_sum(ss, a.d_k);   // executed by every lane; used by q and k lanes only
-                if (!is_v) {
-                    const float inv = rsqrtf(ss + a.qk_eps);
+                win[2] = xc;
+                if (!is_v) {   // uniform over the lanes of a head
+                    const float inv = rsqrtf(head_sum(ss, a.d_k) + a.qk_eps);
 #pragma unroll
                     for (int c = 0; c < 8; ++c) y.f[c] *= inv;
                 }
