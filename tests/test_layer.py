@@ -224,3 +224,62 @@ def test_layer_output_matches_the_oracle(H_v, d_v, T, o_dtype, dtype, out_dtype)
     LY.gdn_layer_output(sh, to_device(o_st), to_device(c.z), to_device(c.norm_w), y, T)
     torch.cuda.synchronize()
     check_tensor(y.float().cpu().numpy().astype(np.float64), ref, out_dtype, "y")
+
+
+@pytest.mark.gpu
+def test_whole_layer_resumed_from_both_checkpointed_states_matches_the_composed_oracles():
+    """Front end -> resumed recurrence -> back end on the GPU against the composition of the two oracles, for the full
+    run and for a request resumed at p from the matrix state AND the convolution state the full run stored.
+
+    The composed reference rounds its fp64 front-end outputs to bf16 as the path does; where the GPU's fp32 front end
+    rounds an element the other way (a one-ulp difference in an input of the recurrence) the outputs move by far less
+    than the recurrence's own tolerance, so the bar is that tolerance: 2e-3 max-normalised on o, + 2^-8 on the bf16 y.
+    """
+    import torch
+    from oracle import gdn_oracle as orc
+    from tests.harness import to_device
+    H, d, K, N, p = 2, 128, 4, 300, 128
+    c = wl.layer_case(91, H, H, d, d, K, "bf16", [N], [0], [[p, N]], n_src_slots=1)
+    scale = d ** -0.5
+
+    # ---- reference: layer oracle -> bf16 -> recurrence oracle -> output oracle
+    rq, rk, rv, rb, rg, _ = oracle_inputs(c, 1e-6)
+    st = lambda a: wl.to_storage(a.astype(np.float32), "bf16")[None]
+    o_ref, S_ref = orc.resume_prefill(st(rq), st(rk), st(rv), st(rb), st(rg), [0, N], [0], [-1], [0, 2], [p, N], scale=scale)
+    y_ref = lo.output_norm_gate(o_ref[0], f64(c.z), c.norm_w, 1e-5)
+
+    def run(x_lo, start, conv_pool, conv_src, S_pool, S_src, emit_pos, conv_emit, S_emit):
+        T = N - x_lo
+        lsh = LY.make_layer_shape(H, H, d, d, K, "bf16", "bf16", "f32", 1e-6, 1e-5)
+        new = lambda *s: torch.full(s, float("nan"), dtype=torch.bfloat16, device="cuda")
+        q, k, v, beta, gate = new(1, T, H, d), new(1, T, H, d), new(1, T, H, d), new(1, T, H), new(1, T, H)
+        ws = torch.empty(max(LY.gdn_layer_workspace_bytes(1, len(emit_pos)), 256), dtype=torch.uint8, device="cuda")
+        ecu = [0, len(emit_pos)]
+        LY.gdn_layer_inputs(lsh, to_device(c.x_qkv[x_lo:]), to_device(c.conv_w), to_device(c.conv_b), to_device(c.a_pre[x_lo:]),
+                            to_device(c.b_pre[x_lo:]), to_device(c.A_log), to_device(c.dt_bias), [0, T], [start], conv_pool, [conv_src],
+                            ecu, emit_pos, conv_pool, conv_emit, q, k, v, beta, gate, ws)
+        sh = B.make_shape(1, H, H, d, d, "bf16", "f32", T, scale)
+        o = torch.full((1, T, H, d), float("nan"), dtype=torch.float32, device="cuda")
+        pws = torch.empty(max(B.gdn_workspace_bytes(sh, 1, T, len(emit_pos)), 256), dtype=torch.uint8, device="cuda")
+        B.gdn_resume_prefill(sh, q, k, v, beta, gate, [0, T], [start], S_pool, [S_src], ecu, emit_pos, S_pool, S_emit, o, pws)
+        y = new(T, H, d)
+        LY.gdn_layer_output(lsh, o, to_device(c.z[x_lo:]), to_device(c.norm_w), y, T)
+        torch.cuda.synchronize()
+        return o[0].cpu().numpy().astype(np.float64), y.float().cpu().numpy().astype(np.float64)
+
+    from tests.harness import max_norm_err
+    conv_pool = torch.zeros((4, K - 1, c.C), dtype=torch.bfloat16, device="cuda")
+    S_pool = torch.zeros((4, 1, H, d, d), dtype=torch.float32, device="cuda")
+    o_full, y_full = run(0, 0, conv_pool, -1, S_pool, -1, [p, N], [0, 1], [0, 1])
+    assert max_norm_err(o_full, o_ref[0]) <= 2e-3 and max_norm_err(y_full, y_ref) <= 2e-3 + 2.0 ** -8
+    assert max_norm_err(S_pool[0].cpu().numpy(), S_ref[0]) <= 2e-3 and max_norm_err(S_pool[1].cpu().numpy(), S_ref[1]) <= 2e-3
+    assert np.array_equal(conv_pool[0].view(torch.int16).cpu().numpy(), c.x_qkv[p - (K - 1):p].view(np.int16))
+    # ---- resumed at p from slots 0 (matrix state and convolution state), new states into slots 2
+    o_res, y_res = run(p, p, conv_pool, 0, S_pool, 0, [N], [2], [2])
+    assert max_norm_err(o_res, o_ref[0, p:]) <= 2e-3 and max_norm_err(y_res, y_ref[p:]) <= 2e-3 + 2.0 ** -8
+    assert max_norm_err(o_res[:16], o_ref[0, p:p + 16]) <= 2e-3          # where a wrong start state would show
+    assert max_norm_err(S_pool[2].cpu().numpy(), S_ref[1]) <= 2e-3
+    assert torch.equal(conv_pool[2], conv_pool[1])
+    # a resume that restores S but not the convolution rows is NOT exact: the first tokens differ visibly
+    o_bad, _ = run(p, p, conv_pool, -1, S_pool, 0, [N], [3], [3])
+    assert max_norm_err(o_bad[:K - 1], o_ref[0, p:p + K - 1]) > 1e-2
