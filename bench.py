@@ -333,6 +333,77 @@ def main() -> int:
     except Exception as exc:
         out["decode_step"] = {"error": str(exc)}
 
+    # ---- throughput regime (not the bench line): a configs[4]-shaped serving step -- 256 requests of log-uniform
+    #      suffix length through 8 independent layers x 16 heads, start states gathered by slot id from a 4096-slot
+    #      (32 GiB) pool, states stored every 1024 positions and at the end; inputs generated on the device
+    try:
+        from paper_2605_05219_amd import workloads as wl4
+        n_rq4, L4, n_slots4 = 256, 8, 4096
+        free_b, _ = torch.cuda.mem_get_info()
+        rng4 = np.random.default_rng(1004)
+        lens4 = wl4.lengths_log_uniform(rng4, n_rq4, 64, 8192)
+        starts4 = (rng4.integers(1, 64, size=n_rq4) * 128).astype(np.int32)
+        ids4 = rng4.permutation(n_slots4)
+        T4 = int(lens4.sum())
+        need4 = n_slots4 * L4 * HEADS * D * D * 4 + L4 * T4 * HEADS * (3 * D * 2 + D * 4 + 4) + (8 << 30)
+        if free_b < need4:
+            raise RuntimeError(f"needs {need4 >> 30} GiB of device memory, {free_b >> 30} free")
+        rule4 = wl4.emit_every(1024)
+        cu4 = np.concatenate([[0], np.cumsum(lens4)]).astype(np.int32)
+        epos4, ecu4, eslot4, nxt4 = [], [0], [], n_rq4
+        for r in range(n_rq4):
+            e = rule4(int(starts4[r]), int(starts4[r] + lens4[r]))
+            epos4 += e
+            ecu4.append(len(epos4))
+            eslot4 += [int(x) for x in ids4[nxt4:nxt4 + len(e)]]
+            nxt4 += len(e)
+        g4 = torch.Generator(device=dev)
+        g4.manual_seed(1004)
+        rn4 = lambda *sh: torch.randn(sh, device=dev, generator=g4, dtype=torch.float32)
+        q4 = torch.empty((L4, T4, HEADS, D), dtype=torch.bfloat16, device=dev)
+        k4, v4 = torch.empty_like(q4), torch.empty_like(q4)
+        for l in range(L4):
+            q4[l] = torch.nn.functional.normalize(rn4(T4, HEADS, D), dim=-1).bfloat16()
+            k4[l] = torch.nn.functional.normalize(rn4(T4, HEADS, D), dim=-1).bfloat16()
+            v4[l] = rn4(T4, HEADS, D).bfloat16()
+        b4 = torch.sigmoid(rn4(L4, T4, HEADS)).bfloat16()
+        a4 = torch.exp(-torch.nn.functional.softplus(rn4(L4, T4, HEADS))).bfloat16()
+        pool4 = torch.empty((n_slots4, L4, HEADS, D, D), dtype=torch.float32, device=dev)
+        for s0 in range(0, n_slots4, 256):
+            pool4[s0:s0 + 256] = rn4(256, L4, HEADS, D, D) * 0.1
+        o4 = torch.empty((L4, T4, HEADS, D), dtype=torch.float32, device=dev)
+        shape4 = B.make_shape(L4, HEADS, HEADS, D, D, "bf16", "f32", T4)
+        ws4 = torch.empty(B.gdn_workspace_bytes(shape4, n_rq4, T4, len(epos4)), dtype=torch.uint8, device=dev)
+
+        def run4():
+            B.gdn_resume_prefill(shape4, q4, k4, v4, b4, a4, cu4, starts4, pool4, ids4[:n_rq4].astype(np.int32), ecu4, epos4, pool4,
+                                 eslot4, o4, ws4)
+
+        run4()
+        torch.cuda.synchronize()
+        reps4 = 3
+        t40 = time.perf_counter()
+        for _ in range(reps4):
+            run4()
+        torch.cuda.synchronize()
+        ms4 = 1e3 * (time.perf_counter() - t40) / reps4
+        th4 = T4 * L4 * HEADS
+        bytes4 = th4 * BYTES_TOKEN_HEAD + (n_rq4 + len(epos4)) * L4 * HEADS * D * D * 4
+        out["throughput"] = {
+            "workload": "configs[4]: 256 requests x 8 layers x 16 heads, d=128, bf16, suffix ~ logU[64,8192], pool of 4096 slots",
+            "tokens_per_layer": T4, "chains": n_rq4 * L4 * HEADS, "emits": len(epos4), "ms_per_call": ms4,
+            "tokens_per_s": T4 / (ms4 * 1e-3), "token_layers_per_s": T4 * L4 / (ms4 * 1e-3),
+            "hbm": {"algorithmic_bytes": bytes4, "achieved_gbs": bytes4 / (ms4 * 1e-3) / 1e9, "peak_gbs": PEAK_HBM_GBS,
+                    "frac": bytes4 / (ms4 * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "mfma": {"achieved_tflops": th4 * (FLOP_PREP + FLOP_RECUR) / (ms4 * 1e-3) / 1e12, "peak_tflops": PEAK_MFMA_TFLOPS,
+                     "frac": th4 * (FLOP_PREP + FLOP_RECUR) / (ms4 * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
+            "note": "whole call on the host clock (planning, plan upload, kernels); the library picks the fused kernel here",
+        }
+        del q4, k4, v4, b4, a4, pool4, o4, ws4
+        torch.cuda.empty_cache()
+    except Exception as exc:
+        out["throughput"] = {"error": str(exc)}
+
     # ---- layer front end (short convolution + SiLU + q/k norm + gates, resumed from stored convolution states) and
     #      back end (gated output norm): memory bound; 32 requests x 2048 tokens of this layer shape, bf16
     try:
