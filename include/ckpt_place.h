@@ -83,6 +83,25 @@ int64_t ckpt_hist_observe(ckpt_hist *h, int32_t t);
 int32_t ckpt_hist_get(const ckpt_hist *h, double *p);
 int32_t ckpt_hist_solve(const ckpt_hist *h, int32_t M, int32_t B, int32_t *pos, double *cost);
 
+/*
+ * Sec. 5, "Our method": the online loop around the histogram.  Every observed overlap depth
+ * updates the exponentially weighted histogram (the paper uses gamma = 0.99); after every
+ * `period` observations (10 in the paper) the dynamic program is solved again on the current
+ * estimate with budget M and the result clipped to blocks of B (1 = no clipping).
+ * ckpt_online_create returns NULL on bad arguments (N, M, B, period < 1, gamma outside (0, 1]).
+ * ckpt_online_observe returns 1 when this observation triggered a re-solve (the schedule may
+ * have changed), 0 otherwise, negative on error (depth outside 1..N: GDN_ERR_COUNT).
+ * ckpt_online_schedule copies the current schedule (empty before the first re-solve) into pos
+ * (room for `capacity`) and returns its length.  ckpt_online_histogram lends the histogram for
+ * ckpt_hist_get.  Not thread safe.
+ */
+typedef struct ckpt_online ckpt_online;
+ckpt_online *ckpt_online_create(int32_t N, int32_t M, int32_t B, double gamma, int32_t period);
+void ckpt_online_destroy(ckpt_online *o);
+int32_t ckpt_online_observe(ckpt_online *o, int32_t t);
+int32_t ckpt_online_schedule(const ckpt_online *o, int32_t *pos, int32_t capacity);
+const ckpt_hist *ckpt_online_histogram(const ckpt_online *o);
+
 #ifdef __cplusplus
 }
 #endif

@@ -219,4 +219,56 @@ int32_t ckpt_hist_solve(const ckpt_hist* h, int32_t M, int32_t B, int32_t* pos, 
     return ckpt_clip_to_blocks(raw.data(), n, B, pos);
 }
 
+// ---- the online loop of Sec. 5 ("Our method"): observe, re-solve every `period` requests
+struct ckpt_online {
+    ckpt_hist* hist;
+    int32_t M, B, period;
+    std::vector<int32_t> pos;
+    int64_t solves;
+};
+
+ckpt_online* ckpt_online_create(int32_t N, int32_t M, int32_t B, double gamma, int32_t period) {
+    if (M < 1 || B < 1 || period < 1) return nullptr;
+    ckpt_hist* h = ckpt_hist_create(N, gamma);
+    if (!h) return nullptr;
+    ckpt_online* o = new (std::nothrow) ckpt_online;
+    if (!o) {
+        ckpt_hist_destroy(h);
+        return nullptr;
+    }
+    o->hist = h; o->M = M; o->B = B; o->period = period; o->solves = 0;
+    return o;
+}
+
+void ckpt_online_destroy(ckpt_online* o) {
+    if (!o) return;
+    ckpt_hist_destroy(o->hist);
+    delete o;
+}
+
+int32_t ckpt_online_observe(ckpt_online* o, int32_t t) {
+    if (!o) return GDN_ERR_NULL;
+    const int64_t n = ckpt_hist_observe(o->hist, t);
+    if (n < 0) return (int32_t)n;
+    if (n % o->period != 0) return 0;
+    std::vector<int32_t> next((size_t)o->M);
+    const int32_t k = ckpt_hist_solve(o->hist, o->M, o->B, next.data(), nullptr);
+    if (k < 0) return k;
+    next.resize((size_t)k);
+    o->pos.swap(next);
+    o->solves += 1;
+    return 1;
+}
+
+int32_t ckpt_online_schedule(const ckpt_online* o, int32_t* pos, int32_t capacity) {
+    if (!o) return GDN_ERR_NULL;
+    const int32_t n = (int32_t)o->pos.size();
+    if (n > capacity) return GDN_ERR_WORKSPACE;
+    if (n > 0 && !pos) return GDN_ERR_NULL;
+    if (n > 0) std::memcpy(pos, o->pos.data(), sizeof(int32_t) * (size_t)n);
+    return n;
+}
+
+const ckpt_hist* ckpt_online_histogram(const ckpt_online* o) { return o ? o->hist : nullptr; }
+
 }  // extern "C"

@@ -12,7 +12,8 @@ _i32, _i64, _vp, _f64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.
 
 EXPORTS = ["ckpt_place_balanced", "ckpt_place_block", "ckpt_place_sqrt", "ckpt_place_log", "ckpt_clip_to_blocks",
            "ckpt_expected_recompute", "ckpt_place_dp", "ckpt_hist_create", "ckpt_hist_destroy", "ckpt_hist_observe",
-           "ckpt_hist_get", "ckpt_hist_solve"]
+           "ckpt_hist_get", "ckpt_hist_solve", "ckpt_online_create", "ckpt_online_destroy", "ckpt_online_observe",
+           "ckpt_online_schedule", "ckpt_online_histogram"]
 
 _ready = False
 
@@ -45,6 +46,16 @@ def _lib():
         L.ckpt_hist_get.argtypes = [_vp, _vp]
         L.ckpt_hist_solve.restype = _i32
         L.ckpt_hist_solve.argtypes = [_vp, _i32, _i32, _vp, _vp]
+        L.ckpt_online_create.restype = _vp
+        L.ckpt_online_create.argtypes = [_i32, _i32, _i32, _f64, _i32]
+        L.ckpt_online_destroy.restype = None
+        L.ckpt_online_destroy.argtypes = [_vp]
+        L.ckpt_online_observe.restype = _i32
+        L.ckpt_online_observe.argtypes = [_vp, _i32]
+        L.ckpt_online_schedule.restype = _i32
+        L.ckpt_online_schedule.argtypes = [_vp, _vp, _i32]
+        L.ckpt_online_histogram.restype = _vp
+        L.ckpt_online_histogram.argtypes = [_vp]
         _ready = True
     return L
 
@@ -145,6 +156,40 @@ class OverlapHistogram:
         if self._h:
             _lib().ckpt_hist_destroy(self._h)
             self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class OnlineScheduler:
+    """The online loop: observe overlap depths, re-solve the placement every `period` observations."""
+
+    def __init__(self, N: int, M: int, B: int = 1, gamma: float = 0.99, period: int = 10):
+        self._o = _lib().ckpt_online_create(N, M, B, gamma, period)
+        if not self._o:
+            raise ValueError("ckpt_online_create: N, M, B, period must be >= 1 and gamma in (0, 1]")
+        self.N, self.M = N, M
+
+    def observe(self, t: int) -> bool:
+        return bool(_count(int(_lib().ckpt_online_observe(self._o, t)), "ckpt_online_observe"))
+
+    def schedule(self) -> List[int]:
+        out = np.zeros(self.M, np.int32)
+        n = _count(_lib().ckpt_online_schedule(self._o, _ptr(out), self.M), "ckpt_online_schedule")
+        return out[:n].tolist()
+
+    def histogram(self) -> np.ndarray:
+        p = np.zeros(self.N, np.float64)
+        _count(_lib().ckpt_hist_get(_lib().ckpt_online_histogram(self._o), _ptr(p)), "ckpt_hist_get")
+        return p
+
+    def close(self):
+        if self._o:
+            _lib().ckpt_online_destroy(self._o)
+            self._o = None
 
     def __del__(self):
         try:

@@ -151,3 +151,77 @@ def test_histogram_tracks_a_drifting_law_and_the_schedule_follows():
     assert cost_ew <= best + 2 * N * np.abs(ew.get() - law_b).sum() + 1e-9      # Lemma 1 applied twice
     assert cost_ew < 2.0 * best + 1.0
     assert cost_emp > cost_ew                                                  # the unweighted estimate lags
+
+
+def test_online_loop_is_observe_plus_resolve_every_period():
+    """Sec. 5, "Our method": the loop object equals histogram + dynamic program + clipping driven by hand."""
+    rng = np.random.default_rng(21)
+    N, M, Bk, period = 200, 5, 8, 10
+    t = np.arange(1, N + 1)
+    law = np.exp(-0.5 * ((t - 150) / 20.0) ** 2); law /= law.sum()
+    on, h = P.OnlineScheduler(N, M, Bk, 0.99, period), P.OverlapHistogram(N, 0.99)
+    assert on.schedule() == []
+    want = []
+    for i in range(95):
+        d = int(rng.choice(t, p=law))
+        h.observe(d)
+        fired = on.observe(d)
+        assert fired == ((i + 1) % period == 0)
+        if fired:
+            want = h.solve(M, Bk)[1]
+        assert on.schedule() == want
+    assert np.array_equal(on.histogram(), h.get())
+    assert all(c % Bk == 0 and 0 < c <= N for c in want) and want == sorted(set(want))
+    with pytest.raises(B.GdnError):
+        on.observe(N + 1)
+    for bad in [(0, 1, 1, 0.9, 1), (8, 0, 1, 0.9, 1), (8, 1, 0, 0.9, 1), (8, 1, 1, 0.0, 1), (8, 1, 1, 0.9, 0)]:
+        with pytest.raises(ValueError):
+            P.OnlineScheduler(*bad)
+
+
+def test_empirical_plug_in_schedule_meets_the_stationary_guarantee():
+    """Theorem 3: with n i.i.d. depths, ||p^ - p||_1 <= sqrt(N/n) + sqrt(2 log(1/delta)/n) with probability >= 1 - delta, and
+    then the plug-in schedule's excess cost under the true law lies in [0, 2N times that bound]."""
+    rng = np.random.default_rng(31)
+    N, M, n, delta, trials = 32, 4, 1500, 0.1, 40
+    t = np.arange(1, N + 1)
+    p = rng.dirichlet(np.full(N, 0.3))
+    best = po.dp_optimal(p, M)[0]
+    bound = math.sqrt(N / n) + math.sqrt(2 * math.log(1 / delta) / n)
+    held = 0
+    for _ in range(trials):
+        h = P.OverlapHistogram(N, 1.0)
+        for d in rng.choice(t, p=p, size=n):
+            h.observe(int(d))
+        l1 = np.abs(h.get() - p).sum()
+        excess = po.expected_recompute(p, h.solve(M)[1]) - best
+        assert excess >= -1e-9                                   # no schedule beats the optimum of the true law
+        if l1 <= bound:
+            held += 1
+            assert excess <= 2 * N * bound + 1e-9
+        h.close()
+    assert held >= (1 - delta) * trials
+
+
+def test_exponential_histogram_meets_the_tracking_bound_under_drift():
+    """Theorem 4: E||p^_t - p_t||_1 <= (1-g)/(1-g^t) sum_s g^(t-s) ||p_s - p_t||_1 + sqrt(N (1-g)/(1+g) (1+g^t)/(1-g^t)),
+    laws drifting linearly from one bump to another; the mean over seeded trials stands in for the expectation."""
+    rng = np.random.default_rng(41)
+    N, T, gamma, trials = 24, 300, 0.95, 150
+    t = np.arange(1, N + 1)
+    a = np.exp(-0.5 * ((t - 6) / 2.5) ** 2); a /= a.sum()
+    b = np.exp(-0.5 * ((t - 18) / 2.5) ** 2); b /= b.sum()
+    laws = [(1 - s / (T - 1)) * a + (s / (T - 1)) * b for s in range(T)]
+    w = gamma ** np.arange(T - 1, -1, -1, dtype=np.float64)
+    bias = (1 - gamma) / (1 - gamma ** T) * sum(w[s] * np.abs(laws[s] - laws[-1]).sum() for s in range(T))
+    var = math.sqrt(N * (1 - gamma) / (1 + gamma) * (1 + gamma ** T) / (1 - gamma ** T))
+    errs = []
+    for _ in range(trials):
+        h = P.OverlapHistogram(N, gamma)
+        for s in range(T):
+            h.observe(int(rng.choice(t, p=laws[s])))
+        errs.append(np.abs(h.get() - laws[-1]).sum())
+        h.close()
+    mean, sem = float(np.mean(errs)), float(np.std(errs) / math.sqrt(trials))
+    assert mean + 3 * sem <= bias + var                          # the bound holds with room to spare
+    assert mean >= 0.5 * bias                                    # and the drift is really felt (the test is not vacuous)
