@@ -156,6 +156,18 @@ CASES = [
 ]
 
 
+def _many_short_requests(n_req=257, seed=7):
+    """Many short requests, some empty, each storing its last state: the request lookup and run counting at scale."""
+    rng = np.random.default_rng(seed)
+    lens = [int(x) for x in rng.integers(0, 41, size=n_req)]
+    starts = [int(x) for x in rng.integers(0, 3, size=n_req) * 64]
+    emits = [[s + l] if l > 0 else [] for s, l in zip(starts, lens)]
+    return (2, 2, 64, 64, 4, lens, starts, emits)
+
+
+CASES.append(_many_short_requests())
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("case_i", range(len(CASES)))
 @pytest.mark.parametrize("dtype,out_dtype", [("bf16", "bf16"), ("f32", "f32"), ("bf16", "f32")])
