@@ -178,11 +178,12 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
  *
  * gdn_resume_prefill_host: gdn_resume_prefill with the start states read from a pinned HOST
  * pool (host_state_src, host pointer; src_slot indexes it; -1 = zero state as before).  The
- * states are copied to a staging area of the workspace on a stream of the library's own while
- * the first preparation launch runs on the caller's stream; only the recurrence waits for
- * them.  The workspace must hold gdn_workspace_bytes_host(...) bytes.  Outputs are bitwise
- * those of gdn_resume_prefill on a device copy of the pool.  Calls are serialised inside the
- * library while their work is being enqueued.
+ * states are brought to a staging area behind the workspace proper: when the pool is pinned
+ * memory the device can address, by workgroups appended to the first preparation launch (the
+ * transfer rides under that launch; only the recurrence needs the states), otherwise by
+ * copies on `stream` ahead of the first launch.  The workspace must hold
+ * gdn_workspace_bytes_host(...) bytes.  Outputs are bitwise those of gdn_resume_prefill on a
+ * device copy of the pool.
  */
 int32_t ckpt_fetch_host(const float *host_pool, int64_t host_slot_stride, int32_t host_n_slots,
                         const int32_t *host_ids,

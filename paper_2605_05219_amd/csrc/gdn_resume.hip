@@ -198,22 +198,6 @@ private:
 };
 
 // ------------------------------------------------------------------ host tier
-// Copies between a pinned host pool and device memory run on a stream of the library's own
-// (default priority), ordered against the caller's stream with two events.
-struct HostTier {
-    std::mutex mu;
-    hipStream_t stream = nullptr;
-    hipEvent_t start = nullptr, ready = nullptr;
-    hipError_t init() {
-        if (stream) return hipSuccess;
-        hipError_t e = hipStreamCreateWithFlags(&stream, hipStreamNonBlocking);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&start, hipEventDisableTiming);
-        if (e == hipSuccess) e = hipEventCreateWithFlags(&ready, hipEventDisableTiming);
-        return e;
-    }
-};
-HostTier g_tier;
-
 int32_t check_tier_args(const void* host_pool, int64_t host_stride, int32_t host_n, const int32_t* host_ids,
                         const void* dev_pool, int64_t dev_stride, int32_t dev_n, const int32_t* dev_ids, int32_t n,
                         int64_t state_elems) {
@@ -361,13 +345,11 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
     return nw;
 }
 
-// Chunk rounds per slab.  The latency variant wants a slab's operand images to stay in the
-// last-level caches between the kernel that writes them and the one that reads them; the
-// throughput variant only bounds the workspace.
-// Chunk rounds per slab.  The slab should stay cache resident between the preparation launch
+// Chunk rounds per slab.  In the latency variant the slab should stay cache resident between the preparation launch
 // that writes it and the recurrence launch that reads it back (budget), and a preparation
 // launch should fill the chip a whole number of times (512 = two of its workgroups on each of
-// the 256 compute units).  gdn_tune_slab_rounds overrides the choice.
+// the 256 compute units); the throughput variants only bound the workspace.  gdn_tune_slab_rounds
+// overrides the choice.
 std::atomic<int32_t> g_forced_rounds{0};
 inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
     const int32_t forced = g_forced_rounds.load();
@@ -679,8 +661,6 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     if (n_chunks == 0) return GDN_OK;  // nothing to replay
     if (!q || !k || !v || !beta || !gate || !o) return GDN_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return GDN_ERR_ALIGN;
-    const int64_t esz = s.in_dtype == GDN_F32 ? 4 : 2;
-    if (((int64_t)s.H_v * esz) & 1) return GDN_ERR_ALIGN;
 
     const WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
     const int64_t pb = wl.plan;
