@@ -9,7 +9,8 @@
 //     L_ij = b_i exp(g_i-g_j) (k_i.k_j)  for j < i,
 // it produces, with T = (I+L)^-1 (fp32):
 //     W  = -T diag(b gam) K          [C][d_k]   (so that U = U~ + W S_0^T)
-//     U~ =  T diag(b) V              [C][d_v]   fp32, in the recurrence kernel's accumulator order
+//     U~ =  T diag(b) V              [C][d_v]   in the recurrence kernel's accumulator order (fp16 for
+//                                               16-bit inputs, fp32 for fp32 inputs)
 //     P_ij = scale * exp(g_i-g_j) (q_i.k_j), j <= i   [C][C]
 //     Q, K^T diag(dec) with dec_i = exp(g_C - g_i) (the decay to the chunk end rides on K, so
 //     the recurrence uses one conversion of U for both of its uses), gam_i, bookkeeping words
