@@ -16,11 +16,11 @@
 //   A   K [C][d_k+4]          -> V^T [d_v][C+4] (after K K^T, K Q^T) -> W fragment image (after U~)
 //   B   Q [C][d_k+4]          kept until the recurrence has used it
 //   KT  K^T [d_k][C+4]        kept until the recurrence has used it
-//   LF  L / T fp32 [C][C+4]   -> Tb | Tbg (fp16) written into the very rows they are made from
+//   LF  L / T fp32 [C][C+4]   T stays fp32; the fp16 fragments of T diag(b) and -T diag(b gam) are made from its rows when used
 //   X   inversion scratch     -> P fragment image
-//   SM  g, b, gam, dec
+//   SM  g, b, gam, dec, -b gam
 // The decay to the chunk end is applied to U (a second conversion of U), not to K^T, so that
-// the K^T tile serves both W^T = K^T Tbg^T and the state update.
+// the K^T tile serves both W^T = K^T (-T diag(b gam))^T and the state update.
 #pragma once
 #include "gdn_prep_kernel.h"
 #include "gdn_recur_kernel.h"
@@ -55,7 +55,6 @@ struct FusedSmem {
     static constexpr int C = 64;
     static constexpr int PAD = Elem<half_t>::PAD;
     static constexpr int K_LD = DK + PAD, KT_LD = C + PAD, VT_LD = C + PAD, LF_LD = C + 4;
-    static constexpr int T_LD = 2 * LF_LD;                      // fp16 elements in one fp32 row of LF
     static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
     static constexpr int cmax(int x, int y) { return x > y ? x : y; }
     static constexpr int W_IMG_BYTES = 2 * (DK / 16) * 64 * 16;  // W fragments: 2 row tiles x d_k/16 steps
@@ -72,7 +71,7 @@ struct FusedSmem {
     static constexpr int X_OFF = LF_OFF + LF_BYTES;
     static constexpr int X_BYTES = cmax(P_IMG_BYTES, 4 * 16 * PLD * 4);
     static constexpr int SM_OFF = X_OFF + X_BYTES;
-    static constexpr int BYTES = SM_OFF + 4 * C * 4;
+    static constexpr int BYTES = SM_OFF + 5 * C * 4;
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
 };
 
@@ -85,7 +84,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     typedef typename EL::Raw8 Raw8;
     typedef FusedSmem<DK, DV> SM;
     constexpr int C = 64;
-    constexpr int K_LD = SM::K_LD, KT_LD = SM::KT_LD, VT_LD = SM::VT_LD, LF_LD = SM::LF_LD, T_LD = SM::T_LD, PLD = SM::PLD;
+    constexpr int K_LD = SM::K_LD, KT_LD = SM::KT_LD, VT_LD = SM::VT_LD, LF_LD = SM::LF_LD, PLD = SM::PLD;
     constexpr int SPT = EL::STEPS_PER_TILE;
     constexpr int NKD = DK / EL::KSTEP, NKC = C / EL::KSTEP, MT = DK / 32;
     static_assert(DV / 32 == 4 && DK / 32 == 4, "one wave per d_v slice, one W^T row tile per wave");
@@ -97,13 +96,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     E* const Qs = reinterpret_cast<E*>(smem + SM::B_OFF);
     E* const KTs = reinterpret_cast<E*>(smem + SM::KT_OFF);
     float* const Lf = reinterpret_cast<float*>(smem + SM::LF_OFF);
-    E* const Tb = reinterpret_cast<E*>(smem + SM::LF_OFF);          // row i: fp16 [0, C) of LF's row i
-    E* const Tbg = Tb + LF_LD;                                       // row i: fp16 [LF_LD, LF_LD + C)
     Frag* const p_img = reinterpret_cast<Frag*>(smem + SM::X_OFF);
     float* const gS = reinterpret_cast<float*>(smem + SM::SM_OFF);
     float* const bS = gS + C;
     float* const gamS = bS + C;
     float* const decS = gamS + C;
+    float* const bgS = decS + C;     // -b gam
 
     const int tid = threadIdx.x;
     const int lane_ = tid & 63;
@@ -244,8 +242,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const float g_last = __shfl(s, 63, 64);
             gS[lane] = s;
             bS[lane] = b;
-            gamS[lane] = EL::exp_(s);
+            const float gam = EL::exp_(s);
+            gamS[lane] = gam;
             decS[lane] = EL::exp_(g_last - s);
+            bgS[lane] = -b * gam;
         }
         // ---- stage K, Q (row-major) and K^T (token-contiguous) as fp16
         {
@@ -392,44 +392,40 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         __syncthreads();  // T complete in Lf
 
-        // ---- Tb = T diag(b), Tbg = -T diag(b gam) as fp16, written over the fp32 rows they come
-        //      from (a row of 68 floats holds both 64-element fp16 rows); the tile above the
-        //      diagonal tiles is never written and is taken as zero here.  P's fragments go to X.
-        {
-            int tid_p = tid;
-            pin(tid_p);
-            const int i = tid_p >> 2, j0 = (tid_p & 3) * 16;
-            float tb[16], tn[16];
+        // ---- P's fragments go to X (free since the diagonal blocks of T are in place).  T stays in
+        //      fp32: the operand fragments of T diag(b) and -T diag(b gam) are made from its rows on
+        //      the fly (two 16-byte reads, the scale, the conversion), so no fp16 copy of T is written
+        //      and no barrier separates T from its two uses.  Entries above the diagonal inside the
+        //      tiles that are read are exact zeros (written so by the K K^T epilogue and kept by the
+        //      inversion); the tile above the diagonal tiles is never read.
+        if (p_mj >= 0) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int j = j0 + e;
-                const float t = (j <= i) ? Lf[i * LF_LD + j] * bS[j] : 0.f;
-                tb[e] = t;
-                tn[e] = -t * gamS[j];
-            }
-            __syncthreads();  // every fp32 row has been read
-#pragma unroll
-            for (int jj = 0; jj < 16; jj += 4) {
-                EL::store4(Tb + i * T_LD + j0 + jj, tb[jj], tb[jj + 1], tb[jj + 2], tb[jj + 3]);
-                EL::store4(Tbg + i * T_LD + j0 + jj, tn[jj], tn[jj + 1], tn[jj + 2], tn[jj + 3]);
-            }
-            if (p_mj >= 0) {
-#pragma unroll
-                for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = pfr[sub];
-            }
+            for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = pfr[sub];
         }
-        __syncthreads();
+        auto t_frag = [&](const float* row, const float* vec, int s_) -> Frag {
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(row + 16 * s_ + 4 * g);
+            const f32x4 hi = *reinterpret_cast<const f32x4*>(row + 16 * s_ + 8 + 4 * g);
+            const f32x4 vl = *reinterpret_cast<const f32x4*>(vec + 16 * s_ + 4 * g);
+            const f32x4 vh = *reinterpret_cast<const f32x4*>(vec + 16 * s_ + 8 + 4 * g);
+            Frag f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f[e] = (half_t)(lo[e] * vl[e]);
+                f[4 + e] = (half_t)(hi[e] * vh[e]);
+            }
+            return f;
+        };
 
         // ---- U~ for this wave's slice (both token tiles), straight into the recurrence's accumulators
         f32x16 accU[2];
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
             f32x16 acc = {0};
-            const E* ar = Tb + (32 * rt + lr) * T_LD;
+            const float* ar = Lf + (32 * rt + lr) * LF_LD;
             const E* br = VTs + (32 * sl + lr) * VT_LD;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (rt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+                if (s < (rt == 0 ? NKC / 2 : NKC)) acc = EL::mma(t_frag(ar, bS, s), EL::load(br, s, g), acc);
             accU[rt] = acc;
         }
         __syncthreads();  // V^T is dead
@@ -440,10 +436,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int mt = wave;
             f32x16 acc = {0};
             const E* ar = KTs + (32 * mt + lr) * KT_LD;
-            const E* br = Tbg + (32 * nt + lr) * T_LD;
+            const float* br = Lf + (32 * nt + lr) * LF_LD;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (nt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+                if (s < (nt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), t_frag(br, bgS, s), acc);
 #pragma unroll
             for (int sub = 0; sub < SPT; ++sub) w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
         }
