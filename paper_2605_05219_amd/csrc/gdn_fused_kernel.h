@@ -402,20 +402,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
             for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = pfr[sub];
         }
-        auto t_frag = [&](const float* row, const float* vec, int s_) -> Frag {
-            const f32x4 lo = *reinterpret_cast<const f32x4*>(row + 16 * s_ + 4 * g);
-            const f32x4 hi = *reinterpret_cast<const f32x4*>(row + 16 * s_ + 8 + 4 * g);
-            const f32x4 vl = *reinterpret_cast<const f32x4*>(vec + 16 * s_ + 4 * g);
-            const f32x4 vh = *reinterpret_cast<const f32x4*>(vec + 16 * s_ + 8 + 4 * g);
-            Frag f;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                f[e] = (half_t)(lo[e] * vl[e]);
-                f[4 + e] = (half_t)(hi[e] * vh[e]);
-            }
-            return f;
-        };
-
         // ---- U~ for this wave's slice (both token tiles), straight into the recurrence's accumulators
         f32x16 accU[2];
 #pragma unroll
@@ -425,7 +411,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const E* br = VTs + (32 * sl + lr) * VT_LD;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (rt == 0 ? NKC / 2 : NKC)) acc = EL::mma(t_frag(ar, bS, s), EL::load(br, s, g), acc);
+                if (s < (rt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load_scaled(ar, bS, s, g), EL::load(br, s, g), acc);
             accU[rt] = acc;
         }
         __syncthreads();  // V^T is dead
@@ -439,7 +425,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const float* br = Lf + (32 * nt + lr) * LF_LD;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (nt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), t_frag(br, bgS, s), acc);
+                if (s < (nt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), EL::load_scaled(br, bgS, s, g), acc);
 #pragma unroll
             for (int sub = 0; sub < SPT; ++sub) w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
         }

@@ -73,6 +73,20 @@ template <> struct Elem<half_t> {
         for (int e = 0; e < 8; ++e) f[e] = (half_t)acc[8 * sub + e];
         return f;
     }
+    // the operand fragment load() would return for the row (x[c] * vec[c])_c, x and vec fp32 in LDS
+    static __device__ __forceinline__ Frag load_scaled(const float* x, const float* vec, int s, int g) {
+        const f32x4 lo = *reinterpret_cast<const f32x4*>(x + 16 * s + 4 * g);
+        const f32x4 hi = *reinterpret_cast<const f32x4*>(x + 16 * s + 8 + 4 * g);
+        const f32x4 vl = *reinterpret_cast<const f32x4*>(vec + 16 * s + 4 * g);
+        const f32x4 vh = *reinterpret_cast<const f32x4*>(vec + 16 * s + 8 + 4 * g);
+        Frag f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[e] = (half_t)(lo[e] * vl[e]);
+            f[4 + e] = (half_t)(hi[e] * vh[e]);
+        }
+        return f;
+    }
     static __device__ __forceinline__ void store4(half_t* p, float a, float b, float c, float d) {
         half4 h;
         h[0] = (half_t)a; h[1] = (half_t)b; h[2] = (half_t)c; h[3] = (half_t)d;
@@ -125,6 +139,11 @@ template <> struct Elem<float> {
         return f * vec[32 * (s >> 4) + 8 * (w >> 2) + 4 * g + (w & 3)];
     }
     static __device__ __forceinline__ Frag from_acc(const f32x16& acc, int sub) { return acc[sub]; }
+    static __device__ __forceinline__ Frag load_scaled(const float* x, const float* vec, int s, int g) {
+        const int w = s & 15;
+        const int c = 32 * (s >> 4) + 8 * (w >> 2) + 4 * g + (w & 3);
+        return x[c] * vec[c];
+    }
     static __device__ __forceinline__ void store4(float* p, float a, float b, float c, float d) {
         p[0] = a; p[1] = b; p[2] = c; p[3] = d;
     }

@@ -78,7 +78,6 @@ struct PrepSmem {
     static constexpr int C = 64;
     static constexpr int PAD = Elem<E>::PAD;
     static constexpr int LF_LD = C + 4;   // rows 16-byte aligned
-    static constexpr int T_LD = C + PAD;  // Tb / Tbg rows
     static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
     static constexpr int KT_LD = C + PAD;
     static constexpr int VT_LD = C + PAD;
@@ -86,16 +85,16 @@ struct PrepSmem {
     // region A: K [C][DK+PAD]; once the first products are done, V^T [DV][C+PAD]
     static constexpr int A_OFF = 0;
     static constexpr int A_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), a16(DV * VT_LD * (int)sizeof(E)));
-    // region B: Q [C][DK+PAD], later Tb and Tbg
     static constexpr int B_OFF = A_OFF + A_BYTES;
-    static constexpr int TB_BYTES = a16(C * T_LD * (int)sizeof(E));
-    static constexpr int B_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), 2 * TB_BYTES);
+    // region B: Q [C][DK+PAD]; later the inversion's power buffers (three 16 x 20 fp32 blocks per wave)
+    static constexpr int POW_BYTES = 4 * 3 * 16 * 20 * (int)sizeof(float);
+    static constexpr int B_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), POW_BYTES);
     static constexpr int KT_OFF = B_OFF + B_BYTES;
     static constexpr int KT_BYTES = a16(DK * KT_LD * (int)sizeof(E));
     static constexpr int LF_OFF = KT_OFF + KT_BYTES;
     static constexpr int LF_BYTES = a16(C * LF_LD * (int)sizeof(float));
-    static constexpr int SM_OFF = LF_OFF + LF_BYTES;  // g[C], b[C], gam[C], dec[C]
-    static constexpr int BYTES = SM_OFF + 4 * C * (int)sizeof(float);
+    static constexpr int SM_OFF = LF_OFF + LF_BYTES;  // g[C], b[C], gam[C], dec[C], -b gam [C]
+    static constexpr int BYTES = SM_OFF + 5 * C * (int)sizeof(float);
 };
 
 // The work of one preparation workgroup: workgroup `wg` of `n_prep_wgs` that share a launch's items.
@@ -112,7 +111,6 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     constexpr int KT_LD = SM::KT_LD;
     constexpr int VT_LD = SM::VT_LD;
     constexpr int LF_LD = SM::LF_LD;
-    constexpr int T_LD = SM::T_LD;
 
     extern __shared__ __align__(16) char smem[];
     E* Ks = reinterpret_cast<E*>(smem + SM::A_OFF);
@@ -124,8 +122,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     float* bS = gS + C;
     float* gamS = bS + C;
     float* decS = gamS + C;
-    E* Tb = Qs;                                           // after the first products
-    E* Tbg = reinterpret_cast<E*>(smem + SM::B_OFF + SM::TB_BYTES);
+    float* bgS = decS + C;   // -b gam
 
     const int tid = threadIdx.x;
     const int lane_ = tid & 63;
@@ -243,8 +240,10 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         const float g_last = __shfl(s, 63, 64);
         gS[lane] = s;
         bS[lane] = b;
-        gamS[lane] = EL::exp_(s);
+        const float gam = EL::exp_(s);
+        gamS[lane] = gam;
         decS[lane] = EL::exp_(g_last - s);
+        bgS[lane] = -b * gam;
     }
 
     // ---- stage K, Q (row-major) and K^T (token-contiguous), converted to E; the transposed
@@ -408,25 +407,11 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     }
     __syncthreads();  // T complete in Lf
 
-    // ---- Tb = T diag(b), Tbg = -T diag(b gam), converted to E (region B; Q is dead)
-    {
-        const int i = tid_p >> 2, j0 = (tid_p & 3) * 16;
-#pragma unroll
-        for (int jj = 0; jj < 16; jj += 4) {
-            float tb[4], tn[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = j0 + jj + e;
-                const float t = Lf[i * LF_LD + j] * bS[j];
-                tb[e] = t;
-                tn[e] = -t * gamS[j];
-            }
-            EL::store4(Tb + i * T_LD + EL::slot4(j0 + jj), tb[0], tb[1], tb[2], tb[3]);
-            EL::store4(Tbg + i * T_LD + EL::slot4(j0 + jj), tn[0], tn[1], tn[2], tn[3]);
-        }
-    }
-    __syncthreads();
-
+    // T stays in fp32: the operand fragments of Tb = T diag(b) and Tbg = -T diag(b gam) are made
+    // from its rows on use (the scale, the conversion), so no converted copy is written and no
+    // barrier separates T from its two uses.  Entries above the diagonal inside the tiles that
+    // are read are exact zeros (written so by the K K^T epilogue and kept by the inversion); the
+    // tile above the diagonal tiles is never read.
     // ---- W^T tile (mt, nt): D[d_k][token i] = sum_j K^T[d_k][j] Tbg[i][j].  The accumulators of
     //      lane (i, g) are W's fragments of row tile nt, steps SPT*mt ..; the A operands are
     //      K^T's fragments.  T is lower triangular: token tile 0 only contracts over j < 32.
@@ -435,14 +420,14 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         const int mt = t % (DK / 32), nt = t / (DK / 32);   // a wave's tiles: one of each token tile where possible
         f32x16 acc = {0};
         const E* ar = KTs + (32 * mt + lr) * KT_LD;
-        const E* br = Tbg + (32 * nt + lr) * T_LD;
+        const float* br = Lf + (32 * nt + lr) * LF_LD;
         const int ns = (nt == 0) ? NKC / 2 : NKC;
 #pragma unroll
         for (int s = 0; s < NKC; ++s)
             if (s < ns) {
                 const Frag kf = EL::load(ar, s, g);
                 if (nt == 1) kt_img[(mt * NKC + s) * 64 + lane] = EL::scale(kf, decS, s, g);   // decayed to the chunk end
-                acc = EL::mma(kf, EL::load(br, s, g), acc);
+                acc = EL::mma(kf, EL::load_scaled(br, bgS, s, g), acc);
             }
 #pragma unroll
         for (int sub = 0; sub < SPT; ++sub)
@@ -456,12 +441,12 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         for (int p = wave; p < (DV / 32) * 2; p += 4) {
             const int sl = p % (DV / 32), rt = p / (DV / 32);
             f32x16 acc = {0};
-            const E* ar = Tb + (32 * rt + lr) * T_LD;
+            const float* ar = Lf + (32 * rt + lr) * LF_LD;
             const E* br = VTs + (32 * sl + lr) * VT_LD;
             const int ns = (rt == 0) ? NKC / 2 : NKC;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < ns) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
+                if (s < ns) acc = EL::mma(EL::load_scaled(ar, bS, s, g), EL::load(br, s, g), acc);
 #pragma unroll
             for (int pc = 0; pc < EL::UT_PIECES; ++pc) ut[((sl * 2 + rt) * EL::UT_PIECES + pc) * 64 + lane] = EL::ut_pack(acc, pc);
         }
