@@ -233,13 +233,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 la = fmaxf(EL::log_(EL::widen(graw)), -88.f);
                 b = EL::widen(braw);
             }
-            float s = la;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const float t = __shfl_up(s, d, 64);
-                if (lane >= d) s += t;
-            }
-            const float g_last = __shfl(s, 63, 64);
+            const float s = wave_running_sum(la);
+            const float g_last = wave_last_lane(s);
             gS[lane] = s;
             bS[lane] = b;
             const float gam = EL::exp_(s);

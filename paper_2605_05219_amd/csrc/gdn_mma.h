@@ -33,6 +33,26 @@ template <typename T>
 __device__ __forceinline__ void pin(T& x) { asm volatile("" : "+v"(x)); }
 
 // Output row (within a 32x32 tile) held by accumulator register idx of half-wave g.
+// Inclusive running sum over the 64 lanes of a wave by cross-lane adds only (no LDS traffic):
+// shifts by 1, 2, 4 and 8 inside each row of 16 lanes with zeros shifted in, then lane 15 of
+// rows 0 and 2 added to the row above, then lane 31 added to the upper half.  All lanes active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_or_zero(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, true));
+}
+__device__ __forceinline__ float wave_running_sum(float x) {
+    x += dpp_or_zero<0x111, 0xF>(x);   // row_shr:1
+    x += dpp_or_zero<0x112, 0xF>(x);   // row_shr:2
+    x += dpp_or_zero<0x114, 0xF>(x);   // row_shr:4
+    x += dpp_or_zero<0x118, 0xF>(x);   // row_shr:8
+    x += dpp_or_zero<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+    x += dpp_or_zero<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
+    return x;
+}
+__device__ __forceinline__ float wave_last_lane(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
+}
+
 __device__ __forceinline__ int acc_row(int idx, int g) { return 8 * (idx >> 2) + 4 * g + (idx & 3); }
 
 template <typename E> struct Elem;
