@@ -381,9 +381,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 x3 = mm16_ll<LF_LD>(x3, blk(3, 1), blk(1, rb), m16, g4);
                 r = mm16_lr<LF_LD>(r, blk(3, 3), x3, m16, g4);
             }
-            __syncthreads();  // every wave has read the L blocks it needs before any is overwritten
+            // The 32x32 block below the diagonal tiles is stored in the tile ABOVE them (rows 0..31, columns 32..63),
+            // which nothing else uses: no L block that another wave still reads is overwritten, so no barrier.
 #pragma unroll
-            for (int e = 0; e < 4; ++e) Lf[(16 * ra + 4 * g4 + e) * LF_LD + 16 * rb + m16] = -r[e];
+            for (int e = 0; e < 4; ++e) Lf[(16 * (ra - 2) + 4 * g4 + e) * LF_LD + 32 + 16 * rb + m16] = -r[e];
         }
         __syncthreads();  // T complete in Lf
 
@@ -392,7 +393,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         //      the fly (two 16-byte reads, the scale, the conversion), so no fp16 copy of T is written
         //      and no barrier separates T from its two uses.  Entries above the diagonal inside the
         //      tiles that are read are exact zeros (written so by the K K^T epilogue and kept by the
-        //      inversion); the tile above the diagonal tiles is never read.
+        //      inversion); the tile above the diagonal tiles holds the block below them.
         if (p_mj >= 0) {
 #pragma unroll
             for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = pfr[sub];
@@ -403,10 +404,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int rt = 0; rt < 2; ++rt) {
             f32x16 acc = {0};
             const float* ar = Lf + (32 * rt + lr) * LF_LD;
+            const float* ar10 = Lf + lr * LF_LD + 32;   // rows 32.., columns 0..31 of T live above the diagonal tiles
             const E* br = VTs + (32 * sl + lr) * VT_LD;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (rt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load_scaled(ar, bS, s, g), EL::load(br, s, g), acc);
+                if (s < (rt == 0 ? NKC / 2 : NKC))
+                    acc = EL::mma(EL::load_scaled((rt == 1 && s < NKC / 2) ? ar10 : ar, bS, s, g), EL::load(br, s, g), acc);
             accU[rt] = acc;
         }
         __syncthreads();  // V^T is dead
@@ -418,9 +421,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             f32x16 acc = {0};
             const E* ar = KTs + (32 * mt + lr) * KT_LD;
             const float* br = Lf + (32 * nt + lr) * LF_LD;
+            const float* br10 = Lf + lr * LF_LD + 32;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < (nt == 0 ? NKC / 2 : NKC)) acc = EL::mma(EL::load(ar, s, g), EL::load_scaled(br, bgS, s, g), acc);
+                if (s < (nt == 0 ? NKC / 2 : NKC))
+                    acc = EL::mma(EL::load(ar, s, g), EL::load_scaled((nt == 1 && s < NKC / 2) ? br10 : br, bgS, s, g), acc);
 #pragma unroll
             for (int sub = 0; sub < SPT; ++sub) w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
         }

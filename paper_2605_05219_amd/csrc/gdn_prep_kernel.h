@@ -396,9 +396,10 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
             x3 = mm16_ll<LF_LD>(x3, blk(3, 1), blk(1, rb), m16, g4);
             r = mm16_lr<LF_LD>(r, blk(3, 3), x3, m16, g4);
         }
-        __syncthreads();  // every wave has read the L blocks it needs before any is overwritten
+        // The 32x32 block below the diagonal tiles is stored in the tile ABOVE them (rows 0..31, columns 32..63),
+        // which nothing else uses: no L block that another wave still reads is overwritten, so no barrier.
 #pragma unroll
-        for (int e = 0; e < 4; ++e) Lf[(16 * ra + 4 * g4 + e) * LF_LD + 16 * rb + m16] = -r[e];
+        for (int e = 0; e < 4; ++e) Lf[(16 * (ra - 2) + 4 * g4 + e) * LF_LD + 32 + 16 * rb + m16] = -r[e];
     }
     __syncthreads();  // T complete in Lf
 
@@ -406,7 +407,7 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     // from its rows on use (the scale, the conversion), so no converted copy is written and no
     // barrier separates T from its two uses.  Entries above the diagonal inside the tiles that
     // are read are exact zeros (written so by the K K^T epilogue and kept by the inversion); the
-    // tile above the diagonal tiles is never read.
+    // tile above the diagonal tiles holds the block below them.
     // ---- W^T tile (mt, nt): D[d_k][token i] = sum_j K^T[d_k][j] Tbg[i][j].  The accumulators of
     //      lane (i, g) are W's fragments of row tile nt, steps SPT*mt ..; the A operands are
     //      K^T's fragments.  T is lower triangular: token tile 0 only contracts over j < 32.
@@ -416,13 +417,14 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
         f32x16 acc = {0};
         const E* ar = KTs + (32 * mt + lr) * KT_LD;
         const float* br = Lf + (32 * nt + lr) * LF_LD;
+        const float* br10 = Lf + lr * LF_LD + 32;   // rows 32.., columns 0..31 of T live above the diagonal tiles
         const int ns = (nt == 0) ? NKC / 2 : NKC;
 #pragma unroll
         for (int s = 0; s < NKC; ++s)
             if (s < ns) {
                 const Frag kf = EL::load(ar, s, g);
                 if (nt == 1) kt_img[(mt * NKC + s) * 64 + lane] = EL::scale(kf, decS, s, g);   // decayed to the chunk end
-                acc = EL::mma(kf, EL::load_scaled(br, bgS, s, g), acc);
+                acc = EL::mma(kf, EL::load_scaled((nt == 1 && s < NKC / 2) ? br10 : br, bgS, s, g), acc);
             }
 #pragma unroll
         for (int sub = 0; sub < SPT; ++sub)
@@ -437,11 +439,12 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
             const int sl = p % (DV / 32), rt = p / (DV / 32);
             f32x16 acc = {0};
             const float* ar = Lf + (32 * rt + lr) * LF_LD;
+            const float* ar10 = Lf + lr * LF_LD + 32;
             const E* br = VTs + (32 * sl + lr) * VT_LD;
             const int ns = (rt == 0) ? NKC / 2 : NKC;
 #pragma unroll
             for (int s = 0; s < NKC; ++s)
-                if (s < ns) acc = EL::mma(EL::load_scaled(ar, bS, s, g), EL::load(br, s, g), acc);
+                if (s < ns) acc = EL::mma(EL::load_scaled((rt == 1 && s < NKC / 2) ? ar10 : ar, bS, s, g), EL::load(br, s, g), acc);
 #pragma unroll
             for (int pc = 0; pc < EL::UT_PIECES; ++pc) ut[((sl * 2 + rt) * EL::UT_PIECES + pc) * 64 + lane] = EL::ut_pack(acc, pc);
         }
