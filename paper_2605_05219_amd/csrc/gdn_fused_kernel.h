@@ -17,7 +17,7 @@
 //   B   Q [C][d_k+4]          kept until the recurrence has used it
 //   KT  K^T [d_k][C+4]        kept until the recurrence has used it
 //   LF  L / T fp32 [C][C+4]   T stays fp32; the fp16 fragments of T diag(b) and -T diag(b gam) are made from its rows when used
-//   X   inversion scratch     -> P fragment image
+//   X   P fragment image
 //   SM  g, b, gam, dec, -b gam
 // The decay to the chunk end is applied to U (a second conversion of U), not to K^T, so that
 // the K^T tile serves both W^T = K^T (-T diag(b gam))^T and the state update.
@@ -59,7 +59,6 @@ struct FusedSmem {
     static constexpr int cmax(int x, int y) { return x > y ? x : y; }
     static constexpr int W_IMG_BYTES = 2 * (DK / 16) * 64 * 16;  // W fragments: 2 row tiles x d_k/16 steps
     static constexpr int P_IMG_BYTES = 2 * (C / 16) * 64 * 16;   // P fragments
-    static constexpr int PLD = 20;                               // inversion scratch rows (floats)
     static constexpr int A_OFF = 0;
     static constexpr int A_BYTES = cmax(cmax(a16(C * K_LD * 2), a16(DV * VT_LD * 2)), W_IMG_BYTES);
     static constexpr int B_OFF = A_OFF + A_BYTES;
@@ -69,7 +68,7 @@ struct FusedSmem {
     static constexpr int LF_OFF = KT_OFF + KT_BYTES;
     static constexpr int LF_BYTES = a16(C * LF_LD * 4);
     static constexpr int X_OFF = LF_OFF + LF_BYTES;
-    static constexpr int X_BYTES = cmax(P_IMG_BYTES, 4 * 16 * PLD * 4);
+    static constexpr int X_BYTES = P_IMG_BYTES;
     static constexpr int SM_OFF = X_OFF + X_BYTES;
     static constexpr int BYTES = SM_OFF + 5 * C * 4;
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
@@ -84,7 +83,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     typedef typename EL::Raw8 Raw8;
     typedef FusedSmem<DK, DV> SM;
     constexpr int C = 64;
-    constexpr int K_LD = SM::K_LD, KT_LD = SM::KT_LD, VT_LD = SM::VT_LD, LF_LD = SM::LF_LD, PLD = SM::PLD;
+    constexpr int K_LD = SM::K_LD, KT_LD = SM::KT_LD, VT_LD = SM::VT_LD, LF_LD = SM::LF_LD;
     constexpr int SPT = EL::STEPS_PER_TILE;
     constexpr int NKD = DK / EL::KSTEP, NKC = C / EL::KSTEP, MT = DK / 32;
     static_assert(DV / 32 == 4 && DK / 32 == 4, "one wave per d_v slice, one W^T row tile per wave");
@@ -263,14 +262,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (GDN_FUSED_PREFETCH && nxt.chain >= 0) fetch_kq(nxt);
         __syncthreads();
 
-        // ---- K K^T -> L (fp32) and K Q^T -> P fragments (kept in registers until X is free)
+        // ---- K K^T -> L (fp32) and K Q^T -> P fragments (to X: the previous chunk's recurrence is done with it)
         //      wave 0: KK(0,0) KQ(0,0)   wave 1: KK(1,0)   wave 2: KK(1,1) KQ(1,1)   wave 3: KQ(0,1)
         int p_mj = -1, p_ni = -1;
-        Frag pfr[SPT];
-#pragma unroll
-        for (int sub = 0; sub < SPT; ++sub)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) pfr[sub][e] = (half_t)0.f;
         {
             int kk_mi = -1, kk_nj = -1;
             if (wave == 0) { kk_mi = 0; kk_nj = 0; p_mj = 0; p_ni = 0; }
@@ -307,7 +301,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     acc[idx] = (j <= i) ? val : 0.f;
                 }
 #pragma unroll
-                for (int sub = 0; sub < SPT; ++sub) pfr[sub] = EL::from_acc(acc, sub);
+                for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
             }
         }
         __syncthreads();  // L is complete; K in LDS is dead
@@ -324,35 +318,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (GDN_FUSED_PREFETCH == 1 && nxt.chain >= 0) fetch_v(nxt);
 
         // ---- T = (I + L)^-1, fp32, by 16x16 blocks (see gdn_prep_kernel).  Stage 1: diagonal blocks
-        //      by (I + D)^-1 = (I + D^8)(I + D^4)(I + D^2)(I - D), the powers through ONE scratch
-        //      block per wave (each power is last read before the next one overwrites it).
+        //      by (I + D)^-1 = (I + D^8)(I + D^4)(I + D^2)(I - D), in registers.
         {
             float* const D = Lf + (16 * wave) * LF_LD + 16 * wave;
-            float* const PB = reinterpret_cast<float*>(smem + SM::X_OFF) + wave * 16 * PLD;
-            const f32x4 zero = {0, 0, 0, 0};
-            f32x4 d1, y;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                d1[e] = D[(4 * g4 + e) * LF_LD + m16];
-                y[e] = ((4 * g4 + e) == m16 ? 1.f : 0.f) - d1[e];
-            }
-            const f32x4 d2 = mm16_lr<LF_LD>(zero, D, d1, m16, g4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) PB[(4 * g4 + e) * PLD + m16] = d2[e];
-            __builtin_amdgcn_wave_barrier();
-            y = mm16_lr<PLD>(y, PB, y, m16, g4);
-            const f32x4 d4 = mm16_lr<PLD>(zero, PB, d2, m16, g4);
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int e = 0; e < 4; ++e) PB[(4 * g4 + e) * PLD + m16] = d4[e];
-            __builtin_amdgcn_wave_barrier();
-            y = mm16_lr<PLD>(y, PB, y, m16, g4);
-            const f32x4 d8 = mm16_lr<PLD>(zero, PB, d4, m16, g4);
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int e = 0; e < 4; ++e) PB[(4 * g4 + e) * PLD + m16] = d8[e];
-            __builtin_amdgcn_wave_barrier();
-            y = mm16_lr<PLD>(y, PB, y, m16, g4);
+            const f32x4 y = inv16_unit_lower<LF_LD>(D, m16, g4);
 #pragma unroll
             for (int e = 0; e < 4; ++e) D[(4 * g4 + e) * LF_LD + m16] = y[e];
         }
@@ -388,16 +357,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         __syncthreads();  // T complete in Lf
 
-        // ---- P's fragments go to X (free since the diagonal blocks of T are in place).  T stays in
-        //      fp32: the operand fragments of T diag(b) and -T diag(b gam) are made from its rows on
-        //      the fly (two 16-byte reads, the scale, the conversion), so no fp16 copy of T is written
-        //      and no barrier separates T from its two uses.  Entries above the diagonal inside the
-        //      tiles that are read are exact zeros (written so by the K K^T epilogue and kept by the
+        // ---- T stays in fp32: the operand fragments of T diag(b) and -T diag(b gam) are made from its
+        //      rows on the fly (two 16-byte reads, the scale, the conversion), so no fp16 copy of T is
+        //      written and no barrier separates T from its two uses.  Entries above the diagonal inside
+        //      the tiles that are read are exact zeros (written so by the K K^T epilogue and kept by the
         //      inversion); the tile above the diagonal tiles holds the block below them.
-        if (p_mj >= 0) {
-#pragma unroll
-            for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = pfr[sub];
-        }
+
         // ---- U~ for this wave's slice (both token tiles), straight into the recurrence's accumulators
         f32x16 accU[2];
 #pragma unroll

@@ -72,6 +72,37 @@ __device__ __forceinline__ f32x4 mm16_lr(f32x4 acc, const float* A, const f32x4 
     return acc;
 }
 
+// Same with both operands in registers: D += A B given the accumulator-layout tiles of A^T and of B
+// (lane (m, g4) holds rows 4 g4 .. 4 g4 + 3 of column m; step e contracts over the indices 4 g4' + e).
+__device__ __forceinline__ f32x4 mm16_rr(f32x4 acc, const f32x4 At, const f32x4 B) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(At[e], B[e], acc, 0, 0, 0);
+    return acc;
+}
+
+// (I + D)^-1 for a strictly lower triangular 16x16 block D of an fp32 matrix in LDS, by the nilpotent
+// product (I + D^8)(I + D^4)(I + D^2)(I - D) (exact: D^16 = 0), entirely in registers: every power is
+// carried as the accumulator tiles of itself and of its transpose, which is what a product needs of its
+// left and right operand, so nothing goes back through LDS (eight 16x16 products on v_mfma_f32_16x16x4_f32).
+// Returns the accumulator tile of the inverse: element e of lane (m, g4) is entry (4 g4 + e, m).
+template <int LD>
+__device__ __forceinline__ f32x4 inv16_unit_lower(const float* D, int m, int g4) {
+    f32x4 d, y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        d[e] = D[(4 * g4 + e) * LD + m];
+        y[e] = ((4 * g4 + e) == m ? 1.f : 0.f) - d[e];
+    }
+    const f32x4 dt = *reinterpret_cast<const f32x4*>(D + m * LD + 4 * g4);   // tile of D^T: row m of D
+    const f32x4 zero = {0, 0, 0, 0};
+    const f32x4 p2 = mm16_rr(zero, dt, d), p2t = mm16_rr(zero, d, dt);       // D^2 and its transpose
+    y = mm16_rr(y, p2t, y);                                                  // (I + D^2)(I - D)
+    const f32x4 p4 = mm16_rr(zero, p2t, p2), p4t = mm16_rr(zero, p2, p2t);
+    y = mm16_rr(y, p4t, y);
+    const f32x4 p8t = mm16_rr(zero, p4, p4t);
+    return mm16_rr(y, p8t, y);
+}
+
 template <typename E, int DK, int DV>
 struct PrepSmem {
     typedef UnitLayout<E, DK, DV> U;
@@ -86,9 +117,8 @@ struct PrepSmem {
     static constexpr int A_OFF = 0;
     static constexpr int A_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), a16(DV * VT_LD * (int)sizeof(E)));
     static constexpr int B_OFF = A_OFF + A_BYTES;
-    // region B: Q [C][DK+PAD]; later the inversion's power buffers (three 16 x 20 fp32 blocks per wave)
-    static constexpr int POW_BYTES = 4 * 3 * 16 * 20 * (int)sizeof(float);
-    static constexpr int B_BYTES = cmax(a16(C * (DK + PAD) * (int)sizeof(E)), POW_BYTES);
+    // region B: Q [C][DK+PAD]
+    static constexpr int B_BYTES = a16(C * (DK + PAD) * (int)sizeof(E));
     static constexpr int KT_OFF = B_OFF + B_BYTES;
     static constexpr int KT_BYTES = a16(DK * KT_LD * (int)sizeof(E));
     static constexpr int LF_OFF = KT_OFF + KT_BYTES;
@@ -330,40 +360,12 @@ __device__ __forceinline__ void prep_body(const PrepArgs& a, const int wg, const
     // ---- T = (I + L)^-1, fp32, by 16x16 blocks.  Stage 1: the four diagonal blocks, one per
     //      wave.  A strictly lower triangular 16x16 block D has D^16 = 0, so
     //          (I + D)^-1 = (I + D^8)(I + D^4)(I + D^2)(I - D)
-    //      exactly: three squarings and three products on the matrix cores instead of a
-    //      sixteen-step substitution.  The running product stays in accumulators (it is always
-    //      the right operand); the powers pass through a wave-private LDS buffer (Q's region is
-    //      dead) to become left operands.
+    //      exactly: squarings and products on the matrix cores instead of a sixteen-step
+    //      substitution, all in registers (see inv16_unit_lower).
     const int m16 = lane & 15, g4 = lane >> 4;
     {
-        constexpr int PLD = 20;   // 16-byte aligned rows, no bank conflict between the four row groups
-        static_assert(4 * 3 * 16 * PLD * (int)sizeof(float) <= SM::B_BYTES, "power buffers fit in Q's region");
         float* const D = Lf + (16 * wave) * LF_LD + 16 * wave;
-        float* const P2 = reinterpret_cast<float*>(smem + SM::B_OFF) + wave * 3 * 16 * PLD;
-        float* const P4 = P2 + 16 * PLD;
-        float* const P8 = P4 + 16 * PLD;
-        const f32x4 zero = {0, 0, 0, 0};
-        f32x4 d1, y;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            d1[e] = D[(4 * g4 + e) * LF_LD + m16];
-            y[e] = ((4 * g4 + e) == m16 ? 1.f : 0.f) - d1[e];
-        }
-        const f32x4 d2 = mm16_lr<LF_LD>(zero, D, d1, m16, g4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) P2[(4 * g4 + e) * PLD + m16] = d2[e];
-        __builtin_amdgcn_wave_barrier();
-        y = mm16_lr<PLD>(y, P2, y, m16, g4);
-        const f32x4 d4 = mm16_lr<PLD>(zero, P2, d2, m16, g4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) P4[(4 * g4 + e) * PLD + m16] = d4[e];
-        __builtin_amdgcn_wave_barrier();
-        y = mm16_lr<PLD>(y, P4, y, m16, g4);
-        const f32x4 d8 = mm16_lr<PLD>(zero, P4, d4, m16, g4);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) P8[(4 * g4 + e) * PLD + m16] = d8[e];
-        __builtin_amdgcn_wave_barrier();
-        y = mm16_lr<PLD>(y, P8, y, m16, g4);
+        const f32x4 y = inv16_unit_lower<LF_LD>(D, m16, g4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) D[(4 * g4 + e) * LF_LD + m16] = y[e];
     }
