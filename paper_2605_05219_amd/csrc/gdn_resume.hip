@@ -335,9 +335,13 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
 
 // Which recurrence variant a call gets: 1 = latency variant (few chains), else the number of
 // d_v slices (waves) per workgroup of the throughput variant.
+constexpr int CHIP_CUS = 256;   // compute units of the chip the variants are sized for (MI355X)
 inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
     int nw = ns;
     while (nw > 1 && n_chains * (ns / nw) < 512) nw >>= 1;
+    // A latency-variant workgroup fills a compute unit's LDS: with more of them than compute units
+    // they would run in turns (measured: 96 chains 1.0 ms against 0.70 ms with two slices per workgroup).
+    if (nw == 1 && n_chains * ns > CHIP_CUS) nw = 2;
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && ns == 4)) nw = o;
     }
@@ -394,7 +398,11 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
     // slab buffers (latency variant) the preparation of the next slab shares the recurrence's launch.
     ProfChain prof(stream);
     static const bool no_overlap = std::getenv("GDN_NO_OVERLAP") != nullptr;
-    const bool overlap = nw == 1 && n_bufs >= 2 && n_slabs > 1 && !no_overlap && sizeof(typename Elem<E>::Frag) == 16;
+    // The preparation of the next slab shares the recurrence's launch only while the recurrence leaves half
+    // of the compute units to it: the two kinds of workgroup cannot share a compute unit's LDS, so beyond that
+    // the preparation would be left with a few workgroups (measured at 64 chains: 1.77 ms shared, 0.56 ms apart).
+    const bool overlap = nw == 1 && n_bufs >= 2 && n_slabs > 1 && !no_overlap && sizeof(typename Elem<E>::Frag) == 16 &&
+                         n_chains * NS <= n_cus / 2;
     const int64_t items = (int64_t)n_req * R * units;
     if (items > INT32_MAX) return GDN_ERR_COUNT;
     auto launch_prep = [&](int32_t sb, char* buf, bool with_copies) -> hipError_t {
