@@ -311,13 +311,14 @@ hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
 }
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
-// plentiful (the chip stays full: two workgroups on each of 256 compute units) and the longest
-// chain does not outlast the whole two-kernel run.  Figures measured on MI355X (bf16, d = 128):
-// 12.8 us per chunk of one chain and 0.029 us per (chunk, chain) unit of a large call in the
-// fused kernel, 0.056 us per unit in the two-kernel path; with 512 chains or fewer the
-// two-kernel path wins (0.62 against 0.79 ms at 512 chains), from 1024 chains on the fused one
-// (0.90 against 1.03 ms at 1024 chains, 26 against 45 ms at 32768).  gdn_tune_fused (or GDN_FUSED=0/1
-// in the environment) forces the choice.
+// plentiful and the longest chain does not outlast the whole two-kernel run.  Estimates from
+// figures measured on MI355X (bf16, d = 128; one call of 8 to 96 requests of up to 8192 tokens,
+// and the large configurations): fused, per chunk of one chain 9 us with one workgroup per
+// compute unit (up to 256 chains) and 11.5 us with two, per (chunk, chain) unit of a large call
+// 0.035 us (0.029 at 32768 chains); two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured
+// crossover: 128 chains 1.12 ms fused against 0.75 ms, 256 chains 1.16 against 1.28, 512 chains
+// 1.45 against 2.16, 896 chains 2.28 against 3.61.  gdn_tune_fused (or GDN_FUSED=0/1 in the
+// environment) forces the choice.
 std::atomic<int32_t> g_forced_fused{-1};
 inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
     if (s.in_dtype != GDN_BF16 || s.d_k != 128 || s.d_v != 128) return false;
@@ -327,9 +328,10 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
     }();
     const int forced = g_forced_fused.load() >= 0 ? g_forced_fused.load() : env_forced;
     if (forced >= 0) return forced != 0;
-    if (n_chains < 1024) return false;
-    const double t_two = 0.056 * (double)total_units;
-    const double t_fused = std::max(0.029 * (double)total_units, 12.8 * (double)longest_chain_chunks);
+    if (n_chains < 128) return false;
+    const double per_chunk = n_chains <= 256 ? 9.0 : 11.5;   // us: one or two workgroups per compute unit
+    const double t_two = 0.056 * (double)total_units + 150.0;
+    const double t_fused = std::max(0.035 * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
 }
 
