@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed steps and their event pass (no latency sweep, pool copies, host tier, decode, "
                          "CPU baseline): what the profiler runs use")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time ONE call of k = 1..64 requests of this workload's kind (side object "
+                         "`batch_sweep`; about a minute of host-side input generation)")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP event pass (no roofline object)")
     ap.add_argument("--events-in-timed-region", action="store_true",
@@ -403,6 +406,31 @@ def main() -> int:
         torch.cuda.empty_cache()
     except Exception as exc:
         out["throughput"] = {"error": str(exc)}
+
+    # ---- optional: one call of k requests (k configs[1]-style draws packed together), to show how the variant
+    #      choice (latency variant, two or four slices per workgroup, fused kernel) behaves between the
+    #      batch-1 bench line and the throughput regime
+    if args.batch_sweep:
+        sweep = []
+        for kreq in (1, 2, 4, 8, 16, 32, 64):
+            try:
+                scs = wl.config1(B.gdn_deepest_ckpt, seed=SEED, n_draws=kreq, N=N_PREFIX, M=M_CKPT, H=HEADS, d=D)
+                gk = GpuCall(scs.resume, torch.randn((scs.n_slots, 1, HEADS, D, D), device=dev) * 0.1)
+                for _ in range(2):
+                    gk.run()
+                torch.cuda.synchronize()
+                tk0 = time.perf_counter()
+                for _ in range(5):
+                    gk.run()
+                torch.cuda.synchronize()
+                msk = 1e3 * (time.perf_counter() - tk0) / 5
+                sweep.append({"requests": kreq, "chains": kreq * HEADS, "suffix_tokens": scs.resume.total_tokens,
+                              "longest": int(np.diff(scs.resume.cu_seqlens).max()), "ms_per_call": msk,
+                              "tokens_per_s": scs.resume.total_tokens / (msk * 1e-3)})
+                del gk
+            except Exception as exc:
+                sweep.append({"requests": kreq, "error": str(exc)})
+        out["batch_sweep"] = sweep
 
     # ---- layer front end (short convolution + SiLU + q/k norm + gates, resumed from stored convolution states) and
     #      back end (gated output norm): memory bound; 32 requests x 2048 tokens of this layer shape, bf16
