@@ -115,10 +115,14 @@ int32_t gdn_layer_inputs(const gdn_layer_shape* s, const void* x_qkv, const floa
     for (const void* p : ptrs)
         if (!aligned16(p)) return GDN_ERR_ALIGN;
     const int64_t per16 = 16 / elem_bytes(s->in_dtype);
-    if ((any_src && (src_slot_stride % per16 || src_slot_stride < K1 * C)) ||
-        (n_emit > 0 && (dst_slot_stride % per16 || dst_slot_stride < K1 * C)))
-        return any_src && src_slot_stride % per16 ? GDN_ERR_ALIGN
-                                                  : (n_emit > 0 && dst_slot_stride % per16 ? GDN_ERR_ALIGN : GDN_ERR_SHAPE);
+    if (any_src) {
+        if (src_slot_stride % per16) return GDN_ERR_ALIGN;
+        if (src_slot_stride < K1 * C) return GDN_ERR_SHAPE;
+    }
+    if (n_emit > 0) {
+        if (dst_slot_stride % per16) return GDN_ERR_ALIGN;
+        if (dst_slot_stride < K1 * C) return GDN_ERR_SHAPE;
+    }
     const int64_t need = gdn_layer_workspace_bytes(n_req, n_emit);
     if (!workspace || !aligned16(workspace) || workspace_bytes < need) return GDN_ERR_WORKSPACE;
 
