@@ -178,6 +178,17 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         if (TAIL > 0 && tid < TAIL) pre_tail = src_[NFULL * NT];                  \
     }
     if (STAGED) GDN_PREFETCH_IMAGE(unit)
+    // U~ of this wave's slice travels outside the staged image; it is fetched one chunk ahead as well, so
+    // that no global load sits at the head of a chunk's dependent chain
+    typedef typename EL::UtVec UtVec;
+    constexpr int NUT = 2 * EL::UT_PIECES;
+    UtVec ut_pre[NUT];
+#define GDN_PREFETCH_UT(ptr)                                                                     \
+    {                                                                                            \
+        const UtVec* ut_ = reinterpret_cast<const UtVec*>((ptr) + U::UT_OFF) + (sl * NUT) * 64 + lane; \
+        _Pragma("unroll") for (int k_ = 0; k_ < NUT; ++k_) ut_pre[k_] = ut_[k_ * 64];           \
+    }
+    GDN_PREFETCH_UT(unit)
 
     for (int c = c_begin; c < c_end; ++c, unit += unit_stride) {
 
@@ -203,17 +214,11 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
         const int n = meta[AUX_LEN];
         const int64_t row0 = (int64_t)l * a.T_alloc + meta[AUX_TOK0];
 
-        // U~ (this slice), already in accumulator order
+        // U~ (this slice), already in accumulator order; then the next chunk's is requested
         f32x16 accU[2];
-        {
-            typedef typename EL::UtVec UtVec;
-            const UtVec* ut = reinterpret_cast<const UtVec*>(unit + U::UT_OFF);
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int pc = 0; pc < EL::UT_PIECES; ++pc)
-                    EL::ut_unpack(ut[((sl * 2 + rt) * EL::UT_PIECES + pc) * 64 + lane], accU[rt], pc);
-        }
+        for (int k = 0; k < NUT; ++k) EL::ut_unpack(ut_pre[k], accU[k / EL::UT_PIECES], k % EL::UT_PIECES);
+        GDN_PREFETCH_UT((c + 1 < c_end) ? unit + unit_stride : unit)
 
         // state as the B operand of the two products that contract over d_k
         Frag sf[NKD];
@@ -267,6 +272,7 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
 }
 
 #undef GDN_PREFETCH_IMAGE
+#undef GDN_PREFETCH_UT
 
 template <typename E, int DK, int DV>
 constexpr int recur_smem_bytes() {
