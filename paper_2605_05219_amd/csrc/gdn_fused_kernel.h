@@ -119,12 +119,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     static_assert((C / 4) * (DK / 8) == 256 && (C / 4) * (DV / 8) == 256, "one block per thread");
 
     // ---- the workgroup's items: the chunks of chains blockIdx.x, blockIdx.x + gridDim.x, ...
-    struct Item { int chain, c, c_end, lh, tok0, n; };   // chain < 0: none
+    struct Item { int chain, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
     auto open_chain = [&](int chain) -> Item {
         Item it;
         for (;; chain += (int)gridDim.x) {
             it.chain = chain < a.n_chains ? chain : -1;
             it.c = it.c_end = it.lh = it.tok0 = it.n = 0;
+            it.eslot = -1;
             if (it.chain < 0) return it;
             const int r = a.req_order[chain / units];
             it.lh = chain % units;
@@ -134,6 +135,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         it.tok0 = a.chunk_tok0[it.c];
         it.n = a.chunk_len[it.c];
+        it.eslot = a.chunk_emit_slot[it.c];
         return it;
     };
     auto next_item = [&](const Item& cur) -> Item {
@@ -142,6 +144,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             it.c = cur.c + 1;
             it.tok0 = a.chunk_tok0[it.c];
             it.n = a.chunk_len[it.c];
+            it.eslot = a.chunk_emit_slot[it.c];
             return it;
         }
         return open_chain(cur.chain + (int)gridDim.x);
@@ -202,7 +205,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         // registers, 2.4 times slower).
         int lane = lane_, lr = lr_, g = g_, m16 = m16_, g4 = g4_, tg = tg_, d0 = d0_, tgv = tgv_, d0v = d0v_;
         pin(lane); pin(lr); pin(g); pin(m16); pin(g4); pin(tg); pin(d0); pin(tgv); pin(d0v);
-        const int c = cur.c;
         const int n = cur.n;
         const int l = cur.lh / a.H_v, hv = cur.lh % a.H_v;
         const int sl = wave;
@@ -448,7 +450,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int s = 0; s < NKC; ++s) accS[mt] = EL::mma(EL::load(kr, s, g), uf[s], accS[mt]);
             }
             // checkpoint emission: exact state after the last token of this chunk
-            const int eslot = a.chunk_emit_slot[c];
+            const int eslot = cur.eslot;   // looked up one item ahead, with the chunk's other bookkeeping
             if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
         }
 

@@ -327,7 +327,6 @@ __device__ __forceinline__ void recur_quad_body(const RecurArgs& a, const int wg
     constexpr int C = 64;
     constexpr int NS = DV / 32;
     constexpr int SPT = EL::STEPS_PER_TILE;
-    constexpr int RPS = 16 / SPT;            // accumulator registers one step consumes as operand
     constexpr int NKD = U::NKD;
     constexpr int NKC = U::NKC;
     constexpr int MT = DK / 32;

@@ -673,7 +673,6 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return GDN_ERR_ALIGN;
 
     const WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
-    const int64_t pb = wl.plan;
     int32_t n_staged = 0;
     if (src_on_host)
         for (int32_t r = 0; r < n_req; ++r) n_staged += src_slot[r] >= 0;
