@@ -342,8 +342,10 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
     int nw = ns;
     while (nw > 1 && n_chains * (ns / nw) < 512) nw >>= 1;
     // A latency-variant workgroup fills a compute unit's LDS: with more of them than compute units
-    // they would run in turns (measured: 96 chains 1.0 ms against 0.70 ms with two slices per workgroup).
-    if (nw == 1 && n_chains * ns > CHIP_CUS) nw = 2;
+    // they would run in turns (measured: 96 chains 1.0 ms against 0.70 ms with two slices per
+    // workgroup), and once they take the whole chip no preparation can run beside them (64 chains:
+    // 0.55 ms against 0.49 ms with two slices per workgroup; 48 chains: even).
+    if (nw == 1 && n_chains * ns > (CHIP_CUS * 3) / 4) nw = 2;
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && ns == 4)) nw = o;
     }
