@@ -343,14 +343,22 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
     while (nw > 1 && n_chains * (ns / nw) < 512) nw >>= 1;
     // A latency-variant workgroup fills a compute unit's LDS: with more of them than compute units
     // they would run in turns (measured: 96 chains 1.0 ms against 0.70 ms with two slices per
-    // workgroup), and once they take the whole chip no preparation can run beside them (64 chains:
-    // 0.55 ms against 0.49 ms with two slices per workgroup; 48 chains: even).
-    if (nw == 1 && n_chains * ns > (CHIP_CUS * 3) / 4) nw = 2;
+    // workgroup).
+    if (nw == 1 && n_chains * ns > CHIP_CUS) nw = 2;
     if (const int o = recur_waves_override()) {
         if (o == 1 || o == 2 || (o == 4 && ns == 4)) nw = o;
     }
     if (nw == 1 && !frag16) nw = 2;   // fp32 operands: the latency variant's registers are sized for 16-byte fragments
     return nw;
+}
+
+// Latency variant: does the preparation of the next slab share the recurrence's launch?  Only while the
+// recurrence leaves half of the compute units to it: the two kinds of workgroup cannot share a compute
+// unit's LDS, so beyond that the preparation would be left with a few workgroups (measured at 64 chains:
+// 1.77 ms shared, 0.56 ms apart).
+inline bool latency_shared(int64_t n_chains, int ns) {
+    static const bool no_overlap = std::getenv("GDN_NO_OVERLAP") != nullptr;
+    return !no_overlap && n_chains * ns <= CHIP_CUS / 2;
 }
 
 // Chunk rounds per slab.  In the latency variant the slab should stay cache resident between the preparation launch
@@ -359,9 +367,13 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
 // the 256 compute units); the throughput variants only bound the workspace.  gdn_tune_slab_rounds
 // overrides the choice.
 std::atomic<int32_t> g_forced_rounds{0};
-inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw) {
+inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw, int ns) {
     const int32_t forced = g_forced_rounds.load();
     if (forced > 0) return forced;
+    // Latency variant with launches apart (33 to 64 chains at four slices): every slab costs two launches
+    // and a hand-over of the states, so slabs are long (measured at 64 chains: 0.56 ms with 8 rounds, 0.31 ms
+    // with 64).
+    if (nw == 1 && !latency_shared(n_chains, ns)) return 64;
     // Throughput variants: the states are carried through memory from slab to slab (d_v d_k floats per
     // chain each way), so a slab is at least 8 rounds long whatever the budget says.
     const int64_t budget = nw == 1 ? (int64_t)48 << 20 : (int64_t)1 << 30;
@@ -401,12 +413,7 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
     // back by the recurrence launch right behind it while they are still in the caches.  With two
     // slab buffers (latency variant) the preparation of the next slab shares the recurrence's launch.
     ProfChain prof(stream);
-    static const bool no_overlap = std::getenv("GDN_NO_OVERLAP") != nullptr;
-    // The preparation of the next slab shares the recurrence's launch only while the recurrence leaves half
-    // of the compute units to it: the two kinds of workgroup cannot share a compute unit's LDS, so beyond that
-    // the preparation would be left with a few workgroups (measured at 64 chains: 1.77 ms shared, 0.56 ms apart).
-    const bool overlap = nw == 1 && n_bufs >= 2 && n_slabs > 1 && !no_overlap && sizeof(typename Elem<E>::Frag) == 16 &&
-                         n_chains * NS <= n_cus / 2;
+    const bool overlap = nw == 1 && n_bufs >= 2 && n_slabs > 1 && sizeof(typename Elem<E>::Frag) == 16 && latency_shared(n_chains, NS);
     const int64_t items = (int64_t)n_req * R * units;
     if (items > INT32_MAX) return GDN_ERR_COUNT;
     auto launch_prep = [&](int32_t sb, char* buf, bool with_copies) -> hipError_t {
@@ -438,7 +445,7 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
                     pl.ws_units = slab_base + ((sb + 1) & 1) * slab_bytes;
                     pl.slab_begin = (sb + 1) * R;
                     pl.n_copy_wgs = 0;
-                    e = launch_quad_overlap<E, DK, DV>(ra, pl, n_chains, items, n_cus, stream);
+                    e = launch_quad_overlap<E, DK, DV>(ra, pl, n_chains, items, CHIP_CUS, stream);
                 } else {
                     e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
                 }
@@ -599,11 +606,11 @@ static WsLayout ws_layout(const gdn_shape& s, int64_t n_chunks, int64_t max_roun
     const int64_t units = (int64_t)s.L * s.H_v, n_chains = units * n_req, ub = unit_bytes(s);
     const int nw = pick_waves(n_chains, s.d_v / 32, s.in_dtype != GDN_F32);
     WsLayout w;
-    w.R = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slab_rounds(n_chains, ub, nw), max_rounds));
+    w.R = (int32_t)std::max<int64_t>(1, std::min<int64_t>(slab_rounds(n_chains, ub, nw, s.d_v / 32), max_rounds));
     w.plan = plan_bytes(n_chunks, n_req);
     w.carry = align_up(n_chains * s.d_v * s.d_k * (int64_t)sizeof(float), 256);
     w.slab = n_chains * w.R * ub;
-    w.n_bufs = nw == 1 ? 2 : 1;   // latency variant: the next slab is prepared while this one is consumed
+    w.n_bufs = (nw == 1 && latency_shared(n_chains, s.d_v / 32)) ? 2 : 1;   // two buffers: the next slab is prepared while this one is consumed
     w.total = w.plan + w.carry + w.n_bufs * w.slab;
     return w;
 }

@@ -148,8 +148,8 @@ def test_destination_may_be_own_source_slot():
 @pytest.mark.parametrize("n_req", [2, 3, 4, 6, 12, 16, 32])
 def test_batch_sizes_cover_every_launch_shape(n_req):
     """16 heads x n_req requests: 32 chains run the latency variant with the next slab's preparation sharing the
-    recurrence's launch, 48 chains the latency variant with separate launches (the recurrence takes most of the chip),
-    64 to 256 chains two value-head slices per workgroup or the fused kernel, 512 chains the fused kernel."""
+    recurrence's launch, 48 and 64 chains the latency variant with separate launches (the recurrence takes most of the chip),
+    96 to 256 chains two value-head slices per workgroup or the fused kernel, 512 chains the fused kernel."""
     sc = wl.config2(orc.deepest_ckpt, seed=2000 + n_req, n_req=n_req, N=1024, M=4, tail=70)
     pool, _, _ = fill_pool_from_oracle(sc)
     check_call(sc.resume, pool, TOL["bf16"])
