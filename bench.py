@@ -190,6 +190,18 @@ def main() -> int:
             "token_heads_per_launch": units_per_launch,
             "flop_per_token_head": dom_flop,
         }
+        # The same launches against the memory roof: by arithmetic intensity (flop per algorithmic byte, below the
+        # ridge of 2500 TFLOP/s over 8 TB/s = 312) the memory roof is the one a saturated run of this path would hit
+        # first; this batch-1 workload saturates neither (it is bound by the per-chunk dependent chain).
+        if rec_dom:
+            in_bytes = (2 * D + D) * 2 + 2 * 2          # q, k, v, beta, gate per token.head (read by the preparation)
+            dom_bytes = token_heads * (D * 4) + later * in_bytes
+            gbs = dom_bytes / (dom_ms * 1e-3) / 1e9
+            out["roofline"]["memory_view"] = {
+                "algorithmic_bytes_per_launch": dom_bytes / dom_n, "achieved_gbs": gbs, "peak_gbs": PEAK_HBM_GBS,
+                "frac": gbs / PEAK_HBM_GBS, "flop_per_byte": dom_flops_total / dom_bytes,
+                "ridge_flop_per_byte": PEAK_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS,
+            }
         out["kernels"] = {
             "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps, "launches": prep_n,
                                 "avg_launch_ms": prep_ms / max(prep_n, 1),
