@@ -135,7 +135,8 @@ int32_t ckpt_scatter(float *pool, int64_t slot_stride, int32_t n_slots,
  * Request r owns packed tokens [cu_seqlens[r], cu_seqlens[r+1]); they are the tokens at
  * absolute positions start_pos[r]+1 .. of its sequence.  A zero-length request is legal and
  * does nothing.  bf16 inputs must be finite and below 65504 in magnitude (they are widened
- * exactly to fp16 for the matrix cores).
+ * exactly to fp16 for the matrix cores), and the states must stay below it too: on the bf16
+ * path the state and the per-chunk updates enter the matrix cores rounded to fp16.
  *
  *   cu_seqlens  host int32 [n_req+1], cu_seqlens[0] == 0, non-decreasing, last <= T_alloc
  *   start_pos   host int32 [n_req], >= 0: position l_r of the loaded state
