@@ -274,6 +274,13 @@ int32_t gdn_tune_slab_rounds(int32_t rounds);
  */
 int32_t gdn_tune_fused(int32_t mode);
 
+/*
+ * Environment variables, read once per process, for experiments only (results meet the same
+ * tolerances under every setting): GDN_FUSED=0|1 as gdn_tune_fused; GDN_NO_OVERLAP (any value)
+ * keeps the preparation of a slab out of the previous slab's recurrence launch;
+ * GDN_RECUR_WAVES=1|2|4 forces the value-head slices per recurrence workgroup.
+ */
+
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);
 
