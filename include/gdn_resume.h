@@ -278,7 +278,8 @@ int32_t gdn_tune_fused(int32_t mode);
  * Environment variables, read once per process, for experiments only (results meet the same
  * tolerances under every setting): GDN_FUSED=0|1 as gdn_tune_fused; GDN_NO_OVERLAP (any value)
  * keeps the preparation of a slab out of the previous slab's recurrence launch;
- * GDN_RECUR_WAVES=1|2|4 forces the value-head slices per recurrence workgroup.
+ * GDN_RECUR_WAVES=1|2|4 forces the value-head slices per recurrence workgroup; GDN_NO_RING
+ * (any value) keeps the register-staged recurrence kernel where the LDS-ring one would run.
  */
 
 /* Version of the library (major * 100 + minor). */

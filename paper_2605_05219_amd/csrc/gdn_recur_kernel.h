@@ -274,6 +274,191 @@ __global__ void __launch_bounds__(64 * NW) gdn_recur_kernel(RecurArgs a) {
 #undef GDN_PREFETCH_IMAGE
 #undef GDN_PREFETCH_UT
 
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left alone)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
+}
+
+// Ring variant, for calls with at most one such workgroup per compute unit: NSW value-head slices of a
+// chain per workgroup, one computing wave per slice and one more wave that only loads.  The operand image
+// of a chunk and the U~ slices of this workgroup are copied into one of two LDS stages with 16-byte
+// global->LDS loads (no registers) while the computing waves work on the other stage, so no global load
+// sits on a chunk's dependent chain.  One barrier per chunk: the computing waves reach it when every LDS
+// read of their stage has returned, the loader when the next chunk has landed.
+template <typename E, int DK, int DV, int NSW>
+struct RingSmem {
+    typedef UnitLayout<E, DK, DV> U;
+    static constexpr int IMG_PIECES = U::STAGED_BYTES / 1024;                  // whole 1 KiB pieces of the image
+    static constexpr int IMG_TAIL_LANES = (U::STAGED_BYTES % 1024) / 16;      // lanes of its last, partial piece
+    static constexpr int UT_PIECES = NSW * U::UT_SLICE_BYTES / 1024;
+    static constexpr int UT_OFF = (U::STAGED_BYTES + 1023) / 1024 * 1024;     // U~ slices behind the image
+    static constexpr int STAGE_BYTES = UT_OFF + NSW * U::UT_SLICE_BYTES;
+    static constexpr int BYTES = 2 * STAGE_BYTES;
+    static_assert(BYTES <= 160 * 1024, "LDS");
+    static_assert((NSW * U::UT_SLICE_BYTES) % 1024 == 0 && U::STAGED_BYTES % 16 == 0, "piece sizes");
+};
+
+template <typename E, int DK, int DV, int NSW>
+__device__ __forceinline__ void recur_ring_body(const RecurArgs& a, const int block) {
+    typedef Elem<E> EL;
+    typedef typename EL::Frag Frag;
+    typedef typename EL::UtVec UtVec;
+    typedef UnitLayout<E, DK, DV> U;
+    typedef RingSmem<E, DK, DV, NSW> SM;
+    constexpr int C = 64;
+    constexpr int NS = DV / 32;
+    constexpr int SG = NS / NSW;             // workgroups per chain
+    constexpr int SPT = EL::STEPS_PER_TILE;
+    constexpr int NKD = U::NKD;
+    constexpr int NKC = U::NKC;
+    constexpr int MT = DK / 32;
+    constexpr int NUT = 2 * EL::UT_PIECES;
+
+    extern __shared__ __align__(16) char smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
+    const int lr = lane & 31;
+    const int g = lane >> 5;
+
+    const int units = a.L * a.H_v;
+    const int sg = block % SG;
+    const int chain = block / SG;
+    const int r = a.req_order[chain / units];
+    const int lh = chain % units;
+    const int l = lh / a.H_v;
+    const int hv = lh % a.H_v;
+    const int c_last = a.req_chunk_cu[r + 1];
+    const int c_begin = a.req_chunk_cu[r] + a.slab_begin;
+    if (c_begin >= c_last) return;
+    const int n_chunks = min(c_last - c_begin, a.R);
+    const int64_t unit_stride = (int64_t)units * U::UNIT_BYTES;
+    const char* unit0 = a.ws_units + ((int64_t)r * a.R * units + lh) * U::UNIT_BYTES;
+
+    if (wave == NSW) {
+        // ------------------------------------------------------------ loader wave
+        // A chunk is more pieces than the 6-bit outstanding-load counter should hold at once: it is
+        // issued in two parts with a wait in between.
+        constexpr int NP = SM::IMG_PIECES;
+        constexpr int NA = NP > 40 ? 40 : NP, NB = NP - NA;
+        static_assert(16 + NB + 1 + SM::UT_PIECES <= 63 && NA <= 63, "parts vs the outstanding-load counter");
+        auto issue = [&](int i) {
+            const char* src = unit0 + i * unit_stride + lane * 16;
+            char* dst = smem + (i & 1) * SM::STAGE_BYTES;
+#pragma unroll
+            for (int k = 0; k < NA; ++k)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024),
+                                                 (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
+            if (NB > 0) wait_vmcnt<16>();
+#pragma unroll
+            for (int k = NA; k < NP; ++k)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + k * 1024),
+                                                 (__attribute__((address_space(3))) void*)(dst + k * 1024), 16, 0, 0);
+            if (SM::IMG_TAIL_LANES > 0 && lane < SM::IMG_TAIL_LANES)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + NP * 1024),
+                                                 (__attribute__((address_space(3))) void*)(dst + NP * 1024), 16, 0, 0);
+            const char* usrc = src + U::UT_OFF + (sg * NSW) * U::UT_SLICE_BYTES;
+#pragma unroll
+            for (int k = 0; k < SM::UT_PIECES; ++k)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(usrc + k * 1024),
+                                                 (__attribute__((address_space(3))) void*)(dst + SM::UT_OFF + k * 1024), 16, 0, 0);
+        };
+        issue(0);
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();               // chunk 0 is in stage 0
+        for (int i = 0; i < n_chunks; ++i) {
+            if (i + 1 < n_chunks) issue(i + 1);     // into the stage the computing waves left at the last barrier
+            wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();           // chunk i is consumed, chunk i + 1 has landed
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------- computing waves
+    const int sl = sg * NSW + wave;          // this wave's d_v slice
+    f32x16 accS[MT];
+    const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK + (int64_t)(32 * sl + lr) * DK;
+    float* const carry = a.carry + (int64_t)r * units * DV * DK + head_off;
+    {
+        const int slot = a.req_src_slot[r];
+        if (a.slab_begin > 0) {
+            load_state<MT>(accS, carry, g);
+        } else if (slot >= 0) {
+            load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) accS[mt][i] = 0.f;
+        }
+    }
+    __syncthreads();   // chunk 0 is in stage 0
+    for (int i = 0; i < n_chunks; ++i) {
+        const char* img = smem + (i & 1) * SM::STAGE_BYTES;
+        const Frag* w_img = reinterpret_cast<const Frag*>(img + U::W_OFF) + lane;
+        const Frag* q_img = reinterpret_cast<const Frag*>(img + U::Q_OFF) + lane;
+        const Frag* kt_img = reinterpret_cast<const Frag*>(img + U::KT_OFF) + lane;
+        const Frag* p_img = reinterpret_cast<const Frag*>(img + U::P_OFF) + lane;
+        const UtVec* ut = reinterpret_cast<const UtVec*>(img + SM::UT_OFF) + (wave * NUT) * 64 + lane;
+        const float* gamS = reinterpret_cast<const float*>(img + U::AUX_OFF);
+        const int32_t* meta = reinterpret_cast<const int32_t*>(gamS + 2 * C);
+        const int eslot = meta[AUX_EMIT_SLOT];
+        const int n = meta[AUX_LEN];
+        const int64_t row0 = (int64_t)l * a.T_alloc + meta[AUX_TOK0];
+
+        f32x16 accU[2];
+#pragma unroll
+        for (int k = 0; k < NUT; ++k) EL::ut_unpack(ut[k * 64], accU[k / EL::UT_PIECES], k % EL::UT_PIECES);
+        Frag sf[NKD];
+#pragma unroll
+        for (int s = 0; s < NKD; ++s) sf[s] = EL::from_acc(accS[s / SPT], s % SPT);
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int s = 0; s < NKD; ++s) accU[rt] = EL::mma(w_img[(rt * NKD + s) * 64], sf[s], accU[rt]);
+        Frag uf[2 * SPT];
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+            for (int s = 0; s < SPT; ++s) uf[rt * SPT + s] = EL::from_acc(accU[rt], s);
+        const float gam_last = gamS[C - 1];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) accS[mt][k] *= gam_last;
+#pragma unroll
+            for (int s = 0; s < NKC; ++s) accS[mt] = EL::mma(kt_img[(mt * NKC + s) * 64], uf[s], accS[mt]);
+        }
+        if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
+        f32x16 ot[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            f32x16 acc = {0};
+#pragma unroll
+            for (int s = 0; s < NKD; ++s) acc = EL::mma(sf[s], q_img[(tt * NKD + s) * 64], acc);
+            const float gm = gamS[32 * tt + lr] * a.scale;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc[k] *= gm;
+#pragma unroll
+            for (int s = 0; s < (tt + 1) * SPT; ++s) acc = EL::mma(uf[s], p_img[(tt * NKC + s) * 64], acc);
+            ot[tt] = acc;
+        }
+        store_o_t<DV>(a, row0, hv, sl, lr, g, n, ot);
+        // Done with this stage once every LDS read has returned; the stores of O stay in flight across
+        // the barrier (waiting for them here would put a memory round trip on every chunk).
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+        __builtin_amdgcn_s_barrier();         // the next chunk has landed in the other stage
+    }
+    if (c_begin + n_chunks < c_last) store_state<MT>(accS, carry, g);
+}
+
+template <typename E, int DK, int DV, int NSW>
+__global__ void __launch_bounds__(64 * (NSW + 1)) gdn_recur_ring_kernel(RecurArgs a) {
+    recur_ring_body<E, DK, DV, NSW>(a, (int)blockIdx.x);
+}
+
 template <typename E, int DK, int DV>
 constexpr int recur_smem_bytes() {
     return UnitLayout<E, DK, DV>::STAGED_BYTES;
@@ -308,12 +493,6 @@ struct QuadSmem {
     static constexpr int DMA_PER_STAGE = STAGE_BYTES / 1024;
     static_assert(BYTES <= 160 * 1024, "LDS");
 };
-
-// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left alone)
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
-}
 
 #define GDN_FENCE() __builtin_amdgcn_sched_barrier(0)   // nothing is scheduled across this point
 

@@ -149,13 +149,14 @@ def test_destination_may_be_own_source_slot():
 def test_batch_sizes_cover_every_launch_shape(n_req):
     """16 heads x n_req requests: 32 chains run the latency variant with the next slab's preparation sharing the
     recurrence's launch, 48 and 64 chains the latency variant with separate launches (the recurrence takes most of the chip),
-    96 to 256 chains two value-head slices per workgroup or the fused kernel, 512 chains the fused kernel."""
+    96 chains two value-head slices per workgroup fed through an LDS ring, 192 chains the register-staged kernel, 256 and
+    512 chains the fused kernel."""
     sc = wl.config2(orc.deepest_ckpt, seed=2000 + n_req, n_req=n_req, N=1024, M=4, tail=70)
     pool, _, _ = fill_pool_from_oracle(sc)
     check_call(sc.resume, pool, TOL["bf16"])
 
 
-@pytest.mark.parametrize("n_req,dtype", [(1, "bf16"), (4, "bf16"), (32, "bf16"), (3, "f32")])
+@pytest.mark.parametrize("n_req,dtype", [(1, "bf16"), (4, "bf16"), (6, "bf16"), (32, "bf16"), (3, "f32")])
 @pytest.mark.parametrize("rounds", [1, 3])
 def test_short_slabs_carry_the_state_bitwise(n_req, dtype, rounds):
     """Slabs of 1 or 3 chunk rounds: every recurrence variant hands its state from slab to slab
