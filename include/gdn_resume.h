@@ -23,6 +23,9 @@
  *     upload to leave a small pinned staging buffer the library owns.
  *   - Every argument is validated on the host before anything is enqueued; on error nothing
  *     is enqueued and a negative code is returned.  HIP failures return GDN_ERR_HIP - hipError.
+ *   - The library is written for one GPU per process (kernel attributes and the device's size
+ *     are looked up once, on the device that is current at the first call); calls may come from
+ *     several host threads and streams.
  *   - A checkpoint slot holds the states of all layers and value heads of one position:
  *     [L][H_v][d_v][d_k] fp32, contiguous; a pool is slots at a fixed stride (in floats).
  */
