@@ -265,6 +265,29 @@ def test_run_to_run_bitwise_determinism():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
 
 
+def test_calls_on_a_side_stream_and_interleaved_streams_are_bitwise_the_default_stream_result():
+    """The library enqueues on the caller's stream only: a call on a side stream, and two calls with their own
+    workspaces interleaved on two streams, give the default-stream result bit for bit."""
+    import torch
+    from tests.harness import GpuCall
+    sc = wl.config2(orc.deepest_ckpt, seed=17, n_req=5, N=1024, M=4, tail=40)
+    pool, _, _ = fill_pool_from_oracle(sc)
+    ref_o, ref_pool = run_call_gpu(sc.resume, pool)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    g1, g2 = GpuCall(sc.resume, pool), GpuCall(sc.resume, pool)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        with torch.cuda.stream(s1):
+            g1.run(s1)
+        with torch.cuda.stream(s2):
+            g2.run(s2)
+    torch.cuda.synchronize()
+    T = sc.resume.total_tokens
+    for g in (g1, g2):
+        assert np.array_equal(g.o[:, :T].float().cpu().numpy(), ref_o)
+        assert np.array_equal(g.pool.cpu().numpy(), ref_pool)
+
+
 # ------------------------------------------------------------------ the configurations at full size
 def test_config1_full_size_build_and_resume():
     """N = 8192, 16 heads, d = 128, M = 16: the entry build (8192 tokens) and resumes at seeded
