@@ -233,13 +233,12 @@ template <typename E, int DK, int DV, int NW>
 hipError_t launch_recur_nw(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
     constexpr int SG = (DV / 32) / NW;
     constexpr int smem = recur_smem_bytes<E, DK, DV>();
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per process, also when several host threads make their first call together
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    std::call_once(once, [] { once_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_kernel<E, DK, DV, NW>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+    if (once_err != hipSuccess) return once_err;
     hipLaunchKernelGGL((gdn_recur_kernel<E, DK, DV, NW>), dim3((unsigned)(n_chains * SG)), dim3(64 * NW), smem, stream, ra);
     return hipGetLastError();
 }
@@ -248,13 +247,12 @@ template <typename E, int DK, int DV, int NSW>
 hipError_t launch_recur_ring(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
     constexpr int smem = RingSmem<E, DK, DV, NSW>::BYTES;
     constexpr int SG = (DV / 32) / NSW;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_ring_kernel<E, DK, DV, NSW>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per process, also when several host threads make their first call together
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    std::call_once(once, [] { once_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_ring_kernel<E, DK, DV, NSW>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+    if (once_err != hipSuccess) return once_err;
     hipLaunchKernelGGL((gdn_recur_ring_kernel<E, DK, DV, NSW>), dim3((unsigned)(n_chains * SG)), dim3(64 * (NSW + 1)), smem, stream,
                        ra);
     return hipGetLastError();
@@ -263,13 +261,12 @@ hipError_t launch_recur_ring(const RecurArgs& ra, int64_t n_chains, hipStream_t 
 template <typename E, int DK, int DV>
 hipError_t launch_recur_quad(const RecurArgs& ra, int64_t n_chains, hipStream_t stream) {
     constexpr int smem = QuadSmem<E, DK, DV>::BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_quad_kernel<E, DK, DV>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per process, also when several host threads make their first call together
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    std::call_once(once, [] { once_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_recur_quad_kernel<E, DK, DV>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+    if (once_err != hipSuccess) return once_err;
     hipLaunchKernelGGL((gdn_recur_quad_kernel<E, DK, DV>), dim3((unsigned)(n_chains * (DV / 32))), dim3(256), smem, stream, ra);
     return hipGetLastError();
 }
@@ -292,13 +289,12 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
                                hipStream_t stream) {
     constexpr int smem = QuadSmem<E, DK, DV>::BYTES > PrepSmem<E, DK, DV>::BYTES ? QuadSmem<E, DK, DV>::BYTES
                                                                                : PrepSmem<E, DK, DV>::BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_quad_overlap_kernel<E, DK, DV>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // once per process, also when several host threads make their first call together
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    std::call_once(once, [] { once_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_quad_overlap_kernel<E, DK, DV>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, smem); });
+    if (once_err != hipSuccess) return once_err;
     const int n_recur = (int)(n_chains * (DV / 32));
     const int n_prep = (int)std::min<int64_t>(prep_items, std::max(cus - n_recur, 16));   // one workgroup per compute unit
     hipLaunchKernelGGL((gdn_quad_overlap_kernel<E, DK, DV>), dim3((unsigned)(n_recur + n_prep)), dim3(256), smem, stream, ra, pa,
@@ -309,18 +305,20 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
 // Fused throughput kernel (bf16 inputs, d = 128): see gdn_fused_kernel.h.
 hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
     typedef FusedSmem<128, 128> SM;
-    static int slots = 0;
-    if (slots == 0) {
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    static int slots = 1;
+    std::call_once(once, [] {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<128, 128>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
-        if (e != hipSuccess) return e;
         int dev = 0, cus = 0, per_cu = 0;
-        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<128, 128>, 256, SM::BYTES);
-        if (e != hipSuccess) return e;
-        slots = std::max(1, cus * per_cu);
-    }
+        once_err = e;
+        if (e == hipSuccess) slots = std::max(1, cus * per_cu);
+    });
+    if (once_err != hipSuccess) return once_err;
     hipLaunchKernelGGL((gdn_fused_kernel<128, 128>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
                        stream, fa);
     return hipGetLastError();
@@ -404,20 +402,21 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
                    char* slab_base, int64_t slab_bytes, int32_t n_bufs, hipStream_t stream) {
     typedef PrepSmem<E, DK, DV> SM;
     // workgroups of the preparation kernel the chip holds at once (per kernel instance)
-    static int prep_slots = 0, n_cus = 0;
-    if (prep_slots == 0) {
+    static std::once_flag once;
+    static hipError_t once_err = hipSuccess;
+    static int prep_slots = 1;
+    std::call_once(once, [] {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_prep_kernel<E, DK, DV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
-        if (e != hipSuccess) return hip_err(e);
         int dev = 0, cus = 0, per_cu = 0;
-        e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
             e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_prep_kernel<E, DK, DV>, 256, SM::BYTES);
-        if (e != hipSuccess) return hip_err(e);
-        prep_slots = std::max(1, cus * per_cu);
-        n_cus = cus;
-    }
+        once_err = e;
+        if (e == hipSuccess) prep_slots = std::max(1, cus * per_cu);
+    });
+    if (once_err != hipSuccess) return hip_err(once_err);
     const int units = s.L * s.H_v;
     const int64_t n_chains = (int64_t)n_req * units;
     constexpr int NS = DV / 32;
