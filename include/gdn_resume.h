@@ -238,7 +238,8 @@ int32_t gdn_decode_step(const gdn_shape *shape,
  * the totals and starts recording, gdn_profile_enable(0) stops.  gdn_profile_collect waits (on
  * the host) for the recorded events and returns, since recording started: the summed
  * intervals per kernel in milliseconds, the number of calls, and the number of launches of
- * each kernel; any output pointer may be NULL.
+ * each kernel; any output pointer may be NULL.  The intervals are taken between consecutive
+ * events of all calls: meaningful only while calls do not overlap in time.
  */
 int32_t gdn_profile_enable(int32_t on);
 int32_t gdn_profile_collect(double *prep_ms, double *recur_ms, int64_t *calls,

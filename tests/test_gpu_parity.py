@@ -288,6 +288,42 @@ def test_calls_on_a_side_stream_and_interleaved_streams_are_bitwise_the_default_
         assert np.array_equal(g.pool.cpu().numpy(), ref_pool)
 
 
+def test_two_host_threads_calling_concurrently_get_the_single_thread_result():
+    """Two host threads, each with its own stream, tensors and workspace, call the library at the same time (ctypes
+    drops the interpreter lock during a call): the shared plan staging buffer and the one-time set-up are guarded, and
+    every call's result is the single-thread result bit for bit."""
+    import threading
+    import torch
+    from tests.harness import GpuCall
+    scs = [wl.config2(orc.deepest_ckpt, seed=21 + i, n_req=3 + 2 * i, N=1024, M=4, tail=40) for i in range(2)]
+    pools = [fill_pool_from_oracle(sc)[0] for sc in scs]
+    refs = [run_call_gpu(sc.resume, pool) for sc, pool in zip(scs, pools)]
+    calls = [GpuCall(sc.resume, pool) for sc, pool in zip(scs, pools)]
+    streams = [torch.cuda.Stream() for _ in scs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            for _ in range(25):
+                calls[i].run(streams[i])
+            streams[i].synchronize()
+        except Exception as exc:   # surfaced below: an exception in a thread would otherwise be lost
+            errors.append(exc)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for i, sc in enumerate(scs):
+        T = sc.resume.total_tokens
+        assert np.array_equal(calls[i].o[:, :T].float().cpu().numpy(), refs[i][0])
+        assert np.array_equal(calls[i].pool.cpu().numpy(), refs[i][1])
+
+
 # ------------------------------------------------------------------ the configurations at full size
 def test_config1_full_size_build_and_resume():
     """N = 8192, 16 heads, d = 128, M = 16: the entry build (8192 tokens) and resumes at seeded
