@@ -1,0 +1,73 @@
+"""ctypes binding of the attention layers' side of a cache hit (include/attn_resume.h): argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+
+from .binding import GDN_BF16, GDN_F32, _check, _dp, _h32, _hp, _stream_ptr, lib
+
+_i32, _i64, _vp, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
+
+EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_suffix_prefill"]
+
+
+class attn_shape(ctypes.Structure):
+    _fields_ = [("H_q", _i32), ("H_kv", _i32), ("d", _i32), ("o_dtype", _i32), ("scale", _f32)]
+
+
+def make_attn_shape(H_q, H_kv, d, o_dtype="f32", scale=None) -> attn_shape:
+    code = {"f32": GDN_F32, "bf16": GDN_BF16, GDN_F32: GDN_F32, GDN_BF16: GDN_BF16}
+    return attn_shape(H_q, H_kv, d, code[o_dtype], float(d ** -0.5 if scale is None else scale))
+
+
+_ready = False
+
+
+def _lib():
+    global _ready
+    L = lib()
+    if not _ready:
+        L.attn_workspace_bytes.restype = _i64
+        L.attn_workspace_bytes.argtypes = [_i32, _i64]
+        L.attn_kv_restore.restype = _i32
+        L.attn_kv_restore.argtypes = ([ctypes.POINTER(attn_shape), _i32, _vp] + [_vp, _vp, _i64, _i32, _vp]
+                                      + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp])
+        L.attn_suffix_prefill.restype = _i32
+        L.attn_suffix_prefill.argtypes = ([ctypes.POINTER(attn_shape)] + [_vp] * 4 + [_i32, _vp, _vp]
+                                          + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp, _vp, _i64, _vp])
+        _ready = True
+    return L
+
+
+def attn_workspace_bytes(n_req: int, total_tokens: int) -> int:
+    return _check(int(_lib().attn_workspace_bytes(int(n_req), int(total_tokens))), "attn_workspace_bytes")
+
+
+def _pool_geometry(pool):
+    """(slot stride in elements, slots, rows per slot) of a [n_slots][cap][H_kv][d] tensor."""
+    if pool is None:
+        return 0, 0, 0
+    return int(pool.stride(0)), int(pool.shape[0]), int(pool.shape[1])
+
+
+def attn_kv_restore(shape: attn_shape, prefix_len, host_k, host_v, host_slot, k_cache, v_cache, seq_slot, stream=None) -> None:
+    """See include/attn_resume.h.  host_k / host_v are host tensors [n_host_slots][cap][H_kv][d] (pinned for
+    overlap), k_cache / v_cache device tensors of the same slot geometry; index arrays are host sequences."""
+    pl, hs, ss = _h32(prefix_len), _h32(host_slot), _h32(seq_slot)
+    stride, n_slots, cap = _pool_geometry(k_cache)
+    hstride, hn, _ = _pool_geometry(host_k)
+    _check(_lib().attn_kv_restore(ctypes.byref(shape), int(pl.size), _hp(pl), _dp(host_k), _dp(host_v), hstride, hn, _hp(hs),
+                                  _dp(k_cache), _dp(v_cache), stride, n_slots, cap, _hp(ss), _stream_ptr(stream)),
+           "attn_kv_restore")
+
+
+def attn_suffix_prefill(shape: attn_shape, q, k_new, v_new, out_gate, cu_seqlens, start_pos, k_cache, v_cache, seq_slot, o,
+                        workspace, stream=None) -> None:
+    """See include/attn_resume.h.  Device arguments are torch tensors (out_gate may be None); the caches are
+    [n_slots][cap][H_kv][d] tensors whose first stride is the slot stride; index arrays are host sequences."""
+    cu, sp, ss = _h32(cu_seqlens), _h32(start_pos), _h32(seq_slot)
+    stride, n_slots, cap = _pool_geometry(k_cache)
+    _check(_lib().attn_suffix_prefill(
+        ctypes.byref(shape), _dp(q), _dp(k_new), _dp(v_new), _dp(out_gate), int(sp.size), _hp(cu), _hp(sp),
+        _dp(k_cache), _dp(v_cache), stride, n_slots, cap, _hp(ss), _dp(o),
+        _dp(workspace), int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream_ptr(stream)), "attn_suffix_prefill")

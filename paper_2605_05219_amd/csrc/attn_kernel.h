@@ -1,0 +1,354 @@
+// Device side of the attention layers' part of a cache hit (see include/attn_resume.h): the
+// append of the suffix's keys and values to the cache, and causal softmax attention of the suffix
+// over positions 1 .. its own, for gfx950 (wave64, bf16 matrix cores, fp32 accumulation).
+//
+// Attention kernel.  One workgroup of four waves owns ATT_BQ = 128 consecutive suffix tokens of
+// one (request, query head); wave w owns 32 of them, one per lane column.  Key/value rows are
+// walked in tiles of ATT_KT = 64, each tile brought into one of two LDS stages by 16-byte
+// global->LDS loads (no registers) while the waves compute on the other stage.
+//
+// Both contractions are computed transposed, so that a query is a COLUMN of every accumulator
+// tile and everything a softmax row needs sits in one lane (and its partner 32 lanes up):
+//   S^T[kv][q] = sum_d K[kv][d] Q[q][d]      A = a key tile row (16-byte LDS read), B = the
+//                                            query fragment, held in registers for the whole walk
+//   O^T[dv][q] += sum_kv V^T[dv][kv] P^T[kv][q]
+//                                            (fp16 operands: the value cache is kept in fp16)
+//                                            B = the weights, packed to fp16 straight from the
+//                                            S^T accumulators: accumulator register 4b+e of
+//                                            half-wave g holds row 8b+4g+e, so registers 8s..8s+7
+//                                            are rows 16s+4g+{0..3} and 16s+8+4g+{0..3}; A = the
+//                                            same two runs of four kv rows of one value column,
+//                                            which is what the 16-bit LDS transpose read returns
+//                                            (lane i of a group of 16 receives element i%4 of the
+//                                            8-byte rows addressed by lanes i/4, i/4+4, i/4+8,
+//                                            i/4+12 of the group).
+// LDS rows are unpadded (the global->LDS load writes a wave's 64 x 16 bytes contiguously); bank
+// conflicts are avoided by storing 16-byte chunk c of row r at chunk position c ^ f(r), with f
+// chosen per tile for its read pattern (16 rows x same chunk for keys, 4 rows x 4 chunks for values).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attn {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2 __attribute__((ext_vector_type(2)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int ATT_BQ = 128;       // suffix tokens per workgroup
+constexpr int ATT_KT = 64;        // key/value rows per tile
+constexpr int ATT_THREADS = 256;
+constexpr int APPEND_THREADS = 256;
+
+struct AttnArgs {
+    const uint16_t* q;        // [T][H_q][D]
+    const uint16_t* gate;     // [T][H_q][D] or nullptr
+    const uint16_t* k_cache;  // slots of [cap][H_kv][D]
+    const uint16_t* v_cache;  // fp16 bits
+    void* o;                  // [T][H_q][D], float or bf16
+    const int32_t* cu;        // device: n_req + 1
+    const int32_t* start;     // device: n_req
+    const int32_t* slot;      // device: n_req
+    const int32_t* item_req;  // device: n_items, heaviest first
+    const int32_t* item_tile; // device: n_items, index of the 128-token tile inside the request
+    int64_t slot_stride;      // elements
+    int32_t n_items;
+    int32_t H_q, H_kv;
+    int32_t xcd_split;        // 1: blocks are dealt to the 8 XCDs by key/value head
+    float scale_log2e;        // scale * log2(e)
+};
+
+struct AppendArgs {
+    const uint16_t* k_new;    // [T][H_kv][D]
+    const uint16_t* v_new;
+    uint16_t* k_cache;
+    uint16_t* v_cache;        // fp16 bits
+    const int32_t* cu;
+    const int32_t* start;
+    const int32_t* slot;
+    int64_t slot_stride;
+    int64_t n_chunks;         // T * row_chunks
+    int32_t n_req;
+    int32_t row_chunks;       // 16-byte chunks per token row: H_kv * D / 8
+};
+
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left alone)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
+}
+
+// max / sum of a value with the lane 32 up or down (one swap instruction, no LDS)
+__device__ __forceinline__ float max_with_other_half(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto p = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, (unsigned)p[0]), __builtin_bit_cast(float, (unsigned)p[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto p = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (unsigned)p[0]) + __builtin_bit_cast(float, (unsigned)p[1]);
+}
+
+// Appends the suffix's key and value rows to the cache rows start .. start+n-1 of each request's
+// slot: one 16-byte chunk of k and of v per thread, the values widened from bf16 to fp16.
+__global__ void __launch_bounds__(APPEND_THREADS) attn_append_kernel(AppendArgs a) {
+    const int64_t id = (int64_t)blockIdx.x * APPEND_THREADS + threadIdx.x;
+    if (id >= a.n_chunks) return;
+    const int32_t t = (int32_t)(id / a.row_chunks);
+    const int32_t c = (int32_t)(id - (int64_t)t * a.row_chunks);
+    int lo = 0, hi = a.n_req;                       // request with cu[r] <= t < cu[r+1]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    const int r = lo;
+    const int64_t row = (int64_t)a.start[r] + (t - a.cu[r]);
+    const int64_t dst = (int64_t)a.slot[r] * a.slot_stride + (row * a.row_chunks + c) * 8;
+    const int64_t src = ((int64_t)t * a.row_chunks + c) * 8;
+    *reinterpret_cast<u32x4*>(a.k_cache + dst) = *reinterpret_cast<const u32x4*>(a.k_new + src);
+    const u32x4 vb = *reinterpret_cast<const u32x4*>(a.v_new + src);
+    half8 vh;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        vh[2 * i] = (_Float16)__builtin_bit_cast(float, vb[i] << 16);
+        vh[2 * i + 1] = (_Float16)__builtin_bit_cast(float, vb[i] & 0xffff0000u);
+    }
+    *reinterpret_cast<u32x4*>(a.v_cache + dst) = __builtin_bit_cast(u32x4, vh);
+}
+
+template <int D>
+struct AttnSmem {
+    static constexpr int CPR = D / 8;                     // 16-byte chunks per row
+    static constexpr int ROW_BYTES = D * 2;
+    static constexpr int TILE_BYTES = ATT_KT * ROW_BYTES;
+    static constexpr int K_OFF = 0, V_OFF = TILE_BYTES;
+    static constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+    static constexpr int BYTES = 2 * STAGE_BYTES;
+    static constexpr int PIECES = TILE_BYTES / 1024;      // 1 KiB wave-wide loads per tile
+    static constexpr int ROWS_PER_PIECE = 64 / CPR > 0 ? 64 / CPR : 1;
+    static_assert(D == 64 || D == 128 || D == 256, "head size");
+    static_assert(PIECES % 4 == 0, "pieces split evenly over four waves");
+    // chunk position swizzles
+    static __device__ __forceinline__ int fk(int row) { return CPR >= 16 ? (row & 15) : ((row >> 1) & 7); }
+    static __device__ __forceinline__ int fv(int row) { return CPR >= 16 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+};
+
+template <int D, typename OT>
+__global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_kernel(AttnArgs a) {
+    typedef AttnSmem<D> SM;
+    constexpr int CPR = SM::CPR;
+    constexpr int KB = D / 16;      // contraction steps of S^T
+    constexpr int RB = D / 32;      // row tiles of O^T
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 31;      // query column of this lane
+    const int g = lane >> 5;        // half-wave
+
+    // ---- which (item, query head)
+    int item, hq;
+    {
+        const int G = a.H_q / a.H_kv;
+        if (a.xcd_split) {
+            const int X = 8 / a.H_kv;                 // XCDs per key/value head
+            const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+            const int kvh = xcd % a.H_kv, sub = xcd / a.H_kv;
+            const int64_t e = (int64_t)k * X + sub;
+            if (e >= (int64_t)a.n_items * G) return;
+            item = (int)(e / G);
+            hq = kvh * G + (int)(e % G);
+        } else {
+            item = blockIdx.x / a.H_q;
+            hq = blockIdx.x % a.H_q;
+        }
+    }
+    const int kvh = hq / (a.H_q / a.H_kv);
+    const int r = a.item_req[item];
+    const int q0 = a.item_tile[item] * ATT_BQ;
+    const int tok0 = a.cu[r];
+    const int n = a.cu[r + 1] - tok0;
+    const int c0 = a.start[r];
+    const int q_end = min(q0 + ATT_BQ, n);                 // valid suffix rows of this workgroup: [q0, q_end)
+    const int kv_len = c0 + q_end;                         // key rows any of them may see
+    const int n_tiles = (kv_len + ATT_KT - 1) / ATT_KT;
+    const int wq0 = q0 + 32 * wave;                        // first row of this wave
+    const int n_tiles_w = wq0 < q_end ? (c0 + min(wq0 + 32, q_end) + ATT_KT - 1) / ATT_KT : 0;
+    const int qrow = min(wq0 + col, q_end - 1);            // clamped: lanes past the end repeat the last row
+    const int lim = c0 + qrow;                             // last visible key row (0-based) of this lane's query
+
+    const int64_t row_stride = (int64_t)a.H_kv * D;        // elements between key rows
+    const uint16_t* const kbase = a.k_cache + (int64_t)a.slot[r] * a.slot_stride + (int64_t)kvh * D;
+    const uint16_t* const vbase = a.v_cache + (int64_t)a.slot[r] * a.slot_stride + (int64_t)kvh * D;
+
+    // ---- tile loader: wave w brings pieces [w*PIECES/4, (w+1)*PIECES/4) of the key and of the value tile
+    auto issue = [&](int t, int stage) {
+        char* const sb = smem + stage * SM::STAGE_BYTES;
+        const int kv0 = t * ATT_KT;
+#pragma unroll
+        for (int i = 0; i < SM::PIECES / 4; ++i) {
+            const int p = wave * (SM::PIECES / 4) + i;
+            const int s = p * 64 + lane;                   // 16-byte slot inside the tile
+            const int row = s / CPR, pos = s % CPR;
+            const int64_t grow = min(kv0 + row, kv_len - 1);
+            const uint16_t* const ksrc = kbase + grow * row_stride + ((pos ^ SM::fk(row)) << 3);
+            const uint16_t* const vsrc = vbase + grow * row_stride + ((pos ^ SM::fv(row)) << 3);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
+                                             (__attribute__((address_space(3))) void*)(sb + SM::K_OFF + p * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vsrc,
+                                             (__attribute__((address_space(3))) void*)(sb + SM::V_OFF + p * 1024), 16, 0, 0);
+        }
+    };
+    issue(0, 0);
+
+    // ---- query fragments: B operand of S^T, d = 16*kb + 8*g + {0..7}
+    bf16x8 qf[KB];
+    {
+        const uint16_t* const qp = a.q + ((int64_t)(tok0 + qrow) * a.H_q + hq) * D + 8 * g;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) qf[kb] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + 16 * kb));
+    }
+
+    f32x16 O[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[rb][i] = 0.f;
+    float m = -INFINITY;     // running maximum of the raw logits of this lane's query (both half-waves agree)
+    float l = 0.f;           // this half-wave's share of the normaliser
+    const float c = a.scale_log2e;
+
+    // per-lane LDS byte offsets inside a stage
+    const int krow_off = col * SM::ROW_BYTES;                       // + 32*kvblk rows
+    const int kz = g ^ SM::fk(col);                                 // chunk position of step kb: (2*kb) ^ kz
+    const int i16 = lane & 15, b4 = (lane >> 4) & 1;
+    const int vrow = 4 * g + (i16 >> 2);                            // + 16*s + 8*grp rows
+    const int vfv = SM::fv(vrow);
+    const int vrow_off = SM::V_OFF + vrow * SM::ROW_BYTES + 8 * (i16 & 1);
+    const int vchunk = 2 * b4 + ((i16 & 3) >> 1);                   // + 4*rb
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int stage = t & 1;
+        wait_vmcnt<0>();
+        __syncthreads();                       // tile t has landed; everyone has left the other stage
+        if (t + 1 < n_tiles) issue(t + 1, stage ^ 1);
+        if (t >= n_tiles_w) continue;          // wave-uniform: nothing of this tile is visible to this wave
+        const char* const sb = smem + stage * SM::STAGE_BYTES;
+        const int kv0 = t * ATT_KT;
+
+        // ---- S^T = K Q^T, two 32-row tiles
+        f32x16 S[2];
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) S[kvb][i] = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                const bf16x8 kf = __builtin_bit_cast(
+                    bf16x8, *reinterpret_cast<const u32x4*>(sb + SM::K_OFF + kvb * 32 * SM::ROW_BYTES + krow_off + (((2 * kb) ^ kz) << 4)));
+                S[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kb], S[kvb], 0, 0, 0);
+            }
+        }
+        // ---- causal mask on the tiles that reach past the first row's limit
+        if (kv0 + ATT_KT - 1 > c0 + wq0) {
+#pragma unroll
+            for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int kv = kv0 + 32 * kvb + 8 * (i >> 2) + 4 * g + (i & 3);
+                    if (kv > lim) S[kvb][i] = -INFINITY;
+                }
+        }
+        // ---- online softmax for this lane's query
+        float mx = S[0][0];
+#pragma unroll
+        for (int kvb = 0; kvb < 2; ++kvb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[kvb][i]);
+        mx = max_with_other_half(mx);
+        const float m_new = fmaxf(m, mx);      // finite: key row 0 is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
+        const float mc = m_new * c;
+        m = m_new;
+        half8 pf[4];                           // B operands of the four 16-row steps
+        float lsum = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            f32x2 e[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                e[j][0] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[s >> 1][8 * (s & 1) + 2 * j], c, -mc));
+                e[j][1] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[s >> 1][8 * (s & 1) + 2 * j + 1], c, -mc));
+            }
+            half2 h[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                h[j] = __builtin_convertvector(e[j], half2);
+                const half2 one = {(_Float16)1.0f, (_Float16)1.0f};
+                lsum = __builtin_amdgcn_fdot2(h[j], one, lsum, false);   // the sum of the ROUNDED weights
+            }
+            pf[s] = __builtin_shufflevector(__builtin_shufflevector(h[0], h[1], 0, 1, 2, 3),
+                                            __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+        }
+        l = l * alpha + lsum;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) O[rb][i] *= alpha;
+        }
+        // ---- O^T += V^T P^T
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+            const int vpos = ((4 * rb + vchunk) ^ vfv) << 4;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const char* const p0 = sb + vrow_off + vpos + (16 * s) * SM::ROW_BYTES;
+                const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0));
+                const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0 + 8 * SM::ROW_BYTES));
+                const half8 vf = __builtin_bit_cast(half8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                O[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf, pf[s], O[rb], 0, 0, 0);
+            }
+        }
+    }
+
+    // ---- normalise, gate, store: register 4b+e of tile rb is value column 32*rb + 8*b + 4*g + e
+    if (wq0 + col < q_end) {
+        const float inv = 1.f / sum_with_other_half(l);
+        const int64_t base = ((int64_t)(tok0 + wq0 + col) * a.H_q + hq) * D;
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int dv = 32 * rb + 8 * b + 4 * g;
+                f32x4 y = {O[rb][4 * b] * inv, O[rb][4 * b + 1] * inv, O[rb][4 * b + 2] * inv, O[rb][4 * b + 3] * inv};
+                if (a.gate) {
+                    const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gate + base + dv);
+                    const float g0 = __builtin_bit_cast(float, gb[0] << 16), g1 = __builtin_bit_cast(float, gb[0] & 0xffff0000u);
+                    const float g2 = __builtin_bit_cast(float, gb[1] << 16), g3 = __builtin_bit_cast(float, gb[1] & 0xffff0000u);
+                    y[0] *= 1.f / (1.f + __expf(-g0));
+                    y[1] *= 1.f / (1.f + __expf(-g1));
+                    y[2] *= 1.f / (1.f + __expf(-g2));
+                    y[3] *= 1.f / (1.f + __expf(-g3));
+                }
+                if constexpr (sizeof(OT) == 4) {
+                    *reinterpret_cast<f32x4*>(static_cast<float*>(a.o) + base + dv) = y;
+                } else {
+                    const bf16x4 yb = __builtin_convertvector(y, bf16x4);
+                    *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.o) + base + dv) = __builtin_bit_cast(u32x2, yb);
+                }
+            }
+    }
+}
+
+}  // namespace attn

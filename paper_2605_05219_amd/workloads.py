@@ -458,3 +458,59 @@ def layer_case(seed: int, H_qk: int, H_v: int, d_k: int, d_v: int, K: int, dtype
         to_storage(normal(T, H_v, d_v), dtype), normal(T, H_v, d_v), (1.0 + normal(d_v, s=0.1)).astype(np.float32),
         to_storage(normal(n_src_slots + max(int(epos.size), 1), K - 1, C), dtype),
         cu, np.asarray(starts, np.int32), src, ecu, epos, eslot)
+
+
+# ----------------------------------------------------------------------------- attention side of a hit
+@dataclass
+class AttnCase:
+    """Seeded inputs of the attention layers' side of a cache hit for a packed batch of resumed
+    requests, all bf16 bit patterns.  Draws only: queries, keys, values (and the output gate's
+    pre-activation) ~ N(0,1) times a chosen spread; they stand in for the projections of the model
+    the paper measures (Sec. 5, runtime experiment), whose weights are not available.  Request r
+    owns sequence slot seq_slot[r]; k_full[r] / v_full[r] hold its keys and values of positions
+    1 .. start+len (the restored prefix, then the suffix)."""
+    H_q: int
+    H_kv: int
+    d: int
+    q: np.ndarray                 # [T][H_q][d]
+    gate: np.ndarray              # [T][H_q][d]
+    k_full: List[np.ndarray]      # per request [start+len][H_kv][d]
+    v_full: List[np.ndarray]
+    cu_seqlens: np.ndarray
+    start_pos: np.ndarray
+    seq_slot: np.ndarray
+    n_slots: int
+    cap: int
+
+    @property
+    def T(self) -> int:
+        return int(self.cu_seqlens[-1])
+
+    def suffix(self, which: str) -> np.ndarray:
+        """Packed [T][H_kv][d] keys ('k') or values ('v') of the suffix tokens."""
+        full = self.k_full if which == "k" else self.v_full
+        parts = [f[s:] for f, s in zip(full, self.start_pos)]
+        return np.concatenate(parts, axis=0) if parts else np.zeros((0, self.H_kv, self.d), np.uint16)
+
+
+def attn_case(seed: int, H_q: int, H_kv: int, d: int, lens: Sequence[int], starts: Sequence[int],
+              cap: Optional[int] = None, q_spread: float = 1.0, spare_slots: int = 1) -> AttnCase:
+    rng = np.random.default_rng(seed)
+    T = int(sum(lens))
+    n_req = len(lens)
+
+    def normal(*shape, s=1.0):
+        return f32_to_bf16_bits((rng.standard_normal(shape, dtype=np.float32) * np.float32(s)).astype(np.float32))
+
+    cu = np.zeros(n_req + 1, np.int32)
+    cu[1:] = np.cumsum(lens)
+    need = max([int(s) + int(l) for s, l in zip(starts, lens)] + [1])
+    cap = int(cap if cap is not None else need)
+    assert cap >= need
+    n_slots = n_req + spare_slots
+    slot = rng.permutation(n_slots)[:n_req].astype(np.int32)
+    q = normal(T, H_q, d, s=q_spread)
+    gate = normal(T, H_q, d)
+    k_full = [normal(int(s) + int(l), H_kv, d) for s, l in zip(starts, lens)]
+    v_full = [normal(int(s) + int(l), H_kv, d) for s, l in zip(starts, lens)]
+    return AttnCase(H_q, H_kv, d, q, gate, k_full, v_full, cu, np.asarray(starts, np.int32), slot, n_slots, cap)

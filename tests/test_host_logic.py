@@ -300,13 +300,13 @@ def test_probe_ceilings_argument_errors(monkeypatch, dev, code):
 
 
 def test_headers_are_plain_c_and_a_c_program_can_call_the_library(tmp_path):
-    """The boundary is a C ABI: the three headers compile as strict C99 and a C program linked against the
+    """The boundary is a C ABI: the headers compile as strict C99 and a C program linked against the
     library calls host-only entry points through them."""
     import subprocess
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     src = tmp_path / "abi.c"
     src.write_text(
-        '#include <stdio.h>\n#include "gdn_resume.h"\n#include "gdn_layer.h"\n#include "ckpt_place.h"\n'
+        '#include <stdio.h>\n#include "gdn_resume.h"\n#include "gdn_layer.h"\n#include "attn_resume.h"\n#include "ckpt_place.h"\n'
         "int main(void) {\n"
         "    const int32_t pos[3] = {128, 256, 384};\n"
         "    int32_t out[4];\n"
@@ -315,6 +315,7 @@ def test_headers_are_plain_c_and_a_c_program_can_call_the_library(tmp_path):
         "    if (gdn_deepest_ckpt(pos, 3, 300) != 1 || gdn_deepest_ckpt(pos, 3, 5) != -1) return 2;\n"
         "    if (gdn_workspace_bytes(&s, 1, 256, 2) <= 0) return 3;\n"
         "    if (gdn_layer_workspace_bytes(2, 3) <= 0) return 4;\n"
+        "    if (attn_workspace_bytes(2, 300) <= 0) return 6;\n"
         "    if (ckpt_place_balanced(511, 3, out) != 3 || out[0] != 128 || out[2] != 384) return 5;\n"
         '    printf("ok\\n");\n    return 0;\n}\n')
     exe = tmp_path / "abi"
