@@ -46,8 +46,10 @@ typedef struct attn_shape {
     float scale;      /* logit multiplier, usually 1/sqrt(d); finite and > 0 */
 } attn_shape;
 
-/* Bytes of device workspace attn_suffix_prefill needs (its index arrays).  Negative on error. */
-int64_t attn_workspace_bytes(int32_t n_req, int64_t total_tokens);
+/* Bytes of device workspace attn_suffix_prefill needs: its index arrays and, for calls with too few
+ * (request, head, 128-token) pieces to fill the chip, the partial results of split key walks (a
+ * fixed region of 768 x 128 x (d + 2) floats).  Negative on error. */
+int64_t attn_workspace_bytes(const attn_shape *shape, int32_t n_req, int64_t total_tokens);
 
 /*
  * Restore the cached prefix of n_req requests from a HOST pool with the same slot layout
@@ -71,7 +73,10 @@ int32_t attn_kv_restore(const attn_shape *shape, int32_t n_req, const int32_t *p
 /*
  * Suffix prefill of the attention layer for a packed batch of resumed requests: appends the
  * suffix's keys and values to each request's cache rows and computes the attention output of
- * every suffix token over positions 1 .. its own (two launches on `stream`).
+ * every suffix token over positions 1 .. its own (two launches on `stream`; three when the call
+ * is small enough for key walks of 1024 keys and more to be split over workgroups, after which a
+ * merge pass writes o).  Results do not depend on the batch a request is packed with as long as
+ * its walk is not split.  Environment: ATTN_NO_SPLIT=1 (read at every call) keeps every walk whole.
  *   q            device, bf16, [T][H_q][d] (T = cu_seqlens[n_req]);  k_new, v_new: [T][H_kv][d]
  *   out_gate     device, bf16, [T][H_q][d], or NULL (no gate)
  *   cu_seqlens   host, n_req + 1;  start_pos: host, n_req, the restored prefix length c >= 0
@@ -79,7 +84,7 @@ int32_t attn_kv_restore(const attn_shape *shape, int32_t n_req, const int32_t *p
  *                rows [c, c+n) are written by this call; seq_slot: host, n_req ids in
  *                [0, n_slots), distinct;  c + n <= cap
  *   o            device, o_dtype, [T][H_q][d]
- *   workspace    device, 16-byte aligned, >= attn_workspace_bytes(n_req, T)
+ *   workspace    device, 16-byte aligned, >= attn_workspace_bytes(shape, n_req, T)
  * Errors: GDN_ERR_NULL, _ALIGN, _SHAPE, _SEQLENS, _START (negative, or c + n > cap), _COUNT,
  * _SLOT_RANGE, _SLOT_DUP, _WORKSPACE.  A request of length 0 is legal and does nothing.
  */

@@ -27,7 +27,7 @@ def _lib():
     L = lib()
     if not _ready:
         L.attn_workspace_bytes.restype = _i64
-        L.attn_workspace_bytes.argtypes = [_i32, _i64]
+        L.attn_workspace_bytes.argtypes = [ctypes.POINTER(attn_shape), _i32, _i64]
         L.attn_kv_restore.restype = _i32
         L.attn_kv_restore.argtypes = ([ctypes.POINTER(attn_shape), _i32, _vp] + [_vp, _vp, _i64, _i32, _vp]
                                       + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp])
@@ -38,8 +38,8 @@ def _lib():
     return L
 
 
-def attn_workspace_bytes(n_req: int, total_tokens: int) -> int:
-    return _check(int(_lib().attn_workspace_bytes(int(n_req), int(total_tokens))), "attn_workspace_bytes")
+def attn_workspace_bytes(shape: attn_shape, n_req: int, total_tokens: int) -> int:
+    return _check(int(_lib().attn_workspace_bytes(ctypes.byref(shape), int(n_req), int(total_tokens))), "attn_workspace_bytes")
 
 
 def _pool_geometry(pool):

@@ -22,6 +22,10 @@
 //                                            (lane i of a group of 16 receives element i%4 of the
 //                                            8-byte rows addressed by lanes i/4, i/4+4, i/4+8,
 //                                            i/4+12 of the group).
+// A call with too few (request, head, 128-token) pieces to fill the chip splits the key walk of a
+// piece into parts of whole tiles: each part is a workgroup that leaves its unnormalised O, running
+// maximum and normaliser in a workspace slot, and a second kernel merges the parts of a piece.
+//
 // LDS rows are unpadded (the global->LDS load writes a wave's 64 x 16 bytes contiguously); bank
 // conflicts are avoided by storing 16-byte chunk c of row r at chunk position c ^ f(r), with f
 // chosen per tile for its read pattern (16 rows x same chunk for keys, 4 rows x 4 chunks for values).
@@ -58,10 +62,15 @@ struct AttnArgs {
     const int32_t* cu;        // device: n_req + 1
     const int32_t* start;     // device: n_req
     const int32_t* slot;      // device: n_req
-    const int32_t* item_req;  // device: n_items, heaviest first
-    const int32_t* item_tile; // device: n_items, index of the 128-token tile inside the request
+    const int32_t* unit_req;  // device: n_units, heaviest first
+    const int32_t* unit_tile; // device: index of the 128-token tile inside the request
+    const int32_t* unit_t0;   // device: first key tile of the unit
+    const int32_t* unit_t1;   // device: one past its last key tile
+    const int32_t* unit_part; // device: workspace slot of a partial result, or -1: the unit is a whole walk
+    float* part_o;            // [slot][H_q][ATT_BQ][D] unnormalised partial outputs
+    float* part_ml;           // [slot][H_q][ATT_BQ][2] running maximum (raw logits) and normaliser
     int64_t slot_stride;      // elements
-    int32_t n_items;
+    int32_t n_units;
     int32_t H_q, H_kv;
     int32_t xcd_split;        // 1: blocks are dealt to the 8 XCDs by key/value head
     float scale_log2e;        // scale * log2(e)
@@ -135,7 +144,6 @@ struct AttnSmem {
     static constexpr int STAGE_BYTES = 2 * TILE_BYTES;
     static constexpr int BYTES = 2 * STAGE_BYTES;
     static constexpr int PIECES = TILE_BYTES / 1024;      // 1 KiB wave-wide loads per tile
-    static constexpr int ROWS_PER_PIECE = 64 / CPR > 0 ? 64 / CPR : 1;
     static_assert(D == 64 || D == 128 || D == 256, "head size");
     static_assert(PIECES % 4 == 0, "pieces split evenly over four waves");
     // chunk position swizzles
@@ -165,7 +173,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
             const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
             const int kvh = xcd % a.H_kv, sub = xcd / a.H_kv;
             const int64_t e = (int64_t)k * X + sub;
-            if (e >= (int64_t)a.n_items * G) return;
+            if (e >= (int64_t)a.n_units * G) return;
             item = (int)(e / G);
             hq = kvh * G + (int)(e % G);
         } else {
@@ -174,16 +182,17 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         }
     }
     const int kvh = hq / (a.H_q / a.H_kv);
-    const int r = a.item_req[item];
-    const int q0 = a.item_tile[item] * ATT_BQ;
+    const int r = a.unit_req[item];
+    const int q0 = a.unit_tile[item] * ATT_BQ;
+    const int t0 = a.unit_t0[item], t1 = a.unit_t1[item];  // key tiles [t0, t1) of this unit
+    const int part = a.unit_part[item];
     const int tok0 = a.cu[r];
     const int n = a.cu[r + 1] - tok0;
     const int c0 = a.start[r];
     const int q_end = min(q0 + ATT_BQ, n);                 // valid suffix rows of this workgroup: [q0, q_end)
     const int kv_len = c0 + q_end;                         // key rows any of them may see
-    const int n_tiles = (kv_len + ATT_KT - 1) / ATT_KT;
     const int wq0 = q0 + 32 * wave;                        // first row of this wave
-    const int n_tiles_w = wq0 < q_end ? (c0 + min(wq0 + 32, q_end) + ATT_KT - 1) / ATT_KT : 0;
+    const int n_tiles_w = wq0 < q_end ? (c0 + min(wq0 + 32, q_end) + ATT_KT - 1) / ATT_KT : 0;   // tiles this wave can see
     const int qrow = min(wq0 + col, q_end - 1);            // clamped: lanes past the end repeat the last row
     const int lim = c0 + qrow;                             // last visible key row (0-based) of this lane's query
 
@@ -209,7 +218,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
                                              (__attribute__((address_space(3))) void*)(sb + SM::V_OFF + p * 1024), 16, 0, 0);
         }
     };
-    issue(0, 0);
+    issue(t0, 0);
 
     // ---- query fragments: B operand of S^T, d = 16*kb + 8*g + {0..7}
     bf16x8 qf[KB];
@@ -237,11 +246,11 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
     const int vrow_off = SM::V_OFF + vrow * SM::ROW_BYTES + 8 * (i16 & 1);
     const int vchunk = 2 * b4 + ((i16 & 3) >> 1);                   // + 4*rb
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int stage = t & 1;
+    for (int t = t0; t < t1; ++t) {
+        const int stage = (t - t0) & 1;
         wait_vmcnt<0>();
         __syncthreads();                       // tile t has landed; everyone has left the other stage
-        if (t + 1 < n_tiles) issue(t + 1, stage ^ 1);
+        if (t + 1 < t1) issue(t + 1, stage ^ 1);
         if (t >= n_tiles_w) continue;          // wave-uniform: nothing of this tile is visible to this wave
         const char* const sb = smem + stage * SM::STAGE_BYTES;
         const int kv0 = t * ATT_KT;
@@ -276,9 +285,11 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[kvb][i]);
         mx = max_with_other_half(mx);
-        const float m_new = fmaxf(m, mx);      // finite: key row 0 is visible to every query
-        const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c);
-        const float mc = m_new * c;
+        const float m_new = fmaxf(m, mx);
+        // -inf only in a part of a split walk whose first tiles lie past this query's limit: nothing to weigh yet
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f((m - m_ref) * c);
+        const float mc = m_ref * c;
         m = m_new;
         half8 pf[4];                           // B operands of the four 16-row steps
         float lsum = 0.f;
@@ -322,6 +333,21 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         }
     }
 
+    // ---- a part of a split walk leaves its unnormalised result in its workspace slot
+    if (part >= 0) {
+        if (wq0 + col < q_end) {
+            const int64_t prow = ((int64_t)part * a.H_q + hq) * ATT_BQ + 32 * wave + col;
+            const float lt = sum_with_other_half(l);
+            if (g == 0) *reinterpret_cast<f32x2*>(a.part_ml + prow * 2) = f32x2{m, lt};
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    *reinterpret_cast<f32x4*>(a.part_o + prow * D + 32 * rb + 8 * b + 4 * g) =
+                        f32x4{O[rb][4 * b], O[rb][4 * b + 1], O[rb][4 * b + 2], O[rb][4 * b + 3]};
+        }
+        return;
+    }
     // ---- normalise, gate, store: register 4b+e of tile rb is value column 32*rb + 8*b + 4*g + e
     if (wq0 + col < q_end) {
         const float inv = 1.f / sum_with_other_half(l);
@@ -348,6 +374,81 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
                     *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.o) + base + dv) = __builtin_bit_cast(u32x2, yb);
                 }
             }
+    }
+}
+
+struct CombineArgs {
+    const float* part_o;
+    const float* part_ml;
+    const uint16_t* gate;     // or nullptr
+    void* o;
+    const int32_t* cu;
+    const int32_t* piece_req;   // device: n_pieces split pieces
+    const int32_t* piece_tile;
+    const int32_t* piece_base;  // first workspace slot of the piece
+    const int32_t* piece_parts; // its number of parts (consecutive slots)
+    int32_t H_q;
+    float scale_log2e;
+};
+
+// Merges the parts of one split piece for one query head: o = sum_p w_p O_p / sum_p w_p l_p with
+// w_p = 2^((m_p - max_p m_p) * scale * log2 e); a part that saw no key has m_p = -inf, weight 0 and O_p = 0.
+// One thread per (row, four value columns), COMBINE_SUBS workgroups per (piece, head); the loads of all
+// parts are independent of each other, so the pass costs a few memory round trips, not one per part.
+template <int D>
+struct CombineShape {
+    static constexpr int CH = D / 4;                               // threads per row
+    static constexpr int SUBS = ATT_BQ * CH / ATT_THREADS;         // workgroups per (piece, head)
+};
+
+template <int D, typename OT>
+__global__ void __launch_bounds__(ATT_THREADS) attn_combine_kernel(CombineArgs a) {
+    constexpr int CH = CombineShape<D>::CH, SUBS = CombineShape<D>::SUBS;
+    const int ph = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
+    const int piece = ph / a.H_q, hq = ph % a.H_q;
+    const int r = a.piece_req[piece];
+    const int q0 = a.piece_tile[piece] * ATT_BQ;
+    const int tok0 = a.cu[r];
+    const int rows = min(ATT_BQ, a.cu[r + 1] - tok0 - q0);
+    const int base = a.piece_base[piece], P = a.piece_parts[piece];
+    {
+        const int idx = sub * ATT_THREADS + threadIdx.x;
+        const int row = idx / CH, ch = idx - row * CH;
+        if (row >= rows) return;
+        const int64_t prow0 = ((int64_t)base * a.H_q + hq) * ATT_BQ + row;
+        const int64_t pstep = (int64_t)a.H_q * ATT_BQ;                // rows between consecutive parts
+        float M = -INFINITY;
+#pragma unroll 4
+        for (int p = 0; p < P; ++p) M = fmaxf(M, a.part_ml[(prow0 + p * pstep) * 2]);   // finite: part 0 sees key row 0
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float L = 0.f;
+#pragma unroll 4
+        for (int p = 0; p < P; ++p) {
+            const int64_t prow = prow0 + p * pstep;
+            const f32x2 ml = *reinterpret_cast<const f32x2*>(a.part_ml + prow * 2);
+            const f32x4 op = *reinterpret_cast<const f32x4*>(a.part_o + prow * D + 4 * ch);
+            const float w = __builtin_amdgcn_exp2f((ml[0] - M) * a.scale_log2e);
+            acc[0] += w * op[0]; acc[1] += w * op[1]; acc[2] += w * op[2]; acc[3] += w * op[3];
+            L += w * ml[1];
+        }
+        const float inv = 1.f / L;
+        f32x4 y = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
+        const int64_t at = ((int64_t)(tok0 + q0 + row) * a.H_q + hq) * D + 4 * ch;
+        if (a.gate) {
+            const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gate + at);
+            const float g0 = __builtin_bit_cast(float, gb[0] << 16), g1 = __builtin_bit_cast(float, gb[0] & 0xffff0000u);
+            const float g2 = __builtin_bit_cast(float, gb[1] << 16), g3 = __builtin_bit_cast(float, gb[1] & 0xffff0000u);
+            y[0] *= 1.f / (1.f + __expf(-g0));
+            y[1] *= 1.f / (1.f + __expf(-g1));
+            y[2] *= 1.f / (1.f + __expf(-g2));
+            y[3] *= 1.f / (1.f + __expf(-g3));
+        }
+        if constexpr (sizeof(OT) == 4) {
+            *reinterpret_cast<f32x4*>(static_cast<float*>(a.o) + at) = y;
+        } else {
+            const bf16x4 yb = __builtin_convertvector(y, bf16x4);
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(a.o) + at) = __builtin_bit_cast(u32x2, yb);
+        }
     }
 }
 

@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -47,9 +48,22 @@ int32_t check_slots(const int32_t* ids, int32_t n, int32_t n_slots, bool skip_em
     return GDN_OK;
 }
 
-// ints of the uploaded index arrays: cu (n_req+1), start, slot (n_req each), item_req, item_tile
+// Splitting the key walk: calls with fewer than SPLIT_BELOW workgroups cut the walks of their pieces
+// into parts of at least SPLIT_MIN_TILES key tiles, aiming at SPLIT_BELOW workgroups in all; the
+// partial results of at most SPLIT_MAX_WGS (part, head) pairs live in the workspace.
+constexpr int SPLIT_BELOW = 512;       // two workgroups per compute unit
+constexpr int SPLIT_MIN_TILES = 8;
+constexpr int SPLIT_MAX_WGS = 768;
+
+// ints of the uploaded index arrays: cu (n_req+1), start, slot (n_req each), five per unit, four per split piece
 inline int64_t max_items(int32_t n_req, int64_t T) { return T / ATT_BQ + n_req; }
-inline int64_t plan_ints(int32_t n_req, int64_t T) { return 3 * (int64_t)n_req + 1 + 2 * max_items(n_req, T); }
+inline int64_t max_units(int32_t n_req, int64_t T) { return max_items(n_req, T) + SPLIT_MAX_WGS; }
+inline int64_t plan_ints(int32_t n_req, int64_t T) {
+    return 3 * (int64_t)n_req + 1 + 5 * max_units(n_req, T) + 4 * max_items(n_req, T);
+}
+inline int64_t plan_bytes(int32_t n_req, int64_t T) { return (plan_ints(n_req, T) * (int64_t)sizeof(int32_t) + 255) / 256 * 256; }
+inline int64_t part_ml_bytes() { return (int64_t)SPLIT_MAX_WGS * ATT_BQ * 2 * sizeof(float); }
+inline int64_t part_o_bytes(int d) { return (int64_t)SPLIT_MAX_WGS * ATT_BQ * d * sizeof(float); }
 
 template <int D, typename OT>
 hipError_t launch_attn(const AttnArgs& a, unsigned blocks, hipStream_t stream) {
@@ -73,6 +87,16 @@ hipError_t launch_attn_d(int d, const AttnArgs& a, unsigned blocks, hipStream_t 
     }
 }
 
+template <typename OT>
+hipError_t launch_combine_d(int d, const CombineArgs& a, unsigned blocks /* (piece, head) pairs */, hipStream_t stream) {
+    switch (d) {
+        case 64: hipLaunchKernelGGL((attn_combine_kernel<64, OT>), dim3(blocks * CombineShape<64>::SUBS), dim3(ATT_THREADS), 0, stream, a); break;
+        case 128: hipLaunchKernelGGL((attn_combine_kernel<128, OT>), dim3(blocks * CombineShape<128>::SUBS), dim3(ATT_THREADS), 0, stream, a); break;
+        default: hipLaunchKernelGGL((attn_combine_kernel<256, OT>), dim3(blocks * CombineShape<256>::SUBS), dim3(ATT_THREADS), 0, stream, a); break;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 }  // namespace attn
 
@@ -80,9 +104,11 @@ using namespace attn;
 
 extern "C" {
 
-int64_t attn_workspace_bytes(int32_t n_req, int64_t total_tokens) {
+int64_t attn_workspace_bytes(const attn_shape* s, int32_t n_req, int64_t total_tokens) {
+    const int32_t rc = check_shape(s);
+    if (rc != GDN_OK) return rc;
     if (n_req < 0 || total_tokens < 0) return GDN_ERR_COUNT;
-    return (plan_ints(n_req, total_tokens) * (int64_t)sizeof(int32_t) + 255) / 256 * 256;
+    return plan_bytes(n_req, total_tokens) + part_ml_bytes() + part_o_bytes(s->d);
 }
 
 int32_t attn_kv_restore(const attn_shape* s, int32_t n_req, const int32_t* prefix_len, const void* host_k, const void* host_v,
@@ -151,39 +177,84 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o) ||
         !aligned16(out_gate))
         return GDN_ERR_ALIGN;
-    if (!workspace || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(n_req, T)) return GDN_ERR_WORKSPACE;
+    if (!workspace || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(s, n_req, T)) return GDN_ERR_WORKSPACE;
 
-    // ---- work items: one per 128 suffix tokens of a request, those that see the most keys first
-    struct Item { int32_t req, tile, kv; };
-    std::vector<Item> items;
+    // ---- pieces: one per 128 suffix tokens of a request
+    struct Piece { int32_t req, tile, n_tiles, parts; };
+    std::vector<Piece> pieces;
+    int64_t total_tiles = 0;
     for (int32_t r = 0; r < n_req; ++r)
-        for (int32_t t = 0; t * ATT_BQ < len[r]; ++t)
-            items.push_back({r, t, start_pos[r] + std::min((t + 1) * ATT_BQ, len[r])});
-    std::stable_sort(items.begin(), items.end(), [](const Item& x, const Item& y) { return x.kv > y.kv; });
-    const int64_t n_items = (int64_t)items.size();
+        for (int32_t t = 0; t * ATT_BQ < len[r]; ++t) {
+            const int32_t kv = start_pos[r] + std::min((t + 1) * ATT_BQ, len[r]);
+            pieces.push_back({r, t, (kv + ATT_KT - 1) / ATT_KT, 1});
+            total_tiles += pieces.back().n_tiles;
+        }
+    const int64_t n_items = (int64_t)pieces.size();
+    // ---- too few workgroups for the chip: cut long key walks into parts
+    int64_t split_wgs = 0;
+    const char* no_split = std::getenv("ATTN_NO_SPLIT");
+    if (n_items * s->H_q < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
+        int64_t tp = std::max<int64_t>(SPLIT_MIN_TILES, (total_tiles * s->H_q + SPLIT_BELOW - 1) / SPLIT_BELOW);
+        for (;; tp *= 2) {
+            split_wgs = 0;
+            for (Piece& p : pieces) {
+                p.parts = p.n_tiles >= 2 * tp ? (int32_t)((p.n_tiles + tp - 1) / tp) : 1;
+                if (p.parts > 1) split_wgs += (int64_t)p.parts * s->H_q;
+            }
+            if (split_wgs <= SPLIT_MAX_WGS) break;
+        }
+    }
+    // ---- units: a whole walk or one part of it; those with the most key tiles first
+    struct Unit { int32_t req, tile, t0, t1, part; };
+    std::vector<Unit> units;
+    std::vector<int32_t> piece_req, piece_tile, piece_base, piece_parts;
+    int32_t next_slot = 0;
+    for (const Piece& p : pieces) {
+        if (p.parts == 1) {
+            units.push_back({p.req, p.tile, 0, p.n_tiles, -1});
+            continue;
+        }
+        piece_req.push_back(p.req); piece_tile.push_back(p.tile); piece_base.push_back(next_slot); piece_parts.push_back(p.parts);
+        const int32_t per = (p.n_tiles + p.parts - 1) / p.parts;
+        for (int32_t j = 0; j < p.parts; ++j)
+            units.push_back({p.req, p.tile, j * per, std::min((j + 1) * per, p.n_tiles), next_slot++});
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit& x, const Unit& y) { return x.t1 - x.t0 > y.t1 - y.t0; });
+    const int64_t n_units = (int64_t)units.size();
+    const int64_t n_pieces = (int64_t)piece_req.size();
     const int G = s->H_q / s->H_kv;
     const bool xcd_split = 8 % s->H_kv == 0;
     int64_t blocks;
     if (xcd_split) {
         const int X = 8 / s->H_kv;
-        blocks = 8 * ((n_items * G + X - 1) / X);
+        blocks = 8 * ((n_units * G + X - 1) / X);
     } else {
-        blocks = n_items * s->H_q;
+        blocks = n_units * s->H_q;
     }
     if (blocks > INT32_MAX) return GDN_ERR_COUNT;
 
+    const int64_t MU = max_units(n_req, T), MI = max_items(n_req, T);
     std::vector<int32_t> img((size_t)plan_ints(n_req, T), 0);
     int32_t* p_cu = img.data();
     int32_t* p_start = p_cu + n_req + 1;
     int32_t* p_slot = p_start + n_req;
-    int32_t* p_ireq = p_slot + n_req;
-    int32_t* p_itile = p_ireq + max_items(n_req, T);
+    int32_t* p_unit = p_slot + n_req;          // five arrays of MU
+    int32_t* p_piece = p_unit + 5 * MU;        // four arrays of MI
     std::memcpy(p_cu, cu_seqlens, sizeof(int32_t) * (n_req + 1));
     std::memcpy(p_start, start_pos, sizeof(int32_t) * n_req);
     std::memcpy(p_slot, seq_slot, sizeof(int32_t) * n_req);
-    for (int64_t i = 0; i < n_items; ++i) {
-        p_ireq[i] = items[i].req;
-        p_itile[i] = items[i].tile;
+    for (int64_t i = 0; i < n_units; ++i) {
+        p_unit[i] = units[i].req;
+        p_unit[MU + i] = units[i].tile;
+        p_unit[2 * MU + i] = units[i].t0;
+        p_unit[3 * MU + i] = units[i].t1;
+        p_unit[4 * MU + i] = units[i].part;
+    }
+    for (int64_t i = 0; i < n_pieces; ++i) {
+        p_piece[i] = piece_req[i];
+        p_piece[MI + i] = piece_tile[i];
+        p_piece[2 * MI + i] = piece_base[i];
+        p_piece[3 * MI + i] = piece_parts[i];
     }
     rc = gdn::upload_plan(img.data(), img.size() * sizeof(int32_t), workspace, stream);
     if (rc != GDN_OK) return rc;
@@ -216,16 +287,37 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     a.cu = ap.cu;
     a.start = ap.start;
     a.slot = ap.slot;
-    a.item_req = d + 3 * (int64_t)n_req + 1;
-    a.item_tile = a.item_req + max_items(n_req, T);
+    a.unit_req = d + 3 * (int64_t)n_req + 1;
+    a.unit_tile = a.unit_req + MU;
+    a.unit_t0 = a.unit_req + 2 * MU;
+    a.unit_t1 = a.unit_req + 3 * MU;
+    a.unit_part = a.unit_req + 4 * MU;
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T));
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T) + part_ml_bytes());
     a.slot_stride = slot_stride;
-    a.n_items = (int32_t)n_items;
+    a.n_units = (int32_t)n_units;
     a.H_q = s->H_q;
     a.H_kv = s->H_kv;
     a.xcd_split = xcd_split ? 1 : 0;
     a.scale_log2e = s->scale * 1.4426950408889634f;
     e = s->o_dtype == GDN_F32 ? launch_attn_d<float>(s->d, a, (unsigned)blocks, stream)
                               : launch_attn_d<uint16_t>(s->d, a, (unsigned)blocks, stream);
+    if (e != hipSuccess || n_pieces == 0) return hip_err(e);
+
+    CombineArgs ca;
+    ca.part_o = a.part_o;
+    ca.part_ml = a.part_ml;
+    ca.gate = a.gate;
+    ca.o = o;
+    ca.cu = a.cu;
+    ca.piece_req = a.unit_req + 5 * MU;
+    ca.piece_tile = ca.piece_req + MI;
+    ca.piece_base = ca.piece_req + 2 * MI;
+    ca.piece_parts = ca.piece_req + 3 * MI;
+    ca.H_q = s->H_q;
+    ca.scale_log2e = a.scale_log2e;
+    e = s->o_dtype == GDN_F32 ? launch_combine_d<float>(s->d, ca, (unsigned)(n_pieces * s->H_q), stream)
+                              : launch_combine_d<uint16_t>(s->d, ca, (unsigned)(n_pieces * s->H_q), stream);
     return hip_err(e);
 }
 

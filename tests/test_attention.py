@@ -46,7 +46,7 @@ class FakePool:
 def prefill_args(**over):
     d = FakePool()
     a = dict(shape=AT.make_attn_shape(4, 2, 64), q=d, k_new=d, v_new=d, out_gate=None, cu_seqlens=[0, 100, 130], start_pos=[0, 64],
-             k_cache=FakePool(ptr=0x200000), v_cache=FakePool(ptr=0x300000), seq_slot=[1, 3], o=d, workspace=FakePool(ptr=0x100000))
+             k_cache=FakePool(ptr=0x200000), v_cache=FakePool(ptr=0x300000), seq_slot=[1, 3], o=d, workspace=FakePool(ptr=0x100000, nbytes=1 << 28))
     a.update(over)
     return a
 
@@ -102,9 +102,11 @@ def test_restore_argument_errors_and_empty_calls(monkeypatch):
     AT.attn_kv_restore(sh, [0, 0], h, h, [0, 0], kc, vc, [0, 1])                     # empty prefixes copy nothing
     AT.attn_suffix_prefill(sh, None, None, None, None, [0], [], None, None, [], None, None)
     AT.attn_suffix_prefill(sh, None, None, None, None, [0, 0, 0], [3, 3], kc, vc, [2, 2], None, None)   # empty requests only
-    assert AT.attn_workspace_bytes(3, 1000) >= 4 * (3 * 3 + 1 + 2 * (1000 // 128 + 3))
+    assert AT.attn_workspace_bytes(sh, 3, 1000) >= 4 * (3 * 3 + 1 + 9 * (1000 // 128 + 3)) + 768 * 128 * (64 + 2) * 4
     with pytest.raises(B.GdnError):
-        AT.attn_workspace_bytes(-1, 0)
+        AT.attn_workspace_bytes(sh, -1, 0)
+    with pytest.raises(B.GdnError):
+        AT.attn_workspace_bytes(AT.make_attn_shape(4, 2, 100), 1, 10)
 
 
 # ----------------------------------------------------------------------------- GPU parity
@@ -143,7 +145,7 @@ def gpu_prefill(c, o_dtype="f32", gate=False, scale=None, pools=None):
     kp, vp = pools if pools is not None else pools_with_prefix(c)
     k_cache, v_cache = to_device(kp), to_device(vp)
     o = torch.full((max(c.T, 1), c.H_q, c.d), float("nan"), dtype=torch.float32 if o_dtype == "f32" else torch.bfloat16, device="cuda")
-    ws = torch.empty(max(AT.attn_workspace_bytes(len(c.start_pos), c.T), 256), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(AT.attn_workspace_bytes(sh, len(c.start_pos), c.T), dtype=torch.uint8, device="cuda")
     dev = lambda a: to_device(np.ascontiguousarray(a)) if a.size else None
     AT.attn_suffix_prefill(sh, dev(c.q), dev(c.suffix("k")), dev(c.suffix("v")), dev(c.gate) if gate else None, c.cu_seqlens,
                            c.start_pos, k_cache, v_cache, c.seq_slot, o, ws)
@@ -203,6 +205,23 @@ def test_peaked_and_flat_logits_stay_within_tolerance():
     ref = oracle_o(c, 0.37)
     check_o(got, ref, "f32", "flat")
     assert np.abs(got - ref).max() <= 2e-5 * np.abs(ref).max()     # no bf16 weight error at all in this case
+
+
+@pytest.mark.gpu
+def test_split_key_walks_agree_with_whole_walks(monkeypatch):
+    """A call with few workgroups splits its long key walks and merges the parts: the same result up to the
+    rounding of the fp16 weights (taken against another running maximum: 2^-12 relative each), also when parts
+    lie wholly past some queries' limits (a short request behind a long prefix, off the tile grid)."""
+    for seed, H_q, H_kv, d, lens, starts in [(3500, 4, 2, 128, [40, 300], [2000, 1111]), (3501, 2, 1, 64, [1, 129], [4095, 1500]),
+                                             (3502, 2, 2, 256, [70], [1300])]:
+        c = wl.attn_case(seed, H_q, H_kv, d, lens, starts)
+        monkeypatch.setenv("ATTN_NO_SPLIT", "1")
+        whole, _, _ = gpu_prefill(c, gate=True)
+        monkeypatch.delenv("ATTN_NO_SPLIT")
+        split, _, _ = gpu_prefill(c, gate=True)
+        assert not np.array_equal(whole, split)                       # the split path did run
+        assert np.abs(whole - split).max() <= 2.0 ** -11 * np.abs(whole).max()
+        check_o(split, oracle_o(c, d ** -0.5, True), "f32")
 
 
 @pytest.mark.gpu

@@ -315,7 +315,8 @@ def test_headers_are_plain_c_and_a_c_program_can_call_the_library(tmp_path):
         "    if (gdn_deepest_ckpt(pos, 3, 300) != 1 || gdn_deepest_ckpt(pos, 3, 5) != -1) return 2;\n"
         "    if (gdn_workspace_bytes(&s, 1, 256, 2) <= 0) return 3;\n"
         "    if (gdn_layer_workspace_bytes(2, 3) <= 0) return 4;\n"
-        "    if (attn_workspace_bytes(2, 300) <= 0) return 6;\n"
+        "    attn_shape as = {16, 2, 128, GDN_BF16, 0.088f};\n"
+        "    if (attn_workspace_bytes(&as, 2, 300) <= 0) return 6;\n"
         "    if (ckpt_place_balanced(511, 3, out) != 3 || out[0] != 128 || out[2] != 384) return 5;\n"
         '    printf("ok\\n");\n    return 0;\n}\n')
     exe = tmp_path / "abi"
