@@ -491,6 +491,48 @@ def main() -> int:
     except Exception as exc:
         out["layer_io"] = {"error": str(exc)}
 
+    # ---- the attention layer of the layer group on the same draws: suffix attention over the restored prefix
+    #      (16 query heads, 2 key/value heads, d = 128, bf16), the KV cache resident in HBM; matrix-core bound
+    try:
+        from paper_2605_05219_amd import attention as AT
+        HKV = 2
+        ash = AT.make_attn_shape(HEADS, HKV, D, "bf16")
+        kc = torch.randn((1, N_PREFIX, HKV, D), device=dev).bfloat16()
+        vc = torch.randn((1, N_PREFIX, HKV, D), device=dev).half()
+        starts = [int(c.call.start_pos[0]) for c in calls]
+        aq = [torch.randn((n, HEADS, D), device=dev).bfloat16() for n in suffix]
+        akn = [torch.randn((n, HKV, D), device=dev).bfloat16() for n in suffix]
+        avn = [torch.randn((n, HKV, D), device=dev).bfloat16() for n in suffix]
+        ao_ = torch.empty((N_PREFIX, HEADS, D), dtype=torch.bfloat16, device=dev)
+        aws = torch.empty(AT.attn_workspace_bytes(ash, 1, N_PREFIX), dtype=torch.uint8, device=dev)
+
+        def attn_step(i):
+            j = i % N_DRAWS
+            AT.attn_suffix_prefill(ash, aq[j], akn[j], avn[j], None, [0, suffix[j]], [starts[j]], kc, vc, [0], ao_, aws)
+
+        for i in range(N_DRAWS):
+            attn_step(i)
+        torch.cuda.synchronize()
+        ta0 = time.perf_counter()
+        for i in range(args.steps):
+            attn_step(i)
+        torch.cuda.synchronize()
+        a_ms = 1e3 * (time.perf_counter() - ta0) / args.steps
+        a_tok = sum(suffix[i % N_DRAWS] for i in range(args.steps))
+        # (query, key) pairs inside the causal limit; 4 d flops each (two contractions)
+        pairs = sum(suffix[i % N_DRAWS] * starts[i % N_DRAWS] + suffix[i % N_DRAWS] * (suffix[i % N_DRAWS] + 1) // 2
+                    for i in range(args.steps))
+        a_tf = 4.0 * D * pairs * HEADS / (a_ms * 1e-3 * args.steps) / 1e12
+        out["attention"] = {"ms_per_step": a_ms, "tokens_per_s": a_tok / (a_ms * 1e-3 * args.steps), "TFLOPs": a_tf,
+                            "peak_TFLOPs": PEAK_MFMA_TFLOPS, "frac": a_tf / PEAK_MFMA_TFLOPS,
+                            "heads": [HEADS, HKV], "d": D,
+                            "note": "attn_suffix_prefill on the same draws (append + attention [+ merge of split key walks]); "
+                                    "wall time per call; causal flops 4 d per visible (query, key) pair against the dense "
+                                    "bf16 peak"}
+        del kc, vc, aq, akn, avn, ao_, aws
+    except Exception as exc:
+        out["attention"] = {"error": str(exc)}
+
     # ---- side measurement: what this chip delivers (fp16 matrix-instruction loop, plain 1 GiB copy), as context
     #      for the data-sheet peaks the roofline is priced against
     try:
