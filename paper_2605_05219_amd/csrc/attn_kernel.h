@@ -5,7 +5,7 @@
 // Attention kernel.  One workgroup of four waves owns ATT_BQ = 128 consecutive suffix tokens of
 // one (request, query head); wave w owns 32 of them, one per lane column.  Key/value rows are
 // walked in tiles of ATT_KT = 64, each tile brought into one of two LDS stages by 16-byte
-// global->LDS loads (no registers) while the waves compute on the other stage.
+// buffer loads to LDS (no registers) while the waves compute on the other stage.
 //
 // Both contractions are computed transposed, so that a query is a COLUMN of every accumulator
 // tile and everything a softmax row needs sits in one lane (and its partner 32 lanes up):
@@ -26,7 +26,7 @@
 // piece into parts of whole tiles: each part is a workgroup that leaves its unnormalised O, running
 // maximum and normaliser in a workspace slot, and a second kernel merges the parts of a piece.
 //
-// LDS rows are unpadded (the global->LDS load writes a wave's 64 x 16 bytes contiguously); bank
+// LDS rows are unpadded (a load to LDS writes a wave's 64 x 16 bytes contiguously); bank
 // conflicts are avoided by storing 16-byte chunk c of row r at chunk position c ^ f(r), with f
 // chosen per tile for its read pattern (16 rows x same chunk for keys, 4 rows x 4 chunks for values).
 #pragma once
@@ -49,7 +49,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int ATT_BQ = 128;       // suffix tokens per workgroup
-constexpr int ATT_KT = 64;        // key/value rows per tile
+constexpr int ATT_KT = 64;        // key/value rows per tile (a multiple of 32)
+constexpr int ATT_KVB = ATT_KT / 32;   // 32-row accumulator tiles of S^T per key tile
 constexpr int ATT_THREADS = 256;
 constexpr int APPEND_THREADS = 256;
 
@@ -94,6 +95,13 @@ struct AppendArgs {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
+}
+
+// One wave-wide 16-byte-per-lane buffer load to LDS: lane i's chunk lands at lds + 16 i.  The descriptor covers
+// `bytes` from `base`; a lane whose byte offset voff + soff lies past it writes zeros.
+__device__ __forceinline__ void load_to_lds(const void* base, int bytes, char* lds, int voff, int soff) {
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds, 16, voff, soff, 0, 0);
 }
 
 // max / sum of a value with the lane 32 up or down (one swap instruction, no LDS)
@@ -196,26 +204,33 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
     const int qrow = min(wq0 + col, q_end - 1);            // clamped: lanes past the end repeat the last row
     const int lim = c0 + qrow;                             // last visible key row (0-based) of this lane's query
 
-    const int64_t row_stride = (int64_t)a.H_kv * D;        // elements between key rows
-    const uint16_t* const kbase = a.k_cache + (int64_t)a.slot[r] * a.slot_stride + (int64_t)kvh * D;
-    const uint16_t* const vbase = a.v_cache + (int64_t)a.slot[r] * a.slot_stride + (int64_t)kvh * D;
-
-    // ---- tile loader: wave w brings pieces [w*PIECES/4, (w+1)*PIECES/4) of the key and of the value tile
+    // ---- tile loader: wave w brings pieces [w*PPW, (w+1)*PPW) of the key and of the value tile, one 16-byte
+    // chunk per lane and piece, by buffer loads to LDS.  The descriptors cover rows [0, kv_len) of the request's
+    // slot: lanes of rows past kv_len (the ragged end of the last tile) write zeros, which the mask never weighs.
+    // A lane's offset inside a piece does not change from tile to tile; the tile and piece move in the scalar offset.
+    constexpr int PPW = SM::PIECES / 4;                    // pieces per wave and tensor
+    constexpr int RPP = 64 / CPR;                          // rows per piece
+    const int row_bytes = a.H_kv * D * 2;
+    const uint16_t* const kslot = a.k_cache + (int64_t)a.slot[r] * a.slot_stride;
+    const uint16_t* const vslot = a.v_cache + (int64_t)a.slot[r] * a.slot_stride;
+    const int slot_bytes = kv_len * row_bytes;
+    int koff[PPW], voff[PPW];
+#pragma unroll
+    for (int i = 0; i < PPW; ++i) {
+        const int s = (wave * PPW + i) * 64 + lane;        // 16-byte slot inside the tile
+        const int row = s / CPR, pos = s % CPR;
+        const int in_piece = (row - (wave * PPW + i) * RPP) * row_bytes + kvh * D * 2;
+        koff[i] = in_piece + ((pos ^ SM::fk(row)) << 4);
+        voff[i] = in_piece + ((pos ^ SM::fv(row)) << 4);
+    }
     auto issue = [&](int t, int stage) {
         char* const sb = smem + stage * SM::STAGE_BYTES;
-        const int kv0 = t * ATT_KT;
 #pragma unroll
-        for (int i = 0; i < SM::PIECES / 4; ++i) {
-            const int p = wave * (SM::PIECES / 4) + i;
-            const int s = p * 64 + lane;                   // 16-byte slot inside the tile
-            const int row = s / CPR, pos = s % CPR;
-            const int64_t grow = min(kv0 + row, kv_len - 1);
-            const uint16_t* const ksrc = kbase + grow * row_stride + ((pos ^ SM::fk(row)) << 3);
-            const uint16_t* const vsrc = vbase + grow * row_stride + ((pos ^ SM::fv(row)) << 3);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ksrc,
-                                             (__attribute__((address_space(3))) void*)(sb + SM::K_OFF + p * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)vsrc,
-                                             (__attribute__((address_space(3))) void*)(sb + SM::V_OFF + p * 1024), 16, 0, 0);
+        for (int i = 0; i < PPW; ++i) {
+            const int p = wave * PPW + i;
+            const int soff = (t * ATT_KT + p * RPP) * row_bytes;
+            load_to_lds(kslot, slot_bytes, sb + SM::K_OFF + p * 1024, koff[i], soff);
+            load_to_lds(vslot, slot_bytes, sb + SM::V_OFF + p * 1024, voff[i], soff);
         }
     };
     issue(t0, 0);
@@ -255,10 +270,10 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         const char* const sb = smem + stage * SM::STAGE_BYTES;
         const int kv0 = t * ATT_KT;
 
-        // ---- S^T = K Q^T, two 32-row tiles
-        f32x16 S[2];
+        // ---- S^T = K Q^T, in 32-row tiles
+        f32x16 S[ATT_KVB];
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb) {
+        for (int kvb = 0; kvb < ATT_KVB; ++kvb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) S[kvb][i] = 0.f;
 #pragma unroll
@@ -271,7 +286,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         // ---- causal mask on the tiles that reach past the first row's limit
         if (kv0 + ATT_KT - 1 > c0 + wq0) {
 #pragma unroll
-            for (int kvb = 0; kvb < 2; ++kvb)
+            for (int kvb = 0; kvb < ATT_KVB; ++kvb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int kv = kv0 + 32 * kvb + 8 * (i >> 2) + 4 * g + (i & 3);
@@ -281,7 +296,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         // ---- online softmax for this lane's query
         float mx = S[0][0];
 #pragma unroll
-        for (int kvb = 0; kvb < 2; ++kvb)
+        for (int kvb = 0; kvb < ATT_KVB; ++kvb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[kvb][i]);
         mx = max_with_other_half(mx);
@@ -291,10 +306,10 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         const float alpha = __builtin_amdgcn_exp2f((m - m_ref) * c);
         const float mc = m_ref * c;
         m = m_new;
-        half8 pf[4];                           // B operands of the four 16-row steps
+        half8 pf[2 * ATT_KVB];                 // B operands of the 16-row steps
         float lsum = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int s = 0; s < 2 * ATT_KVB; ++s) {
             f32x2 e[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -323,7 +338,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         for (int rb = 0; rb < RB; ++rb) {
             const int vpos = ((4 * rb + vchunk) ^ vfv) << 4;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < 2 * ATT_KVB; ++s) {
                 const char* const p0 = sb + vrow_off + vpos + (16 * s) * SM::ROW_BYTES;
                 const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0));
                 const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4*)(p0 + 8 * SM::ROW_BYTES));

@@ -32,6 +32,7 @@ int32_t check_pool(const attn_shape* s, int64_t slot_stride, int32_t n_slots, in
     if (n_slots < 0 || cap < 0) return GDN_ERR_COUNT;
     if (slot_stride < 0 || slot_stride % 8 != 0) return GDN_ERR_ALIGN;
     if (slot_stride < (int64_t)cap * s->H_kv * s->d) return GDN_ERR_SHAPE;   // slots would overlap
+    if ((int64_t)cap * s->H_kv * s->d * 2 > INT32_MAX) return GDN_ERR_SHAPE;   // a slot is addressed with 32-bit byte offsets
     return GDN_OK;
 }
 
@@ -52,7 +53,7 @@ int32_t check_slots(const int32_t* ids, int32_t n, int32_t n_slots, bool skip_em
 // into parts of at least SPLIT_MIN_TILES key tiles, aiming at SPLIT_BELOW workgroups in all; the
 // partial results of at most SPLIT_MAX_WGS (part, head) pairs live in the workspace.
 constexpr int SPLIT_BELOW = 512;       // two workgroups per compute unit
-constexpr int SPLIT_MIN_TILES = 8;
+constexpr int SPLIT_MIN_TILES = 512 / ATT_KT;   // 512 keys
 constexpr int SPLIT_MAX_WGS = 768;
 
 // ints of the uploaded index arrays: cu (n_req+1), start, slot (n_req each), five per unit, four per split piece
