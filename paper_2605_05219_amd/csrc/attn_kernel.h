@@ -265,10 +265,17 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         const int stage = (t - t0) & 1;
         wait_vmcnt<0>();
         __syncthreads();                       // tile t has landed; everyone has left the other stage
-        if (t + 1 < t1) issue(t + 1, stage ^ 1);
-        if (t >= n_tiles_w) continue;          // wave-uniform: nothing of this tile is visible to this wave
+        if (t >= n_tiles_w) {                  // wave-uniform: nothing of this tile is visible to this wave
+            issue(t + 1, stage ^ 1);
+            continue;
+        }
         const char* const sb = smem + stage * SM::STAGE_BYTES;
         const int kv0 = t * ATT_KT;
+        // The next tile's loads are issued in between the matrix instructions of S^T (issuing one takes some
+        // tens of cycles, which a matrix instruction in flight covers).  Past the unit's last tile the loads
+        // are issued all the same: they stay inside the slot, or are cut to zeros by the descriptor, and land
+        // in the stage nobody reads.
+        issue(t + 1, stage ^ 1);
 
         // ---- S^T = K Q^T, in 32-row tiles
         f32x16 S[ATT_KVB];
@@ -282,6 +289,13 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
                     bf16x8, *reinterpret_cast<const u32x4*>(sb + SM::K_OFF + kvb * 32 * SM::ROW_BYTES + krow_off + (((2 * kb) ^ kz) << 4)));
                 S[kvb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kb], S[kvb], 0, 0, 0);
             }
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);            // four key fragments ahead
+#pragma unroll
+        for (int i = 0; i < ATT_KVB * KB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        // one matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        // one key fragment read
+            if (i < 2 * PPW) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // one load to LDS
         }
         // ---- causal mask on the tiles that reach past the first row's limit
         if (kv0 + ATT_KT - 1 > c0 + wq0) {
@@ -348,6 +362,7 @@ __global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_ker
         }
     }
 
+    wait_vmcnt<0>();                           // no load to LDS may be in flight when the workgroup's LDS is given back
     // ---- a part of a split walk leaves its unnormalised result in its workspace slot
     if (part >= 0) {
         if (wq0 + col < q_end) {
