@@ -72,6 +72,17 @@ int32_t attn_kv_restore(const attn_shape *shape, int32_t n_req, const int32_t *p
                         int32_t cap, const int32_t *seq_slot, void *stream);
 
 /*
+ * The reverse of attn_kv_restore: rows 0 .. n_rows[r]-1 of device slot seq_slot[r] go to the same
+ * rows of host slot host_slot[r] (how a finished request's keys and values reach the host pool);
+ * host_slot ids distinct.  Same argument meaning and errors.
+ */
+int32_t attn_kv_spill(const attn_shape *shape, int32_t n_req, const int32_t *n_rows,
+                      void *host_k, void *host_v, int64_t host_slot_stride,
+                      int32_t n_host_slots, const int32_t *host_slot,
+                      const void *k_cache, const void *v_cache, int64_t slot_stride, int32_t n_slots,
+                      int32_t cap, const int32_t *seq_slot, void *stream);
+
+/*
  * Suffix prefill of the attention layer for a packed batch of resumed requests: appends the
  * suffix's keys and values to each request's cache rows and computes the attention output of
  * every suffix token over positions 1 .. its own (two launches on `stream`; three when the call

@@ -7,7 +7,7 @@ from .binding import GDN_BF16, GDN_F32, _check, _dp, _h32, _hp, _stream_ptr, lib
 
 _i32, _i64, _vp, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
 
-EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_suffix_prefill"]
+EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_kv_spill", "attn_suffix_prefill"]
 
 
 class attn_shape(ctypes.Structure):
@@ -31,6 +31,8 @@ def _lib():
         L.attn_kv_restore.restype = _i32
         L.attn_kv_restore.argtypes = ([ctypes.POINTER(attn_shape), _i32, _vp] + [_vp, _vp, _i64, _i32, _vp]
                                       + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp])
+        L.attn_kv_spill.restype = _i32
+        L.attn_kv_spill.argtypes = L.attn_kv_restore.argtypes
         L.attn_suffix_prefill.restype = _i32
         L.attn_suffix_prefill.argtypes = ([ctypes.POINTER(attn_shape)] + [_vp] * 4 + [_i32, _vp, _vp]
                                           + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp, _vp, _i64, _vp])
@@ -58,6 +60,16 @@ def attn_kv_restore(shape: attn_shape, prefix_len, host_k, host_v, host_slot, k_
     _check(_lib().attn_kv_restore(ctypes.byref(shape), int(pl.size), _hp(pl), _dp(host_k), _dp(host_v), hstride, hn, _hp(hs),
                                   _dp(k_cache), _dp(v_cache), stride, n_slots, cap, _hp(ss), _stream_ptr(stream)),
            "attn_kv_restore")
+
+
+def attn_kv_spill(shape: attn_shape, n_rows, host_k, host_v, host_slot, k_cache, v_cache, seq_slot, stream=None) -> None:
+    """See include/attn_resume.h: the reverse of attn_kv_restore (device slots to host slots)."""
+    nr, hs, ss = _h32(n_rows), _h32(host_slot), _h32(seq_slot)
+    stride, n_slots, cap = _pool_geometry(k_cache)
+    hstride, hn, _ = _pool_geometry(host_k)
+    _check(_lib().attn_kv_spill(ctypes.byref(shape), int(nr.size), _hp(nr), _dp(host_k), _dp(host_v), hstride, hn, _hp(hs),
+                                _dp(k_cache), _dp(v_cache), stride, n_slots, cap, _hp(ss), _stream_ptr(stream)),
+           "attn_kv_spill")
 
 
 def attn_suffix_prefill(shape: attn_shape, q, k_new, v_new, out_gate, cu_seqlens, start_pos, k_cache, v_cache, seq_slot, o,

@@ -112,10 +112,11 @@ int64_t attn_workspace_bytes(const attn_shape* s, int32_t n_req, int64_t total_t
     return plan_bytes(n_req, total_tokens) + part_ml_bytes() + part_o_bytes(s->d);
 }
 
-int32_t attn_kv_restore(const attn_shape* s, int32_t n_req, const int32_t* prefix_len, const void* host_k, const void* host_v,
-                        int64_t host_slot_stride, int32_t n_host_slots, const int32_t* host_slot, void* k_cache, void* v_cache,
-                        int64_t slot_stride, int32_t n_slots, int32_t cap, const int32_t* seq_slot, void* stream_v) {
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+// shared by attn_kv_restore and attn_kv_spill: rows [0, n_rows[r]) of one pool's slot to the other's
+static int32_t kv_tier_copy(const attn_shape* s, int32_t n_req, const int32_t* n_rows, void* host_k, void* host_v,
+                            int64_t host_slot_stride, int32_t n_host_slots, const int32_t* host_slot, void* k_cache, void* v_cache,
+                            int64_t slot_stride, int32_t n_slots, int32_t cap, const int32_t* seq_slot, bool to_device,
+                            hipStream_t stream) {
     int32_t rc = check_shape(s);
     if (rc != GDN_OK) return rc;
     if (n_req < 0 || n_host_slots < 0) return GDN_ERR_COUNT;
@@ -124,31 +125,53 @@ int32_t attn_kv_restore(const attn_shape* s, int32_t n_req, const int32_t* prefi
     rc = check_pool(s, host_slot_stride, n_host_slots, cap);
     if (rc != GDN_OK) return rc;
     if (n_req == 0) return GDN_OK;
-    if (!prefix_len || !host_slot || !seq_slot) return GDN_ERR_NULL;
+    if (!n_rows || !host_slot || !seq_slot) return GDN_ERR_NULL;
     int64_t total = 0;
     for (int32_t r = 0; r < n_req; ++r) {
-        if (prefix_len[r] < 0 || prefix_len[r] > cap) return GDN_ERR_START;
-        if (host_slot[r] < 0 || host_slot[r] >= n_host_slots) return GDN_ERR_SLOT_RANGE;
-        total += prefix_len[r];
+        if (n_rows[r] < 0 || n_rows[r] > cap) return GDN_ERR_START;
+        total += n_rows[r];
     }
-    rc = check_slots(seq_slot, n_req, n_slots, false, nullptr);
+    // the source slots only have to exist; the destination slots must also differ
+    for (int32_t r = 0; r < n_req; ++r) {
+        if (host_slot[r] < 0 || host_slot[r] >= n_host_slots) return GDN_ERR_SLOT_RANGE;
+        if (seq_slot[r] < 0 || seq_slot[r] >= n_slots) return GDN_ERR_SLOT_RANGE;
+    }
+    rc = to_device ? check_slots(seq_slot, n_req, n_slots, false, nullptr) : check_slots(host_slot, n_req, n_host_slots, false, nullptr);
     if (rc != GDN_OK) return rc;
     if (total == 0) return GDN_OK;
     if (!host_k || !host_v || !k_cache || !v_cache) return GDN_ERR_NULL;
     if (!aligned16(k_cache) || !aligned16(v_cache)) return GDN_ERR_ALIGN;
     const int64_t row = (int64_t)s->H_kv * s->d;
     for (int32_t r = 0; r < n_req; ++r) {
-        if (prefix_len[r] == 0) continue;
-        const size_t bytes = (size_t)prefix_len[r] * row * sizeof(uint16_t);
-        const int64_t src = (int64_t)host_slot[r] * host_slot_stride, dst = (int64_t)seq_slot[r] * slot_stride;
-        hipError_t e = hipMemcpyAsync(static_cast<uint16_t*>(k_cache) + dst, static_cast<const uint16_t*>(host_k) + src, bytes,
-                                      hipMemcpyHostToDevice, stream);
+        if (n_rows[r] == 0) continue;
+        const size_t bytes = (size_t)n_rows[r] * row * sizeof(uint16_t);
+        const int64_t ho = (int64_t)host_slot[r] * host_slot_stride, dv = (int64_t)seq_slot[r] * slot_stride;
+        uint16_t* const hk = static_cast<uint16_t*>(host_k) + ho;
+        uint16_t* const hv = static_cast<uint16_t*>(host_v) + ho;
+        uint16_t* const dk = static_cast<uint16_t*>(k_cache) + dv;
+        uint16_t* const dvp = static_cast<uint16_t*>(v_cache) + dv;
+        hipError_t e = to_device ? hipMemcpyAsync(dk, hk, bytes, hipMemcpyHostToDevice, stream)
+                                 : hipMemcpyAsync(hk, dk, bytes, hipMemcpyDeviceToHost, stream);
         if (e != hipSuccess) return hip_err(e);
-        e = hipMemcpyAsync(static_cast<uint16_t*>(v_cache) + dst, static_cast<const uint16_t*>(host_v) + src, bytes,
-                           hipMemcpyHostToDevice, stream);
+        e = to_device ? hipMemcpyAsync(dvp, hv, bytes, hipMemcpyHostToDevice, stream)
+                      : hipMemcpyAsync(hv, dvp, bytes, hipMemcpyDeviceToHost, stream);
         if (e != hipSuccess) return hip_err(e);
     }
     return GDN_OK;
+}
+
+int32_t attn_kv_restore(const attn_shape* s, int32_t n_req, const int32_t* prefix_len, const void* host_k, const void* host_v,
+                        int64_t host_slot_stride, int32_t n_host_slots, const int32_t* host_slot, void* k_cache, void* v_cache,
+                        int64_t slot_stride, int32_t n_slots, int32_t cap, const int32_t* seq_slot, void* stream) {
+    return kv_tier_copy(s, n_req, prefix_len, const_cast<void*>(host_k), const_cast<void*>(host_v), host_slot_stride, n_host_slots,
+                        host_slot, k_cache, v_cache, slot_stride, n_slots, cap, seq_slot, true, static_cast<hipStream_t>(stream));
+}
+
+int32_t attn_kv_spill(const attn_shape* s, int32_t n_req, const int32_t* n_rows, void* host_k, void* host_v,
+                      int64_t host_slot_stride, int32_t n_host_slots, const int32_t* host_slot, const void* k_cache,
+                      const void* v_cache, int64_t slot_stride, int32_t n_slots, int32_t cap, const int32_t* seq_slot, void* stream) {
+    return kv_tier_copy(s, n_req, n_rows, host_k, host_v, host_slot_stride, n_host_slots, host_slot, const_cast<void*>(k_cache),
+                        const_cast<void*>(v_cache), slot_stride, n_slots, cap, seq_slot, false, static_cast<hipStream_t>(stream));
 }
 
 int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_new, const void* v_new, const void* out_gate,

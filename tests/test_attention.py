@@ -98,6 +98,9 @@ def test_restore_argument_errors_and_empty_calls(monkeypatch):
         with pytest.raises(B.GdnError) as ei:
             AT.attn_kv_restore(*args)
         assert ei.value.code == code
+    with pytest.raises(B.GdnError) as ei:                                            # spill: two requests into one host slot
+        AT.attn_kv_spill(sh, [5, 1], h, h, [2, 2], kc, vc, [0, 1])
+    assert ei.value.code == -6
     AT.attn_kv_restore(sh, [], None, None, [], None, None, [])                       # nothing to do, nothing touched
     AT.attn_kv_restore(sh, [0, 0], h, h, [0, 0], kc, vc, [0, 1])                     # empty prefixes copy nothing
     AT.attn_suffix_prefill(sh, None, None, None, None, [0], [], None, None, [], None, None)
@@ -267,8 +270,18 @@ def test_restore_from_a_pinned_host_pool_is_bitwise_and_feeds_the_prefill():
         p = int(c.start_pos[r])
         k_want[s, :p], v_want[s, :p] = c.k_full[r][:p], v_bits(c.v_full[r][:p])
     assert np.array_equal(bits(k_cache), k_want) and np.array_equal(bits(v_cache), v_want)
-    got, _, _ = gpu_prefill(c, pools=(bits(k_cache), bits(v_cache)))
+    got, k_after, v_after = gpu_prefill(c, pools=(bits(k_cache), bits(v_cache)))
     check_o(got, oracle_o(c, d ** -0.5), "f32")
+    # and back: the finished requests' rows (prefix + suffix) spilled to fresh host slots, bit for bit, nothing else
+    back_k, back_v = pin(np.full_like(hk, 0x1111)), pin(np.full_like(hv, 0x1111))
+    n_rows = [len(kf) for kf in c.k_full]
+    AT.attn_kv_spill(sh, n_rows, back_k, back_v, [1, 2, 0], to_device(k_after), to_device(v_after), c.seq_slot)
+    torch.cuda.synchronize()
+    hb = lambda t: t.view(torch.int16).numpy().view(np.uint16)
+    for r, hs in enumerate([1, 2, 0]):
+        assert np.array_equal(hb(back_k)[hs, :n_rows[r]], c.k_full[r]) and np.array_equal(hb(back_v)[hs, :n_rows[r]], v_bits(c.v_full[r]))
+        assert (hb(back_k)[hs, n_rows[r]:] == 0x1111).all() and (hb(back_v)[hs, n_rows[r]:] == 0x1111).all()
+    assert (hb(back_k)[3:] == 0x1111).all() and (hb(back_v)[3:] == 0x1111).all()
 
 
 @pytest.mark.gpu
