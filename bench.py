@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time ONE call of k = 1..64 requests of this workload's kind (side object "
                          "`batch_sweep`; about a minute of host-side input generation)")
+    ap.add_argument("--layer-group", action="store_true",
+                    help="also time a whole cache hit on a layer group (3 GatedDeltaNet layers + 1 attention layer, "
+                         "checkpoint and KV cache restored from pinned host memory) against the suffix length")
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="skip the per-kernel HIP event pass (no roofline object)")
     ap.add_argument("--events-in-timed-region", action="store_true",
@@ -532,6 +535,90 @@ def main() -> int:
         del kc, vc, aq, akn, avn, ao_, aws
     except Exception as exc:
         out["attention"] = {"error": str(exc)}
+
+    # ---- a whole cache hit on a layer group as in the paper's runtime experiment (Sec. 5: one full attention layer
+    #      and three GatedDeltaNet layers; projections excluded): checkpoint states and the attention KV prefix are
+    #      restored from pinned host memory, then the suffix runs through the layers' front ends, the resumed
+    #      recurrence (3 layers in one call, downstream checkpoints stored), the back ends and the attention layer.
+    if args.layer_group:
+        try:
+            from paper_2605_05219_amd import attention as AT, layer as LY
+            Lg, HKV, N = 3, 2, N_PREFIX
+            Cc = 3 * HEADS * D
+            step_ck = N // M_CKPT
+            lsh = LY.make_layer_shape(HEADS, HEADS, D, D, 4, "bf16", "bf16", "f32")
+            ash = AT.make_attn_shape(HEADS, HKV, D, "bf16")
+            gsh = B.make_shape(Lg, HEADS, HEADS, D, D, "bf16", "f32", N)
+            bf = lambda *sh_: torch.randn(sh_, device=dev).bfloat16()
+            xs = [bf(N, Cc) for _ in range(Lg)]
+            aps, bps, zs = [bf(N, HEADS) for _ in range(Lg)], [bf(N, HEADS) for _ in range(Lg)], [bf(N, HEADS, D) for _ in range(Lg)]
+            cw, cb = torch.randn((Cc, 4), device=dev) * 0.5, torch.randn(Cc, device=dev) * 0.1
+            Al, dtb, nw = torch.zeros(HEADS, device=dev), torch.zeros(HEADS, device=dev), torch.ones(D, device=dev)
+            qp, kp, vp = (torch.empty((Lg, N, HEADS, D), dtype=torch.bfloat16, device=dev) for _ in range(3))
+            bp_, gp_ = (torch.empty((Lg, N, HEADS), dtype=torch.bfloat16, device=dev) for _ in range(2))
+            op = torch.empty((Lg, N, HEADS, D), dtype=torch.float32, device=dev)
+            yp = torch.empty((N, HEADS, D), dtype=torch.bfloat16, device=dev)
+            spool = torch.zeros((M_CKPT + 2, Lg, HEADS, D, D), dtype=torch.float32, device=dev)   # slot 0: the loaded state
+            hstate = (torch.randn((M_CKPT + 1, Lg, HEADS, D, D)) * 0.05).pin_memory()
+            cpools = [bf(M_CKPT + 2, 3, Cc) for _ in range(Lg)]
+            hk = torch.randn((1, N, HKV, D)).bfloat16().pin_memory()
+            hv = torch.randn((1, N, HKV, D)).half().pin_memory()
+            kc2 = torch.empty((1, N, HKV, D), dtype=torch.bfloat16, device=dev)
+            vc2 = torch.empty((1, N, HKV, D), dtype=torch.float16, device=dev)
+            aq2, akn2, avn2 = bf(N, HEADS, D), bf(N, HKV, D), bf(N, HKV, D)
+            ao2 = torch.empty((N, HEADS, D), dtype=torch.bfloat16, device=dev)
+            gws = torch.empty(B.gdn_workspace_bytes(gsh, 1, N, M_CKPT), dtype=torch.uint8, device=dev)
+            lws = torch.empty(LY.gdn_layer_workspace_bytes(1, M_CKPT), dtype=torch.uint8, device=dev)
+            aws2 = torch.empty(AT.attn_workspace_bytes(ash, 1, N), dtype=torch.uint8, device=dev)
+
+            def hit(n, from_host):
+                c = N - n                                   # the checkpoint the request resumes from
+                emits = list(range(c + step_ck, N + 1, step_ck))
+                eslots = list(range(1, 1 + len(emits)))
+                if c > 0 and from_host:
+                    B.ckpt_fetch_host(hstate, [c // step_ck], spool, [0])
+                    AT.attn_kv_restore(ash, [c], hk, hv, [0], kc2, vc2, [0])
+                for l in range(Lg):
+                    LY.gdn_layer_inputs(lsh, xs[l][c:], cw, cb, aps[l][c:], bps[l][c:], Al, dtb, [0, n], [c], cpools[l],
+                                        [0 if c > 0 else -1], [0, len(emits)], emits, cpools[l], eslots,
+                                        qp[l], kp[l], vp[l], bp_[l], gp_[l], lws)
+                B.gdn_resume_prefill(gsh, qp, kp, vp, bp_, gp_, [0, n], [c], spool, [0 if c > 0 else -1], [0, len(emits)], emits,
+                                     spool, eslots, op, gws)
+                for l in range(Lg):
+                    LY.gdn_layer_output(lsh, op[l], zs[l][c:], nw, yp, n)
+                AT.attn_suffix_prefill(ash, aq2[c:], akn2[c:], avn2[c:], None, [0, n], [c], kc2, vc2, [0], ao2, aws2)
+
+            pts = []
+            for n in (512, 1024, 2048, 4096, 6144, 8192):
+                row = {"suffix_tokens": n}
+                for key, from_host in (("ms_host_tier", True), ("ms_hbm_tier", False)):
+                    for _ in range(3):
+                        hit(n, from_host)
+                    torch.cuda.synchronize()
+                    reps, batches = 8, []
+                    for _ in range(5):                      # the median of five batches: one slow copy does not decide a point
+                        tg0 = time.perf_counter()
+                        for _ in range(reps):
+                            hit(n, from_host)
+                        torch.cuda.synchronize()
+                        batches.append(1e3 * (time.perf_counter() - tg0) / reps)
+                    row[key] = float(np.median(batches))
+                c = N - n
+                row["restored_bytes"] = (Lg * HEADS * D * D * 4 + 2 * c * HKV * D * 2) if c > 0 else 0
+                pts.append(row)
+            xs_ = np.array([p["suffix_tokens"] for p in pts], float)
+            fit = {}
+            for key in ("ms_host_tier", "ms_hbm_tier"):
+                slope, icpt = np.polyfit(xs_[:-1], np.array([p[key] for p in pts[:-1]]), 1)    # the hits; the last point is the miss
+                fit[key] = {"per_1k_tokens": 1e3 * slope, "offset": icpt}
+            out["layer_group"] = {"layers": "3 GatedDeltaNet + 1 attention (16 query / 2 kv heads), d = 128, projections excluded",
+                                  "points": pts, "fit_ms": fit,
+                                  "note": "wall time of a whole hit per suffix length (8192 = a miss: nothing restored); host tier: "
+                                          "checkpoint states (3 MiB) and the KV prefix come from pinned host memory inside the timed "
+                                          "region; hbm tier: both are already in device memory"}
+            del xs, zs, qp, kp, vp, op, spool, hstate, cpools, kc2, vc2
+        except Exception as exc:
+            out["layer_group"] = {"error": repr(exc)}
 
     # ---- side measurement: what this chip delivers (fp16 matrix-instruction loop, plain 1 GiB copy), as context
     #      for the data-sheet peaks the roofline is priced against
