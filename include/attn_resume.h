@@ -5,7 +5,7 @@
  * except the wait for the previous call's plan upload).
  *
  * Why it belongs to the path: the paper's hybrid runs keep the full attention KV cache beside
- * the sparse recurrent checkpoints (Table 1, caption), count "loading the cached KV state" as
+ * the sparse recurrent checkpoints (Table 1, caption), count the load of the cached keys and values as
  * the third part of a hit's cost (Sec. 5, overhead decomposition), and time a layer group with
  * one full attention layer (Sec. 5, runtime experiment).  The paper does not restate attention;
  * what is computed is causal softmax attention of the recomputed suffix over the restored prefix:

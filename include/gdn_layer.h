@@ -4,9 +4,9 @@
  * device pointers, validation before anything is enqueued, negative error codes, no
  * allocation, no stream synchronisation except the wait for the previous call's plan upload).
  *
- * Why it belongs to the path: the paper restores layers "whose hidden state can be extracted
- * and restored exactly" (Sec. 1) and times a layer group with GatedDeltaNet layers (Sec. 5,
- * runtime experiment).  Besides the matrix state S, such a layer carries the last K-1 inputs of
+ * Why it belongs to the path: the paper's method applies to layers whose hidden state can be
+ * taken out and put back without loss (Sec. 1), and it times a layer group with GatedDeltaNet
+ * layers (Sec. 5, runtime experiment).  Besides the matrix state S, such a layer carries the last K-1 inputs of
  * its short convolution; a resumed request is exact only if those rows are checkpointed and
  * restored with S.  The paper does not restate the layer; what is computed is the published
  * GatedDeltaNet layer (projections excluded: they are plain GEMMs):

@@ -4,7 +4,7 @@ Only tests/ may import this module.  Plain numpy, fp64, the definition written o
 a library matmul as the only primitive; it shares no code with the library.
 
 The paper's hybrid runs keep the full attention KV cache next to the sparse recurrent checkpoints
-(Table 1, caption) and list "loading the cached KV state" for the attention layers as the third
+(Table 1, caption) and name the load of the attention layers' cached keys and values as the third
 part of a cache hit's cost (Sec. 5, overhead decomposition); its timed layer group holds one full
 attention layer (Sec. 5, runtime experiment).  The paper does not restate attention.  What is
 computed is causal softmax attention of the recomputed suffix over the restored prefix:

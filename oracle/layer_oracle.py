@@ -3,7 +3,7 @@
 Only tests/ may import this module.  Plain numpy, fp64, every function the definition written
 out with explicit loops over tokens and taps; it shares no code with the library.
 
-The paper restores "layers whose hidden state can be extracted and restored exactly" (Sec. 1)
+The paper's method applies to layers whose hidden state can be taken out and put back without loss (Sec. 1)
 and measures a layer group with GatedDeltaNet layers (Sec. 5, runtime experiment) without
 restating the layer.  What is computed here is the published GatedDeltaNet layer around the
 recurrence, in the notation of the recurrence oracle (positions 1-based, state "at" position c
