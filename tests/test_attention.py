@@ -216,7 +216,8 @@ def test_split_key_walks_agree_with_whole_walks(monkeypatch):
     rounding of the fp16 weights (taken against another running maximum: 2^-12 relative each), also when parts
     lie wholly past some queries' limits (a short request behind a long prefix, off the tile grid)."""
     for seed, H_q, H_kv, d, lens, starts in [(3500, 4, 2, 128, [40, 300], [2000, 1111]), (3501, 2, 1, 64, [1, 129], [4095, 1500]),
-                                             (3502, 2, 2, 256, [70], [1300])]:
+                                             (3502, 2, 2, 256, [70], [1300]),
+                                             (3503, 4, 2, 128, [100, 64, 0, 200], [0, 3000, 5, 900])]:   # whole and split walks in one call
         c = wl.attn_case(seed, H_q, H_kv, d, lens, starts)
         monkeypatch.setenv("ATTN_NO_SPLIT", "1")
         whole, _, _ = gpu_prefill(c, gate=True)
