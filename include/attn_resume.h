@@ -26,7 +26,7 @@
  * Cache layout: a pool of sequence slots, slot s at k_cache + s * slot_stride (elements), each
  * [cap][H_kv][d] row-major: token-major, so that the restored prefix of a request is ONE
  * contiguous range per tensor.  k and v pools have the same geometry (both 16-bit elements); one
- * slot holds less than 2 GiB per tensor (cap * H_kv * d * 2 bytes).
+ * slot holds less than 2 GiB per tensor ((cap + 128) * H_kv * d * 2 bytes < 2^31).
  */
 #ifndef ATTN_RESUME_H
 #define ATTN_RESUME_H

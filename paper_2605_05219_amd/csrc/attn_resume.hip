@@ -32,7 +32,8 @@ int32_t check_pool(const attn_shape* s, int64_t slot_stride, int32_t n_slots, in
     if (n_slots < 0 || cap < 0) return GDN_ERR_COUNT;
     if (slot_stride < 0 || slot_stride % 8 != 0) return GDN_ERR_ALIGN;
     if (slot_stride < (int64_t)cap * s->H_kv * s->d) return GDN_ERR_SHAPE;   // slots would overlap
-    if ((int64_t)cap * s->H_kv * s->d * 2 > INT32_MAX) return GDN_ERR_SHAPE;   // a slot is addressed with 32-bit byte offsets
+    // a slot is addressed with 32-bit byte offsets, which may run up to two key tiles past its last row
+    if (((int64_t)cap + 2 * ATT_KT) * s->H_kv * s->d * 2 > INT32_MAX) return GDN_ERR_SHAPE;
     return GDN_OK;
 }
 
