@@ -2,7 +2,7 @@
  * attn_resume — the attention layers' side of a cache hit, for one MI355X (gfx950).  Same
  * library and conventions as gdn_resume.h (host / device pointers named per argument, validation
  * before anything is enqueued, negative error codes, no allocation, no stream synchronisation
- * except the wait for the previous call's plan upload).
+ * except the wait for an earlier call's plan upload to leave its pinned staging buffer).
  *
  * Why it belongs to the path: the paper's hybrid runs keep the full attention KV cache beside
  * the sparse recurrent checkpoints (Table 1, caption), count the load of the cached keys and values as

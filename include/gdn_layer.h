@@ -2,7 +2,7 @@
  * gdn_layer — the elementwise front and back ends of a GatedDeltaNet layer around the resumed
  * recurrence of gdn_resume.h, for one MI355X (gfx950).  Same library, same conventions (host /
  * device pointers, validation before anything is enqueued, negative error codes, no
- * allocation, no stream synchronisation except the wait for the previous call's plan upload).
+ * allocation, no stream synchronisation except the wait for an earlier call's plan upload).
  *
  * Why it belongs to the path: the paper's method applies to layers whose hidden state can be
  * taken out and put back without loss (Sec. 1), and it times a layer group with GatedDeltaNet

@@ -19,8 +19,9 @@
  *     are HIP device memory owned by the caller and must stay valid until the work enqueued
  *     on `stream` has finished.  `stream` is a hipStream_t passed as void* (NULL = default).
  *   - No entry point allocates or frees device memory and none synchronises the stream,
- *     except that gdn_resume_prefill may wait (on the host) for its previous call's plan
- *     upload to leave a small pinned staging buffer the library owns.
+ *     except that a call which uploads index arrays may wait (on the host) for the upload of
+ *     the call eight such calls back to leave its pinned staging buffer (the library owns a
+ *     ring of eight).
  *   - Every argument is validated on the host before anything is enqueued; on error nothing
  *     is enqueued and a negative code is returned.  HIP failures return GDN_ERR_HIP - hipError.
  *   - The library is written for one GPU per process (kernel attributes and the device's size

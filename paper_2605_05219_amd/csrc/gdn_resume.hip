@@ -98,27 +98,35 @@ int32_t launch_copy(const float* from, float* to, int64_t from_stride, int64_t t
 }
 
 // ------------------------------------------------------------------ plan staging (pinned host memory)
+// A ring of pinned buffers, each with the event of its last upload: a call waits (on the host) only when the
+// ring has gone round and the upload that used its buffer PLAN_RING calls ago has not left it yet, so
+// back-to-back short calls do not stall the host on one another.
+constexpr int PLAN_RING = 8;
 struct Staging {
     std::mutex mu;
-    void* host = nullptr;
-    size_t bytes = 0;
-    hipEvent_t done = nullptr;
-    bool pending = false;
+    struct Slot {
+        void* host = nullptr;
+        size_t bytes = 0;
+        hipEvent_t done = nullptr;
+        bool pending = false;
+    } slot[PLAN_RING];
+    int next = 0;
 };
 Staging g_staging;
 
 }  // namespace
 
 // Copies `bytes` from `src` into pinned memory and enqueues its upload to `dst` (declared in gdn_host.h:
-// the layer front end uploads its index arrays the same way).
+// the layer front end and the attention side upload their index arrays the same way).
 int32_t upload_plan(const void* src, size_t bytes, void* dst, hipStream_t stream) {
     std::lock_guard<std::mutex> lock(g_staging.mu);
-    Staging& s = g_staging;
+    Staging::Slot& s = g_staging.slot[g_staging.next];
+    g_staging.next = (g_staging.next + 1) % PLAN_RING;
     if (!s.done) {
         const hipError_t e = hipEventCreateWithFlags(&s.done, hipEventDisableTiming);
         if (e != hipSuccess) return hip_err(e);
     }
-    if (s.pending) {  // the previous upload must have left the buffer
+    if (s.pending) {  // the upload that last used this buffer must have left it
         const hipError_t e = hipEventSynchronize(s.done);
         if (e != hipSuccess) return hip_err(e);
         s.pending = false;
