@@ -4,7 +4,7 @@
 //
 // Attention kernel.  One workgroup of four waves owns ATT_BQ = 128 consecutive suffix tokens of
 // one (request, query head); wave w owns 32 of them, one per lane column.  Key/value rows are
-// walked in tiles of ATT_KT = 64, each tile brought into one of two LDS stages by 16-byte
+// walked in tiles of 64 (32 at d = 256), each tile brought into one of two LDS stages by 16-byte
 // buffer loads to LDS (no registers) while the waves compute on the other stage.
 //
 // Both contractions are computed transposed, so that a query is a COLUMN of every accumulator
@@ -49,8 +49,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int ATT_BQ = 128;       // suffix tokens per workgroup
-constexpr int ATT_KT = 64;        // key/value rows per tile (a multiple of 32)
-constexpr int ATT_KVB = ATT_KT / 32;   // 32-row accumulator tiles of S^T per key tile
+// key/value rows per tile (a multiple of 32): 64, and 32 at d = 256, where the shorter tile brings the
+// kernel under 256 registers and two workgroups onto a compute unit
+__host__ __device__ constexpr int att_kt(int d) { return d == 256 ? 32 : 64; }
 constexpr int ATT_THREADS = 256;
 constexpr int APPEND_THREADS = 256;
 
@@ -147,7 +148,8 @@ template <int D>
 struct AttnSmem {
     static constexpr int CPR = D / 8;                     // 16-byte chunks per row
     static constexpr int ROW_BYTES = D * 2;
-    static constexpr int TILE_BYTES = ATT_KT * ROW_BYTES;
+    static constexpr int KT = att_kt(D);                  // key/value rows per tile
+    static constexpr int TILE_BYTES = KT * ROW_BYTES;
     static constexpr int K_OFF = 0, V_OFF = TILE_BYTES;
     static constexpr int STAGE_BYTES = 2 * TILE_BYTES;
     static constexpr int BYTES = 2 * STAGE_BYTES;
@@ -160,11 +162,13 @@ struct AttnSmem {
 };
 
 template <int D, typename OT>
-__global__ void __launch_bounds__(ATT_THREADS, D == 256 ? 1 : 2) attn_suffix_kernel(AttnArgs a) {
+__global__ void __launch_bounds__(ATT_THREADS, 2) attn_suffix_kernel(AttnArgs a) {
     typedef AttnSmem<D> SM;
     constexpr int CPR = SM::CPR;
     constexpr int KB = D / 16;      // contraction steps of S^T
     constexpr int RB = D / 32;      // row tiles of O^T
+    constexpr int ATT_KT = SM::KT;
+    constexpr int ATT_KVB = ATT_KT / 32;   // 32-row accumulator tiles of S^T per key tile
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int lane = threadIdx.x & 63;

@@ -33,7 +33,7 @@ int32_t check_pool(const attn_shape* s, int64_t slot_stride, int32_t n_slots, in
     if (slot_stride < 0 || slot_stride % 8 != 0) return GDN_ERR_ALIGN;
     if (slot_stride < (int64_t)cap * s->H_kv * s->d) return GDN_ERR_SHAPE;   // slots would overlap
     // a slot is addressed with 32-bit byte offsets, which may run up to two key tiles past its last row
-    if (((int64_t)cap + 2 * ATT_KT) * s->H_kv * s->d * 2 > INT32_MAX) return GDN_ERR_SHAPE;
+    if (((int64_t)cap + 128) * s->H_kv * s->d * 2 > INT32_MAX) return GDN_ERR_SHAPE;
     return GDN_OK;
 }
 
@@ -51,10 +51,10 @@ int32_t check_slots(const int32_t* ids, int32_t n, int32_t n_slots, bool skip_em
 }
 
 // Splitting the key walk: calls with fewer than SPLIT_BELOW workgroups cut the walks of their pieces
-// into parts of at least SPLIT_MIN_TILES key tiles, aiming at SPLIT_BELOW workgroups in all; the
+// into parts of at least SPLIT_MIN_KEYS keys (whole tiles), aiming at SPLIT_BELOW workgroups in all; the
 // partial results of at most SPLIT_MAX_WGS (part, head) pairs live in the workspace.
 constexpr int SPLIT_BELOW = 512;       // two workgroups per compute unit
-constexpr int SPLIT_MIN_TILES = 512 / ATT_KT;   // 512 keys
+constexpr int SPLIT_MIN_KEYS = 512;
 constexpr int SPLIT_MAX_WGS = 768;
 
 // ints of the uploaded index arrays: cu (n_req+1), start, slot (n_req each), five per unit, four per split piece
@@ -205,13 +205,14 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     if (!workspace || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(s, n_req, T)) return GDN_ERR_WORKSPACE;
 
     // ---- pieces: one per 128 suffix tokens of a request
+    const int KT = att_kt(s->d);
     struct Piece { int32_t req, tile, n_tiles, parts; };
     std::vector<Piece> pieces;
     int64_t total_tiles = 0;
     for (int32_t r = 0; r < n_req; ++r)
         for (int32_t t = 0; t * ATT_BQ < len[r]; ++t) {
             const int32_t kv = start_pos[r] + std::min((t + 1) * ATT_BQ, len[r]);
-            pieces.push_back({r, t, (kv + ATT_KT - 1) / ATT_KT, 1});
+            pieces.push_back({r, t, (kv + KT - 1) / KT, 1});
             total_tiles += pieces.back().n_tiles;
         }
     const int64_t n_items = (int64_t)pieces.size();
@@ -219,7 +220,7 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     int64_t split_wgs = 0;
     const char* no_split = std::getenv("ATTN_NO_SPLIT");
     if (n_items * s->H_q < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
-        int64_t tp = std::max<int64_t>(SPLIT_MIN_TILES, (total_tiles * s->H_q + SPLIT_BELOW - 1) / SPLIT_BELOW);
+        int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * s->H_q + SPLIT_BELOW - 1) / SPLIT_BELOW);
         for (;; tp *= 2) {
             split_wgs = 0;
             for (Piece& p : pieces) {
