@@ -176,6 +176,7 @@ CASES = [
     (16, 2, 128, [700], [1500]),                             # the grouping of the measured model family, 8 query heads per kv head
     (8, 8, 128, [128, 256, 127, 0, 65], [0, 64, 1, 9, 63]),  # exact tiles, an empty request, starts off the tile grid
     (2, 1, 64, [3, 2, 1, 4] * 16, [0, 1, 2, 70] * 16),       # many short requests
+    (8, 4, 64, [70, 130], [33, 0]),                          # four key/value heads: two XCDs each in the block order
 ]
 
 
