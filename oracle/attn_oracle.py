@@ -1,6 +1,6 @@
 """Oracle of the attention layers' side of a cache hit.  TEST INFRASTRUCTURE ONLY.
 
-Only tests/ may import this module.  Plain numpy, fp64, the definition written out per head with
+Only tests/ and the smoke entry point may import this module.  Plain numpy, fp64, the definition per head with
 a library matmul as the only primitive; it shares no code with the library.
 
 The paper's hybrid runs keep the full attention KV cache next to the sparse recurrent checkpoints
