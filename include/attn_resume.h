@@ -88,7 +88,9 @@ int32_t attn_kv_spill(const attn_shape *shape, int32_t n_req, const int32_t *n_r
  * every suffix token over positions 1 .. its own (two launches on `stream`; three when the call
  * is small enough for key walks of 1024 keys and more to be split over workgroups, after which a
  * merge pass writes o).  Results do not depend on the batch a request is packed with as long as
- * its walk is not split.  Environment: ATTN_NO_SPLIT=1 (read at every call) keeps every walk whole.
+ * its walk is not split.  Environment (read at every call): ATTN_NO_SPLIT=1 keeps every walk whole;
+ * ATTN_NO_PACK=1 keeps one query head per workgroup also where suffixes are short (otherwise the
+ * heads of a key/value group then share a workgroup's rows; results are bitwise the same either way).
  *   q            device, bf16, [T][H_q][d] (T = cu_seqlens[n_req]);  k_new, v_new: [T][H_kv][d]
  *   out_gate     device, bf16, [T][H_q][d], or NULL (no gate)
  *   cu_seqlens   host, n_req + 1;  start_pos: host, n_req, the restored prefix length c >= 0

@@ -22,6 +22,11 @@
 //                                            (lane i of a group of 16 receives element i%4 of the
 //                                            8-byte rows addressed by lanes i/4, i/4+4, i/4+8,
 //                                            i/4+12 of the group).
+// Calls whose suffixes are short against the 128 rows of a workgroup pack the query heads of a key/value group
+// into the rows instead (row = token * G + head of the group, 128 / G tokens per workgroup): the rows of a
+// workgroup then all share one key/value head anyway, and a 16-token suffix fills the rows that 16 tokens of one
+// head would leave empty.  Nothing else changes: a row's arithmetic does not depend on which lane carries it.
+//
 // A call with too few (request, head, 128-token) pieces to fill the chip splits the key walk of a
 // piece into parts of whole tiles: each part is a workgroup that leaves its unnormalised O, running
 // maximum and normaliser in a workspace slot, and a second kernel merges the parts of a piece.
@@ -75,6 +80,7 @@ struct AttnArgs {
     int32_t n_units;
     int32_t H_q, H_kv;
     int32_t xcd_split;        // 1: blocks are dealt to the 8 XCDs by key/value head
+    int32_t pack;             // query heads per token in a workgroup's rows: 1, or H_q / H_kv (a divisor of 128)
     float scale_log2e;        // scale * log2(e)
 };
 
@@ -176,36 +182,42 @@ __global__ void __launch_bounds__(ATT_THREADS, 2) attn_suffix_kernel(AttnArgs a)
     const int col = lane & 31;      // query column of this lane
     const int g = lane >> 5;        // half-wave
 
-    // ---- which (item, query head)
-    int item, hq;
-    {
-        const int G = a.H_q / a.H_kv;
-        if (a.xcd_split) {
-            const int X = 8 / a.H_kv;                 // XCDs per key/value head
-            const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
-            const int kvh = xcd % a.H_kv, sub = xcd / a.H_kv;
-            const int64_t e = (int64_t)k * X + sub;
-            if (e >= (int64_t)a.n_units * G) return;
-            item = (int)(e / G);
-            hq = kvh * G + (int)(e % G);
-        } else {
-            item = blockIdx.x / a.H_q;
-            hq = blockIdx.x % a.H_q;
-        }
+    // ---- which (unit, head block): a head block is one query head, or with packed rows the heads of one group
+    const int R = a.pack;                 // query heads per token in this workgroup's rows
+    const int per = a.H_q / a.H_kv / R;   // head blocks per key/value head: the group size, or 1
+    int item, hb;
+    if (a.xcd_split) {
+        const int X = 8 / a.H_kv;                 // XCDs per key/value head
+        const int xcd = blockIdx.x & 7, k = blockIdx.x >> 3;
+        const int sub = xcd / a.H_kv;
+        const int64_t e = (int64_t)k * X + sub;
+        if (e >= (int64_t)a.n_units * per) return;
+        item = (int)(e / per);
+        hb = (xcd % a.H_kv) * per + (int)(e % per);
+    } else {
+        const int HB = a.H_q / R;
+        item = blockIdx.x / HB;
+        hb = blockIdx.x % HB;
     }
-    const int kvh = hq / (a.H_q / a.H_kv);
+    const int kvh = hb / per;
+    const int TPW = ATT_BQ / R;           // tokens per workgroup
+    const int wrow = 32 * wave + col;     // this lane's row of the workgroup: token wrow / R, head hb * R + wrow % R
+    const int tl = wrow / R;
+    const int hq = hb * R + (wrow - tl * R);
     const int r = a.unit_req[item];
-    const int q0 = a.unit_tile[item] * ATT_BQ;
+    const int q0 = a.unit_tile[item] * TPW;
     const int t0 = a.unit_t0[item], t1 = a.unit_t1[item];  // key tiles [t0, t1) of this unit
     const int part = a.unit_part[item];
     const int tok0 = a.cu[r];
     const int n = a.cu[r + 1] - tok0;
     const int c0 = a.start[r];
-    const int q_end = min(q0 + ATT_BQ, n);                 // valid suffix rows of this workgroup: [q0, q_end)
+    const int q_end = min(q0 + TPW, n);                    // suffix tokens of this workgroup: [q0, q_end)
     const int kv_len = c0 + q_end;                         // key rows any of them may see
-    const int wq0 = q0 + 32 * wave;                        // first row of this wave
-    const int n_tiles_w = wq0 < q_end ? (c0 + min(wq0 + 32, q_end) + ATT_KT - 1) / ATT_KT : 0;   // tiles this wave can see
-    const int qrow = min(wq0 + col, q_end - 1);            // clamped: lanes past the end repeat the last row
+    const int wq0 = q0 + (32 * wave) / R;                  // first token of this wave
+    const int wq1 = min(q0 + (32 * wave + 31) / R + 1, q_end);   // one past its last
+    const int n_tiles_w = wq0 < q_end ? (c0 + wq1 + ATT_KT - 1) / ATT_KT : 0;   // tiles this wave can see
+    const bool valid = q0 + tl < q_end;                    // this lane's row is a token of the request
+    const int qrow = min(q0 + tl, q_end - 1);              // clamped: lanes past the end repeat the last token
     const int lim = c0 + qrow;                             // last visible key row (0-based) of this lane's query
 
     // ---- tile loader: wave w brings pieces [w*PPW, (w+1)*PPW) of the key and of the value tile, one 16-byte
@@ -369,8 +381,8 @@ __global__ void __launch_bounds__(ATT_THREADS, 2) attn_suffix_kernel(AttnArgs a)
     wait_vmcnt<0>();                           // no load to LDS may be in flight when the workgroup's LDS is given back
     // ---- a part of a split walk leaves its unnormalised result in its workspace slot
     if (part >= 0) {
-        if (wq0 + col < q_end) {
-            const int64_t prow = ((int64_t)part * a.H_q + hq) * ATT_BQ + 32 * wave + col;
+        if (valid) {
+            const int64_t prow = ((int64_t)part * (a.H_q / R) + hb) * ATT_BQ + wrow;
             const float lt = sum_with_other_half(l);
             if (g == 0) *reinterpret_cast<f32x2*>(a.part_ml + prow * 2) = f32x2{m, lt};
 #pragma unroll
@@ -383,9 +395,9 @@ __global__ void __launch_bounds__(ATT_THREADS, 2) attn_suffix_kernel(AttnArgs a)
         return;
     }
     // ---- normalise, gate, store: register 4b+e of tile rb is value column 32*rb + 8*b + 4*g + e
-    if (wq0 + col < q_end) {
+    if (valid) {
         const float inv = 1.f / sum_with_other_half(l);
-        const int64_t base = ((int64_t)(tok0 + wq0 + col) * a.H_q + hq) * D;
+        const int64_t base = ((int64_t)(tok0 + q0 + tl) * a.H_q + hq) * D;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -422,6 +434,7 @@ struct CombineArgs {
     const int32_t* piece_base;  // first workspace slot of the piece
     const int32_t* piece_parts; // its number of parts (consecutive slots)
     int32_t H_q;
+    int32_t pack;               // as in AttnArgs
     float scale_log2e;
 };
 
@@ -439,18 +452,20 @@ template <int D, typename OT>
 __global__ void __launch_bounds__(ATT_THREADS) attn_combine_kernel(CombineArgs a) {
     constexpr int CH = CombineShape<D>::CH, SUBS = CombineShape<D>::SUBS;
     const int ph = blockIdx.x / SUBS, sub = blockIdx.x % SUBS;
-    const int piece = ph / a.H_q, hq = ph % a.H_q;
+    const int R = a.pack, HB = a.H_q / R, TPW = ATT_BQ / R;
+    const int piece = ph / HB, hb = ph % HB;
     const int r = a.piece_req[piece];
-    const int q0 = a.piece_tile[piece] * ATT_BQ;
+    const int q0 = a.piece_tile[piece] * TPW;
     const int tok0 = a.cu[r];
-    const int rows = min(ATT_BQ, a.cu[r + 1] - tok0 - q0);
+    const int rows = min(TPW, a.cu[r + 1] - tok0 - q0) * R;
     const int base = a.piece_base[piece], P = a.piece_parts[piece];
     {
         const int idx = sub * ATT_THREADS + threadIdx.x;
         const int row = idx / CH, ch = idx - row * CH;
         if (row >= rows) return;
-        const int64_t prow0 = ((int64_t)base * a.H_q + hq) * ATT_BQ + row;
-        const int64_t pstep = (int64_t)a.H_q * ATT_BQ;                // rows between consecutive parts
+        const int64_t prow0 = ((int64_t)base * HB + hb) * ATT_BQ + row;
+        const int64_t pstep = (int64_t)HB * ATT_BQ;                   // rows between consecutive parts
+        const int tl = row / R, hq = hb * R + (row - tl * R);
         float M = -INFINITY;
 #pragma unroll 4
         for (int p = 0; p < P; ++p) M = fmaxf(M, a.part_ml[(prow0 + p * pstep) * 2]);   // finite: part 0 sees key row 0
@@ -467,7 +482,7 @@ __global__ void __launch_bounds__(ATT_THREADS) attn_combine_kernel(CombineArgs a
         }
         const float inv = 1.f / L;
         f32x4 y = {acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv};
-        const int64_t at = ((int64_t)(tok0 + q0 + row) * a.H_q + hq) * D + 4 * ch;
+        const int64_t at = ((int64_t)(tok0 + q0 + tl) * a.H_q + hq) * D + 4 * ch;
         if (a.gate) {
             const u32x2 gb = *reinterpret_cast<const u32x2*>(a.gate + at);
             const float g0 = __builtin_bit_cast(float, gb[0] << 16), g1 = __builtin_bit_cast(float, gb[0] & 0xffff0000u);

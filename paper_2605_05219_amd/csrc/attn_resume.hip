@@ -58,12 +58,15 @@ constexpr int SPLIT_MIN_KEYS = 512;
 constexpr int SPLIT_MAX_WGS = 768;
 
 // ints of the uploaded index arrays: cu (n_req+1), start, slot (n_req each), five per unit, four per split piece
-inline int64_t max_items(int32_t n_req, int64_t T) { return T / ATT_BQ + n_req; }
-inline int64_t max_units(int32_t n_req, int64_t T) { return max_items(n_req, T) + SPLIT_MAX_WGS; }
-inline int64_t plan_ints(int32_t n_req, int64_t T) {
-    return 3 * (int64_t)n_req + 1 + 5 * max_units(n_req, T) + 4 * max_items(n_req, T);
+// (with packed rows a piece is 128 / G tokens, G the heads per key/value head: at most G times as many pieces)
+inline int64_t max_items(int32_t n_req, int64_t T, int G) { return T * G / ATT_BQ + n_req; }
+inline int64_t max_units(int32_t n_req, int64_t T, int G) { return max_items(n_req, T, G) + SPLIT_MAX_WGS; }
+inline int64_t plan_ints(int32_t n_req, int64_t T, int G) {
+    return 3 * (int64_t)n_req + 1 + 5 * max_units(n_req, T, G) + 4 * max_items(n_req, T, G);
 }
-inline int64_t plan_bytes(int32_t n_req, int64_t T) { return (plan_ints(n_req, T) * (int64_t)sizeof(int32_t) + 255) / 256 * 256; }
+inline int64_t plan_bytes(int32_t n_req, int64_t T, int G) {
+    return (plan_ints(n_req, T, G) * (int64_t)sizeof(int32_t) + 255) / 256 * 256;
+}
 inline int64_t part_ml_bytes() { return (int64_t)SPLIT_MAX_WGS * ATT_BQ * 2 * sizeof(float); }
 inline int64_t part_o_bytes(int d) { return (int64_t)SPLIT_MAX_WGS * ATT_BQ * d * sizeof(float); }
 
@@ -110,7 +113,7 @@ int64_t attn_workspace_bytes(const attn_shape* s, int32_t n_req, int64_t total_t
     const int32_t rc = check_shape(s);
     if (rc != GDN_OK) return rc;
     if (n_req < 0 || total_tokens < 0) return GDN_ERR_COUNT;
-    return plan_bytes(n_req, total_tokens) + part_ml_bytes() + part_o_bytes(s->d);
+    return plan_bytes(n_req, total_tokens, s->H_q / s->H_kv) + part_ml_bytes() + part_o_bytes(s->d);
 }
 
 // shared by attn_kv_restore and attn_kv_spill: rows [0, n_rows[r]) of one pool's slot to the other's
@@ -204,14 +207,29 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
         return GDN_ERR_ALIGN;
     if (!workspace || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(s, n_req, T)) return GDN_ERR_WORKSPACE;
 
-    // ---- pieces: one per 128 suffix tokens of a request
+    // ---- rows of a workgroup: 128 tokens of one query head, or, where that would leave at least a fifth of all
+    // rows empty (short suffixes), 128 / G tokens of the G heads of a key/value group
     const int KT = att_kt(s->d);
+    const int G = s->H_q / s->H_kv;
+    int pack = 1;
+    if (G > 1 && ATT_BQ % G == 0) {
+        int64_t rows_plain = 0, rows_packed = 0;
+        for (int32_t r = 0; r < n_req; ++r) {
+            rows_plain += (int64_t)((len[r] + ATT_BQ - 1) / ATT_BQ) * s->H_q;
+            rows_packed += (int64_t)((len[r] + ATT_BQ / G - 1) / (ATT_BQ / G)) * s->H_kv;
+        }
+        const char* no_pack = std::getenv("ATTN_NO_PACK");
+        if (rows_packed * 5 <= rows_plain * 4 && !(no_pack && no_pack[0] == '1')) pack = G;
+    }
+    const int TPW = ATT_BQ / pack;        // tokens per workgroup
+    const int HB = s->H_q / pack;         // head blocks (workgroups) per unit
+    // ---- pieces: one per TPW suffix tokens of a request
     struct Piece { int32_t req, tile, n_tiles, parts; };
     std::vector<Piece> pieces;
     int64_t total_tiles = 0;
     for (int32_t r = 0; r < n_req; ++r)
-        for (int32_t t = 0; t * ATT_BQ < len[r]; ++t) {
-            const int32_t kv = start_pos[r] + std::min((t + 1) * ATT_BQ, len[r]);
+        for (int32_t t = 0; t * TPW < len[r]; ++t) {
+            const int32_t kv = start_pos[r] + std::min((t + 1) * TPW, len[r]);
             pieces.push_back({r, t, (kv + KT - 1) / KT, 1});
             total_tiles += pieces.back().n_tiles;
         }
@@ -219,13 +237,13 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     // ---- too few workgroups for the chip: cut long key walks into parts
     int64_t split_wgs = 0;
     const char* no_split = std::getenv("ATTN_NO_SPLIT");
-    if (n_items * s->H_q < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
-        int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * s->H_q + SPLIT_BELOW - 1) / SPLIT_BELOW);
+    if (n_items * HB < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
+        int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * HB + SPLIT_BELOW - 1) / SPLIT_BELOW);
         for (;; tp *= 2) {
             split_wgs = 0;
             for (Piece& p : pieces) {
                 p.parts = p.n_tiles >= 2 * tp ? (int32_t)((p.n_tiles + tp - 1) / tp) : 1;
-                if (p.parts > 1) split_wgs += (int64_t)p.parts * s->H_q;
+                if (p.parts > 1) split_wgs += (int64_t)p.parts * HB;
             }
             if (split_wgs <= SPLIT_MAX_WGS) break;
         }
@@ -248,24 +266,25 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     std::stable_sort(units.begin(), units.end(), [](const Unit& x, const Unit& y) { return x.t1 - x.t0 > y.t1 - y.t0; });
     const int64_t n_units = (int64_t)units.size();
     const int64_t n_pieces = (int64_t)piece_req.size();
-    const int G = s->H_q / s->H_kv;
     const bool xcd_split = 8 % s->H_kv == 0;
     int64_t blocks;
     if (xcd_split) {
         const int X = 8 / s->H_kv;
-        blocks = 8 * ((n_units * G + X - 1) / X);
+        blocks = 8 * ((n_units * (G / pack) + X - 1) / X);
     } else {
-        blocks = n_units * s->H_q;
+        blocks = n_units * HB;
     }
     if (blocks > INT32_MAX) return GDN_ERR_COUNT;
 
-    const int64_t MU = max_units(n_req, T), MI = max_items(n_req, T);
-    std::vector<int32_t> img((size_t)plan_ints(n_req, T), 0);
+    // the uploaded image is packed to what this call uses (the workspace is sized for the most a call can need):
+    // a copy of a few hundred bytes takes the runtime's short path, one of 16 KiB and more does not
+    const int64_t MU = n_units, MI = n_pieces;
+    std::vector<int32_t> img((size_t)(3 * (int64_t)n_req + 1 + 5 * MU + 4 * MI), 0);
     int32_t* p_cu = img.data();
     int32_t* p_start = p_cu + n_req + 1;
     int32_t* p_slot = p_start + n_req;
-    int32_t* p_unit = p_slot + n_req;          // five arrays of MU
-    int32_t* p_piece = p_unit + 5 * MU;        // four arrays of MI
+    int32_t* p_unit = p_slot + n_req;          // five arrays of n_units
+    int32_t* p_piece = p_unit + 5 * MU;        // four arrays of n_pieces
     std::memcpy(p_cu, cu_seqlens, sizeof(int32_t) * (n_req + 1));
     std::memcpy(p_start, start_pos, sizeof(int32_t) * n_req);
     std::memcpy(p_slot, seq_slot, sizeof(int32_t) * n_req);
@@ -318,13 +337,14 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     a.unit_t0 = a.unit_req + 2 * MU;
     a.unit_t1 = a.unit_req + 3 * MU;
     a.unit_part = a.unit_req + 4 * MU;
-    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T));
-    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T) + part_ml_bytes());
+    a.part_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T, G));
+    a.part_o = reinterpret_cast<float*>(static_cast<char*>(workspace) + plan_bytes(n_req, T, G) + part_ml_bytes());
     a.slot_stride = slot_stride;
     a.n_units = (int32_t)n_units;
     a.H_q = s->H_q;
     a.H_kv = s->H_kv;
     a.xcd_split = xcd_split ? 1 : 0;
+    a.pack = pack;
     a.scale_log2e = s->scale * 1.4426950408889634f;
     e = s->o_dtype == GDN_F32 ? launch_attn_d<float>(s->d, a, (unsigned)blocks, stream)
                               : launch_attn_d<uint16_t>(s->d, a, (unsigned)blocks, stream);
@@ -341,9 +361,10 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
     ca.piece_base = ca.piece_req + 2 * MI;
     ca.piece_parts = ca.piece_req + 3 * MI;
     ca.H_q = s->H_q;
+    ca.pack = pack;
     ca.scale_log2e = a.scale_log2e;
-    e = s->o_dtype == GDN_F32 ? launch_combine_d<float>(s->d, ca, (unsigned)(n_pieces * s->H_q), stream)
-                              : launch_combine_d<uint16_t>(s->d, ca, (unsigned)(n_pieces * s->H_q), stream);
+    e = s->o_dtype == GDN_F32 ? launch_combine_d<float>(s->d, ca, (unsigned)(n_pieces * HB), stream)
+                              : launch_combine_d<uint16_t>(s->d, ca, (unsigned)(n_pieces * HB), stream);
     return hip_err(e);
 }
 

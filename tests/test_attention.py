@@ -230,6 +230,25 @@ def test_split_key_walks_agree_with_whole_walks(monkeypatch):
 
 
 @pytest.mark.gpu
+def test_rows_packed_by_head_group_give_bitwise_the_unpacked_result(monkeypatch):
+    """Short suffixes put the query heads of a key/value group into one workgroup's rows; a row's arithmetic does not
+    depend on the lane that carries it, so the outputs equal the one-head-per-workgroup run bit for bit (walks under
+    1024 keys, so neither run splits them), and a packed call with split walks still matches the oracle."""
+    for seed, H_q, H_kv, d, lens, starts in [(3600, 8, 2, 128, [5, 40, 1, 33], [100, 300, 700, 0]), (3601, 16, 2, 64, [17, 64], [900, 13]),
+                                             (3602, 4, 1, 256, [31, 2], [64, 500])]:
+        c = wl.attn_case(seed, H_q, H_kv, d, lens, starts)
+        monkeypatch.setenv("ATTN_NO_PACK", "1")
+        plain, k1, v1 = gpu_prefill(c, gate=True)
+        monkeypatch.delenv("ATTN_NO_PACK")
+        packed, k2, v2 = gpu_prefill(c, gate=True)
+        assert np.array_equal(plain, packed) and np.array_equal(k1, k2) and np.array_equal(v1, v2)
+        check_o(packed, oracle_o(c, d ** -0.5, True), "f32")
+    c = wl.attn_case(3603, 16, 2, 128, [64, 3], [5000, 2100])          # packed rows and split walks together
+    got, _, _ = gpu_prefill(c, "bf16", True)
+    check_o(got, oracle_o(c, 128 ** -0.5, True), "bf16")
+
+
+@pytest.mark.gpu
 def test_resuming_at_c_reproduces_the_full_prefill_bit_for_bit():
     """Exact reuse on the attention side: the rows after c of a prefill from 0 equal a call resumed at c over the
     restored prefix, bitwise (key tiles sit on an absolute grid, so every query sees the same arithmetic)."""
