@@ -53,7 +53,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int ATT_BQ = 128;       // suffix tokens per workgroup
+constexpr int ATT_BQ = 128;       // rows (query columns of the accumulators) per workgroup
 // key/value rows per tile (a multiple of 32): 64, and 32 at d = 256, where the shorter tile brings the
 // kernel under 256 registers and two workgroups onto a compute unit
 __host__ __device__ constexpr int att_kt(int d) { return d == 256 ? 32 : 64; }

@@ -324,3 +324,12 @@ def test_headers_are_plain_c_and_a_c_program_can_call_the_library(tmp_path):
     subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
                            str(src), "-o", str(exe), "-L", pkg, "-lgdn_resume", "-Wl,-rpath," + pkg])
     assert subprocess.run([str(exe)], capture_output=True, text=True).stdout.strip() == "ok"
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    """bench.py --gpus N with N above 1 exits at once with a message that says why (nothing touches a GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode == 2 and res.stdout == "" and "ONE GPU" in res.stderr
