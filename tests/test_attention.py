@@ -196,6 +196,32 @@ def test_suffix_attention_matches_the_oracle_and_appends_the_suffix(case_i, o_dt
 
 
 @pytest.mark.gpu
+def test_seeded_random_shapes_match_the_oracle():
+    """Head groupings (also ones that cannot be packed or dealt to the XCDs), head sizes, request counts, lengths and
+    starts drawn from a seeded generator: packed and plain rows, whole and split walks, ragged tiles in combinations the
+    hand-picked cases do not list."""
+    rng = np.random.default_rng(12345)
+    heads = [(4, 2), (8, 1), (16, 2), (6, 3), (8, 8), (2, 2), (32, 4), (12, 4)]
+    for it in range(24):
+        H_q, H_kv = heads[rng.integers(len(heads))]
+        d = int(rng.choice([64, 128, 256]))
+        n_req = int(rng.integers(1, 7))
+        lens = [int(x) for x in (rng.integers(0, 40, n_req) if it % 3 == 0 else rng.integers(0, 300, n_req) if it % 3 == 1
+                                 else rng.choice([1, 16, 64, 127, 128, 129, 200], n_req))]
+        starts = [int(x) for x in rng.choice([0, 1, 63, 64, 65, 500, 1023, 1024, 2500], n_req)]
+        if sum(lens) == 0:
+            lens[0] = 3
+        o_dtype, gate = ("f32", False) if it % 2 == 0 else ("bf16", True)
+        c = wl.attn_case(9000 + it, H_q, H_kv, d, lens, starts)
+        got, k_after, v_after = gpu_prefill(c, o_dtype, gate)
+        check_o(got, oracle_o(c, d ** -0.5, gate), o_dtype, f"case {it} {(H_q, H_kv, d, lens, starts)}")
+        k_want, v_want = pools_with_prefix(c)
+        for r, s in enumerate(c.seq_slot):
+            k_want[s, :len(c.k_full[r])], v_want[s, :len(c.v_full[r])] = c.k_full[r], v_bits(c.v_full[r])
+        assert np.array_equal(k_after, k_want) and np.array_equal(v_after, v_want), it
+
+
+@pytest.mark.gpu
 def test_peaked_and_flat_logits_stay_within_tolerance():
     """Widely spread logits (a few keys carry the weight; the running maximum moves often) and all-equal logits
     (every weight is exactly 1: the result is the running mean of the values to fp32 accuracy)."""
