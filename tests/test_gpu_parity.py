@@ -537,6 +537,37 @@ def test_prefill_from_host_pool_equals_prefill_from_device_pool(n_req, pinned):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("many", [False, True])
+def test_seeded_random_calls_match_the_oracle(many):
+    """Shapes, request counts, lengths (also empty), start positions, source slots and emit positions drawn from a seeded
+    generator, with random start states: combinations the hand-picked cases do not list; `many` draws 5 to 21 requests of
+    the 16-head shapes, i.e. 80 to 336 chains, across the boundaries between the kernel variants."""
+    rng = np.random.default_rng(4242 if many else 777)
+    shapes = [(1, 2, 2, 64), (1, 2, 4, 128), (2, 1, 2, 64), (1, 4, 4, 128), (1, 16, 16, 128), (3, 2, 2, 128), (1, 8, 16, 128)]
+    for it in range(16):
+        L, H_qk, H_v, d = shapes[rng.integers(len(shapes))]
+        dtype = "bf16" if (it % 4 or d != 64) else "f32"
+        big = H_v * L >= 16
+        n_req = int(rng.integers(5, 22)) if (many and big) else int(rng.integers(1, 5 if big else 40))
+        lens = [int(x) for x in (rng.integers(0, 200, n_req) if (it % 2 or many) else rng.integers(0, 500 if big else 900, n_req))]
+        if sum(lens) == 0:
+            lens[0] = 5
+        starts = [int(x) for x in rng.choice([0, 0, 64, 100, 512, 1000], n_req)]
+        n_src, nxt = 3, 3
+        emits, eslots = [], []
+        for s0, ln in zip(starts, lens):
+            e = sorted(set(int(x) for x in rng.integers(s0 + 1, s0 + ln + 1, int(rng.integers(0, 4))))) if ln > 0 else []
+            emits.append(e)
+            eslots.append(list(range(nxt, nxt + len(e))))
+            nxt += len(e)
+        per_req = [wl.token_streams(rng, L, ln, H_qk, H_v, d, d, dtype, "slow" if it % 3 == 0 else "config") for ln in lens]
+        src = [-1 if s0 == 0 else int(rng.integers(0, n_src)) for s0 in starts]
+        call = wl.pack_call(L, H_qk, H_v, d, d, dtype, per_req, starts, src, emits, eslots, nxt + 1)
+        pool = rng.standard_normal((nxt + 1,) + call.slot_shape).astype(np.float32) * 0.1
+        check_call(call, pool, TOL[dtype], o_dtype="bf16" if it % 5 == 0 else "f32")
+
+
+@pytest.mark.gpu
 def test_probe_ceilings_reports_plausible_machine_rates():
     """The probe's figures lie between a fifth of the data-sheet peaks and the peaks themselves."""
     import torch
