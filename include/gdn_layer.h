@@ -19,6 +19,11 @@
  *   gate a             exp(-exp(A_log[h]) softplus(a_pre + dt_bias[h]))
  *   output             y = o / sqrt(mean(o^2) + norm_eps) * weight * SiLU(z) per (token, value head)
  *
+ * Stacked layers: with L > 1 every tensor below gains a leading layer index -- token tensors are
+ * [L][T_alloc][...] planes (the layout gdn_resume_prefill reads q, k, v, beta, gate in and writes o
+ * in), parameters are [L][...], a convolution-state slot is [L][K-1][C] -- and one launch handles all
+ * layers; the request and emit index arrays are shared by the layers.
+ *
  * Channels of the convolution input: C = 2 H_qk d_k + H_v d_v, ordered [q heads | k heads | v heads].
  * Positions are absolute and 1-based as in gdn_resume.h: request r owns packed rows
  * [cu_seqlens[r], cu_seqlens[r+1]) = tokens at positions start_pos[r]+1 ...
@@ -45,6 +50,9 @@ typedef struct gdn_layer_shape {
     int32_t o_dtype;    /* GDN_F32 or GDN_BF16: the recurrence output o read by gdn_layer_output */
     float qk_eps;       /* inside the root of the q/k normalisation */
     float norm_eps;     /* inside the root of the output normalisation */
+    int32_t L;          /* stacked layers handled by one call (>= 1), independent problems with their own
+                           inputs and parameters, as in gdn_shape */
+    int64_t T_alloc;    /* tokens per layer plane of the token tensors (>= the call's T); 0 = exactly T */
 } gdn_layer_shape;
 
 /* Bytes of device workspace gdn_layer_inputs needs (its index arrays).  Negative on error. */
@@ -70,7 +78,8 @@ int64_t gdn_layer_workspace_bytes(int32_t n_req, int32_t n_emit);
  *               may be NULL when there is no emission.
  *   q, k        device, out_dtype, [T][H_qk][d_k];  v: [T][H_v][d_v];  beta, gate: [T][H_v]
  *   workspace   device, 16-byte aligned, >= gdn_layer_workspace_bytes(n_req, n_emit)
- * Errors: GDN_ERR_NULL, _ALIGN (pointers and slot strides 16-byte aligned), _SHAPE, _SEQLENS,
+ * Errors: GDN_ERR_NULL, _ALIGN (pointers and slot strides 16-byte aligned), _SHAPE (also a slot
+ * smaller than L (K-1) C), _SEQLENS (also more tokens than T_alloc),
  * _START, _EMIT, _SLOT_RANGE, _SLOT_DUP, _SLOT_HAZARD (conv_dst == conv_src and an emit slot is
  * any request's source slot: the launch reads and writes concurrently), _WORKSPACE, _COUNT.
  * A request of length 0 is legal: its states at start_pos[r] cannot be asked for (the emit
@@ -93,7 +102,8 @@ int32_t gdn_layer_inputs(const gdn_layer_shape *shape,
  *   o       device, o_dtype, [T][H_v][d_v] (the recurrence output of gdn_resume_prefill, one layer)
  *   z       device, in_dtype, [T][H_v][d_v];  weight: device, fp32, [d_v]
  *   y       device, out_dtype, [T][H_v][d_v]
- * Errors: GDN_ERR_NULL, _ALIGN, _SHAPE, _COUNT.  T = 0 is legal.
+ * With L > 1: o, z, y are [L][T_alloc][H_v][d_v], weight [L][d_v].
+ * Errors: GDN_ERR_NULL, _ALIGN, _SHAPE, _COUNT, _SEQLENS (T beyond T_alloc).  T = 0 is legal.
  */
 int32_t gdn_layer_output(const gdn_layer_shape *shape, const void *o, const void *z, const float *weight,
                          void *y, int64_t T, void *stream);

@@ -19,7 +19,7 @@ inline int elem_bytes(int32_t t) { return t == GDN_F32 ? 4 : 2; }
 
 int32_t check_shape(const gdn_layer_shape* s) {
     if (!s) return GDN_ERR_NULL;
-    if (s->H_qk <= 0 || s->H_v <= 0) return GDN_ERR_SHAPE;
+    if (s->H_qk <= 0 || s->H_v <= 0 || s->L <= 0 || s->T_alloc < 0) return GDN_ERR_SHAPE;
     if ((s->d_k != 64 && s->d_k != 128) || (s->d_v != 64 && s->d_v != 128)) return GDN_ERR_SHAPE;
     if (s->conv_k < 2 || s->conv_k > 4) return GDN_ERR_SHAPE;
     if (!dtype_ok(s->in_dtype) || !dtype_ok(s->out_dtype) || !dtype_ok(s->o_dtype)) return GDN_ERR_SHAPE;
@@ -34,14 +34,14 @@ int32_t check_shape(const gdn_layer_shape* s) {
 inline int64_t plan_ints(int32_t n_req, int32_t n_emit) { return 4 * (int64_t)n_req + 2 + 3 * (int64_t)n_emit; }
 
 template <typename In, typename Out>
-hipError_t launch_inputs(const LayerArgs& a, int64_t blocks, hipStream_t stream) {
-    hipLaunchKernelGGL((gdn_layer_inputs_kernel<In, Out>), dim3((unsigned)blocks), dim3(LAYER_THREADS), 0, stream, a);
+hipError_t launch_inputs(const LayerArgs& a, int64_t blocks, int layers, hipStream_t stream) {
+    hipLaunchKernelGGL((gdn_layer_inputs_kernel<In, Out>), dim3((unsigned)blocks, (unsigned)layers), dim3(LAYER_THREADS), 0, stream, a);
     return hipGetLastError();
 }
 
 template <typename O, typename In, typename Out>
-hipError_t launch_output(const LayerOutArgs& a, int64_t blocks, hipStream_t stream) {
-    hipLaunchKernelGGL((gdn_layer_output_kernel<O, In, Out>), dim3((unsigned)blocks), dim3(LAYER_THREADS), 0, stream, a);
+hipError_t launch_output(const LayerOutArgs& a, int64_t blocks, int layers, hipStream_t stream) {
+    hipLaunchKernelGGL((gdn_layer_output_kernel<O, In, Out>), dim3((unsigned)blocks, (unsigned)layers), dim3(LAYER_THREADS), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -77,6 +77,7 @@ int32_t gdn_layer_inputs(const gdn_layer_shape* s, const void* x_qkv, const floa
         if (start_pos[r] < 0 || (int64_t)start_pos[r] + (cu_seqlens[r + 1] - cu_seqlens[r]) > INT32_MAX) return GDN_ERR_START;
     }
     const int64_t T = cu_seqlens[n_req];
+    if (s->T_alloc && T > s->T_alloc) return GDN_ERR_SEQLENS;
     const int32_t n_emit = emit_cu[n_req];
     if (n_emit > 0 && (!emit_pos || !emit_slot)) return GDN_ERR_NULL;
     const int32_t K1 = s->conv_k - 1;
@@ -117,11 +118,11 @@ int32_t gdn_layer_inputs(const gdn_layer_shape* s, const void* x_qkv, const floa
     const int64_t per16 = 16 / elem_bytes(s->in_dtype);
     if (any_src) {
         if (src_slot_stride % per16) return GDN_ERR_ALIGN;
-        if (src_slot_stride < K1 * C) return GDN_ERR_SHAPE;
+        if (src_slot_stride < (int64_t)s->L * K1 * C) return GDN_ERR_SHAPE;
     }
     if (n_emit > 0) {
         if (dst_slot_stride % per16) return GDN_ERR_ALIGN;
-        if (dst_slot_stride < K1 * C) return GDN_ERR_SHAPE;
+        if (dst_slot_stride < (int64_t)s->L * K1 * C) return GDN_ERR_SHAPE;
     }
     const int64_t need = gdn_layer_workspace_bytes(n_req, n_emit);
     if (!workspace || !aligned16(workspace) || workspace_bytes < need) return GDN_ERR_WORKSPACE;
@@ -170,11 +171,14 @@ int32_t gdn_layer_inputs(const gdn_layer_shape* s, const void* x_qkv, const floa
     a.C = (int32_t)C; a.nq = s->H_qk * s->d_k; a.d_k = s->d_k; a.H_v = s->H_v; a.K = s->conv_k;
     a.T = T; a.qk_eps = s->qk_eps;
     a.conv_blocks = (int32_t)conv_blocks; a.gate_blocks = (int32_t)gate_blocks;
+    const int64_t Tp = s->T_alloc ? s->T_alloc : T;    // tokens per layer plane
+    a.ls_x = Tp * C; a.ls_tok_h = Tp * s->H_v; a.ls_qk = Tp * a.nq; a.ls_v = Tp * (C - 2 * a.nq);
+    a.ls_w = C * s->conv_k; a.ls_c = C; a.ls_h = s->H_v; a.ls_conv = (int64_t)K1 * C;
     hipError_t e;
     if (s->in_dtype == GDN_BF16)
-        e = s->out_dtype == GDN_BF16 ? launch_inputs<uint16_t, uint16_t>(a, blocks, stream) : launch_inputs<uint16_t, float>(a, blocks, stream);
+        e = s->out_dtype == GDN_BF16 ? launch_inputs<uint16_t, uint16_t>(a, blocks, s->L, stream) : launch_inputs<uint16_t, float>(a, blocks, s->L, stream);
     else
-        e = s->out_dtype == GDN_BF16 ? launch_inputs<float, uint16_t>(a, blocks, stream) : launch_inputs<float, float>(a, blocks, stream);
+        e = s->out_dtype == GDN_BF16 ? launch_inputs<float, uint16_t>(a, blocks, s->L, stream) : launch_inputs<float, float>(a, blocks, s->L, stream);
     return hip_err(e);
 }
 
@@ -184,6 +188,7 @@ int32_t gdn_layer_output(const gdn_layer_shape* s, const void* o, const void* z,
     const int32_t rc = check_shape(s);
     if (rc != GDN_OK) return rc;
     if (T < 0) return GDN_ERR_COUNT;
+    if (s->T_alloc && T > s->T_alloc) return GDN_ERR_SEQLENS;
     if (T == 0) return GDN_OK;
     if (!o || !z || !weight || !y) return GDN_ERR_NULL;
     if (!aligned16(o) || !aligned16(z) || !aligned16(weight) || !aligned16(y)) return GDN_ERR_ALIGN;
@@ -192,19 +197,20 @@ int32_t gdn_layer_output(const gdn_layer_shape* s, const void* o, const void* z,
     a.n_groups = T * s->H_v * (s->d_v / 8);
     a.d_v = s->d_v;
     a.eps = s->norm_eps;
+    a.ls_tok = (s->T_alloc ? s->T_alloc : T) * s->H_v * s->d_v;
     const int64_t blocks = (a.n_groups + LAYER_THREADS - 1) / LAYER_THREADS;
     if (blocks > INT32_MAX) return GDN_ERR_COUNT;
     const int key = (s->o_dtype == GDN_BF16) * 4 + (s->in_dtype == GDN_BF16) * 2 + (s->out_dtype == GDN_BF16);
     hipError_t e = hipSuccess;
     switch (key) {
-        case 0: e = launch_output<float, float, float>(a, blocks, stream); break;
-        case 1: e = launch_output<float, float, uint16_t>(a, blocks, stream); break;
-        case 2: e = launch_output<float, uint16_t, float>(a, blocks, stream); break;
-        case 3: e = launch_output<float, uint16_t, uint16_t>(a, blocks, stream); break;
-        case 4: e = launch_output<uint16_t, float, float>(a, blocks, stream); break;
-        case 5: e = launch_output<uint16_t, float, uint16_t>(a, blocks, stream); break;
-        case 6: e = launch_output<uint16_t, uint16_t, float>(a, blocks, stream); break;
-        default: e = launch_output<uint16_t, uint16_t, uint16_t>(a, blocks, stream); break;
+        case 0: e = launch_output<float, float, float>(a, blocks, s->L, stream); break;
+        case 1: e = launch_output<float, float, uint16_t>(a, blocks, s->L, stream); break;
+        case 2: e = launch_output<float, uint16_t, float>(a, blocks, s->L, stream); break;
+        case 3: e = launch_output<float, uint16_t, uint16_t>(a, blocks, s->L, stream); break;
+        case 4: e = launch_output<uint16_t, float, float>(a, blocks, s->L, stream); break;
+        case 5: e = launch_output<uint16_t, float, uint16_t>(a, blocks, s->L, stream); break;
+        case 6: e = launch_output<uint16_t, uint16_t, float>(a, blocks, s->L, stream); break;
+        default: e = launch_output<uint16_t, uint16_t, uint16_t>(a, blocks, s->L, stream); break;
     }
     return hip_err(e);
 }

@@ -42,6 +42,11 @@ struct LayerArgs {
     float qk_eps;
     int32_t conv_blocks, gate_blocks;  // blocks [0, conv_blocks) convolve, the next gate_blocks make the gates,
                                        // the rest copy convolution states
+    // stacked layers (grid.y): element strides from one layer's plane to the next
+    int64_t ls_x, ls_tok_h;            // x_qkv; a_pre, b_pre, beta, gate
+    int64_t ls_qk, ls_v;               // q and k; v
+    int64_t ls_w, ls_c, ls_h;          // taps; bias; A_log and dt_bias
+    int64_t ls_conv;                   // a layer's rows inside a convolution-state slot: (K-1) C
 };
 
 // ---- 8 adjacent elements <-> fp32
@@ -124,6 +129,23 @@ __device__ __forceinline__ float head_sum(float s, int d) {
 
 template <typename In, typename Out>
 __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_inputs_kernel(LayerArgs a) {
+    {   // this block's layer: every tensor moves to that layer's plane
+        const int64_t l = blockIdx.y;
+        a.x = reinterpret_cast<const In*>(a.x) + l * a.ls_x;
+        a.a_pre = reinterpret_cast<const In*>(a.a_pre) + l * a.ls_tok_h;
+        a.b_pre = reinterpret_cast<const In*>(a.b_pre) + l * a.ls_tok_h;
+        a.w += l * a.ls_w;
+        if (a.bias) a.bias += l * a.ls_c;
+        a.A_log += l * a.ls_h;
+        a.dt_bias += l * a.ls_h;
+        if (a.conv_src) a.conv_src = reinterpret_cast<const In*>(a.conv_src) + l * a.ls_conv;
+        if (a.conv_dst) a.conv_dst = reinterpret_cast<In*>(a.conv_dst) + l * a.ls_conv;
+        a.q = reinterpret_cast<Out*>(a.q) + l * a.ls_qk;
+        a.k = reinterpret_cast<Out*>(a.k) + l * a.ls_qk;
+        a.v = reinterpret_cast<Out*>(a.v) + l * a.ls_v;
+        a.beta = reinterpret_cast<Out*>(a.beta) + l * a.ls_tok_h;
+        a.gate = reinterpret_cast<Out*>(a.gate) + l * a.ls_tok_h;
+    }
     const In* const x = reinterpret_cast<const In*>(a.x);
     const int CG = a.C / 8;   // channel groups per row
     const int K1 = a.K - 1;
@@ -265,6 +287,7 @@ struct LayerOutArgs {
     const float* weight; // [d_v]
     void* y;
     int64_t n_groups;    // T * H_v * d_v / 8
+    int64_t ls_tok;      // stacked layers (grid.y): elements from one layer's plane of o, z, y to the next
     int32_t d_v;
     float eps;
 };
@@ -275,9 +298,10 @@ __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_output_kernel(LayerOu
     const int64_t gi = (int64_t)blockIdx.x * LAYER_THREADS + threadIdx.x;
     if (gi >= a.n_groups) return;   // whole heads leave together
     const int c0 = (int)(gi % (a.d_v / 8)) * 8;
-    const F8 o = load8(reinterpret_cast<const O*>(a.o) + gi * 8);
-    const F8 z = load8(reinterpret_cast<const In*>(a.z) + gi * 8);
-    const F8 w = load8(a.weight + c0);
+    const int64_t lo = (int64_t)blockIdx.y * a.ls_tok;   // this block's layer
+    const F8 o = load8(reinterpret_cast<const O*>(a.o) + lo + gi * 8);
+    const F8 z = load8(reinterpret_cast<const In*>(a.z) + lo + gi * 8);
+    const F8 w = load8(a.weight + (int64_t)blockIdx.y * a.d_v + c0);
     float ss = 0.f;
 #pragma unroll
     for (int c = 0; c < 8; ++c) ss = fmaf(o.f[c], o.f[c], ss);
@@ -286,7 +310,7 @@ __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_output_kernel(LayerOu
     F8 y;
 #pragma unroll
     for (int c = 0; c < 8; ++c) y.f[c] = o.f[c] * inv * w.f[c] * silu_f(z.f[c]);
-    store8(reinterpret_cast<Out*>(a.y) + gi * 8, y);
+    store8(reinterpret_cast<Out*>(a.y) + lo + gi * 8, y);
 }
 
 }  // namespace gdn

@@ -12,14 +12,14 @@ EXPORTS = ["gdn_layer_workspace_bytes", "gdn_layer_inputs", "gdn_layer_output"]
 
 class gdn_layer_shape(ctypes.Structure):
     _fields_ = [("H_qk", _i32), ("H_v", _i32), ("d_k", _i32), ("d_v", _i32), ("conv_k", _i32), ("in_dtype", _i32),
-                ("out_dtype", _i32), ("o_dtype", _i32), ("qk_eps", _f32), ("norm_eps", _f32)]
+                ("out_dtype", _i32), ("o_dtype", _i32), ("qk_eps", _f32), ("norm_eps", _f32), ("L", _i32), ("T_alloc", _i64)]
 
 
 def make_layer_shape(H_qk, H_v, d_k, d_v, conv_k=4, in_dtype="bf16", out_dtype="bf16", o_dtype="f32", qk_eps=1e-6,
-                     norm_eps=1e-5) -> gdn_layer_shape:
+                     norm_eps=1e-5, L=1, T_alloc=0) -> gdn_layer_shape:
     code = {"f32": GDN_F32, "bf16": GDN_BF16, GDN_F32: GDN_F32, GDN_BF16: GDN_BF16}
     return gdn_layer_shape(H_qk, H_v, d_k, d_v, conv_k, code[in_dtype], code[out_dtype], code[o_dtype], float(qk_eps),
-                           float(norm_eps))
+                           float(norm_eps), int(L), int(T_alloc))
 
 
 _ready = False

@@ -75,6 +75,10 @@ def inputs_args(**over):
     (dict(conv_src=FakeDev(stride0=2 * 384)), -3),                      # slot smaller than a state
     (dict(workspace=None), -9),
     (dict(workspace=FakeDev(ptr=0x100000, nbytes=16)), -9),
+    (dict(shape=LY.make_layer_shape(2, 2, 64, 64, L=0)), -3),
+    (dict(shape=LY.make_layer_shape(2, 2, 64, 64, L=2)), -3),             # a slot of 3 x 384 holds one layer's rows, not two
+    (dict(shape=LY.make_layer_shape(2, 2, 64, 64, T_alloc=129)), -4),     # 130 tokens do not fit a plane of 129
+    (dict(shape=LY.make_layer_shape(2, 2, 64, 64, T_alloc=-1)), -3),
 ])
 def test_layer_inputs_argument_errors(monkeypatch, over, code):
     """Every check fires on the host, before anything is enqueued."""
@@ -185,6 +189,58 @@ def test_layer_inputs_match_the_oracle(case_i, dtype, out_dtype):
     for e, s in enumerate(c.emit_slot):
         want[s] = stor[e]
     assert np.array_equal(pool_after, want)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,out_dtype", [("bf16", "bf16"), ("f32", "f32")])
+def test_stacked_layers_in_one_call_equal_one_call_per_layer_bitwise(dtype, out_dtype):
+    """L = 3 layers with their own inputs and parameters in one launch ([L][T_alloc][...] planes with spare rows, slots of
+    [L][K-1][C]) give bit for bit what three single-layer calls give (those are checked against the oracle above), for
+    the front end, its emitted convolution states, and the back end."""
+    import torch
+    from tests.harness import to_device
+    H_qk, H_v, d_k, d_v, K = 2, 4, 128, 128, 4
+    lens, starts, emits = [97, 0, 33, 200], [64, 5, 0, 1000], [[65, 66, 161], [], [33], [1100, 1200]]
+    cs = [wl.layer_case(2600 + l, H_qk, H_v, d_k, d_v, K, dtype, lens, starts, emits) for l in range(3)]
+    for c in cs[1:]:
+        c.src_slot, c.emit_slot = cs[0].src_slot, cs[0].emit_slot
+    singles = [gpu_inputs(c, out_dtype, 1e-6) for c in cs]
+    L, T, Ta, C = 3, cs[0].T, cs[0].T + 7, cs[0].C
+    sh = LY.make_layer_shape(H_qk, H_v, d_k, d_v, K, dtype, out_dtype, "f32", 1e-6, L=L, T_alloc=Ta)
+    tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
+    def planes(arrs, fill=0):                                  # [L][T_alloc][...] from per-layer [T][...]
+        out = np.full((L, Ta) + arrs[0].shape[1:], fill, arrs[0].dtype)
+        for l, a in enumerate(arrs):
+            out[l, :T] = a
+        return to_device(out)
+    new = lambda *s_: torch.full(s_, float("nan"), dtype=tdt, device="cuda")
+    q, k, v = new(L, Ta, H_qk, d_k), new(L, Ta, H_qk, d_k), new(L, Ta, H_v, d_v)
+    beta, gate = new(L, Ta, H_v), new(L, Ta, H_v)
+    pool = to_device(np.ascontiguousarray(np.stack([c.conv_pool for c in cs], axis=1)))     # [slots][L][K-1][C]
+    ws = torch.empty(LY.gdn_layer_workspace_bytes(len(starts), int(cs[0].emit_pos.size)), dtype=torch.uint8, device="cuda")
+    stack = lambda name: to_device(np.ascontiguousarray(np.stack([getattr(c, name) for c in cs])))
+    LY.gdn_layer_inputs(sh, planes([c.x_qkv for c in cs]), stack("conv_w"), stack("conv_b"), planes([c.a_pre for c in cs]),
+                        planes([c.b_pre for c in cs]), stack("A_log"), stack("dt_bias"), cs[0].cu_seqlens, cs[0].start_pos, pool,
+                        cs[0].src_slot, cs[0].emit_cu, cs[0].emit_pos, pool, cs[0].emit_slot, q, k, v, beta, gate, ws)
+    torch.cuda.synchronize()
+    host = lambda t: t.float().cpu().numpy().astype(np.float64)
+    bits = lambda t: (t.view(torch.int16) if t.dtype == torch.bfloat16 else t).cpu().numpy()
+    for l in range(L):
+        for got, want in zip((q, k, v, beta, gate), singles[l][0]):
+            assert np.array_equal(host(got[l, :T]), want)
+        assert np.array_equal(bits(pool)[:, l], singles[l][1])
+    assert torch.isnan(q[:, T:].float()).all()                                              # spare rows of the planes stay untouched
+    # back end on the same planes
+    o = planes([c.o for c in cs])
+    z = planes([c.z for c in cs])
+    y = new(L, Ta, H_v, d_v)
+    LY.gdn_layer_output(sh, o, z, stack("norm_w"), y, T)
+    sh1 = LY.make_layer_shape(H_qk, H_v, d_k, d_v, K, dtype, out_dtype, "f32", 1e-6)
+    for l in range(L):
+        y1 = new(T, H_v, d_v)
+        LY.gdn_layer_output(sh1, to_device(cs[l].o), to_device(cs[l].z), to_device(cs[l].norm_w), y1, T)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(y[l, :T]), host(y1))
 
 
 @pytest.mark.gpu
