@@ -109,6 +109,22 @@ int32_t attn_suffix_prefill(const attn_shape *shape, const void *q, const void *
                             int32_t cap, const int32_t *seq_slot,
                             void *o, void *workspace, int64_t workspace_bytes, void *stream);
 
+/*
+ * The work list attn_suffix_prefill makes for a call (host only, integers; exposed for tests and
+ * for callers that want to see the launch shape).  A unit is one workgroup's walk for each head
+ * block: rows = 128 / *heads_per_row_group suffix tokens starting at token unit_tile * that many
+ * of request unit_req (with *heads_per_row_group query heads of a key/value group per token: 1,
+ * or H_q / H_kv in calls with short suffixes), key tiles [unit_t0, unit_t1) of *key_tile_rows rows
+ * each; unit_part is the workspace slot of a part of a split walk, or -1 for a whole walk.  Units
+ * come in launch order, most key tiles first.  The five arrays hold `capacity` entries;
+ * *n_units is set also when that is too few (GDN_ERR_COUNT).
+ */
+int32_t attn_plan(const attn_shape *shape, int32_t n_req, const int32_t *cu_seqlens,
+                  const int32_t *start_pos, int32_t capacity,
+                  int32_t *unit_req, int32_t *unit_tile, int32_t *unit_t0, int32_t *unit_t1,
+                  int32_t *unit_part, int32_t *n_units, int32_t *heads_per_row_group,
+                  int32_t *key_tile_rows);
+
 #ifdef __cplusplus
 }
 #endif

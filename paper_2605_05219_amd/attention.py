@@ -7,7 +7,7 @@ from .binding import GDN_BF16, GDN_F32, _check, _dp, _h32, _hp, _stream_ptr, lib
 
 _i32, _i64, _vp, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
 
-EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_kv_spill", "attn_suffix_prefill"]
+EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_kv_spill", "attn_suffix_prefill", "attn_plan"]
 
 
 class attn_shape(ctypes.Structure):
@@ -36,12 +36,26 @@ def _lib():
         L.attn_suffix_prefill.restype = _i32
         L.attn_suffix_prefill.argtypes = ([ctypes.POINTER(attn_shape)] + [_vp] * 4 + [_i32, _vp, _vp]
                                           + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp, _vp, _i64, _vp])
+        L.attn_plan.restype = _i32
+        L.attn_plan.argtypes = [ctypes.POINTER(attn_shape), _i32, _vp, _vp, _i32] + [_vp] * 8
         _ready = True
     return L
 
 
 def attn_workspace_bytes(shape: attn_shape, n_req: int, total_tokens: int) -> int:
     return _check(int(_lib().attn_workspace_bytes(ctypes.byref(shape), int(n_req), int(total_tokens))), "attn_workspace_bytes")
+
+
+def attn_plan(shape: attn_shape, cu_seqlens, start_pos, capacity: int = 1 << 16):
+    """See include/attn_resume.h: (units as an int32 array [n_units][5] of (req, tile, t0, t1, part), heads per row
+    group, key tile rows).  Host only."""
+    import numpy as np
+    cu, sp = _h32(cu_seqlens), _h32(start_pos)
+    arrs = [np.zeros(capacity, np.int32) for _ in range(5)]
+    n, pack, kt = _i32(0), _i32(0), _i32(0)
+    _check(_lib().attn_plan(ctypes.byref(shape), int(sp.size), _hp(cu), _hp(sp), int(capacity), *[_vp(a.ctypes.data) for a in arrs],
+                            ctypes.byref(n), ctypes.byref(pack), ctypes.byref(kt)), "attn_plan")
+    return np.stack([a[:n.value] for a in arrs], axis=1), pack.value, kt.value
 
 
 def _pool_geometry(pool):

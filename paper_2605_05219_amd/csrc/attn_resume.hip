@@ -102,6 +102,77 @@ hipError_t launch_combine_d(int d, const CombineArgs& a, unsigned blocks /* (pie
     return hipGetLastError();
 }
 
+// The work of one attn_suffix_prefill call (host, integer): how the rows of a workgroup are made up, the pieces
+// (row tiles of a request), the cut of long key walks into parts, and the units (whole walks or parts) in launch order.
+struct Unit { int32_t req, tile, t0, t1, part; };
+struct UnitPlan {
+    int pack = 1;                     // query heads per token in a workgroup's rows: 1, or H_q / H_kv
+    std::vector<Unit> units;          // those with the most key tiles first
+    std::vector<int32_t> piece_req, piece_tile, piece_base, piece_parts;   // the split pieces and their workspace slots
+};
+
+void build_units(const attn_shape& sh, int32_t n_req, const int32_t* len, const int32_t* start_pos, UnitPlan& out) {
+    const attn_shape* s = &sh;
+    // ---- rows of a workgroup: 128 tokens of one query head, or, where that would leave at least a fifth of all
+    // rows empty (short suffixes), 128 / G tokens of the G heads of a key/value group
+    const int KT = att_kt(s->d);
+    const int G = s->H_q / s->H_kv;
+    int pack = 1;
+    if (G > 1 && ATT_BQ % G == 0) {
+        int64_t rows_plain = 0, rows_packed = 0;
+        for (int32_t r = 0; r < n_req; ++r) {
+            rows_plain += (int64_t)((len[r] + ATT_BQ - 1) / ATT_BQ) * s->H_q;
+            rows_packed += (int64_t)((len[r] + ATT_BQ / G - 1) / (ATT_BQ / G)) * s->H_kv;
+        }
+        const char* no_pack = std::getenv("ATTN_NO_PACK");
+        if (rows_packed * 5 <= rows_plain * 4 && !(no_pack && no_pack[0] == '1')) pack = G;
+    }
+    const int TPW = ATT_BQ / pack;        // tokens per workgroup
+    const int HB = s->H_q / pack;         // head blocks (workgroups) per unit
+    // ---- pieces: one per TPW suffix tokens of a request
+    struct Piece { int32_t req, tile, n_tiles, parts; };
+    std::vector<Piece> pieces;
+    int64_t total_tiles = 0;
+    for (int32_t r = 0; r < n_req; ++r)
+        for (int32_t t = 0; t * TPW < len[r]; ++t) {
+            const int32_t kv = start_pos[r] + std::min((t + 1) * TPW, len[r]);
+            pieces.push_back({r, t, (kv + KT - 1) / KT, 1});
+            total_tiles += pieces.back().n_tiles;
+        }
+    const int64_t n_items = (int64_t)pieces.size();
+    // ---- too few workgroups for the chip: cut long key walks into parts
+    int64_t split_wgs = 0;
+    const char* no_split = std::getenv("ATTN_NO_SPLIT");
+    if (n_items * HB < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
+        int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * HB + SPLIT_BELOW - 1) / SPLIT_BELOW);
+        for (;; tp *= 2) {
+            split_wgs = 0;
+            for (Piece& p : pieces) {
+                p.parts = p.n_tiles >= 2 * tp ? (int32_t)((p.n_tiles + tp - 1) / tp) : 1;
+                if (p.parts > 1) split_wgs += (int64_t)p.parts * HB;
+            }
+            if (split_wgs <= SPLIT_MAX_WGS) break;
+        }
+    }
+    // ---- units: a whole walk or one part of it; those with the most key tiles first
+    std::vector<Unit>& units = out.units;
+    std::vector<int32_t>&piece_req = out.piece_req, &piece_tile = out.piece_tile, &piece_base = out.piece_base,
+                        &piece_parts = out.piece_parts;
+    int32_t next_slot = 0;
+    for (const Piece& p : pieces) {
+        if (p.parts == 1) {
+            units.push_back({p.req, p.tile, 0, p.n_tiles, -1});
+            continue;
+        }
+        piece_req.push_back(p.req); piece_tile.push_back(p.tile); piece_base.push_back(next_slot); piece_parts.push_back(p.parts);
+        const int32_t per = (p.n_tiles + p.parts - 1) / p.parts;
+        for (int32_t j = 0; j < p.parts; ++j)
+            units.push_back({p.req, p.tile, j * per, std::min((j + 1) * per, p.n_tiles), next_slot++});
+    }
+    std::stable_sort(units.begin(), units.end(), [](const Unit& x, const Unit& y) { return x.t1 - x.t0 > y.t1 - y.t0; });
+    out.pack = pack;
+}
+
 }  // namespace
 }  // namespace attn
 
@@ -178,6 +249,41 @@ int32_t attn_kv_spill(const attn_shape* s, int32_t n_req, const int32_t* n_rows,
                         const_cast<void*>(v_cache), slot_stride, n_slots, cap, seq_slot, false, static_cast<hipStream_t>(stream));
 }
 
+int32_t attn_plan(const attn_shape* s, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos, int32_t capacity,
+                  int32_t* unit_req, int32_t* unit_tile, int32_t* unit_t0, int32_t* unit_t1, int32_t* unit_part,
+                  int32_t* n_units, int32_t* heads_per_row_group, int32_t* key_tile_rows) {
+    const int32_t rc = check_shape(s);
+    if (rc != GDN_OK) return rc;
+    if (n_req < 0 || capacity < 0) return GDN_ERR_COUNT;
+    if (!n_units || !heads_per_row_group || !key_tile_rows) return GDN_ERR_NULL;
+    *n_units = 0;
+    *heads_per_row_group = 1;
+    *key_tile_rows = att_kt(s->d);
+    if (n_req == 0) return GDN_OK;
+    if (!cu_seqlens || !start_pos) return GDN_ERR_NULL;
+    if (cu_seqlens[0] != 0) return GDN_ERR_SEQLENS;
+    std::vector<int32_t> len(n_req);
+    for (int32_t r = 0; r < n_req; ++r) {
+        if (cu_seqlens[r + 1] < cu_seqlens[r]) return GDN_ERR_SEQLENS;
+        len[r] = cu_seqlens[r + 1] - cu_seqlens[r];
+        if (start_pos[r] < 0 || (int64_t)start_pos[r] + len[r] > INT32_MAX - 256) return GDN_ERR_START;
+    }
+    UnitPlan plan;
+    build_units(*s, n_req, len.data(), start_pos, plan);
+    *n_units = (int32_t)plan.units.size();
+    *heads_per_row_group = plan.pack;
+    if ((int64_t)plan.units.size() > capacity) return GDN_ERR_COUNT;
+    if (!plan.units.empty() && (!unit_req || !unit_tile || !unit_t0 || !unit_t1 || !unit_part)) return GDN_ERR_NULL;
+    for (size_t i = 0; i < plan.units.size(); ++i) {
+        unit_req[i] = plan.units[i].req;
+        unit_tile[i] = plan.units[i].tile;
+        unit_t0[i] = plan.units[i].t0;
+        unit_t1[i] = plan.units[i].t1;
+        unit_part[i] = plan.units[i].part;
+    }
+    return GDN_OK;
+}
+
 int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_new, const void* v_new, const void* out_gate,
                             int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos, void* k_cache, void* v_cache,
                             int64_t slot_stride, int32_t n_slots, int32_t cap, const int32_t* seq_slot, void* o, void* workspace,
@@ -207,63 +313,13 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
         return GDN_ERR_ALIGN;
     if (!workspace || !aligned16(workspace) || workspace_bytes < attn_workspace_bytes(s, n_req, T)) return GDN_ERR_WORKSPACE;
 
-    // ---- rows of a workgroup: 128 tokens of one query head, or, where that would leave at least a fifth of all
-    // rows empty (short suffixes), 128 / G tokens of the G heads of a key/value group
-    const int KT = att_kt(s->d);
+    UnitPlan plan;
+    build_units(*s, n_req, len.data(), start_pos, plan);
     const int G = s->H_q / s->H_kv;
-    int pack = 1;
-    if (G > 1 && ATT_BQ % G == 0) {
-        int64_t rows_plain = 0, rows_packed = 0;
-        for (int32_t r = 0; r < n_req; ++r) {
-            rows_plain += (int64_t)((len[r] + ATT_BQ - 1) / ATT_BQ) * s->H_q;
-            rows_packed += (int64_t)((len[r] + ATT_BQ / G - 1) / (ATT_BQ / G)) * s->H_kv;
-        }
-        const char* no_pack = std::getenv("ATTN_NO_PACK");
-        if (rows_packed * 5 <= rows_plain * 4 && !(no_pack && no_pack[0] == '1')) pack = G;
-    }
-    const int TPW = ATT_BQ / pack;        // tokens per workgroup
-    const int HB = s->H_q / pack;         // head blocks (workgroups) per unit
-    // ---- pieces: one per TPW suffix tokens of a request
-    struct Piece { int32_t req, tile, n_tiles, parts; };
-    std::vector<Piece> pieces;
-    int64_t total_tiles = 0;
-    for (int32_t r = 0; r < n_req; ++r)
-        for (int32_t t = 0; t * TPW < len[r]; ++t) {
-            const int32_t kv = start_pos[r] + std::min((t + 1) * TPW, len[r]);
-            pieces.push_back({r, t, (kv + KT - 1) / KT, 1});
-            total_tiles += pieces.back().n_tiles;
-        }
-    const int64_t n_items = (int64_t)pieces.size();
-    // ---- too few workgroups for the chip: cut long key walks into parts
-    int64_t split_wgs = 0;
-    const char* no_split = std::getenv("ATTN_NO_SPLIT");
-    if (n_items * HB < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
-        int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * HB + SPLIT_BELOW - 1) / SPLIT_BELOW);
-        for (;; tp *= 2) {
-            split_wgs = 0;
-            for (Piece& p : pieces) {
-                p.parts = p.n_tiles >= 2 * tp ? (int32_t)((p.n_tiles + tp - 1) / tp) : 1;
-                if (p.parts > 1) split_wgs += (int64_t)p.parts * HB;
-            }
-            if (split_wgs <= SPLIT_MAX_WGS) break;
-        }
-    }
-    // ---- units: a whole walk or one part of it; those with the most key tiles first
-    struct Unit { int32_t req, tile, t0, t1, part; };
-    std::vector<Unit> units;
-    std::vector<int32_t> piece_req, piece_tile, piece_base, piece_parts;
-    int32_t next_slot = 0;
-    for (const Piece& p : pieces) {
-        if (p.parts == 1) {
-            units.push_back({p.req, p.tile, 0, p.n_tiles, -1});
-            continue;
-        }
-        piece_req.push_back(p.req); piece_tile.push_back(p.tile); piece_base.push_back(next_slot); piece_parts.push_back(p.parts);
-        const int32_t per = (p.n_tiles + p.parts - 1) / p.parts;
-        for (int32_t j = 0; j < p.parts; ++j)
-            units.push_back({p.req, p.tile, j * per, std::min((j + 1) * per, p.n_tiles), next_slot++});
-    }
-    std::stable_sort(units.begin(), units.end(), [](const Unit& x, const Unit& y) { return x.t1 - x.t0 > y.t1 - y.t0; });
+    const int pack = plan.pack, HB = s->H_q / pack;
+    const std::vector<Unit>& units = plan.units;
+    const std::vector<int32_t>&piece_req = plan.piece_req, &piece_tile = plan.piece_tile, &piece_base = plan.piece_base,
+                              &piece_parts = plan.piece_parts;
     const int64_t n_units = (int64_t)units.size();
     const int64_t n_pieces = (int64_t)piece_req.size();
     const bool xcd_split = 8 % s->H_kv == 0;

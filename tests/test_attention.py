@@ -112,6 +112,76 @@ def test_restore_argument_errors_and_empty_calls(monkeypatch):
         AT.attn_workspace_bytes(AT.make_attn_shape(4, 2, 100), 1, 10)
 
 
+def _check_plan(H_q, H_kv, d, lens, starts):
+    """Invariants of the work list: every (token tile, key tile) a request needs is walked exactly once, parts of a
+    split walk are consecutive ranges of whole tiles with consecutive slots, units come with the most tiles first."""
+    sh = AT.make_attn_shape(H_q, H_kv, d)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    units, pack, kt = AT.attn_plan(sh, cu, starts)
+    G = H_q // H_kv
+    assert kt == (32 if d == 256 else 64) and pack in (1, G) and 128 % pack == 0
+    tpw = 128 // pack
+    spans = [int(u[3] - u[2]) for u in units]
+    assert spans == sorted(spans, reverse=True) and all(x > 0 for x in spans)
+    by_piece = {}
+    for req, tile, t0, t1, part in units:
+        by_piece.setdefault((int(req), int(tile)), []).append((int(t0), int(t1), int(part)))
+    want_pieces = {(r, t) for r, n in enumerate(lens) for t in range(-(-n // tpw))}
+    assert set(by_piece) == want_pieces
+    slots = []
+    for (r, t), parts in by_piece.items():
+        parts.sort()
+        kv = starts[r] + min((t + 1) * tpw, lens[r])
+        assert parts[0][0] == 0 and parts[-1][1] == -(-kv // kt)
+        assert all(a[1] == b[0] for a, b in zip(parts, parts[1:]))            # consecutive, no gap, no overlap
+        if len(parts) == 1:
+            assert parts[0][2] == -1
+        else:
+            ids = [p[2] for p in parts]
+            assert ids == list(range(ids[0], ids[0] + len(ids)))              # consecutive workspace slots, in key order
+            slots += ids
+            # parts are balanced after the count is fixed from a target of at least 512 keys: none below two thirds of it
+            assert min(p[1] - p[0] for p in parts) >= 1 and max(p[1] - p[0] for p in parts) * kt * 3 >= 512 * 2
+    assert sorted(slots) == list(range(len(slots)))                           # slots are dense and distinct
+    assert len(slots) * (H_q // pack) <= 768                                  # the partial results fit the workspace region
+    return units, pack
+
+
+def test_work_list_covers_every_tile_once_and_packs_and_splits_as_documented(monkeypatch):
+    # long suffix, many workgroups: plain rows, whole walks
+    u, pack = _check_plan(16, 2, 128, [8192], [0])
+    assert pack == 1 and (u[:, 4] == -1).all() and len(u) == 64
+    # short suffix behind a long prefix: packed rows (16 tokens x 8 heads), walks split into parts of 8 tiles
+    u, pack = _check_plan(16, 2, 128, [64], [8000])
+    assert pack == 8 and len(u) == 4 * 16 and (u[:, 3] - u[:, 2] <= 8).all()
+    # 512 tokens: packing would not save rows; the walks are split
+    u, pack = _check_plan(16, 2, 128, [512], [7680])
+    assert pack == 1 and (u[:, 4] >= 0).all()
+    # a group size that does not divide 128 is never packed; H_kv = 3 is fine for the planner
+    _, pack = _check_plan(6, 2, 64, [5, 9], [100, 0])
+    assert pack == 1
+    # mixed batch, empty requests, d = 256 tiles of 32
+    _check_plan(8, 1, 256, [0, 3, 200, 0, 129], [5, 4000, 64, 0, 1])
+    _check_plan(4, 4, 64, [1] * 40, list(range(0, 4000, 100)))
+    rng = np.random.default_rng(3)
+    for _ in range(30):
+        H_q, H_kv = [(4, 2), (16, 2), (8, 8), (32, 4), (12, 4)][rng.integers(5)]
+        n = int(rng.integers(1, 9))
+        _check_plan(H_q, H_kv, int(rng.choice([64, 128, 256])), [int(x) for x in rng.integers(0, 700, n)],
+                    [int(x) for x in rng.integers(0, 9000, n)])
+    # the switches
+    monkeypatch.setenv("ATTN_NO_PACK", "1")
+    assert _check_plan(16, 2, 128, [64], [8000])[1] == 1
+    monkeypatch.setenv("ATTN_NO_SPLIT", "1")
+    u, _ = _check_plan(16, 2, 128, [64], [8000])
+    assert (u[:, 4] == -1).all() and len(u) == 1
+    # too small a capacity reports the count it needs
+    sh = AT.make_attn_shape(16, 2, 128)
+    with pytest.raises(B.GdnError) as ei:
+        AT.attn_plan(sh, [0, 8192], [0], capacity=10)
+    assert ei.value.code == -11
+
+
 # ----------------------------------------------------------------------------- GPU parity
 def f64(a):
     return wl.to_f32(a).astype(np.float64)

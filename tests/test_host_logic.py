@@ -317,6 +317,8 @@ def test_headers_are_plain_c_and_a_c_program_can_call_the_library(tmp_path):
         "    if (gdn_layer_workspace_bytes(2, 3) <= 0) return 4;\n"
         "    attn_shape as = {16, 2, 128, GDN_BF16, 0.088f};\n"
         "    if (attn_workspace_bytes(&as, 2, 300) <= 0) return 6;\n"
+        "    { const int32_t cu[2] = {0, 64}, st[1] = {8000}; int32_t u[5][64], nu, pk, kt;\n"
+        "      if (attn_plan(&as, 1, cu, st, 64, u[0], u[1], u[2], u[3], u[4], &nu, &pk, &kt) != GDN_OK || nu != 64 || pk != 8 || kt != 64) return 7; }\n"
         "    if (ckpt_place_balanced(511, 3, out) != 3 || out[0] != 128 || out[2] != 384) return 5;\n"
         '    printf("ok\\n");\n    return 0;\n}\n')
     exe = tmp_path / "abi"
