@@ -361,6 +361,35 @@ def test_resuming_at_c_reproduces_the_full_prefill_bit_for_bit():
 
 
 @pytest.mark.gpu
+def test_calls_interleaved_on_two_side_streams_equal_the_default_stream_result():
+    """Two requests' calls (each with its own caches, output and workspace) enqueued alternately on two side streams,
+    several times over, give bit for bit what the same calls give on the default stream: the index arrays of the calls
+    travel through a shared ring of staging buffers and must not mix."""
+    import torch
+    from tests.harness import to_device
+    cases = [wl.attn_case(3700, 8, 2, 128, [150, 3], [700, 2100]), wl.attn_case(3701, 8, 2, 128, [64], [1500])]
+    want = [gpu_prefill(c, gate=True)[0] for c in cases]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sets = []
+    for c in cases:
+        sh = AT.make_attn_shape(c.H_q, c.H_kv, c.d, "f32")
+        kp, vp = pools_with_prefix(c)
+        sets.append(dict(sh=sh, c=c, k=to_device(kp), v=to_device(vp), q=to_device(c.q), kn=to_device(c.suffix("k")),
+                         vn=to_device(c.suffix("v")), g=to_device(c.gate),
+                         o=torch.full((c.T, c.H_q, c.d), float("nan"), dtype=torch.float32, device="cuda"),
+                         ws=torch.empty(AT.attn_workspace_bytes(sh, len(c.start_pos), c.T), dtype=torch.uint8, device="cuda")))
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for s_, st in zip(sets, streams):
+            c = s_["c"]
+            AT.attn_suffix_prefill(s_["sh"], s_["q"], s_["kn"], s_["vn"], s_["g"], c.cu_seqlens, c.start_pos, s_["k"], s_["v"],
+                                   c.seq_slot, s_["o"], s_["ws"], stream=st)
+    torch.cuda.synchronize()
+    for s_, w in zip(sets, want):
+        assert np.array_equal(s_["o"].cpu().numpy().astype(np.float64), w)
+
+
+@pytest.mark.gpu
 def test_restore_from_a_pinned_host_pool_is_bitwise_and_feeds_the_prefill():
     import torch
     from tests.harness import to_device
