@@ -1,22 +1,28 @@
 #!/usr/bin/env python3
 """Benchmark of the resume + checkpoint-emit prefill on one MI355X.
 
-Workload (configs[1]): one GatedDeltaNet layer, batch 1, 16 heads, d_k = d_v = 128, bf16 inputs,
-fp32 state and outputs, cached prefix N = 8192 with M = 16 uniformly spaced checkpoints.  A
-step is one request: its overlap depth t is a seeded draw from U[0, N); it loads the state of
-the deepest checkpoint at or below t straight from the HBM pool, replays tokens l+1..N and
-stores every downstream checkpoint state to fresh pool slots.  Steps cycle through a fixed
-list of seeded draws.  Inputs are resident in HBM before the timed region; the timed region
-covers the whole call per step (host planning, plan upload, both kernels).
+Headline workload (configs[4], the largest single-GPU configuration): a layer-group serving step.
+256 concurrent requests with suffix lengths log-uniform in [64, 8192] run through 8 stacked
+GatedDeltaNet layers of 16 heads (d_k = d_v = 128, bf16 inputs, fp32 state and outputs).  Each
+request gathers its start state by slot id from a 4096-slot HBM checkpoint pool (32 GiB of fp32
+states), replays its suffix and stores the exact state at every multiple of 1024 inside the suffix
+and at its end to freshly assigned slots.  A step is ONE call of gdn_resume_prefill over the whole
+batch (host planning, plan upload, one fused launch: 32768 chains).  Inputs are generated on the
+device with a fixed seed and are resident in HBM before the timed region.
 
-Prints ONE JSON line.  Roofline accounting: algorithmic flops (dense tiles of the chunked form) of the launches
-that run the recurrence, over their HIP-event time, against the fp16 MFMA peak.
+Prints ONE JSON line.  `value` = suffix tokens per second through the whole 8-layer group.
+`roofline` is that of the dominant kernel (gdn_fused_kernel, one launch per step) from HIP events
+the library records on the launch stream: algorithmic HBM bytes over the launch duration against
+8 TB/s (the binding roof: 140 flop per byte against a ridge of 312), with the matrix-core view
+beside it.  configs[1] (batch 1, latency bound) is reported as the side object `latency`.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
+import re
 import sys
 import time
 
@@ -33,51 +39,177 @@ C = 64
 # algorithmic flops per token.head (dense tiles, chunk 64): chunk preparation and recurrence
 FLOP_PREP = C * (6 * D + 2 * D)             # K K^T, K Q^T, W (each 2 C d_k) + U~ (2 C d_v)
 FLOP_RECUR = 6 * D * D + 2 * C * D          # W S^T, Q S^T, state update (2 d_k d_v each) + P U (2 C d_v)
-# algorithmic HBM bytes per token.head: q, k, v in bf16, beta, gate, o in fp32
+# algorithmic HBM bytes per token.head: q, k, v in bf16, beta, gate, o in fp32 (bf16 o: 2 d_v less)
 BYTES_TOKEN_HEAD = (2 * D + D) * 2 + 2 * 2 + D * 4
-# measured HBM bytes per token.head of a call (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/), by launch
-# kind: the first slab's preparation launch; the recurrence launches, which also prepare every later slab
-TRAFFIC_PREP = 319 + 444       # read + written
-TRAFFIC_RECUR = 1671 + 1347
-SLAB_TOKENS = 32 * C           # the latency variant's slab at 16 chains (checked against the launch count below)
+BYTES_TOKEN_HEAD_BF16_O = (2 * D + D) * 2 + 2 * 2 + D * 2
+STATE_BYTES = D * D * 4                      # one head's state, read once per chain and written once per emission
+SLAB_TOKENS = 32 * C           # configs[1]: the latency variant's slab at 16 chains (checked against the launch count)
 PEAK_MFMA_TFLOPS = 2500.0                   # dense fp16/bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
+PROFILES = os.path.join(ROOT, "profiles")
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=64)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--main-only", action="store_true",
-                    help="only the timed steps and their event pass (no latency sweep, pool copies, host tier, decode, "
-                         "CPU baseline): what the profiler runs use")
-    ap.add_argument("--batch-sweep", action="store_true",
-                    help="also time ONE call of k = 1..64 requests of this workload's kind (side object "
-                         "`batch_sweep`; about a minute of host-side input generation)")
-    ap.add_argument("--layer-group", action="store_true",
-                    help="also time a whole cache hit on a layer group (3 GatedDeltaNet layers + 1 attention layer, "
-                         "checkpoint and KV cache restored from pinned host memory) against the suffix length")
-    ap.add_argument("--no-kernel-events", action="store_true",
-                    help="skip the per-kernel HIP event pass (no roofline object)")
-    ap.add_argument("--events-in-timed-region", action="store_true",
-                    help="record the per-kernel events inside the timed steps themselves instead of in a "
-                         "repeat of them (the events cost some microseconds per launch)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        return 2
+def measured_traffic(name: str, key: str):
+    """A figure from a committed rocprofv3 summary under profiles/ (a line `key: number`), or None."""
+    try:
+        with open(os.path.join(PROFILES, name)) as f:
+            m = re.search(r"^" + re.escape(key) + r":\s*([0-9.eE+-]+)", f.read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
 
-    import torch
-    from paper_2605_05219_amd import binding as B, workloads as wl
-    from tests.harness import GpuCall
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
+def bench_config4(args, torch, B, dev):
+    """The headline: configs[4] at full size, one call per step."""
+    from paper_2605_05219_amd.device_call import config4_device
+    step = config4_device()
+    n_chains = step.n_req * step.L * step.H
+    th = step.T * step.L * step.H                       # token.heads of one step
+    state_moves = (step.n_req + step.n_emit) * step.L * step.H
+    alg_bytes = th * BYTES_TOKEN_HEAD + state_moves * STATE_BYTES
+    alg_flops = th * (FLOP_PREP + FLOP_RECUR)
 
+    for _ in range(args.warmup):
+        step.run()
+    torch.cuda.synchronize()
+
+    def timed(events):
+        if events:
+            B.gdn_profile_enable(True)
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        for _ in range(args.steps):
+            step.run()
+        torch.cuda.synchronize()
+        tb = time.perf_counter()
+        if not events:
+            return tb - ta, 0.0, 0
+        _, k_ms, n_prof, _, k_n = B.gdn_profile_collect()
+        B.gdn_profile_enable(False)
+        assert n_prof == args.steps and k_n == args.steps, (n_prof, k_n)
+        return tb - ta, k_ms, k_n
+
+    if args.no_kernel_events:
+        wall, k_ms, k_n = timed(False)
+    elif args.events_in_timed_region:
+        wall, k_ms, k_n = timed(True)
+    else:
+        wall = timed(False)[0]
+        _, k_ms, k_n = timed(True)
+
+    ms = 1e3 * wall / args.steps
+    out = {
+        "metric": "recomputed suffix tokens/sec/GPU (resume+ckpt emit)",
+        "value": step.T / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[4]: layer-group serving step, 256 requests x 8 GatedDeltaNet layers x 16 heads, "
+                        "d_k=d_v=128, suffix ~ logU[64,8192], 4096-slot fp32 checkpoint pool in HBM addressed by int32 slot "
+                        "ids, states stored every 1024 positions and at each request's end; bf16 inputs, fp32 state and outputs",
+            "seed": 1004, "requests": step.n_req, "layers": step.L, "heads": step.H,
+            "suffix_tokens_per_layer": step.T, "chains": n_chains, "emitted_states": step.n_emit,
+            "token_layers_per_s": step.T * step.L / (ms * 1e-3),
+            "token_heads_per_s": th / (ms * 1e-3),
+            "workspace_bytes": int(step.workspace.numel()),
+            "chunk": C,
+        },
+    }
+    if not args.no_kernel_events:
+        launch_ms = k_ms / k_n
+        gbs = alg_bytes / (launch_ms * 1e-3) / 1e9
+        tfl = alg_flops / (launch_ms * 1e-3) / 1e12
+        traffic = measured_traffic("fused_kernel_config4_hbm_traffic.txt", "traffic_bytes_per_launch")
+        out["roofline"] = {
+            "bound": "hbm", "kernel": "gdn_fused_kernel (one launch per step)",
+            "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+            # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size),
+            # read from the committed summary of the same command; None when that file is absent
+            "traffic": traffic,
+            "avg_launch_ms": launch_ms, "launches": k_n,
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "bytes_per_token_head": BYTES_TOKEN_HEAD, "token_heads_per_launch": th,
+            "state_bytes_per_launch": state_moves * STATE_BYTES,
+            "flop_per_byte": alg_flops / alg_bytes, "ridge_flop_per_byte": PEAK_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS,
+            "mfma_view": {"achieved": tfl, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": tfl / PEAK_MFMA_TFLOPS,
+                          "flop_per_token_head": FLOP_PREP + FLOP_RECUR,
+                          "at_hbm_peak_frac": PEAK_HBM_GBS * 1e9 * (alg_flops / alg_bytes) / 1e12 / PEAK_MFMA_TFLOPS},
+            "host_ms_per_step_outside_the_kernel": ms - launch_ms,
+        }
+    if args.main_only:
+        return out, None
+
+    # ---- the same step with bf16 outputs (a throughput variant with its own tolerance, 2e-3 + 2^-8: o in fp32 is 40 % of
+    #      the algorithmic bytes)
+    try:
+        o16 = torch.empty(step.o.shape, dtype=torch.bfloat16, device=dev)
+        s16 = dataclasses.replace(step, o=o16, shape=B.make_shape(step.L, step.H, step.H, step.d, step.d, "bf16", "bf16", step.T))
+        for _ in range(2):
+            s16.run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            s16.run()
+        torch.cuda.synchronize()
+        ms16 = 1e3 * (time.perf_counter() - t0) / 5
+        b16 = th * BYTES_TOKEN_HEAD_BF16_O + state_moves * STATE_BYTES
+        out["bf16_outputs"] = {"ms_per_step": ms16, "tokens_per_s": step.T / (ms16 * 1e-3), "algorithmic_bytes": b16,
+                               "achieved_gbs": b16 / (ms16 * 1e-3) / 1e9, "frac_of_hbm_peak": b16 / (ms16 * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                               "mfma_frac": alg_flops / (ms16 * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS,
+                               "note": "whole call on the host clock; same step with o stored as bf16"}
+        del o16, s16
+    except Exception as exc:
+        out["bf16_outputs"] = {"error": str(exc)}
+
+    # ---- the oracle on the host cores: a bounded, seeded subsample of the same step (every layer and head of 16
+    #      requests, then layer 0 of the other requests until about 20 s are spent)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import gdn_oracle as orc
+        rng = np.random.default_rng(4004)
+        picks = sorted(int(x) for x in rng.choice(step.n_req, size=16, replace=False))
+        jobs = [(r, list(range(step.L))) for r in picks] + [(r, [0]) for r in range(step.n_req) if r not in picks]
+        subs = []
+        for r, layers in jobs:                       # host copies made outside the timed loop
+            sub = step.host_request(r, layers)
+            start = step.pool[int(step.src_slot[r])][layers].cpu().numpy()[None]
+            subs.append((sub, start))
+        orc.resume_prefill(*subs[0][0].streams.slice(0, 64).fields(), [0, 64], [0], [-1], [0, 0], [])      # load + warm
+        tc0 = time.perf_counter()
+        th_cpu = n_done = 0
+        for sub, start in subs:
+            orc.resume_prefill(*sub.streams.fields(), sub.cu_seqlens, sub.start_pos, [0], sub.emit_cu, sub.emit_pos,
+                               state_src=start)
+            th_cpu += sub.total_tokens * sub.L * sub.H_v
+            n_done += 1
+            if time.perf_counter() - tc0 > 20.0:
+                break
+        tc1 = time.perf_counter()
+        per_token = step.L * step.H                   # token.heads one suffix token costs in this workload
+        cpu = {
+            "value": th_cpu / per_token / (tc1 - tc0), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{n_done} of {len(subs)} oracle calls on the same step's inputs: all 8 layers x 16 heads of 16 seeded requests, "
+                      f"then layer 0 of the other requests; {th_cpu} token.heads in {tc1 - tc0:.1f} s; fp64 token loop, one (layer, head) "
+                      f"chain per thread; tokens/s = token.heads/s / {per_token} (a token passes 8 layers x 16 heads)",
+            "token_heads_per_s": th_cpu / (tc1 - tc0), "seconds": tc1 - tc0,
+        }
+    del step
+    torch.cuda.empty_cache()
+    return out, cpu
+
+
+def bench_config1(args, torch, B, wl, dev):
+    """configs[1], batch 1: latency bound by construction (16 chains of up to 128 dependent chunk steps)."""
+    from paper_2605_05219_amd.device_call import GpuCall
+    steps, warmup = args.latency_steps, 16
     # ---- the cache entry and the requests (host side, seeded)
     sc = wl.config1(B.gdn_deepest_ckpt, seed=SEED, n_draws=N_DRAWS, N=N_PREFIX, M=M_CKPT, H=HEADS, d=D)
     n_slots = M_CKPT + M_CKPT + 1
@@ -101,7 +233,7 @@ def main() -> int:
     def step(i):
         calls[i % N_DRAWS].run()
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
 
@@ -110,7 +242,7 @@ def main() -> int:
             B.gdn_profile_enable(True)
         torch.cuda.synchronize()
         ta = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(steps):
             step(i)
         torch.cuda.synchronize()
         tb = time.perf_counter()
@@ -118,59 +250,34 @@ def main() -> int:
             return tb - ta, 0.0, 0.0, 0, 0
         p_ms, r_ms, n_prof, p_n, r_n = B.gdn_profile_collect()
         B.gdn_profile_enable(False)
-        assert n_prof == args.steps
+        assert n_prof == steps
         return tb - ta, p_ms, r_ms, p_n, r_n
 
     # The timed region; the per-kernel durations come from HIP events the library records on the
     # launch stream between its kernels, by default in an immediate repeat of the same steps so
     # that the events' own cost stays out of `value`.
     events_wall = None
-    if args.no_kernel_events:
-        wall_s, prep_ms, recur_ms, prep_n, recur_n = timed(False)
-    elif args.events_in_timed_region:
-        wall_s, prep_ms, recur_ms, prep_n, recur_n = timed(True)
-        events_wall = wall_s
-    else:
-        wall_s = timed(False)[0]
-        events_wall, prep_ms, recur_ms, prep_n, recur_n = timed(True)
+    wall_s = timed(False)[0]
+    events_wall, prep_ms, recur_ms, prep_n, recur_n = timed(True)
 
-    tokens = sum(suffix[i % N_DRAWS] for i in range(args.steps))
+    tokens = sum(suffix[i % N_DRAWS] for i in range(steps))
     wall = wall_s
-    value = tokens / wall
     token_heads = tokens * HEADS
-
     out = {
-        "metric": "recomputed suffix tokens/sec/GPU (resume+ckpt emit)",
-        "value": value,
-        "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": 1e3 * wall / args.steps,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f16",
-        "data": "synthetic",
-        "config": {
-            "workload": "configs[1]: 1 layer, batch 1, 16 heads, d_k=d_v=128, N=8192, M=16 checkpoints at 512 i, "
-                        "depth ~ U[0,N), bf16 inputs, fp32 state and outputs",
-            "draws": N_DRAWS, "seed": SEED,
-            "depths": [int(x) for x in r.meta["depths"]],
-            "suffix_tokens": suffix,
-            "mean_suffix_tokens": float(np.mean(suffix)),
-            "emits_per_step": float(np.mean([int(r.emit_cu[i + 1] - r.emit_cu[i]) for i in range(N_DRAWS)])),
-            "chunk": C,
-        },
+        "workload": "configs[1]: 1 layer, batch 1, 16 heads, d_k=d_v=128, N=8192, M=16 checkpoints at 512 i, depth ~ U[0,N), "
+                    "bf16 inputs, fp32 state and outputs; a step is one request",
+        "tokens_per_s": tokens / wall, "ms_per_step": 1e3 * wall / steps, "steps": steps,
+        "draws": N_DRAWS, "seed": SEED, "depths": [int(x) for x in r.meta["depths"]], "suffix_tokens": suffix,
+        "mean_suffix_tokens": float(np.mean(suffix)),
+        "emits_per_step": float(np.mean([int(r.emit_cu[i + 1] - r.emit_cu[i]) for i in range(N_DRAWS)])),
     }
-
-    if not args.no_kernel_events:
+    if True:
         # A step prepares its first slab (32 chunk rounds) in a launch of its own; every recurrence launch
         # but the last also prepares the next slab (gdn_quad_overlap_kernel).  The recurrence launches are
         # therefore priced at the recurrence's flops of every token plus the preparation's flops of the
         # tokens beyond the first slab; the preparation launches at the first slab's preparation flops.
-        step_suffix = [suffix[i % N_DRAWS] for i in range(args.steps)]
-        slabs_ok = recur_n == sum(-(-t // SLAB_TOKENS) for t in step_suffix) and prep_n == args.steps
+        step_suffix = [suffix[i % N_DRAWS] for i in range(steps)]
+        slabs_ok = recur_n == sum(-(-t // SLAB_TOKENS) for t in step_suffix) and prep_n == steps
         later = sum(max(0, t - SLAB_TOKENS) for t in step_suffix) * HEADS if slabs_ok else 0
         first = token_heads - later
         rec_dom = recur_ms >= prep_ms
@@ -178,7 +285,9 @@ def main() -> int:
         dom_ms, dom_n = (recur_ms, recur_n) if rec_dom else (prep_ms, prep_n)
         dom_flops_total = token_heads * FLOP_RECUR + later * FLOP_PREP if rec_dom else first * FLOP_PREP
         dom_flop = dom_flops_total / token_heads
-        dom_traffic = TRAFFIC_RECUR if rec_dom else TRAFFIC_PREP
+        # measured HBM bytes per token.head of these launches (rocprofv3 --pmc, committed summary), or None
+        dom_traffic = measured_traffic("prefill_kernels_config1_hbm_traffic.txt",
+                                       "recurrence_launch_bytes_per_token_head" if rec_dom else "first_preparation_launch_bytes_per_token_head")
         units_per_launch = token_heads / dom_n
         achieved = dom_flops_total / (dom_ms * 1e-3) / 1e12
         out["roofline"] = {
@@ -206,23 +315,18 @@ def main() -> int:
                 "ridge_flop_per_byte": PEAK_MFMA_TFLOPS * 1e3 / PEAK_HBM_GBS,
             }
         out["kernels"] = {
-            "gdn_prep_kernel": {"avg_ms": prep_ms / args.steps, "launches": prep_n,
+            "gdn_prep_kernel": {"avg_ms": prep_ms / steps, "launches": prep_n,
                                 "avg_launch_ms": prep_ms / max(prep_n, 1),
                                 "tflops": first * FLOP_PREP / (prep_ms * 1e-3) / 1e12},
-            "gdn_recur_kernel": {"avg_ms": recur_ms / args.steps, "launches": recur_n,
+            "gdn_recur_kernel": {"avg_ms": recur_ms / steps, "launches": recur_n,
                                  "avg_launch_ms": recur_ms / max(recur_n, 1),
                                  "tflops": (token_heads * FLOP_RECUR + later * FLOP_PREP) / (recur_ms * 1e-3) / 1e12},
             "token_heads_prepared_in_recurrence_launches": later,
             "both_kernels_hbm_gbs_algorithmic": token_heads * BYTES_TOKEN_HEAD / ((prep_ms + recur_ms) * 1e-3) / 1e9,
-            "events": "same steps, inside the timed region" if args.events_in_timed_region
-                      else "immediate repeat of the timed steps",
-            "ms_per_step_with_events": 1e3 * events_wall / args.steps,
-            "other_ms_per_step_with_events": 1e3 * events_wall / args.steps - (prep_ms + recur_ms) / args.steps,
+            "events": "immediate repeat of the timed steps",
+            "ms_per_step_with_events": 1e3 * events_wall / steps,
+            "other_ms_per_step_with_events": 1e3 * events_wall / steps - (prep_ms + recur_ms) / steps,
         }
-
-    if args.main_only:
-        print(json.dumps(out))
-        return 0
 
     # ---- latency against suffix length (Sec. 6, overhead decomposition: the resume cost is a small constant
     #      for loading the checkpoint plus a term linear in the replayed suffix): every draw timed on its own
@@ -247,6 +351,18 @@ def main() -> int:
         }
     except Exception as exc:
         out["latency_vs_suffix"] = {"error": str(exc)}
+
+    return out, calls, pool, suffix
+
+
+def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms):
+    """Side objects: pool copies, host tier, decode step, layer front/back end, attention side, optional sweeps."""
+    from paper_2605_05219_amd.device_call import GpuCall
+    out = {}
+    r_steps = args.latency_steps
+
+    def step(i):
+        calls[i % N_DRAWS].run()
 
     # ---- standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB each way
     try:
@@ -294,10 +410,10 @@ def main() -> int:
             host_step(i)
         torch.cuda.synchronize()
         ta = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(r_steps):
             host_step(i)
         torch.cuda.synchronize()
-        host_ms = 1e3 * (time.perf_counter() - ta) / args.steps
+        host_ms = 1e3 * (time.perf_counter() - ta) / r_steps
         n_f = 64
         stage_f = torch.empty((n_f,) + tuple(pool.shape[1:]), dtype=torch.float32, device=dev)
         big_host = torch.randn((n_f,) + tuple(pool.shape[1:]), dtype=torch.float32).pin_memory()
@@ -311,7 +427,7 @@ def main() -> int:
         f_s = (time.perf_counter() - ta) / 4
         out["host_tier"] = {
             "ms_per_step_pool_in_pinned_host_memory": host_ms,
-            "ms_per_step_pool_in_hbm": 1e3 * wall / args.steps,
+            "ms_per_step_pool_in_hbm": wall_cfg1_ms,
             "state_bytes": int(pool[0].numel() * 4),
             "fetch_gbs": n_f * pool[0].numel() * 4 / f_s / 1e9,
             "draws_that_load_a_state": int(sum(int(c.call.src_slot[0]) >= 0 for c in calls)),
@@ -350,77 +466,6 @@ def main() -> int:
         del dpool
     except Exception as exc:
         out["decode_step"] = {"error": str(exc)}
-
-    # ---- throughput regime (not the bench line): a configs[4]-shaped serving step -- 256 requests of log-uniform
-    #      suffix length through 8 independent layers x 16 heads, start states gathered by slot id from a 4096-slot
-    #      (32 GiB) pool, states stored every 1024 positions and at the end; inputs generated on the device
-    try:
-        from paper_2605_05219_amd import workloads as wl4
-        n_rq4, L4, n_slots4 = 256, 8, 4096
-        free_b, _ = torch.cuda.mem_get_info()
-        rng4 = np.random.default_rng(1004)
-        lens4 = wl4.lengths_log_uniform(rng4, n_rq4, 64, 8192)
-        starts4 = (rng4.integers(1, 64, size=n_rq4) * 128).astype(np.int32)
-        ids4 = rng4.permutation(n_slots4)
-        T4 = int(lens4.sum())
-        need4 = n_slots4 * L4 * HEADS * D * D * 4 + L4 * T4 * HEADS * (3 * D * 2 + D * 4 + 4) + (8 << 30)
-        if free_b < need4:
-            raise RuntimeError(f"needs {need4 >> 30} GiB of device memory, {free_b >> 30} free")
-        rule4 = wl4.emit_every(1024)
-        cu4 = np.concatenate([[0], np.cumsum(lens4)]).astype(np.int32)
-        epos4, ecu4, eslot4, nxt4 = [], [0], [], n_rq4
-        for r in range(n_rq4):
-            e = rule4(int(starts4[r]), int(starts4[r] + lens4[r]))
-            epos4 += e
-            ecu4.append(len(epos4))
-            eslot4 += [int(x) for x in ids4[nxt4:nxt4 + len(e)]]
-            nxt4 += len(e)
-        g4 = torch.Generator(device=dev)
-        g4.manual_seed(1004)
-        rn4 = lambda *sh: torch.randn(sh, device=dev, generator=g4, dtype=torch.float32)
-        q4 = torch.empty((L4, T4, HEADS, D), dtype=torch.bfloat16, device=dev)
-        k4, v4 = torch.empty_like(q4), torch.empty_like(q4)
-        for l in range(L4):
-            q4[l] = torch.nn.functional.normalize(rn4(T4, HEADS, D), dim=-1).bfloat16()
-            k4[l] = torch.nn.functional.normalize(rn4(T4, HEADS, D), dim=-1).bfloat16()
-            v4[l] = rn4(T4, HEADS, D).bfloat16()
-        b4 = torch.sigmoid(rn4(L4, T4, HEADS)).bfloat16()
-        a4 = torch.exp(-torch.nn.functional.softplus(rn4(L4, T4, HEADS))).bfloat16()
-        pool4 = torch.empty((n_slots4, L4, HEADS, D, D), dtype=torch.float32, device=dev)
-        for s0 in range(0, n_slots4, 256):
-            pool4[s0:s0 + 256] = rn4(256, L4, HEADS, D, D) * 0.1
-        o4 = torch.empty((L4, T4, HEADS, D), dtype=torch.float32, device=dev)
-        shape4 = B.make_shape(L4, HEADS, HEADS, D, D, "bf16", "f32", T4)
-        ws4 = torch.empty(B.gdn_workspace_bytes(shape4, n_rq4, T4, len(epos4)), dtype=torch.uint8, device=dev)
-
-        def run4():
-            B.gdn_resume_prefill(shape4, q4, k4, v4, b4, a4, cu4, starts4, pool4, ids4[:n_rq4].astype(np.int32), ecu4, epos4, pool4,
-                                 eslot4, o4, ws4)
-
-        run4()
-        torch.cuda.synchronize()
-        reps4 = 3
-        t40 = time.perf_counter()
-        for _ in range(reps4):
-            run4()
-        torch.cuda.synchronize()
-        ms4 = 1e3 * (time.perf_counter() - t40) / reps4
-        th4 = T4 * L4 * HEADS
-        bytes4 = th4 * BYTES_TOKEN_HEAD + (n_rq4 + len(epos4)) * L4 * HEADS * D * D * 4
-        out["throughput"] = {
-            "workload": "configs[4]: 256 requests x 8 layers x 16 heads, d=128, bf16, suffix ~ logU[64,8192], pool of 4096 slots",
-            "tokens_per_layer": T4, "chains": n_rq4 * L4 * HEADS, "emits": len(epos4), "ms_per_call": ms4,
-            "tokens_per_s": T4 / (ms4 * 1e-3), "token_layers_per_s": T4 * L4 / (ms4 * 1e-3),
-            "hbm": {"algorithmic_bytes": bytes4, "achieved_gbs": bytes4 / (ms4 * 1e-3) / 1e9, "peak_gbs": PEAK_HBM_GBS,
-                    "frac": bytes4 / (ms4 * 1e-3) / 1e9 / PEAK_HBM_GBS},
-            "mfma": {"achieved_tflops": th4 * (FLOP_PREP + FLOP_RECUR) / (ms4 * 1e-3) / 1e12, "peak_tflops": PEAK_MFMA_TFLOPS,
-                     "frac": th4 * (FLOP_PREP + FLOP_RECUR) / (ms4 * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
-            "note": "whole call on the host clock (planning, plan upload, kernels); the library picks the fused kernel here",
-        }
-        del q4, k4, v4, b4, a4, pool4, o4, ws4
-        torch.cuda.empty_cache()
-    except Exception as exc:
-        out["throughput"] = {"error": str(exc)}
 
     # ---- optional: one call of k requests (k configs[1]-style draws packed together), to show how the variant
     #      choice (latency variant, two or four slices per workgroup, fused kernel) behaves between the
@@ -517,16 +562,16 @@ def main() -> int:
             attn_step(i)
         torch.cuda.synchronize()
         ta0 = time.perf_counter()
-        for i in range(args.steps):
+        for i in range(r_steps):
             attn_step(i)
         torch.cuda.synchronize()
-        a_ms = 1e3 * (time.perf_counter() - ta0) / args.steps
-        a_tok = sum(suffix[i % N_DRAWS] for i in range(args.steps))
+        a_ms = 1e3 * (time.perf_counter() - ta0) / r_steps
+        a_tok = sum(suffix[i % N_DRAWS] for i in range(r_steps))
         # (query, key) pairs inside the causal limit; 4 d flops each (two contractions)
         pairs = sum(suffix[i % N_DRAWS] * starts[i % N_DRAWS] + suffix[i % N_DRAWS] * (suffix[i % N_DRAWS] + 1) // 2
-                    for i in range(args.steps))
-        a_tf = 4.0 * D * pairs * HEADS / (a_ms * 1e-3 * args.steps) / 1e12
-        out["attention"] = {"ms_per_step": a_ms, "tokens_per_s": a_tok / (a_ms * 1e-3 * args.steps), "TFLOPs": a_tf,
+                    for i in range(r_steps))
+        a_tf = 4.0 * D * pairs * HEADS / (a_ms * 1e-3 * r_steps) / 1e12
+        out["attention"] = {"ms_per_step": a_ms, "tokens_per_s": a_tok / (a_ms * 1e-3 * r_steps), "TFLOPs": a_tf,
                             "peak_TFLOPs": PEAK_MFMA_TFLOPS, "frac": a_tf / PEAK_MFMA_TFLOPS,
                             "heads": [HEADS, HKV], "d": D,
                             "note": "attn_suffix_prefill on the same draws (append + attention [+ merge of split key walks]); "
@@ -536,7 +581,7 @@ def main() -> int:
     except Exception as exc:
         out["attention"] = {"error": str(exc)}
 
-    # ---- a whole cache hit on a layer group as in the paper's runtime experiment (Sec. 5: one full attention layer
+    # ---- a whole cache hit on a layer group as in the paper's runtime experiment (Sec. 6, prototype wall-clock time: one full attention layer
     #      and three GatedDeltaNet layers; projections excluded): checkpoint states and the attention KV prefix are
     #      restored from pinned host memory, then the suffix runs through the layers' front ends, the resumed
     #      recurrence (3 layers in one call, downstream checkpoints stored), the back ends and the attention layer.
@@ -628,28 +673,62 @@ def main() -> int:
     except Exception as exc:
         out["ceilings"] = {"error": str(exc)}
 
-    # ---- the oracle on the host cores, same workload (all draws once)
-    if not args.no_cpu_baseline:
-        from oracle import gdn_oracle as orc
-        pool_host = pool.cpu().numpy()
-        s0 = calls[0].call
-        orc.resume_prefill(*s0.streams.slice(0, 64).fields(), [0, 64], [0], [-1], [0, 0], [])  # load + warm
-        tc0 = time.perf_counter()
-        cpu_tokens = cpu_calls = 0
-        while time.perf_counter() - tc0 < 10.0:      # about 10 s of CPU work, whole draws only
-            cc = calls[cpu_calls % N_DRAWS].call
-            orc.resume_prefill(*cc.streams.fields(), cc.cu_seqlens, cc.start_pos, cc.src_slot, cc.emit_cu,
-                               cc.emit_pos, state_src=pool_host)
-            cpu_tokens += cc.total_tokens
-            cpu_calls += 1
-        tc1 = time.perf_counter()
-        out["cpu_baseline"] = {
-            "value": cpu_tokens / (tc1 - tc0), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"the same {N_DRAWS} draws cycled for about 10 s: {cpu_calls} requests, {cpu_tokens} suffix tokens "
-                      f"x {HEADS} heads; fp64 token loop, one (layer, head) chain per thread",
-            "seconds": tc1 - tc0,
-        }
+    return out
 
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--latency-steps", type=int, default=64, help="steps of the configs[1] side measurement")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed steps and their event pass (no side objects, no CPU baseline): what the "
+                         "profiler runs use")
+    ap.add_argument("--latency-only", action="store_true",
+                    help="only the configs[1] side measurement (what the profiler runs of the latency kernels use)")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time ONE call of k = 1..64 configs[1]-style requests (side object `batch_sweep`; about "
+                         "a minute of host-side input generation)")
+    ap.add_argument("--layer-group", action="store_true",
+                    help="also time a whole cache hit on a layer group (3 GatedDeltaNet layers + 1 attention layer, "
+                         "checkpoint and KV cache restored from pinned host memory) against the suffix length")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="skip the per-kernel HIP event pass (no roofline object)")
+    ap.add_argument("--events-in-timed-region", action="store_true",
+                    help="record the per-kernel events inside the timed steps themselves instead of in a "
+                         "repeat of them (the events cost some microseconds per launch)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2605_05219_amd import binding as B, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    if args.latency_only:
+        lat, _, _, _ = bench_config1(args, torch, B, wl, dev)
+        print(json.dumps({"latency": lat}))
+        return 0
+
+    out, cpu = bench_config4(args, torch, B, dev)
+    if args.main_only:
+        print(json.dumps(out))
+        return 0
+    try:
+        lat, calls, pool, suffix = bench_config1(args, torch, B, wl, dev)
+        out["latency"] = lat
+        out.update(side_measurements(args, torch, B, wl, dev, calls, pool, suffix, lat["ms_per_step"]))
+    except Exception as exc:       # side measurements never lose the main line
+        out["latency"] = {"error": repr(exc)}
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
     return 0
 

@@ -6,8 +6,8 @@
  *
  * Why it belongs to the path: the paper's hybrid runs keep the full attention KV cache beside
  * the sparse recurrent checkpoints (Table 1, caption), count the load of the cached keys and values as
- * the third part of a hit's cost (Sec. 5, overhead decomposition), and time a layer group with
- * one full attention layer (Sec. 5, runtime experiment).  The paper does not restate attention;
+ * the third part of a hit's cost (Sec. 6, overhead decomposition), and time a layer group with
+ * one full attention layer (Sec. 6, prototype wall-clock time).  The paper does not restate attention;
  * what is computed is causal softmax attention of the recomputed suffix over the restored prefix:
  *
  *   request r resumed at position c = start_pos[r] (keys / values 1..c already in its cache
@@ -54,7 +54,7 @@ int64_t attn_workspace_bytes(const attn_shape *shape, int32_t n_req, int64_t tot
 
 /*
  * Restore the cached prefix of n_req requests from a HOST pool with the same slot layout
- * (Sec. 5, overhead decomposition, part iii): rows 0 .. prefix_len[r]-1 of host slot
+ * (Sec. 6, overhead decomposition, part iii): rows 0 .. prefix_len[r]-1 of host slot
  * host_slot[r] go to the same rows of device slot seq_slot[r], k and v, as asynchronous copies
  * on `stream` (pinned host memory lets them overlap; pageable memory works but blocks the
  * host).  Bit-exact.
@@ -88,9 +88,9 @@ int32_t attn_kv_spill(const attn_shape *shape, int32_t n_req, const int32_t *n_r
  * every suffix token over positions 1 .. its own (two launches on `stream`; three when the call
  * is small enough for key walks of 1024 keys and more to be split over workgroups, after which a
  * merge pass writes o).  Results do not depend on the batch a request is packed with as long as
- * its walk is not split.  Environment (read at every call): ATTN_NO_SPLIT=1 keeps every walk whole;
- * ATTN_NO_PACK=1 keeps one query head per workgroup also where suffixes are short (otherwise the
- * heads of a key/value group then share a workgroup's rows; results are bitwise the same either way).
+ * its walk is not split.  attn_tune_split(0) keeps every walk whole; attn_tune_pack(0) keeps one
+ * query head per workgroup also where suffixes are short (otherwise the heads of a key/value group
+ * then share a workgroup's rows; results are bitwise the same either way).
  *   q            device, bf16, [T][H_q][d] (T = cu_seqlens[n_req]);  k_new, v_new: [T][H_kv][d]
  *   out_gate     device, bf16, [T][H_q][d], or NULL (no gate)
  *   cu_seqlens   host, n_req + 1;  start_pos: host, n_req, the restored prefix length c >= 0
@@ -124,6 +124,15 @@ int32_t attn_plan(const attn_shape *shape, int32_t n_req, const int32_t *cu_seql
                   int32_t *unit_req, int32_t *unit_tile, int32_t *unit_t0, int32_t *unit_t1,
                   int32_t *unit_part, int32_t *n_units, int32_t *heads_per_row_group,
                   int32_t *key_tile_rows);
+
+/*
+ * Tuning knobs (not steps of the method; for tests and experiments).  attn_tune_split(0) forbids
+ * cutting long key walks into parts, attn_tune_pack(0) forbids packing the query heads of a
+ * key/value group into one workgroup's rows; a non-zero argument restores the automatic choice.
+ * Each returns its previous setting (1 = automatic).  Process-wide; read at every call.
+ */
+int32_t attn_tune_split(int32_t allow);
+int32_t attn_tune_pack(int32_t allow);
 
 #ifdef __cplusplus
 }

@@ -6,7 +6,7 @@
  *
  * Why it belongs to the path: the paper's method applies to layers whose hidden state can be
  * taken out and put back without loss (Sec. 1), and it times a layer group with GatedDeltaNet
- * layers (Sec. 5, runtime experiment).  Besides the matrix state S, such a layer carries the last K-1 inputs of
+ * layers (Sec. 6, prototype wall-clock time).  Besides the matrix state S, such a layer carries the last K-1 inputs of
  * its short convolution; a resumed request is exact only if those rows are checkpointed and
  * restored with S.  The paper does not restate the layer; what is computed is the published
  * GatedDeltaNet layer (projections excluded: they are plain GEMMs):
@@ -80,8 +80,8 @@ int64_t gdn_layer_workspace_bytes(int32_t n_req, int32_t n_emit);
  *   workspace   device, 16-byte aligned, >= gdn_layer_workspace_bytes(n_req, n_emit)
  * Errors: GDN_ERR_NULL, _ALIGN (pointers and slot strides 16-byte aligned), _SHAPE (also a slot
  * smaller than L (K-1) C), _SEQLENS (also more tokens than T_alloc),
- * _START, _EMIT, _SLOT_RANGE, _SLOT_DUP, _SLOT_HAZARD (conv_dst == conv_src and an emit slot is
- * any request's source slot: the launch reads and writes concurrently), _WORKSPACE, _COUNT.
+ * _START, _EMIT, _SLOT_RANGE, _SLOT_DUP, _SLOT_HAZARD (an emit slot overlaps, by address, any
+ * request's source slot: the launch reads and writes concurrently), _WORKSPACE, _COUNT.
  * A request of length 0 is legal: its states at start_pos[r] cannot be asked for (the emit
  * interval is empty).
  */

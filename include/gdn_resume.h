@@ -47,7 +47,7 @@ enum {
     GDN_ERR_SEQLENS = -4,     /* cu_seqlens not starting at 0, decreasing, or beyond T_alloc */
     GDN_ERR_SLOT_RANGE = -5,  /* a slot id outside its pool (sources may be -1) */
     GDN_ERR_SLOT_DUP = -6,    /* two states written to the same destination slot */
-    GDN_ERR_SLOT_HAZARD = -7, /* a destination slot is another request's source slot in the same pool */
+    GDN_ERR_SLOT_HAZARD = -7, /* a destination slot overlaps (by address) a source slot that is not the writer's own */
     GDN_ERR_EMIT = -8,        /* emit positions not strictly increasing inside (start, end] */
     GDN_ERR_WORKSPACE = -9,   /* workspace NULL, misaligned or too small */
     GDN_ERR_START = -10,      /* negative start position, or positions overflowing int32 */
@@ -108,6 +108,16 @@ int64_t gdn_workspace_bytes(const gdn_shape *shape, int32_t n_req, int64_t total
                             int32_t n_emit);
 
 /*
+ * The smaller workspace that suffices when the call is served by the fused kernel (bf16 inputs,
+ * d_k = d_v = 128: preparation and recurrence of a chain in one workgroup, see gdn_tune_fused):
+ * the chunk plan only.  A call given at least this much but less than gdn_workspace_bytes runs
+ * the fused kernel whatever the library's estimate says; for other shapes the value equals
+ * gdn_workspace_bytes.  Negative on error.
+ */
+int64_t gdn_workspace_bytes_fused(const gdn_shape *shape, int32_t n_req, int64_t total_tokens,
+                                  int32_t n_emit);
+
+/*
  * Checkpoint load (Sec. 6, overhead decomposition, item (i): loading the stored checkpoint),
  * here from a pool in HBM:  dst[i] = pool[slot_ids[i]] for i < n, zeros when slot_ids[i] == -1.
  *   pool      device, fp32, n_slots slots at slot_stride floats
@@ -150,9 +160,11 @@ int32_t ckpt_scatter(float *pool, int64_t slot_stride, int32_t n_slots,
  *   emit_pos    host int32 [n_emit]: absolute positions, strictly increasing per request,
  *               inside (start_pos[r], start_pos[r] + len_r]
  *   state_dst   device fp32 pool written with the emitted states (may equal state_src)
- *   emit_slot   host int32 [n_emit] in [0, dst_n_slots), all distinct; when state_dst and
- *               state_src are the same pool, a destination may not be the source slot of a
- *               different request of this call
+ *   emit_slot   host int32 [n_emit] in [0, dst_n_slots), all distinct.  Source and destination
+ *               slots are compared by address (the pools may be the same memory, also under
+ *               different base pointers): a destination may be the writer's own source slot
+ *               (the very same memory), any other overlap with a source slot read by this call
+ *               is GDN_ERR_SLOT_HAZARD
  *   o           device, written for every packed token
  *   workspace   device, 256-byte aligned, at least gdn_workspace_bytes(...) bytes; contents
  *               are scratch, nothing is carried between calls
@@ -278,14 +290,6 @@ int32_t gdn_tune_slab_rounds(int32_t rounds);
  * differ in rounding.  Returns the previous setting (-1 = automatic).
  */
 int32_t gdn_tune_fused(int32_t mode);
-
-/*
- * Environment variables, read once per process, for experiments only (results meet the same
- * tolerances under every setting): GDN_FUSED=0|1 as gdn_tune_fused; GDN_NO_OVERLAP (any value)
- * keeps the preparation of a slab out of the previous slab's recurrence launch;
- * GDN_RECUR_WAVES=1|2|4 forces the value-head slices per recurrence workgroup; GDN_NO_RING
- * (any value) keeps the register-staged recurrence kernel where the LDS-ring one would run.
- */
 
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);

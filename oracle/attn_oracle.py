@@ -5,8 +5,8 @@ a library matmul as the only primitive; it shares no code with the library.
 
 The paper's hybrid runs keep the full attention KV cache next to the sparse recurrent checkpoints
 (Table 1, caption) and name the load of the attention layers' cached keys and values as the third
-part of a cache hit's cost (Sec. 5, overhead decomposition); its timed layer group holds one full
-attention layer (Sec. 5, runtime experiment).  The paper does not restate attention.  What is
+part of a cache hit's cost (Sec. 6, overhead decomposition); its timed layer group holds one full
+attention layer (Sec. 6, prototype wall-clock time).  The paper does not restate attention.  What is
 computed is causal softmax attention of the recomputed suffix over the restored prefix:
 
   a request resumed at position c (keys and values 1..c restored from the cache) with suffix

@@ -4,7 +4,7 @@ Only tests/ may import this module.  Plain numpy, fp64, every function the defin
 out with explicit loops over tokens and taps; it shares no code with the library.
 
 The paper's method applies to layers whose hidden state can be taken out and put back without loss (Sec. 1)
-and measures a layer group with GatedDeltaNet layers (Sec. 5, runtime experiment) without
+and measures a layer group with GatedDeltaNet layers (Sec. 6, prototype wall-clock time) without
 restating the layer.  What is computed here is the published GatedDeltaNet layer around the
 recurrence, in the notation of the recurrence oracle (positions 1-based, state "at" position c
 = after consuming tokens 1..c):

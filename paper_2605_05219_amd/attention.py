@@ -7,7 +7,8 @@ from .binding import GDN_BF16, GDN_F32, _check, _dp, _h32, _hp, _stream_ptr, lib
 
 _i32, _i64, _vp, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_float
 
-EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_kv_spill", "attn_suffix_prefill", "attn_plan"]
+EXPORTS = ["attn_workspace_bytes", "attn_kv_restore", "attn_kv_spill", "attn_suffix_prefill", "attn_plan", "attn_tune_split",
+           "attn_tune_pack"]
 
 
 class attn_shape(ctypes.Structure):
@@ -38,8 +39,21 @@ def _lib():
                                           + [_vp, _vp, _i64, _i32, _i32, _vp] + [_vp, _vp, _i64, _vp])
         L.attn_plan.restype = _i32
         L.attn_plan.argtypes = [ctypes.POINTER(attn_shape), _i32, _vp, _vp, _i32] + [_vp] * 8
+        for f in (L.attn_tune_split, L.attn_tune_pack):
+            f.restype = _i32
+            f.argtypes = [_i32]
         _ready = True
     return L
+
+
+def attn_tune_split(allow: bool) -> bool:
+    """False: key walks are never cut into parts; True: automatic.  Returns the previous setting."""
+    return bool(_lib().attn_tune_split(1 if allow else 0))
+
+
+def attn_tune_pack(allow: bool) -> bool:
+    """False: one query head per workgroup always; True: automatic.  Returns the previous setting."""
+    return bool(_lib().attn_tune_pack(1 if allow else 0))
 
 
 def attn_workspace_bytes(shape: attn_shape, n_req: int, total_tokens: int) -> int:

@@ -69,6 +69,8 @@ def lib():
         L.gdn_plan_chunks.argtypes = [_i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32]
         L.gdn_workspace_bytes.restype = _i64
         L.gdn_workspace_bytes.argtypes = [ctypes.POINTER(gdn_shape), _i32, _i64, _i32]
+        L.gdn_workspace_bytes_fused.restype = _i64
+        L.gdn_workspace_bytes_fused.argtypes = [ctypes.POINTER(gdn_shape), _i32, _i64, _i32]
         L.ckpt_gather.restype = _i32
         L.ckpt_gather.argtypes = [_vp, _i64, _i32, _vp, _i32, _vp, _i64, _i64, _vp]
         L.ckpt_scatter.restype = _i32
@@ -92,6 +94,7 @@ def lib():
 
 
 EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_profile_enable", "gdn_profile_collect", "gdn_probe_ceilings", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+           "gdn_workspace_bytes_fused",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
            "gdn_workspace_bytes_host", "gdn_resume_prefill_host"]
 
@@ -183,6 +186,12 @@ def gdn_plan_chunks(cu_seqlens, start_pos, emit_cu, emit_pos, capacity: Optional
 def gdn_workspace_bytes(shape: gdn_shape, n_req: int, total_tokens: int, n_emit: int) -> int:
     return _check(lib().gdn_workspace_bytes(ctypes.byref(shape), int(n_req), int(total_tokens), int(n_emit)),
                   "gdn_workspace_bytes")
+
+
+def gdn_workspace_bytes_fused(shape: gdn_shape, n_req: int, total_tokens: int, n_emit: int) -> int:
+    """The plan-only workspace that makes a call run the fused kernel (see include/gdn_resume.h)."""
+    return _check(lib().gdn_workspace_bytes_fused(ctypes.byref(shape), int(n_req), int(total_tokens), int(n_emit)),
+                  "gdn_workspace_bytes_fused")
 
 
 # ----------------------------------------------------------------------------- device entry points

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -104,6 +105,7 @@ hipError_t launch_combine_d(int d, const CombineArgs& a, unsigned blocks /* (pie
 
 // The work of one attn_suffix_prefill call (host, integer): how the rows of a workgroup are made up, the pieces
 // (row tiles of a request), the cut of long key walks into parts, and the units (whole walks or parts) in launch order.
+std::atomic<int32_t> g_allow_split{1}, g_allow_pack{1};   // attn_tune_split / attn_tune_pack
 struct Unit { int32_t req, tile, t0, t1, part; };
 struct UnitPlan {
     int pack = 1;                     // query heads per token in a workgroup's rows: 1, or H_q / H_kv
@@ -124,8 +126,7 @@ void build_units(const attn_shape& sh, int32_t n_req, const int32_t* len, const 
             rows_plain += (int64_t)((len[r] + ATT_BQ - 1) / ATT_BQ) * s->H_q;
             rows_packed += (int64_t)((len[r] + ATT_BQ / G - 1) / (ATT_BQ / G)) * s->H_kv;
         }
-        const char* no_pack = std::getenv("ATTN_NO_PACK");
-        if (rows_packed * 5 <= rows_plain * 4 && !(no_pack && no_pack[0] == '1')) pack = G;
+        if (rows_packed * 5 <= rows_plain * 4 && g_allow_pack.load() != 0) pack = G;
     }
     const int TPW = ATT_BQ / pack;        // tokens per workgroup
     const int HB = s->H_q / pack;         // head blocks (workgroups) per unit
@@ -142,8 +143,7 @@ void build_units(const attn_shape& sh, int32_t n_req, const int32_t* len, const 
     const int64_t n_items = (int64_t)pieces.size();
     // ---- too few workgroups for the chip: cut long key walks into parts
     int64_t split_wgs = 0;
-    const char* no_split = std::getenv("ATTN_NO_SPLIT");
-    if (n_items * HB < SPLIT_BELOW && !(no_split && no_split[0] == '1')) {
+    if (n_items * HB < SPLIT_BELOW && g_allow_split.load() != 0) {
         int64_t tp = std::max<int64_t>(SPLIT_MIN_KEYS / KT, (total_tiles * HB + SPLIT_BELOW - 1) / SPLIT_BELOW);
         for (;; tp *= 2) {
             split_wgs = 0;
@@ -423,5 +423,9 @@ int32_t attn_suffix_prefill(const attn_shape* s, const void* q, const void* k_ne
                               : launch_combine_d<uint16_t>(s->d, ca, (unsigned)(n_pieces * HB), stream);
     return hip_err(e);
 }
+
+int32_t attn_tune_split(int32_t allow) { return g_allow_split.exchange(allow != 0); }
+
+int32_t attn_tune_pack(int32_t allow) { return g_allow_pack.exchange(allow != 0); }
 
 }  // extern "C"

@@ -104,9 +104,22 @@ int32_t gdn_layer_inputs(const gdn_layer_shape* s, const void* x_qkv, const floa
             if (id < 0 || id >= n_dst_slots) return GDN_ERR_SLOT_RANGE;
         std::sort(sorted.begin(), sorted.end());
         if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return GDN_ERR_SLOT_DUP;
-        if (n_emit > 0 && any_src && conv_dst == conv_src)
-            for (int32_t r = 0; r < n_req; ++r)
-                if (src_slot[r] >= 0 && std::binary_search(sorted.begin(), sorted.end(), src_slot[r])) return GDN_ERR_SLOT_HAZARD;
+    }
+    if (n_emit > 0 && any_src && conv_src && conv_dst) {
+        // by address (the pools may be the same memory under different base pointers): no destination slot may
+        // overlap a source slot that this launch reads
+        const uintptr_t eb = (uintptr_t)elem_bytes(s->in_dtype), bytes = (uintptr_t)s->L * K1 * C * eb;
+        std::vector<uintptr_t> dlo((size_t)n_emit);
+        for (int32_t e = 0; e < n_emit; ++e)
+            dlo[(size_t)e] = reinterpret_cast<uintptr_t>(conv_dst) + (uintptr_t)emit_slot[e] * (uintptr_t)dst_slot_stride * eb;
+        std::sort(dlo.begin(), dlo.end());
+        for (int32_t r = 0; r < n_req; ++r) {
+            if (src_slot[r] < 0) continue;
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(conv_src) + (uintptr_t)src_slot[r] * (uintptr_t)src_slot_stride * eb;
+            auto it = std::upper_bound(dlo.begin(), dlo.end(), lo);
+            if (it != dlo.begin() && *(it - 1) + bytes > lo) return GDN_ERR_SLOT_HAZARD;
+            if (it != dlo.end() && *it < lo + bytes) return GDN_ERR_SLOT_HAZARD;
+        }
     }
     // ---- pointers
     if (T > 0 && (!x_qkv || !conv_w || !a_pre || !b_pre || !A_log || !dt_bias || !q || !k || !v || !beta || !gate))

@@ -71,33 +71,18 @@ int32_t plan_chunks(int32_t n_req, const int32_t* cu, const int32_t* start_pos,
 }
 
 int32_t check_slots(int32_t n_req, const int32_t* src_slot, int32_t src_n_slots,
-                    const int32_t* emit_cu, const int32_t* emit_slot, int32_t dst_n_slots,
-                    bool same_pool) {
+                    const int32_t* emit_cu, const int32_t* emit_slot, int32_t dst_n_slots) {
     if (n_req > 0 && !src_slot) return GDN_ERR_NULL;
     if (src_n_slots < 0 || dst_n_slots < 0) return GDN_ERR_COUNT;
     for (int32_t r = 0; r < n_req; ++r)
         if (src_slot[r] < -1 || src_slot[r] >= src_n_slots) return GDN_ERR_SLOT_RANGE;
     const int32_t n_emit = emit_cu[n_req];
     if (n_emit > 0 && !emit_slot) return GDN_ERR_NULL;
-    std::vector<std::pair<int32_t, int32_t>> dst;  // (slot, request)
-    dst.reserve(n_emit);
-    for (int32_t r = 0; r < n_req; ++r)
-        for (int32_t e = emit_cu[r]; e < emit_cu[r + 1]; ++e) {
-            if (emit_slot[e] < 0 || emit_slot[e] >= dst_n_slots) return GDN_ERR_SLOT_RANGE;
-            dst.emplace_back(emit_slot[e], r);
-        }
+    std::vector<int32_t> dst(emit_slot, emit_slot + n_emit);
+    for (int32_t id : dst)
+        if (id < 0 || id >= dst_n_slots) return GDN_ERR_SLOT_RANGE;
     std::sort(dst.begin(), dst.end());
-    for (size_t i = 1; i < dst.size(); ++i)
-        if (dst[i].first == dst[i - 1].first) return GDN_ERR_SLOT_DUP;
-    if (same_pool && !dst.empty()) {
-        // a destination may be the writer's own source (read at its start, written later by
-        // the same chain) but never another request's source
-        for (int32_t r = 0; r < n_req; ++r) {
-            if (src_slot[r] < 0) continue;
-            auto it = std::lower_bound(dst.begin(), dst.end(), std::make_pair(src_slot[r], INT32_MIN));
-            if (it != dst.end() && it->first == src_slot[r] && it->second != r) return GDN_ERR_SLOT_HAZARD;
-        }
-    }
+    if (std::adjacent_find(dst.begin(), dst.end()) != dst.end()) return GDN_ERR_SLOT_DUP;
     return GDN_OK;
 }
 

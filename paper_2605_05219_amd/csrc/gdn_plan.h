@@ -21,11 +21,10 @@ struct ChunkPlan {
 int32_t plan_chunks(int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
                     const int32_t* emit_cu, const int32_t* emit_pos, ChunkPlan* out);
 
-// Slot checks of one prefill call: ranges, distinct destinations, and no destination that is
-// another request's source when both pools are the same memory.
+// Slot checks of one prefill call: ranges and distinct destinations (overlaps between source and
+// destination slots are checked by address where the pools are known).
 int32_t check_slots(int32_t n_req, const int32_t* src_slot, int32_t src_n_slots,
-                    const int32_t* emit_cu, const int32_t* emit_slot, int32_t dst_n_slots,
-                    bool same_pool);
+                    const int32_t* emit_cu, const int32_t* emit_slot, int32_t dst_n_slots);
 
 // Requests ordered by decreasing chunk count (longest chains are launched first).
 std::vector<int32_t> longest_first(const ChunkPlan& plan, int32_t n_req);

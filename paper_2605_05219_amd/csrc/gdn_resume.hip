@@ -220,6 +220,38 @@ int32_t check_tier_args(const void* host_pool, int64_t host_stride, int32_t host
     return GDN_OK;
 }
 
+// Read-after-write hazards between the source and the destination slots of one call, by ADDRESS (the two pools may
+// be the same memory under different base pointers or strides).  A request may store a state over its own start
+// state when the two slots are the very same memory (the chain reads it before it writes); every other overlap of
+// a destination with a source that is read in this call is an error: another workgroup may still be reading it.
+int32_t check_slot_overlap(int32_t n_req, const float* src, int64_t src_stride, const int32_t* src_slot, const int32_t* emit_cu,
+                           const float* dst, int64_t dst_stride, const int32_t* emit_slot, int64_t slot_elems) {
+    if (!src || !dst || slot_elems <= 0) return GDN_OK;
+    struct Range { uintptr_t lo, hi; int32_t req; };
+    std::vector<Range> d;
+    const uintptr_t bytes = (uintptr_t)slot_elems * sizeof(float);
+    for (int32_t r = 0; r < n_req; ++r)
+        for (int32_t e = emit_cu[r]; e < emit_cu[r + 1]; ++e) {
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(dst + (int64_t)emit_slot[e] * dst_stride);
+            d.push_back({lo, lo + bytes, r});
+        }
+    if (d.empty()) return GDN_OK;
+    std::sort(d.begin(), d.end(), [](const Range& a, const Range& b) { return a.lo < b.lo; });
+    for (int32_t r = 0; r < n_req; ++r) {
+        if (src_slot[r] < 0) continue;
+        const uintptr_t lo = reinterpret_cast<uintptr_t>(src + (int64_t)src_slot[r] * src_stride), hi = lo + bytes;
+        // destinations are disjoint and sorted: the candidates are the last one starting at or below lo and those after it
+        auto it = std::upper_bound(d.begin(), d.end(), lo, [](uintptr_t x, const Range& a) { return x < a.lo; });
+        if (it != d.begin()) --it;
+        for (; it != d.end() && it->lo < hi; ++it) {
+            if (it->hi <= lo) continue;
+            if (it->req == r && it->lo == lo) continue;   // its own start state, the same memory exactly
+            return GDN_ERR_SLOT_HAZARD;
+        }
+    }
+    return GDN_OK;
+}
+
 // ------------------------------------------------------------------ kernel dispatch
 template <typename E, int DK, int DV>
 int64_t unit_bytes_of() { return UnitLayout<E, DK, DV>::UNIT_BYTES; }
@@ -229,10 +261,13 @@ int64_t unit_bytes(const gdn_shape& s) {
     return s.d_k == 64 ? unit_bytes_of<half_t, 64, 64>() : unit_bytes_of<half_t, 128, 128>();
 }
 
-int recur_waves_override() {
+// Compute units of the current device, looked up once (the variant choices below are sized by it).
+int chip_cus() {
     static const int v = [] {
-        const char* e = std::getenv("GDN_RECUR_WAVES");
-        return e ? std::atoi(e) : 0;
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
     }();
     return v;
 }
@@ -339,19 +374,15 @@ hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
 // compute unit (up to 256 chains) and 11.5 us with two, per (chunk, chain) unit of a large call
 // 0.035 us (0.029 at 32768 chains); two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured
 // crossover: 128 chains 1.12 ms fused against 0.75 ms, 256 chains 1.16 against 1.28, 512 chains
-// 1.45 against 2.16, 896 chains 2.28 against 3.61.  gdn_tune_fused (or GDN_FUSED=0/1 in the
-// environment) forces the choice.
+// 1.45 against 2.16, 896 chains 2.28 against 3.61.  gdn_tune_fused forces the choice.
 std::atomic<int32_t> g_forced_fused{-1};
+inline bool fused_applies(const gdn_shape& s) { return s.in_dtype == GDN_BF16 && s.d_k == 128 && s.d_v == 128; }
 inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
-    if (s.in_dtype != GDN_BF16 || s.d_k != 128 || s.d_v != 128) return false;
-    static const int env_forced = [] {
-        const char* e = std::getenv("GDN_FUSED");
-        return e ? std::atoi(e) : -1;
-    }();
-    const int forced = g_forced_fused.load() >= 0 ? g_forced_fused.load() : env_forced;
+    if (!fused_applies(s)) return false;
+    const int forced = g_forced_fused.load();
     if (forced >= 0) return forced != 0;
     if (n_chains < 128) return false;
-    const double per_chunk = n_chains <= 256 ? 9.0 : 11.5;   // us: one or two workgroups per compute unit
+    const double per_chunk = n_chains <= chip_cus() ? 9.0 : 11.5;   // us: one or two workgroups per compute unit
     const double t_two = 0.056 * (double)total_units + 150.0;
     const double t_fused = std::max(0.035 * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
@@ -359,17 +390,13 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
 
 // Which recurrence variant a call gets: 1 = latency variant (few chains), else the number of
 // d_v slices (waves) per workgroup of the throughput variant.
-constexpr int CHIP_CUS = 256;   // compute units of the chip the variants are sized for (MI355X)
 inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
     int nw = ns;
     while (nw > 1 && n_chains * (ns / nw) < 512) nw >>= 1;
     // A latency-variant workgroup fills a compute unit's LDS: with more of them than compute units
     // they would run in turns (measured: 96 chains 1.0 ms against 0.70 ms with two slices per
     // workgroup).
-    if (nw == 1 && n_chains * ns > CHIP_CUS) nw = 2;
-    if (const int o = recur_waves_override()) {
-        if (o == 1 || o == 2 || (o == 4 && ns == 4)) nw = o;
-    }
+    if (nw == 1 && n_chains * ns > chip_cus()) nw = 2;
     if (nw == 1 && !frag16) nw = 2;   // fp32 operands: the latency variant's registers are sized for 16-byte fragments
     return nw;
 }
@@ -379,8 +406,7 @@ inline int pick_waves(int64_t n_chains, int ns, bool frag16) {
 // unit's LDS, so beyond that the preparation would be left with a few workgroups (measured at 64 chains:
 // 1.77 ms shared, 0.56 ms apart).
 inline bool latency_shared(int64_t n_chains, int ns) {
-    static const bool no_overlap = std::getenv("GDN_NO_OVERLAP") != nullptr;
-    return !no_overlap && n_chains * ns <= CHIP_CUS / 2;
+    return n_chains * ns <= chip_cus() / 2;
 }
 
 // Chunk rounds per slab.  In the latency variant the slab should stay cache resident between the preparation launch
@@ -397,9 +423,9 @@ inline int32_t slab_rounds(int64_t n_chains, int64_t unit_bytes, int nw, int ns)
     // with 64).
     if (nw == 1 && !latency_shared(n_chains, ns)) return 64;
     // Throughput variants: the states are carried through memory from slab to slab (d_v d_k floats per
-    // chain each way), so a slab is at least 8 rounds long whatever the budget says.
+    // chain each way), so slabs are as long as the byte budget allows.
     const int64_t budget = nw == 1 ? (int64_t)48 << 20 : (int64_t)1 << 30;
-    int64_t r = std::max<int64_t>(nw == 1 ? 1 : 8, budget / std::max<int64_t>(1, n_chains * unit_bytes));
+    int64_t r = std::max<int64_t>(1, budget / std::max<int64_t>(1, n_chains * unit_bytes));
     const int64_t q = std::max<int64_t>(1, 512 / std::max<int64_t>(1, n_chains));
     r = std::max(q, r / q * q);
     return (int32_t)std::min<int64_t>(r, 1 << 16);
@@ -468,7 +494,7 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
                     pl.ws_units = slab_base + ((sb + 1) & 1) * slab_bytes;
                     pl.slab_begin = (sb + 1) * R;
                     pl.n_copy_wgs = 0;
-                    e = launch_quad_overlap<E, DK, DV>(ra, pl, n_chains, items, CHIP_CUS, stream);
+                    e = launch_quad_overlap<E, DK, DV>(ra, pl, n_chains, items, chip_cus(), stream);
                 } else {
                     e = launch_recur_quad<E, DK, DV>(ra, n_chains, stream);
                 }
@@ -480,8 +506,7 @@ int32_t launch_all(const gdn_shape& s, PrepArgs pa, RecurArgs ra, int32_t n_req,
         // 0.64 ms).
         bool ring = false;
         if constexpr (sizeof(typename Elem<E>::Frag) == 16 && NS == 4) {
-            static const bool no_ring = std::getenv("GDN_NO_RING") != nullptr;
-            if (!no_ring && nw >= 2 && n_chains * 2 <= CHIP_CUS && recur_waves_override() == 0) {
+            if (nw >= 2 && n_chains * 2 <= chip_cus()) {
                 e = launch_recur_ring<E, DK, DV, 2>(ra, n_chains, stream);
                 ring = true;
             }
@@ -658,6 +683,14 @@ int64_t gdn_workspace_bytes(const gdn_shape* shape, int32_t n_req, int64_t total
     return ws_layout(*shape, max_chunks, max_chunks, n_req).total;
 }
 
+int64_t gdn_workspace_bytes_fused(const gdn_shape* shape, int32_t n_req, int64_t total_tokens, int32_t n_emit) {
+    const int32_t rc = check_shape(shape);
+    if (rc != GDN_OK) return rc;
+    if (n_req < 0 || total_tokens < 0 || n_emit < 0) return GDN_ERR_COUNT;
+    if (!fused_applies(*shape)) return gdn_workspace_bytes(shape, n_req, total_tokens, n_emit);
+    return plan_bytes(total_tokens / GDN_CHUNK + n_req + n_emit + 1, n_req);
+}
+
 int32_t ckpt_gather(const float* pool, int64_t slot_stride, int32_t n_slots, const int32_t* slot_ids, int32_t n,
                     float* dst, int64_t dst_stride, int64_t state_elems, void* stream) {
     const int32_t rc = check_copy_args(pool, slot_stride, n_slots, slot_ids, n, dst, dst_stride, state_elems, true);
@@ -675,18 +708,20 @@ int32_t ckpt_scatter(float* pool, int64_t slot_stride, int32_t n_slots, const in
     return launch_copy<false>(src, pool, src_stride, slot_stride, state_elems, slot_ids, n, (hipStream_t)stream);
 }
 
-// The body of gdn_resume_prefill; with src_on_host the start states live in a pinned host pool
+// The body of gdn_resume_prefill; with POOL_HOST the start states live in a pinned host pool
 // and are first copied to a staging area behind the workspace proper.
+enum PoolKind { POOL_DEVICE = 0, POOL_HOST = 1 };
 static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
                             const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
                             const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
                             const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
                             float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
-                            void* o, void* workspace, int64_t workspace_bytes, void* stream_v, bool src_on_host) {
+                            void* o, void* workspace, int64_t workspace_bytes, void* stream_v, PoolKind kind) {
     hipStream_t stream = (hipStream_t)stream_v;
     int32_t rc = check_shape(shape);
     if (rc != GDN_OK) return rc;
     const gdn_shape& s = *shape;
+    const bool src_on_host = kind == POOL_HOST;
 
     ChunkPlan plan;
     rc = plan_chunks(n_req, cu_seqlens, start_pos, emit_cu, emit_pos, &plan);
@@ -694,8 +729,7 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     const int64_t total_tokens = cu_seqlens[n_req];
     if (total_tokens > s.T_alloc) return GDN_ERR_SEQLENS;
     const int32_t n_emit = emit_cu[n_req];
-    rc = check_slots(n_req, src_slot, src_n_slots, emit_cu, emit_slot, dst_n_slots,
-                     !src_on_host && state_src != nullptr && (const void*)state_src == (const void*)state_dst);
+    rc = check_slots(n_req, src_slot, src_n_slots, emit_cu, emit_slot, dst_n_slots);
     if (rc != GDN_OK) return rc;
 
     const int64_t slot_elems = (int64_t)s.L * s.H_v * s.d_v * s.d_k;
@@ -711,17 +745,37 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         if (!aligned16(state_dst) || (dst_slot_stride & 3)) return GDN_ERR_ALIGN;
         if (dst_slot_stride < slot_elems) return GDN_ERR_SHAPE;
     }
+    if (!src_on_host) {
+        rc = check_slot_overlap(n_req, state_src, src_slot_stride, src_slot, emit_cu, state_dst, dst_slot_stride, emit_slot,
+                                slot_elems);
+        if (rc != GDN_OK) return rc;
+    }
     const int32_t n_chunks = (int32_t)plan.chunk_tok0.size();
     if (n_chunks == 0) return GDN_OK;  // nothing to replay
     if (!q || !k || !v || !beta || !gate || !o) return GDN_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return GDN_ERR_ALIGN;
 
-    const WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
+    // The fused kernel needs the plan image only; the two-kernel path needs the carried states and a slab as well.
+    // A workspace too small for the two-kernel path but large enough for the fused kernel gets the fused kernel
+    // whatever the estimate says (gdn_workspace_bytes_fused is the size that asks for this).
+    WsLayout wl = ws_layout(s, n_chunks, plan.max_chunks_per_req, n_req);
     int32_t n_staged = 0;
     if (src_on_host)
         for (int32_t r = 0; r < n_req; ++r) n_staged += src_slot[r] >= 0;
+    const int64_t staged_bytes = src_on_host ? (int64_t)n_staged * slot_elems * (int64_t)sizeof(float) : 0;
+    bool use_fused = choose_fused(s, (int64_t)n_req * s.L * s.H_v, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
+    if (!use_fused && fused_applies(s) && g_forced_fused.load() != 0 &&
+        workspace_bytes < align_up(wl.total, 256) + staged_bytes)
+        use_fused = true;
+
+    if (use_fused) {
+        wl.carry = 0;
+        wl.slab = 0;
+        wl.n_bufs = 0;
+        wl.total = wl.plan;
+    }
     const int64_t staging_off = align_up(wl.total, 256);
-    const int64_t need = src_on_host ? staging_off + (int64_t)n_staged * slot_elems * (int64_t)sizeof(float) : wl.total;
+    const int64_t need = src_on_host ? staging_off + staged_bytes : wl.total;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GDN_ERR_WORKSPACE;
     if (workspace_bytes < need) return GDN_ERR_WORKSPACE;
 
@@ -787,9 +841,6 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     ra.T_alloc = s.T_alloc;
     ra.scale = s.scale;
     ra.o_bf16 = s.o_dtype == GDN_BF16;
-
-
-    const bool use_fused = choose_fused(s, (int64_t)n_req * s.L * s.H_v, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
 
     // ---- host tier: the start states go to the staging area.  If the pool is device-accessible
     //      pinned memory, workgroups appended to the first preparation launch fetch them over
@@ -863,8 +914,9 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
                            void* o, void* workspace, int64_t workspace_bytes, void* stream) {
     return prefill_impl(shape, q, k, v, beta, gate, n_req, cu_seqlens, start_pos, state_src, src_slot_stride, src_n_slots,
                         src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o, workspace,
-                        workspace_bytes, stream, false);
+                        workspace_bytes, stream, POOL_DEVICE);
 }
+
 
 int32_t gdn_resume_prefill_host(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
                                 const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
@@ -874,7 +926,7 @@ int32_t gdn_resume_prefill_host(const gdn_shape* shape, const void* q, const voi
                                 void* o, void* workspace, int64_t workspace_bytes, void* stream) {
     return prefill_impl(shape, q, k, v, beta, gate, n_req, cu_seqlens, start_pos, host_state_src, src_slot_stride,
                         src_n_slots, src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o,
-                        workspace, workspace_bytes, stream, true);
+                        workspace, workspace_bytes, stream, POOL_HOST);
 }
 
 int64_t gdn_workspace_bytes_host(const gdn_shape* shape, int32_t n_req, int64_t total_tokens, int32_t n_emit) {

@@ -397,7 +397,7 @@ class LayerCase:
     requests (storage dtype for activations and convolution states, fp32 parameters).  Draws only:
     pre-activations ~ N(0,1), taps ~ N(0, 0.5^2), small biases, A_log ~ U(log 0.5, log 4),
     dt_bias ~ N(0, 0.5^2), norm weight 1 + 0.1 N(0,1); they stand in for the projections of the
-    model the paper measures (Sec. 5, runtime experiment), whose weights are not available."""
+    model the paper measures (Sec. 6, prototype wall-clock time), whose weights are not available."""
     H_qk: int
     H_v: int
     d_k: int
@@ -466,7 +466,7 @@ class AttnCase:
     """Seeded inputs of the attention layers' side of a cache hit for a packed batch of resumed
     requests, all bf16 bit patterns.  Draws only: queries, keys, values (and the output gate's
     pre-activation) ~ N(0,1) times a chosen spread; they stand in for the projections of the model
-    the paper measures (Sec. 5, runtime experiment), whose weights are not available.  Request r
+    the paper measures (Sec. 6, prototype wall-clock time), whose weights are not available.  Request r
     owns sequence slot seq_slot[r]; k_full[r] / v_full[r] hold its keys and values of positions
     1 .. start+len (the restored prefix, then the suffix)."""
     H_q: int

@@ -170,11 +170,15 @@ def test_work_list_covers_every_tile_once_and_packs_and_splits_as_documented(mon
         _check_plan(H_q, H_kv, int(rng.choice([64, 128, 256])), [int(x) for x in rng.integers(0, 700, n)],
                     [int(x) for x in rng.integers(0, 9000, n)])
     # the switches
-    monkeypatch.setenv("ATTN_NO_PACK", "1")
-    assert _check_plan(16, 2, 128, [64], [8000])[1] == 1
-    monkeypatch.setenv("ATTN_NO_SPLIT", "1")
-    u, _ = _check_plan(16, 2, 128, [64], [8000])
-    assert (u[:, 4] == -1).all() and len(u) == 1
+    try:
+        AT.attn_tune_pack(False)
+        assert _check_plan(16, 2, 128, [64], [8000])[1] == 1
+        AT.attn_tune_split(False)
+        u, _ = _check_plan(16, 2, 128, [64], [8000])
+        assert (u[:, 4] == -1).all() and len(u) == 1
+    finally:
+        AT.attn_tune_pack(True)
+        AT.attn_tune_split(True)
     # too small a capacity reports the count it needs
     sh = AT.make_attn_shape(16, 2, 128)
     with pytest.raises(B.GdnError) as ei:
@@ -316,9 +320,11 @@ def test_split_key_walks_agree_with_whole_walks(monkeypatch):
                                              (3502, 2, 2, 256, [70], [1300]),
                                              (3503, 4, 2, 128, [100, 64, 0, 200], [0, 3000, 5, 900])]:   # whole and split walks in one call
         c = wl.attn_case(seed, H_q, H_kv, d, lens, starts)
-        monkeypatch.setenv("ATTN_NO_SPLIT", "1")
-        whole, _, _ = gpu_prefill(c, gate=True)
-        monkeypatch.delenv("ATTN_NO_SPLIT")
+        AT.attn_tune_split(False)
+        try:
+            whole, _, _ = gpu_prefill(c, gate=True)
+        finally:
+            AT.attn_tune_split(True)
         split, _, _ = gpu_prefill(c, gate=True)
         assert not np.array_equal(whole, split)                       # the split path did run
         assert np.abs(whole - split).max() <= 2.0 ** -11 * np.abs(whole).max()
@@ -333,9 +339,11 @@ def test_rows_packed_by_head_group_give_bitwise_the_unpacked_result(monkeypatch)
     for seed, H_q, H_kv, d, lens, starts in [(3600, 8, 2, 128, [5, 40, 1, 33], [100, 300, 700, 0]), (3601, 16, 2, 64, [17, 64], [900, 13]),
                                              (3602, 4, 1, 256, [31, 2], [64, 500])]:
         c = wl.attn_case(seed, H_q, H_kv, d, lens, starts)
-        monkeypatch.setenv("ATTN_NO_PACK", "1")
-        plain, k1, v1 = gpu_prefill(c, gate=True)
-        monkeypatch.delenv("ATTN_NO_PACK")
+        AT.attn_tune_pack(False)
+        try:
+            plain, k1, v1 = gpu_prefill(c, gate=True)
+        finally:
+            AT.attn_tune_pack(True)
         packed, k2, v2 = gpu_prefill(c, gate=True)
         assert np.array_equal(plain, packed) and np.array_equal(k1, k2) and np.array_equal(v1, v2)
         check_o(packed, oracle_o(c, d ** -0.5, True), "f32")

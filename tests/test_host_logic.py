@@ -159,6 +159,11 @@ def call_prefill(monkeypatch, **over):
     (dict(emit_slot=[3, 3]), -6),                               # duplicate destination
     (dict(cu_seqlens=[0, 100, 256], start_pos=[256, 0], src_slot=[1, 3], emit_cu=[0, 1, 2],
           emit_pos=[356, 156], emit_slot=[3, 4]), -7),          # request 0 writes request 1's source
+    # the same hazard when the destination pool is a view of the source pool two slots further on (slots compared by address)
+    (dict(cu_seqlens=[0, 100, 256], start_pos=[256, 0], src_slot=[1, 3], emit_cu=[0, 1, 2],
+          emit_pos=[356, 156], emit_slot=[1, 4], state_dst=FakeDev(ptr=0x10000 + 2 * 4 * 2 * 2 * 64 * 64)), -7),
+    # a destination that overlaps the writer's own source only partly (view shifted by half a slot)
+    (dict(emit_slot=[0, 4], state_dst=FakeDev(ptr=0x10000 + 5 * 2 * 2 * 64 * 64)), -7),
     (dict(emit_pos=[384, 513]), -8),
     (dict(cu_seqlens=[0, 600], emit_pos=[384, 512]), -4),       # more tokens than T_alloc
     (dict(q=FakeDev(ptr=0)), -1),
