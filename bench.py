@@ -206,6 +206,42 @@ def bench_config4(args, torch, B, dev):
     return out, cpu
 
 
+def bench_ckpt_copy(torch, B, dev):
+    """Standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB gathered, then scattered."""
+    out = {}
+    # ---- standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB each way
+    try:
+        n_copy, elems = 256, HEADS * D * D
+        big = torch.randn((n_copy * 2, elems), dtype=torch.float32, device=dev)
+        stage = torch.empty((n_copy, elems), dtype=torch.float32, device=dev)
+        ids = np.random.default_rng(SEED).permutation(n_copy * 2)[:n_copy].astype(np.int32)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        for _ in range(3):
+            B.ckpt_gather(big, ids, stage)
+            B.ckpt_scatter(big, ids, stage)
+        reps = 20
+        ev[0].record()
+        for _ in range(reps):
+            B.ckpt_gather(big, ids, stage)
+        ev[1].record()
+        for _ in range(reps):
+            B.ckpt_scatter(big, ids, stage)
+        ev[2].record()
+        torch.cuda.synchronize()
+        nbytes = 2.0 * n_copy * elems * 4
+        out["ckpt_copy"] = {
+            "states": n_copy, "state_bytes": elems * 4,
+            "gather_gbs": nbytes * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
+            "scatter_gbs": nbytes * reps / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9,
+            "peak_gbs": PEAK_HBM_GBS,
+        }
+        del big, stage
+    except Exception as exc:  # the copies are a side measurement; never lose the main line
+        out["ckpt_copy"] = {"error": str(exc)}
+
+    return out["ckpt_copy"]
+
+
 def bench_config1(args, torch, B, wl, dev):
     """configs[1], batch 1: latency bound by construction (16 chains of up to 128 dependent chunk steps)."""
     from paper_2605_05219_amd.device_call import GpuCall
@@ -364,35 +400,7 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
     def step(i):
         calls[i % N_DRAWS].run()
 
-    # ---- standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB each way
-    try:
-        n_copy, elems = 256, HEADS * D * D
-        big = torch.randn((n_copy * 2, elems), dtype=torch.float32, device=dev)
-        stage = torch.empty((n_copy, elems), dtype=torch.float32, device=dev)
-        ids = np.random.default_rng(SEED).permutation(n_copy * 2)[:n_copy].astype(np.int32)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-        for _ in range(3):
-            B.ckpt_gather(big, ids, stage)
-            B.ckpt_scatter(big, ids, stage)
-        reps = 20
-        ev[0].record()
-        for _ in range(reps):
-            B.ckpt_gather(big, ids, stage)
-        ev[1].record()
-        for _ in range(reps):
-            B.ckpt_scatter(big, ids, stage)
-        ev[2].record()
-        torch.cuda.synchronize()
-        nbytes = 2.0 * n_copy * elems * 4
-        out["ckpt_copy"] = {
-            "states": n_copy, "state_bytes": elems * 4,
-            "gather_gbs": nbytes * reps / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9,
-            "scatter_gbs": nbytes * reps / (ev[1].elapsed_time(ev[2]) * 1e-3) / 1e9,
-            "peak_gbs": PEAK_HBM_GBS,
-        }
-        del big, stage
-    except Exception as exc:  # the copies are a side measurement; never lose the main line
-        out["ckpt_copy"] = {"error": str(exc)}
+    out["ckpt_copy"] = bench_ckpt_copy(torch, B, dev)
 
     # ---- host tier (Sec. 6: loading the stored checkpoint from host memory is overhead (i) of a hit): the same
     #      draws with the checkpoint pool in pinned host memory, and the raw host -> HBM state copy rate
@@ -688,6 +696,9 @@ def main() -> int:
                          "profiler runs use")
     ap.add_argument("--latency-only", action="store_true",
                     help="only the configs[1] side measurement (what the profiler runs of the latency kernels use)")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="only the checkpoint pool copies (256 MiB read and written per launch: the known-size copy the "
+                         "profiler's byte counters are calibrated on)")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time ONE call of k = 1..64 configs[1]-style requests (side object `batch_sweep`; about "
                          "a minute of host-side input generation)")
@@ -712,6 +723,9 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.copy_only:
+        print(json.dumps({"ckpt_copy": bench_ckpt_copy(torch, B, dev)}))
+        return 0
     if args.latency_only:
         lat, _, _, _ = bench_config1(args, torch, B, wl, dev)
         print(json.dumps({"latency": lat}))
