@@ -52,6 +52,7 @@ enum {
     GDN_ERR_WORKSPACE = -9,   /* workspace NULL, misaligned or too small */
     GDN_ERR_START = -10,      /* negative start position, or positions overflowing int32 */
     GDN_ERR_COUNT = -11,      /* a negative count */
+    GDN_ERR_STATIC_LIMIT = -12, /* gdn_resume_prefill_static: the call's chunk plan exceeds the library's static array */
     GDN_ERR_HIP = -1000       /* GDN_ERR_HIP - (int)hipError_t */
 };
 
@@ -181,6 +182,33 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
                            float *state_dst, int64_t dst_slot_stride, int32_t dst_n_slots,
                            const int32_t *emit_slot,
                            void *o, void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * gdn_resume_prefill for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and errors as gdn_resume_prefill without the workspace.  The call's chunk
+ * plan (a few int32 per 64-token chunk and per request) lives in a static device array inside
+ * the library, gdn_static_plan_capacity() bytes per GPU (512 KiB, held until the process ends;
+ * enough for about 43 000 chunks, i.e. 2.7 M tokens per layer), and is written there by the
+ * arguments of small launches on `stream`: no hipMalloc, no hipFree, no pinned staging buffer,
+ * no host-to-device copy.  The fused kernel serves the call (bf16 inputs, d_k = d_v = 128; other
+ * shapes return GDN_ERR_SHAPE; gdn_tune_fused does not apply); a plan beyond the capacity returns
+ * GDN_ERR_STATIC_LIMIT before anything is enqueued.  Every call on a GPU uses that GPU's one array:
+ * calls must be ordered on one stream (or otherwise not overlap in time), two overlapping calls
+ * race on the plan.  Nothing in the array needs clearing between calls: a call overwrites the
+ * part it reads.  Outputs are bitwise those of gdn_resume_prefill when that runs the fused kernel.
+ */
+int32_t gdn_resume_prefill_static(const gdn_shape *shape,
+                                  const void *q, const void *k, const void *v,
+                                  const void *beta, const void *gate,
+                                  int32_t n_req, const int32_t *cu_seqlens, const int32_t *start_pos,
+                                  const float *state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                                  const int32_t *src_slot,
+                                  const int32_t *emit_cu, const int32_t *emit_pos,
+                                  float *state_dst, int64_t dst_slot_stride, int32_t dst_n_slots,
+                                  const int32_t *emit_slot,
+                                  void *o, void *stream);
+int64_t gdn_static_plan_capacity(void);
 
 /*
  * Host tier (Sec. 5, implementation details: the prototype keeps checkpoints in CPU RAM;

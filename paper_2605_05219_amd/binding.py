@@ -21,7 +21,7 @@ GDN_CHUNK = 64
 ERRORS = {
     -1: "GDN_ERR_NULL", -2: "GDN_ERR_ALIGN", -3: "GDN_ERR_SHAPE", -4: "GDN_ERR_SEQLENS",
     -5: "GDN_ERR_SLOT_RANGE", -6: "GDN_ERR_SLOT_DUP", -7: "GDN_ERR_SLOT_HAZARD", -8: "GDN_ERR_EMIT",
-    -9: "GDN_ERR_WORKSPACE", -10: "GDN_ERR_START", -11: "GDN_ERR_COUNT",
+    -9: "GDN_ERR_WORKSPACE", -10: "GDN_ERR_START", -11: "GDN_ERR_COUNT", -12: "GDN_ERR_STATIC_LIMIT",
 }
 
 
@@ -89,6 +89,11 @@ def lib():
         L.gdn_resume_prefill.argtypes = ([ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _vp]
                                          + [_vp, _i64, _i32, _vp] + [_vp, _vp]
                                          + [_vp, _i64, _i32, _vp] + [_vp, _vp, _i64, _vp])
+        L.gdn_resume_prefill_static.restype = _i32
+        L.gdn_resume_prefill_static.argtypes = ([ctypes.POINTER(gdn_shape)] + [_vp] * 5 + [_i32, _vp, _vp]
+                                                + [_vp, _i64, _i32, _vp] + [_vp, _vp]
+                                                + [_vp, _i64, _i32, _vp] + [_vp, _vp])
+        L.gdn_static_plan_capacity.restype = _i64
         _lib = L
     return _lib
 
@@ -96,7 +101,7 @@ def lib():
 EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_profile_enable", "gdn_profile_collect", "gdn_probe_ceilings", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "gdn_workspace_bytes_fused",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
-           "gdn_workspace_bytes_host", "gdn_resume_prefill_host"]
+           "gdn_workspace_bytes_host", "gdn_resume_prefill_host", "gdn_resume_prefill_static", "gdn_static_plan_capacity"]
 
 
 def _h32(x) -> np.ndarray:
@@ -236,6 +241,31 @@ def gdn_resume_prefill(shape: gdn_shape, q, k, v, beta, gate, cu_seqlens, start_
                                     _dp(state_dst), dst_stride, dst_n, _hp(eslot),
                                     _dp(o), _dp(workspace), ws_bytes, _stream_ptr(stream)),
            "gdn_resume_prefill")
+
+
+def gdn_resume_prefill_static(shape: gdn_shape, q, k, v, beta, gate, cu_seqlens, start_pos,
+                              state_src, src_slot, emit_cu, emit_pos, state_dst, emit_slot, o, stream=None) -> None:
+    """gdn_resume_prefill without a workspace: the plan lives in the library's static device array and nothing is
+    allocated (see include/gdn_resume.h)."""
+    cu, sp, ss = _h32(cu_seqlens), _h32(start_pos), _h32(src_slot)
+    ecu, epos, eslot = _h32(emit_cu), _h32(emit_pos), _h32(emit_slot)
+    n_req = int(sp.size)
+    if cu.size != n_req + 1 or ecu.size != n_req + 1 or ss.size != n_req or eslot.size != epos.size:
+        raise ValueError("index arrays have inconsistent lengths")
+    src_stride = int(state_src.stride(0)) if state_src is not None else 0
+    src_n = int(state_src.shape[0]) if state_src is not None else 0
+    dst_stride = int(state_dst.stride(0)) if state_dst is not None else 0
+    dst_n = int(state_dst.shape[0]) if state_dst is not None else 0
+    _check(lib().gdn_resume_prefill_static(ctypes.byref(shape), _dp(q), _dp(k), _dp(v), _dp(beta), _dp(gate),
+                                           n_req, _hp(cu), _hp(sp),
+                                           _dp(state_src), src_stride, src_n, _hp(ss), _hp(ecu), _hp(epos),
+                                           _dp(state_dst), dst_stride, dst_n, _hp(eslot),
+                                           _dp(o), _stream_ptr(stream)),
+           "gdn_resume_prefill_static")
+
+
+def gdn_static_plan_capacity() -> int:
+    return int(lib().gdn_static_plan_capacity())
 
 
 def gdn_decode_step(shape: gdn_shape, q, k, v, beta, gate, pool, slot, o, stream=None) -> None:

@@ -97,6 +97,42 @@ int32_t launch_copy(const float* from, float* to, int64_t from_stride, int64_t t
     return GDN_OK;
 }
 
+// ------------------------------------------------------------------ plan image without allocation or staging
+// gdn_resume_prefill_static keeps its plan image in this array (one copy per GPU, held until the process ends)
+// and writes it there by kernel arguments, so the call needs neither a workspace nor the pinned staging ring.
+constexpr int64_t STATIC_SCRATCH_BYTES = 512 << 10;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int PLAN_PIECE_WORDS = 896;   // 3.5 KiB of the 4 KiB a launch may carry as arguments
+struct PlanPiece {
+    int32_t w[PLAN_PIECE_WORDS];
+};
+__global__ void __launch_bounds__(256) plan_write_kernel(PlanPiece piece, int32_t* __restrict__ dst, int32_t n) {
+    for (int i = threadIdx.x; i < n; i += 256) dst[i] = piece.w[i];
+}
+
+// The device address of `scratch` on the current device, looked up once per device (the array's name is only a
+// host-side handle, never a device address: host code uses the pointer returned here).
+constexpr int MAX_DEVICES = 64;
+int32_t static_scratch_ptr(void** out) {
+    static std::mutex mu;
+    static void* ptr[MAX_DEVICES] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_err(e);
+    if (dev < 0 || dev >= MAX_DEVICES) return GDN_ERR_COUNT;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_err(e);
+        if (!p) return GDN_ERR_NULL;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return GDN_OK;
+}
+
 // ------------------------------------------------------------------ plan staging (pinned host memory)
 // A ring of pinned buffers, each with the event of its last upload: a call waits (on the host) only when the
 // ring has gone round and the upload that used its buffer PLAN_RING calls ago has not left it yet, so
@@ -709,8 +745,9 @@ int32_t ckpt_scatter(float* pool, int64_t slot_stride, int32_t n_slots, const in
 }
 
 // The body of gdn_resume_prefill; with POOL_HOST the start states live in a pinned host pool
-// and are first copied to a staging area behind the workspace proper.
-enum PoolKind { POOL_DEVICE = 0, POOL_HOST = 1 };
+// and are first copied to a staging area behind the workspace proper; with POOL_DEVICE_STATIC the
+// plan image goes to the library's static array and the fused kernel runs.
+enum PoolKind { POOL_DEVICE = 0, POOL_HOST = 1, POOL_DEVICE_STATIC = 2 };
 static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
                             const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
                             const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
@@ -722,6 +759,13 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     if (rc != GDN_OK) return rc;
     const gdn_shape& s = *shape;
     const bool src_on_host = kind == POOL_HOST;
+    const bool no_alloc = kind == POOL_DEVICE_STATIC;   // plan image in the library's static array, written by kernel arguments
+    if (no_alloc) {
+        if (!fused_applies(s)) return GDN_ERR_SHAPE;
+        rc = static_scratch_ptr(&workspace);
+        if (rc != GDN_OK) return rc;
+        workspace_bytes = STATIC_SCRATCH_BYTES;
+    }
 
     ChunkPlan plan;
     rc = plan_chunks(n_req, cu_seqlens, start_pos, emit_cu, emit_pos, &plan);
@@ -767,7 +811,10 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     if (!use_fused && fused_applies(s) && g_forced_fused.load() != 0 &&
         workspace_bytes < align_up(wl.total, 256) + staged_bytes)
         use_fused = true;
-
+    if (no_alloc) {
+        if (wl.plan > STATIC_SCRATCH_BYTES) return GDN_ERR_STATIC_LIMIT;
+        use_fused = true;
+    }
     if (use_fused) {
         wl.carry = 0;
         wl.slab = 0;
@@ -805,8 +852,20 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     const std::vector<int32_t> order = longest_first(plan, n_req);
     std::memcpy(p_order, order.data(), sizeof(int32_t) * n_req);
 
-    rc = upload_plan(img.data(), img.size() * sizeof(int32_t), workspace, stream);
-    if (rc != GDN_OK) return rc;
+    if (no_alloc) {
+        // by value in the arguments of a few small launches: no staging buffer, nothing for a replay to find changed
+        for (size_t at = 0; at < img.size(); at += PLAN_PIECE_WORDS) {
+            PlanPiece piece;
+            const int32_t n = (int32_t)std::min<size_t>(PLAN_PIECE_WORDS, img.size() - at);
+            std::memcpy(piece.w, img.data() + at, sizeof(int32_t) * (size_t)n);
+            hipLaunchKernelGGL(plan_write_kernel, dim3(1), dim3(256), 0, stream, piece, reinterpret_cast<int32_t*>(workspace) + at, n);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_err(e);
+        }
+    } else {
+        rc = upload_plan(img.data(), img.size() * sizeof(int32_t), workspace, stream);
+        if (rc != GDN_OK) return rc;
+    }
 
     const int32_t* d = reinterpret_cast<const int32_t*>(workspace);
     char* slab_base = reinterpret_cast<char*>(workspace) + wl.plan + wl.carry;
@@ -916,6 +975,19 @@ int32_t gdn_resume_prefill(const gdn_shape* shape, const void* q, const void* k,
                         src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o, workspace,
                         workspace_bytes, stream, POOL_DEVICE);
 }
+
+int32_t gdn_resume_prefill_static(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,
+                                  const void* gate, int32_t n_req, const int32_t* cu_seqlens, const int32_t* start_pos,
+                                  const float* state_src, int64_t src_slot_stride, int32_t src_n_slots,
+                                  const int32_t* src_slot, const int32_t* emit_cu, const int32_t* emit_pos,
+                                  float* state_dst, int64_t dst_slot_stride, int32_t dst_n_slots, const int32_t* emit_slot,
+                                  void* o, void* stream) {
+    return prefill_impl(shape, q, k, v, beta, gate, n_req, cu_seqlens, start_pos, state_src, src_slot_stride, src_n_slots,
+                        src_slot, emit_cu, emit_pos, state_dst, dst_slot_stride, dst_n_slots, emit_slot, o, nullptr, 0,
+                        stream, POOL_DEVICE_STATIC);
+}
+
+int64_t gdn_static_plan_capacity(void) { return STATIC_SCRATCH_BYTES; }
 
 
 int32_t gdn_resume_prefill_host(const gdn_shape* shape, const void* q, const void* k, const void* v, const void* beta,

@@ -1,0 +1,88 @@
+"""The entry point that allocates nothing (gdn_resume_prefill_static) against gdn_resume_prefill, through the C ABI.
+
+Two calls in a row on the same GPU, the second with a smaller input: the plan of the second call overwrites only the
+head of the static array, so stale words of the first plan stay behind it and must not matter.  Outputs and emitted
+states must be bitwise those of the workspace call that runs the fused kernel, and so meet the oracle tolerance."""
+import numpy as np
+import pytest
+
+from oracle import gdn_oracle as orc
+from paper_2605_05219_amd import binding as B, workloads as wl
+from paper_2605_05219_amd.device_call import GpuCall
+from tests.harness import worst_head_err, worst_state_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(seed, n_req, max_len):
+    rng = np.random.default_rng(seed)
+    L, H, d = 2, 4, 128
+    lens = [int(x) for x in rng.integers(1, max_len, size=n_req)]
+    lens[0] = max_len
+    starts = [int(x) for x in rng.choice([0, 64, 100, 512], n_req)]
+    n_src = 3
+    src = [-1 if s0 == 0 else int(rng.integers(0, n_src)) for s0 in starts]
+    emits, slots, nxt = [], [], n_src
+    for s0, ln in zip(starts, lens):
+        e = sorted({s0 + ln, s0 + (ln + 1) // 2})
+        emits.append(e)
+        slots.append(list(range(nxt, nxt + len(e))))
+        nxt += len(e)
+    per = [wl.token_streams(rng, L, n, H, H, d, d, "bf16", "slow") for n in lens]
+    call = wl.pack_call(L, H, H, d, d, "bf16", per, starts, src, emits, slots, nxt)
+    pool = (rng.standard_normal((nxt,) + call.slot_shape) * 0.3).astype(np.float32)
+    return call, pool
+
+
+def _run_both(call, pool):
+    import torch
+    ref = GpuCall(call, pool)
+    prev = B.gdn_tune_fused(1)
+    try:
+        ref.run()
+    finally:
+        B.gdn_tune_fused(prev)
+    torch.cuda.synchronize()
+    got = GpuCall(call, pool)
+    c = call
+    B.gdn_resume_prefill_static(got.shape, got.q, got.k, got.v, got.beta, got.gate, c.cu_seqlens, c.start_pos, got.pool,
+                                c.src_slot, c.emit_cu, c.emit_pos, got.pool, c.emit_slot, got.o)
+    torch.cuda.synchronize()
+    T = call.total_tokens
+    return (ref.o[:, :T].cpu().numpy(), ref.pool.cpu().numpy()), (got.o[:, :T].cpu().numpy(), got.pool.cpu().numpy())
+
+
+def test_static_entry_point_equals_the_workspace_entry_point_on_two_calls_in_a_row():
+    for seed, n_req, max_len in [(8101, 9, 700), (8102, 3, 130)]:          # the second call is smaller
+        call, pool = _case(seed, n_req, max_len)
+        (o_ref, pool_ref), (o, pool_after) = _run_both(call, pool)
+        assert not np.isnan(o).any()
+        assert np.array_equal(o, o_ref) and np.array_equal(pool_after, pool_ref)
+        o_orc, st_orc = orc.resume_prefill(*call.streams.fields(), call.cu_seqlens, call.start_pos, call.src_slot,
+                                           call.emit_cu, call.emit_pos, state_src=pool)
+        err, where = worst_head_err(o, o_orc, call.cu_seqlens)
+        assert err <= 2e-3, (err, where)
+        for e, s in enumerate(call.emit_slot):
+            assert worst_state_err(pool_after[s], st_orc[e]) <= 2e-3
+
+
+def test_static_entry_point_rejects_what_it_cannot_serve():
+    import torch
+    assert B.gdn_static_plan_capacity() == 512 << 10
+    call, pool = _case(8103, 2, 70)
+    g = GpuCall(call, pool)
+    c = call
+    bad = B.make_shape(c.L, c.H_qk, c.H_v, 64, 64, "bf16", "f32", g.shape.T_alloc)          # a shape without a fused kernel
+    with pytest.raises(B.GdnError) as ei:
+        B.gdn_resume_prefill_static(bad, g.q, g.k, g.v, g.beta, g.gate, c.cu_seqlens, c.start_pos, g.pool, c.src_slot,
+                                    c.emit_cu, c.emit_pos, g.pool, c.emit_slot, g.o)
+    assert ei.value.code == -3
+    # a plan beyond the static array: 50 000 one-token requests need 50 000 chunks (about 800 KB of plan); the size
+    # check comes before any pointer is used
+    n = 50000
+    big = B.make_shape(1, 1, 1, 128, 128, "bf16", "f32", n)
+    z = torch.zeros(16, device="cuda")
+    with pytest.raises(B.GdnError) as ei:
+        B.gdn_resume_prefill_static(big, z, z, z, z, z, np.arange(n + 1, dtype=np.int32), np.zeros(n, np.int32), None,
+                                    np.full(n, -1, np.int32), np.zeros(n + 1, np.int32), [], None, [], z)
+    assert ei.value.code == -12
