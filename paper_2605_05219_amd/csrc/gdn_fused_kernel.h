@@ -1,26 +1,37 @@
 // Fused throughput kernel (bf16 inputs, d_k = d_v = 128): chunk preparation and recurrence of
 // one chain (request, layer, value head) in ONE workgroup, chunk after chunk, the chunk
-// operands never leaving the compute unit.
+// operands never leaving the compute unit.  HBM sees q, k, v, the gates, o and the states,
+// nothing else.  A chain's chunks are serial, so the kernel only pays when chains are plentiful
+// and none is so long that it outlasts the rest (the host decides).
 //
-// When a call has many more chains than the chip has workgroup slots, the two-kernel path is
-// bound by the round trip of the operand image through memory (about three times the
-// algorithmic bytes).  Here a workgroup of four waves takes a chain; per chunk it runs the
-// preparation (same arithmetic as gdn_prep_kernel: gates, K K^T, K Q^T, T = (I+L)^-1, W, U~)
-// with every result kept in LDS or registers, then its four waves, one per 32-column d_v slice,
-// run the recurrence step (same arithmetic as gdn_recur_kernel) against those LDS tiles.  HBM
-// sees q, k, v, the gates, o and the states, nothing else.  The price: a chain's preparation
-// is serial along the chain, so the kernel only pays when chains are plentiful and none is so
-// long that it outlasts the rest (the host decides).
+// Per 64-token chunk, with g the running sum of log a, gam = exp(g), L_ij = b_i exp(g_i - g_j)(k_i.k_j)
+// for j < i, the chunk-local form of the gated delta rule is
+//     (I + L) U = diag(b) V - diag(b gam) K S0^T ,   O = diag(gam scale) Q S0^T + P U ,
+//     S_C = gam_C S0 + (diag(dec) U)^T K ,           P_ij = scale exp(g_i - g_j)(q_i.k_j), j <= i, dec_i = exp(g_C - g_i).
+// T = (I + L)^-1 is never formed.  The chunk is cut into four blocks of 16 tokens and U is found by block
+// forward substitution, block row a after block row a-1:
+//     U_a = T_aa diag(b_a) V_a  -  T_aa diag(b gam)_a (K_a S0^T)  -  sum_{c<a} (T_aa L_ac) U_c ,
+// where only the four 16x16 diagonal inverses T_aa = (I + L_aa)^-1 are computed (fp32, in registers, see
+// inv16_tiles) and the state-independent blocks  T_aa diag(b),  -T_aa diag(b gam),  -T_aa L_ac  (fp32 products,
+// rounded once to fp16) are left in LDS as matrix-core operands.  Every other product is a
+// v_mfma_f32_16x16x32_f16 (or 16x16x16 where the contraction is one block): an accumulator tile holds rows
+// 4 g4 + e of column m in lane (m, g4), which is exactly the B operand of a product that contracts over those
+// rows, so K S0^T, U_c and U feed the next product from registers.
 //
-// LDS plan (76.5 KiB, two workgroups per compute unit):
-//   A   K [C][d_k+4]          -> V^T [d_v][C+4] (after K K^T, K Q^T) -> W fragment image (after U~)
-//   B   Q [C][d_k+4]          kept until the recurrence has used it
-//   KT  K^T [d_k][C+4]        kept until the recurrence has used it
-//   LF  L / T fp32 [C][C+4]   T stays fp32; the fp16 fragments of T diag(b) and -T diag(b gam) are made from its rows when used
-//   X   P fragment image
-//   SM  g, b, gam, dec, -b gam
-// The decay to the chunk end is applied to U (a second conversion of U), not to K^T, so that
-// the K^T tile serves both W^T = K^T (-T diag(b gam))^T and the state update.
+// A workgroup is four waves.  Preparation: wave a owns block row a (its diagonal inverse, its L blocks and
+// their products with T_aa) and the P blocks of query block 3 - a, five 16x16 gram blocks each.  Recurrence:
+// wave w owns the 32 d_v columns 32 w .. 32 w + 31 of the state (two 16-column tiles, the state of a tile in
+// eight accumulator tiles over d_k).  Three barriers per chunk.
+//
+// LDS (65 KiB, two workgroups per compute unit):
+//   K, Q, V  fp16 [64][128], rows unpadded, the 8-byte pieces of a row XOR-swizzled with the row number so
+//            that both read patterns are free of bank conflicts: row reads (lane = token, 8 bytes of a row:
+//            the A/B operand of a product over d_k) and transposing reads (ds_read_b64_tr_b16: lane = column,
+//            four tokens: K^T for the state update, V^T for the substitution)
+//   TbTg[a]  [16][32 (+4)] fp16: row i of T_aa diag(b) followed by row i of -T_aa diag(b gam)
+//   M[a][c]  [16][16 (+4)] fp16: -T_aa L_ac, c < a         P[ia][c] [16][16 (+4)] fp16, c <= ia
+//   Tf[w]    fp32 [16][20]: a wave's T_aa on its way from the accumulator layout to its transpose
+//   g, b, gam, dec, -b gam: fp32 [64] each
 #pragma once
 #include "gdn_prep_kernel.h"
 #include "gdn_recur_kernel.h"
@@ -50,52 +61,97 @@ struct FusedArgs {
     int32_t o_bf16;
 };
 
-template <int DK, int DV>
 struct FusedSmem {
-    static constexpr int C = 64;
-    static constexpr int PAD = Elem<half_t>::PAD;
-    static constexpr int K_LD = DK + PAD, KT_LD = C + PAD, VT_LD = C + PAD, LF_LD = C + 4;
-    static constexpr int a16(int x) { return (x + 15) / 16 * 16; }
-    static constexpr int cmax(int x, int y) { return x > y ? x : y; }
-    static constexpr int W_IMG_BYTES = 2 * (DK / 16) * 64 * 16;  // W fragments: 2 row tiles x d_k/16 steps
-    static constexpr int P_IMG_BYTES = 2 * (C / 16) * 64 * 16;   // P fragments
-    static constexpr int A_OFF = 0;
-    static constexpr int A_BYTES = cmax(cmax(a16(C * K_LD * 2), a16(DV * VT_LD * 2)), W_IMG_BYTES);
-    static constexpr int B_OFF = A_OFF + A_BYTES;
-    static constexpr int B_BYTES = a16(C * K_LD * 2);
-    static constexpr int KT_OFF = B_OFF + B_BYTES;
-    static constexpr int KT_BYTES = a16(DK * KT_LD * 2);
-    static constexpr int LF_OFF = KT_OFF + KT_BYTES;
-    static constexpr int LF_BYTES = a16(C * LF_LD * 4);
-    static constexpr int X_OFF = LF_OFF + LF_BYTES;
-    static constexpr int X_BYTES = P_IMG_BYTES;
-    static constexpr int SM_OFF = X_OFF + X_BYTES;
+    static constexpr int C = 64, D = 128;
+    static constexpr int TILE_BYTES = C * D * 2;            // one of K, Q, V
+    static constexpr int TBTG_LD = 36, BLK_LD = 20, TF_LD = 20;
+    static constexpr int TBTG_BYTES = 16 * TBTG_LD * 2;     // per block row
+    static constexpr int BLK_BYTES = 16 * BLK_LD * 2;       // one 16x16 fp16 block
+    static constexpr int K_OFF = 0;
+    static constexpr int Q_OFF = K_OFF + TILE_BYTES;
+    static constexpr int V_OFF = Q_OFF + TILE_BYTES;
+    static constexpr int TBTG_OFF = V_OFF + TILE_BYTES;
+    static constexpr int M_OFF = TBTG_OFF + 4 * TBTG_BYTES;  // block (a, c), c < a, at index a (a - 1) / 2 + c
+    static constexpr int P_OFF = M_OFF + 6 * BLK_BYTES;      // block (ia, c), c <= ia, at index ia (ia + 1) / 2 + c
+    static constexpr int TF_OFF = P_OFF + 10 * BLK_BYTES;
+    static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
     static constexpr int BYTES = SM_OFF + 5 * C * 4;
+    static_assert(TBTG_OFF % 16 == 0 && M_OFF % 8 == 0 && P_OFF % 8 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
 };
 
-template <int DK, int DV>
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+
+// Byte offset of 8-byte piece `piece` (0..31: four fp16 columns) of row `row` inside a swizzled [64][128] fp16 tile.
+__device__ __forceinline__ int tile_off(int row, int piece) {
+    return row * 256 + ((piece ^ (((row & 3) << 2) | ((row >> 2) & 3))) << 3);
+}
+
+// Operand of a 16x16x32 product over d_k taken along the rows of K or Q: lane (m, g4) carries, for token row
+// `row`, columns 32 s + 4 g4 + {0..3} and 32 s + 16 + 4 g4 + {0..3}; the partner operand (an accumulator tile pair
+// over d_k tiles 2 s and 2 s + 1, or the same read of another row) assigns the same columns to the same slots.
+__device__ __forceinline__ half8 row_frag(const char* tile, int row, int s, int g4) {
+    const half4 lo = *reinterpret_cast<const half4*>(tile + tile_off(row, 8 * s + g4));
+    const half4 hi = *reinterpret_cast<const half4*>(tile + tile_off(row, 8 * s + 4 + g4));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Transposing read: lane (i, g4) receives, for column col0 + i, the four tokens tok0 + 4 g4 + {0..3} of a swizzled
+// tile.  The hardware hands lane i of a group of 16 element i % 4 of the 8-byte pieces addressed by lanes
+// i / 4 + {0, 4, 8, 12} of its group: lane j therefore addresses token tok0 + 4 g4 + j / 4, columns col0 + 4 (j % 4) ...
+__device__ __forceinline__ half4 tr_frag(const char* tile, int tok0, int col0, int j, int g4) {
+    const int row = tok0 + 4 * g4 + (j >> 2);
+    const char* p = tile + tile_off(row, (col0 >> 2) + (j & 3));
+    const i16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p));
+    return __builtin_bit_cast(half4, x);
+}
+
+__device__ __forceinline__ half4 cvt4(const f32x4& x) {
+    half4 h;
+    h[0] = (half_t)x[0]; h[1] = (half_t)x[1]; h[2] = (half_t)x[2]; h[3] = (half_t)x[3];
+    return h;
+}
+__device__ __forceinline__ half8 cat8(const half4& lo, const half4& hi) {
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+__device__ __forceinline__ f32x4 mma32(const half8& a, const half8& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mma16(const half4& a, const half4& b, const f32x4& c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+}
+
+// (I + D)^-1 of a strictly lower triangular 16x16 block given the accumulator-layout tiles of D (d: element e of
+// lane (m, g4) is D[4 g4 + e][m]) and of its transpose (dt: D[m][4 g4 + e]); the nilpotent product of
+// inv16_unit_lower, all in registers.  Returns the tile of the inverse.
+__device__ __forceinline__ f32x4 inv16_tiles(const f32x4& d, const f32x4& dt, int m, int g4) {
+    f32x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = ((4 * g4 + e) == m ? 1.f : 0.f) - d[e];
+    const f32x4 zero = {0, 0, 0, 0};
+    const f32x4 p2 = mm16_rr(zero, dt, d), p2t = mm16_rr(zero, d, dt);
+    y = mm16_rr(y, p2t, y);
+    const f32x4 p4 = mm16_rr(zero, p2t, p2), p4t = mm16_rr(zero, p2, p2t);
+    y = mm16_rr(y, p4t, y);
+    const f32x4 p8t = mm16_rr(zero, p4, p4t);
+    return mm16_rr(y, p8t, y);
+}
+
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_fused_kernel(FusedArgs a) {
-    typedef half_t E;
-    typedef Elem<E> EL;
-    typedef typename EL::In In;
-    typedef typename EL::Frag Frag;
-    typedef typename EL::Raw8 Raw8;
-    typedef FusedSmem<DK, DV> SM;
-    constexpr int C = 64;
-    constexpr int K_LD = SM::K_LD, KT_LD = SM::KT_LD, VT_LD = SM::VT_LD, LF_LD = SM::LF_LD;
-    constexpr int SPT = EL::STEPS_PER_TILE;
-    constexpr int NKD = DK / EL::KSTEP, NKC = C / EL::KSTEP, MT = DK / 32;
-    static_assert(DV / 32 == 4 && DK / 32 == 4, "one wave per d_v slice, one W^T row tile per wave");
+    typedef Elem<half_t> EL;
+    typedef EL::In In;
+    typedef EL::Raw8 Raw8;
+    typedef FusedSmem SM;
+    constexpr int C = 64, DK = 128, DV = 128;
 
     extern __shared__ __align__(16) char smem[];
-    E* const Ks = reinterpret_cast<E*>(smem + SM::A_OFF);
-    E* const VTs = reinterpret_cast<E*>(smem + SM::A_OFF);
-    Frag* const w_img = reinterpret_cast<Frag*>(smem + SM::A_OFF);
-    E* const Qs = reinterpret_cast<E*>(smem + SM::B_OFF);
-    E* const KTs = reinterpret_cast<E*>(smem + SM::KT_OFF);
-    float* const Lf = reinterpret_cast<float*>(smem + SM::LF_OFF);
-    Frag* const p_img = reinterpret_cast<Frag*>(smem + SM::X_OFF);
+    char* const Kt = smem + SM::K_OFF;
+    char* const Qt = smem + SM::Q_OFF;
+    char* const Vt = smem + SM::V_OFF;
+    half_t* const tbtg = reinterpret_cast<half_t*>(smem + SM::TBTG_OFF);
+    half_t* const mimg = reinterpret_cast<half_t*>(smem + SM::M_OFF);
+    half_t* const pimg = reinterpret_cast<half_t*>(smem + SM::P_OFF);
     float* const gS = reinterpret_cast<float*>(smem + SM::SM_OFF);
     float* const bS = gS + C;
     float* const gamS = bS + C;
@@ -105,18 +161,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int tid = threadIdx.x;
     const int lane_ = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
-    const int lr_ = lane_ & 31;
-    const int g_ = lane_ >> 5;
-    const int m16_ = lane_ & 15, g4_ = lane_ >> 4;
+    float* const Tf = reinterpret_cast<float*>(smem + SM::TF_OFF) + wave * 16 * SM::TF_LD;
     const int units = a.L * a.H_v;
     const In* const qg = reinterpret_cast<const In*>(a.q);
     const In* const kg = reinterpret_cast<const In*>(a.k);
     const In* const vg = reinterpret_cast<const In*>(a.v);
 
-    // A thread owns 4-token x 8-column blocks of K, Q and V (256 blocks each at d = 128).
-    const int tg_ = tid / (DK / 8), d0_ = (tid % (DK / 8)) * 8;
-    const int tgv_ = tid / (DV / 8), d0v_ = (tid % (DV / 8)) * 8;
-    static_assert((C / 4) * (DK / 8) == 256 && (C / 4) * (DV / 8) == 256, "one block per thread");
+    // A thread owns 4-token x 8-column blocks of K, Q and V (256 blocks each).
+    const int tg_ = tid >> 4, d0_ = (tid & 15) * 8;
 
     // ---- the workgroup's items: the chunks of chains blockIdx.x, blockIdx.x + gridDim.x, ...
     struct Item { int chain, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
@@ -149,10 +201,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         return open_chain(cur.chain + (int)gridDim.x);
     };
+    // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[4], qraw[4], vraw[4];
     In graw = In(), braw = In();
-    auto fetch_kq = [&](const Item& it) {
-        const int l = it.lh / a.H_v, hq = (it.lh % a.H_v) / (a.H_v / a.H_qk);
+    auto fetch = [&](const Item& it) {
+        const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -161,74 +214,61 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0_;
                 kraw[r] = EL::load_raw(kg + off);
                 qraw[r] = EL::load_raw(qg + off);
+                vraw[r] = EL::load_raw(vg + ((row0 + i) * a.H_v + hv) * DV + d0_);
             } else {
                 kraw[r] = EL::zero_raw();
                 qraw[r] = EL::zero_raw();
+                vraw[r] = EL::zero_raw();
             }
         }
-    };
-    auto fetch_v = [&](const Item& it) {
-        const int l = it.lh / a.H_v, hv = it.lh % a.H_v;
-        const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int iv = 4 * tgv_ + r;
-            if (iv < it.n) vraw[r] = EL::load_raw(vg + ((row0 + iv) * a.H_v + hv) * DV + d0v_);
-            else vraw[r] = EL::zero_raw();
-        }
-        if (wave == 0 && lane_ < it.n) {
+        if (lane_ < it.n) {   // every wave keeps its own copy of the 64 gate pairs
             const int64_t gi = (row0 + lane_) * a.H_v + hv;
             graw = reinterpret_cast<const In*>(a.gate)[gi];
             braw = reinterpret_cast<const In*>(a.beta)[gi];
         }
     };
 
-    // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is
-    // processed: 25.0 against 25.8 ms on a 900 k-unit call, 0.84 against 0.91 ms on a 15 k-unit one.
-    // This only pays without spills (with 15 to 116 spilled registers the same fetch cost 32 to
-    // 39 ms): see the note on opaque lane coordinates in the item loop.  Modes: 0 none, 1 K, Q, V, 2 K, Q.
-    constexpr int GDN_FUSED_PREFETCH = 1;
     Item cur = open_chain((int)blockIdx.x);
     if (cur.chain < 0) return;
-    if (GDN_FUSED_PREFETCH) fetch_kq(cur);
-    if (GDN_FUSED_PREFETCH == 1) fetch_v(cur);
+    fetch(cur);
     Item nxt = next_item(cur);
 
-    f32x16 accS[MT];       // this wave's slice of the state: S^T tiles, d_k x 32
+    f32x4 accS[8][2];      // this wave's slice of the state: tile (mt, nt) holds S[32 w + 16 nt + m][16 mt + 4 g4 + e]
     int open = -1;         // chain whose state accS holds
     bool first = true;
 
     for (;;) {
-        // The lane's coordinates are made opaque once per item (and the thread index where it is
-        // used): otherwise every address of the unrolled tile accesses below is hoisted out of
-        // this loop and held in a register of its own for the whole kernel, which spills (116
-        // registers, 2.4 times slower).
-        int lane = lane_, lr = lr_, g = g_, m16 = m16_, g4 = g4_, tg = tg_, d0 = d0_, tgv = tgv_, d0v = d0v_;
-        pin(lane); pin(lr); pin(g); pin(m16); pin(g4); pin(tg); pin(d0); pin(tgv); pin(d0v);
+        // The lane's coordinates are made opaque once per item: otherwise every address of the unrolled tile
+        // accesses below is hoisted out of this loop and held in a register of its own for the whole kernel.
+        int lane = lane_, tg = tg_, d0 = d0_;
+        pin(lane); pin(tg); pin(d0);
+        const int m = lane & 15, g4 = lane >> 4;
         const int n = cur.n;
         const int l = cur.lh / a.H_v, hv = cur.lh % a.H_v;
-        const int sl = wave;
-        const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK + (int64_t)(32 * sl + lr) * DK;
+        const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK;
 
         if (open != cur.chain) {   // a new chain: its start state, from the pool slot or zero
             const int slot = a.req_src_slot[a.req_order[cur.chain / units]];
             if (slot >= 0) {
-                load_state<MT>(accS, a.state_src + slot * a.src_slot_stride + head_off, g);
+                const float* src = a.state_src + slot * a.src_slot_stride + head_off;
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt)
+                        accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (int64_t)(32 * wave + 16 * nt + m) * DK + 16 * mt + 4 * g4);
             } else {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
+                for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) accS[mt][i] = 0.f;
+                    for (int mt = 0; mt < 8; ++mt) accS[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
             open = cur.chain;
         }
         if (!first) __syncthreads();   // the previous item's recurrence is done with every LDS tile
         first = false;
 
-        if (!GDN_FUSED_PREFETCH) fetch_kq(cur);
-        if (GDN_FUSED_PREFETCH != 1) fetch_v(cur);   // V and the gates: used two barriers from here
-        // ---- gates: g_i = inclusive running sum of log a (wave 0), b_i; identity beyond n
-        if (wave == 0) {
+        // ---- gates: g_i = inclusive running sum of log a, b_i; identity beyond n (every wave computes them, wave 0 stores)
+        {
             float la = 0.f, b = 0.f;
             if (lane < n) {
                 la = fmaxf(EL::log_(EL::widen(graw)), -88.f);
@@ -236,222 +276,228 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             const float s = wave_running_sum(la);
             const float g_last = wave_last_lane(s);
-            gS[lane] = s;
-            bS[lane] = b;
             const float gam = EL::exp_(s);
-            gamS[lane] = gam;
-            decS[lane] = EL::exp_(g_last - s);
-            bgS[lane] = -b * gam;
-        }
-        // ---- stage K, Q (row-major) and K^T (token-contiguous) as fp16
-        {
-            float kv[4][8];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int i = 4 * tg + r;
-                float qv[8];
-                EL::unpack(kraw[r], kv[r]);
-                EL::unpack(qraw[r], qv);
-                EL::store4(Ks + i * K_LD + d0, kv[r][0], kv[r][1], kv[r][2], kv[r][3]);
-                EL::store4(Ks + i * K_LD + d0 + 4, kv[r][4], kv[r][5], kv[r][6], kv[r][7]);
-                EL::store4(Qs + i * K_LD + d0, qv[0], qv[1], qv[2], qv[3]);
-                EL::store4(Qs + i * K_LD + d0 + 4, qv[4], qv[5], qv[6], qv[7]);
+            if (wave == 0) {
+                gS[lane] = s;
+                bS[lane] = b;
+                gamS[lane] = gam;
+                decS[lane] = EL::exp_(g_last - s);
+                bgS[lane] = -b * gam;
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                EL::store4(KTs + (d0 + e) * KT_LD + 4 * tg, kv[0][e], kv[1][e], kv[2][e], kv[3][e]);
         }
-        if (GDN_FUSED_PREFETCH && nxt.chain >= 0) fetch_kq(nxt);
+        // ---- stage K, Q, V as fp16 (exact widening of bf16), rows swizzled
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 4 * tg + r;
+            float kv[8], qv[8], vv[8];
+            EL::unpack(kraw[r], kv);
+            EL::unpack(qraw[r], qv);
+            EL::unpack(vraw[r], vv);
+            const int p0 = d0 >> 2;
+            EL::store4(reinterpret_cast<half_t*>(Kt + tile_off(i, p0)), kv[0], kv[1], kv[2], kv[3]);
+            EL::store4(reinterpret_cast<half_t*>(Kt + tile_off(i, p0 + 1)), kv[4], kv[5], kv[6], kv[7]);
+            EL::store4(reinterpret_cast<half_t*>(Qt + tile_off(i, p0)), qv[0], qv[1], qv[2], qv[3]);
+            EL::store4(reinterpret_cast<half_t*>(Qt + tile_off(i, p0 + 1)), qv[4], qv[5], qv[6], qv[7]);
+            EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0)), vv[0], vv[1], vv[2], vv[3]);
+            EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0 + 1)), vv[4], vv[5], vv[6], vv[7]);
+        }
+        if (nxt.chain >= 0) fetch(nxt);
         __syncthreads();
 
-        // ---- K K^T -> L (fp32) and K Q^T -> P fragments (to X: the previous chunk's recurrence is done with it)
-        //      wave 0: KK(0,0) KQ(0,0)   wave 1: KK(1,0)   wave 2: KK(1,1) KQ(1,1)   wave 3: KQ(0,1)
-        int p_mj = -1, p_ni = -1;
+        // ---- preparation.  Wave a: block row a of L (diagonal inverse T_aa, the blocks -T_aa L_ac, T_aa diag(b),
+        //      -T_aa diag(b gam)) and the P blocks of query block ia = 3 - a.
         {
-            int kk_mi = -1, kk_nj = -1;
-            if (wave == 0) { kk_mi = 0; kk_nj = 0; p_mj = 0; p_ni = 0; }
-            if (wave == 1) { kk_mi = 1; kk_nj = 0; }
-            if (wave == 2) { kk_mi = 1; kk_nj = 1; p_mj = 1; p_ni = 1; }
-            if (wave == 3) { p_mj = 0; p_ni = 1; }
-            if (kk_mi >= 0) {
-                f32x16 acc = {0};
-                const E* ar = Ks + (32 * kk_mi + lr) * K_LD;
-                const E* br = Ks + (32 * kk_nj + lr) * K_LD;
+            const int ab = wave, ia = 3 - wave;
+            half8 ka[4], qf[4];        // K rows of block ab and Q rows of block ia as operands over d_k
 #pragma unroll
-                for (int s = 0; s < NKD; ++s) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
-                const int j = 32 * kk_nj + lr;
-                const float gj = gS[j];
+            for (int s = 0; s < 4; ++s) {
+                ka[s] = row_frag(Kt, 16 * ab + m, s, g4);
+                qf[s] = row_frag(Qt, 16 * ia + m, s, g4);
+            }
+            // diagonal block: raw gram (symmetric), scaled into the tiles of D and of D^T
+            f32x4 gr = {0, 0, 0, 0};
 #pragma unroll
-                for (int idx = 0; idx < 16; ++idx) {
-                    const int i = 32 * kk_mi + acc_row(idx, g);
-                    const float val = bS[i] * EL::exp_(fminf(gS[i] - gj, 0.f)) * acc[idx];
-                    Lf[i * LF_LD + j] = (j < i) ? val : 0.f;
+            for (int s = 0; s < 4; ++s) gr = mma32(ka[s], ka[s], gr);
+            const f32x4 gi = *reinterpret_cast<const f32x4*>(gS + 16 * ab + 4 * g4);
+            const f32x4 bi = *reinterpret_cast<const f32x4*>(bS + 16 * ab + 4 * g4);
+            const float gj = gS[16 * ab + m], bj = bS[16 * ab + m];
+            f32x4 d, dt;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = 4 * g4 + e;
+                d[e] = (m < i) ? bi[e] * EL::exp_(fminf(gi[e] - gj, 0.f)) * gr[e] : 0.f;     // D[i][m]
+                dt[e] = (i < m) ? bj * EL::exp_(fminf(gj - gi[e], 0.f)) * gr[e] : 0.f;       // D[m][i]
+            }
+            const f32x4 y = inv16_tiles(d, dt, m, g4);
+            // T_aa from the accumulator layout to its transpose through the wave's own LDS patch (a wave's LDS
+            // accesses execute in order)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) Tf[(4 * g4 + e) * SM::TF_LD + m] = y[e];
+            const f32x4 at = *reinterpret_cast<const f32x4*>(Tf + m * SM::TF_LD + 4 * g4);   // T[m][4 g4 + e]
+            {
+                const f32x4 bg = *reinterpret_cast<const f32x4*>(bgS + 16 * ab + 4 * g4);
+                f32x4 tb, tgm;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { tb[e] = at[e] * bi[e]; tgm[e] = at[e] * bg[e]; }
+                half_t* row = tbtg + (ab * 16 + m) * SM::TBTG_LD;
+                *reinterpret_cast<half4*>(row + 4 * g4) = cvt4(tb);
+                *reinterpret_cast<half4*>(row + 16 + 4 * g4) = cvt4(tgm);
+            }
+            const float gq = gS[16 * ia + m];
+            // key blocks c: left of the diagonal of block row ab, L_ac -> -(T_aa L_ac) stored by rows; up to query
+            // block ia, P (rows j = keys in registers, lane = query i)
+            for (int c = 0; c < 4; ++c) {
+                if (c >= ab && c > ia) continue;
+                half8 kc[4];
+#pragma unroll
+                for (int s = 0; s < 4; ++s) kc[s] = row_frag(Kt, 16 * c + m, s, g4);
+                if (c < ab) {
+                    f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) acc = mma32(ka[s], kc[s], acc);   // rows i in block ab, lanes j in block c
+                    const float gjc = gS[16 * c + m];
+                    f32x4 lt;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lt[e] = bi[e] * EL::exp_(fminf(gi[e] - gjc, 0.f)) * acc[e];   // L_ac[4 g4 + e][m]
+                    const f32x4 zero = {0, 0, 0, 0};
+                    const f32x4 mt_ = mm16_rr(zero, lt, at);     // (L^T T^T): element e of lane (m, g4) = (T L)[m][4 g4 + e]
+                    f32x4 neg;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) neg[e] = -mt_[e];
+                    *reinterpret_cast<half4*>(mimg + ((ab * (ab - 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4) = cvt4(neg);
+                }
+                if (c <= ia) {
+                    f32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) acc = mma32(kc[s], qf[s], acc);
+                    const f32x4 gk = *reinterpret_cast<const f32x4*>(gS + 16 * c + 4 * g4);
+                    f32x4 p;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float val = a.scale * EL::exp_(fminf(gq - gk[e], 0.f)) * acc[e];
+                        p[e] = (16 * c + 4 * g4 + e <= 16 * ia + m) ? val : 0.f;
+                    }
+                    *reinterpret_cast<half4*>(pimg + ((ia * (ia + 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4) = cvt4(p);
                 }
             }
-            if (p_mj >= 0) {
-                f32x16 acc = {0};
-                const E* ar = Ks + (32 * p_mj + lr) * K_LD;   // rows: key token j
-                const E* br = Qs + (32 * p_ni + lr) * K_LD;   // rows: query token i
-#pragma unroll
-                for (int s = 0; s < NKD; ++s) acc = EL::mma(EL::load(ar, s, g), EL::load(br, s, g), acc);
-                const int i = 32 * p_ni + lr;
-                const float gi = gS[i];
-#pragma unroll
-                for (int idx = 0; idx < 16; ++idx) {
-                    const int j = 32 * p_mj + acc_row(idx, g);
-                    const float val = a.scale * EL::exp_(fminf(gi - gS[j], 0.f)) * acc[idx];
-                    acc[idx] = (j <= i) ? val : 0.f;
-                }
-#pragma unroll
-                for (int sub = 0; sub < SPT; ++sub) p_img[(p_ni * NKC + p_mj * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
-            }
-        }
-        __syncthreads();  // L is complete; K in LDS is dead
-
-        // ---- V^T into K's place
-        {
-            float vv[4][8];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) EL::unpack(vraw[r], vv[r]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                EL::store4(VTs + (d0v + e) * VT_LD + 4 * tgv, vv[0][e], vv[1][e], vv[2][e], vv[3][e]);
-        }
-        if (GDN_FUSED_PREFETCH == 1 && nxt.chain >= 0) fetch_v(nxt);
-
-        // ---- T = (I + L)^-1, fp32, by 16x16 blocks (see gdn_prep_kernel).  Stage 1: diagonal blocks
-        //      by (I + D)^-1 = (I + D^8)(I + D^4)(I + D^2)(I - D), in registers.
-        {
-            float* const D = Lf + (16 * wave) * LF_LD + 16 * wave;
-            const f32x4 y = inv16_unit_lower<LF_LD>(D, m16, g4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) D[(4 * g4 + e) * LF_LD + m16] = y[e];
-        }
-        __syncthreads();  // diagonal blocks of T in place
-        auto blk = [&](int br, int bc) -> const float* { return Lf + (16 * br) * LF_LD + 16 * bc; };
-        if (wave < 2) {   // Stage 2: T_10 = -T_11 (L_10 T_00), T_32 = -T_33 (L_32 T_22)
-            const int ra = 2 * wave + 1, rb = 2 * wave;
-            f32x4 m = {0, 0, 0, 0};
-            m = mm16_ll<LF_LD>(m, blk(ra, rb), blk(rb, rb), m16, g4);
-            f32x4 r = {0, 0, 0, 0};
-            r = mm16_lr<LF_LD>(r, blk(ra, ra), m, m16, g4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) Lf[(16 * ra + 4 * g4 + e) * LF_LD + 16 * rb + m16] = -r[e];
         }
         __syncthreads();
-        {   // Stage 3: the 32x32 block below the diagonal; wave w owns T_ab, a = 2 + w/2, b = w%2
-            const int ra = 2 + (wave >> 1), rb = wave & 1;
-            f32x4 x2 = {0, 0, 0, 0};
-            if (rb == 0) x2 = mm16_ll<LF_LD>(x2, blk(2, 0), blk(0, 0), m16, g4);
-            x2 = mm16_ll<LF_LD>(x2, blk(2, 1), blk(1, rb), m16, g4);
-            f32x4 r = {0, 0, 0, 0};
-            r = mm16_lr<LF_LD>(r, blk(ra, 2), x2, m16, g4);
-            if (ra == 3) {
-                f32x4 x3 = {0, 0, 0, 0};
-                if (rb == 0) x3 = mm16_ll<LF_LD>(x3, blk(3, 0), blk(0, 0), m16, g4);
-                x3 = mm16_ll<LF_LD>(x3, blk(3, 1), blk(1, rb), m16, g4);
-                r = mm16_lr<LF_LD>(r, blk(3, 3), x3, m16, g4);
-            }
-            // The 32x32 block below the diagonal tiles is stored in the tile ABOVE them (rows 0..31, columns 32..63),
-            // which nothing else uses: no L block that another wave still reads is overwritten, so no barrier.
-#pragma unroll
-            for (int e = 0; e < 4; ++e) Lf[(16 * (ra - 2) + 4 * g4 + e) * LF_LD + 32 + 16 * rb + m16] = -r[e];
-        }
-        __syncthreads();  // T complete in Lf
 
-        // ---- T stays in fp32: the operand fragments of T diag(b) and -T diag(b gam) are made from its
-        //      rows on the fly (two 16-byte reads, the scale, the conversion), so no fp16 copy of T is
-        //      written and no barrier separates T from its two uses.  Entries above the diagonal inside
-        //      the tiles that are read are exact zeros (written so by the K K^T epilogue and kept by the
-        //      inversion); the tile above the diagonal tiles holds the block below them.
-
-        // ---- U~ for this wave's slice (both token tiles), straight into the recurrence's accumulators
-        f32x16 accU[2];
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt) {
-            f32x16 acc = {0};
-            const float* ar = Lf + (32 * rt + lr) * LF_LD;
-            const float* ar10 = Lf + lr * LF_LD + 32;   // rows 32.., columns 0..31 of T live above the diagonal tiles
-            const E* br = VTs + (32 * sl + lr) * VT_LD;
-#pragma unroll
-            for (int s = 0; s < NKC; ++s)
-                if (s < (rt == 0 ? NKC / 2 : NKC))
-                    acc = EL::mma(EL::load_scaled((rt == 1 && s < NKC / 2) ? ar10 : ar, bS, s, g), EL::load(br, s, g), acc);
-            accU[rt] = acc;
-        }
-        __syncthreads();  // V^T is dead
-
-        // ---- W^T tiles (d_k rows 32 wave .., both token tiles) -> W fragments in A
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int mt = wave;
-            f32x16 acc = {0};
-            const E* ar = KTs + (32 * mt + lr) * KT_LD;
-            const float* br = Lf + (32 * nt + lr) * LF_LD;
-            const float* br10 = Lf + lr * LF_LD + 32;
-#pragma unroll
-            for (int s = 0; s < NKC; ++s)
-                if (s < (nt == 0 ? NKC / 2 : NKC))
-                    acc = EL::mma(EL::load(ar, s, g), EL::load_scaled((nt == 1 && s < NKC / 2) ? br10 : br, bgS, s, g), acc);
-#pragma unroll
-            for (int sub = 0; sub < SPT; ++sub) w_img[(nt * NKD + mt * SPT + sub) * 64 + lane] = EL::from_acc(acc, sub);
-        }
-        __syncthreads();  // W image complete
-
-        // ---- recurrence step of this chunk, slice sl = wave (see gdn_recur_kernel)
+        // ---- recurrence step of this chunk, d_v columns 32 wave + 16 nt + m
         {
-            Frag sf[NKD];
+            half8 sf[4][2];        // the state as an operand over d_k: step s = d_k tiles 2 s, 2 s + 1
 #pragma unroll
-            for (int s = 0; s < NKD; ++s) sf[s] = EL::from_acc(accS[s / SPT], s % SPT);
-            // U = U~ + W S^T
+            for (int s = 0; s < 4; ++s)
 #pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int s = 0; s < NKD; ++s) accU[rt] = EL::mma(w_img[(rt * NKD + s) * 64 + lane], sf[s], accU[rt]);
-            Frag uf[2 * SPT];
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int s = 0; s < SPT; ++s) uf[rt * SPT + s] = EL::from_acc(accU[rt], s);
-            // O^T = (S Q^T) diag(gam) + U^T P^T with the state of the chunk start
+                for (int nt = 0; nt < 2; ++nt) sf[s][nt] = cat8(cvt4(accS[2 * s][nt]), cvt4(accS[2 * s + 1][nt]));
+            half4 uh[4][2];   // U, block a, as an operand over the block's tokens
             const int64_t row0 = (int64_t)l * a.T_alloc + cur.tok0;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
-                f32x16 acc = {0};
-                const E* qr = Qs + (32 * tt + lr) * K_LD;
+            for (int ab = 0; ab < 4; ++ab) {
+                const int row = 16 * ab + m;
+                // K_a S0^T (tokens in registers) and (Q_a S0^T)^T (d_v in registers, lane = token)
+                f32x4 ks[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, ot[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
 #pragma unroll
-                for (int s = 0; s < NKD; ++s) acc = EL::mma(sf[s], EL::load(qr, s, g), acc);
-                const float gm = gamS[32 * tt + lr] * a.scale;
+                for (int s = 0; s < 4; ++s) {
+                    const half8 kfr = row_frag(Kt, row, s, g4);
+                    const half8 qfr = row_frag(Qt, row, s, g4);
 #pragma unroll
-                for (int k = 0; k < 16; ++k) acc[k] *= gm;
-#pragma unroll
-                for (int s = 0; s < (tt + 1) * SPT; ++s) acc = EL::mma(uf[s], p_img[(tt * NKC + s) * 64 + lane], acc);
-                store_o_tile<DV>(a, row0, hv, sl, lr, g, n, tt, acc);
-            }
-            // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.])
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt) {
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 32 * rt + 8 * b + 4 * g);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) accU[rt][4 * b + e] *= dc[e];
+                    for (int nt = 0; nt < 2; ++nt) {
+                        ks[nt] = mma32(kfr, sf[s][nt], ks[nt]);
+                        ot[nt] = mma32(sf[s][nt], qfr, ot[nt]);
+                    }
                 }
+                // U_a = [T_aa diag(b) | -T_aa diag(b gam)] [V_a ; K_a S0^T] + sum_c (-T_aa L_ac) U_c
+                const half_t* trow = tbtg + (ab * 16 + m) * SM::TBTG_LD;
+                const half8 tf = cat8(*reinterpret_cast<const half4*>(trow + 4 * g4), *reinterpret_cast<const half4*>(trow + 16 + 4 * g4));
+                f32x4 u[2];
 #pragma unroll
-                for (int s = 0; s < SPT; ++s) uf[rt * SPT + s] = EL::from_acc(accU[rt], s);
+                for (int nt = 0; nt < 2; ++nt) {
+                    const half4 vt = tr_frag(Vt, 16 * ab, 32 * wave + 16 * nt, m, g4);
+                    const f32x4 zero = {0, 0, 0, 0};
+                    u[nt] = mma32(tf, cat8(vt, cvt4(ks[nt])), zero);
+                }
+                // (one matrix instruction shape throughout: the products over one or two blocks of U are 16x16x32 as
+                // well, a lone block paired with a zero operand)
+                const half4 hz = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+#pragma unroll
+                for (int c = 0; c < 3; c += 2)
+                    if (c < ab) {
+                        const half_t* mrow = mimg + ((ab * (ab - 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4;
+                        const half4 m0 = *reinterpret_cast<const half4*>(mrow);
+                        const bool two = c + 1 < ab;
+                        const half4 m1 = two ? *reinterpret_cast<const half4*>(mrow + 16 * SM::BLK_LD) : hz;
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) u[nt] = mma32(cat8(m0, m1), cat8(uh[c][nt], two ? uh[c + 1][nt] : hz), u[nt]);
+                    }
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) uh[ab][nt] = cvt4(u[nt]);
+                // O_a^T = diag(gam scale) (Q_a S0^T)^T + sum_{c <= a} U_c^T P_ac^T   (lane = token)
+                const float gm = gamS[row] * a.scale;
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ot[nt][e] *= gm;
+#pragma unroll
+                for (int c = 0; c < 4; c += 2)
+                    if (c <= ab) {
+                        const half_t* prow = pimg + ((ab * (ab + 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4;
+                        const half4 p0 = *reinterpret_cast<const half4*>(prow);
+                        const bool two = c + 1 <= ab;
+                        const half4 p1 = two ? *reinterpret_cast<const half4*>(prow + 16 * SM::BLK_LD) : hz;
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) ot[nt] = mma32(cat8(uh[c][nt], two ? uh[c + 1][nt] : hz), cat8(p0, p1), ot[nt]);
+                    }
+                if (row < n) {
+                    const int64_t off = ((row0 + row) * a.H_v + hv) * DV + 32 * wave + 4 * g4;
+                    if (a.o_bf16) {
+                        uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) {
+                            const uint32_t lo = f32_to_bf16_rne(ot[nt][0]) | ((uint32_t)f32_to_bf16_rne(ot[nt][1]) << 16);
+                            const uint32_t hi = f32_to_bf16_rne(ot[nt][2]) | ((uint32_t)f32_to_bf16_rne(ot[nt][3]) << 16);
+                            *reinterpret_cast<uint2*>(p + 16 * nt) = make_uint2(lo, hi);
+                        }
+                    } else {
+                        float* p = reinterpret_cast<float*>(a.o) + off;
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt) *reinterpret_cast<f32x4*>(p + 16 * nt) = ot[nt];
+                    }
+                }
             }
+            // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
+            half4 ud[4][2];   // diag(dec) U
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
+            for (int ab = 0; ab < 4; ++ab) {
+                const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 16 * ab + 4 * g4);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) accS[mt][i] *= gam_last;
-                const E* kr = KTs + (32 * mt + lr) * KT_LD;
+                for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                for (int s = 0; s < NKC; ++s) accS[mt] = EL::mma(EL::load(kr, s, g), uf[s], accS[mt]);
+                    for (int e = 0; e < 4; ++e) ud[ab][nt][e] = (half_t)((float)uh[ab][nt][e] * dc[e]);
+            }
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const half8 k0 = cat8(tr_frag(Kt, 0, 16 * mt, m, g4), tr_frag(Kt, 16, 16 * mt, m, g4));
+                const half8 k1 = cat8(tr_frag(Kt, 32, 16 * mt, m, g4), tr_frag(Kt, 48, 16 * mt, m, g4));
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) accS[mt][nt][e] *= gam_last;
+                    accS[mt][nt] = mma32(k0, cat8(ud[0][nt], ud[1][nt]), accS[mt][nt]);
+                    accS[mt][nt] = mma32(k1, cat8(ud[2][nt], ud[3][nt]), accS[mt][nt]);
+                }
             }
             // checkpoint emission: exact state after the last token of this chunk
             const int eslot = cur.eslot;   // looked up one item ahead, with the chunk's other bookkeeping
-            if (eslot >= 0) store_state<MT>(accS, a.state_dst + eslot * a.dst_slot_stride + head_off, g);
+            if (eslot >= 0) {
+                float* dst = a.state_dst + eslot * a.dst_slot_stride + head_off;
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt)
+                        *reinterpret_cast<f32x4*>(dst + (int64_t)(32 * wave + 16 * nt + m) * DK + 16 * mt + 4 * g4) = accS[mt][nt];
+            }
         }
 
         if (nxt.chain < 0) break;

@@ -383,22 +383,22 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
 
 // Fused throughput kernel (bf16 inputs, d = 128): see gdn_fused_kernel.h.
 hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
-    typedef FusedSmem<128, 128> SM;
+    typedef FusedSmem SM;
     static std::once_flag once;
     static hipError_t once_err = hipSuccess;
     static int slots = 1;
     std::call_once(once, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<128, 128>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
         int dev = 0, cus = 0, per_cu = 0;
         if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<128, 128>, 256, SM::BYTES);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel, 256, SM::BYTES);
         once_err = e;
         if (e == hipSuccess) slots = std::max(1, cus * per_cu);
     });
     if (once_err != hipSuccess) return once_err;
-    hipLaunchKernelGGL((gdn_fused_kernel<128, 128>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
+    hipLaunchKernelGGL(gdn_fused_kernel, dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
                        stream, fa);
     return hipGetLastError();
 }
