@@ -80,6 +80,13 @@ struct FusedSmem {
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
 };
 
+// A wave-uniform word of the call's plan, read through the scalar cache (the plan is read-only while the kernel runs).
+// A vector load here would share the in-flight counter of the output stores and make the item loop wait for them.
+__device__ __forceinline__ int32_t plan_word(const int32_t* p, int i) {
+    typedef const __attribute__((address_space(4))) int32_t* cptr;
+    return ((cptr)(uintptr_t)p)[i];
+}
+
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
@@ -179,24 +186,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             it.c = it.c_end = it.lh = it.tok0 = it.n = 0;
             it.eslot = -1;
             if (it.chain < 0) return it;
-            const int r = a.req_order[chain / units];
+            const int r = plan_word(a.req_order, chain / units);
             it.lh = chain % units;
-            it.c = a.req_chunk_cu[r];
-            it.c_end = a.req_chunk_cu[r + 1];
+            it.c = plan_word(a.req_chunk_cu, r);
+            it.c_end = plan_word(a.req_chunk_cu, r + 1);
             if (it.c < it.c_end) break;
         }
-        it.tok0 = a.chunk_tok0[it.c];
-        it.n = a.chunk_len[it.c];
-        it.eslot = a.chunk_emit_slot[it.c];
+        it.tok0 = plan_word(a.chunk_tok0, it.c);
+        it.n = plan_word(a.chunk_len, it.c);
+        it.eslot = plan_word(a.chunk_emit_slot, it.c);
         return it;
     };
     auto next_item = [&](const Item& cur) -> Item {
         if (cur.c + 1 < cur.c_end) {
             Item it = cur;
             it.c = cur.c + 1;
-            it.tok0 = a.chunk_tok0[it.c];
-            it.n = a.chunk_len[it.c];
-            it.eslot = a.chunk_emit_slot[it.c];
+            it.tok0 = plan_word(a.chunk_tok0, it.c);
+            it.n = plan_word(a.chunk_len, it.c);
+            it.eslot = plan_word(a.chunk_emit_slot, it.c);
             return it;
         }
         return open_chain(cur.chain + (int)gridDim.x);
@@ -204,34 +211,39 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[4], qraw[4], vraw[4];
     In graw = In(), braw = In();
-    auto fetch = [&](const Item& it) {
+    auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
         const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
+        // wave-uniform 64-bit bases, 32-bit per-thread offsets
+        const In* const kb = kg + (row0 * a.H_qk + hq) * DK;
+        const In* const qb = qg + (row0 * a.H_qk + hq) * DK;
+        const In* const vb = vg + (row0 * a.H_v + hv) * DV;
+        const int qk_step = a.H_qk * DK, v_step = a.H_v * DV;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int i = 4 * tg_ + r;
+            const int i = 4 * tg + r;
             if (i < it.n) {
-                const int64_t off = ((row0 + i) * a.H_qk + hq) * DK + d0_;
-                kraw[r] = EL::load_raw(kg + off);
-                qraw[r] = EL::load_raw(qg + off);
-                vraw[r] = EL::load_raw(vg + ((row0 + i) * a.H_v + hv) * DV + d0_);
+                kraw[r] = EL::load_raw(kb + (i * qk_step + d0));
+                qraw[r] = EL::load_raw(qb + (i * qk_step + d0));
+                vraw[r] = EL::load_raw(vb + (i * v_step + d0));
             } else {
                 kraw[r] = EL::zero_raw();
                 qraw[r] = EL::zero_raw();
                 vraw[r] = EL::zero_raw();
             }
         }
-        if (lane_ < it.n) {   // every wave keeps its own copy of the 64 gate pairs
-            const int64_t gi = (row0 + lane_) * a.H_v + hv;
-            graw = reinterpret_cast<const In*>(a.gate)[gi];
-            braw = reinterpret_cast<const In*>(a.beta)[gi];
+        if (lane < it.n) {   // every wave keeps its own copy of the 64 gate pairs
+            const int gi = lane * a.H_v;
+            graw = (reinterpret_cast<const In*>(a.gate) + (row0 * a.H_v + hv))[gi];
+            braw = (reinterpret_cast<const In*>(a.beta) + (row0 * a.H_v + hv))[gi];
         }
     };
 
     Item cur = open_chain((int)blockIdx.x);
     if (cur.chain < 0) return;
-    fetch(cur);
+    fetch(cur, tg_, d0_, lane_);
     Item nxt = next_item(cur);
+    wait_vmcnt<0>();   // the first item's inputs: inside the loop the fetched registers are then known to have landed on every path
 
     f32x4 accS[8][2];      // this wave's slice of the state: tile (mt, nt) holds S[32 w + 16 nt + m][16 mt + 4 g4 + e]
     int open = -1;         // chain whose state accS holds
@@ -248,7 +260,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK;
 
         if (open != cur.chain) {   // a new chain: its start state, from the pool slot or zero
-            const int slot = a.req_src_slot[a.req_order[cur.chain / units]];
+            const int slot = plan_word(a.req_src_slot, plan_word(a.req_order, cur.chain / units));
             if (slot >= 0) {
                 const float* src = a.state_src + slot * a.src_slot_stride + head_off;
 #pragma unroll
@@ -256,6 +268,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int mt = 0; mt < 8; ++mt)
                         accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (int64_t)(32 * wave + 16 * nt + m) * DK + 16 * mt + 4 * g4);
+                // waited for here, once per chain: otherwise every later use of the state registers in the loop waits
+                // for whatever loads are in flight at that point (the next item's inputs), since the compiler cannot
+                // tell the iterations apart
+                wait_vmcnt<0>();
             } else {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -301,7 +317,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0)), vv[0], vv[1], vv[2], vv[3]);
             EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0 + 1)), vv[4], vv[5], vv[6], vv[7]);
         }
-        if (nxt.chain >= 0) fetch(nxt);
+        if (nxt.chain >= 0) fetch(nxt, tg, d0, lane);
         __syncthreads();
 
         // ---- preparation.  Wave a: block row a of L (diagonal inverse T_aa, the blocks -T_aa L_ac, T_aa diag(b),
@@ -448,6 +464,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt) ot[nt] = mma32(cat8(uh[c][nt], two ? uh[c + 1][nt] : hz), cat8(p0, p1), ot[nt]);
                     }
+                // The next item's inputs (fetched at staging time) must have landed before this item's first store is
+                // issued: loads and stores share one in-flight counter, and with both kinds pending the first use of a
+                // fetched register would wait for every store to be acknowledged (thousands of cycles at the top of the
+                // next item).  Here the fetch is thousands of cycles old and nothing else is pending, so this costs nothing.
+                if (ab == 0) wait_vmcnt<0>();
                 if (row < n) {
                     const int64_t off = ((row0 + row) * a.H_v + hv) * DV + 32 * wave + 4 * g4;
                     if (a.o_bf16) {
@@ -464,6 +485,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                         for (int nt = 0; nt < 2; ++nt) *reinterpret_cast<f32x4*>(p + 16 * nt) = ot[nt];
                     }
                 }
+                __builtin_amdgcn_sched_barrier(0);   // block rows one after the other: hoisting the next row's operand loads costs registers
             }
             // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
