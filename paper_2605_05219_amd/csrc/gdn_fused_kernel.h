@@ -64,20 +64,22 @@ struct FusedArgs {
 struct FusedSmem {
     static constexpr int C = 64, D = 128;
     static constexpr int TILE_BYTES = C * D * 2;            // one of K, Q, V
-    static constexpr int TBTG_LD = 36, BLK_LD = 20, TF_LD = 20;
-    static constexpr int TBTG_BYTES = 16 * TBTG_LD * 2;     // per block row
-    static constexpr int BLK_BYTES = 16 * BLK_LD * 2;       // one 16x16 fp16 block
+    static constexpr int PAIR_LD = 40, TF_LD = 20;          // halfs / floats per row
+    static constexpr int PAIR_BYTES = 16 * PAIR_LD * 2;     // one 16 x (2 x 16) fp16 pair tile
     static constexpr int K_OFF = 0;
     static constexpr int Q_OFF = K_OFF + TILE_BYTES;
     static constexpr int V_OFF = Q_OFF + TILE_BYTES;
-    static constexpr int TBTG_OFF = V_OFF + TILE_BYTES;
-    static constexpr int M_OFF = TBTG_OFF + 4 * TBTG_BYTES;  // block (a, c), c < a, at index a (a - 1) / 2 + c
-    static constexpr int P_OFF = M_OFF + 6 * BLK_BYTES;      // block (ia, c), c <= ia, at index ia (ia + 1) / 2 + c
-    static constexpr int TF_OFF = P_OFF + 10 * BLK_BYTES;
+    static constexpr int TBTG_OFF = V_OFF + TILE_BYTES;      // pair tile a: [T_aa diag(b) | -T_aa diag(b gam)]
+    static constexpr int M_OFF = TBTG_OFF + 4 * PAIR_BYTES;  // pair tiles (1: M10,0) (2: M20,M21) (3: M30,M31) (3: M32,0)
+    static constexpr int P_OFF = M_OFF + 4 * PAIR_BYTES;     // pair tiles (0: P00,0) (1: P10,P11) (2: P20,P21) (2: P22,0) (3: P30,P31) (3: P32,P33)
+    static constexpr int TF_OFF = P_OFF + 6 * PAIR_BYTES;
     static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
     static constexpr int BYTES = SM_OFF + 5 * C * 4;
-    static_assert(TBTG_OFF % 16 == 0 && M_OFF % 8 == 0 && P_OFF % 8 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
+    static_assert(TBTG_OFF % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
+    // pair tile index of block (a, c) of M (c < a) and of P (c <= a)
+    static constexpr __host__ __device__ int m_pair(int a, int c) { return (a == 1 ? 0 : a == 2 ? 1 : 2) + (c >> 1); }
+    static constexpr __host__ __device__ int p_pair(int a, int c) { return (a == 0 ? 0 : a == 1 ? 1 : a == 2 ? 2 : 4) + (c >> 1); }
 };
 
 // A wave-uniform word of the call's plan, read through the scalar cache (the plan is read-only while the kernel runs).
@@ -90,29 +92,8 @@ __device__ __forceinline__ int32_t plan_word(const int32_t* p, int i) {
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-// Byte offset of 8-byte piece `piece` (0..31: four fp16 columns) of row `row` inside a swizzled [64][128] fp16 tile.
-__device__ __forceinline__ int tile_off(int row, int piece) {
-    return row * 256 + ((piece ^ (((row & 3) << 2) | ((row >> 2) & 3))) << 3);
-}
-
-// Operand of a 16x16x32 product over d_k taken along the rows of K or Q: lane (m, g4) carries, for token row
-// `row`, columns 32 s + 4 g4 + {0..3} and 32 s + 16 + 4 g4 + {0..3}; the partner operand (an accumulator tile pair
-// over d_k tiles 2 s and 2 s + 1, or the same read of another row) assigns the same columns to the same slots.
-__device__ __forceinline__ half8 row_frag(const char* tile, int row, int s, int g4) {
-    const half4 lo = *reinterpret_cast<const half4*>(tile + tile_off(row, 8 * s + g4));
-    const half4 hi = *reinterpret_cast<const half4*>(tile + tile_off(row, 8 * s + 4 + g4));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-// Transposing read: lane (i, g4) receives, for column col0 + i, the four tokens tok0 + 4 g4 + {0..3} of a swizzled
-// tile.  The hardware hands lane i of a group of 16 element i % 4 of the 8-byte pieces addressed by lanes
-// i / 4 + {0, 4, 8, 12} of its group: lane j therefore addresses token tok0 + 4 g4 + j / 4, columns col0 + 4 (j % 4) ...
-__device__ __forceinline__ half4 tr_frag(const char* tile, int tok0, int col0, int j, int g4) {
-    const int row = tok0 + 4 * g4 + (j >> 2);
-    const char* p = tile + tile_off(row, (col0 >> 2) + (j & 3));
-    const i16x4 x = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p));
-    return __builtin_bit_cast(half4, x);
-}
+// Swizzle of the 16-byte pieces of a row of a [64][128] fp16 tile: piece p of row r sits at p ^ swz(r).
+__device__ __forceinline__ int swz(int row) { return ((row & 1) << 2) | ((row >> 1) & 3); }
 
 __device__ __forceinline__ half4 cvt4(const f32x4& x) {
     half4 h;
@@ -125,8 +106,8 @@ __device__ __forceinline__ half8 cat8(const half4& lo, const half4& hi) {
 __device__ __forceinline__ f32x4 mma32(const half8& a, const half8& b, const f32x4& c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ f32x4 mma16(const half4& a, const half4& b, const f32x4& c) {
-    return __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ half4 tr_read(const char* p) {
+    return __builtin_bit_cast(half4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p)));
 }
 
 // (I + D)^-1 of a strictly lower triangular 16x16 block given the accumulator-layout tiles of D (d: element e of
@@ -150,7 +131,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     typedef EL::In In;
     typedef EL::Raw8 Raw8;
     typedef FusedSmem SM;
-    constexpr int C = 64, DK = 128, DV = 128;
+    constexpr int C = 64, DK = 128, DV = 128, PLD = SM::PAIR_LD;
 
     extern __shared__ __align__(16) char smem[];
     char* const Kt = smem + SM::K_OFF;
@@ -176,6 +157,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // A thread owns 4-token x 8-column blocks of K, Q and V (256 blocks each).
     const int tg_ = tid >> 4, d0_ = (tid & 15) * 8;
+
+    // The unused halves of the pair tiles (a lone block is paired with zeros) are zeroed once; nothing writes them later.
+    for (int i = tid; i < (SM::TF_OFF - SM::TBTG_OFF) / 16; i += 256)
+        reinterpret_cast<u32x4*>(smem + SM::TBTG_OFF)[i] = u32x4{0u, 0u, 0u, 0u};
 
     // ---- the workgroup's items: the chunks of chains blockIdx.x, blockIdx.x + gridDim.x, ...
     struct Item { int chain, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
@@ -245,7 +230,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     Item nxt = next_item(cur);
     wait_vmcnt<0>();   // the first item's inputs: inside the loop the fetched registers are then known to have landed on every path
 
-    f32x4 accS[8][2];      // this wave's slice of the state: tile (mt, nt) holds S[32 w + 16 nt + m][16 mt + 4 g4 + e]
+    // State tile (mt = 2 s + h, nt): element e of lane (m, g4) is S[32 w + 16 nt + m][32 s + 8 g4 + 4 h + e], so that the
+    // tile pair of step s is, lane for lane, the operand over d_k columns 32 s + 8 g4 .. + 7: one 16-byte piece of a K or Q row.
+    f32x4 accS[8][2];
     int open = -1;         // chain whose state accS holds
     bool first = true;
 
@@ -258,6 +245,21 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int n = cur.n;
         const int l = cur.lh / a.H_v, hv = cur.lh % a.H_v;
         const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK;
+        // LDS byte offsets of this lane inside a K/Q/V tile; the rest of every address is a compile-time constant.
+        //   row reads: lane (m, g4) reads piece 4 s + g4 of row 16 blk + m; (4 s + g4) ^ swz(m) moves with the parity of s only
+        const int row_lo = m * 256 + 16 * (g4 ^ ((m >> 1) & 3));
+        const int row_e = row_lo + 64 * (m & 1), row_o = row_lo + 64 * ((m & 1) ^ 1);          // s even / odd; + blk * 4096 + (s >> 1) * 128
+        //   transposing reads of K for the state update: lane j of group g4 addresses token tok0 + 4 g4 + j / 4, d_k columns
+        //   32 s + 8 (j % 4) + 4 h ...: lane i then receives column 32 s + 8 (i / 4) + 4 h + i % 4, which is row i of state tile 2 s + h
+        const int trow = 4 * g4 + (m >> 2);
+        const int tr_lo = trow * 256 + 16 * ((m & 3) ^ ((trow >> 1) & 3));
+        const int tr_e = tr_lo + 64 * (trow & 1), tr_o = tr_lo + 64 * ((trow & 1) ^ 1);        // + tok0 * 256 + (s >> 1) * 128 + 8 h
+        //   transposing reads of V for the substitution: lane i receives column 32 w + 16 nt + i: lane j addresses columns
+        //   32 w + 16 nt + 4 (j % 4) ..., i.e. piece 4 w + 2 nt + (j % 4) / 2, half (j % 4) % 2
+        int tv[2];
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+            tv[nt] = trow * 256 + 16 * ((4 * wave + 2 * nt + ((m & 3) >> 1)) ^ swz(trow)) + 8 * (m & 1);   // + tok0 * 256
 
         if (open != cur.chain) {   // a new chain: its start state, from the pool slot or zero
             const int slot = plan_word(a.req_src_slot, plan_word(a.req_order, cur.chain / units));
@@ -267,7 +269,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int mt = 0; mt < 8; ++mt)
-                        accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (int64_t)(32 * wave + 16 * nt + m) * DK + 16 * mt + 4 * g4);
+                        accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (32 * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1));
                 // waited for here, once per chain: otherwise every later use of the state registers in the loop waits
                 // for whatever loads are in flight at that point (the next item's inputs), since the compiler cannot
                 // tell the iterations apart
@@ -301,24 +303,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 bgS[lane] = -b * gam;
             }
         }
-        // ---- stage K, Q, V as fp16 (exact widening of bf16), rows swizzled
+        // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * tg + r;
+            const int off = i * 256 + (((d0 >> 3) ^ swz(i)) << 4);
             float kv[8], qv[8], vv[8];
             EL::unpack(kraw[r], kv);
             EL::unpack(qraw[r], qv);
             EL::unpack(vraw[r], vv);
-            const int p0 = d0 >> 2;
-            EL::store4(reinterpret_cast<half_t*>(Kt + tile_off(i, p0)), kv[0], kv[1], kv[2], kv[3]);
-            EL::store4(reinterpret_cast<half_t*>(Kt + tile_off(i, p0 + 1)), kv[4], kv[5], kv[6], kv[7]);
-            EL::store4(reinterpret_cast<half_t*>(Qt + tile_off(i, p0)), qv[0], qv[1], qv[2], qv[3]);
-            EL::store4(reinterpret_cast<half_t*>(Qt + tile_off(i, p0 + 1)), qv[4], qv[5], qv[6], qv[7]);
-            EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0)), vv[0], vv[1], vv[2], vv[3]);
-            EL::store4(reinterpret_cast<half_t*>(Vt + tile_off(i, p0 + 1)), vv[4], vv[5], vv[6], vv[7]);
+            half8 kh, qh, vh;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { kh[e] = (half_t)kv[e]; qh[e] = (half_t)qv[e]; vh[e] = (half_t)vv[e]; }
+            *reinterpret_cast<half8*>(Kt + off) = kh;
+            *reinterpret_cast<half8*>(Qt + off) = qh;
+            *reinterpret_cast<half8*>(Vt + off) = vh;
         }
         if (nxt.chain >= 0) fetch(nxt, tg, d0, lane);
         __syncthreads();
+
+        // operand over d_k columns 32 s + 8 g4 .. + 7 of row 16 blk + m of a tile
+        auto row_frag = [&](const char* tile, int blk, int s) -> half8 {
+            return *reinterpret_cast<const half8*>(tile + ((s & 1) ? row_o : row_e) + blk * 4096 + (s >> 1) * 128);
+        };
 
         // ---- preparation.  Wave a: block row a of L (diagonal inverse T_aa, the blocks -T_aa L_ac, T_aa diag(b),
         //      -T_aa diag(b gam)) and the P blocks of query block ia = 3 - a.
@@ -327,8 +334,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             half8 ka[4], qf[4];        // K rows of block ab and Q rows of block ia as operands over d_k
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                ka[s] = row_frag(Kt, 16 * ab + m, s, g4);
-                qf[s] = row_frag(Qt, 16 * ia + m, s, g4);
+                ka[s] = row_frag(Kt, ab, s);
+                qf[s] = row_frag(Qt, ia, s);
             }
             // diagonal block: raw gram (symmetric), scaled into the tiles of D and of D^T
             f32x4 gr = {0, 0, 0, 0};
@@ -355,9 +362,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 f32x4 tb, tgm;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { tb[e] = at[e] * bi[e]; tgm[e] = at[e] * bg[e]; }
-                half_t* row = tbtg + (ab * 16 + m) * SM::TBTG_LD;
-                *reinterpret_cast<half4*>(row + 4 * g4) = cvt4(tb);
-                *reinterpret_cast<half4*>(row + 16 + 4 * g4) = cvt4(tgm);
+                *reinterpret_cast<half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4) = cat8(cvt4(tb), cvt4(tgm));
             }
             const float gq = gS[16 * ia + m];
             // key blocks c: left of the diagonal of block row ab, L_ac -> -(T_aa L_ac) stored by rows; up to query
@@ -366,7 +371,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if (c >= ab && c > ia) continue;
                 half8 kc[4];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) kc[s] = row_frag(Kt, 16 * c + m, s, g4);
+                for (int s = 0; s < 4; ++s) kc[s] = row_frag(Kt, c, s);
                 if (c < ab) {
                     f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
@@ -380,7 +385,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     f32x4 neg;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) neg[e] = -mt_[e];
-                    *reinterpret_cast<half4*>(mimg + ((ab * (ab - 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4) = cvt4(neg);
+                    *reinterpret_cast<half4*>(mimg + (SM::m_pair(ab, c) * 16 + m) * PLD + 8 * g4 + 4 * (c & 1)) = cvt4(neg);
                 }
                 if (c <= ia) {
                     f32x4 acc = {0, 0, 0, 0};
@@ -393,7 +398,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                         const float val = a.scale * EL::exp_(fminf(gq - gk[e], 0.f)) * acc[e];
                         p[e] = (16 * c + 4 * g4 + e <= 16 * ia + m) ? val : 0.f;
                     }
-                    *reinterpret_cast<half4*>(pimg + ((ia * (ia + 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4) = cvt4(p);
+                    *reinterpret_cast<half4*>(pimg + (SM::p_pair(ia, c) * 16 + m) * PLD + 8 * g4 + 4 * (c & 1)) = cvt4(p);
                 }
             }
         }
@@ -401,12 +406,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
         // ---- recurrence step of this chunk, d_v columns 32 wave + 16 nt + m
         {
-            half8 sf[4][2];        // the state as an operand over d_k: step s = d_k tiles 2 s, 2 s + 1
+            half8 sf[4][2];        // the state as an operand over d_k: step s = state tiles 2 s, 2 s + 1
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) sf[s][nt] = cat8(cvt4(accS[2 * s][nt]), cvt4(accS[2 * s + 1][nt]));
-            half4 uh[4][2];   // U, block a, as an operand over the block's tokens
+            // U as an operand over the tokens of block pair p (blocks 2 p, 2 p + 1); a block not yet computed reads as zero
+            half8 uh[2][2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) uh[p][nt][e] = (half_t)0.f;
             const int64_t row0 = (int64_t)l * a.T_alloc + cur.tok0;
 #pragma unroll
             for (int ab = 0; ab < 4; ++ab) {
@@ -415,39 +427,36 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 f32x4 ks[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, ot[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    const half8 kfr = row_frag(Kt, row, s, g4);
-                    const half8 qfr = row_frag(Qt, row, s, g4);
+                    const half8 kfr = row_frag(Kt, ab, s);
+                    const half8 qfr = row_frag(Qt, ab, s);
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt) {
                         ks[nt] = mma32(kfr, sf[s][nt], ks[nt]);
                         ot[nt] = mma32(sf[s][nt], qfr, ot[nt]);
                     }
                 }
-                // U_a = [T_aa diag(b) | -T_aa diag(b gam)] [V_a ; K_a S0^T] + sum_c (-T_aa L_ac) U_c
-                const half_t* trow = tbtg + (ab * 16 + m) * SM::TBTG_LD;
-                const half8 tf = cat8(*reinterpret_cast<const half4*>(trow + 4 * g4), *reinterpret_cast<const half4*>(trow + 16 + 4 * g4));
+                // U_a = [T_aa diag(b) | -T_aa diag(b gam)] [V_a ; K_a S0^T] + sum_c (-T_aa L_ac) U_c, two blocks c per product
+                const half8 tf = *reinterpret_cast<const half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4);
                 f32x4 u[2];
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
-                    const half4 vt = tr_frag(Vt, 16 * ab, 32 * wave + 16 * nt, m, g4);
+                    const half4 vt = tr_read(Vt + tv[nt] + ab * 4096);
                     const f32x4 zero = {0, 0, 0, 0};
                     u[nt] = mma32(tf, cat8(vt, cvt4(ks[nt])), zero);
                 }
-                // (one matrix instruction shape throughout: the products over one or two blocks of U are 16x16x32 as
-                // well, a lone block paired with a zero operand)
-                const half4 hz = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
 #pragma unroll
-                for (int c = 0; c < 3; c += 2)
-                    if (c < ab) {
-                        const half_t* mrow = mimg + ((ab * (ab - 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4;
-                        const half4 m0 = *reinterpret_cast<const half4*>(mrow);
-                        const bool two = c + 1 < ab;
-                        const half4 m1 = two ? *reinterpret_cast<const half4*>(mrow + 16 * SM::BLK_LD) : hz;
+                for (int p = 0; p < 2; ++p)
+                    if (2 * p < ab) {
+                        const half8 mf = *reinterpret_cast<const half8*>(mimg + (SM::m_pair(ab, 2 * p) * 16 + m) * PLD + 8 * g4);
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) u[nt] = mma32(cat8(m0, m1), cat8(uh[c][nt], two ? uh[c + 1][nt] : hz), u[nt]);
+                        for (int nt = 0; nt < 2; ++nt) u[nt] = mma32(mf, uh[p][nt], u[nt]);
                     }
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) uh[ab][nt] = cvt4(u[nt]);
+                for (int nt = 0; nt < 2; ++nt) {
+                    const half4 h = cvt4(u[nt]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) uh[ab >> 1][nt][4 * (ab & 1) + e] = h[e];
+                }
                 // O_a^T = diag(gam scale) (Q_a S0^T)^T + sum_{c <= a} U_c^T P_ac^T   (lane = token)
                 const float gm = gamS[row] * a.scale;
 #pragma unroll
@@ -455,14 +464,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int e = 0; e < 4; ++e) ot[nt][e] *= gm;
 #pragma unroll
-                for (int c = 0; c < 4; c += 2)
-                    if (c <= ab) {
-                        const half_t* prow = pimg + ((ab * (ab + 1) / 2 + c) * 16 + m) * SM::BLK_LD + 4 * g4;
-                        const half4 p0 = *reinterpret_cast<const half4*>(prow);
-                        const bool two = c + 1 <= ab;
-                        const half4 p1 = two ? *reinterpret_cast<const half4*>(prow + 16 * SM::BLK_LD) : hz;
+                for (int p = 0; p < 2; ++p)
+                    if (2 * p <= ab) {
+                        const half8 pf = *reinterpret_cast<const half8*>(pimg + (SM::p_pair(ab, 2 * p) * 16 + m) * PLD + 8 * g4);
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) ot[nt] = mma32(cat8(uh[c][nt], two ? uh[c + 1][nt] : hz), cat8(p0, p1), ot[nt]);
+                        for (int nt = 0; nt < 2; ++nt) ot[nt] = mma32(uh[p][nt], pf, ot[nt]);
                     }
                 // The next item's inputs (fetched at staging time) must have landed before this item's first store is
                 // issued: loads and stores share one in-flight counter, and with both kinds pending the first use of a
@@ -485,29 +491,33 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                         for (int nt = 0; nt < 2; ++nt) *reinterpret_cast<f32x4*>(p + 16 * nt) = ot[nt];
                     }
                 }
-                __builtin_amdgcn_sched_barrier(0);   // block rows one after the other: hoisting the next row's operand loads costs registers
             }
             // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
-            half4 ud[4][2];   // diag(dec) U
+            half8 ud[2][2];   // diag(dec) U
 #pragma unroll
-            for (int ab = 0; ab < 4; ++ab) {
-                const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 16 * ab + 4 * g4);
+            for (int p = 0; p < 2; ++p) {
+                const f32x4 d0v = *reinterpret_cast<const f32x4*>(decS + 32 * p + 4 * g4);
+                const f32x4 d1v = *reinterpret_cast<const f32x4*>(decS + 32 * p + 16 + 4 * g4);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) ud[ab][nt][e] = (half_t)((float)uh[ab][nt][e] * dc[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        ud[p][nt][e] = (half_t)((float)uh[p][nt][e] * d0v[e]);
+                        ud[p][nt][4 + e] = (half_t)((float)uh[p][nt][4 + e] * d1v[e]);
+                    }
             }
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
-                const half8 k0 = cat8(tr_frag(Kt, 0, 16 * mt, m, g4), tr_frag(Kt, 16, 16 * mt, m, g4));
-                const half8 k1 = cat8(tr_frag(Kt, 32, 16 * mt, m, g4), tr_frag(Kt, 48, 16 * mt, m, g4));
+                const char* kt = Kt + (((mt >> 1) & 1) ? tr_o : tr_e) + (mt >> 2) * 128 + 8 * (mt & 1);
+                const half8 k0 = cat8(tr_read(kt), tr_read(kt + 16 * 256));
+                const half8 k1 = cat8(tr_read(kt + 32 * 256), tr_read(kt + 48 * 256));
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) accS[mt][nt][e] *= gam_last;
-                    accS[mt][nt] = mma32(k0, cat8(ud[0][nt], ud[1][nt]), accS[mt][nt]);
-                    accS[mt][nt] = mma32(k1, cat8(ud[2][nt], ud[3][nt]), accS[mt][nt]);
+                    accS[mt][nt] = mma32(k0, ud[0][nt], accS[mt][nt]);
+                    accS[mt][nt] = mma32(k1, ud[1][nt], accS[mt][nt]);
                 }
             }
             // checkpoint emission: exact state after the last token of this chunk
@@ -518,7 +528,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
                     for (int mt = 0; mt < 8; ++mt)
-                        *reinterpret_cast<f32x4*>(dst + (int64_t)(32 * wave + 16 * nt + m) * DK + 16 * mt + 4 * g4) = accS[mt][nt];
+                        *reinterpret_cast<f32x4*>(dst + (32 * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1)) = accS[mt][nt];
             }
         }
 
