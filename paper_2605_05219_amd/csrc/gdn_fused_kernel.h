@@ -92,8 +92,13 @@ __device__ __forceinline__ int32_t plan_word(const int32_t* p, int i) {
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-// Swizzle of the 16-byte pieces of a row of a [64][128] fp16 tile: piece p of row r sits at p ^ swz(r).
-__device__ __forceinline__ int swz(int row) { return ((row & 1) << 2) | ((row >> 1) & 3); }
+// Swizzle of the 16-byte pieces of a row of a [64][128] fp16 tile: piece p of row r sits at p ^ swz(r).  The LDS
+// has 64 banks of 4 bytes (a row is 256 bytes, so without it every row starts at bank 0).  swz is a bijection of
+// the low four bits of the row: 16 lanes reading the same piece of 16 consecutive rows (row reads, 16 bytes per
+// lane) touch 16 different bank groups; its bit 3 also moves with the row's bit 0, so that the 8 rows x 4 pieces a
+// transposing read addresses per cycle (8 bytes per lane, the same half of every piece) spread two by two over
+// all 16 groups, which is the best that half-pieces allow.
+__device__ __forceinline__ int swz(int row) { return (row & 15) ^ ((row & 1) << 3); }
 
 __device__ __forceinline__ half4 cvt4(const f32x4& x) {
     half4 h;
@@ -246,14 +251,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int l = cur.lh / a.H_v, hv = cur.lh % a.H_v;
         const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK;
         // LDS byte offsets of this lane inside a K/Q/V tile; the rest of every address is a compile-time constant.
-        //   row reads: lane (m, g4) reads piece 4 s + g4 of row 16 blk + m; (4 s + g4) ^ swz(m) moves with the parity of s only
-        const int row_lo = m * 256 + 16 * (g4 ^ ((m >> 1) & 3));
-        const int row_e = row_lo + 64 * (m & 1), row_o = row_lo + 64 * ((m & 1) ^ 1);          // s even / odd; + blk * 4096 + (s >> 1) * 128
+        //   row reads: lane (m, g4) reads piece 4 s + g4 of row 16 blk + m, which sits at (4 s + g4) ^ swz(m)
+        int row_b[4], tr_b[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) row_b[s] = m * 256 + 16 * ((4 * s + g4) ^ swz(m));       // + blk * 4096
         //   transposing reads of K for the state update: lane j of group g4 addresses token tok0 + 4 g4 + j / 4, d_k columns
         //   32 s + 8 (j % 4) + 4 h ...: lane i then receives column 32 s + 8 (i / 4) + 4 h + i % 4, which is row i of state tile 2 s + h
         const int trow = 4 * g4 + (m >> 2);
-        const int tr_lo = trow * 256 + 16 * ((m & 3) ^ ((trow >> 1) & 3));
-        const int tr_e = tr_lo + 64 * (trow & 1), tr_o = tr_lo + 64 * ((trow & 1) ^ 1);        // + tok0 * 256 + (s >> 1) * 128 + 8 h
+#pragma unroll
+        for (int s = 0; s < 4; ++s) tr_b[s] = trow * 256 + 16 * ((4 * s + (m & 3)) ^ swz(trow));   // + tok0 * 256 + 8 h
         //   transposing reads of V for the substitution: lane i receives column 32 w + 16 nt + i: lane j addresses columns
         //   32 w + 16 nt + 4 (j % 4) ..., i.e. piece 4 w + 2 nt + (j % 4) / 2, half (j % 4) % 2
         int tv[2];
@@ -324,7 +330,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
         // operand over d_k columns 32 s + 8 g4 .. + 7 of row 16 blk + m of a tile
         auto row_frag = [&](const char* tile, int blk, int s) -> half8 {
-            return *reinterpret_cast<const half8*>(tile + ((s & 1) ? row_o : row_e) + blk * 4096 + (s >> 1) * 128);
+            return *reinterpret_cast<const half8*>(tile + row_b[s] + blk * 4096);
         };
 
         // ---- preparation.  Wave a: block row a of L (diagonal inverse T_aa, the blocks -T_aa L_ac, T_aa diag(b),
@@ -509,7 +515,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
-                const char* kt = Kt + (((mt >> 1) & 1) ? tr_o : tr_e) + (mt >> 2) * 128 + 8 * (mt & 1);
+                const char* kt = Kt + tr_b[mt >> 1] + 8 * (mt & 1);
                 const half8 k0 = cat8(tr_read(kt), tr_read(kt + 16 * 256));
                 const half8 k1 = cat8(tr_read(kt + 32 * 256), tr_read(kt + 48 * 256));
 #pragma unroll
