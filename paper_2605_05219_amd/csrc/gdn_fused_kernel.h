@@ -131,6 +131,7 @@ __device__ __forceinline__ f32x4 inv16_tiles(const f32x4& d, const f32x4& dt, in
     return mm16_rr(y, p8t, y);
 }
 
+template <bool O_BF16>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_fused_kernel(FusedArgs a) {
     typedef Elem<half_t> EL;
     typedef EL::In In;
@@ -426,11 +427,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int e = 0; e < 8; ++e) uh[p][nt][e] = (half_t)0.f;
             const int64_t row0 = (int64_t)l * a.T_alloc + cur.tok0;
+            // K_a S0^T (tokens in registers) and (Q_a S0^T)^T (d_v in registers, lane = token) of block row ab: 16 independent
+            // products.  They are issued one block row ahead, in between the short dependent products of the substitution.
+            auto state_products = [&](int ab, f32x4 (&ks)[2], f32x4 (&ot)[2]) {
 #pragma unroll
-            for (int ab = 0; ab < 4; ++ab) {
-                const int row = 16 * ab + m;
-                // K_a S0^T (tokens in registers) and (Q_a S0^T)^T (d_v in registers, lane = token)
-                f32x4 ks[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}}, ot[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+                for (int nt = 0; nt < 2; ++nt) { ks[nt] = f32x4{0, 0, 0, 0}; ot[nt] = f32x4{0, 0, 0, 0}; }
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     const half8 kfr = row_frag(Kt, ab, s);
@@ -441,6 +442,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                         ot[nt] = mma32(sf[s][nt], qfr, ot[nt]);
                     }
                 }
+            };
+            f32x4 ks_n[2], ot_n[2];
+            state_products(0, ks_n, ot_n);
+            half8 ud[2][2];   // diag(dec) U, like uh
+#pragma unroll
+            for (int ab = 0; ab < 4; ++ab) {
+                const int row = 16 * ab + m;
+                f32x4 ks[2] = {ks_n[0], ks_n[1]}, ot[2] = {ot_n[0], ot_n[1]};
+                if (ab < 3) state_products(ab + 1, ks_n, ot_n);
                 // U_a = [T_aa diag(b) | -T_aa diag(b gam)] [V_a ; K_a S0^T] + sum_c (-T_aa L_ac) U_c, two blocks c per product
                 const half8 tf = *reinterpret_cast<const half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4);
                 f32x4 u[2];
@@ -457,11 +467,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt) u[nt] = mma32(mf, uh[p][nt], u[nt]);
                     }
+                const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 16 * ab + 4 * g4);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt) {
                     const half4 h = cvt4(u[nt]);
+                    f32x4 x;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) uh[ab >> 1][nt][4 * (ab & 1) + e] = h[e];
+                    for (int e = 0; e < 4; ++e) x[e] = u[nt][e] * dc[e];
+                    const half4 hd = cvt4(x);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uh[ab >> 1][nt][4 * (ab & 1) + e] = h[e];
+                        ud[ab >> 1][nt][4 * (ab & 1) + e] = hd[e];
+                    }
                 }
                 // O_a^T = diag(gam scale) (Q_a S0^T)^T + sum_{c <= a} U_c^T P_ac^T   (lane = token)
                 const float gm = gamS[row] * a.scale;
@@ -483,7 +501,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if (ab == 0) wait_vmcnt<0>();
                 if (row < n) {
                     const int64_t off = ((row0 + row) * a.H_v + hv) * DV + 32 * wave + 4 * g4;
-                    if (a.o_bf16) {
+                    if (O_BF16) {
                         uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt) {
@@ -500,19 +518,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
-            half8 ud[2][2];   // diag(dec) U
-#pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const f32x4 d0v = *reinterpret_cast<const f32x4*>(decS + 32 * p + 4 * g4);
-                const f32x4 d1v = *reinterpret_cast<const f32x4*>(decS + 32 * p + 16 + 4 * g4);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        ud[p][nt][e] = (half_t)((float)uh[p][nt][e] * d0v[e]);
-                        ud[p][nt][4 + e] = (half_t)((float)uh[p][nt][4 + e] * d1v[e]);
-                    }
-            }
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
                 const char* kt = Kt + tr_b[mt >> 1] + 8 * (mt & 1);

@@ -382,25 +382,29 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
 }
 
 // Fused throughput kernel (bf16 inputs, d = 128): see gdn_fused_kernel.h.
-hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
+template <bool O_BF16>
+hipError_t launch_fused_t(const FusedArgs& fa, hipStream_t stream) {
     typedef FusedSmem SM;
     static std::once_flag once;
     static hipError_t once_err = hipSuccess;
     static int slots = 1;
     std::call_once(once, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
         int dev = 0, cus = 0, per_cu = 0;
         if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel, 256, SM::BYTES);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16>, 256, SM::BYTES);
         once_err = e;
         if (e == hipSuccess) slots = std::max(1, cus * per_cu);
     });
     if (once_err != hipSuccess) return once_err;
-    hipLaunchKernelGGL(gdn_fused_kernel, dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
+    hipLaunchKernelGGL(gdn_fused_kernel<O_BF16>, dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
                        stream, fa);
     return hipGetLastError();
+}
+hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
+    return fa.o_bf16 ? launch_fused_t<true>(fa, stream) : launch_fused_t<false>(fa, stream);
 }
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
