@@ -170,12 +170,12 @@ def bench_config4(args, torch, B, dev):
         out["bf16_outputs"] = {"error": str(exc)}
 
     # ---- the oracle on the host cores: a bounded, seeded subsample of the same step (every layer and head of 16
-    #      requests, then layer 0 of the other requests until about 20 s are spent)
+    #      48 seeded requests, then layer 0 of the other requests, until about 25 s are spent)
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import gdn_oracle as orc
         rng = np.random.default_rng(4004)
-        picks = sorted(int(x) for x in rng.choice(step.n_req, size=16, replace=False))
+        picks = sorted(int(x) for x in rng.choice(step.n_req, size=48, replace=False))
         jobs = [(r, list(range(step.L))) for r in picks] + [(r, [0]) for r in range(step.n_req) if r not in picks]
         subs = []
         for r, layers in jobs:                       # host copies made outside the timed loop
@@ -190,13 +190,13 @@ def bench_config4(args, torch, B, dev):
                                state_src=start)
             th_cpu += sub.total_tokens * sub.L * sub.H_v
             n_done += 1
-            if time.perf_counter() - tc0 > 20.0:
+            if time.perf_counter() - tc0 > 25.0:
                 break
         tc1 = time.perf_counter()
         per_token = step.L * step.H                   # token.heads one suffix token costs in this workload
         cpu = {
             "value": th_cpu / per_token / (tc1 - tc0), "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{n_done} of {len(subs)} oracle calls on the same step's inputs: all 8 layers x 16 heads of 16 seeded requests, "
+            "sample": f"{n_done} of {len(subs)} oracle calls on the same step's inputs: all 8 layers x 16 heads of 48 seeded requests, "
                       f"then layer 0 of the other requests; {th_cpu} token.heads in {tc1 - tc0:.1f} s; fp64 token loop, one (layer, head) "
                       f"chain per thread; tokens/s = token.heads/s / {per_token} (a token passes 8 layers x 16 heads)",
             "token_heads_per_s": th_cpu / (tc1 - tc0), "seconds": tc1 - tc0,

@@ -166,6 +166,7 @@ def config4_device(seed: int = 1004, n_req: int = 256, L: int = 8, H: int = 16, 
         pool[s0:s0 + n] = rn(n, L, H, d, d) * pool_scale
     o = torch.full((L, T, H, d), float("nan"), dtype=torch.float32 if o_dtype == "f32" else torch.bfloat16, device=dev)
     shape = binding.make_shape(L, H, H, d, d, "bf16", o_dtype, T)
-    ws = torch.empty(max(256, binding.gdn_workspace_bytes(shape, n_req, T, len(epos))), dtype=torch.uint8, device=dev)
+    # the plan-only workspace: the call runs the fused kernel (the library's own choice for a call of this size)
+    ws = torch.empty(max(256, binding.gdn_workspace_bytes_fused(shape, n_req, T, len(epos))), dtype=torch.uint8, device=dev)
     return ServingStep(L, H, d, n_slots, lens, cu, starts, ids[:n_req].astype(np.int32), np.asarray(ecu, np.int32),
                        np.asarray(epos, np.int32), np.asarray(eslot, np.int32), q, k, v, beta, gate, pool, o, shape, ws)
