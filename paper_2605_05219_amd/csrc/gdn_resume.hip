@@ -409,12 +409,12 @@ hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
 // plentiful and the longest chain does not outlast the whole two-kernel run.  Estimates from
-// figures measured on MI355X (bf16, d = 128; one call of 8 to 96 requests of up to 8192 tokens,
-// and the large configurations): fused, per chunk of one chain 9 us with one workgroup per
-// compute unit (up to 256 chains) and 11.5 us with two, per (chunk, chain) unit of a large call
-// 0.035 us (0.029 at 32768 chains); two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured
-// crossover: 128 chains 1.12 ms fused against 0.75 ms, 256 chains 1.16 against 1.28, 512 chains
-// 1.45 against 2.16, 896 chains 2.28 against 3.61.  gdn_tune_fused forces the choice.
+// figures measured on MI355X (bf16, d = 128; one call of 1 to 64 requests of up to 8192 tokens,
+// and the large configurations): fused, per chunk of one chain 5.9 us with one workgroup per
+// compute unit (up to 256 chains) and 7.7 us with two, per (chunk, chain) unit of a large call
+// 0.022 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured: 128 chains 0.77 ms
+// fused against 0.56 ms, 160 chains 0.77 against 0.82, 256 chains 0.82 against 1.22, 512 chains
+// 0.99 against 2.09, 1024 chains 1.67 against 3.98.  gdn_tune_fused forces the choice.
 std::atomic<int32_t> g_forced_fused{-1};
 inline bool fused_applies(const gdn_shape& s) { return s.in_dtype == GDN_BF16 && s.d_k == 128 && s.d_v == 128; }
 inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
@@ -422,9 +422,9 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
     const int forced = g_forced_fused.load();
     if (forced >= 0) return forced != 0;
     if (n_chains < 128) return false;
-    const double per_chunk = n_chains <= chip_cus() ? 9.0 : 11.5;   // us: one or two workgroups per compute unit
+    const double per_chunk = n_chains <= chip_cus() ? 5.9 : 7.7;   // us: one or two workgroups per compute unit
     const double t_two = 0.056 * (double)total_units + 150.0;
-    const double t_fused = std::max(0.035 * (double)total_units, per_chunk * (double)longest_chain_chunks);
+    const double t_fused = std::max(0.022 * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
 }
 

@@ -148,15 +148,21 @@ def test_destination_may_be_own_source_slot():
     check_call(call, pool, TOL["bf16"])
 
 
-@pytest.mark.parametrize("n_req", [2, 3, 4, 6, 12, 16, 32])
-def test_batch_sizes_cover_every_launch_shape(n_req):
+@pytest.mark.parametrize("n_req,fused", [(2, -1), (3, -1), (4, -1), (6, -1), (12, 0), (12, -1), (16, 0), (16, -1), (32, 0), (32, -1)])
+def test_batch_sizes_cover_every_launch_shape(n_req, fused):
     """16 heads x n_req requests: 32 chains run the latency variant with the next slab's preparation sharing the
     recurrence's launch, 48 and 64 chains the latency variant with separate launches (the recurrence takes most of the chip),
-    96 chains two value-head slices per workgroup fed through an LDS ring, 192 chains the register-staged kernel, 256 and
-    512 chains the fused kernel."""
+    96 chains two value-head slices per workgroup fed through an LDS ring; with the fused kernel forbidden 192 and 256 chains
+    run the register-staged kernel with two slices per workgroup and 512 chains the one with four; left to itself the library
+    gives these three sizes (short chains) to the fused kernel."""
+    from paper_2605_05219_amd import binding as B
     sc = wl.config2(orc.deepest_ckpt, seed=2000 + n_req, n_req=n_req, N=1024, M=4, tail=70)
     pool, _, _ = fill_pool_from_oracle(sc)
-    check_call(sc.resume, pool, TOL["bf16"])
+    prev = B.gdn_tune_fused(fused)
+    try:
+        check_call(sc.resume, pool, TOL["bf16"])
+    finally:
+        B.gdn_tune_fused(prev)
 
 
 @pytest.mark.parametrize("n_req,dtype", [(1, "bf16"), (4, "bf16"), (6, "bf16"), (32, "bf16"), (3, "f32")])
