@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libgdn_resume.so")
-SOURCES = ["gdn_resume.hip", "gdn_layer.hip", "attn_resume.hip", "gdn_plan.cpp", "ckpt_place.cpp"]
+SOURCES = ["gdn_resume.hip", "gdn_layer.hip", "gdn_linear.hip", "attn_resume.hip", "gdn_plan.cpp", "ckpt_place.cpp"]
 
 
 def build_library(verbose: bool = False) -> str:

@@ -1,0 +1,52 @@
+"""ctypes binding of the layers' projections (include/gdn_linear.h): argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+
+from .binding import GDN_BF16, GDN_F32, _check, _dp, _stream_ptr, lib
+
+_i32, _i64, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+
+EXPORTS = ["gdn_linear"]
+
+_ready = False
+
+
+def _lib():
+    global _ready
+    L = lib()
+    if not _ready:
+        L.gdn_linear.restype = _i32
+        L.gdn_linear.argtypes = [_vp, _i64, _vp, _i64, _vp, _vp, _i64, _i32, _i64, _i32, _i32, _vp]
+        _ready = True
+    return L
+
+
+def gdn_linear_raw(x_ptr: int, ldx: int, w_ptr: int, ldw: int, bias_ptr: int, y_ptr: int, ldy: int, out_dtype: int,
+                   T: int, N: int, K: int, stream_ptr: int = 0) -> int:
+    """The C entry point with plain integers for the pointers; returns the status code (no exception)."""
+    return int(_lib().gdn_linear(_vp(x_ptr), int(ldx), _vp(w_ptr), int(ldw), _vp(bias_ptr), _vp(y_ptr), int(ldy),
+                                 int(out_dtype), int(T), int(N), int(K), _vp(stream_ptr)))
+
+
+def gdn_linear(x, w, bias, y, stream=None) -> None:
+    """y[t][n] = bias[n] + sum_k x[t][k] w[n][k].  x [T][K] and w [N][K] are bf16 tensors with unit inner stride,
+    bias an fp32 [N] tensor or None, y [T][N] bf16 or fp32 with unit inner stride (it may be a column slice of a wider
+    tensor: its row stride is passed on)."""
+    import torch
+    T, K = int(x.shape[0]), int(x.shape[1])
+    N = int(w.shape[0])
+    if int(w.shape[1]) != K or tuple(y.shape) != (T, N) or (bias is not None and tuple(bias.shape) != (N,)):
+        raise ValueError("gdn_linear: shapes do not match")
+    if x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16 or (bias is not None and bias.dtype != torch.float32):
+        raise ValueError("gdn_linear: x and w are bf16, bias fp32")
+    if (K > 1 and (x.stride(1) != 1 or w.stride(1) != 1)) or (N > 1 and y.stride(1) != 1):
+        raise ValueError("gdn_linear: inner strides must be 1")
+    code = {torch.bfloat16: GDN_BF16, torch.float32: GDN_F32}.get(y.dtype)
+    if code is None:
+        raise ValueError("gdn_linear: y is bf16 or fp32")
+    ldx = int(x.stride(0)) if T > 1 else K
+    ldw = int(w.stride(0)) if N > 1 else K
+    ldy = int(y.stride(0)) if T > 1 else max(N, int(y.stride(0)))
+    _check(_lib().gdn_linear(_dp(x), ldx, _dp(w), ldw, _dp(bias), _dp(y), ldy, code, T, N, K, _stream_ptr(stream)),
+           "gdn_linear")
