@@ -547,6 +547,34 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
     except Exception as exc:
         out["layer_io"] = {"error": str(exc)}
 
+    # ---- the layers' projections (gdn_linear, bf16 on the matrix cores): in-projection of a GatedDeltaNet layer
+    #      (d_model 2048 -> conv input 6144 | z 2048 | a 16 | b 16) and its out-projection, at a miss's token count and at
+    #      a serving step's
+    try:
+        from paper_2605_05219_amd import linear as LN
+        rows = []
+        for Tp, Np, Kp in ((N_PREFIX, 3 * HEADS * D, 2048), (N_PREFIX, 2048, 2048), (131072, 3 * HEADS * D, 2048), (131072, 2048, 2048)):
+            xp = torch.randn((Tp, Kp), device=dev).bfloat16()
+            wp = (torch.randn((Np, Kp), device=dev) / Kp ** 0.5).bfloat16()
+            yp_ = torch.empty((Tp, Np), dtype=torch.bfloat16, device=dev)
+            for _ in range(3):
+                LN.gdn_linear(xp, wp, None, yp_)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            reps = 20
+            ev[0].record()
+            for _ in range(reps):
+                LN.gdn_linear(xp, wp, None, yp_)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / reps
+            tf = 2.0 * Tp * Np * Kp / (ms * 1e-3) / 1e12
+            rows.append({"tokens": Tp, "out": Np, "in": Kp, "ms": ms, "TFLOPs": tf, "frac": tf / PEAK_MFMA_TFLOPS})
+            del xp, wp, yp_
+        out["projections"] = {"peak_TFLOPs": PEAK_MFMA_TFLOPS, "shapes": rows,
+                              "note": "gdn_linear, bf16 in and out, fp32 accumulation; 2 T N K flops against the dense bf16 peak"}
+    except Exception as exc:
+        out["projections"] = {"error": str(exc)}
+
     # ---- the attention layer of the layer group on the same draws: suffix attention over the restored prefix
     #      (16 query heads, 2 key/value heads, d = 128, bf16), the KV cache resident in HBM; matrix-core bound
     try:
@@ -590,13 +618,13 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
         out["attention"] = {"error": str(exc)}
 
     # ---- a whole cache hit on a layer group as in the paper's runtime experiment (Sec. 6, prototype wall-clock time: one full attention layer
-    #      and three GatedDeltaNet layers; projections excluded): checkpoint states and the attention KV prefix are
+    #      and three GatedDeltaNet layers, with their projections): checkpoint states and the attention KV prefix are
     #      restored from pinned host memory, then the suffix runs through the layers' front ends, the resumed
     #      recurrence (3 layers in one call, downstream checkpoints stored), the back ends and the attention layer.
     if args.layer_group:
         try:
-            from paper_2605_05219_amd import attention as AT, layer as LY
-            Lg, HKV, N = 3, 2, N_PREFIX
+            from paper_2605_05219_amd import attention as AT, layer as LY, linear as LN
+            Lg, HKV, N, DM = 3, 2, N_PREFIX, 2048
             Cc = 3 * HEADS * D
             step_ck = N // M_CKPT
             lsh = LY.make_layer_shape(HEADS, HEADS, D, D, 4, "bf16", "bf16", "f32", L=Lg, T_alloc=N)   # the three layers in one call
@@ -622,33 +650,76 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
             gws = torch.empty(B.gdn_workspace_bytes(gsh, 1, N, M_CKPT), dtype=torch.uint8, device=dev)
             lws = torch.empty(LY.gdn_layer_workspace_bytes(1, M_CKPT), dtype=torch.uint8, device=dev)
             aws2 = torch.empty(AT.attn_workspace_bytes(ash, 1, N), dtype=torch.uint8, device=dev)
+            # the projections: the hidden stream of d_model 2048 into [conv input | z | a | b] per GatedDeltaNet layer and
+            # [q | k | v] for the attention layer, and each layer's output back to d_model (seeded synthetic weights)
+            HV = HEADS * D
+            hid = bf(N, DM)
+            hid_out = torch.empty((Lg + 1, N, DM), dtype=torch.bfloat16, device=dev)
+            w_in = (torch.randn((Lg, Cc + HV + 2 * HEADS, DM), device=dev) / DM ** 0.5).bfloat16()
+            w_out = (torch.randn((Lg + 1, DM, HV), device=dev) / HV ** 0.5).bfloat16()
+            w_att = (torch.randn((HV + 2 * HKV * D, DM), device=dev) / DM ** 0.5).bfloat16()
+            cur = torch.cuda.current_stream().cuda_stream
+            BF = B.GDN_BF16
 
-            def hit(n, from_host):
+            def lin(x, ldx, w, n_out, k_in, y, ldy, n_tok):
+                rc = LN.gdn_linear_raw(x, ldx, w, k_in, 0, y, ldy, BF, n_tok, n_out, k_in, cur)
+                if rc < 0:
+                    raise B.GdnError(rc, "gdn_linear")
+
+            def proj_in(c, n):
+                x = hid.data_ptr() + 2 * c * DM
+                for l in range(Lg):
+                    wl_ = w_in.data_ptr() + 2 * l * w_in.stride(0)
+                    lin(x, DM, wl_, Cc, DM, xs.data_ptr() + 2 * (l * N + c) * Cc, Cc, n)
+                    lin(x, DM, wl_ + 2 * Cc * DM, HV, DM, zs.data_ptr() + 2 * (l * N + c) * HV, HV, n)
+                    lin(x, DM, wl_ + 2 * (Cc + HV) * DM, HEADS, DM, aps.data_ptr() + 2 * (l * N + c) * HEADS, HEADS, n)
+                    lin(x, DM, wl_ + 2 * (Cc + HV + HEADS) * DM, HEADS, DM, bps.data_ptr() + 2 * (l * N + c) * HEADS, HEADS, n)
+                wa = w_att.data_ptr()
+                lin(x, DM, wa, HV, DM, aq2.data_ptr() + 2 * c * HV, HV, n)
+                lin(x, DM, wa + 2 * HV * DM, HKV * D, DM, akn2.data_ptr() + 2 * c * HKV * D, HKV * D, n)
+                lin(x, DM, wa + 2 * (HV + HKV * D) * DM, HKV * D, DM, avn2.data_ptr() + 2 * c * HKV * D, HKV * D, n)
+
+            def proj_out_gdn(c, n):
+                for l in range(Lg):
+                    lin(yp.data_ptr() + 2 * l * N * HV, HV, w_out.data_ptr() + 2 * l * DM * HV, DM, HV,
+                        hid_out.data_ptr() + 2 * (l * N + c) * DM, DM, n)
+
+            def proj_out_attn(c, n):
+                lin(ao2.data_ptr(), HV, w_out.data_ptr() + 2 * Lg * DM * HV, DM, HV, hid_out.data_ptr() + 2 * (Lg * N + c) * DM, DM, n)
+
+            def hit(n, from_host, proj=True):
                 c = N - n                                   # the checkpoint the request resumes from
                 emits = list(range(c + step_ck, N + 1, step_ck))
                 eslots = list(range(1, 1 + len(emits)))
                 if c > 0 and from_host:
                     B.ckpt_fetch_host(hstate, [c // step_ck], spool, [0])
                     AT.attn_kv_restore(ash, [c], hk, hv, [0], kc2, vc2, [0])
+                if proj:
+                    proj_in(c, n)
                 LY.gdn_layer_inputs(lsh, xs[0, c:], cw, cb, aps[0, c:], bps[0, c:], Al, dtb, [0, n], [c], cpool,
                                     [0 if c > 0 else -1], [0, len(emits)], emits, cpool, eslots, qp, kp, vp, bp_, gp_, lws)
                 B.gdn_resume_prefill(gsh, qp, kp, vp, bp_, gp_, [0, n], [c], spool, [0 if c > 0 else -1], [0, len(emits)], emits,
                                      spool, eslots, op, gws)
                 LY.gdn_layer_output(lsh, op, zs[0, c:], nw, yp, n)
+                if proj:
+                    proj_out_gdn(c, n)
                 AT.attn_suffix_prefill(ash, aq2[c:], akn2[c:], avn2[c:], None, [0, n], [c], kc2, vc2, [0], ao2, aws2)
+                if proj:
+                    proj_out_attn(c, n)
 
             pts = []
+            keys = (("ms_host_tier", True, True), ("ms_hbm_tier", False, True), ("ms_hbm_tier_without_projections", False, False))
             for n in (512, 1024, 2048, 4096, 6144, 8192):
                 row = {"suffix_tokens": n}
-                for key, from_host in (("ms_host_tier", True), ("ms_hbm_tier", False)):
+                for key, from_host, proj in keys:
                     for _ in range(3):
-                        hit(n, from_host)
+                        hit(n, from_host, proj)
                     torch.cuda.synchronize()
                     reps, batches = 8, []
                     for _ in range(5):                      # the median of five batches: one slow copy does not decide a point
                         tg0 = time.perf_counter()
                         for _ in range(reps):
-                            hit(n, from_host)
+                            hit(n, from_host, proj)
                         torch.cuda.synchronize()
                         batches.append(1e3 * (time.perf_counter() - tg0) / reps)
                     row[key] = float(np.median(batches))
@@ -657,15 +728,18 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
                 pts.append(row)
             xs_ = np.array([p["suffix_tokens"] for p in pts], float)
             fit = {}
-            for key in ("ms_host_tier", "ms_hbm_tier"):
+            for key, _, _ in keys:
                 slope, icpt = np.polyfit(xs_[:-1], np.array([p[key] for p in pts[:-1]]), 1)    # the hits; the last point is the miss
                 fit[key] = {"per_1k_tokens": 1e3 * slope, "offset": icpt}
-            out["layer_group"] = {"layers": "3 GatedDeltaNet + 1 attention (16 query / 2 kv heads), d = 128, projections excluded",
-                                  "points": pts, "fit_ms": fit,
-                                  "note": "wall time of a whole hit per suffix length (8192 = a miss: nothing restored; four entry-point calls "
-                                          "per hit: front ends of the three layers, recurrence, back ends, attention); host tier: "
-                                          "checkpoint states (3 MiB) and the KV prefix come from pinned host memory inside the timed "
-                                          "region; hbm tier: both are already in device memory"}
+            proj_flops_per_token = 2.0 * DM * (Lg * (Cc + HV + 2 * HEADS) + HV + 2 * HKV * D + (Lg + 1) * HV)
+            out["layer_group"] = {"layers": "3 GatedDeltaNet + 1 attention (16 query / 2 kv heads), d = 128, d_model 2048, projections included",
+                                  "points": pts, "fit_ms": fit, "projection_flops_per_token": proj_flops_per_token,
+                                  "note": "wall time of a whole hit per suffix length (8192 = a miss: nothing restored): in-projections of "
+                                          "the four layers (gdn_linear, bf16), front ends of the three GatedDeltaNet layers, recurrence, "
+                                          "back ends, their out-projections, attention and its out-projection; every layer reads the same "
+                                          "hidden rows (the cost of a stacked group, not its data flow); host tier: checkpoint states "
+                                          "(3 MiB) and the KV prefix come from pinned host memory inside the timed region; hbm tier: both "
+                                          "are already in device memory; the last column leaves the projections out"}
             del xs, zs, qp, kp, vp, op, spool, hstate, cpool, kc2, vc2
         except Exception as exc:
             out["layer_group"] = {"error": repr(exc)}
