@@ -14,22 +14,25 @@
 // where only the four 16x16 diagonal inverses T_aa = (I + L_aa)^-1 are computed (fp32, in registers, see
 // inv16_tiles) and the state-independent blocks  T_aa diag(b),  -T_aa diag(b gam),  -T_aa L_ac  (fp32 products,
 // rounded once to fp16) are left in LDS as matrix-core operands.  Every other product is a
-// v_mfma_f32_16x16x32_f16 (or 16x16x16 where the contraction is one block): an accumulator tile holds rows
-// 4 g4 + e of column m in lane (m, g4), which is exactly the B operand of a product that contracts over those
-// rows, so K S0^T, U_c and U feed the next product from registers.
+// v_mfma_f32_16x16x32_f16, a lone 16-row block being paired with a zero half (one instruction shape throughout: a
+// 16x16x16 that takes as its accumulator input the result of the 16x16x32 issued just before it was seen to read
+// stale values).  An accumulator tile holds rows 4 g4 + e of column m in lane (m, g4), which is exactly the B
+// operand of a product that contracts over those rows, so K S0^T, U_c and U feed the next product from registers.
 //
 // A workgroup is four waves.  Preparation: wave a owns block row a (its diagonal inverse, its L blocks and
 // their products with T_aa) and the P blocks of query block 3 - a, five 16x16 gram blocks each.  Recurrence:
 // wave w owns the 32 d_v columns 32 w .. 32 w + 31 of the state (two 16-column tiles, the state of a tile in
-// eight accumulator tiles over d_k).  Three barriers per chunk.
+// eight accumulator tiles over d_k); the state products of block row a + 1 are issued ahead of block row a's
+// substitution.  Three barriers per chunk.
 //
-// LDS (65 KiB, two workgroups per compute unit):
-//   K, Q, V  fp16 [64][128], rows unpadded, the 8-byte pieces of a row XOR-swizzled with the row number so
-//            that both read patterns are free of bank conflicts: row reads (lane = token, 8 bytes of a row:
-//            the A/B operand of a product over d_k) and transposing reads (ds_read_b64_tr_b16: lane = column,
-//            four tokens: K^T for the state update, V^T for the substitution)
-//   TbTg[a]  [16][32 (+4)] fp16: row i of T_aa diag(b) followed by row i of -T_aa diag(b gam)
-//   M[a][c]  [16][16 (+4)] fp16: -T_aa L_ac, c < a         P[ia][c] [16][16 (+4)] fp16, c <= ia
+// LDS (FusedSmem, 72.3 KB, two workgroups per compute unit):
+//   K, Q, V  fp16 [64][128], rows unpadded, the 16-byte pieces of a row XOR-swizzled with the row number (swz):
+//            row reads (lane = token, one piece: the A/B operand of a product over d_k) are free of bank
+//            conflicts, transposing reads (ds_read_b64_tr_b16: lane = column, four tokens: K^T for the state
+//            update, V^T for the substitution) touch one half of every piece and are two-way at best
+//   pair tiles [16][2 x 16 (+8)] fp16, two blocks side by side so that a 16x16x32 operand is one 16-byte read:
+//            TbTg[a] = [T_aa diag(b) | -T_aa diag(b gam)],  M = -T_aa L_ac (c < a),  P (c <= ia); a lone block's
+//            partner half stays zero from the start of the kernel
 //   Tf[w]    fp32 [16][20]: a wave's T_aa on its way from the accumulator layout to its transpose
 //   g, b, gam, dec, -b gam: fp32 [64] each
 #pragma once
