@@ -171,15 +171,22 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     for (int i = tid; i < (SM::TF_OFF - SM::TBTG_OFF) / 16; i += 256)
         reinterpret_cast<u32x4*>(smem + SM::TBTG_OFF)[i] = u32x4{0u, 0u, 0u, 0u};
 
-    // ---- the workgroup's items: the chunks of chains blockIdx.x, blockIdx.x + gridDim.x, ...
-    struct Item { int chain, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
-    auto open_chain = [&](int chain) -> Item {
+    // ---- the workgroup's items: the chunks of one chain per round of gridDim.x chains.  The chains come longest first,
+    //      so the rounds are dealt in alternating directions (workgroup b takes chain b of an even round and chain
+    //      gridDim.x - 1 - b of an odd one): dealt one way only, workgroup 0 would get the longest chain of every round and
+    //      the last workgroup the shortest, and the sums would differ by the length of the longest chain.
+    struct Item { int chain, round, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
+    auto open_chain = [&](int round) -> Item {
         Item it;
-        for (;; chain += (int)gridDim.x) {
-            it.chain = chain < a.n_chains ? chain : -1;
+        const int G = (int)gridDim.x, b = (int)blockIdx.x;
+        for (;; ++round) {
+            const int chain = round * G + ((round & 1) ? G - 1 - b : b);
+            it.chain = (round * G < a.n_chains && chain < a.n_chains) ? chain : -1;
+            it.round = round;
             it.c = it.c_end = it.lh = it.tok0 = it.n = 0;
             it.eslot = -1;
-            if (it.chain < 0) return it;
+            if (round * G >= a.n_chains) return it;     // no round left
+            if (it.chain < 0) continue;                 // the last, partial round dealt downwards may still hold a chain for b: none here
             const int r = plan_word(a.req_order, chain / units);
             it.lh = chain % units;
             it.c = plan_word(a.req_chunk_cu, r);
@@ -200,7 +207,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             it.eslot = plan_word(a.chunk_emit_slot, it.c);
             return it;
         }
-        return open_chain(cur.chain + (int)gridDim.x);
+        return open_chain(cur.round + 1);
     };
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[4], qraw[4], vraw[4];
@@ -233,7 +240,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
     };
 
-    Item cur = open_chain((int)blockIdx.x);
+    Item cur = open_chain(0);
     if (cur.chain < 0) return;
     fetch(cur, tg_, d0_, lane_);
     Item nxt = next_item(cur);
