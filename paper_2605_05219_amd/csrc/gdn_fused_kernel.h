@@ -34,7 +34,7 @@
 //            TbTg[a] = [T_aa diag(b) | -T_aa diag(b gam)],  M = -T_aa L_ac (c < a),  P (c <= ia); a lone block's
 //            partner half stays zero from the start of the kernel
 //   Tf[w]    fp32 [16][20]: a wave's T_aa on its way from the accumulator layout to its transpose
-//   g, b, gam, dec, -b gam: fp32 [64] each
+//   g, b, gam, dec, -b gam, and the factors of the decay between blocks (s, b r_c, scale r_c; see the gates): fp32 [64] each
 #pragma once
 #include "gdn_prep_kernel.h"
 #include "gdn_recur_kernel.h"
@@ -77,7 +77,7 @@ struct FusedSmem {
     static constexpr int P_OFF = M_OFF + 4 * PAIR_BYTES;     // pair tiles (0: P00,0) (1: P10,P11) (2: P20,P21) (2: P22,0) (3: P30,P31) (3: P32,P33)
     static constexpr int TF_OFF = P_OFF + 6 * PAIR_BYTES;
     static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
-    static constexpr int BYTES = SM_OFF + 5 * C * 4;
+    static constexpr int BYTES = SM_OFF + 12 * C * 4;        // g, b, gam, dec, -b gam, s, 3 x b r, 3 x scale r
     static_assert(TBTG_OFF % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
     // pair tile index of block (a, c) of M (c < a) and of P (c <= a)
@@ -154,6 +154,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     float* const gamS = bS + C;
     float* const decS = gamS + C;
     float* const bgS = decS + C;     // -b gam
+    float* const sS = bgS + C;       // s_j = exp(g_end(block of j) - g_j)
+    float* const brS = sS + C;       // [3][64]: b_i exp(g_i - g_end(c)), c = 0..2, for tokens i of later blocks
+    float* const prS = brS + 3 * C;  // [3][64]: scale exp(g_i - g_end(c))
 
     const int tid = threadIdx.x;
     const int lane_ = tid & 63;
@@ -302,7 +305,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (!first) __syncthreads();   // the previous item's recurrence is done with every LDS tile
         first = false;
 
-        // ---- gates: g_i = inclusive running sum of log a, b_i; identity beyond n (every wave computes them, wave 0 stores)
+        // ---- gates: g_i = inclusive running sum of log a, b_i; identity beyond n.  Every wave runs the scan; the derived
+        //      arrays are shared out over the waves.  Between blocks of 16 tokens the decay factors into a row and a column
+        //      part, exp(g_i - g_j) = exp(g_i - g_end(c)) exp(g_end(c) - g_j) for j in block c and i in a later block, both
+        //      exponents <= 0 since g never rises: the blocks off the diagonal then need no exponential per element.
         {
             float la = 0.f, b = 0.f;
             if (lane < n) {
@@ -310,14 +316,30 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 b = EL::widen(braw);
             }
             const float s = wave_running_sum(la);
+            const int sbits = __builtin_bit_cast(int, s);
+            const float e0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 15));
+            const float e1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 31));
+            const float e2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 47));
             const float g_last = wave_last_lane(s);
-            const float gam = EL::exp_(s);
             if (wave == 0) {
                 gS[lane] = s;
                 bS[lane] = b;
-                gamS[lane] = gam;
+                gamS[lane] = EL::exp_(s);
+            } else if (wave == 1) {
                 decS[lane] = EL::exp_(g_last - s);
-                bgS[lane] = -b * gam;
+                bgS[lane] = -b * EL::exp_(s);
+            } else if (wave == 2) {
+                const float eb = lane < 16 ? e0 : lane < 32 ? e1 : lane < 48 ? e2 : g_last;
+                sS[lane] = EL::exp_(fminf(eb - s, 0.f));
+                const float r0 = EL::exp_(fminf(s - e0, 0.f));
+                brS[lane] = b * r0;
+                prS[lane] = a.scale * r0;
+            } else {
+                const float r1 = EL::exp_(fminf(s - e1, 0.f)), r2 = EL::exp_(fminf(s - e2, 0.f));
+                brS[C + lane] = b * r1;
+                prS[C + lane] = a.scale * r1;
+                brS[2 * C + lane] = b * r2;
+                prS[2 * C + lane] = a.scale * r2;
             }
         }
         // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
@@ -393,10 +415,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
                     for (int s = 0; s < 4; ++s) acc = mma32(ka[s], kc[s], acc);   // rows i in block ab, lanes j in block c
-                    const float gjc = gS[16 * c + m];
+                    const float sj = sS[16 * c + m];
+                    const f32x4 br = *reinterpret_cast<const f32x4*>(brS + c * C + 16 * ab + 4 * g4);
                     f32x4 lt;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) lt[e] = bi[e] * EL::exp_(fminf(gi[e] - gjc, 0.f)) * acc[e];   // L_ac[4 g4 + e][m]
+                    for (int e = 0; e < 4; ++e) lt[e] = br[e] * (sj * acc[e]);   // L_ac[4 g4 + e][m]
                     const f32x4 zero = {0, 0, 0, 0};
                     const f32x4 mt_ = mm16_rr(zero, lt, at);     // (L^T T^T): element e of lane (m, g4) = (T L)[m][4 g4 + e]
                     f32x4 neg;
@@ -408,12 +431,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
                     for (int s = 0; s < 4; ++s) acc = mma32(kc[s], qf[s], acc);
-                    const f32x4 gk = *reinterpret_cast<const f32x4*>(gS + 16 * c + 4 * g4);
                     f32x4 p;
+                    if (c < ia) {   // a block below the diagonal: every key is visible, the decay factors
+                        const float pr = prS[c * C + 16 * ia + m];
+                        const f32x4 sk = *reinterpret_cast<const f32x4*>(sS + 16 * c + 4 * g4);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float val = a.scale * EL::exp_(fminf(gq - gk[e], 0.f)) * acc[e];
-                        p[e] = (16 * c + 4 * g4 + e <= 16 * ia + m) ? val : 0.f;
+                        for (int e = 0; e < 4; ++e) p[e] = pr * (sk[e] * acc[e]);
+                    } else {
+                        const f32x4 gk = *reinterpret_cast<const f32x4*>(gS + 16 * c + 4 * g4);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float val = a.scale * EL::exp_(fminf(gq - gk[e], 0.f)) * acc[e];
+                            p[e] = (4 * g4 + e <= m) ? val : 0.f;
+                        }
                     }
                     *reinterpret_cast<half4*>(pimg + (SM::p_pair(ia, c) * 16 + m) * PLD + 8 * g4 + 4 * (c & 1)) = cvt4(p);
                 }
