@@ -23,8 +23,8 @@
  * Arithmetic: bf16 products on the matrix cores, fp32 accumulation over k in the order of the
  * k index by blocks of 16; the bias is added in fp32; one rounding to out_dtype.
  * Errors: GDN_ERR_NULL, GDN_ERR_ALIGN, GDN_ERR_SHAPE (K not a multiple of 64, a leading dimension
- * smaller than its row, an unknown out_dtype), GDN_ERR_COUNT (a negative size, or a matrix of 4 GiB
- * and more per 128-row tile).
+ * smaller than its row, an unknown out_dtype), GDN_ERR_COUNT (a negative size, or a leading dimension of 4 Mi
+ * elements and more: a 256-row tile is addressed with 31-bit byte offsets).
  */
 #ifndef GDN_LINEAR_H
 #define GDN_LINEAR_H
@@ -40,6 +40,14 @@ extern "C" {
 int32_t gdn_linear(const void *x, int64_t ldx, const void *w, int64_t ldw, const float *bias,
                    void *y, int64_t ldy, int32_t out_dtype,
                    int64_t T, int32_t N, int32_t K, void *stream);
+
+/*
+ * Tuning knob, not a method step: fixes the workgroup tile gdn_linear uses (0: 128 x 128, 1: 256 x 256; anything
+ * else: chosen per call from T and N, the default).  Every shape computes the same
+ * sums in the same order, so the results do not depend on it.  Process-wide; returns the previous setting (-1 = per
+ * call).
+ */
+int32_t gdn_linear_tune(int32_t shape);
 
 #ifdef __cplusplus
 }

@@ -1,24 +1,31 @@
 // gdn_linear: the layers' projections y = x w^T + bias on the bf16 matrix cores (see include/gdn_linear.h).
 //
-// One workgroup of four waves makes a 128 (tokens) x 128 (outputs) tile; a wave a 64 x 64 quarter as 2 x 2
-// accumulator tiles of v_mfma_f32_32x32x16_bf16.  Both operands are read along k, so a tile of x and a tile of w
-// (128 rows x 64 k each, 16 KiB) are what a k step of 64 needs; they come from memory with 16-byte buffer loads
-// straight to LDS (no registers), into the other of two stages while the matrix cores work on this one: one
-// barrier per k step.  A load to LDS writes a wave's 1 KiB contiguously (lane i at 16 i), so rows are unpadded
-// (128 bytes) and bank conflicts are avoided by choosing WHICH 16-byte piece of its row a lane fetches: piece p of
-// row r is stored at position p ^ ((r >> 1) & 7), which makes the 16 lanes of a fragment read (16 consecutive rows,
-// the same piece) hit 16 different 16-byte bank groups.  Rows past the end of x or w read as zeros (the buffer
-// descriptor ends with the matrix).  The products are taken transposed (w rows as the left operand), so that a
-// lane holds four consecutive outputs of ONE token and stores them with one 8- or 16-byte store.
+// One workgroup of four waves (2 x 2) makes a BM (tokens) x BN (outputs) tile, a wave a quarter of it as tiles of
+// v_mfma_f32_32x32x16_bf16.  Both operands are read along k, so a k step of BK needs a BM x BK tile of x and a
+// BN x BK tile of w; they come from memory with 16-byte buffer loads straight to LDS (no registers) into a ring of
+// STAGES stages, STAGES - 1 k steps ahead of the matrix cores: one barrier per k step.  Two shapes are built:
+//   128 x 128 x 64, 2 stages, two workgroups per compute unit   small problems (more, smaller workgroups)
+//   256 x 256 x 32, 4 stages, one workgroup per compute unit    a wave holds 128 x 128 outputs in 256 accumulator
+//                   registers: half the operand bytes per flop, from memory and from LDS, and three k steps of
+//                   loads in flight
+// A load to LDS writes a wave's 1 KiB contiguously (lane i at 16 i), so rows are unpadded (2 BK bytes) and bank
+// conflicts are avoided by choosing WHICH 16-byte piece of its row a lane fetches: piece p of row r is stored at
+// position p ^ swz(r), swz(r) = (r / rows per 256 bytes) % pieces per row, which makes the 16 lanes that read the
+// same piece of 16 consecutive rows hit 16 different 16-byte bank groups.  Rows past the end of x or w read as
+// zeros (the buffer descriptor ends with the matrix); they only feed outputs that are never stored.  The products
+// are taken transposed (w rows as the left operand), so that a lane holds four consecutive outputs of ONE token
+// and stores them with one 8- or 16-byte store.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <cmath>
 #include <cstdint>
 
 #include "gdn_linear.h"
 
 namespace gdn {
-namespace {
+namespace linear {
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -26,9 +33,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int LIN_BM = 128, LIN_BN = 128, LIN_BK = 64, LIN_THREADS = 256;
-constexpr int LIN_TILE_BYTES = LIN_BM * LIN_BK * 2;        // 16 KiB: one operand tile of one stage
-constexpr int LIN_SMEM = 4 * LIN_TILE_BYTES;               // x and w tiles, two stages
+constexpr int LIN_THREADS = 256;
 
 struct LinearArgs {
     const void* x;
@@ -43,94 +48,190 @@ struct LinearArgs {
 
 inline int32_t hip_err(hipError_t e) { return e == hipSuccess ? GDN_OK : GDN_ERR_HIP - (int32_t)e; }
 
-__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt vmcnt(N) (gfx9 encoding: vmcnt in bits 3:0 and 15:14; other counters left alone)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
+}
 
-template <bool OUT_BF16>
-__global__ void __launch_bounds__(LIN_THREADS) gdn_linear_kernel(LinearArgs a) {
+template <int BM_, int BN_, int BK_, int STAGES_, int WGS_PER_CU_>
+struct LinCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WGS_PER_CU = WGS_PER_CU_;
+    static constexpr int RB = BK * 2;                  // bytes of a tile row
+    static constexpr int PP = RB / 16;                 // 16-byte pieces per row
+    static constexpr int RL = 256 / RB;                // rows per 256 bytes (the span of the 64 banks)
+    static constexpr int ROWS_PER_LOAD = 1024 / RB;    // rows a wave-wide load covers
+    static constexpr int X_BYTES = BM * RB, W_BYTES = BN * RB, STAGE_BYTES = X_BYTES + W_BYTES;
+    static constexpr int SMEM = STAGES * STAGE_BYTES;
+    static constexpr int TI = BM / 64, TJ = BN / 64;   // 32 x 32 tiles of a wave along tokens / outputs
+    static constexpr int XL = BM / ROWS_PER_LOAD / 4, WL = BN / ROWS_PER_LOAD / 4;   // loads per wave and stage
+    static constexpr int LPS = XL + WL;
+    static constexpr int AHEAD = (STAGES - 2) * LPS;   // loads that may still be in flight when a stage is handed over
+    static_assert(PP * RL == 16 && (STAGES - 1) * LPS < 64 && SMEM <= 160 * 1024 && (BK / 16) % 2 == 0 &&
+                  ((BM / 64) * (BN / 64) % LPS == 0 || LPS % ((BM / 64) * (BN / 64)) == 0), "tile shape");
+};
+typedef LinCfg<128, 128, 64, 2, 2> LinSmall;
+typedef LinCfg<256, 256, 32, 4, 1> LinBig;
+
+// Load j of the LPS loads of one wave for one stage: 1 KiB of its quarter of the x tile (j < XL) or of the w tile.
+template <typename CFG>
+__device__ __forceinline__ void lin_issue_one(int j, char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb,
+                                              int w_bytes, const int* xoff, const int* woff) {
+    // buffer descriptors that end with the matrices: rows past T or N arrive as zeros
+    char* xs = smem + stage * CFG::STAGE_BYTES;
+    char* ws = xs + CFG::X_BYTES;
+    if (j < CFG::XL) {
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xb), 0, x_bytes, 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + ((CFG::BM / 4) * wave + CFG::ROWS_PER_LOAD * j) * CFG::RB), 16, xoff[j], k0 * 2, 0, 0);
+    } else {
+        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wb), 0, w_bytes, 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + ((CFG::BN / 4) * wave + CFG::ROWS_PER_LOAD * (j - CFG::XL)) * CFG::RB), 16, woff[j - CFG::XL], k0 * 2, 0, 0);
+    }
+}
+template <typename CFG>
+__device__ __forceinline__ void lin_issue(char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb, int w_bytes,
+                                          const int* xoff, const int* woff) {
+#pragma unroll
+    for (int j = 0; j < CFG::LPS; ++j) lin_issue_one<CFG>(j, smem, stage, k0, wave, xb, x_bytes, wb, w_bytes, xoff, woff);
+}
+
+template <typename CFG, bool OUT_BF16>
+__global__ void __launch_bounds__(LIN_THREADS) __attribute__((amdgpu_waves_per_eu(CFG::WGS_PER_CU, CFG::WGS_PER_CU)))
+gdn_linear_kernel(LinearArgs a) {
+    constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, STAGES = CFG::STAGES, RB = CFG::RB, PP = CFG::PP, RL = CFG::RL;
+    constexpr int RPL = CFG::ROWS_PER_LOAD, TI = CFG::TI, TJ = CFG::TJ, XL = CFG::XL, WL = CFG::WL;
     extern __shared__ __align__(16) char smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;                 // the wave's quarter: tokens 64 wm .., outputs 64 wn ..
+    const int wm = wave >> 1, wn = wave & 1;                 // the wave's quarter: tokens (BM/2) wm .., outputs (BN/2) wn ..
     const int lr = lane & 31, g = lane >> 5;
     const int tile_m = (int)blockIdx.x / a.tiles_n, tile_n = (int)blockIdx.x % a.tiles_n;
-    const int64_t m0 = (int64_t)tile_m * LIN_BM;
-    const int n0 = tile_n * LIN_BN;
+    const int64_t m0 = (int64_t)tile_m * BM;
+    const int n0 = tile_n * BN;
 
-    // buffer descriptors that end with the matrices: rows past T or N arrive as zeros
-    const int64_t rows_x = a.T - m0 < LIN_BM ? a.T - m0 : LIN_BM;
-    const int rows_w = a.N - n0 < LIN_BN ? a.N - n0 : LIN_BN;
+    const int64_t rows_x = a.T - m0 < BM ? a.T - m0 : BM;
+    const int rows_w = a.N - n0 < BN ? a.N - n0 : BN;
     const char* xb = reinterpret_cast<const char*>(a.x) + m0 * a.ldx * 2;
     const char* wb = reinterpret_cast<const char*>(a.w) + (int64_t)n0 * a.ldw * 2;
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xb), 0, (int)((rows_x - 1) * a.ldx * 2 + a.K * 2), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wb), 0, (int)((int64_t)(rows_w - 1) * a.ldw * 2 + a.K * 2), 0x00020000);
+    const int x_bytes = (int)((rows_x - 1) * a.ldx * 2 + (int64_t)a.K * 2), w_bytes = (int)((int64_t)(rows_w - 1) * a.ldw * 2 + (int64_t)a.K * 2);
 
-    // a wave-wide load writes 8 rows of 128 bytes: lane i lands at row i / 8, position i % 8, and fetches the piece that belongs there
-    const int ld_row = lane >> 3, ld_pos = lane & 7;
-    int xoff[4], woff[4];        // byte offsets (k = 0) of the 4 loads per operand this wave issues per stage: rows 32 wave + 8 j ..
+    // a wave-wide load writes RPL rows of RB bytes: lane i lands at row i / PP, position i % PP, and fetches the piece that belongs there
+    const int ld_row = lane / PP, ld_pos = lane % PP;
+    int xoff[XL], woff[WL];      // byte offsets (k = 0) of the loads this wave issues per stage
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = 32 * wave + 8 * j + ld_row;
-        const int piece = ld_pos ^ ((row >> 1) & 7);
-        xoff[j] = (int)(row * a.ldx * 2) + piece * 16;
-        woff[j] = (int)(row * a.ldw * 2) + piece * 16;
+    for (int j = 0; j < XL; ++j) {
+        const int row = (BM / 4) * wave + RPL * j + ld_row;
+        xoff[j] = (int)(row * a.ldx * 2) + ((ld_pos ^ ((row / RL) % PP)) << 4);
     }
-    auto issue = [&](int stage, int k0) {
-        char* xs = smem + stage * 2 * LIN_TILE_BYTES;
-        char* ws = xs + LIN_TILE_BYTES;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + (32 * wave + 8 * j) * 128), 16, xoff[j], k0 * 2, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + (32 * wave + 8 * j) * 128), 16, woff[j], k0 * 2, 0, 0);
-        }
-    };
-
-    f32x16 acc[2][2];            // [output tile tj][token tile ti]: lane = token, register 4 b + e = output 8 b + 4 g + e
+    for (int j = 0; j < WL; ++j) {
+        const int row = (BN / 4) * wave + RPL * j + ld_row;
+        woff[j] = (int)(row * a.ldw * 2) + ((ld_pos ^ ((row / RL) % PP)) << 4);
+    }
+    f32x16 acc[TJ][TI];          // [output tile][token tile]: lane = token, register 4 b + e = output 8 b + 4 g + e
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TJ; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TI; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // fragment read offsets: row r of a tile, piece 2 kk + g, stored at (2 kk + g) ^ ((r >> 1) & 7)
-    const int sw = (lr >> 1) & 7;            // the same for rows r + 32 ti (32 >> 1 = 16 keeps the low three bits)
-    const int n_steps = a.K / LIN_BK;
-    issue(0, 0);
-    for (int step = 0; step < n_steps; ++step) {
-        const int stage = step & 1;
-        wait_vm0();                          // this stage has landed (nothing else is in flight)
-        __syncthreads();                     // ... for every wave, and every wave is done with the other stage
-        if (step + 1 < n_steps) issue(stage ^ 1, (step + 1) * LIN_BK);
-        const char* xs = smem + stage * 2 * LIN_TILE_BYTES;
-        const char* ws = xs + LIN_TILE_BYTES;
+    // fragment reads: row r of a tile, piece 2 kk + g, stored at (2 kk + g) ^ swz(r); tile origins are multiples of 16 rows
+    const int sw = (lr % 16) / RL;
+    const int xrow = ((BM / 2) * wm + lr) * RB, wrow = ((BN / 2) * wn + lr) * RB;
+    const int n_steps = a.K / BK;
+    constexpr int KK = BK / 16;              // matrix-instruction steps per stage (2 or 4)
+    // The stages are consumed through two fragment sets: while the matrix cores work on one k step of 16, the fragments of
+    // the next are read from LDS, also across the stage boundary.  The hand-over of a stage therefore sits before the LAST
+    // k step of the stage in front of it: wait for this wave's loads of the next stage, for its own fragment reads, then the
+    // barrier; after it the next stage is readable by every wave and the current one (whose last fragments are in
+    // registers) is free and is refilled with the stage STAGES ahead.
+    bf16x8 xf[2][TI], wf[2][TJ];
+    auto read_frags = [&](int stage, int kk, int set) {
+        const char* xs = smem + stage * CFG::STAGE_BYTES;
+        const char* ws = xs + CFG::X_BYTES;
+        const int pos = ((2 * kk + g) ^ sw) * 16;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int pos = ((2 * kk + g) ^ sw) * 16;
-            bf16x8 xf[2], wf[2];
+        for (int t = 0; t < TI; ++t) xf[set][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xs + xrow + 32 * t * RB + pos));
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                xf[t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xs + (64 * wm + 32 * t + lr) * 128 + pos));
-                wf[t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ws + (64 * wn + 32 * t + lr) * 128 + pos));
-            }
+        for (int t = 0; t < TJ; ++t) wf[set][t] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ws + wrow + 32 * t * RB + pos));
+    };
+    // Loads are issued for every stage slot, also past the last k step: there the descriptor is empty (no lane is in
+    // range, nothing is fetched), so that the number of loads in flight, and with it every wait below, is the same in
+    // every round and the loop body has no branch for the scheduler to stop at.
+    auto mma_all = [&](int set) {
 #pragma unroll
-            for (int tj = 0; tj < 2; ++tj)
+        for (int tj = 0; tj < TJ; ++tj)
 #pragma unroll
-                for (int ti = 0; ti < 2; ++ti)
-                    acc[tj][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[tj], xf[ti], acc[tj][ti], 0, 0, 0);
+            for (int ti = 0; ti < TI; ++ti)
+                acc[tj][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[set][tj], xf[set][ti], acc[tj][ti], 0, 0, 0);
+    };
+#pragma unroll
+    for (int p = 0; p < STAGES; ++p) {
+        const bool live = p < n_steps;
+        lin_issue<CFG>(smem, p, p * BK, wave, xb, live ? x_bytes : 0, wb, live ? w_bytes : 0, xoff, woff);
+    }
+    wait_vm<(STAGES - 1) * CFG::LPS>();
+    __syncthreads();
+    read_frags(0, 0, 0);
+    int stage = 0;                           // step % STAGES
+    for (int step = 0; step + 1 < n_steps; ++step) {
+        const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
+#pragma unroll
+        for (int kk = 0; kk + 1 < KK; ++kk) {
+            read_frags(stage, kk + 1, (kk & 1) ^ 1);
+            mma_all(kk & 1);
         }
+        // the next stage has landed for this wave (the STAGES - 2 stages behind it may still be in flight) ...
+        wait_vm<CFG::AHEAD>();
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // ... and this wave's last fragment reads of the current stage are done (lgkmcnt(0))
+        __syncthreads();
+        {
+            // The last k step of the stage (fragment set 1; KK is even), written out in issue order and pinned there: a load
+            // to LDS takes tens of cycles to issue, so one goes out behind every few matrix instructions, which covers it;
+            // the fragments of the next stage's first k step are read in between as well.
+            const bool live = step + STAGES < n_steps;
+            const int xbytes = live ? x_bytes : 0, wbytes = live ? w_bytes : 0;
+            const char* xs = smem + next_stage * CFG::STAGE_BYTES;
+            const char* ws = xs + CFG::X_BYTES;
+            const int pos = (g ^ sw) * 16;
+            constexpr int NM = TI * TJ, NL = CFG::LPS, NR = TI + TJ;
+            constexpr int SLOTS = NM < NL ? NM : NL;             // interleave slots
+#pragma unroll
+            for (int i = 0; i < SLOTS; ++i) {
+#pragma unroll
+                for (int q = i * NM / SLOTS; q < (i + 1) * NM / SLOTS; ++q)
+                    acc[q / TI][q % TI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][q / TI], xf[1][q % TI], acc[q / TI][q % TI], 0, 0, 0);
+#pragma unroll
+                for (int r = i * NR / SLOTS; r < (i + 1) * NR / SLOTS; ++r) {
+                    if (r < TI) xf[0][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xs + xrow + 32 * r * RB + pos));
+                    else wf[0][r - TI] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ws + wrow + 32 * (r - TI) * RB + pos));
+                }
+#pragma unroll
+                for (int j = i * NL / SLOTS; j < (i + 1) * NL / SLOTS; ++j)
+                    lin_issue_one<CFG>(j, smem, stage, (step + STAGES) * BK, wave, xb, xbytes, wb, wbytes, xoff, woff);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        stage = next_stage;
+    }
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {        // the last stage: nothing behind it
+        if (kk + 1 < KK) read_frags(stage, kk + 1, (kk & 1) ^ 1);
+        mma_all(kk & 1);
     }
 
     // ---- epilogue: bias, one rounding, 4 consecutive outputs of a token per store
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti) {
-        const int64_t tok = m0 + 64 * wm + 32 * ti + lr;
+    for (int ti = 0; ti < TI; ++ti) {
+        const int64_t tok = m0 + (BM / 2) * wm + 32 * ti + lr;
         if (tok >= a.T) continue;
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj)
+        for (int tj = 0; tj < TJ; ++tj)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const int col = n0 + 64 * wn + 32 * tj + 8 * b + 4 * g;
+                const int col = n0 + (BN / 2) * wn + 32 * tj + 8 * b + 4 * g;
                 if (col >= a.N) continue;
                 f32x4 v = {acc[tj][ti][4 * b], acc[tj][ti][4 * b + 1], acc[tj][ti][4 * b + 2], acc[tj][ti][4 * b + 3]};
                 const bool whole = col + 4 <= a.N;
@@ -157,16 +258,60 @@ __global__ void __launch_bounds__(LIN_THREADS) gdn_linear_kernel(LinearArgs a) {
     }
 }
 
-}  // namespace
+template <typename CFG, bool OUT_BF16>
+hipError_t launch_linear(LinearArgs a, hipStream_t stream) {
+    static hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_linear_kernel<CFG, OUT_BF16>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, CFG::SMEM);
+    if (attr_err != hipSuccess) return attr_err;
+    const int64_t tiles_m = (a.T + CFG::BM - 1) / CFG::BM;
+    a.tiles_n = (a.N + CFG::BN - 1) / CFG::BN;
+    hipLaunchKernelGGL((gdn_linear_kernel<CFG, OUT_BF16>), dim3((unsigned)(tiles_m * a.tiles_n)), dim3(LIN_THREADS), CFG::SMEM, stream, a);
+    return hipGetLastError();
+}
+
+std::atomic<int32_t> g_linear_shape{-1};
+
+int chip_cus_linear() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+            (void)hipGetLastError();
+            return 256;
+        }
+        return cus;
+    }();
+    return n;
+}
+
+// Which tile shape a problem gets: the estimated time of each shape is its number of rounds of workgroups over the
+// chip times the work of one workgroup over the shape's measured rate (relative figures).
+int choose_linear_shape(int64_t T, int32_t N) {
+    const int forced = g_linear_shape.load();
+    if (forced >= 0) return forced;
+    const double cus = (double)chip_cus_linear();
+    const struct { int bm, bn, per_cu; double rate; } shapes[2] = {{128, 128, 2, 0.36}, {256, 256, 1, 0.40}};
+    int best = 0;
+    double best_t = 0;
+    for (int i = 0; i < 2; ++i) {
+        const double wgs = (double)((T + shapes[i].bm - 1) / shapes[i].bm) * (double)((N + shapes[i].bn - 1) / shapes[i].bn);
+        const double rounds = std::ceil(wgs / (cus * shapes[i].per_cu));
+        const double t = rounds * shapes[i].per_cu * shapes[i].bm * shapes[i].bn / shapes[i].rate;
+        if (i == 0 || t < best_t) { best = i; best_t = t; }
+    }
+    return best;
+}
+
+}  // namespace linear
 }  // namespace gdn
 
 using namespace gdn;
+using namespace gdn::linear;
 
 extern "C" int32_t gdn_linear(const void* x, int64_t ldx, const void* w, int64_t ldw, const float* bias, void* y, int64_t ldy,
                               int32_t out_dtype, int64_t T, int32_t N, int32_t K, void* stream_) {
     if (T < 0 || N < 0 || K < 0) return GDN_ERR_COUNT;
     if (out_dtype != GDN_BF16 && out_dtype != GDN_F32) return GDN_ERR_SHAPE;
-    if (K % LIN_BK != 0 || ldx < K || ldw < K || ldy < N) return GDN_ERR_SHAPE;
+    if (K % 64 != 0 || ldx < K || ldw < K || ldy < N) return GDN_ERR_SHAPE;
     if (T == 0 || N == 0) return GDN_OK;
     if (K == 0) return GDN_ERR_SHAPE;
     if (!x || !w || !y) return GDN_ERR_NULL;
@@ -176,25 +321,23 @@ extern "C" int32_t gdn_linear(const void* x, int64_t ldx, const void* w, int64_t
         return GDN_ERR_ALIGN;
     if ((ldx & 7) || (ldw & 7) || (ldy & 3)) return GDN_ERR_ALIGN;
     // a tile's rows must be addressable with 31-bit byte offsets
-    if ((int64_t)LIN_BM * ldx * 2 >= ((int64_t)1 << 31) || (int64_t)LIN_BN * ldw * 2 >= ((int64_t)1 << 31)) return GDN_ERR_COUNT;
-    const int64_t tiles_m = (T + LIN_BM - 1) / LIN_BM;
-    const int64_t tiles_n = (N + LIN_BN - 1) / LIN_BN;
-    if (tiles_m * tiles_n > INT32_MAX) return GDN_ERR_COUNT;
+    if ((int64_t)256 * ldx * 2 >= ((int64_t)1 << 31) || (int64_t)256 * ldw * 2 >= ((int64_t)1 << 31)) return GDN_ERR_COUNT;
+    if (((T + 127) / 128) * (((int64_t)N + 127) / 128) > INT32_MAX) return GDN_ERR_COUNT;
     LinearArgs a;
     a.x = x; a.w = w; a.bias = bias; a.y = y;
     a.ldx = ldx; a.ldw = ldw; a.ldy = ldy;
     a.T = T; a.N = N; a.K = K;
-    a.tiles_n = (int32_t)tiles_n;
+    a.tiles_n = 0;
     hipStream_t stream = (hipStream_t)stream_;
-    const dim3 grid((unsigned)(tiles_m * tiles_n));
-    static hipError_t attr_err = [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_linear_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, LIN_SMEM);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_linear_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, LIN_SMEM);
-        return e;
-    }();
-    if (attr_err != hipSuccess) return hip_err(attr_err);
-    if (out_dtype == GDN_BF16) hipLaunchKernelGGL(gdn_linear_kernel<true>, grid, dim3(LIN_THREADS), LIN_SMEM, stream, a);
-    else hipLaunchKernelGGL(gdn_linear_kernel<false>, grid, dim3(LIN_THREADS), LIN_SMEM, stream, a);
-    return hip_err(hipGetLastError());
+    const bool bf = out_dtype == GDN_BF16;
+    hipError_t e;
+    switch (choose_linear_shape(T, N)) {
+        case 1: e = bf ? launch_linear<LinBig, true>(a, stream) : launch_linear<LinBig, false>(a, stream); break;
+        default: e = bf ? launch_linear<LinSmall, true>(a, stream) : launch_linear<LinSmall, false>(a, stream); break;
+    }
+    return hip_err(e);
+}
+
+extern "C" int32_t gdn_linear_tune(int32_t shape) {
+    return g_linear_shape.exchange(shape < 0 || shape > 1 ? -1 : shape);
 }

@@ -7,7 +7,7 @@ from .binding import GDN_BF16, GDN_F32, _check, _dp, _stream_ptr, lib
 
 _i32, _i64, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
 
-EXPORTS = ["gdn_linear"]
+EXPORTS = ["gdn_linear", "gdn_linear_tune"]
 
 _ready = False
 
@@ -18,6 +18,8 @@ def _lib():
     if not _ready:
         L.gdn_linear.restype = _i32
         L.gdn_linear.argtypes = [_vp, _i64, _vp, _i64, _vp, _vp, _i64, _i32, _i64, _i32, _i32, _vp]
+        L.gdn_linear_tune.restype = _i32
+        L.gdn_linear_tune.argtypes = [_i32]
         _ready = True
     return L
 
@@ -50,3 +52,8 @@ def gdn_linear(x, w, bias, y, stream=None) -> None:
     ldy = int(y.stride(0)) if T > 1 else max(N, int(y.stride(0)))
     _check(_lib().gdn_linear(_dp(x), ldx, _dp(w), ldw, _dp(bias), _dp(y), ldy, code, T, N, K, _stream_ptr(stream)),
            "gdn_linear")
+
+
+def gdn_linear_tune(shape: int) -> int:
+    """Fixes the workgroup tile (0, 1) or returns the choice to the library (-1); returns the previous setting."""
+    return int(_lib().gdn_linear_tune(int(shape)))

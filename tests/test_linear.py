@@ -49,7 +49,7 @@ def raw(**over):
     (dict(y_ptr=0x400008, out_dtype=B.GDN_F32), -2),
     (dict(bias_ptr=0x300002), -2),
     (dict(ldx=260), -2), (dict(ldw=257), -2), (dict(ldy=514), -2),
-    (dict(ldx=1 << 23), -11),                              # a 128-row tile would pass 2 GiB of byte offsets
+    (dict(ldx=1 << 22), -11),                              # a 256-row tile would pass 2 GiB of byte offsets
 ])
 def test_argument_errors_are_reported_before_any_launch(over, code):
     assert raw(**over) == code
@@ -58,6 +58,12 @@ def test_argument_errors_are_reported_before_any_launch(over, code):
 def test_empty_problems_are_legal_and_touch_nothing():
     assert raw(T=0, x_ptr=0, y_ptr=0) == 0
     assert raw(N=0, w_ptr=0, y_ptr=0, ldy=0) == 0
+
+
+def test_tile_knob_round_trip():
+    prev = LN.gdn_linear_tune(1)
+    assert LN.gdn_linear_tune(7) == 1          # out of range = per call
+    assert LN.gdn_linear_tune(prev) == -1
 
 
 def test_python_binding_rejects_mismatched_tensors():
@@ -126,11 +132,16 @@ def run_gpu(x, w, b, out, ldy=None, col0=0):
     (515, 2048, 2048, True, "f32"),            # the out-projection
     (64, 131, 192, True, "bf16"),              # an output count that is no multiple of 4 is only legal with ldy % 4 == 0
 ])
-def test_linear_against_the_definition(T, N, K, bias, out):
+@pytest.mark.parametrize("shape", [0, 1, -1])
+def test_linear_against_the_definition(T, N, K, bias, out, shape):
     x, w, b = draw(T * 7 + N * 3 + K, T, N, K, bias)
     ref = lo.linear(x, w, b)
     ldy = (N + 3) // 4 * 4
-    y = run_gpu(x, w, b, out, ldy=ldy)
+    prev = LN.gdn_linear_tune(shape)
+    try:
+        y = run_gpu(x, w, b, out, ldy=ldy)
+    finally:
+        LN.gdn_linear_tune(prev)
     assert np.isnan(y[:, N:]).all()            # nothing written past the last output
     err = np.abs(y[:, :N] - ref)
     tol = bound(x, w, b, ref, K, out)
