@@ -73,27 +73,28 @@ struct LinCfg {
 typedef LinCfg<128, 128, 64, 2, 2> LinSmall;
 typedef LinCfg<256, 256, 32, 4, 1> LinBig;
 
-// Load j of the LPS loads of one wave for one stage: 1 KiB of its quarter of the x tile (j < XL) or of the w tile.
+// The loads of one wave for one stage: 1 KiB each, XL of its quarter of the x tile, then WL of the w tile.
 template <typename CFG>
-__device__ __forceinline__ void lin_issue_one(int j, char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb,
-                                              int w_bytes, const int* xoff, const int* woff) {
-    // buffer descriptors that end with the matrices: rows past T or N arrive as zeros
-    char* xs = smem + stage * CFG::STAGE_BYTES;
-    char* ws = xs + CFG::X_BYTES;
-    if (j < CFG::XL) {
-        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xb), 0, x_bytes, 0x00020000);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + ((CFG::BM / 4) * wave + CFG::ROWS_PER_LOAD * j) * CFG::RB), 16, xoff[j], k0 * 2, 0, 0);
-    } else {
-        const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wb), 0, w_bytes, 0x00020000);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + ((CFG::BN / 4) * wave + CFG::ROWS_PER_LOAD * (j - CFG::XL)) * CFG::RB), 16, woff[j - CFG::XL], k0 * 2, 0, 0);
+struct LinLoad {
+    static __device__ __forceinline__ void one(int j, char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb,
+                                               int w_bytes, const int* xoff, const int* woff) {
+        // buffer descriptors that end with the matrices: rows past T or N arrive as zeros
+        char* xs = smem + stage * CFG::STAGE_BYTES;
+        char* ws = xs + CFG::X_BYTES;
+        if (j < CFG::XL) {
+            const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xb), 0, x_bytes, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + ((CFG::BM / 4) * wave + CFG::ROWS_PER_LOAD * j) * CFG::RB), 16, xoff[j], k0 * 2, 0, 0);
+        } else {
+            const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wb), 0, w_bytes, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + ((CFG::BN / 4) * wave + CFG::ROWS_PER_LOAD * (j - CFG::XL)) * CFG::RB), 16, woff[j - CFG::XL], k0 * 2, 0, 0);
+        }
     }
-}
-template <typename CFG>
-__device__ __forceinline__ void lin_issue(char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb, int w_bytes,
-                                          const int* xoff, const int* woff) {
+    static __device__ __forceinline__ void all(char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb, int w_bytes,
+                                               const int* xoff, const int* woff) {
 #pragma unroll
-    for (int j = 0; j < CFG::LPS; ++j) lin_issue_one<CFG>(j, smem, stage, k0, wave, xb, x_bytes, wb, w_bytes, xoff, woff);
-}
+        for (int j = 0; j < CFG::LPS; ++j) one(j, smem, stage, k0, wave, xb, x_bytes, wb, w_bytes, xoff, woff);
+    }
+};
 
 template <typename CFG, bool OUT_BF16>
 __global__ void __launch_bounds__(LIN_THREADS) __attribute__((amdgpu_waves_per_eu(CFG::WGS_PER_CU, CFG::WGS_PER_CU)))
@@ -170,7 +171,7 @@ gdn_linear_kernel(LinearArgs a) {
 #pragma unroll
     for (int p = 0; p < STAGES; ++p) {
         const bool live = p < n_steps;
-        lin_issue<CFG>(smem, p, p * BK, wave, xb, live ? x_bytes : 0, wb, live ? w_bytes : 0, xoff, woff);
+        LinLoad<CFG>::all(smem, p, p * BK, wave, xb, live ? x_bytes : 0, wb, live ? w_bytes : 0, xoff, woff);
     }
     wait_vm<(STAGES - 1) * CFG::LPS>();
     __syncthreads();
@@ -210,7 +211,7 @@ gdn_linear_kernel(LinearArgs a) {
                 }
 #pragma unroll
                 for (int j = i * NL / SLOTS; j < (i + 1) * NL / SLOTS; ++j)
-                    lin_issue_one<CFG>(j, smem, stage, (step + STAGES) * BK, wave, xb, xbytes, wb, wbytes, xoff, woff);
+                    LinLoad<CFG>::one(j, smem, stage, (step + STAGES) * BK, wave, xb, xbytes, wb, wbytes, xoff, woff);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -289,7 +290,7 @@ int choose_linear_shape(int64_t T, int32_t N) {
     const int forced = g_linear_shape.load();
     if (forced >= 0) return forced;
     const double cus = (double)chip_cus_linear();
-    const struct { int bm, bn, per_cu; double rate; } shapes[2] = {{128, 128, 2, 0.36}, {256, 256, 1, 0.40}};
+    const struct { int bm, bn, per_cu; double rate; } shapes[2] = {{128, 128, 2, 0.36}, {256, 256, 1, 0.41}};
     int best = 0;
     double best_t = 0;
     for (int i = 0; i < 2; ++i) {
