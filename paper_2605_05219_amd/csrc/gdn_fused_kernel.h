@@ -34,7 +34,7 @@
 //            TbTg[a] = [T_aa diag(b) | -T_aa diag(b gam)],  M = -T_aa L_ac (c < a),  P (c <= ia); a lone block's
 //            partner half stays zero from the start of the kernel
 //   Tf[w]    fp32 [16][20]: a wave's T_aa on its way from the accumulator layout to its transpose
-//   g, b, gam, dec, -b gam, and the factors of the decay between blocks (s, b r_c, scale r_c; see the gates): fp32 [64] each
+//   g, b, gam, dec, and the factors of the decay between blocks (s, r_c; see the gates): fp32 [64] each
 #pragma once
 #include "gdn_prep_kernel.h"
 #include "gdn_recur_kernel.h"
@@ -77,7 +77,7 @@ struct FusedSmem {
     static constexpr int P_OFF = M_OFF + 4 * PAIR_BYTES;     // pair tiles (0: P00,0) (1: P10,P11) (2: P20,P21) (2: P22,0) (3: P30,P31) (3: P32,P33)
     static constexpr int TF_OFF = P_OFF + 6 * PAIR_BYTES;
     static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
-    static constexpr int BYTES = SM_OFF + 12 * C * 4;        // g, b, gam, dec, -b gam, s, 3 x b r, 3 x scale r
+    static constexpr int BYTES = SM_OFF + 8 * C * 4;         // g, b, gam, dec, s, 3 x r
     static_assert(TBTG_OFF % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
     static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
     // pair tile index of block (a, c) of M (c < a) and of P (c <= a)
@@ -153,10 +153,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     float* const bS = gS + C;
     float* const gamS = bS + C;
     float* const decS = gamS + C;
-    float* const bgS = decS + C;     // -b gam
-    float* const sS = bgS + C;       // s_j = exp(g_end(block of j) - g_j)
-    float* const brS = sS + C;       // [3][64]: b_i exp(g_i - g_end(c)), c = 0..2, for tokens i of later blocks
-    float* const prS = brS + 3 * C;  // [3][64]: scale exp(g_i - g_end(c))
+    float* const sS = decS + C;      // s_j = exp(g_end(block of j) - g_j)
+    float* const rS = sS + C;        // [3][64]: r_i(c) = exp(g_i - g_end(c)), c = 0..2, for tokens i of later blocks
 
     const int tid = threadIdx.x;
     const int lane_ = tid & 63;
@@ -214,7 +212,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     };
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[4], qraw[4], vraw[4];
-    In graw = In(), braw = In();
+    In graw = In();      // wave 0: the lane's gate; wave 1: its beta
     auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
         const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
@@ -236,10 +234,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 vraw[r] = EL::zero_raw();
             }
         }
-        if (lane < it.n) {   // every wave keeps its own copy of the 64 gate pairs
+        // The 64 gates are read by wave 0 and the 64 betas by wave 1 only: a lane per token, 2 bytes each at a stride of a
+        // token's heads, is 64 separate memory requests per instruction.
+        if (lane < it.n && wave < 2) {
             const int gi = lane * a.H_v;
-            graw = (reinterpret_cast<const In*>(a.gate) + (row0 * a.H_v + hv))[gi];
-            braw = (reinterpret_cast<const In*>(a.beta) + (row0 * a.H_v + hv))[gi];
+            graw = (reinterpret_cast<const In*>(wave == 0 ? a.gate : a.beta) + (row0 * a.H_v + hv))[gi];
         }
     };
 
@@ -305,42 +304,28 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (!first) __syncthreads();   // the previous item's recurrence is done with every LDS tile
         first = false;
 
-        // ---- gates: g_i = inclusive running sum of log a, b_i; identity beyond n.  Every wave runs the scan; the derived
-        //      arrays are shared out over the waves.  Between blocks of 16 tokens the decay factors into a row and a column
-        //      part, exp(g_i - g_j) = exp(g_i - g_end(c)) exp(g_end(c) - g_j) for j in block c and i in a later block, both
-        //      exponents <= 0 since g never rises: the blocks off the diagonal then need no exponential per element.
-        {
-            float la = 0.f, b = 0.f;
-            if (lane < n) {
-                la = fmaxf(EL::log_(EL::widen(graw)), -88.f);
-                b = EL::widen(braw);
-            }
+        // ---- gates, by wave 0: g_i = inclusive running sum of log a and what derives from it; identity beyond n.  Between
+        //      blocks of 16 tokens the decay factors into a row and a column part, exp(g_i - g_j) = exp(g_i - g_end(c))
+        //      exp(g_end(c) - g_j) for j in block c and i in a later block, both exponents <= 0 since g never rises: the
+        //      blocks off the diagonal then need no exponential per element.  Wave 1 stores the betas.
+        if (wave == 0) {
+            const float la = lane < n ? fmaxf(EL::log_(EL::widen(graw)), -88.f) : 0.f;
             const float s = wave_running_sum(la);
             const int sbits = __builtin_bit_cast(int, s);
             const float e0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 15));
             const float e1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 31));
             const float e2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(sbits, 47));
             const float g_last = wave_last_lane(s);
-            if (wave == 0) {
-                gS[lane] = s;
-                bS[lane] = b;
-                gamS[lane] = EL::exp_(s);
-            } else if (wave == 1) {
-                decS[lane] = EL::exp_(g_last - s);
-                bgS[lane] = -b * EL::exp_(s);
-            } else if (wave == 2) {
-                const float eb = lane < 16 ? e0 : lane < 32 ? e1 : lane < 48 ? e2 : g_last;
-                sS[lane] = EL::exp_(fminf(eb - s, 0.f));
-                const float r0 = EL::exp_(fminf(s - e0, 0.f));
-                brS[lane] = b * r0;
-                prS[lane] = a.scale * r0;
-            } else {
-                const float r1 = EL::exp_(fminf(s - e1, 0.f)), r2 = EL::exp_(fminf(s - e2, 0.f));
-                brS[C + lane] = b * r1;
-                prS[C + lane] = a.scale * r1;
-                brS[2 * C + lane] = b * r2;
-                prS[2 * C + lane] = a.scale * r2;
-            }
+            const float eb = lane < 16 ? e0 : lane < 32 ? e1 : lane < 48 ? e2 : g_last;
+            gS[lane] = s;
+            gamS[lane] = EL::exp_(s);
+            decS[lane] = EL::exp_(g_last - s);
+            sS[lane] = EL::exp_(fminf(eb - s, 0.f));
+            rS[lane] = EL::exp_(fminf(s - e0, 0.f));
+            rS[C + lane] = EL::exp_(fminf(s - e1, 0.f));
+            rS[2 * C + lane] = EL::exp_(fminf(s - e2, 0.f));
+        } else if (wave == 1) {
+            bS[lane] = lane < n ? EL::widen(graw) : 0.f;
         }
         // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
 #pragma unroll
@@ -397,10 +382,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             for (int e = 0; e < 4; ++e) Tf[(4 * g4 + e) * SM::TF_LD + m] = y[e];
             const f32x4 at = *reinterpret_cast<const f32x4*>(Tf + m * SM::TF_LD + 4 * g4);   // T[m][4 g4 + e]
             {
-                const f32x4 bg = *reinterpret_cast<const f32x4*>(bgS + 16 * ab + 4 * g4);
+                const f32x4 gm = *reinterpret_cast<const f32x4*>(gamS + 16 * ab + 4 * g4);
                 f32x4 tb, tgm;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { tb[e] = at[e] * bi[e]; tgm[e] = at[e] * bg[e]; }
+                for (int e = 0; e < 4; ++e) { tb[e] = at[e] * bi[e]; tgm[e] = -tb[e] * gm[e]; }
                 *reinterpret_cast<half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4) = cat8(cvt4(tb), cvt4(tgm));
             }
             const float gq = gS[16 * ia + m];
@@ -416,10 +401,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int s = 0; s < 4; ++s) acc = mma32(ka[s], kc[s], acc);   // rows i in block ab, lanes j in block c
                     const float sj = sS[16 * c + m];
-                    const f32x4 br = *reinterpret_cast<const f32x4*>(brS + c * C + 16 * ab + 4 * g4);
+                    const f32x4 ri = *reinterpret_cast<const f32x4*>(rS + c * C + 16 * ab + 4 * g4);
                     f32x4 lt;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) lt[e] = br[e] * (sj * acc[e]);   // L_ac[4 g4 + e][m]
+                    for (int e = 0; e < 4; ++e) lt[e] = (bi[e] * ri[e]) * (sj * acc[e]);   // L_ac[4 g4 + e][m]
                     const f32x4 zero = {0, 0, 0, 0};
                     const f32x4 mt_ = mm16_rr(zero, lt, at);     // (L^T T^T): element e of lane (m, g4) = (T L)[m][4 g4 + e]
                     f32x4 neg;
@@ -433,7 +418,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     for (int s = 0; s < 4; ++s) acc = mma32(kc[s], qf[s], acc);
                     f32x4 p;
                     if (c < ia) {   // a block below the diagonal: every key is visible, the decay factors
-                        const float pr = prS[c * C + 16 * ia + m];
+                        const float pr = a.scale * rS[c * C + 16 * ia + m];
                         const f32x4 sk = *reinterpret_cast<const f32x4*>(sS + 16 * c + 4 * g4);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) p[e] = pr * (sk[e] * acc[e]);
