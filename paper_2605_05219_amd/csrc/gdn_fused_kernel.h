@@ -529,10 +529,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (O_BF16) {
                         uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) {
-                            const uint32_t lo = f32_to_bf16_rne(ot[nt][0]) | ((uint32_t)f32_to_bf16_rne(ot[nt][1]) << 16);
-                            const uint32_t hi = f32_to_bf16_rne(ot[nt][2]) | ((uint32_t)f32_to_bf16_rne(ot[nt][3]) << 16);
-                            *reinterpret_cast<uint2*>(p + 16 * nt) = make_uint2(lo, hi);
+                        for (int nt = 0; nt < 2; ++nt) {   // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
+                            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                            *reinterpret_cast<bf16x4*>(p + 16 * nt) = __builtin_convertvector(ot[nt], bf16x4);
                         }
                     } else {
                         float* p = reinterpret_cast<float*>(a.o) + off;
