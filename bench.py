@@ -773,6 +773,9 @@ def main() -> int:
     ap.add_argument("--copy-only", action="store_true",
                     help="only the checkpoint pool copies (256 MiB read and written per launch: the known-size copy the "
                          "profiler's byte counters are calibrated on)")
+    ap.add_argument("--sides-only", action="store_true",
+                    help="only the side objects (configs[1] latency, copies, host tier, decode, layer ends, projections, "
+                         "attention, ceilings): what the profiler runs of the side kernels use")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time ONE call of k = 1..64 configs[1]-style requests (side object `batch_sweep`; about "
                          "a minute of host-side input generation)")
@@ -803,6 +806,13 @@ def main() -> int:
     if args.latency_only:
         lat, _, _, _ = bench_config1(args, torch, B, wl, dev)
         print(json.dumps({"latency": lat}))
+        return 0
+
+    if args.sides_only:
+        lat, calls, pool, suffix = bench_config1(args, torch, B, wl, dev)
+        out = {"latency": lat}
+        out.update(side_measurements(args, torch, B, wl, dev, calls, pool, suffix, lat["ms_per_step"]))
+        print(json.dumps(out))
         return 0
 
     out, cpu = bench_config4(args, torch, B, dev)
