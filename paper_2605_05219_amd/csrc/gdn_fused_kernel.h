@@ -225,9 +225,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * tg + r;
             if (i < it.n) {
-                kraw[r] = EL::load_raw(kb + (i * qk_step + d0));
-                qraw[r] = EL::load_raw(qb + (i * qk_step + d0));
-                vraw[r] = EL::load_raw(vb + (i * v_step + d0));
+                // read once, never again: marked non-temporal (worth 1 % on the large configurations)
+                kraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(kb + (i * qk_step + d0)));
+                qraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(qb + (i * qk_step + d0)));
+                vraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(vb + (i * v_step + d0)));
             } else {
                 kraw[r] = EL::zero_raw();
                 qraw[r] = EL::zero_raw();
