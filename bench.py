@@ -758,6 +758,39 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
     return out
 
 
+def phase_table(torch, B) -> int:
+    """The fused kernel's clocks per phase of one 64-token chunk, from the profiling build of the library (cycle stamps at
+    the phase boundaries of the 40th item of every eighth workgroup, one set per wave), on the configs[4] step."""
+    import ctypes
+    from paper_2605_05219_amd import build as BLD
+    from paper_2605_05219_amd.device_call import config4_device
+    if not os.path.exists(BLD.LIB_PHASES):
+        print("bench.py --phase-table needs the profiling build: python -m paper_2605_05219_amd.build --phase-stamps", file=sys.stderr)
+        return 2
+    B.LIB_PATH = BLD.LIB_PHASES          # before the first call: the binding loads the library lazily
+    step = config4_device()
+    for _ in range(3):
+        step.run()
+    torch.cuda.synchronize()
+    raw = np.zeros(64 * 4 * 16, dtype=np.uint64)
+    rc = int(B.lib().gdn_phase_stamps(raw.ctypes.data_as(ctypes.c_void_p)))
+    if rc != 0:
+        print(f"gdn_phase_stamps: {rc}", file=sys.stderr)
+        return 1
+    t = raw.reshape(64 * 4, 16).astype(np.int64)
+    t = t[(t[:, 0] > 0) & (t[:, 9] > t[:, 0])]
+    names = ["stage K, Q, V and gates", "issue the next chunk's loads", "barrier after staging", "diagonal gram block and its inverse",
+             "L and P blocks", "barrier after preparation", "substitution and outputs", "state update", "emission"]
+    d = np.diff(t[:, :10], axis=1)
+    print(json.dumps({"phase_table": {"workload": "configs[4] step, fused kernel, 40th item (a full 64-token chunk of a long chain) of every eighth workgroup",
+                                      "waves_sampled": int(d.shape[0]), "unit": "shader clocks per wave",
+                                      "mean": {n: float(x) for n, x in zip(names, d.mean(0))},
+                                      "min": {n: float(x) for n, x in zip(names, d.min(0))},
+                                      "max": {n: float(x) for n, x in zip(names, d.max(0))},
+                                      "total_mean": float(d.sum(1).mean())}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -773,6 +806,9 @@ def main() -> int:
     ap.add_argument("--copy-only", action="store_true",
                     help="only the checkpoint pool copies (256 MiB read and written per launch: the known-size copy the "
                          "profiler's byte counters are calibrated on)")
+    ap.add_argument("--phase-table", action="store_true",
+                    help="run the configs[4] step on the profiling build of the library (python -m paper_2605_05219_amd.build "
+                         "--phase-stamps) and print the fused kernel's clocks per phase of a chunk")
     ap.add_argument("--sides-only", action="store_true",
                     help="only the side objects (configs[1] latency, copies, host tier, decode, layer ends, projections, "
                          "attention, ceilings): what the profiler runs of the side kernels use")
@@ -800,6 +836,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    if args.phase_table:
+        return phase_table(torch, B)
     if args.copy_only:
         print(json.dumps({"ckpt_copy": bench_ckpt_copy(torch, B, dev)}))
         return 0

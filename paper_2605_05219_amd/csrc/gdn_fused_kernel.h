@@ -134,6 +134,21 @@ __device__ __forceinline__ f32x4 inv16_tiles(const f32x4& d, const f32x4& dt, in
     return mm16_rr(y, p8t, y);
 }
 
+// Profiling build only (-DGDN_PHASE_STAMPS, a library of its own: see build.py): cycle stamps at the phase boundaries of
+// the 40th item of every eighth workgroup (the kernel's steady state), one set per wave, read back by gdn_phase_stamps.  The product build has none.
+#ifdef GDN_PHASE_STAMPS
+__device__ unsigned long long g_phase_ts[64 * 4 * 16];
+#define GDN_PHASE(k_)                                                                                   \
+    do {                                                                                                \
+        if (gdn_item == 40 && (blockIdx.x & 7) == 0 && blockIdx.x < 512 && lane_ == 0)                   \
+            g_phase_ts[((blockIdx.x >> 3) * 4 + wave) * 16 + (k_)] = __builtin_readcyclecounter();      \
+    } while (0)
+#define GDN_PHASE_ITEM() (++gdn_item)
+#else
+#define GDN_PHASE(k_) do {} while (0)
+#define GDN_PHASE_ITEM() ((void)0)
+#endif
+
 template <bool O_BF16>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_fused_kernel(FusedArgs a) {
     typedef Elem<half_t> EL;
@@ -255,6 +270,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     int open = -1;         // chain whose state accS holds
     bool first = true;
 
+    int gdn_item = 0;      // items done (used by the profiling build only)
+    (void)gdn_item;
     for (;;) {
         // The lane's coordinates are made opaque once per item: otherwise every address of the unrolled tile
         // accesses below is hoisted out of this loop and held in a register of its own for the whole kernel.
@@ -304,6 +321,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         if (!first) __syncthreads();   // the previous item's recurrence is done with every LDS tile
         first = false;
+        GDN_PHASE_ITEM();
+        GDN_PHASE(0);
 
         // ---- gates, by wave 0: g_i = inclusive running sum of log a and what derives from it; identity beyond n.  Between
         //      blocks of 16 tokens the decay factors into a row and a column part, exp(g_i - g_j) = exp(g_i - g_end(c))
@@ -344,8 +363,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             *reinterpret_cast<half8*>(Qt + off) = qh;
             *reinterpret_cast<half8*>(Vt + off) = vh;
         }
+        GDN_PHASE(1);
         if (nxt.chain >= 0) fetch(nxt, tg, d0, lane);
+        GDN_PHASE(2);
         __syncthreads();
+        GDN_PHASE(3);
 
         // operand over d_k columns 32 s + 8 g4 .. + 7 of row 16 blk + m of a tile
         auto row_frag = [&](const char* tile, int blk, int s) -> half8 {
@@ -389,6 +411,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int e = 0; e < 4; ++e) { tb[e] = at[e] * bi[e]; tgm[e] = -tb[e] * gm[e]; }
                 *reinterpret_cast<half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4) = cat8(cvt4(tb), cvt4(tgm));
             }
+            GDN_PHASE(4);
             const float gq = gS[16 * ia + m];
             // key blocks c: left of the diagonal of block row ab, L_ac -> -(T_aa L_ac) stored by rows; up to query
             // block ia, P (rows j = keys in registers, lane = query i)
@@ -435,8 +458,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 }
             }
         }
+        GDN_PHASE(5);
         __syncthreads();
 
+        GDN_PHASE(6);
         // ---- recurrence step of this chunk, d_v columns 32 wave + 16 nt + m
         {
             half8 sf[4][2];        // the state as an operand over d_k: step s = state tiles 2 s, 2 s + 1
@@ -541,6 +566,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                 }
             }
+            GDN_PHASE(7);
             // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
 #pragma unroll
@@ -556,6 +582,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     accS[mt][nt] = mma32(k1, ud[1][nt], accS[mt][nt]);
                 }
             }
+            GDN_PHASE(8);
             // checkpoint emission: exact state after the last token of this chunk
             const int eslot = cur.eslot;   // looked up one item ahead, with the chunk's other bookkeeping
             if (eslot >= 0) {
@@ -568,6 +595,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
         }
 
+        GDN_PHASE(9);
         if (nxt.chain < 0) break;
         cur = nxt;
         nxt = next_item(cur);

@@ -572,6 +572,16 @@ extern "C" {
 
 int32_t gdn_version(void) { return 100; }
 
+#ifdef GDN_PHASE_STAMPS
+// Profiling build only: the cycle stamps the fused kernel left (64 workgroups x 4 waves x 16 stamps), after a device
+// synchronisation.  Not declared in the public header: the product library does not export it.
+extern "C" int32_t gdn_phase_stamps(unsigned long long* out) {
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpyFromSymbol(out, HIP_SYMBOL(gdn::g_phase_ts), sizeof(unsigned long long) * 64 * 4 * 16);
+    return e == hipSuccess ? GDN_OK : GDN_ERR_HIP - (int32_t)e;
+}
+#endif
+
 int32_t gdn_tune_fused(int32_t mode) {
     return g_forced_fused.exchange(mode < 0 ? -1 : (mode != 0));
 }
