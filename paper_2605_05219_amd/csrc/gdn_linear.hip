@@ -184,10 +184,14 @@ gdn_linear_kernel(LinearArgs a) {
             read_frags(stage, kk + 1, (kk & 1) ^ 1);
             mma_all(kk & 1);
         }
+        // (the matrix instructions above stay above: left to itself the scheduler sinks them below the barrier, and the
+        // fragment reads and the barrier are then waited for with the matrix pipe idle)
+        __builtin_amdgcn_sched_barrier(0);
         // the next stage has landed for this wave (the STAGES - 2 stages behind it may still be in flight) ...
         wait_vm<CFG::AHEAD>();
         __builtin_amdgcn_s_waitcnt(0xC07F);          // ... and this wave's last fragment reads of the current stage are done (lgkmcnt(0))
         __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
         {
             // The last k step of the stage (fragment set 1; KK is even), written out in issue order and pinned there: a load
             // to LDS takes tens of cycles to issue, so one goes out behind every few matrix instructions, which covers it;
