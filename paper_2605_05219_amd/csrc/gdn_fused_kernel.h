@@ -231,24 +231,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
         const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
         const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
-        // wave-uniform 64-bit bases, 32-bit per-thread offsets
-        const In* const kb = kg + (row0 * a.H_qk + hq) * DK;
-        const In* const qb = qg + (row0 * a.H_qk + hq) * DK;
-        const In* const vb = vg + (row0 * a.H_v + hv) * DV;
-        const int qk_step = a.H_qk * DK, v_step = a.H_v * DV;
+        // Buffer loads: a wave-uniform descriptor per tensor that starts at the chunk's first row of this head and ends with
+        // its last row (rows past n read as zeros, no branch), 32-bit per-lane offsets.  Read once, never again: non-temporal.
+        const int qk_step = a.H_qk * DK * 2, v_step = a.H_v * DV * 2;      // bytes from token to token
+        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(kg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(qg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(vg + (row0 * a.H_v + hv) * DV), 0, (it.n - 1) * v_step + DV * 2, 0x00020000);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int i = 4 * tg + r;
-            if (i < it.n) {
-                // read once, never again: marked non-temporal (worth 1 % on the large configurations)
-                kraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(kb + (i * qk_step + d0)));
-                qraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(qb + (i * qk_step + d0)));
-                vraw[r] = __builtin_nontemporal_load(reinterpret_cast<const Raw8*>(vb + (i * v_step + d0)));
-            } else {
-                kraw[r] = EL::zero_raw();
-                qraw[r] = EL::zero_raw();
-                vraw[r] = EL::zero_raw();
-            }
+            kraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rk, i * qk_step + d0 * 2, 0, 2));
+            qraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, i * qk_step + d0 * 2, 0, 2));
+            vraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rv, i * v_step + d0 * 2, 0, 2));
         }
         // The 64 gates are read by wave 0 and the 64 betas by wave 1 only: a lane per token, 2 bytes each at a stride of a
         // token's heads, is 64 separate memory requests per instruction.
