@@ -472,6 +472,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int e = 0; e < 8; ++e) uh[p][nt][e] = (half_t)0.f;
             const int64_t row0 = (int64_t)l * a.T_alloc + cur.tok0;
+            // the outputs of this item: rows of H_v d_v elements, this head's d_v columns; byte offsets of lane (m = token, g4)
+            constexpr int OB = O_BF16 ? 2 : 4;
+            const int o_step = a.H_v * DV * OB;
+            const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+                reinterpret_cast<char*>(a.o) + ((row0 * a.H_v + hv) * DV) * OB, 0, (n - 1) * o_step + DV * OB, 0x00020000);
+            const int o_lane = m * o_step + (32 * wave + 4 * g4) * OB;
             // K_a S0^T (tokens in registers) and (Q_a S0^T)^T (d_v in registers, lane = token) of block row ab: 16 independent
             // products.  They are issued one block row ahead, in between the short dependent products of the substitution.
             auto state_products = [&](int ab, f32x4 (&ks)[2], f32x4 (&ot)[2]) {
@@ -544,20 +550,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 // fetched register would wait for every store to be acknowledged (thousands of cycles at the top of the
                 // next item).  Here the fetch is thousands of cycles old and nothing else is pending, so this costs nothing.
                 if (ab == 0) wait_vmcnt<0>();
-                if (row < n) {
-                    const int64_t off = ((row0 + row) * a.H_v + hv) * DV + 32 * wave + 4 * g4;
-                    if (O_BF16) {
-                        uint16_t* p = reinterpret_cast<uint16_t*>(a.o) + off;
+                // buffer stores through the item's output descriptor (it ends with the chunk's last row: rows past n are dropped)
+                if (O_BF16) {
+                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) {   // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
-                            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                            *reinterpret_cast<bf16x4*>(p + 16 * nt) = __builtin_convertvector(ot[nt], bf16x4);
-                        }
-                    } else {
-                        float* p = reinterpret_cast<float*>(a.o) + off;
+                    for (int nt = 0; nt < 2; ++nt)   // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
+                        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(ot[nt], bf16x4)), ro,
+                                                              o_lane + ab * 16 * o_step + 32 * nt, 0, 0);
+                } else {
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) *reinterpret_cast<f32x4*>(p + 16 * nt) = ot[nt];
-                    }
+                    for (int nt = 0; nt < 2; ++nt)
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ot[nt]), ro, o_lane + ab * 16 * o_step + 64 * nt, 0, 0);
                 }
             }
             GDN_PHASE(7);
