@@ -641,6 +641,38 @@ def test_seeded_random_calls_match_the_oracle(many):
 
 
 @pytest.mark.gpu
+def test_seeded_random_calls_on_the_fused_kernel():
+    """The fused kernel forced onto small seeded calls it would not be chosen for: one value head (an output row is then
+    exactly as long as the output descriptor's last row), grouped value heads, chunks of 1 to 64 tokens, requests of
+    length 0, several layers, emits anywhere, both output types."""
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(9090)
+    shapes = [(1, 1, 1), (1, 1, 2), (2, 1, 1), (1, 2, 4), (3, 2, 2), (1, 4, 4), (2, 2, 8)]
+    prev = B.gdn_tune_fused(1)
+    try:
+        for it in range(14):
+            L, H_qk, H_v = shapes[it % len(shapes)]
+            n_req = int(rng.integers(1, 7))
+            lens = [int(x) for x in rng.choice([0, 1, 2, 15, 16, 17, 63, 64, 65, 100, 129, 200], n_req)]
+            if sum(lens) == 0:
+                lens[0] = 3
+            starts = [int(x) for x in rng.choice([0, 0, 64, 100, 512], n_req)]
+            nxt, emits, eslots = 3, [], []
+            for s0, ln in zip(starts, lens):
+                e = sorted(set(int(x) for x in rng.integers(s0 + 1, s0 + ln + 1, int(rng.integers(0, 4))))) if ln > 0 else []
+                emits.append(e)
+                eslots.append(list(range(nxt, nxt + len(e))))
+                nxt += len(e)
+            per_req = [wl.token_streams(rng, L, ln, H_qk, H_v, 128, 128, "bf16", "slow" if it % 3 == 0 else "config") for ln in lens]
+            src = [-1 if s0 == 0 else int(rng.integers(0, 3)) for s0 in starts]
+            call = wl.pack_call(L, H_qk, H_v, 128, 128, "bf16", per_req, starts, src, emits, eslots, nxt + 1)
+            pool = rng.standard_normal((nxt + 1,) + call.slot_shape).astype(np.float32) * 0.1
+            check_call(call, pool, TOL["bf16"], o_dtype="bf16" if it % 2 else "f32")
+    finally:
+        B.gdn_tune_fused(prev)
+
+
+@pytest.mark.gpu
 def test_probe_ceilings_reports_plausible_machine_rates():
     """The probe's figures lie between a fifth of the data-sheet peaks and the peaks themselves."""
     import torch
