@@ -227,39 +227,67 @@ gdn_linear_kernel(LinearArgs a) {
         mma_all(kk & 1);
     }
 
-    // ---- epilogue: bias, one rounding, 4 consecutive outputs of a token per store
+    // ---- epilogue: bias, one rounding, and out through LDS.  A lane holds runs of four outputs of ONE token, 32 tokens per
+    //      instruction: stored from there, every instruction would touch 32 rows of the output with 8 or 16 bytes each.
+    //      Each wave turns its quarter around in its own quarter of the (now idle) stage ring instead: rows of 256 bytes (128
+    //      with the small tile), the 16-byte pieces of a row XOR-swizzled with the token so that both the writes (lane = token)
+    //      and the reads (lane = piece) spread over the banks; then 16 lanes store one row's 256 contiguous bytes.  A wave's LDS
+    //      operations execute in order, so no barrier stands between its writes and reads; the one barrier before keeps the
+    //      other waves' last fragment reads out of the way.
+    constexpr int ES = OUT_BF16 ? 2 : 4;
+    constexpr int WN = BN / 2, WM = BM / 2;                        // the wave's outputs and tokens
+    constexpr int PW = (WN * ES <= 256) ? WN : 256 / ES;           // outputs per pass: a row of at most 256 bytes
+    constexpr int RBY = PW * ES, PPR = RBY / 16;                   // row bytes, 16-byte pieces per row
+    constexpr int RPI = 1024 / RBY;                                // rows a wave-wide 16-byte access covers
+    static_assert(WM * RBY <= CFG::SMEM / 4 && WN % PW == 0 && PW % 32 == 0, "epilogue region");
+    wait_vm<0>();
+    __syncthreads();
+    char* const reg = smem + wave * (CFG::SMEM / 4);
+    const int64_t tok0 = m0 + WM * wm;
+    const int col0 = n0 + WN * wn;
 #pragma unroll
-    for (int ti = 0; ti < TI; ++ti) {
-        const int64_t tok = m0 + (BM / 2) * wm + 32 * ti + lr;
-        if (tok >= a.T) continue;
+    for (int c0 = 0; c0 < WN; c0 += PW) {
 #pragma unroll
-        for (int tj = 0; tj < TJ; ++tj)
+        for (int tj = c0 / 32; tj < (c0 + PW) / 32; ++tj)
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                const int col = n0 + (BN / 2) * wn + 32 * tj + 8 * b + 4 * g;
-                if (col >= a.N) continue;
-                f32x4 v = {acc[tj][ti][4 * b], acc[tj][ti][4 * b + 1], acc[tj][ti][4 * b + 2], acc[tj][ti][4 * b + 3]};
-                const bool whole = col + 4 <= a.N;
+                const int cl = 32 * tj + 8 * b + 4 * g;            // first of the lane's four outputs, within the wave's quarter
+                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
                 if (a.bias) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (col + e < a.N) v[e] += a.bias[col + e];
+                        if (col0 + cl + e < a.N) bv[e] = a.bias[col0 + cl + e];
                 }
-                if (OUT_BF16) {
-                    __bf16* p = reinterpret_cast<__bf16*>(a.y) + tok * a.ldy + col;
-                    const bf16x4 h = __builtin_convertvector(v, bf16x4);
-                    if (whole) *reinterpret_cast<bf16x4*>(p) = h;
-                    else
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < a.N) p[e] = h[e];
-                } else {
-                    float* p = reinterpret_cast<float*>(a.y) + tok * a.ldy + col;
-                    if (whole) *reinterpret_cast<f32x4*>(p) = v;
-                    else
-                        for (int e = 0; e < 4; ++e)
-                            if (col + e < a.N) p[e] = v[e];
+#pragma unroll
+                for (int ti = 0; ti < TI; ++ti) {
+                    const int row = 32 * ti + lr;
+                    f32x4 v = {acc[tj][ti][4 * b] + bv[0], acc[tj][ti][4 * b + 1] + bv[1], acc[tj][ti][4 * b + 2] + bv[2], acc[tj][ti][4 * b + 3] + bv[3]};
+                    const int byte = (cl - c0) * ES;
+                    char* const dst = reg + row * RBY + (((byte >> 4) ^ (row % PPR)) << 4) + (byte & 15);
+                    if (OUT_BF16) *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(v, bf16x4);
+                    else *reinterpret_cast<f32x4*>(dst) = v;
                 }
             }
+#pragma unroll
+        for (int i = 0; i < WM / RPI; ++i) {
+            const int row = RPI * i + lane / PPR, piece = lane % PPR;
+            const u32x4 val = *reinterpret_cast<const u32x4*>(reg + row * RBY + ((piece ^ (row % PPR)) << 4));
+            const int64_t tok = tok0 + row;
+            const int col = col0 + c0 + piece * (16 / ES);
+            if (tok < a.T && col < a.N) {
+                char* const p = reinterpret_cast<char*>(a.y) + (tok * a.ldy + col) * ES;
+                if (col + 16 / ES <= a.N) {
+                    *reinterpret_cast<u32x4*>(p) = val;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16 / ES; ++e)
+                        if (col + e < a.N) {
+                            if (OUT_BF16) reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(val[e >> 1] >> (16 * (e & 1)));
+                            else reinterpret_cast<uint32_t*>(p)[e] = val[e];
+                        }
+                }
+            }
+        }
     }
 }
 
