@@ -42,8 +42,8 @@ int32_t gdn_linear(const void *x, int64_t ldx, const void *w, int64_t ldw, const
                    int64_t T, int32_t N, int32_t K, void *stream);
 
 /*
- * Tuning knob, not a method step: fixes the workgroup tile gdn_linear uses (0: 128 x 128, 1: 256 x 256; anything
- * else: chosen per call from T and N, the default).  Every shape computes the same
+ * Tuning knob, not a method step: fixes the workgroup tile gdn_linear uses (0: 128 x 128; 1: 256 x 256 with four
+ * waves; 2: 256 x 256 with eight waves; anything else: chosen per call from T and N, the default).  Every shape computes the same
  * sums in the same order, so the results do not depend on it.  Process-wide; returns the previous setting (-1 = per
  * call).
  */

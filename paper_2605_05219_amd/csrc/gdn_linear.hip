@@ -1,13 +1,14 @@
 // gdn_linear: the layers' projections y = x w^T + bias on the bf16 matrix cores (see include/gdn_linear.h).
 //
-// One workgroup of four waves (2 x 2) makes a BM (tokens) x BN (outputs) tile, a wave a quarter of it as tiles of
+// One workgroup of four or eight waves makes a BM (tokens) x BN (outputs) tile, a wave its part of it as tiles of
 // v_mfma_f32_32x32x16_bf16.  Both operands are read along k, so a k step of BK needs a BM x BK tile of x and a
 // BN x BK tile of w; they come from memory with 16-byte buffer loads straight to LDS (no registers) into a ring of
-// STAGES stages, STAGES - 1 k steps ahead of the matrix cores: one barrier per k step.  Two shapes are built:
-//   128 x 128 x 64, 2 stages, two workgroups per compute unit   small problems (more, smaller workgroups)
-//   256 x 256 x 32, 4 stages, one workgroup per compute unit    a wave holds 128 x 128 outputs in 256 accumulator
-//                   registers: half the operand bytes per flop, from memory and from LDS, and three k steps of
-//                   loads in flight
+// STAGES stages, STAGES - 1 k steps ahead of the matrix cores: one barrier per k step.  Three shapes are built:
+//   0: 128 x 128 x 64, 2 stages, four waves, two workgroups per compute unit   small problems (more, smaller workgroups)
+//   1: 256 x 256 x 32, 4 stages, four waves, one workgroup per compute unit: a wave holds 128 x 128 outputs in 256
+//      accumulator registers: half the operand bytes per flop, from memory and from LDS, three k steps of loads in flight
+//   2: the same tile with eight waves of 128 tokens x 64 outputs, two per SIMD: while one wave of a SIMD is held up issuing
+//      its loads to LDS the other feeds the matrix pipe (the default for large problems; 1 is kept for comparison)
 // A load to LDS writes a wave's 1 KiB contiguously (lane i at 16 i), so rows are unpadded (2 BK bytes) and bank
 // conflicts are avoided by choosing WHICH 16-byte piece of its row a lane fetches: piece p of row r is stored at
 // position p ^ swz(r), swz(r) = (r / rows per 256 bytes) % pieces per row, which makes the 16 lanes that read the
@@ -33,7 +34,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int LIN_THREADS = 256;
 
 struct LinearArgs {
     const void* x;
@@ -54,24 +54,27 @@ __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt(((N & 0x30) << 10) | (N & 0xF) | 0x0F70);
 }
 
-template <int BM_, int BN_, int BK_, int STAGES_, int WGS_PER_CU_>
+template <int BM_, int BN_, int BK_, int STAGES_, int WGS_PER_CU_, int WAVES_M_, int WAVES_N_>
 struct LinCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, STAGES = STAGES_, WGS_PER_CU = WGS_PER_CU_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, NW = WAVES_M * WAVES_N, THREADS = 64 * NW;   // the wave grid over the tile
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // a wave's tokens and outputs
     static constexpr int RB = BK * 2;                  // bytes of a tile row
     static constexpr int PP = RB / 16;                 // 16-byte pieces per row
     static constexpr int RL = 256 / RB;                // rows per 256 bytes (the span of the 64 banks)
     static constexpr int ROWS_PER_LOAD = 1024 / RB;    // rows a wave-wide load covers
     static constexpr int X_BYTES = BM * RB, W_BYTES = BN * RB, STAGE_BYTES = X_BYTES + W_BYTES;
     static constexpr int SMEM = STAGES * STAGE_BYTES;
-    static constexpr int TI = BM / 64, TJ = BN / 64;   // 32 x 32 tiles of a wave along tokens / outputs
-    static constexpr int XL = BM / ROWS_PER_LOAD / 4, WL = BN / ROWS_PER_LOAD / 4;   // loads per wave and stage
+    static constexpr int TI = WM / 32, TJ = WN / 32;   // 32 x 32 tiles of a wave along tokens / outputs
+    static constexpr int XL = BM / ROWS_PER_LOAD / NW, WL = BN / ROWS_PER_LOAD / NW;   // loads per wave and stage
     static constexpr int LPS = XL + WL;
     static constexpr int AHEAD = (STAGES - 2) * LPS;   // loads that may still be in flight when a stage is handed over
     static_assert(PP * RL == 16 && (STAGES - 1) * LPS < 64 && SMEM <= 160 * 1024 && (BK / 16) % 2 == 0 &&
-                  ((BM / 64) * (BN / 64) % LPS == 0 || LPS % ((BM / 64) * (BN / 64)) == 0), "tile shape");
+                  ((TI * TJ) % LPS == 0 || LPS % (TI * TJ) == 0) && XL >= 1 && WL >= 1, "tile shape");
 };
-typedef LinCfg<128, 128, 64, 2, 2> LinSmall;
-typedef LinCfg<256, 256, 32, 4, 1> LinBig;
+typedef LinCfg<128, 128, 64, 2, 2, 2, 2> LinSmall;
+typedef LinCfg<256, 256, 32, 4, 1, 2, 2> LinBig;      // four waves, 128 x 128 outputs each
+typedef LinCfg<256, 256, 32, 4, 1, 2, 4> LinBig8;     // eight waves, 128 tokens x 64 outputs each: two waves per SIMD
 
 // The loads of one wave for one stage: 1 KiB each, XL of its quarter of the x tile, then WL of the w tile.
 template <typename CFG>
@@ -83,10 +86,10 @@ struct LinLoad {
         char* ws = xs + CFG::X_BYTES;
         if (j < CFG::XL) {
             const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(xb), 0, x_bytes, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + ((CFG::BM / 4) * wave + CFG::ROWS_PER_LOAD * j) * CFG::RB), 16, xoff[j], k0 * 2, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(xs + ((CFG::BM / CFG::NW) * wave + CFG::ROWS_PER_LOAD * j) * CFG::RB), 16, xoff[j], k0 * 2, 0, 0);
         } else {
             const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(wb), 0, w_bytes, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + ((CFG::BN / 4) * wave + CFG::ROWS_PER_LOAD * (j - CFG::XL)) * CFG::RB), 16, woff[j - CFG::XL], k0 * 2, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (__attribute__((address_space(3))) void*)(ws + ((CFG::BN / CFG::NW) * wave + CFG::ROWS_PER_LOAD * (j - CFG::XL)) * CFG::RB), 16, woff[j - CFG::XL], k0 * 2, 0, 0);
         }
     }
     static __device__ __forceinline__ void all(char* smem, int stage, int k0, int wave, const char* xb, int x_bytes, const char* wb, int w_bytes,
@@ -97,7 +100,7 @@ struct LinLoad {
 };
 
 template <typename CFG, bool OUT_BF16>
-__global__ void __launch_bounds__(LIN_THREADS) __attribute__((amdgpu_waves_per_eu(CFG::WGS_PER_CU, CFG::WGS_PER_CU)))
+__global__ void __launch_bounds__(CFG::THREADS) __attribute__((amdgpu_waves_per_eu(CFG::WGS_PER_CU * CFG::NW / 4, CFG::WGS_PER_CU * CFG::NW / 4)))
 gdn_linear_kernel(LinearArgs a) {
     constexpr int BM = CFG::BM, BN = CFG::BN, BK = CFG::BK, STAGES = CFG::STAGES, RB = CFG::RB, PP = CFG::PP, RL = CFG::RL;
     constexpr int RPL = CFG::ROWS_PER_LOAD, TI = CFG::TI, TJ = CFG::TJ, XL = CFG::XL, WL = CFG::WL;
@@ -105,7 +108,7 @@ gdn_linear_kernel(LinearArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;                 // the wave's quarter: tokens (BM/2) wm .., outputs (BN/2) wn ..
+    const int wm = wave / CFG::WAVES_N, wn = wave % CFG::WAVES_N;   // the wave's part: tokens WM wm .., outputs WN wn ..
     const int lr = lane & 31, g = lane >> 5;
     const int tile_m = (int)blockIdx.x / a.tiles_n, tile_n = (int)blockIdx.x % a.tiles_n;
     const int64_t m0 = (int64_t)tile_m * BM;
@@ -122,12 +125,12 @@ gdn_linear_kernel(LinearArgs a) {
     int xoff[XL], woff[WL];      // byte offsets (k = 0) of the loads this wave issues per stage
 #pragma unroll
     for (int j = 0; j < XL; ++j) {
-        const int row = (BM / 4) * wave + RPL * j + ld_row;
+        const int row = (BM / CFG::NW) * wave + RPL * j + ld_row;
         xoff[j] = (int)(row * a.ldx * 2) + ((ld_pos ^ ((row / RL) % PP)) << 4);
     }
 #pragma unroll
     for (int j = 0; j < WL; ++j) {
-        const int row = (BN / 4) * wave + RPL * j + ld_row;
+        const int row = (BN / CFG::NW) * wave + RPL * j + ld_row;
         woff[j] = (int)(row * a.ldw * 2) + ((ld_pos ^ ((row / RL) % PP)) << 4);
     }
     f32x16 acc[TJ][TI];          // [output tile][token tile]: lane = token, register 4 b + e = output 8 b + 4 g + e
@@ -140,7 +143,7 @@ gdn_linear_kernel(LinearArgs a) {
 
     // fragment reads: row r of a tile, piece 2 kk + g, stored at (2 kk + g) ^ swz(r); tile origins are multiples of 16 rows
     const int sw = (lr % 16) / RL;
-    const int xrow = ((BM / 2) * wm + lr) * RB, wrow = ((BN / 2) * wn + lr) * RB;
+    const int xrow = (CFG::WM * wm + lr) * RB, wrow = (CFG::WN * wn + lr) * RB;
     const int n_steps = a.K / BK;
     constexpr int KK = BK / 16;              // matrix-instruction steps per stage (2 or 4)
     // The stages are consumed through two fragment sets: while the matrix cores work on one k step of 16, the fragments of
@@ -235,56 +238,61 @@ gdn_linear_kernel(LinearArgs a) {
     //      operations execute in order, so no barrier stands between its writes and reads; the one barrier before keeps the
     //      other waves' last fragment reads out of the way.
     constexpr int ES = OUT_BF16 ? 2 : 4;
-    constexpr int WN = BN / 2, WM = BM / 2;                        // the wave's outputs and tokens
+    constexpr int WN = CFG::WN, WM = CFG::WM;                      // the wave's outputs and tokens
+    constexpr int REGION = CFG::SMEM / CFG::NW;                    // the wave's part of the ring
     constexpr int PW = (WN * ES <= 256) ? WN : 256 / ES;           // outputs per pass: a row of at most 256 bytes
     constexpr int RBY = PW * ES, PPR = RBY / 16;                   // row bytes, 16-byte pieces per row
     constexpr int RPI = 1024 / RBY;                                // rows a wave-wide 16-byte access covers
-    static_assert(WM * RBY <= CFG::SMEM / 4 && WN % PW == 0 && PW % 32 == 0, "epilogue region");
+    constexpr int TP = (WM * RBY <= REGION) ? WM : REGION / RBY;   // tokens per pass
+    static_assert(TP % 32 == 0 && TP >= 32 && WM % TP == 0 && WN % PW == 0 && PW % 32 == 0, "epilogue region");
     wait_vm<0>();
     __syncthreads();
-    char* const reg = smem + wave * (CFG::SMEM / 4);
+    char* const reg = smem + wave * REGION;
     const int64_t tok0 = m0 + WM * wm;
     const int col0 = n0 + WN * wn;
 #pragma unroll
     for (int c0 = 0; c0 < WN; c0 += PW) {
 #pragma unroll
-        for (int tj = c0 / 32; tj < (c0 + PW) / 32; ++tj)
+        for (int t0 = 0; t0 < WM; t0 += TP) {
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int cl = 32 * tj + 8 * b + 4 * g;            // first of the lane's four outputs, within the wave's quarter
-                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (a.bias) {
+            for (int tj = c0 / 32; tj < (c0 + PW) / 32; ++tj)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (col0 + cl + e < a.N) bv[e] = a.bias[col0 + cl + e];
+                for (int b = 0; b < 4; ++b) {
+                    const int cl = 32 * tj + 8 * b + 4 * g;        // first of the lane's four outputs, within the wave's part
+                    f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+                    if (a.bias) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (col0 + cl + e < a.N) bv[e] = a.bias[col0 + cl + e];
+                    }
+#pragma unroll
+                    for (int ti = t0 / 32; ti < (t0 + TP) / 32; ++ti) {
+                        const int row = 32 * ti + lr - t0;
+                        f32x4 v = {acc[tj][ti][4 * b] + bv[0], acc[tj][ti][4 * b + 1] + bv[1], acc[tj][ti][4 * b + 2] + bv[2], acc[tj][ti][4 * b + 3] + bv[3]};
+                        const int byte = (cl - c0) * ES;
+                        char* const dst = reg + row * RBY + (((byte >> 4) ^ (row % PPR)) << 4) + (byte & 15);
+                        if (OUT_BF16) *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(v, bf16x4);
+                        else *reinterpret_cast<f32x4*>(dst) = v;
+                    }
                 }
 #pragma unroll
-                for (int ti = 0; ti < TI; ++ti) {
-                    const int row = 32 * ti + lr;
-                    f32x4 v = {acc[tj][ti][4 * b] + bv[0], acc[tj][ti][4 * b + 1] + bv[1], acc[tj][ti][4 * b + 2] + bv[2], acc[tj][ti][4 * b + 3] + bv[3]};
-                    const int byte = (cl - c0) * ES;
-                    char* const dst = reg + row * RBY + (((byte >> 4) ^ (row % PPR)) << 4) + (byte & 15);
-                    if (OUT_BF16) *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(v, bf16x4);
-                    else *reinterpret_cast<f32x4*>(dst) = v;
-                }
-            }
+            for (int i = 0; i < TP / RPI; ++i) {
+                const int row = RPI * i + lane / PPR, piece = lane % PPR;
+                const u32x4 val = *reinterpret_cast<const u32x4*>(reg + row * RBY + ((piece ^ (row % PPR)) << 4));
+                const int64_t tok = tok0 + t0 + row;
+                const int col = col0 + c0 + piece * (16 / ES);
+                if (tok < a.T && col < a.N) {
+                    char* const p = reinterpret_cast<char*>(a.y) + (tok * a.ldy + col) * ES;
+                    if (col + 16 / ES <= a.N) {
+                        *reinterpret_cast<u32x4*>(p) = val;
+                    } else {
 #pragma unroll
-        for (int i = 0; i < WM / RPI; ++i) {
-            const int row = RPI * i + lane / PPR, piece = lane % PPR;
-            const u32x4 val = *reinterpret_cast<const u32x4*>(reg + row * RBY + ((piece ^ (row % PPR)) << 4));
-            const int64_t tok = tok0 + row;
-            const int col = col0 + c0 + piece * (16 / ES);
-            if (tok < a.T && col < a.N) {
-                char* const p = reinterpret_cast<char*>(a.y) + (tok * a.ldy + col) * ES;
-                if (col + 16 / ES <= a.N) {
-                    *reinterpret_cast<u32x4*>(p) = val;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 16 / ES; ++e)
-                        if (col + e < a.N) {
-                            if (OUT_BF16) reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(val[e >> 1] >> (16 * (e & 1)));
-                            else reinterpret_cast<uint32_t*>(p)[e] = val[e];
-                        }
+                        for (int e = 0; e < 16 / ES; ++e)
+                            if (col + e < a.N) {
+                                if (OUT_BF16) reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(val[e >> 1] >> (16 * (e & 1)));
+                                else reinterpret_cast<uint32_t*>(p)[e] = val[e];
+                            }
+                    }
                 }
             }
         }
@@ -298,7 +306,7 @@ hipError_t launch_linear(LinearArgs a, hipStream_t stream) {
     if (attr_err != hipSuccess) return attr_err;
     const int64_t tiles_m = (a.T + CFG::BM - 1) / CFG::BM;
     a.tiles_n = (a.N + CFG::BN - 1) / CFG::BN;
-    hipLaunchKernelGGL((gdn_linear_kernel<CFG, OUT_BF16>), dim3((unsigned)(tiles_m * a.tiles_n)), dim3(LIN_THREADS), CFG::SMEM, stream, a);
+    hipLaunchKernelGGL((gdn_linear_kernel<CFG, OUT_BF16>), dim3((unsigned)(tiles_m * a.tiles_n)), dim3(CFG::THREADS), CFG::SMEM, stream, a);
     return hipGetLastError();
 }
 
@@ -322,14 +330,14 @@ int choose_linear_shape(int64_t T, int32_t N) {
     const int forced = g_linear_shape.load();
     if (forced >= 0) return forced;
     const double cus = (double)chip_cus_linear();
-    const struct { int bm, bn, per_cu; double rate; } shapes[2] = {{128, 128, 2, 0.36}, {256, 256, 1, 0.41}};
+    const struct { int id, bm, bn, per_cu; double rate; } shapes[2] = {{0, 128, 128, 2, 0.40}, {2, 256, 256, 1, 0.44}};
     int best = 0;
     double best_t = 0;
     for (int i = 0; i < 2; ++i) {
         const double wgs = (double)((T + shapes[i].bm - 1) / shapes[i].bm) * (double)((N + shapes[i].bn - 1) / shapes[i].bn);
         const double rounds = std::ceil(wgs / (cus * shapes[i].per_cu));
         const double t = rounds * shapes[i].per_cu * shapes[i].bm * shapes[i].bn / shapes[i].rate;
-        if (i == 0 || t < best_t) { best = i; best_t = t; }
+        if (i == 0 || t < best_t) { best = shapes[i].id; best_t = t; }
     }
     return best;
 }
@@ -366,11 +374,12 @@ extern "C" int32_t gdn_linear(const void* x, int64_t ldx, const void* w, int64_t
     hipError_t e;
     switch (choose_linear_shape(T, N)) {
         case 1: e = bf ? launch_linear<LinBig, true>(a, stream) : launch_linear<LinBig, false>(a, stream); break;
+        case 2: e = bf ? launch_linear<LinBig8, true>(a, stream) : launch_linear<LinBig8, false>(a, stream); break;
         default: e = bf ? launch_linear<LinSmall, true>(a, stream) : launch_linear<LinSmall, false>(a, stream); break;
     }
     return hip_err(e);
 }
 
 extern "C" int32_t gdn_linear_tune(int32_t shape) {
-    return g_linear_shape.exchange(shape < 0 || shape > 1 ? -1 : shape);
+    return g_linear_shape.exchange(shape < 0 || shape > 2 ? -1 : shape);
 }

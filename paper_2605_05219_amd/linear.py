@@ -55,5 +55,5 @@ def gdn_linear(x, w, bias, y, stream=None) -> None:
 
 
 def gdn_linear_tune(shape: int) -> int:
-    """Fixes the workgroup tile (0, 1) or returns the choice to the library (-1); returns the previous setting."""
+    """Fixes the workgroup tile (0, 1, 2) or returns the choice to the library (-1); returns the previous setting."""
     return int(_lib().gdn_linear_tune(int(shape)))

@@ -61,8 +61,8 @@ def test_empty_problems_are_legal_and_touch_nothing():
 
 
 def test_tile_knob_round_trip():
-    prev = LN.gdn_linear_tune(1)
-    assert LN.gdn_linear_tune(7) == 1          # out of range = per call
+    prev = LN.gdn_linear_tune(2)
+    assert LN.gdn_linear_tune(7) == 2          # out of range = per call
     assert LN.gdn_linear_tune(prev) == -1
 
 
@@ -132,7 +132,7 @@ def run_gpu(x, w, b, out, ldy=None, col0=0):
     (515, 2048, 2048, True, "f32"),            # the out-projection
     (64, 131, 192, True, "bf16"),              # an output count that is no multiple of 4 is only legal with ldy % 4 == 0
 ])
-@pytest.mark.parametrize("shape", [0, 1, -1])
+@pytest.mark.parametrize("shape", [0, 1, 2, -1])
 def test_linear_against_the_definition(T, N, K, bias, out, shape):
     x, w, b = draw(T * 7 + N * 3 + K, T, N, K, bias)
     ref = lo.linear(x, w, b)
