@@ -263,6 +263,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     f32x4 accS[8][2];
     int open = -1;         // chain whose state accS holds
     bool first = true;
+    bool state_pending = false;   // the start state of a new chain is still on its way
 
     int gdn_item = 0;      // items done (used by the profiling build only)
     (void)gdn_item;
@@ -301,10 +302,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
                     for (int mt = 0; mt < 8; ++mt)
                         accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (32 * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1));
-                // waited for here, once per chain: otherwise every later use of the state registers in the loop waits
-                // for whatever loads are in flight at that point (the next item's inputs), since the compiler cannot
-                // tell the iterations apart
-                wait_vmcnt<0>();
+                // not waited for here: the first chunk's gates, staging and preparation do not need the state, and the
+                // recurrence waits below
+                state_pending = true;
             } else {
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -454,6 +454,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         GDN_PHASE(5);
         __syncthreads();
+        if (state_pending) {   // a chain's first chunk: its start state (and, with it, the next chunk's rows) must have landed
+            wait_vmcnt<0>();
+            state_pending = false;
+        }
 
         GDN_PHASE(6);
         // ---- recurrence step of this chunk, d_v columns 32 wave + 16 nt + m
