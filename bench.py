@@ -666,18 +666,25 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
                 if rc < 0:
                     raise B.GdnError(rc, "gdn_linear")
 
+            def lin_split(x, w, plan, n_tok):
+                rc = LN.gdn_linear_split_raw(x, DM, w, DM, 0, plan, BF, n_tok, DM, cur)
+                if rc < 0:
+                    raise B.GdnError(rc, "gdn_linear_split")
+
             def proj_in(c, n):
+                # one launch per layer: [conv input | z | a | b] to the four tensors the layer's front and back ends read;
+                # one more for the attention layer's [q | k | v]
                 x = hid.data_ptr() + 2 * c * DM
                 for l in range(Lg):
-                    wl_ = w_in.data_ptr() + 2 * l * w_in.stride(0)
-                    lin(x, DM, wl_, Cc, DM, xs.data_ptr() + 2 * (l * N + c) * Cc, Cc, n)
-                    lin(x, DM, wl_ + 2 * Cc * DM, HV, DM, zs.data_ptr() + 2 * (l * N + c) * HV, HV, n)
-                    lin(x, DM, wl_ + 2 * (Cc + HV) * DM, HEADS, DM, aps.data_ptr() + 2 * (l * N + c) * HEADS, HEADS, n)
-                    lin(x, DM, wl_ + 2 * (Cc + HV + HEADS) * DM, HEADS, DM, bps.data_ptr() + 2 * (l * N + c) * HEADS, HEADS, n)
-                wa = w_att.data_ptr()
-                lin(x, DM, wa, HV, DM, aq2.data_ptr() + 2 * c * HV, HV, n)
-                lin(x, DM, wa + 2 * HV * DM, HKV * D, DM, akn2.data_ptr() + 2 * c * HKV * D, HKV * D, n)
-                lin(x, DM, wa + 2 * (HV + HKV * D) * DM, HKV * D, DM, avn2.data_ptr() + 2 * c * HKV * D, HKV * D, n)
+                    plan = LN.SplitPlan([Cc, HV, HEADS, HEADS],
+                                        [xs.data_ptr() + 2 * (l * N + c) * Cc, zs.data_ptr() + 2 * (l * N + c) * HV,
+                                         aps.data_ptr() + 2 * (l * N + c) * HEADS, bps.data_ptr() + 2 * (l * N + c) * HEADS],
+                                        [Cc, HV, HEADS, HEADS])
+                    lin_split(x, w_in.data_ptr() + 2 * l * w_in.stride(0), plan, n)
+                plan = LN.SplitPlan([HV, HKV * D, HKV * D],
+                                    [aq2.data_ptr() + 2 * c * HV, akn2.data_ptr() + 2 * c * HKV * D, avn2.data_ptr() + 2 * c * HKV * D],
+                                    [HV, HKV * D, HKV * D])
+                lin_split(x, w_att.data_ptr(), plan, n)
 
             def proj_out_gdn(c, n):
                 for l in range(Lg):
@@ -735,7 +742,7 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
             out["layer_group"] = {"layers": "3 GatedDeltaNet + 1 attention (16 query / 2 kv heads), d = 128, d_model 2048, projections included",
                                   "points": pts, "fit_ms": fit, "projection_flops_per_token": proj_flops_per_token,
                                   "note": "wall time of a whole hit per suffix length (8192 = a miss: nothing restored): in-projections of "
-                                          "the four layers (gdn_linear, bf16), front ends of the three GatedDeltaNet layers, recurrence, "
+                                          "the four layers (gdn_linear_split, one launch per layer, bf16), front ends of the three GatedDeltaNet layers, recurrence, "
                                           "back ends, their out-projections, attention and its out-projection; every layer reads the same "
                                           "hidden rows (the cost of a stacked group, not its data flow); host tier: checkpoint states "
                                           "(3 MiB) and the KV prefix come from pinned host memory inside the timed region; hbm tier: both "

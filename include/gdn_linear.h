@@ -42,6 +42,22 @@ int32_t gdn_linear(const void *x, int64_t ldx, const void *w, int64_t ldw, const
                    int64_t T, int32_t N, int32_t K, void *stream);
 
 /*
+ * The same map with its outputs split by column range over several destinations, one launch: segment s holds
+ * outputs seg_cols[s] .. seg_cols[s + 1] - 1 and goes to seg_y[s] (T rows of that many elements at seg_ld[s]
+ * elements).  This is the in-projection of a GatedDeltaNet layer as the layer's front end wants it: one weight
+ * matrix [conv input | z | a | b], four separate tensors (include/gdn_layer.h); N = seg_cols[n_seg].
+ *   n_seg      1 .. 8
+ *   seg_cols   host, n_seg + 1, seg_cols[0] = 0, strictly increasing; inner boundaries multiples of 8
+ *   seg_y      host array of n_seg device pointers (alignment as y above);  seg_ld: host, n_seg, multiples of 4
+ * Everything else as gdn_linear.  Errors as gdn_linear, and GDN_ERR_COUNT for n_seg outside 1 .. 8,
+ * GDN_ERR_SHAPE for seg_cols not starting at 0 or not increasing or a seg_ld below its segment's width,
+ * GDN_ERR_ALIGN for an inner boundary that is no multiple of 8.
+ */
+int32_t gdn_linear_split(const void *x, int64_t ldx, const void *w, int64_t ldw, const float *bias,
+                         int32_t n_seg, const int32_t *seg_cols, void *const *seg_y, const int64_t *seg_ld,
+                         int32_t out_dtype, int64_t T, int32_t K, void *stream);
+
+/*
  * Tuning knob, not a method step: fixes the workgroup tile gdn_linear uses (0: 128 x 128; 1: 256 x 256 with four
  * waves; 2: 256 x 256 with eight waves; anything else: chosen per call from T and N, the default).  Every shape computes the same
  * sums in the same order, so the results do not depend on it.  Process-wide; returns the previous setting (-1 = per

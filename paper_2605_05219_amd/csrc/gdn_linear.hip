@@ -35,6 +35,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 
+constexpr int LIN_MAX_SEG = 8;
+
 struct LinearArgs {
     const void* x;
     const void* w;
@@ -44,6 +46,11 @@ struct LinearArgs {
     int64_t T;
     int32_t N, K;
     int32_t tiles_n;
+    // gdn_linear_split: the outputs go to n_seg destinations by column range; n_seg = 0: everything to y
+    int32_t n_seg;
+    int32_t seg_col[LIN_MAX_SEG + 1];   // segment s holds outputs seg_col[s] .. seg_col[s + 1] - 1
+    void* seg_y[LIN_MAX_SEG];
+    int64_t seg_ld[LIN_MAX_SEG];
 };
 
 inline int32_t hip_err(hipError_t e) { return e == hipSuccess ? GDN_OK : GDN_ERR_HIP - (int32_t)e; }
@@ -282,13 +289,28 @@ gdn_linear_kernel(LinearArgs a) {
                 const int64_t tok = tok0 + t0 + row;
                 const int col = col0 + c0 + piece * (16 / ES);
                 if (tok < a.T && col < a.N) {
-                    char* const p = reinterpret_cast<char*>(a.y) + (tok * a.ldy + col) * ES;
-                    if (col + 16 / ES <= a.N) {
+                    // the destination of this piece: the whole output, or the segment its first column lies in (segment
+                    // boundaries are multiples of 8 columns, so a piece lies in one segment)
+                    char* base = reinterpret_cast<char*>(a.y);
+                    int64_t ld = a.ldy;
+                    int c_lo = 0, c_hi = a.N;
+                    if (a.n_seg > 0) {
+#pragma unroll
+                        for (int sg = 0; sg < LIN_MAX_SEG; ++sg)
+                            if (sg < a.n_seg && col >= a.seg_col[sg]) {
+                                base = reinterpret_cast<char*>(a.seg_y[sg]);
+                                ld = a.seg_ld[sg];
+                                c_lo = a.seg_col[sg];
+                                c_hi = a.seg_col[sg + 1];
+                            }
+                    }
+                    char* const p = base + (tok * ld + (col - c_lo)) * ES;
+                    if (col + 16 / ES <= c_hi) {
                         *reinterpret_cast<u32x4*>(p) = val;
                     } else {
 #pragma unroll
                         for (int e = 0; e < 16 / ES; ++e)
-                            if (col + e < a.N) {
+                            if (col + e < c_hi) {
                                 if (OUT_BF16) reinterpret_cast<uint16_t*>(p)[e] = (uint16_t)(val[e >> 1] >> (16 * (e & 1)));
                                 else reinterpret_cast<uint32_t*>(p)[e] = val[e];
                             }
@@ -348,36 +370,84 @@ int choose_linear_shape(int64_t T, int32_t N) {
 using namespace gdn;
 using namespace gdn::linear;
 
-extern "C" int32_t gdn_linear(const void* x, int64_t ldx, const void* w, int64_t ldw, const float* bias, void* y, int64_t ldy,
-                              int32_t out_dtype, int64_t T, int32_t N, int32_t K, void* stream_) {
+namespace {
+int32_t linear_checks(const void* x, int64_t ldx, const void* w, int64_t ldw, const float* bias, int32_t out_dtype, int64_t T, int32_t N,
+                      int32_t K) {
     if (T < 0 || N < 0 || K < 0) return GDN_ERR_COUNT;
     if (out_dtype != GDN_BF16 && out_dtype != GDN_F32) return GDN_ERR_SHAPE;
-    if (K % 64 != 0 || ldx < K || ldw < K || ldy < N) return GDN_ERR_SHAPE;
+    if (K % 64 != 0 || ldx < K || ldw < K) return GDN_ERR_SHAPE;
     if (T == 0 || N == 0) return GDN_OK;
     if (K == 0) return GDN_ERR_SHAPE;
-    if (!x || !w || !y) return GDN_ERR_NULL;
-    const uintptr_t ya = out_dtype == GDN_BF16 ? 7u : 15u;
-    if ((reinterpret_cast<uintptr_t>(x) & 15u) || (reinterpret_cast<uintptr_t>(w) & 15u) || (reinterpret_cast<uintptr_t>(y) & ya) ||
-        (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
+    if (!x || !w) return GDN_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(x) & 15u) || (reinterpret_cast<uintptr_t>(w) & 15u) || (bias && (reinterpret_cast<uintptr_t>(bias) & 3u)))
         return GDN_ERR_ALIGN;
-    if ((ldx & 7) || (ldw & 7) || (ldy & 3)) return GDN_ERR_ALIGN;
+    if ((ldx & 7) || (ldw & 7)) return GDN_ERR_ALIGN;
     // a tile's rows must be addressable with 31-bit byte offsets
     if ((int64_t)256 * ldx * 2 >= ((int64_t)1 << 31) || (int64_t)256 * ldw * 2 >= ((int64_t)1 << 31)) return GDN_ERR_COUNT;
     if (((T + 127) / 128) * (((int64_t)N + 127) / 128) > INT32_MAX) return GDN_ERR_COUNT;
-    LinearArgs a;
-    a.x = x; a.w = w; a.bias = bias; a.y = y;
-    a.ldx = ldx; a.ldw = ldw; a.ldy = ldy;
-    a.T = T; a.N = N; a.K = K;
+    return GDN_OK;
+}
+
+int32_t linear_launch(LinearArgs& a, int32_t out_dtype, hipStream_t stream) {
     a.tiles_n = 0;
-    hipStream_t stream = (hipStream_t)stream_;
     const bool bf = out_dtype == GDN_BF16;
     hipError_t e;
-    switch (choose_linear_shape(T, N)) {
+    switch (choose_linear_shape(a.T, a.N)) {
         case 1: e = bf ? launch_linear<LinBig, true>(a, stream) : launch_linear<LinBig, false>(a, stream); break;
         case 2: e = bf ? launch_linear<LinBig8, true>(a, stream) : launch_linear<LinBig8, false>(a, stream); break;
         default: e = bf ? launch_linear<LinSmall, true>(a, stream) : launch_linear<LinSmall, false>(a, stream); break;
     }
     return hip_err(e);
+}
+}  // namespace
+
+extern "C" int32_t gdn_linear(const void* x, int64_t ldx, const void* w, int64_t ldw, const float* bias, void* y, int64_t ldy,
+                              int32_t out_dtype, int64_t T, int32_t N, int32_t K, void* stream_) {
+    const int32_t rc = linear_checks(x, ldx, w, ldw, bias, out_dtype, T, N, K);
+    if (rc != GDN_OK) return rc;
+    if (ldy < N) return GDN_ERR_SHAPE;
+    if (T == 0 || N == 0) return GDN_OK;
+    if (!y) return GDN_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(y) & (out_dtype == GDN_BF16 ? 7u : 15u)) || (ldy & 3)) return GDN_ERR_ALIGN;
+    LinearArgs a = {};
+    a.x = x; a.w = w; a.bias = bias; a.y = y;
+    a.ldx = ldx; a.ldw = ldw; a.ldy = ldy;
+    a.T = T; a.N = N; a.K = K;
+    a.n_seg = 0;
+    return linear_launch(a, out_dtype, (hipStream_t)stream_);
+}
+
+extern "C" int32_t gdn_linear_split(const void* x, int64_t ldx, const void* w, int64_t ldw, const float* bias, int32_t n_seg,
+                                    const int32_t* seg_cols, void* const* seg_y, const int64_t* seg_ld, int32_t out_dtype, int64_t T,
+                                    int32_t K, void* stream_) {
+    if (n_seg < 1 || n_seg > LIN_MAX_SEG) return GDN_ERR_COUNT;
+    if (!seg_cols || !seg_y || !seg_ld) return GDN_ERR_NULL;
+    if (seg_cols[0] != 0) return GDN_ERR_SHAPE;
+    for (int32_t sg = 0; sg < n_seg; ++sg) {
+        if (seg_cols[sg + 1] <= seg_cols[sg]) return GDN_ERR_SHAPE;                 // empty or decreasing
+        if (sg + 1 < n_seg && (seg_cols[sg + 1] & 7)) return GDN_ERR_ALIGN;         // inner boundaries: whole 16-byte pieces
+    }
+    const int32_t N = seg_cols[n_seg];
+    const int32_t rc = linear_checks(x, ldx, w, ldw, bias, out_dtype, T, N, K);
+    if (rc != GDN_OK) return rc;
+    for (int32_t sg = 0; sg < n_seg; ++sg) {
+        if (seg_ld[sg] < seg_cols[sg + 1] - seg_cols[sg]) return GDN_ERR_SHAPE;
+        if (T > 0 && !seg_y[sg]) return GDN_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(seg_y[sg]) & (out_dtype == GDN_BF16 ? 7u : 15u)) || (seg_ld[sg] & 3)) return GDN_ERR_ALIGN;
+    }
+    if (T == 0) return GDN_OK;
+    LinearArgs a = {};
+    a.x = x; a.w = w; a.bias = bias; a.y = seg_y[0];
+    a.ldx = ldx; a.ldw = ldw; a.ldy = seg_ld[0];
+    a.T = T; a.N = N; a.K = K;
+    a.n_seg = n_seg;
+    for (int32_t sg = 0; sg < n_seg; ++sg) {
+        a.seg_col[sg] = seg_cols[sg];
+        a.seg_y[sg] = seg_y[sg];
+        a.seg_ld[sg] = seg_ld[sg];
+    }
+    for (int32_t sg = n_seg; sg <= LIN_MAX_SEG; ++sg) a.seg_col[sg] = N;
+    return linear_launch(a, out_dtype, (hipStream_t)stream_);
 }
 
 extern "C" int32_t gdn_linear_tune(int32_t shape) {

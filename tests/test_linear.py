@@ -60,6 +60,32 @@ def test_empty_problems_are_legal_and_touch_nothing():
     assert raw(N=0, w_ptr=0, y_ptr=0, ldy=0) == 0
 
 
+def split_raw(**over):
+    a = dict(widths=[512, 256, 16, 16], ptrs=[0x400000, 0x500000, 0x600000, 0x700000], lds=[512, 256, 16, 16], out_dtype=B.GDN_BF16,
+             T=100, K=256, x_ptr=0x100000, ldx=256, w_ptr=0x200000, ldw=256, bias_ptr=0)
+    a.update(over)
+    plan = LN.SplitPlan(a["widths"], a["ptrs"], a["lds"])
+    return LN.gdn_linear_split_raw(a["x_ptr"], a["ldx"], a["w_ptr"], a["ldw"], a["bias_ptr"], plan, a["out_dtype"], a["T"], a["K"])
+
+
+@pytest.mark.parametrize("over,code", [
+    (dict(widths=[8] * 9, ptrs=[0x400000] * 9, lds=[8] * 9), -11),             # more than 8 segments
+    (dict(widths=[512, 0, 16, 16]), -3),                                      # an empty segment
+    (dict(widths=[500, 268, 16, 16]), -2),                                    # an inner boundary inside a 16-byte piece
+    (dict(lds=[512, 128, 16, 16]), -3),                                       # a leading dimension below the segment's width
+    (dict(lds=[512, 258, 16, 16]), -2),
+    (dict(ptrs=[0x400000, 0, 0x600000, 0x700000]), -1),
+    (dict(ptrs=[0x400000, 0x500004, 0x600000, 0x700000]), -2),
+    (dict(K=100), -3), (dict(T=-1), -11), (dict(x_ptr=0), -1),
+])
+def test_split_argument_errors_are_reported_before_any_launch(over, code):
+    assert split_raw(**over) == code
+
+
+def test_split_with_no_tokens_is_legal():
+    assert split_raw(T=0) == 0
+
+
 def test_tile_knob_round_trip():
     prev = LN.gdn_linear_tune(2)
     assert LN.gdn_linear_tune(7) == 2          # out of range = per call
@@ -156,6 +182,37 @@ def test_output_may_be_a_column_slice_of_a_wider_buffer():
     y = run_gpu(x, w, b, "bf16", ldy=1024, col0=512)
     assert np.isnan(y[:, :512]).all() and np.isnan(y[:, 768:]).all()
     assert (np.abs(y[:, 512:768] - ref) <= bound(x, w, b, ref, K, "bf16")).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [0, 2])
+@pytest.mark.parametrize("out", ["bf16", "f32"])
+def test_split_outputs_equal_the_whole_projection(shape, out):
+    """The in-projection of a layer in one launch: [conv input | z | a | b] to four tensors of their own (the last boundary
+    ragged), each segment against the oracle's columns, nothing written outside."""
+    import torch
+    from paper_2605_05219_amd.device_call import to_device
+    T, K = 300, 128
+    widths = [384, 128, 16, 12]
+    N = sum(widths)
+    x, w, b = draw(17, T, N, K, True)
+    ref = lo.linear(x, w, b)
+    dt = torch.bfloat16 if out == "bf16" else torch.float32
+    fulls = [torch.full((T, wd + 8), float("nan"), dtype=dt, device="cuda") for wd in widths]
+    ys = [f[:, 4:4 + wd] for f, wd in zip(fulls, widths)]
+    prev = LN.gdn_linear_tune(shape)
+    try:
+        LN.gdn_linear_split(to_device(x), to_device(w), to_device(b), ys, None)
+        torch.cuda.synchronize()
+    finally:
+        LN.gdn_linear_tune(prev)
+    tol = bound(x, w, b, ref, K, out)
+    c = 0
+    for f, wd in zip(fulls, widths):
+        got = f.float().cpu().numpy().astype(np.float64)
+        assert np.isnan(got[:, :4]).all() and np.isnan(got[:, 4 + wd:]).all()
+        assert (np.abs(got[:, 4:4 + wd] - ref[:, c:c + wd]) <= tol[:, c:c + wd]).all()
+        c += wd
 
 
 @pytest.mark.gpu
