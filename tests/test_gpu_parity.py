@@ -673,6 +673,34 @@ def test_seeded_random_calls_on_the_fused_kernel():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("fused", [0, 1])
+def test_extreme_gates(fused):
+    """Gates that forget within one token (a = 1e-30, below what the clamp of log a lets through unchanged), gates of
+    exactly 1, and ordinary ones mixed token by token, with beta at 0 and 1 among them: the decay factors between blocks
+    may underflow but must never turn into infinities or NaNs, and a forgotten state must really be gone."""
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(31337)
+    L, H, d, n = 1, 2, 128, 200
+    st = wl.token_streams(rng, L, n, H, H, d, d, "bf16")
+    gate = wl.to_f32(st.gate).copy()
+    beta = wl.to_f32(st.beta).copy()
+    pick = rng.integers(0, 4, gate.shape)
+    gate[pick == 0] = 1e-30
+    gate[pick == 1] = 1.0
+    gate[pick == 2] = 1e-3
+    beta[rng.integers(0, 6, beta.shape) == 0] = 0.0
+    beta[rng.integers(0, 6, beta.shape) == 0] = 1.0
+    st = wl.Streams(st.q, st.k, st.v, wl.to_storage(beta, "bf16"), wl.to_storage(gate, "bf16"))
+    call = wl.pack_call(L, H, H, d, d, "bf16", [st], [64], [1], [[100, 264]], [[2, 3]], 5)
+    pool = (rng.standard_normal((5,) + call.slot_shape) * 0.5).astype(np.float32)
+    prev = B.gdn_tune_fused(fused)
+    try:
+        check_call(call, pool, TOL["bf16"])
+    finally:
+        B.gdn_tune_fused(prev)
+
+
+@pytest.mark.gpu
 def test_probe_ceilings_reports_plausible_machine_rates():
     """The probe's figures lie between a fifth of the data-sheet peaks and the peaks themselves."""
     import torch
