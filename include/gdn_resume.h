@@ -110,7 +110,7 @@ int64_t gdn_workspace_bytes(const gdn_shape *shape, int32_t n_req, int64_t total
 
 /*
  * The smaller workspace that suffices when the call is served by the fused kernel (bf16 inputs,
- * d_k = d_v = 128: preparation and recurrence of a chain in one workgroup, see gdn_tune_fused):
+ * d_k = d_v = 128 or 64: preparation and recurrence of a chain in one workgroup, see gdn_tune_fused):
  * the chunk plan only.  A call given at least this much but less than gdn_workspace_bytes runs
  * the fused kernel whatever the library's estimate says; for other shapes the value equals
  * gdn_workspace_bytes.  Negative on error.
@@ -191,7 +191,7 @@ int32_t gdn_resume_prefill(const gdn_shape *shape,
  * the library, gdn_static_plan_capacity() bytes per GPU (512 KiB, held until the process ends;
  * enough for about 43 000 chunks, i.e. 2.7 M tokens per layer), and is written there by the
  * arguments of small launches on `stream`: no hipMalloc, no hipFree, no pinned staging buffer,
- * no host-to-device copy.  The fused kernel serves the call (bf16 inputs, d_k = d_v = 128; other
+ * no host-to-device copy.  The fused kernel serves the call (bf16 inputs, d_k = d_v = 128 or 64; other
  * shapes return GDN_ERR_SHAPE; gdn_tune_fused does not apply); a plan beyond the capacity returns
  * GDN_ERR_STATIC_LIMIT before anything is enqueued.  Every call on a GPU uses that GPU's one array:
  * calls must be ordered on one stream (or otherwise not overlap in time), two overlapping calls
@@ -310,7 +310,7 @@ int32_t gdn_probe_ceilings(void *scratch, int64_t scratch_bytes, double *mfma_f1
 int32_t gdn_tune_slab_rounds(int32_t rounds);
 
 /*
- * Tuning knob (not a step of the method).  Calls with bf16 inputs, d_k = d_v = 128 and many
+ * Tuning knob (not a step of the method).  Calls with bf16 inputs, d_k = d_v = 128 or 64 and many
  * chains are served by one fused kernel (preparation and recurrence of a chain in one
  * workgroup, no operand image in memory) when the library estimates it to be faster than the
  * two-kernel path.  mode 1 forces the fused kernel wherever it applies, mode 0 forbids it,

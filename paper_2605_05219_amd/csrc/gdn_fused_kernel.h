@@ -1,4 +1,4 @@
-// Fused throughput kernel (bf16 inputs, d_k = d_v = 128): chunk preparation and recurrence of
+// Fused throughput kernel (bf16 inputs, d_k = d_v = D = 128 or 64): chunk preparation and recurrence of
 // one chain (request, layer, value head) in ONE workgroup, chunk after chunk, the chunk
 // operands never leaving the compute unit.  HBM sees q, k, v, the gates, o and the states,
 // nothing else.  A chain's chunks are serial, so the kernel only pays when chains are plentiful
@@ -21,12 +21,12 @@
 //
 // A workgroup is four waves.  Preparation: wave a owns block row a (its diagonal inverse, its L blocks and
 // their products with T_aa) and the P blocks of query block 3 - a, five 16x16 gram blocks each.  Recurrence:
-// wave w owns the 32 d_v columns 32 w .. 32 w + 31 of the state (two 16-column tiles, the state of a tile in
-// eight accumulator tiles over d_k); the state products of block row a + 1 are issued ahead of block row a's
+// wave w owns the D / 4 d_v columns of the state from (D / 4) w on (D / 64 16-column tiles, the state of a tile in
+// D / 16 accumulator tiles over d_k); the state products of block row a + 1 are issued ahead of block row a's
 // substitution.  Three barriers per chunk.
 //
-// LDS (FusedSmem, 72.3 KB, two workgroups per compute unit):
-//   K, Q, V  fp16 [64][128], rows unpadded, the 16-byte pieces of a row XOR-swizzled with the row number (swz):
+// LDS (FusedSmem<D>: 73 KB at D = 128, two workgroups per compute unit; 49 KB at D = 64, three):
+//   K, Q, V  fp16 [64][D], rows unpadded, the 16-byte pieces of a row XOR-swizzled with the row number (swz):
 //            row reads (lane = token, one piece: the A/B operand of a product over d_k) are free of bank
 //            conflicts, transposing reads (ds_read_b64_tr_b16: lane = column, four tokens: K^T for the state
 //            update, V^T for the substitution) touch one half of every piece and are two-way at best
@@ -64,8 +64,9 @@ struct FusedArgs {
     int32_t o_bf16;
 };
 
+template <int D_>
 struct FusedSmem {
-    static constexpr int C = 64, D = 128;
+    static constexpr int C = 64, D = D_;
     static constexpr int TILE_BYTES = C * D * 2;            // one of K, Q, V
     static constexpr int PAIR_LD = 40, TF_LD = 20;          // halfs / floats per row
     static constexpr int PAIR_BYTES = 16 * PAIR_LD * 2;     // one 16 x (2 x 16) fp16 pair tile
@@ -95,13 +96,15 @@ __device__ __forceinline__ int32_t plan_word(const int32_t* p, int i) {
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-// Swizzle of the 16-byte pieces of a row of a [64][128] fp16 tile: piece p of row r sits at p ^ swz(r).  The LDS
-// has 64 banks of 4 bytes (a row is 256 bytes, so without it every row starts at bank 0).  swz is a bijection of
-// the low four bits of the row: 16 lanes reading the same piece of 16 consecutive rows (row reads, 16 bytes per
-// lane) touch 16 different bank groups; its bit 3 also moves with the row's bit 0, so that the 8 rows x 4 pieces a
-// transposing read addresses per cycle (8 bytes per lane, the same half of every piece) spread two by two over
-// all 16 groups, which is the best that half-pieces allow.
-__device__ __forceinline__ int swz(int row) { return (row & 15) ^ ((row & 1) << 3); }
+// Swizzle of the 16-byte pieces of a row of a [64][D] fp16 tile: piece p of row r sits at p ^ swz(r).  The LDS has 64
+// banks of 4 bytes.  D = 128 (a row is 256 bytes, so without it every row starts at bank 0): swz is a bijection of the low
+// four bits of the row: 16 lanes reading the same piece of 16 consecutive rows (row reads, 16 bytes per lane) touch 16
+// different bank groups; its bit 3 also moves with the row's bit 0, so that the 8 rows x 4 pieces a transposing read
+// addresses per cycle (8 bytes per lane, the same half of every piece) spread two by two over all 16 groups, which is the
+// best that half-pieces allow.  D = 64 (128-byte rows, two to a bank span, eight pieces): the row's bits 1..3, so that 16
+// consecutive rows with the same piece again touch 16 different groups.  Either way swz(r + 16) = swz(r).
+template <int D>
+__device__ __forceinline__ int swz(int row) { return D == 128 ? ((row & 15) ^ ((row & 1) << 3)) : ((row >> 1) & 7); }
 
 __device__ __forceinline__ half4 cvt4(const f32x4& x) {
     half4 h;
@@ -149,13 +152,20 @@ __device__ unsigned long long g_phase_ts[64 * 4 * 16];
 #define GDN_PHASE_ITEM() ((void)0)
 #endif
 
-template <bool O_BF16>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) gdn_fused_kernel(FusedArgs a) {
+template <bool O_BF16, int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 128 ? 2 : 3))) gdn_fused_kernel(FusedArgs a) {
     typedef Elem<half_t> EL;
     typedef EL::In In;
     typedef EL::Raw8 Raw8;
-    typedef FusedSmem SM;
-    constexpr int C = 64, DK = 128, DV = 128, PLD = SM::PAIR_LD;
+    typedef FusedSmem<D> SM;
+    constexpr int C = 64, DK = D, DV = D, PLD = SM::PAIR_LD;
+    constexpr int NT = D / 64;        // 16-column tiles of the state per wave (a wave owns D / 4 columns of d_v)
+    constexpr int SS = D / 32;        // steps of 32 over d_k (one 16-byte piece per lane and step)
+    constexpr int MT = D / 16;        // 16-wide tiles over d_k
+    constexpr int RBY = 2 * D;        // bytes of a K, Q or V tile row
+    constexpr int PCS = D / 8;        // 16-byte pieces per row
+    constexpr int ROWS = D / 32;      // rows of each tensor a thread stages (256 threads, 64 rows of PCS pieces)
+    constexpr int WC = D / 4;         // d_v columns per wave
 
     extern __shared__ __align__(16) char smem[];
     char* const Kt = smem + SM::K_OFF;
@@ -180,8 +190,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     const In* const kg = reinterpret_cast<const In*>(a.k);
     const In* const vg = reinterpret_cast<const In*>(a.v);
 
-    // A thread owns 4-token x 8-column blocks of K, Q and V (256 blocks each).
-    const int tg_ = tid >> 4, d0_ = (tid & 15) * 8;
+    // A thread owns ROWS-token x 8-column blocks of K, Q and V (256 blocks each).
+    const int tg_ = tid / PCS, d0_ = (tid % PCS) * 8;
 
     // The unused halves of the pair tiles (a lone block is paired with zeros) are zeroed once; nothing writes them later.
     for (int i = tid; i < (SM::TF_OFF - SM::TBTG_OFF) / 16; i += 256)
@@ -226,7 +236,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         return open_chain(cur.round + 1);
     };
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
-    Raw8 kraw[4], qraw[4], vraw[4];
+    Raw8 kraw[ROWS], qraw[ROWS], vraw[ROWS];
     In graw = In();      // wave 0: the lane's gate; wave 1: its beta
     auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
         const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
@@ -238,8 +248,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(qg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
         const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(vg + (row0 * a.H_v + hv) * DV), 0, (it.n - 1) * v_step + DV * 2, 0x00020000);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = 4 * tg + r;
+        for (int r = 0; r < ROWS; ++r) {
+            const int i = ROWS * tg + r;
             kraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rk, i * qk_step + d0 * 2, 0, 2));
             qraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, i * qk_step + d0 * 2, 0, 2));
             vraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rv, i * v_step + d0 * 2, 0, 2));
@@ -260,7 +270,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     // State tile (mt = 2 s + h, nt): element e of lane (m, g4) is S[32 w + 16 nt + m][32 s + 8 g4 + 4 h + e], so that the
     // tile pair of step s is, lane for lane, the operand over d_k columns 32 s + 8 g4 .. + 7: one 16-byte piece of a K or Q row.
-    f32x4 accS[8][2];
+    f32x4 accS[MT][NT];
     int open = -1;         // chain whose state accS holds
     bool first = true;
     bool state_pending = false;   // the start state of a new chain is still on its way
@@ -278,38 +288,38 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         const int64_t head_off = ((int64_t)l * a.H_v + hv) * DV * DK;
         // LDS byte offsets of this lane inside a K/Q/V tile; the rest of every address is a compile-time constant.
         //   row reads: lane (m, g4) reads piece 4 s + g4 of row 16 blk + m, which sits at (4 s + g4) ^ swz(m)
-        int row_b[4], tr_b[4];
+        int row_b[SS], tr_b[SS];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) row_b[s] = m * 256 + 16 * ((4 * s + g4) ^ swz(m));       // + blk * 4096
+        for (int s = 0; s < SS; ++s) row_b[s] = m * RBY + 16 * ((4 * s + g4) ^ swz<D>(m));     // + blk * 16 * RBY
         //   transposing reads of K for the state update: lane j of group g4 addresses token tok0 + 4 g4 + j / 4, d_k columns
         //   32 s + 8 (j % 4) + 4 h ...: lane i then receives column 32 s + 8 (i / 4) + 4 h + i % 4, which is row i of state tile 2 s + h
         const int trow = 4 * g4 + (m >> 2);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) tr_b[s] = trow * 256 + 16 * ((4 * s + (m & 3)) ^ swz(trow));   // + tok0 * 256 + 8 h
+        for (int s = 0; s < SS; ++s) tr_b[s] = trow * RBY + 16 * ((4 * s + (m & 3)) ^ swz<D>(trow));   // + tok0 * RBY + 8 h
         //   transposing reads of V for the substitution: lane i receives column 32 w + 16 nt + i: lane j addresses columns
         //   32 w + 16 nt + 4 (j % 4) ..., i.e. piece 4 w + 2 nt + (j % 4) / 2, half (j % 4) % 2
-        int tv[2];
+        int tv[NT];
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-            tv[nt] = trow * 256 + 16 * ((4 * wave + 2 * nt + ((m & 3) >> 1)) ^ swz(trow)) + 8 * (m & 1);   // + tok0 * 256
+        for (int nt = 0; nt < NT; ++nt)
+            tv[nt] = trow * RBY + 16 * (((WC / 8) * wave + 2 * nt + ((m & 3) >> 1)) ^ swz<D>(trow)) + 8 * (m & 1);   // + tok0 * RBY
 
         if (open != cur.chain) {   // a new chain: its start state, from the pool slot or zero
             const int slot = plan_word(a.req_src_slot, plan_word(a.req_order, cur.chain / units));
             if (slot >= 0) {
                 const float* src = a.state_src + slot * a.src_slot_stride + head_off;
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt)
-                        accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (32 * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1));
+                    for (int mt = 0; mt < MT; ++mt)
+                        accS[mt][nt] = *reinterpret_cast<const f32x4*>(src + (WC * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1));
                 // not waited for here: the first chunk's gates, staging and preparation do not need the state, and the
                 // recurrence waits below
                 state_pending = true;
             } else {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt) accS[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    for (int mt = 0; mt < MT; ++mt) accS[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
             open = cur.chain;
         }
@@ -343,9 +353,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int i = 4 * tg + r;
-            const int off = i * 256 + (((d0 >> 3) ^ swz(i)) << 4);
+        for (int r = 0; r < ROWS; ++r) {
+            const int i = ROWS * tg + r;
+            const int off = i * RBY + (((d0 >> 3) ^ swz<D>(i)) << 4);
             float kv[8], qv[8], vv[8];
             EL::unpack(kraw[r], kv);
             EL::unpack(qraw[r], qv);
@@ -365,23 +375,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
         // operand over d_k columns 32 s + 8 g4 .. + 7 of row 16 blk + m of a tile
         auto row_frag = [&](const char* tile, int blk, int s) -> half8 {
-            return *reinterpret_cast<const half8*>(tile + row_b[s] + blk * 4096);
+            return *reinterpret_cast<const half8*>(tile + row_b[s] + blk * 16 * RBY);
         };
 
         // ---- preparation.  Wave a: block row a of L (diagonal inverse T_aa, the blocks -T_aa L_ac, T_aa diag(b),
         //      -T_aa diag(b gam)) and the P blocks of query block ia = 3 - a.
         {
             const int ab = wave, ia = 3 - wave;
-            half8 ka[4], qf[4];        // K rows of block ab and Q rows of block ia as operands over d_k
+            half8 ka[SS], qf[SS];      // K rows of block ab and Q rows of block ia as operands over d_k
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
+            for (int s = 0; s < SS; ++s) {
                 ka[s] = row_frag(Kt, ab, s);
                 qf[s] = row_frag(Qt, ia, s);
             }
             // diagonal block: raw gram (symmetric), scaled into the tiles of D and of D^T
             f32x4 gr = {0, 0, 0, 0};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) gr = mma32(ka[s], ka[s], gr);
+            for (int s = 0; s < SS; ++s) gr = mma32(ka[s], ka[s], gr);
             const f32x4 gi = *reinterpret_cast<const f32x4*>(gS + 16 * ab + 4 * g4);
             const f32x4 bi = *reinterpret_cast<const f32x4*>(bS + 16 * ab + 4 * g4);
             const float gj = gS[16 * ab + m], bj = bS[16 * ab + m];
@@ -411,13 +421,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             // block ia, P (rows j = keys in registers, lane = query i)
             for (int c = 0; c < 4; ++c) {
                 if (c >= ab && c > ia) continue;
-                half8 kc[4];
+                half8 kc[SS];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) kc[s] = row_frag(Kt, c, s);
+                for (int s = 0; s < SS; ++s) kc[s] = row_frag(Kt, c, s);
                 if (c < ab) {
                     f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) acc = mma32(ka[s], kc[s], acc);   // rows i in block ab, lanes j in block c
+                    for (int s = 0; s < SS; ++s) acc = mma32(ka[s], kc[s], acc);   // rows i in block ab, lanes j in block c
                     const float sj = sS[16 * c + m];
                     const f32x4 ri = *reinterpret_cast<const f32x4*>(rS + c * C + 16 * ab + 4 * g4);
                     f32x4 lt;
@@ -433,7 +443,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 if (c <= ia) {
                     f32x4 acc = {0, 0, 0, 0};
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) acc = mma32(kc[s], qf[s], acc);
+                    for (int s = 0; s < SS; ++s) acc = mma32(kc[s], qf[s], acc);
                     f32x4 p;
                     if (c < ia) {   // a block below the diagonal: every key is visible, the decay factors
                         const float pr = a.scale * rS[c * C + 16 * ia + m];
@@ -460,19 +470,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
 
         GDN_PHASE(6);
-        // ---- recurrence step of this chunk, d_v columns 32 wave + 16 nt + m
+        // ---- recurrence step of this chunk, d_v columns WC wave + 16 nt + m
         {
-            half8 sf[4][2];        // the state as an operand over d_k: step s = state tiles 2 s, 2 s + 1
+            half8 sf[SS][NT];        // the state as an operand over d_k: step s = state tiles 2 s, 2 s + 1
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+            for (int s = 0; s < SS; ++s)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) sf[s][nt] = cat8(cvt4(accS[2 * s][nt]), cvt4(accS[2 * s + 1][nt]));
+                for (int nt = 0; nt < NT; ++nt) sf[s][nt] = cat8(cvt4(accS[2 * s][nt]), cvt4(accS[2 * s + 1][nt]));
             // U as an operand over the tokens of block pair p (blocks 2 p, 2 p + 1); a block not yet computed reads as zero
-            half8 uh[2][2];
+            half8 uh[2][NT];
 #pragma unroll
             for (int p = 0; p < 2; ++p)
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) uh[p][nt][e] = (half_t)0.f;
             const int64_t row0 = (int64_t)l * a.T_alloc + cur.tok0;
@@ -481,37 +491,39 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             const int o_step = a.H_v * DV * OB;
             const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
                 reinterpret_cast<char*>(a.o) + ((row0 * a.H_v + hv) * DV) * OB, 0, (n - 1) * o_step + DV * OB, 0x00020000);
-            const int o_lane = m * o_step + (32 * wave + 4 * g4) * OB;
+            const int o_lane = m * o_step + (WC * wave + 4 * g4) * OB;
             // K_a S0^T (tokens in registers) and (Q_a S0^T)^T (d_v in registers, lane = token) of block row ab: 16 independent
             // products.  They are issued one block row ahead, in between the short dependent products of the substitution.
-            auto state_products = [&](int ab, f32x4 (&ks)[2], f32x4 (&ot)[2]) {
+            auto state_products = [&](int ab, f32x4 (&ks)[NT], f32x4 (&ot)[NT]) {
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) { ks[nt] = f32x4{0, 0, 0, 0}; ot[nt] = f32x4{0, 0, 0, 0}; }
+                for (int nt = 0; nt < NT; ++nt) { ks[nt] = f32x4{0, 0, 0, 0}; ot[nt] = f32x4{0, 0, 0, 0}; }
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
+                for (int s = 0; s < SS; ++s) {
                     const half8 kfr = row_frag(Kt, ab, s);
                     const half8 qfr = row_frag(Qt, ab, s);
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
+                    for (int nt = 0; nt < NT; ++nt) {
                         ks[nt] = mma32(kfr, sf[s][nt], ks[nt]);
                         ot[nt] = mma32(sf[s][nt], qfr, ot[nt]);
                     }
                 }
             };
-            f32x4 ks_n[2], ot_n[2];
+            f32x4 ks_n[NT], ot_n[NT];
             state_products(0, ks_n, ot_n);
-            half8 ud[2][2];   // diag(dec) U, like uh
+            half8 ud[2][NT];   // diag(dec) U, like uh
 #pragma unroll
             for (int ab = 0; ab < 4; ++ab) {
                 const int row = 16 * ab + m;
-                f32x4 ks[2] = {ks_n[0], ks_n[1]}, ot[2] = {ot_n[0], ot_n[1]};
+                f32x4 ks[NT], ot[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) { ks[nt] = ks_n[nt]; ot[nt] = ot_n[nt]; }
                 if (ab < 3) state_products(ab + 1, ks_n, ot_n);
                 // U_a = [T_aa diag(b) | -T_aa diag(b gam)] [V_a ; K_a S0^T] + sum_c (-T_aa L_ac) U_c, two blocks c per product
                 const half8 tf = *reinterpret_cast<const half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4);
-                f32x4 u[2];
+                f32x4 u[NT];
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-                    const half4 vt = tr_read(Vt + tv[nt] + ab * 4096);
+                for (int nt = 0; nt < NT; ++nt) {
+                    const half4 vt = tr_read(Vt + tv[nt] + ab * 16 * RBY);
                     const f32x4 zero = {0, 0, 0, 0};
                     u[nt] = mma32(tf, cat8(vt, cvt4(ks[nt])), zero);
                 }
@@ -520,11 +532,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (2 * p < ab) {
                         const half8 mf = *reinterpret_cast<const half8*>(mimg + (SM::m_pair(ab, 2 * p) * 16 + m) * PLD + 8 * g4);
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) u[nt] = mma32(mf, uh[p][nt], u[nt]);
+                        for (int nt = 0; nt < NT; ++nt) u[nt] = mma32(mf, uh[p][nt], u[nt]);
                     }
                 const f32x4 dc = *reinterpret_cast<const f32x4*>(decS + 16 * ab + 4 * g4);
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
+                for (int nt = 0; nt < NT; ++nt) {
                     const half4 h = cvt4(u[nt]);
                     f32x4 x;
 #pragma unroll
@@ -539,7 +551,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 // O_a^T = diag(gam scale) (Q_a S0^T)^T + sum_{c <= a} U_c^T P_ac^T   (lane = token)
                 const float gm = gamS[row] * a.scale;
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) ot[nt][e] *= gm;
 #pragma unroll
@@ -547,7 +559,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     if (2 * p <= ab) {
                         const half8 pf = *reinterpret_cast<const half8*>(pimg + (SM::p_pair(ab, 2 * p) * 16 + m) * PLD + 8 * g4);
 #pragma unroll
-                        for (int nt = 0; nt < 2; ++nt) ot[nt] = mma32(uh[p][nt], pf, ot[nt]);
+                        for (int nt = 0; nt < NT; ++nt) ot[nt] = mma32(uh[p][nt], pf, ot[nt]);
                     }
                 // The next item's inputs (fetched at staging time) must have landed before this item's first store is
                 // issued: loads and stores share one in-flight counter, and with both kinds pending the first use of a
@@ -559,12 +571,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                     typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
                     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)   // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
+                    for (int nt = 0; nt < NT; ++nt)   // v_cvt_pk_bf16_f32: round to nearest even, two values per instruction
                         __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, __builtin_convertvector(ot[nt], bf16x4)), ro,
                                                               o_lane + ab * 16 * o_step + 32 * nt, 0, 0);
                 } else {
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
+                    for (int nt = 0; nt < NT; ++nt)
                         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, ot[nt]), ro, o_lane + ab * 16 * o_step + 64 * nt, 0, 0);
                 }
             }
@@ -572,12 +584,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             // state update: S^T = gam_C S^T + sum_j K^T[.][j] (dec_j U[j][.]), two token blocks per product
             const float gam_last = gamS[C - 1];
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
+            for (int mt = 0; mt < MT; ++mt) {
                 const char* kt = Kt + tr_b[mt >> 1] + 8 * (mt & 1);
-                const half8 k0 = cat8(tr_read(kt), tr_read(kt + 16 * 256));
-                const half8 k1 = cat8(tr_read(kt + 32 * 256), tr_read(kt + 48 * 256));
+                const half8 k0 = cat8(tr_read(kt), tr_read(kt + 16 * RBY));
+                const half8 k1 = cat8(tr_read(kt + 32 * RBY), tr_read(kt + 48 * RBY));
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
+                for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) accS[mt][nt][e] *= gam_last;
                     accS[mt][nt] = mma32(k0, ud[0][nt], accS[mt][nt]);
@@ -590,10 +602,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
             if (eslot >= 0) {
                 float* dst = a.state_dst + eslot * a.dst_slot_stride + head_off;
 #pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
+                for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt)
-                        *reinterpret_cast<f32x4*>(dst + (32 * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1)) = accS[mt][nt];
+                    for (int mt = 0; mt < MT; ++mt)
+                        *reinterpret_cast<f32x4*>(dst + (WC * wave + 16 * nt + m) * DK + 32 * (mt >> 1) + 8 * g4 + 4 * (mt & 1)) = accS[mt][nt];
             }
         }
 

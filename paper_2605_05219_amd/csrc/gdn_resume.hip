@@ -381,50 +381,55 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
     return hipGetLastError();
 }
 
-// Fused throughput kernel (bf16 inputs, d = 128): see gdn_fused_kernel.h.
-template <bool O_BF16>
+// Fused throughput kernel (bf16 inputs, d_k = d_v = 64 or 128): see gdn_fused_kernel.h.
+template <bool O_BF16, int D>
 hipError_t launch_fused_t(const FusedArgs& fa, hipStream_t stream) {
-    typedef FusedSmem SM;
+    typedef FusedSmem<D> SM;
     static std::once_flag once;
     static hipError_t once_err = hipSuccess;
     static int slots = 1;
     std::call_once(once, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
         int dev = 0, cus = 0, per_cu = 0;
         if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16>, 256, SM::BYTES);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16, D>, 256, SM::BYTES);
         once_err = e;
         if (e == hipSuccess) slots = std::max(1, cus * per_cu);
     });
     if (once_err != hipSuccess) return once_err;
-    hipLaunchKernelGGL(gdn_fused_kernel<O_BF16>, dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
+    hipLaunchKernelGGL((gdn_fused_kernel<O_BF16, D>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
                        stream, fa);
     return hipGetLastError();
 }
-hipError_t launch_fused(const FusedArgs& fa, hipStream_t stream) {
-    return fa.o_bf16 ? launch_fused_t<true>(fa, stream) : launch_fused_t<false>(fa, stream);
+hipError_t launch_fused(const FusedArgs& fa, int d, hipStream_t stream) {
+    if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64>(fa, stream) : launch_fused_t<false, 64>(fa, stream);
+    return fa.o_bf16 ? launch_fused_t<true, 128>(fa, stream) : launch_fused_t<false, 128>(fa, stream);
 }
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
 // plentiful and the longest chain does not outlast the whole two-kernel run.  Estimates from
-// figures measured on MI355X (bf16, d = 128; one call of 1 to 64 requests of up to 8192 tokens,
-// and the large configurations): fused, per chunk of one chain 5.9 us with one workgroup per
+// figures measured on MI355X (bf16; one call of 1 to 64 requests of up to 8192 tokens, and the
+// large configurations).  d = 128: fused, per chunk of one chain 5.9 us with one workgroup per
 // compute unit (up to 256 chains) and 7.7 us with two, per (chunk, chain) unit of a large call
 // 0.022 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured: 128 chains 0.77 ms
 // fused against 0.56 ms, 160 chains 0.77 against 0.82, 256 chains 0.82 against 1.22, 512 chains
-// 0.99 against 2.09, 1024 chains 1.67 against 3.98.  gdn_tune_fused forces the choice.
+// 0.99 against 2.09, 1024 chains 1.67 against 3.98.  d = 64: 3.4 / 4.4 us per chunk, 0.0115 us
+// per unit; two-kernel path 0.036 us per unit plus about 0.1 ms (requests of up to 4096 tokens:
+// 128 chains 0.22 ms either way, 256 chains 0.26 against 0.39, 1024 chains 0.46 against 1.48).
+// gdn_tune_fused forces the choice.
 std::atomic<int32_t> g_forced_fused{-1};
-inline bool fused_applies(const gdn_shape& s) { return s.in_dtype == GDN_BF16 && s.d_k == 128 && s.d_v == 128; }
+inline bool fused_applies(const gdn_shape& s) { return s.in_dtype == GDN_BF16 && s.d_k == s.d_v && (s.d_k == 128 || s.d_k == 64); }
 inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
     if (!fused_applies(s)) return false;
     const int forced = g_forced_fused.load();
     if (forced >= 0) return forced != 0;
     if (n_chains < 128) return false;
-    const double per_chunk = n_chains <= chip_cus() ? 5.9 : 7.7;   // us: one or two workgroups per compute unit
-    const double t_two = 0.056 * (double)total_units + 150.0;
-    const double t_fused = std::max(0.022 * (double)total_units, per_chunk * (double)longest_chain_chunks);
+    const bool big = s.d_k == 128;
+    const double per_chunk = n_chains <= chip_cus() ? (big ? 5.9 : 3.4) : (big ? 7.7 : 4.4);   // us: one or two workgroups per compute unit
+    const double t_two = (big ? 0.056 : 0.036) * (double)total_units + (big ? 150.0 : 100.0);
+    const double t_fused = std::max((big ? 0.022 : 0.0115) * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
 }
 
@@ -965,7 +970,7 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         fa.scale = s.scale;
         fa.o_bf16 = s.o_dtype == GDN_BF16;
         ProfChain prof(stream);
-        const hipError_t e = launch_fused(fa, stream);
+        const hipError_t e = launch_fused(fa, s.d_k, stream);
         if (e != hipSuccess) return hip_err(e);
         prof.mark(1);
         std::lock_guard<std::mutex> lock(g_prof.mu);

@@ -642,16 +642,17 @@ def test_seeded_random_calls_match_the_oracle(many):
 
 @pytest.mark.gpu
 def test_seeded_random_calls_on_the_fused_kernel():
-    """The fused kernel forced onto small seeded calls it would not be chosen for: one value head (an output row is then
-    exactly as long as the output descriptor's last row), grouped value heads, chunks of 1 to 64 tokens, requests of
-    length 0, several layers, emits anywhere, both output types."""
+    """The fused kernel forced onto small seeded calls it would not be chosen for: both head sizes, one value head (an
+    output row is then exactly as long as the output descriptor's last row), grouped value heads, chunks of 1 to 64
+    tokens, requests of length 0, several layers, emits anywhere, both output types."""
     from paper_2605_05219_amd import binding as B
     rng = np.random.default_rng(9090)
-    shapes = [(1, 1, 1), (1, 1, 2), (2, 1, 1), (1, 2, 4), (3, 2, 2), (1, 4, 4), (2, 2, 8)]
+    shapes = [(1, 1, 1, 128), (1, 1, 2, 128), (2, 1, 1, 64), (1, 2, 4, 128), (3, 2, 2, 64), (1, 4, 4, 128), (2, 2, 8, 64),
+              (1, 1, 1, 64), (1, 16, 16, 64)]
     prev = B.gdn_tune_fused(1)
     try:
-        for it in range(14):
-            L, H_qk, H_v = shapes[it % len(shapes)]
+        for it in range(18):
+            L, H_qk, H_v, d = shapes[it % len(shapes)]
             n_req = int(rng.integers(1, 7))
             lens = [int(x) for x in rng.choice([0, 1, 2, 15, 16, 17, 63, 64, 65, 100, 129, 200], n_req)]
             if sum(lens) == 0:
@@ -663,9 +664,9 @@ def test_seeded_random_calls_on_the_fused_kernel():
                 emits.append(e)
                 eslots.append(list(range(nxt, nxt + len(e))))
                 nxt += len(e)
-            per_req = [wl.token_streams(rng, L, ln, H_qk, H_v, 128, 128, "bf16", "slow" if it % 3 == 0 else "config") for ln in lens]
+            per_req = [wl.token_streams(rng, L, ln, H_qk, H_v, d, d, "bf16", "slow" if it % 3 == 0 else "config") for ln in lens]
             src = [-1 if s0 == 0 else int(rng.integers(0, 3)) for s0 in starts]
-            call = wl.pack_call(L, H_qk, H_v, 128, 128, "bf16", per_req, starts, src, emits, eslots, nxt + 1)
+            call = wl.pack_call(L, H_qk, H_v, d, d, "bf16", per_req, starts, src, emits, eslots, nxt + 1)
             pool = rng.standard_normal((nxt + 1,) + call.slot_shape).astype(np.float32) * 0.1
             check_call(call, pool, TOL["bf16"], o_dtype="bf16" if it % 2 else "f32")
     finally:
@@ -673,14 +674,15 @@ def test_seeded_random_calls_on_the_fused_kernel():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("fused", [0, 1])
-def test_extreme_gates(fused):
+def test_extreme_gates(fused, d):
     """Gates that forget within one token (a = 1e-30, below what the clamp of log a lets through unchanged), gates of
     exactly 1, and ordinary ones mixed token by token, with beta at 0 and 1 among them: the decay factors between blocks
     may underflow but must never turn into infinities or NaNs, and a forgotten state must really be gone."""
     from paper_2605_05219_amd import binding as B
     rng = np.random.default_rng(31337)
-    L, H, d, n = 1, 2, 128, 200
+    L, H, n = 1, 2, 200
     st = wl.token_streams(rng, L, n, H, H, d, d, "bf16")
     gate = wl.to_f32(st.gate).copy()
     beta = wl.to_f32(st.beta).copy()

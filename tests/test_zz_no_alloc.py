@@ -72,7 +72,7 @@ def test_static_entry_point_rejects_what_it_cannot_serve():
     call, pool = _case(8103, 2, 70)
     g = GpuCall(call, pool)
     c = call
-    bad = B.make_shape(c.L, c.H_qk, c.H_v, 64, 64, "bf16", "f32", g.shape.T_alloc)          # a shape without a fused kernel
+    bad = B.make_shape(c.L, c.H_qk, c.H_v, 128, 128, "f32", "f32", g.shape.T_alloc)         # fp32 inputs: no fused kernel
     with pytest.raises(B.GdnError) as ei:
         B.gdn_resume_prefill_static(bad, g.q, g.k, g.v, g.beta, g.gate, c.cu_seqlens, c.start_pos, g.pool, c.src_slot,
                                     c.emit_cu, c.emit_pos, g.pool, c.emit_slot, g.o)
