@@ -7,8 +7,9 @@
 //   0: 128 x 128 x 64, 2 stages, four waves, two workgroups per compute unit   small problems (more, smaller workgroups)
 //   1: 256 x 256 x 32, 4 stages, four waves, one workgroup per compute unit: a wave holds 128 x 128 outputs in 256
 //      accumulator registers: half the operand bytes per flop, from memory and from LDS, three k steps of loads in flight
-//   2: the same tile with eight waves of 128 tokens x 64 outputs, two per SIMD: while one wave of a SIMD is held up issuing
-//      its loads to LDS the other feeds the matrix pipe (the default for large problems; 1 is kept for comparison)
+//   2: 256 x 256 x 64, 2 stages, eight waves of 128 tokens x 64 outputs, two per SIMD: while one wave of a SIMD is held up
+//      issuing its loads to LDS the other feeds the matrix pipe, and a barrier covers 64 of k (the default for large
+//      problems; 1 is kept for comparison)
 // A load to LDS writes a wave's 1 KiB contiguously (lane i at 16 i), so rows are unpadded (2 BK bytes) and bank
 // conflicts are avoided by choosing WHICH 16-byte piece of its row a lane fetches: piece p of row r is stored at
 // position p ^ swz(r), swz(r) = (r / rows per 256 bytes) % pieces per row, which makes the 16 lanes that read the
@@ -81,7 +82,7 @@ struct LinCfg {
 };
 typedef LinCfg<128, 128, 64, 2, 2, 2, 2> LinSmall;
 typedef LinCfg<256, 256, 32, 4, 1, 2, 2> LinBig;      // four waves, 128 x 128 outputs each
-typedef LinCfg<256, 256, 32, 4, 1, 2, 4> LinBig8;     // eight waves, 128 tokens x 64 outputs each: two waves per SIMD
+typedef LinCfg<256, 256, 64, 2, 1, 2, 4> LinBig8;     // eight waves, 128 tokens x 64 outputs each: two waves per SIMD
 
 // The loads of one wave for one stage: 1 KiB each, XL of its quarter of the x tile, then WL of the w tile.
 template <typename CFG>
@@ -352,7 +353,7 @@ int choose_linear_shape(int64_t T, int32_t N) {
     const int forced = g_linear_shape.load();
     if (forced >= 0) return forced;
     const double cus = (double)chip_cus_linear();
-    const struct { int id, bm, bn, per_cu; double rate; } shapes[2] = {{0, 128, 128, 2, 0.40}, {2, 256, 256, 1, 0.44}};
+    const struct { int id, bm, bn, per_cu; double rate; } shapes[2] = {{0, 128, 128, 2, 0.34}, {2, 256, 256, 1, 0.53}};
     int best = 0;
     double best_t = 0;
     for (int i = 0; i < 2; ++i) {
