@@ -203,6 +203,39 @@ def bench_config4(args, torch, B, dev):
         }
     del step
     torch.cuda.empty_cache()
+
+    # ---- the same recipe with grouped value heads: 8 query/key heads under the 16 value heads.  Two value heads of a query/key
+    #      head then share a workgroup of eight waves that reads and stages their q and k rows once (the library's choice for
+    #      a call of this size; gdn_tune_fused_pair switches it off for the comparison).
+    try:
+        gv = config4_device(seed=1044, H_qk=8, n_slots=2048)
+        th_g = gv.T * gv.L * gv.H
+        moves_g = (gv.n_req + gv.n_emit) * gv.L * gv.H
+        res = {}
+        for name, pair, per_th in (("one_head_per_workgroup", 0, BYTES_TOKEN_HEAD), ("two_heads_per_workgroup", 1, BYTES_TOKEN_HEAD - 2 * 128)):
+            prev = B.gdn_tune_fused_pair(pair)
+            try:
+                for _ in range(2):
+                    gv.run()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(5):
+                    gv.run()
+                torch.cuda.synchronize()
+            finally:
+                B.gdn_tune_fused_pair(prev)
+            msg = 1e3 * (time.perf_counter() - t0) / 5
+            bts = th_g * per_th + moves_g * STATE_BYTES
+            res[name] = {"ms_per_step": msg, "tokens_per_s": gv.T / (msg * 1e-3), "algorithmic_bytes": bts,
+                         "bytes_per_token_head": per_th, "achieved_gbs": bts / (msg * 1e-3) / 1e9,
+                         "frac_of_hbm_peak": bts / (msg * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        res["note"] = ("configs[4]'s recipe with H_qk = 8, H_v = 16; whole call on the host clock; with two heads per workgroup "
+                       "a q and a k row (256 bytes each) are read once per pair of value heads")
+        out["grouped_value_heads"] = res
+        del gv
+        torch.cuda.empty_cache()
+    except Exception as exc:
+        out["grouped_value_heads"] = {"error": str(exc)}
     return out, cpu
 
 

@@ -25,7 +25,12 @@
 // D / 16 accumulator tiles over d_k); the state products of block row a + 1 are issued ahead of block row a's
 // substitution.  Three barriers per chunk.
 //
-// LDS (FusedSmem<D>: 73 KB at D = 128, two workgroups per compute unit; 49 KB at D = 64, three):
+// Grouped value heads (GV = 2): two value heads of one query/key head in a workgroup of eight waves, four per head as
+// above.  K and Q are fetched (waves 0-3: K, waves 4-7: Q), converted and held in LDS once for both; each head has its own
+// V tile, pair tiles, gate vectors and state, and its arithmetic is that of the one-head kernel instruction for instruction.
+// The barriers span all eight waves.
+//
+// LDS (FusedSmem<D, GV>: 73 KB at D = 128, two workgroups per compute unit; 49 KB at D = 64, three; a pair 113 KB / 81 KB, one):
 //   K, Q, V  fp16 [64][D], rows unpadded, the 16-byte pieces of a row XOR-swizzled with the row number (swz):
 //            row reads (lane = token, one piece: the A/B operand of a product over d_k) are free of bank
 //            conflicts, transposing reads (ds_read_b64_tr_b16: lane = column, four tokens: K^T for the state
@@ -64,23 +69,28 @@ struct FusedArgs {
     int32_t o_bf16;
 };
 
-template <int D_>
+// GV value heads of one query/key head share a workgroup (GV x 4 waves) and its K and Q tiles; everything that depends on
+// the value head (V, the pair tiles, Tf, the gate vectors) exists once per head, HEAD_BYTES apart.
+template <int D_, int GV_ = 1>
 struct FusedSmem {
-    static constexpr int C = 64, D = D_;
+    static constexpr int C = 64, D = D_, GV = GV_;
     static constexpr int TILE_BYTES = C * D * 2;            // one of K, Q, V
     static constexpr int PAIR_LD = 40, TF_LD = 20;          // halfs / floats per row
     static constexpr int PAIR_BYTES = 16 * PAIR_LD * 2;     // one 16 x (2 x 16) fp16 pair tile
     static constexpr int K_OFF = 0;
     static constexpr int Q_OFF = K_OFF + TILE_BYTES;
-    static constexpr int V_OFF = Q_OFF + TILE_BYTES;
-    static constexpr int TBTG_OFF = V_OFF + TILE_BYTES;      // pair tile a: [T_aa diag(b) | -T_aa diag(b gam)]
+    static constexpr int V_OFF = Q_OFF + TILE_BYTES;         // V of head h at V_OFF + h TILE_BYTES
+    static constexpr int HEAD_OFF = V_OFF + GV * TILE_BYTES; // the per-head part of head h at HEAD_OFF + h HEAD_BYTES, offsets inside it:
+    static constexpr int TBTG_OFF = 0;                       // pair tile a: [T_aa diag(b) | -T_aa diag(b gam)]
     static constexpr int M_OFF = TBTG_OFF + 4 * PAIR_BYTES;  // pair tiles (1: M10,0) (2: M20,M21) (3: M30,M31) (3: M32,0)
     static constexpr int P_OFF = M_OFF + 4 * PAIR_BYTES;     // pair tiles (0: P00,0) (1: P10,P11) (2: P20,P21) (2: P22,0) (3: P30,P31) (3: P32,P33)
     static constexpr int TF_OFF = P_OFF + 6 * PAIR_BYTES;
     static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
-    static constexpr int BYTES = SM_OFF + 8 * C * 4;         // g, b, gam, dec, s, 3 x r
-    static_assert(TBTG_OFF % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
-    static_assert(BYTES <= 80 * 1024, "two workgroups per compute unit");
+    static constexpr int HEAD_BYTES = SM_OFF + 8 * C * 4;    // g, b, gam, dec, s, 3 x r
+    static constexpr int BYTES = HEAD_OFF + GV * HEAD_BYTES;
+    static_assert(HEAD_OFF % 16 == 0 && HEAD_BYTES % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
+    static_assert(GV == 1 || GV == 2, "one head or a pair");
+    static_assert(GV == 2 ? BYTES <= 160 * 1024 : BYTES <= 80 * 1024, "a pair has a compute unit to itself; two single-head workgroups share one");
     // pair tile index of block (a, c) of M (c < a) and of P (c <= a)
     static constexpr __host__ __device__ int m_pair(int a, int c) { return (a == 1 ? 0 : a == 2 ? 1 : 2) + (c >> 1); }
     static constexpr __host__ __device__ int p_pair(int a, int c) { return (a == 0 ? 0 : a == 1 ? 1 : a == 2 ? 2 : 4) + (c >> 1); }
@@ -143,7 +153,7 @@ __device__ __forceinline__ f32x4 inv16_tiles(const f32x4& d, const f32x4& dt, in
 __device__ unsigned long long g_phase_ts[64 * 4 * 16];
 #define GDN_PHASE(k_)                                                                                   \
     do {                                                                                                \
-        if (gdn_item == 40 && (blockIdx.x & 7) == 0 && blockIdx.x < 512 && lane_ == 0)                   \
+        if (gdn_item == 40 && (blockIdx.x & 7) == 0 && blockIdx.x < 512 && lane_ == 0 && hsel == 0)     \
             g_phase_ts[((blockIdx.x >> 3) * 4 + wave) * 16 + (k_)] = __builtin_readcyclecounter();      \
     } while (0)
 #define GDN_PHASE_ITEM() (++gdn_item)
@@ -152,12 +162,12 @@ __device__ unsigned long long g_phase_ts[64 * 4 * 16];
 #define GDN_PHASE_ITEM() ((void)0)
 #endif
 
-template <bool O_BF16, int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D == 128 ? 2 : 3))) gdn_fused_kernel(FusedArgs a) {
+template <bool O_BF16, int D, int GV>
+__global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2, (D == 128 || GV == 2) ? 2 : 3))) gdn_fused_kernel(FusedArgs a) {
     typedef Elem<half_t> EL;
     typedef EL::In In;
     typedef EL::Raw8 Raw8;
-    typedef FusedSmem<D> SM;
+    typedef FusedSmem<D, GV> SM;
     constexpr int C = 64, DK = D, DV = D, PLD = SM::PAIR_LD;
     constexpr int NT = D / 64;        // 16-column tiles of the state per wave (a wave owns D / 4 columns of d_v)
     constexpr int SS = D / 32;        // steps of 32 over d_k (one 16-byte piece per lane and step)
@@ -167,35 +177,41 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D =
     constexpr int ROWS = D / 32;      // rows of each tensor a thread stages (256 threads, 64 rows of PCS pieces)
     constexpr int WC = D / 4;         // d_v columns per wave
 
+    // A workgroup is GV groups of four waves, group hsel on value head hsel of the workgroup's GV heads (which share a
+    // query/key head: the host sees to that); wave = the wave's number inside its group.
+    const int tid = threadIdx.x & 255;
+    const int lane_ = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
+    const int hsel = GV == 1 ? 0 : __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8);
+
     extern __shared__ __align__(16) char smem[];
     char* const Kt = smem + SM::K_OFF;
     char* const Qt = smem + SM::Q_OFF;
-    char* const Vt = smem + SM::V_OFF;
-    half_t* const tbtg = reinterpret_cast<half_t*>(smem + SM::TBTG_OFF);
-    half_t* const mimg = reinterpret_cast<half_t*>(smem + SM::M_OFF);
-    half_t* const pimg = reinterpret_cast<half_t*>(smem + SM::P_OFF);
-    float* const gS = reinterpret_cast<float*>(smem + SM::SM_OFF);
+    char* const Vt = smem + SM::V_OFF + hsel * SM::TILE_BYTES;
+    char* const hsm = smem + SM::HEAD_OFF + hsel * SM::HEAD_BYTES;
+    half_t* const tbtg = reinterpret_cast<half_t*>(hsm + SM::TBTG_OFF);
+    half_t* const mimg = reinterpret_cast<half_t*>(hsm + SM::M_OFF);
+    half_t* const pimg = reinterpret_cast<half_t*>(hsm + SM::P_OFF);
+    float* const gS = reinterpret_cast<float*>(hsm + SM::SM_OFF);
     float* const bS = gS + C;
     float* const gamS = bS + C;
     float* const decS = gamS + C;
     float* const sS = decS + C;      // s_j = exp(g_end(block of j) - g_j)
     float* const rS = sS + C;        // [3][64]: r_i(c) = exp(g_i - g_end(c)), c = 0..2, for tokens i of later blocks
 
-    const int tid = threadIdx.x;
-    const int lane_ = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction: say so
-    float* const Tf = reinterpret_cast<float*>(smem + SM::TF_OFF) + wave * 16 * SM::TF_LD;
-    const int units = a.L * a.H_v;
+    float* const Tf = reinterpret_cast<float*>(hsm + SM::TF_OFF) + wave * 16 * SM::TF_LD;
+    const int units = a.L * a.H_v / GV;     // chains of a request: one per layer and group of GV value heads
     const In* const qg = reinterpret_cast<const In*>(a.q);
     const In* const kg = reinterpret_cast<const In*>(a.k);
     const In* const vg = reinterpret_cast<const In*>(a.v);
 
-    // A thread owns ROWS-token x 8-column blocks of K, Q and V (256 blocks each).
+    // A thread owns ROWS-token x 8-column blocks (256 blocks per tensor): of K, Q and V when the workgroup has one head; of
+    // its head's V and of one of the shared tensors (group 0: K, group 1: Q) when it has two.
     const int tg_ = tid / PCS, d0_ = (tid % PCS) * 8;
 
     // The unused halves of the pair tiles (a lone block is paired with zeros) are zeroed once; nothing writes them later.
     for (int i = tid; i < (SM::TF_OFF - SM::TBTG_OFF) / 16; i += 256)
-        reinterpret_cast<u32x4*>(smem + SM::TBTG_OFF)[i] = u32x4{0u, 0u, 0u, 0u};
+        reinterpret_cast<u32x4*>(hsm + SM::TBTG_OFF)[i] = u32x4{0u, 0u, 0u, 0u};
 
     // ---- the workgroup's items: the chunks of one chain per round of gridDim.x chains.  The chains come longest first,
     //      so the rounds are dealt in alternating directions (workgroup b takes chain b of an even round and chain
@@ -214,7 +230,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D =
             if (round * G >= a.n_chains) return it;     // no round left
             if (it.chain < 0) continue;                 // the last, partial round dealt downwards may still hold a chain for b: none here
             const int r = plan_word(a.req_order, chain / units);
-            it.lh = chain % units;
+            it.lh = (chain % units) * GV + hsel;
             it.c = plan_word(a.req_chunk_cu, r);
             it.c_end = plan_word(a.req_chunk_cu, r + 1);
             if (it.c < it.c_end) break;
@@ -236,7 +252,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D =
         return open_chain(cur.round + 1);
     };
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
-    Raw8 kraw[ROWS], qraw[ROWS], vraw[ROWS];
+    Raw8 kraw[ROWS], qraw[ROWS], vraw[ROWS];   // two heads: kraw holds the group's shared tensor, qraw is unused
     In graw = In();      // wave 0: the lane's gate; wave 1: its beta
     auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
         const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
@@ -244,14 +260,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D =
         // Buffer loads: a wave-uniform descriptor per tensor that starts at the chunk's first row of this head and ends with
         // its last row (rows past n read as zeros, no branch), 32-bit per-lane offsets.  Read once, never again: non-temporal.
         const int qk_step = a.H_qk * DK * 2, v_step = a.H_v * DV * 2;      // bytes from token to token
-        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(kg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
+        const In* const kg_ = (GV == 2 && hsel == 1) ? qg : kg;          // the group's shared tensor
+        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(kg_ + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
         const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(qg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
         const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(vg + (row0 * a.H_v + hv) * DV), 0, (it.n - 1) * v_step + DV * 2, 0x00020000);
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             const int i = ROWS * tg + r;
             kraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rk, i * qk_step + d0 * 2, 0, 2));
-            qraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, i * qk_step + d0 * 2, 0, 2));
+            if (GV == 1) qraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, i * qk_step + d0 * 2, 0, 2));
             vraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rv, i * v_step + d0 * 2, 0, 2));
         }
         // The 64 gates are read by wave 0 and the 64 betas by wave 1 only: a lane per token, 2 bytes each at a stride of a
@@ -352,19 +369,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, D =
             bS[lane] = lane < n ? EL::widen(graw) : 0.f;
         }
         // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
+        char* const Kt_ = (GV == 2 && hsel == 1) ? Qt : Kt;     // where the group's shared tensor goes
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             const int i = ROWS * tg + r;
             const int off = i * RBY + (((d0 >> 3) ^ swz<D>(i)) << 4);
             float kv[8], qv[8], vv[8];
             EL::unpack(kraw[r], kv);
-            EL::unpack(qraw[r], qv);
+            if (GV == 1) EL::unpack(qraw[r], qv);
             EL::unpack(vraw[r], vv);
             half8 kh, qh, vh;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { kh[e] = (half_t)kv[e]; qh[e] = (half_t)qv[e]; vh[e] = (half_t)vv[e]; }
-            *reinterpret_cast<half8*>(Kt + off) = kh;
-            *reinterpret_cast<half8*>(Qt + off) = qh;
+            for (int e = 0; e < 8; ++e) { kh[e] = (half_t)kv[e]; vh[e] = (half_t)vv[e]; }
+            *reinterpret_cast<half8*>(Kt_ + off) = kh;
+            if (GV == 1) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qh[e] = (half_t)qv[e];
+                *reinterpret_cast<half8*>(Qt + off) = qh;
+            }
             *reinterpret_cast<half8*>(Vt + off) = vh;
         }
         GDN_PHASE(1);

@@ -382,30 +382,53 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
 }
 
 // Fused throughput kernel (bf16 inputs, d_k = d_v = 64 or 128): see gdn_fused_kernel.h.
-template <bool O_BF16, int D>
+template <bool O_BF16, int D, int GV>
 hipError_t launch_fused_t(const FusedArgs& fa, hipStream_t stream) {
-    typedef FusedSmem<D> SM;
+    typedef FusedSmem<D, GV> SM;
     static std::once_flag once;
     static hipError_t once_err = hipSuccess;
     static int slots = 1;
     std::call_once(once, [] {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16, D, GV>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
         int dev = 0, cus = 0, per_cu = 0;
         if (e == hipSuccess) e = hipGetDevice(&dev);
         if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16, D>, 256, SM::BYTES);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16, D, GV>, 256 * GV, SM::BYTES);
         once_err = e;
         if (e == hipSuccess) slots = std::max(1, cus * per_cu);
     });
     if (once_err != hipSuccess) return once_err;
-    hipLaunchKernelGGL((gdn_fused_kernel<O_BF16, D>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256), SM::BYTES,
-                       stream, fa);
+    hipLaunchKernelGGL((gdn_fused_kernel<O_BF16, D, GV>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256 * GV),
+                       SM::BYTES, stream, fa);
     return hipGetLastError();
 }
-hipError_t launch_fused(const FusedArgs& fa, int d, hipStream_t stream) {
-    if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64>(fa, stream) : launch_fused_t<false, 64>(fa, stream);
-    return fa.o_bf16 ? launch_fused_t<true, 128>(fa, stream) : launch_fused_t<false, 128>(fa, stream);
+// gv = value heads per workgroup (1, or 2 when the heads of a pair share a query/key head); fa.n_chains counts groups of gv heads.
+hipError_t launch_fused(const FusedArgs& fa, int d, int gv, hipStream_t stream) {
+    if (gv == 2) {
+        if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 2>(fa, stream) : launch_fused_t<false, 64, 2>(fa, stream);
+        return fa.o_bf16 ? launch_fused_t<true, 128, 2>(fa, stream) : launch_fused_t<false, 128, 2>(fa, stream);
+    }
+    if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 1>(fa, stream) : launch_fused_t<false, 64, 1>(fa, stream);
+    return fa.o_bf16 ? launch_fused_t<true, 128, 1>(fa, stream) : launch_fused_t<false, 128, 1>(fa, stream);
+}
+
+// Grouped value heads (H_v a multiple of H_qk): two value heads of one query/key head can share a workgroup of eight waves,
+// which then reads and stages that head's q and k rows once for both (a fifth of a call's bytes with fp32 outputs).  It
+// needs an even group size.  The eight waves move in step, where two workgroups of four on a compute unit overlap each
+// other's phases, so a chunk of a chain takes longer (8.2 against 7.7 us at d = 128) and only calls bound by their
+// volume gain.  Measured at d = 128, 8 query/key heads under 16 value heads, pairs against single heads: 32768 chains of
+// up to 126 chunks 16.3 against 18.2 ms; 8192 chains 4.25 against 4.74; 4096 chains 2.29 against 2.32; 2048 chains 1.36
+// either way; 2048 chains of up to 32 chunks 0.47 against 0.44; 1024 chains of up to 320 chunks 2.66 against 2.50.  At
+// d = 64 a pair's 81 KB of LDS leave a compute unit one workgroup where three single-head ones fit, and pairs never won
+// (9.47 against 9.56 ms on 32768 chains, 1.39 against 1.17 on 4096): forced only.  gdn_tune_fused_pair forces the choice.
+std::atomic<int32_t> g_forced_pair{-1};
+inline int fused_heads_per_wg(const gdn_shape& s, int64_t total_units, int32_t longest_chain_chunks) {
+    if (s.H_qk <= 0 || s.H_v % s.H_qk != 0 || (s.H_v / s.H_qk) % 2 != 0) return 1;
+    const int forced = g_forced_pair.load();
+    if (forced >= 0) return forced != 0 ? 2 : 1;
+    if (s.d_k != 128) return 1;
+    return 0.0197 * (double)total_units >= 2.0 * 8.2 * (double)longest_chain_chunks ? 2 : 1;
 }
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
@@ -589,6 +612,10 @@ extern "C" int32_t gdn_phase_stamps(unsigned long long* out) {
 
 int32_t gdn_tune_fused(int32_t mode) {
     return g_forced_fused.exchange(mode < 0 ? -1 : (mode != 0));
+}
+
+int32_t gdn_tune_fused_pair(int32_t mode) {
+    return g_forced_pair.exchange(mode < 0 ? -1 : (mode != 0));
 }
 
 int32_t gdn_tune_slab_rounds(int32_t rounds) {
@@ -964,13 +991,14 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         fa.req_chunk_cu = ra.req_chunk_cu; fa.req_src_slot = ra.req_src_slot; fa.req_order = ra.req_order;
         fa.state_src = ra.state_src; fa.state_dst = state_dst;   // (the staging area when the pool is on the host)
         fa.src_slot_stride = ra.src_slot_stride; fa.dst_slot_stride = dst_slot_stride;
-        fa.n_chains = (int32_t)((int64_t)n_req * s.L * s.H_v);
+        const int gv = fused_heads_per_wg(s, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
+        fa.n_chains = (int32_t)((int64_t)n_req * s.L * s.H_v / gv);
         fa.L = s.L; fa.H_qk = s.H_qk; fa.H_v = s.H_v;
         fa.T_alloc = s.T_alloc;
         fa.scale = s.scale;
         fa.o_bf16 = s.o_dtype == GDN_BF16;
         ProfChain prof(stream);
-        const hipError_t e = launch_fused(fa, s.d_k, stream);
+        const hipError_t e = launch_fused(fa, s.d_k, gv, stream);
         if (e != hipSuccess) return hip_err(e);
         prof.mark(1);
         std::lock_guard<std::mutex> lock(g_prof.mu);

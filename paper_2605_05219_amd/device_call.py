@@ -89,6 +89,7 @@ class ServingStep:
     o: object
     shape: object
     workspace: object
+    H_qk: int = 0          # query/key heads when value heads are grouped (0: as many as value heads)
 
     @property
     def n_req(self) -> int:
@@ -115,18 +116,19 @@ class ServingStep:
         e0, e1 = int(self.emit_cu[r]), int(self.emit_cu[r + 1])
         bits = lambda t: t[layers, lo:hi].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
         st = wl.Streams(bits(self.q), bits(self.k), bits(self.v), bits(self.beta), bits(self.gate))
-        return wl.pack_call(len(layers), self.H, self.H, self.d, self.d, "bf16", [st], [int(self.start_pos[r])],
+        return wl.pack_call(len(layers), self.H_qk or self.H, self.H, self.d, self.d, "bf16", [st], [int(self.start_pos[r])],
                             [int(self.src_slot[r])], [list(self.emit_pos[e0:e1])], [list(self.emit_slot[e0:e1])],
                             self.n_slots)
 
 
 def config4_device(seed: int = 1004, n_req: int = 256, L: int = 8, H: int = 16, d: int = 128, n_slots: int = 4096,
                    lo: int = 64, hi: int = 8192, emit_step: int = 1024, o_dtype: str = "f32",
-                   pool_scale: float = 0.1) -> ServingStep:
+                   pool_scale: float = 0.1, H_qk: int = 0) -> ServingStep:
     """Draws the serving step on the current device.  Recipe of the configs: q, k ~ N(0,1) L2-normalised per head
     (fp32, then rounded to bf16), v ~ N(0,1), beta = sigmoid(N(0,1)), gate = exp(-softplus(N(0,1))); suffix lengths
     log-uniform in [lo, hi]; start positions multiples of 128; pool entries N(0, pool_scale^2) (any state is a valid
-    resume point); source slots n_req distinct ids, destination slots fresh distinct ids."""
+    resume point); source slots n_req distinct ids, destination slots fresh distinct ids.  H_qk > 0 gives the H value
+    heads H_qk query/key heads to share (grouped value heads)."""
     import torch
     dev = torch.device("cuda")
     rng = np.random.default_rng(seed)
@@ -151,11 +153,12 @@ def config4_device(seed: int = 1004, n_req: int = 256, L: int = 8, H: int = 16, 
     g = torch.Generator(device=dev)
     g.manual_seed(seed)
     rn = lambda *sh: torch.randn(sh, device=dev, generator=g, dtype=torch.float32)
-    q = torch.empty((L, T, H, d), dtype=torch.bfloat16, device=dev)
-    k, v = torch.empty_like(q), torch.empty_like(q)
+    Hq = H_qk or H
+    q = torch.empty((L, T, Hq, d), dtype=torch.bfloat16, device=dev)
+    k, v = torch.empty_like(q), torch.empty((L, T, H, d), dtype=torch.bfloat16, device=dev)
     for l in range(L):
-        q[l] = torch.nn.functional.normalize(rn(T, H, d), dim=-1).bfloat16()
-        k[l] = torch.nn.functional.normalize(rn(T, H, d), dim=-1).bfloat16()
+        q[l] = torch.nn.functional.normalize(rn(T, Hq, d), dim=-1).bfloat16()
+        k[l] = torch.nn.functional.normalize(rn(T, Hq, d), dim=-1).bfloat16()
         v[l] = rn(T, H, d).bfloat16()
     beta = torch.sigmoid(rn(L, T, H)).bfloat16()
     gate = torch.exp(-torch.nn.functional.softplus(rn(L, T, H))).bfloat16()
@@ -165,8 +168,8 @@ def config4_device(seed: int = 1004, n_req: int = 256, L: int = 8, H: int = 16, 
         n = min(step, n_slots - s0)
         pool[s0:s0 + n] = rn(n, L, H, d, d) * pool_scale
     o = torch.full((L, T, H, d), float("nan"), dtype=torch.float32 if o_dtype == "f32" else torch.bfloat16, device=dev)
-    shape = binding.make_shape(L, H, H, d, d, "bf16", o_dtype, T)
+    shape = binding.make_shape(L, Hq, H, d, d, "bf16", o_dtype, T)
     # the plan-only workspace: the call runs the fused kernel (the library's own choice for a call of this size)
     ws = torch.empty(max(256, binding.gdn_workspace_bytes_fused(shape, n_req, T, len(epos))), dtype=torch.uint8, device=dev)
     return ServingStep(L, H, d, n_slots, lens, cu, starts, ids[:n_req].astype(np.int32), np.asarray(ecu, np.int32),
-                       np.asarray(epos, np.int32), np.asarray(eslot, np.int32), q, k, v, beta, gate, pool, o, shape, ws)
+                       np.asarray(epos, np.int32), np.asarray(eslot, np.int32), q, k, v, beta, gate, pool, o, shape, ws, Hq)

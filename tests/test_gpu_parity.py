@@ -480,6 +480,28 @@ def test_config3_full_size_sampled_requests():
     check_call_sampled(sc.resume, pool, TOL["bf16"], sorted(set(short + sample_requests(sc.resume, 4, rng))))
 
 
+def compare_step_request(step, r, layers, start):
+    """Request r of a device-generated serving step, the given layers, every head: copied to the host, through the oracle
+    from the start state `start`, compared element by element (outputs, the first tokens after the resume point on their
+    own, every emitted state)."""
+    sub = step.host_request(r, layers)
+    one = np.ascontiguousarray(start[None])                                  # a one-slot pool for the oracle
+    o_ref, st_ref = orc.resume_prefill(*sub.streams.fields(), sub.cu_seqlens, sub.start_pos, [0], sub.emit_cu,
+                                       sub.emit_pos, state_src=one)
+    lo, hi = int(step.cu_seqlens[r]), int(step.cu_seqlens[r + 1])
+    o = step.o[layers, lo:hi].cpu().numpy()
+    err, where = worst_head_err(o, o_ref, [0, hi - lo])
+    assert err <= TOL["bf16"], f"request {r} ({hi - lo} tokens): o error {err:.3e} at (layer, head) {where[1:]}"
+    n16 = min(16, hi - lo)
+    err, where = worst_head_err(o[:, :n16], o_ref[:, :n16], [0, n16])
+    assert err <= TOL["bf16"], f"request {r}: o error {err:.3e} in the first tokens after the resume point"
+    for e, s in enumerate(sub.emit_slot):
+        got = step.pool[int(s)][layers].cpu().numpy()
+        err = worst_state_err(got, st_ref[e])
+        assert err <= TOL["bf16"], f"request {r}: emitted state {e} (slot {int(s)}) error {err:.3e}"
+    return sub.total_tokens
+
+
 def test_config4_full_size_sampled_against_the_oracle():
     """configs[4] as specified and as `bench.py` times it: 256 requests x 8 layers x 16 heads = 32768 chains in one
     fused launch (each workgroup walks about 64 chains one after the other), a 4096-slot pool of 32 GiB, inputs
@@ -514,30 +536,45 @@ def test_config4_full_size_sampled_against_the_oracle():
     assert np.array_equal(step.pool[watch].cpu().numpy(), watch_before)
     assert not torch.isnan(step.o).any(), "an output row was never written"
 
-    def compare(r, layers, start):
-        sub = step.host_request(r, layers)
-        one = np.ascontiguousarray(start[None])                                  # a one-slot pool for the oracle
-        o_ref, st_ref = orc.resume_prefill(*sub.streams.fields(), sub.cu_seqlens, sub.start_pos, [0], sub.emit_cu,
-                                           sub.emit_pos, state_src=one)
-        lo, hi = int(step.cu_seqlens[r]), int(step.cu_seqlens[r + 1])
-        o = step.o[layers, lo:hi].cpu().numpy()
-        err, where = worst_head_err(o, o_ref, [0, hi - lo])
-        assert err <= TOL["bf16"], f"request {r} ({hi - lo} tokens): o error {err:.3e} at (layer, head) {where[1:]}"
-        n16 = min(16, hi - lo)
-        err, where = worst_head_err(o[:, :n16], o_ref[:, :n16], [0, n16])
-        assert err <= TOL["bf16"], f"request {r}: o error {err:.3e} in the first tokens after the resume point"
-        for e, s in enumerate(sub.emit_slot):
-            got = step.pool[int(s)][layers].cpu().numpy()
-            err = worst_state_err(got, st_ref[e])
-            assert err <= TOL["bf16"], f"request {r}: emitted state {e} (slot {int(s)}) error {err:.3e}"
-        return sub.total_tokens
-
     all_layers = list(range(step.L))
     for r in sorted(picks):
-        compare(r, all_layers, start_states[r])
+        compare_step_request(step, r, all_layers, start_states[r])
     for r in range(step.n_req):
         if r not in picks:
-            compare(r, [0], start_l0[r][None])
+            compare_step_request(step, r, [0], start_l0[r][None])
+
+
+def test_grouped_heads_serving_step_pairs_chosen_by_the_library():
+    """A serving step of configs[4]'s recipe with 8 query/key heads under 16 value heads: 128 requests x 4 layers = 8192
+    chains, enough for the library to give two value heads of a query/key head one workgroup.  That choice is checked
+    against the oracle on sampled requests (every layer and head), and bit for bit, over the whole output and every pool
+    slot, against the same call with one head per workgroup."""
+    import torch
+    from paper_2605_05219_amd import binding as B
+    from paper_2605_05219_amd.device_call import config4_device
+    step = config4_device(seed=1044, n_req=128, L=4, n_slots=1024, H_qk=8)
+    rng = np.random.default_rng(4044)
+    picks = {int(np.argmax(step.lens)), int(np.argmin(step.lens))}
+    picks.update(int(x) for x in rng.choice(step.n_req, size=3, replace=False))
+    start_states = {r: step.pool[int(step.src_slot[r])].cpu().numpy() for r in picks}
+    pool_before = step.pool.clone()
+    step.run()                                   # the library's own choice
+    torch.cuda.synchronize()
+    assert not torch.isnan(step.o).any(), "an output row was never written"
+    for r in sorted(picks):
+        compare_step_request(step, r, list(range(step.L)), start_states[r])
+    o_auto, pool_auto = step.o.clone(), step.pool.clone()
+    for pair in (0, 1):
+        step.pool.copy_(pool_before)
+        step.o.fill_(float("nan"))
+        prev = B.gdn_tune_fused_pair(pair)
+        try:
+            step.run()
+            torch.cuda.synchronize()
+        finally:
+            B.gdn_tune_fused_pair(prev)
+        assert torch.equal(step.o.view(torch.int32), o_auto.view(torch.int32)), f"pair mode {pair}"
+        assert torch.equal(step.pool.view(torch.int32), pool_auto.view(torch.int32)), f"pair mode {pair}"
 
 
 # ------------------------------------------------------------------ host tier
@@ -641,15 +678,18 @@ def test_seeded_random_calls_match_the_oracle(many):
 
 
 @pytest.mark.gpu
-def test_seeded_random_calls_on_the_fused_kernel():
+@pytest.mark.parametrize("pair", [0, 1])
+def test_seeded_random_calls_on_the_fused_kernel(pair):
     """The fused kernel forced onto small seeded calls it would not be chosen for: both head sizes, one value head (an
-    output row is then exactly as long as the output descriptor's last row), grouped value heads, chunks of 1 to 64
-    tokens, requests of length 0, several layers, emits anywhere, both output types."""
+    output row is then exactly as long as the output descriptor's last row), grouped value heads (one head per workgroup,
+    and two heads of a query/key head per workgroup where the group size is even), chunks of 1 to 64 tokens, requests of
+    length 0, several layers, emits anywhere, both output types."""
     from paper_2605_05219_amd import binding as B
     rng = np.random.default_rng(9090)
     shapes = [(1, 1, 1, 128), (1, 1, 2, 128), (2, 1, 1, 64), (1, 2, 4, 128), (3, 2, 2, 64), (1, 4, 4, 128), (2, 2, 8, 64),
               (1, 1, 1, 64), (1, 16, 16, 64)]
     prev = B.gdn_tune_fused(1)
+    prev_pair = B.gdn_tune_fused_pair(pair)
     try:
         for it in range(18):
             L, H_qk, H_v, d = shapes[it % len(shapes)]
@@ -671,6 +711,40 @@ def test_seeded_random_calls_on_the_fused_kernel():
             check_call(call, pool, TOL["bf16"], o_dtype="bf16" if it % 2 else "f32")
     finally:
         B.gdn_tune_fused(prev)
+        B.gdn_tune_fused_pair(prev_pair)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,H_qk,H_v", [(128, 2, 8), (128, 3, 6), (64, 1, 4)])
+def test_head_pairs_in_one_workgroup_equal_single_heads_bitwise(d, H_qk, H_v):
+    """Two value heads of a query/key head in one workgroup share only the staged q and k rows: every head's arithmetic is
+    that of the one-head kernel, so outputs and stored states agree bit for bit (and the one-head kernel is compared with
+    the oracle)."""
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(4242 + d + H_v)
+    L, lens, starts = 2, [200, 64, 1, 333, 0, 129], [128, 0, 64, 0, 0, 256]
+    nxt, emits, eslots = 3, [], []
+    for s0, ln in zip(starts, lens):
+        e = sorted(set(int(x) for x in rng.integers(s0 + 1, s0 + ln + 1, 3))) if ln > 0 else []
+        emits.append(e)
+        eslots.append(list(range(nxt, nxt + len(e))))
+        nxt += len(e)
+    per_req = [wl.token_streams(rng, L, ln, H_qk, H_v, d, d, "bf16") for ln in lens]
+    src = [-1 if s0 == 0 else int(rng.integers(0, 3)) for s0 in starts]
+    call = wl.pack_call(L, H_qk, H_v, d, d, "bf16", per_req, starts, src, emits, eslots, nxt + 1)
+    pool = rng.standard_normal((nxt + 1,) + call.slot_shape).astype(np.float32) * 0.1
+    prev = B.gdn_tune_fused(1)
+    prev_pair = B.gdn_tune_fused_pair(0)
+    try:
+        check_call(call, pool, TOL["bf16"])
+        o1, p1 = run_call_gpu(call, pool)
+        B.gdn_tune_fused_pair(1)
+        o2, p2 = run_call_gpu(call, pool)
+    finally:
+        B.gdn_tune_fused(prev)
+        B.gdn_tune_fused_pair(prev_pair)
+    assert np.array_equal(o1.view(np.uint32), o2.view(np.uint32))
+    assert np.array_equal(p1.view(np.uint32), p2.view(np.uint32))
 
 
 @pytest.mark.gpu
