@@ -204,9 +204,15 @@ def bench_config4(args, torch, B, dev):
     del step
     torch.cuda.empty_cache()
 
-    # ---- the same recipe with grouped value heads: 8 query/key heads under the 16 value heads.  Two value heads of a query/key
-    #      head then share a workgroup of eight waves that reads and stages their q and k rows once (the library's choice for
-    #      a call of this size; gdn_tune_fused_pair switches it off for the comparison).
+    out["grouped_value_heads"] = bench_grouped_heads(torch, B)
+    return out, cpu
+
+
+def bench_grouped_heads(torch, B, reps: int = 5):
+    """configs[4]'s recipe with grouped value heads: 8 query/key heads under the 16 value heads.  Two value heads of a
+    query/key head then share a workgroup of eight waves that reads and stages their q and k rows once (the library's choice
+    for a call of this size; gdn_tune_fused_pair switches it off for the comparison)."""
+    from paper_2605_05219_amd.device_call import config4_device
     try:
         gv = config4_device(seed=1044, H_qk=8, n_slots=2048)
         th_g = gv.T * gv.L * gv.H
@@ -219,24 +225,23 @@ def bench_config4(args, torch, B, dev):
                     gv.run()
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
-                for _ in range(5):
+                for _ in range(reps):
                     gv.run()
                 torch.cuda.synchronize()
             finally:
                 B.gdn_tune_fused_pair(prev)
-            msg = 1e3 * (time.perf_counter() - t0) / 5
+            msg = 1e3 * (time.perf_counter() - t0) / reps
             bts = th_g * per_th + moves_g * STATE_BYTES
             res[name] = {"ms_per_step": msg, "tokens_per_s": gv.T / (msg * 1e-3), "algorithmic_bytes": bts,
                          "bytes_per_token_head": per_th, "achieved_gbs": bts / (msg * 1e-3) / 1e9,
-                         "frac_of_hbm_peak": bts / (msg * 1e-3) / 1e9 / PEAK_HBM_GBS}
-        res["note"] = ("configs[4]'s recipe with H_qk = 8, H_v = 16; whole call on the host clock; with two heads per workgroup "
-                       "a q and a k row (256 bytes each) are read once per pair of value heads")
-        out["grouped_value_heads"] = res
+                         "frac_of_hbm_peak": bts / (msg * 1e-3) / 1e9 / PEAK_HBM_GBS, "launches": reps + 2}
+        res["note"] = ("configs[4]'s recipe with H_qk = 8, H_v = 16 (seed 1044, 2048-slot pool); whole call on the host clock; "
+                       "with two heads per workgroup a q and a k row (256 bytes each) are read once per pair of value heads")
         del gv
         torch.cuda.empty_cache()
+        return res
     except Exception as exc:
-        out["grouped_value_heads"] = {"error": str(exc)}
-    return out, cpu
+        return {"error": str(exc)}
 
 
 def bench_ckpt_copy(torch, B, dev):
@@ -846,6 +851,9 @@ def main() -> int:
     ap.add_argument("--copy-only", action="store_true",
                     help="only the checkpoint pool copies (256 MiB read and written per launch: the known-size copy the "
                          "profiler's byte counters are calibrated on)")
+    ap.add_argument("--grouped-heads-only", action="store_true",
+                    help="only the grouped-value-heads side measurement (configs[4]'s recipe with 8 query/key heads; what "
+                         "the profiler runs of the two-heads-per-workgroup kernel use)")
     ap.add_argument("--phase-table", action="store_true",
                     help="run the configs[4] step on the profiling build of the library (python -m paper_2605_05219_amd.build "
                          "--phase-stamps) and print the fused kernel's clocks per phase of a chunk")
@@ -880,6 +888,9 @@ def main() -> int:
         return phase_table(torch, B)
     if args.copy_only:
         print(json.dumps({"ckpt_copy": bench_ckpt_copy(torch, B, dev)}))
+        return 0
+    if args.grouped_heads_only:
+        print(json.dumps({"grouped_value_heads": bench_grouped_heads(torch, B, reps=3)}))
         return 0
     if args.latency_only:
         lat, _, _, _ = bench_config1(args, torch, B, wl, dev)
