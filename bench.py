@@ -824,8 +824,9 @@ def phase_table(torch, B) -> int:
         return 1
     t = raw.reshape(64 * 4, 16).astype(np.int64)
     t = t[(t[:, 0] > 0) & (t[:, 9] > t[:, 0])]
-    names = ["stage K, Q, V and gates", "issue the next chunk's loads", "barrier after staging", "diagonal gram block and its inverse",
-             "L and P blocks", "barrier after preparation", "substitution and outputs", "state update", "emission"]
+    names = ["gates; stage K, Q, V, the next chunk's K loads in between", "the next chunk's gate loads", "barrier after staging",
+             "the next chunk's Q loads, diagonal gram block and its inverse", "the next chunk's V loads, L and P blocks",
+             "barrier after preparation", "substitution and outputs", "state update", "emission"]
     d = np.diff(t[:, :10], axis=1)
     print(json.dumps({"phase_table": {"workload": "configs[4] step, fused kernel, 40th item (a full 64-token chunk of a long chain) of every eighth workgroup",
                                       "waves_sampled": int(d.shape[0]), "unit": "shader clocks per wave",

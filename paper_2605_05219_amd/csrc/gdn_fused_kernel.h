@@ -23,7 +23,8 @@
 // their products with T_aa) and the P blocks of query block 3 - a, five 16x16 gram blocks each.  Recurrence:
 // wave w owns the D / 4 d_v columns of the state from (D / 4) w on (D / 64 16-column tiles, the state of a tile in
 // D / 16 accumulator tiles over d_k); the state products of block row a + 1 are issued ahead of block row a's
-// substitution.  Three barriers per chunk.
+// substitution.  Three barriers per chunk.  The rows of the next chunk are fetched into registers meanwhile, in three
+// instalments spread over the staging and the preparation (see the staging loop).
 //
 // Grouped value heads (GV = 2): two value heads of one query/key head in a workgroup of eight waves, four per head as
 // above.  K and Q are fetched (waves 0-3: K, waves 4-7: Q), converted and held in LDS once for both; each head has its own
@@ -254,34 +255,48 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[ROWS], qraw[ROWS], vraw[ROWS];   // two heads: kraw holds the group's shared tensor, qraw is unused
     In graw = In();      // wave 0: the lane's gate; wave 1: its beta
-    auto fetch = [&](const Item& it, int tg, int d0, int lane) {   // the thread's coordinates, opaque in the item loop
-        const int l = it.lh / a.H_v, hv = it.lh % a.H_v, hq = hv / (a.H_v / a.H_qk);
-        const int64_t row0 = (int64_t)l * a.T_alloc + it.tok0;
-        // Buffer loads: a wave-uniform descriptor per tensor that starts at the chunk's first row of this head and ends with
-        // its last row (rows past n read as zeros, no branch), 32-bit per-lane offsets.  Read once, never again: non-temporal.
-        const int qk_step = a.H_qk * DK * 2, v_step = a.H_v * DV * 2;      // bytes from token to token
-        const In* const kg_ = (GV == 2 && hsel == 1) ? qg : kg;          // the group's shared tensor
-        const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(kg_ + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(qg + (row0 * a.H_qk + hq) * DK), 0, (it.n - 1) * qk_step + DK * 2, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(vg + (row0 * a.H_v + hv) * DV), 0, (it.n - 1) * v_step + DV * 2, 0x00020000);
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            const int i = ROWS * tg + r;
-            kraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rk, i * qk_step + d0 * 2, 0, 2));
-            if (GV == 1) qraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, i * qk_step + d0 * 2, 0, 2));
-            vraw[r] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rv, i * v_step + d0 * 2, 0, 2));
-        }
-        // The 64 gates are read by wave 0 and the 64 betas by wave 1 only: a lane per token, 2 bytes each at a stride of a
-        // token's heads, is 64 separate memory requests per instruction.
-        if (lane < it.n && wave < 2) {
-            const int gi = lane * a.H_v;
-            graw = (reinterpret_cast<const In*>(wave == 0 ? a.gate : a.beta) + (row0 * a.H_v + hv))[gi];
-        }
-    };
+    // Buffer loads: a wave-uniform descriptor per tensor that starts at the chunk's first row of this head and ends with its
+    // last row (rows past n, and every row when there is no item, read as zeros, no branch), 32-bit per-lane offsets.  Read
+    // once, never again: non-temporal.  (Written out as macros: descriptors do not pass through lambdas on the host pass.)
+    const int qk_step = a.H_qk * DK * 2, v_step = a.H_v * DV * 2;      // bytes from token to token
+    const In* const kg_ = (GV == 2 && hsel == 1) ? qg : kg;            // the group's shared tensor
+#define GDN_FETCH_DESCRIPTORS(it_)                                                                                              \
+    const int f_l = (it_).lh / a.H_v, f_hv = (it_).lh % a.H_v, f_hq = f_hv / (a.H_v / a.H_qk);                                 \
+    const int64_t f_row0 = (int64_t)f_l * a.T_alloc + (it_).tok0;                                                               \
+    const bool f_on = (it_).chain >= 0;                                                                                         \
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(kg_ + (f_row0 * a.H_qk + f_hq) * DK), 0, \
+                                                                         f_on ? ((it_).n - 1) * qk_step + DK * 2 : 0, 0x00020000); \
+    const __amdgpu_buffer_rsrc_t rq = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(qg + (f_row0 * a.H_qk + f_hq) * DK), 0,  \
+                                                                         f_on ? ((it_).n - 1) * qk_step + DK * 2 : 0, 0x00020000); \
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<In*>(vg + (f_row0 * a.H_v + f_hv) * DV), 0,   \
+                                                                         f_on ? ((it_).n - 1) * v_step + DV * 2 : 0, 0x00020000)
+#define GDN_FETCH_K(r_, tg_v, d0_v) kraw[r_] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rk, (ROWS * (tg_v) + (r_)) * qk_step + (d0_v) * 2, 0, 2))
+#define GDN_FETCH_Q(r_, tg_v, d0_v) if (GV == 1) qraw[r_] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rq, (ROWS * (tg_v) + (r_)) * qk_step + (d0_v) * 2, 0, 2))
+#define GDN_FETCH_V(r_, tg_v, d0_v) vraw[r_] = __builtin_bit_cast(Raw8, __builtin_amdgcn_raw_buffer_load_b128(rv, (ROWS * (tg_v) + (r_)) * v_step + (d0_v) * 2, 0, 2))
+// All ROWS rows of one tensor, pinned where they stand: the compiler would otherwise gather the loads into one burst again.
+#define GDN_FETCH_ALL(which_, tg_v, d0_v)                                                                                        \
+    do {                                                                                                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                                      \
+        _Pragma("unroll") for (int r_ = 0; r_ < ROWS; ++r_) { which_(r_, tg_v, d0_v); }                                        \
+        __builtin_amdgcn_sched_barrier(0);                                                                                      \
+    } while (0)
+    // The 64 gates are read by wave 0 and the 64 betas by wave 1 only: a lane per token, 2 bytes each at a stride of a
+    // token's heads, is 64 separate memory requests per instruction.
+#define GDN_FETCH_GATES(it_, lane_v)                                                                                             \
+    do {                                                                                                                        \
+        if ((lane_v) < (it_).n && wave < 2 && f_on)                                                                             \
+            graw = (reinterpret_cast<const In*>(wave == 0 ? a.gate : a.beta) + (f_row0 * a.H_v + f_hv))[(lane_v) * a.H_v];      \
+    } while (0)
 
     Item cur = open_chain(0);
     if (cur.chain < 0) return;
-    fetch(cur, tg_, d0_, lane_);
+    {
+        GDN_FETCH_DESCRIPTORS(cur);
+        GDN_FETCH_ALL(GDN_FETCH_K, tg_, d0_);
+        GDN_FETCH_ALL(GDN_FETCH_Q, tg_, d0_);
+        GDN_FETCH_ALL(GDN_FETCH_V, tg_, d0_);
+        GDN_FETCH_GATES(cur, lane_);
+    }
     Item nxt = next_item(cur);
     wait_vmcnt<0>();   // the first item's inputs: inside the loop the fetched registers are then known to have landed on every path
 
@@ -369,7 +384,13 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
             bS[lane] = lane < n ? EL::widen(graw) : 0.f;
         }
         // ---- stage K, Q, V as fp16 (exact widening of bf16): one 16-byte piece per row and tensor, swizzled
+        //      The next item's rows are fetched in three instalments, each where the registers it overwrites are free and
+        //      spaced by a few thousand clocks of other work: K row by row between the conversions here (a row's registers are
+        //      free once it is converted), Q after the barrier below, V after the diagonal inverse.  Issued in one burst, the
+        //      workgroup's 56 load instructions queue in the compute unit's memory pipeline (about 16 clocks each, behind the
+        //      other workgroup's and the output stores) and every wave stands in the issue for one to two thousand clocks.
         char* const Kt_ = (GV == 2 && hsel == 1) ? Qt : Kt;     // where the group's shared tensor goes
+        GDN_FETCH_DESCRIPTORS(nxt);
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             const int i = ROWS * tg + r;
@@ -388,14 +409,18 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
                 *reinterpret_cast<half8*>(Qt + off) = qh;
             }
             *reinterpret_cast<half8*>(Vt + off) = vh;
+            __builtin_amdgcn_sched_barrier(0);
+            GDN_FETCH_K(r, tg, d0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         GDN_PHASE(1);
-        if (nxt.chain >= 0) fetch(nxt, tg, d0, lane);
+        GDN_FETCH_GATES(nxt, lane);
         GDN_PHASE(2);
         __syncthreads();
         GDN_PHASE(3);
 
         // operand over d_k columns 32 s + 8 g4 .. + 7 of row 16 blk + m of a tile
+        GDN_FETCH_ALL(GDN_FETCH_Q, tg, d0);
         auto row_frag = [&](const char* tile, int blk, int s) -> half8 {
             return *reinterpret_cast<const half8*>(tile + row_b[s] + blk * 16 * RBY);
         };
@@ -438,6 +463,7 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
                 *reinterpret_cast<half8*>(tbtg + (ab * 16 + m) * PLD + 8 * g4) = cat8(cvt4(tb), cvt4(tgm));
             }
             GDN_PHASE(4);
+            GDN_FETCH_ALL(GDN_FETCH_V, tg, d0);
             const float gq = gS[16 * ia + m];
             // key blocks c: left of the diagonal of block row ab, L_ac -> -(T_aa L_ac) stored by rows; up to query
             // block ia, P (rows j = keys in registers, lane = query i)
@@ -637,5 +663,12 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
         nxt = next_item(cur);
     }
 }
+
+#undef GDN_FETCH_DESCRIPTORS
+#undef GDN_FETCH_ALL
+#undef GDN_FETCH_K
+#undef GDN_FETCH_Q
+#undef GDN_FETCH_V
+#undef GDN_FETCH_GATES
 
 }  // namespace gdn
