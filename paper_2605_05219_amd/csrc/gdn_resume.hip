@@ -421,7 +421,8 @@ hipError_t launch_fused(const FusedArgs& fa, int d, int gv, hipStream_t stream) 
 // up to 126 chunks 16.3 against 18.2 ms; 8192 chains 4.25 against 4.74; 4096 chains 2.29 against 2.32; 2048 chains 1.36
 // either way; 2048 chains of up to 32 chunks 0.47 against 0.44; 1024 chains of up to 320 chunks 2.66 against 2.50.  At
 // d = 64 a pair's 81 KB of LDS leave a compute unit one workgroup where three single-head ones fit, and pairs never won
-// (9.47 against 9.56 ms on 32768 chains, 1.39 against 1.17 on 4096): forced only.  gdn_tune_fused_pair forces the choice.
+// (9.47 against 9.56 ms on 32768 chains, 1.39 against 1.17 on 4096): forced only.  (Both kernels have since gained
+// 2 to 5 % from one change to their loads; the ratios stand.)  gdn_tune_fused_pair forces the choice.
 std::atomic<int32_t> g_forced_pair{-1};
 inline int fused_heads_per_wg(const gdn_shape& s, int64_t total_units, int32_t longest_chain_chunks) {
     if (s.H_qk <= 0 || s.H_v % s.H_qk != 0 || (s.H_v / s.H_qk) % 2 != 0) return 1;
@@ -433,15 +434,16 @@ inline int fused_heads_per_wg(const gdn_shape& s, int64_t total_units, int32_t l
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
 // plentiful and the longest chain does not outlast the whole two-kernel run.  Estimates from
-// figures measured on MI355X (bf16; one call of 1 to 64 requests of up to 8192 tokens, and the
-// large configurations).  d = 128: fused, per chunk of one chain 5.9 us with one workgroup per
-// compute unit (up to 256 chains) and 7.7 us with two, per (chunk, chain) unit of a large call
-// 0.022 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured: 128 chains 0.77 ms
-// fused against 0.56 ms, 160 chains 0.77 against 0.82, 256 chains 0.82 against 1.22, 512 chains
-// 0.99 against 2.09, 1024 chains 1.67 against 3.98.  d = 64: 3.4 / 4.4 us per chunk, 0.0115 us
-// per unit; two-kernel path 0.036 us per unit plus about 0.1 ms (requests of up to 4096 tokens:
-// 128 chains 0.22 ms either way, 256 chains 0.26 against 0.39, 1024 chains 0.46 against 1.48).
-// gdn_tune_fused forces the choice.
+// figures measured on MI355X (bf16; one call of 4 to 64 requests of up to 8192 tokens, 16 heads,
+// and the large configurations).  d = 128: fused, per chunk of one chain 5.5 us with one workgroup
+// per compute unit (up to 256 chains) and 6.8 us with two, per (chunk, chain) unit of a large call
+// 0.0195 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured, fused against
+// two-kernel: 64 chains 0.60 against 0.40 ms, 96 chains 0.61 against 0.52, 128 chains 0.62 against
+// 0.63, 160 chains 0.70 against 0.85, 256 chains 0.70 against 1.14, 512 chains 0.87 against 2.04,
+// 1024 chains 1.49 against 4.17.  d = 64: 3.4 / 4.4 us per chunk, 0.0115 us per unit; two-kernel
+// path 0.036 us per unit plus about 0.1 ms (requests of up to 4096 tokens: 96 chains 0.21 against
+// 0.17 ms, 128 chains 0.21 against 0.22, 256 chains 0.25 against 0.39, 1024 chains 0.45 against
+// 1.48).  gdn_tune_fused forces the choice.
 std::atomic<int32_t> g_forced_fused{-1};
 inline bool fused_applies(const gdn_shape& s) { return s.in_dtype == GDN_BF16 && s.d_k == s.d_v && (s.d_k == 128 || s.d_k == 64); }
 inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_units, int32_t longest_chain_chunks) {
@@ -450,9 +452,9 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
     if (forced >= 0) return forced != 0;
     if (n_chains < 128) return false;
     const bool big = s.d_k == 128;
-    const double per_chunk = n_chains <= chip_cus() ? (big ? 5.9 : 3.4) : (big ? 7.7 : 4.4);   // us: one or two workgroups per compute unit
+    const double per_chunk = n_chains <= chip_cus() ? (big ? 5.5 : 3.4) : (big ? 6.8 : 4.4);   // us: one or two workgroups per compute unit
     const double t_two = (big ? 0.056 : 0.036) * (double)total_units + (big ? 150.0 : 100.0);
-    const double t_fused = std::max((big ? 0.022 : 0.0115) * (double)total_units, per_chunk * (double)longest_chain_chunks);
+    const double t_fused = std::max((big ? 0.0195 : 0.0115) * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
 }
 
