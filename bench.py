@@ -244,6 +244,42 @@ def bench_grouped_heads(torch, B, reps: int = 5):
         return {"error": str(exc)}
 
 
+def bench_other_configs(torch, B, wl, reps: int = 20):
+    """configs[2] and configs[3] as specified, one call each on the library's own choice of path (both take the fused
+    kernel), start states seeded random states; whole call on the host clock.  configs[3]: 32 value heads on 16 query/key
+    heads, bound by its longest chain."""
+    from paper_2605_05219_amd.device_call import GpuCall
+    out = {}
+    for name, mk in (("configs[2]", wl.config2), ("configs[3]", wl.config3)):
+        try:
+            sc = mk(B.gdn_deepest_ckpt)
+            call = sc.resume
+            rng = np.random.default_rng(2003)
+            pool = (rng.standard_normal((sc.n_slots,) + sc.build.slot_shape) * 0.3).astype(np.float32)
+            g = GpuCall(call, pool)
+            lens = np.diff(call.cu_seqlens)
+            for _ in range(3):
+                g.run()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                g.run()
+            torch.cuda.synchronize()
+            ms = 1e3 * (time.perf_counter() - t0) / reps
+            th = call.total_tokens * call.L * call.H_v
+            per_th = (2 * D * call.H_qk // call.H_v + D) * 2 + 2 * 2 + D * 4
+            out[name] = {"ms_per_call": ms, "tokens_per_s": call.total_tokens / (ms * 1e-3), "requests": call.n_req,
+                         "chains": call.n_req * call.L * call.H_v, "suffix_tokens": int(call.total_tokens),
+                         "longest_chain_chunks": int((lens.max() + C - 1) // C), "launches": reps + 3,
+                         "algorithmic_gbs": th * per_th / (ms * 1e-3) / 1e9,
+                         "us_per_chunk_of_the_longest_chain": 1e3 * ms / float((lens.max() + C - 1) // C)}
+            del g
+        except Exception as exc:
+            out[name] = {"error": repr(exc)}
+    torch.cuda.empty_cache()
+    return out
+
+
 def bench_ckpt_copy(torch, B, dev):
     """Standalone checkpoint pool copies (HBM bound): 256 states of 1 MiB gathered, then scattered."""
     out = {}
@@ -439,6 +475,7 @@ def side_measurements(args, torch, B, wl, dev, calls, pool, suffix, wall_cfg1_ms
         calls[i % N_DRAWS].run()
 
     out["ckpt_copy"] = bench_ckpt_copy(torch, B, dev)
+    out["other_configs"] = bench_other_configs(torch, B, wl)
 
     # ---- host tier (Sec. 6: loading the stored checkpoint from host memory is overhead (i) of a hit): the same
     #      draws with the checkpoint pool in pinned host memory, and the raw host -> HBM state copy rate
@@ -852,6 +889,8 @@ def main() -> int:
     ap.add_argument("--copy-only", action="store_true",
                     help="only the checkpoint pool copies (256 MiB read and written per launch: the known-size copy the "
                          "profiler's byte counters are calibrated on)")
+    ap.add_argument("--other-configs-only", action="store_true",
+                    help="only configs[2] and configs[3], one call each (side object `other_configs`; what their profiler run uses)")
     ap.add_argument("--grouped-heads-only", action="store_true",
                     help="only the grouped-value-heads side measurement (configs[4]'s recipe with 8 query/key heads; what "
                          "the profiler runs of the two-heads-per-workgroup kernel use)")
@@ -889,6 +928,9 @@ def main() -> int:
         return phase_table(torch, B)
     if args.copy_only:
         print(json.dumps({"ckpt_copy": bench_ckpt_copy(torch, B, dev)}))
+        return 0
+    if args.other_configs_only:
+        print(json.dumps({"other_configs": bench_other_configs(torch, B, wl)}))
         return 0
     if args.grouped_heads_only:
         print(json.dumps({"grouped_value_heads": bench_grouped_heads(torch, B, reps=3)}))

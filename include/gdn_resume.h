@@ -329,6 +329,15 @@ int32_t gdn_tune_fused(int32_t mode);
  */
 int32_t gdn_tune_fused_pair(int32_t mode);
 
+/*
+ * Tuning knob (not a step of the method).  How many workgroups of the fused kernel may share a
+ * compute unit: n >= 1 forces that number (more than fit means as many as fit), n < 1 restores
+ * the automatic choice (as many as fit, or one per compute unit when the call is bound by its
+ * longest chain: a chain's chunk takes less time on a compute unit of its own).  Outputs are
+ * bitwise the same for every setting.  Returns the previous setting (-1 = automatic).
+ */
+int32_t gdn_tune_fused_per_cu(int32_t n);
+
 /* Version of the library (major * 100 + minor). */
 int32_t gdn_version(void);
 

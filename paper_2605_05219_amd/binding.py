@@ -59,6 +59,8 @@ def lib():
         L.gdn_tune_fused.argtypes = [_i32]
         L.gdn_tune_fused_pair.restype = _i32
         L.gdn_tune_fused_pair.argtypes = [_i32]
+        L.gdn_tune_fused_per_cu.restype = _i32
+        L.gdn_tune_fused_per_cu.argtypes = [_i32]
         L.gdn_profile_enable.restype = _i32
         L.gdn_profile_enable.argtypes = [_i32]
         L.gdn_profile_collect.restype = _i32
@@ -100,7 +102,7 @@ def lib():
     return _lib
 
 
-EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_tune_fused_pair", "gdn_profile_enable", "gdn_profile_collect", "gdn_probe_ceilings", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
+EXPORTS = ["gdn_version", "gdn_tune_slab_rounds", "gdn_tune_fused", "gdn_tune_fused_pair", "gdn_tune_fused_per_cu", "gdn_profile_enable", "gdn_profile_collect", "gdn_probe_ceilings", "gdn_deepest_ckpt", "gdn_plan_chunks", "gdn_workspace_bytes",
            "gdn_workspace_bytes_fused",
            "ckpt_gather", "ckpt_scatter", "gdn_resume_prefill", "gdn_decode_step", "ckpt_fetch_host", "ckpt_spill_host",
            "gdn_workspace_bytes_host", "gdn_resume_prefill_host", "gdn_resume_prefill_static", "gdn_static_plan_capacity"]
@@ -154,6 +156,12 @@ def gdn_tune_fused_pair(mode: int) -> int:
     """Fused kernel with grouped value heads: 1: two heads of a query/key head per workgroup wherever the group size is
     even, 0: one head per workgroup, < 0: automatic; returns the previous setting."""
     return int(lib().gdn_tune_fused_pair(int(mode)))
+
+
+def gdn_tune_fused_per_cu(n: int) -> int:
+    """Workgroups of the fused kernel per compute unit: n >= 1 forces that number (capped at what fits), n < 1: automatic;
+    returns the previous setting."""
+    return int(lib().gdn_tune_fused_per_cu(int(n)))
 
 
 def gdn_profile_enable(on: bool) -> None:

@@ -60,6 +60,7 @@ struct FusedArgs {
     const int32_t* req_chunk_cu;
     const int32_t* req_src_slot;
     const int32_t* req_order;        // requests, longest chain first
+    int32_t* next_chain;             // one word, zero when the kernel starts: chains handed out beyond the first two rounds
     const float* state_src;
     float* state_dst;
     int64_t src_slot_stride, dst_slot_stride;
@@ -88,7 +89,8 @@ struct FusedSmem {
     static constexpr int TF_OFF = P_OFF + 6 * PAIR_BYTES;
     static constexpr int SM_OFF = TF_OFF + 4 * 16 * TF_LD * 4;
     static constexpr int HEAD_BYTES = SM_OFF + 8 * C * 4;    // g, b, gam, dec, s, 3 x r
-    static constexpr int BYTES = HEAD_OFF + GV * HEAD_BYTES;
+    static constexpr int RESERVE_OFF = HEAD_OFF + GV * HEAD_BYTES;   // one word: the chain the workgroup opens after the next one
+    static constexpr int BYTES = RESERVE_OFF + 16;
     static_assert(HEAD_OFF % 16 == 0 && HEAD_BYTES % 16 == 0 && M_OFF % 16 == 0 && P_OFF % 16 == 0 && TF_OFF % 16 == 0 && SM_OFF % 16 == 0, "alignment");
     static_assert(GV == 1 || GV == 2, "one head or a pair");
     static_assert(GV == 2 ? BYTES <= 160 * 1024 : BYTES <= 80 * 1024, "a pair has a compute unit to itself; two single-head workgroups share one");
@@ -214,28 +216,31 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
     for (int i = tid; i < (SM::TF_OFF - SM::TBTG_OFF) / 16; i += 256)
         reinterpret_cast<u32x4*>(hsm + SM::TBTG_OFF)[i] = u32x4{0u, 0u, 0u, 0u};
 
-    // ---- the workgroup's items: the chunks of one chain per round of gridDim.x chains.  The chains come longest first,
-    //      so the rounds are dealt in alternating directions (workgroup b takes chain b of an even round and chain
-    //      gridDim.x - 1 - b of an odd one): dealt one way only, workgroup 0 would get the longest chain of every round and
-    //      the last workgroup the shortest, and the sums would differ by the length of the longest chain.
-    struct Item { int chain, round, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
-    auto open_chain = [&](int round) -> Item {
+    // ---- the workgroup's items: the chunks of one chain after the other.  The chains come longest first (every one has
+    //      at least one chunk: requests without tokens are not among them).  Workgroup b starts with chain b and holds chain
+    //      2 gridDim.x - 1 - b in reserve (the second round dealt backwards: the longest chain of the first round is followed by
+    //      the shortest of the second); from then on a workgroup that opens its reserve draws a new one from a counter in memory
+    //      (2 gridDim.x + the counter's value: longest-first list scheduling, so a workgroup that drew short chains simply draws
+    //      more of them).  The draw is an atomic with a round trip to memory, so it is made a whole item before its result
+    //      can be needed: the first wave issues it when the reserve is opened, puts the result into LDS after the next wait
+    //      on its memory operations, and every wave picks it up behind the barrier at the top of the next item.  Which
+    //      workgroup runs a chain does not touch the chain's arithmetic: results are the same bit for bit whatever the draw.
+    struct Item { int chain, c, c_end, lh, tok0, n, eslot; };   // chain < 0: none; eslot: pool slot the chunk's end state goes to, or -1
+    int* const reserve_lds = reinterpret_cast<int*>(smem + SM::RESERVE_OFF);
+    int reserve = 2 * (int)gridDim.x - 1 - (int)blockIdx.x;   // the chain to open after the current one
+    bool reserve_stale = false;                       // opened: the next one is on its way through LDS
+    bool draw_pending = false;                        // first wave: an atomic is in flight
+    int drawn = 0;                                    // first wave, lane 0: its result
+    auto open_chain = [&](int chain) -> Item {
         Item it;
-        const int G = (int)gridDim.x, b = (int)blockIdx.x;
-        for (;; ++round) {
-            const int chain = round * G + ((round & 1) ? G - 1 - b : b);
-            it.chain = (round * G < a.n_chains && chain < a.n_chains) ? chain : -1;
-            it.round = round;
-            it.c = it.c_end = it.lh = it.tok0 = it.n = 0;
-            it.eslot = -1;
-            if (round * G >= a.n_chains) return it;     // no round left
-            if (it.chain < 0) continue;                 // the last, partial round dealt downwards may still hold a chain for b: none here
-            const int r = plan_word(a.req_order, chain / units);
-            it.lh = (chain % units) * GV + hsel;
-            it.c = plan_word(a.req_chunk_cu, r);
-            it.c_end = plan_word(a.req_chunk_cu, r + 1);
-            if (it.c < it.c_end) break;
-        }
+        it.chain = chain < a.n_chains ? chain : -1;
+        it.c = it.c_end = it.lh = it.tok0 = it.n = 0;
+        it.eslot = -1;
+        if (it.chain < 0) return it;
+        const int r = plan_word(a.req_order, chain / units);
+        it.lh = (chain % units) * GV + hsel;
+        it.c = plan_word(a.req_chunk_cu, r);
+        it.c_end = plan_word(a.req_chunk_cu, r + 1);
         it.tok0 = plan_word(a.chunk_tok0, it.c);
         it.n = plan_word(a.chunk_len, it.c);
         it.eslot = plan_word(a.chunk_emit_slot, it.c);
@@ -250,7 +255,14 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
             it.eslot = plan_word(a.chunk_emit_slot, it.c);
             return it;
         }
-        return open_chain(cur.round + 1);
+        const Item it = open_chain(reserve);
+        if (it.chain >= 0) {       // the reserve is used up: draw the next one (past the last chain nothing is left to draw)
+            if (wave == 0 && hsel == 0 && lane_ == 0)
+                drawn = 2 * (int)gridDim.x + __hip_atomic_fetch_add(a.next_chain, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            draw_pending = true;
+            reserve_stale = true;
+        }
+        return it;
     };
     // The next item's K, Q, V and gates are fetched (raw, into registers) while the current item is processed.
     Raw8 kraw[ROWS], qraw[ROWS], vraw[ROWS];   // two heads: kraw holds the group's shared tensor, qraw is unused
@@ -288,7 +300,7 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
             graw = (reinterpret_cast<const In*>(wave == 0 ? a.gate : a.beta) + (f_row0 * a.H_v + f_hv))[(lane_v) * a.H_v];      \
     } while (0)
 
-    Item cur = open_chain(0);
+    Item cur = open_chain((int)blockIdx.x);
     if (cur.chain < 0) return;
     {
         GDN_FETCH_DESCRIPTORS(cur);
@@ -297,7 +309,6 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
         GDN_FETCH_ALL(GDN_FETCH_V, tg_, d0_);
         GDN_FETCH_GATES(cur, lane_);
     }
-    Item nxt = next_item(cur);
     wait_vmcnt<0>();   // the first item's inputs: inside the loop the fetched registers are then known to have landed on every path
 
     // State tile (mt = 2 s + h, nt): element e of lane (m, g4) is S[32 w + 16 nt + m][32 s + 8 g4 + 4 h + e], so that the
@@ -357,6 +368,11 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
         }
         if (!first) __syncthreads();   // the previous item's recurrence is done with every LDS tile
         first = false;
+        if (reserve_stale) {           // the chain drawn during the previous item, now in LDS for every wave
+            reserve = __builtin_amdgcn_readfirstlane(reserve_lds[0]);
+            reserve_stale = false;
+        }
+        const Item nxt = next_item(cur);
         GDN_PHASE_ITEM();
         GDN_PHASE(0);
 
@@ -613,7 +629,13 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
                 // issued: loads and stores share one in-flight counter, and with both kinds pending the first use of a
                 // fetched register would wait for every store to be acknowledged (thousands of cycles at the top of the
                 // next item).  Here the fetch is thousands of cycles old and nothing else is pending, so this costs nothing.
-                if (ab == 0) wait_vmcnt<0>();
+                if (ab == 0) {
+                    wait_vmcnt<0>();
+                    if (draw_pending) {     // the draw made at the top of this item has returned with the loads
+                        if (wave == 0 && hsel == 0 && lane_ == 0) reserve_lds[0] = drawn;
+                        draw_pending = false;
+                    }
+                }
                 // buffer stores through the item's output descriptor (it ends with the chunk's last row: rows past n are dropped)
                 if (O_BF16) {
                     typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -660,7 +682,6 @@ __global__ void __launch_bounds__(256 * GV) __attribute__((amdgpu_waves_per_eu(2
         GDN_PHASE(9);
         if (nxt.chain < 0) break;
         cur = nxt;
-        nxt = next_item(cur);
     }
 }
 

@@ -382,35 +382,61 @@ hipError_t launch_quad_overlap(const RecurArgs& ra, const PrepArgs& pa, int64_t 
 }
 
 // Fused throughput kernel (bf16 inputs, d_k = d_v = 64 or 128): see gdn_fused_kernel.h.
+// per_cu: workgroups that may share a compute unit (0 or more than fit: as many as fit).  Fewer than fit are enforced by asking
+// for so much LDS per workgroup that one more would not fit; the grid is the compute units times that number.
+constexpr int CU_LDS_BYTES = 160 * 1024;
 template <bool O_BF16, int D, int GV>
-hipError_t launch_fused_t(const FusedArgs& fa, hipStream_t stream) {
+hipError_t launch_fused_t(const FusedArgs& fa, int per_cu, hipStream_t stream) {
     typedef FusedSmem<D, GV> SM;
     static std::once_flag once;
     static hipError_t once_err = hipSuccess;
-    static int slots = 1;
+    static int cus = 1, fit = 1;
     std::call_once(once, [] {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gdn_fused_kernel<O_BF16, D, GV>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
-        int dev = 0, cus = 0, per_cu = 0;
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, CU_LDS_BYTES);
+        int dev = 0, n_cu = 0, n_fit = 0;
         if (e == hipSuccess) e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gdn_fused_kernel<O_BF16, D, GV>, 256 * GV, SM::BYTES);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n_fit, gdn_fused_kernel<O_BF16, D, GV>, 256 * GV, SM::BYTES);
         once_err = e;
-        if (e == hipSuccess) slots = std::max(1, cus * per_cu);
+        if (e == hipSuccess) { cus = std::max(1, n_cu); fit = std::max(1, n_fit); }
     });
     if (once_err != hipSuccess) return once_err;
-    hipLaunchKernelGGL((gdn_fused_kernel<O_BF16, D, GV>), dim3((unsigned)std::min<int64_t>(fa.n_chains, slots)), dim3(256 * GV),
-                       SM::BYTES, stream, fa);
+    int lds = SM::BYTES, n = fit;
+    if (per_cu >= 1 && per_cu < fit) {
+        n = per_cu;
+        lds = std::max(lds, (CU_LDS_BYTES / (per_cu + 1) + 256) & ~255);    // per_cu + 1 of these exceed a compute unit's LDS
+    }
+    hipLaunchKernelGGL((gdn_fused_kernel<O_BF16, D, GV>), dim3((unsigned)std::min<int64_t>(fa.n_chains, (int64_t)cus * n)), dim3(256 * GV),
+                       lds, stream, fa);
     return hipGetLastError();
 }
 // gv = value heads per workgroup (1, or 2 when the heads of a pair share a query/key head); fa.n_chains counts groups of gv heads.
-hipError_t launch_fused(const FusedArgs& fa, int d, int gv, hipStream_t stream) {
+hipError_t launch_fused(const FusedArgs& fa, int d, int gv, int per_cu, hipStream_t stream) {
     if (gv == 2) {
-        if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 2>(fa, stream) : launch_fused_t<false, 64, 2>(fa, stream);
-        return fa.o_bf16 ? launch_fused_t<true, 128, 2>(fa, stream) : launch_fused_t<false, 128, 2>(fa, stream);
+        if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 2>(fa, per_cu, stream) : launch_fused_t<false, 64, 2>(fa, per_cu, stream);
+        return fa.o_bf16 ? launch_fused_t<true, 128, 2>(fa, per_cu, stream) : launch_fused_t<false, 128, 2>(fa, per_cu, stream);
     }
-    if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 1>(fa, stream) : launch_fused_t<false, 64, 1>(fa, stream);
-    return fa.o_bf16 ? launch_fused_t<true, 128, 1>(fa, stream) : launch_fused_t<false, 128, 1>(fa, stream);
+    if (d == 64) return fa.o_bf16 ? launch_fused_t<true, 64, 1>(fa, per_cu, stream) : launch_fused_t<false, 64, 1>(fa, per_cu, stream);
+    return fa.o_bf16 ? launch_fused_t<true, 128, 1>(fa, per_cu, stream) : launch_fused_t<false, 128, 1>(fa, per_cu, stream);
+}
+
+// How many fused workgroups share a compute unit (0: as many as fit).  A chunk of a chain takes less time when its
+// workgroup has the compute unit to itself (measured at d = 128: 5.5 us against 6.8 us with two), so a call bound by its
+// longest chain rather than by its volume runs better on fewer, faster workgroups.  Estimates: one per compute unit
+// max(longest chain x 5.5 us, units x 0.0257 us) (all 256 busy, a chunk takes 6.6 us), two max(longest chain x 6.8 us,
+// units x 0.0195 us).  Measured, one against two: 1024 chains of up to 66 chunks, 14.8 k units 0.431 against 0.449 ms; 384
+// chains of up to 128 chunks, 28 k units 0.72 against 0.79; 512 chains, 39 k units 0.92 against 0.87; 1024 chains of up to 345
+// chunks, 99.5 k units 2.56 against 2.31.  gdn_tune_fused_per_cu forces the number.
+std::atomic<int32_t> g_forced_per_cu{-1};
+inline int fused_wgs_per_cu(const gdn_shape& s, int gv, int64_t total_units, int32_t longest_chain_chunks) {
+    const int forced = g_forced_per_cu.load();
+    if (forced >= 1) return forced;
+    if (s.d_k != 128 || gv != 1) return 0;
+    const double cus = (double)chip_cus(), units = (double)total_units, longest = (double)longest_chain_chunks;   // (figures from 256 compute units)
+    const double t1 = std::max(longest * 5.5, units * 0.0257 * 256.0 / cus);
+    const double t2 = std::max(longest * 6.8, units * 0.0195 * 256.0 / cus);
+    return t1 < t2 ? 1 : 0;
 }
 
 // Grouped value heads (H_v a multiple of H_qk): two value heads of one query/key head can share a workgroup of eight waves,
@@ -616,6 +642,10 @@ int32_t gdn_tune_fused(int32_t mode) {
     return g_forced_fused.exchange(mode < 0 ? -1 : (mode != 0));
 }
 
+int32_t gdn_tune_fused_per_cu(int32_t n) {
+    return g_forced_per_cu.exchange(n >= 1 ? n : -1);
+}
+
 int32_t gdn_tune_fused_pair(int32_t mode) {
     return g_forced_pair.exchange(mode < 0 ? -1 : (mode != 0));
 }
@@ -734,7 +764,7 @@ int32_t gdn_plan_chunks(int32_t n_req, const int32_t* cu_seqlens, const int32_t*
 }
 
 static int64_t plan_bytes(int64_t n_chunks, int64_t n_req) {
-    return align_up((3 * n_chunks + 4 * n_req + 1) * (int64_t)sizeof(int32_t), 256);
+    return align_up((3 * n_chunks + 4 * n_req + 2) * (int64_t)sizeof(int32_t), 256);
 }
 
 // Workspace = [plan | carried states | slab buffers].  A slab buffer holds the units of R chunk
@@ -874,8 +904,9 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return GDN_ERR_WORKSPACE;
     if (workspace_bytes < need) return GDN_ERR_WORKSPACE;
 
-    // ---- plan image: [tok0 | len | emit slot] per chunk, [chunk_cu | src slot | order] per request
-    std::vector<int32_t> img((size_t)(3 * (int64_t)n_chunks + 4 * (int64_t)n_req + 1));   // + staged host slots
+    // ---- plan image: [tok0 | len | emit slot] per chunk, [chunk_cu | src slot | order | staged host slots] per request, and
+    //      one word that starts at zero: the fused kernel's counter of chains handed out
+    std::vector<int32_t> img((size_t)(3 * (int64_t)n_chunks + 4 * (int64_t)n_req + 2));
     int32_t* p_tok0 = img.data();
     int32_t* p_len = p_tok0 + n_chunks;
     int32_t* p_eslot = p_len + n_chunks;
@@ -994,13 +1025,17 @@ static int32_t prefill_impl(const gdn_shape* shape, const void* q, const void* k
         fa.state_src = ra.state_src; fa.state_dst = state_dst;   // (the staging area when the pool is on the host)
         fa.src_slot_stride = ra.src_slot_stride; fa.dst_slot_stride = dst_slot_stride;
         const int gv = fused_heads_per_wg(s, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
-        fa.n_chains = (int32_t)((int64_t)n_req * s.L * s.H_v / gv);
+        int32_t n_live = 0;          // requests with tokens: they come first in the order, and only they have chains
+        for (int32_t r = 0; r < n_req; ++r) n_live += plan.req_chunk_cu[r + 1] > plan.req_chunk_cu[r];
+        fa.n_chains = (int32_t)((int64_t)n_live * s.L * s.H_v / gv);
+        fa.next_chain = reinterpret_cast<int32_t*>(workspace) + (3 * (int64_t)n_chunks + 4 * (int64_t)n_req + 1);
         fa.L = s.L; fa.H_qk = s.H_qk; fa.H_v = s.H_v;
         fa.T_alloc = s.T_alloc;
         fa.scale = s.scale;
         fa.o_bf16 = s.o_dtype == GDN_BF16;
         ProfChain prof(stream);
-        const hipError_t e = launch_fused(fa, s.d_k, gv, stream);
+        const int per_cu = fused_wgs_per_cu(s, gv, (int64_t)n_chunks * s.L * s.H_v, plan.max_chunks_per_req);
+        const hipError_t e = launch_fused(fa, s.d_k, gv, per_cu, stream);
         if (e != hipSuccess) return hip_err(e);
         prof.mark(1);
         std::lock_guard<std::mutex> lock(g_prof.mu);

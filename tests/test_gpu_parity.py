@@ -749,6 +749,43 @@ def test_head_pairs_in_one_workgroup_equal_single_heads_bitwise(d, H_qk, H_v):
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("d", [128, 64])
+def test_fused_chains_drawn_from_the_counter_match_the_oracle_for_any_workgroup_count(d):
+    """640 short chains (20 requests, some empty, x 2 layers x 16 heads) on the fused kernel with one workgroup per compute
+    unit: the first two rounds of chains are dealt by workgroup number, the rest are drawn from the counter in memory while
+    the kernel runs.  Checked against the oracle, and bit for bit against the same call with as many workgroups per compute
+    unit as fit (another grid, another assignment of chains to workgroups)."""
+    from paper_2605_05219_amd import binding as B
+    rng = np.random.default_rng(6400 + d)
+    L, H, n_req = 2, 16, 20
+    lens = [int(x) for x in rng.choice([0, 1, 30, 64, 65, 100, 129, 200, 260], n_req)]
+    lens[3] = 0
+    starts = [int(x) for x in rng.choice([0, 64, 128], n_req)]
+    nxt, emits, eslots = 3, [], []
+    for s0, ln in zip(starts, lens):
+        e = sorted(set(int(x) for x in rng.integers(s0 + 1, s0 + ln + 1, 2))) if ln > 0 else []
+        emits.append(e)
+        eslots.append(list(range(nxt, nxt + len(e))))
+        nxt += len(e)
+    per_req = [wl.token_streams(rng, L, ln, H, H, d, d, "bf16") for ln in lens]
+    src = [-1 if s0 == 0 else int(rng.integers(0, 3)) for s0 in starts]
+    call = wl.pack_call(L, H, H, d, d, "bf16", per_req, starts, src, emits, eslots, nxt + 1)
+    pool = rng.standard_normal((nxt + 1,) + call.slot_shape).astype(np.float32) * 0.1
+    prev = B.gdn_tune_fused(1)
+    prev_n = B.gdn_tune_fused_per_cu(1)
+    try:
+        check_call(call, pool, TOL["bf16"])
+        o1, p1 = run_call_gpu(call, pool)
+        B.gdn_tune_fused_per_cu(8)
+        o2, p2 = run_call_gpu(call, pool)
+    finally:
+        B.gdn_tune_fused(prev)
+        B.gdn_tune_fused_per_cu(prev_n)
+    assert np.array_equal(o1.view(np.uint32), o2.view(np.uint32))
+    assert np.array_equal(p1.view(np.uint32), p2.view(np.uint32))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("fused", [0, 1])
 def test_extreme_gates(fused, d):
     """Gates that forget within one token (a = 1e-30, below what the clamp of log a lets through unchanged), gates of
