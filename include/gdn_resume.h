@@ -323,8 +323,8 @@ int32_t gdn_tune_fused(int32_t mode);
  * Tuning knob (not a step of the method).  With grouped value heads (H_v / H_qk even) the fused
  * kernel can give two value heads of one query/key head a workgroup of eight waves that reads
  * and stages that head's q and k rows once for both.  mode 1 forces pairs wherever the shape
- * allows them, mode 0 forbids them, mode < 0 restores the automatic choice (pairs once there
- * are at least as many of them as compute units).  Outputs are bitwise the same either way:
+ * allows them, mode 0 forbids them, mode < 0 restores the automatic choice (pairs at d_k = 128
+ * when the call is bound by its volume, not by its longest chain).  Outputs are bitwise the same either way:
  * each head's arithmetic is unchanged.  Returns the previous setting (-1 = automatic).
  */
 int32_t gdn_tune_fused_pair(int32_t mode);

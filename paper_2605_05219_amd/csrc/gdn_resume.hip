@@ -425,7 +425,7 @@ hipError_t launch_fused(const FusedArgs& fa, int d, int gv, int per_cu, hipStrea
 // workgroup has the compute unit to itself (measured at d = 128: 5.5 us against 6.8 us with two), so a call bound by its
 // longest chain rather than by its volume runs better on fewer, faster workgroups.  Estimates: one per compute unit
 // max(longest chain x 5.5 us, units x 0.0257 us) (all 256 busy, a chunk takes 6.6 us), two max(longest chain x 6.8 us,
-// units x 0.0195 us).  Measured, one against two: 1024 chains of up to 66 chunks, 14.8 k units 0.431 against 0.449 ms; 384
+// units x 0.0183 us).  Measured, one against two: 1024 chains of up to 66 chunks, 14.8 k units 0.431 against 0.449 ms; 384
 // chains of up to 128 chunks, 28 k units 0.72 against 0.79; 512 chains, 39 k units 0.92 against 0.87; 1024 chains of up to 345
 // chunks, 99.5 k units 2.56 against 2.31.  gdn_tune_fused_per_cu forces the number.
 std::atomic<int32_t> g_forced_per_cu{-1};
@@ -435,7 +435,7 @@ inline int fused_wgs_per_cu(const gdn_shape& s, int gv, int64_t total_units, int
     if (s.d_k != 128 || gv != 1) return 0;
     const double cus = (double)chip_cus(), units = (double)total_units, longest = (double)longest_chain_chunks;   // (figures from 256 compute units)
     const double t1 = std::max(longest * 5.5, units * 0.0257 * 256.0 / cus);
-    const double t2 = std::max(longest * 6.8, units * 0.0195 * 256.0 / cus);
+    const double t2 = std::max(longest * 6.8, units * 0.0183 * 256.0 / cus);
     return t1 < t2 ? 1 : 0;
 }
 
@@ -447,15 +447,16 @@ inline int fused_wgs_per_cu(const gdn_shape& s, int gv, int64_t total_units, int
 // up to 126 chunks 16.3 against 18.2 ms; 8192 chains 4.25 against 4.74; 4096 chains 2.29 against 2.32; 2048 chains 1.36
 // either way; 2048 chains of up to 32 chunks 0.47 against 0.44; 1024 chains of up to 320 chunks 2.66 against 2.50.  At
 // d = 64 a pair's 81 KB of LDS leave a compute unit one workgroup where three single-head ones fit, and pairs never won
-// (9.47 against 9.56 ms on 32768 chains, 1.39 against 1.17 on 4096): forced only.  (Both kernels have since gained
-// 2 to 5 % from one change to their loads; the ratios stand.)  gdn_tune_fused_pair forces the choice.
+// (9.47 against 9.56 ms on 32768 chains, 1.39 against 1.17 on 4096): forced only.  (Since then the one-head kernel has gained
+// about 10 % and the pair kernel 5 % from changes to their loads and to the order of the chains: on the first of these calls
+// 16.7 against 17.4 ms; the threshold was raised accordingly, pairs from three times the longest chain's time in volume.)  gdn_tune_fused_pair forces the choice.
 std::atomic<int32_t> g_forced_pair{-1};
 inline int fused_heads_per_wg(const gdn_shape& s, int64_t total_units, int32_t longest_chain_chunks) {
     if (s.H_qk <= 0 || s.H_v % s.H_qk != 0 || (s.H_v / s.H_qk) % 2 != 0) return 1;
     const int forced = g_forced_pair.load();
     if (forced >= 0) return forced != 0 ? 2 : 1;
     if (s.d_k != 128) return 1;
-    return 0.0197 * (double)total_units >= 2.0 * 8.2 * (double)longest_chain_chunks ? 2 : 1;
+    return 0.0197 * (double)total_units >= 3.0 * 8.2 * (double)longest_chain_chunks ? 2 : 1;
 }
 
 // The fused kernel serialises a chain's preparation along the chain; it pays when chains are
@@ -463,10 +464,10 @@ inline int fused_heads_per_wg(const gdn_shape& s, int64_t total_units, int32_t l
 // figures measured on MI355X (bf16; one call of 4 to 64 requests of up to 8192 tokens, 16 heads,
 // and the large configurations).  d = 128: fused, per chunk of one chain 5.5 us with one workgroup
 // per compute unit (up to 256 chains) and 6.8 us with two, per (chunk, chain) unit of a large call
-// 0.0195 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured, fused against
+// 0.0183 us; two-kernel path 0.056 us per unit plus about 0.15 ms.  Measured, fused against
 // two-kernel: 64 chains 0.60 against 0.40 ms, 96 chains 0.61 against 0.52, 128 chains 0.62 against
 // 0.63, 160 chains 0.70 against 0.85, 256 chains 0.70 against 1.14, 512 chains 0.87 against 2.04,
-// 1024 chains 1.49 against 4.17.  d = 64: 3.4 / 4.4 us per chunk, 0.0115 us per unit; two-kernel
+// 1024 chains 1.49 against 4.17.  d = 64: 3.4 / 4.4 us per chunk, 0.0094 us per unit; two-kernel
 // path 0.036 us per unit plus about 0.1 ms (requests of up to 4096 tokens: 96 chains 0.21 against
 // 0.17 ms, 128 chains 0.21 against 0.22, 256 chains 0.25 against 0.39, 1024 chains 0.45 against
 // 1.48).  gdn_tune_fused forces the choice.
@@ -480,7 +481,7 @@ inline bool choose_fused(const gdn_shape& s, int64_t n_chains, int64_t total_uni
     const bool big = s.d_k == 128;
     const double per_chunk = n_chains <= chip_cus() ? (big ? 5.5 : 3.4) : (big ? 6.8 : 4.4);   // us: one or two workgroups per compute unit
     const double t_two = (big ? 0.056 : 0.036) * (double)total_units + (big ? 150.0 : 100.0);
-    const double t_fused = std::max((big ? 0.0195 : 0.0115) * (double)total_units, per_chunk * (double)longest_chain_chunks);
+    const double t_fused = std::max((big ? 0.0183 : 0.0094) * (double)total_units, per_chunk * (double)longest_chain_chunks);
     return t_fused < t_two;
 }
 
