@@ -192,8 +192,13 @@ gdn_linear_kernel(LinearArgs a) {
         const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
 #pragma unroll
         for (int kk = 0; kk + 1 < KK; ++kk) {
+            // the fragments of k step kk + 1 are requested BEFORE the matrix instructions of k step kk are issued (pinned: left
+            // to itself the scheduler reads them into the registers the matrix instructions have just used, behind them, and
+            // waits out the LDS latency with the matrix pipe idle)
             read_frags(stage, kk + 1, (kk & 1) ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
             mma_all(kk & 1);
+            __builtin_amdgcn_sched_barrier(0);
         }
         // (the matrix instructions above stay above: left to itself the scheduler sinks them below the barrier, and the
         // fragment reads and the barrier are then waited for with the matrix pipe idle)
