@@ -59,7 +59,8 @@ int32_t gdn_linear_split(const void *x, int64_t ldx, const void *w, int64_t ldw,
 
 /*
  * Tuning knob, not a method step: fixes the workgroup tile gdn_linear uses (0: 128 x 128; 1: 256 x 256 with four
- * waves; 2: 256 x 256 with eight waves; anything else: chosen per call from T and N, the default).  Every shape computes the same
+ * waves; 2: 256 x 256 with eight waves; 3: 64 x 64, which needs K a multiple of 128 and gives way to 0 otherwise;
+ * anything else: chosen per call from T, N and K, the default).  Every shape computes the same
  * sums in the same order, so the results do not depend on it.  Process-wide; returns the previous setting (-1 = per
  * call).
  */

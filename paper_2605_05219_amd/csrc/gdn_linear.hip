@@ -3,13 +3,16 @@
 // One workgroup of four or eight waves makes a BM (tokens) x BN (outputs) tile, a wave its part of it as tiles of
 // v_mfma_f32_32x32x16_bf16.  Both operands are read along k, so a k step of BK needs a BM x BK tile of x and a
 // BN x BK tile of w; they come from memory with 16-byte buffer loads straight to LDS (no registers) into a ring of
-// STAGES stages, STAGES - 1 k steps ahead of the matrix cores: one barrier per k step.  Three shapes are built:
+// STAGES stages, STAGES - 1 k steps ahead of the matrix cores: one barrier per k step.  Four shapes are built:
 //   0: 128 x 128 x 64, 2 stages, four waves, two workgroups per compute unit   small problems (more, smaller workgroups)
 //   1: 256 x 256 x 32, 4 stages, four waves, one workgroup per compute unit: a wave holds 128 x 128 outputs in 256
 //      accumulator registers: half the operand bytes per flop, from memory and from LDS, three k steps of loads in flight
 //   2: 256 x 256 x 64, 2 stages, eight waves of 128 tokens x 64 outputs, two per SIMD: while one wave of a SIMD is held up
 //      issuing its loads to LDS the other feeds the matrix pipe, and a barrier covers 64 of k (the default for large
 //      problems; 1 is kept for comparison)
+//   3: 64 x 64 x 128, 4 stages, four waves of one 32 x 32 tile: problems so small that their 64 x 64 tiles fit the chip in two
+//      rounds (a 512-token out-projection: 64 workgroups of shape 0 would walk k one after the other, each step waiting for
+//      its loads; 256 small workgroups with three steps of 128 in flight take 11 us against 18)
 // A load to LDS writes a wave's 1 KiB contiguously (lane i at 16 i), so rows are unpadded (2 BK bytes) and bank
 // conflicts are avoided by choosing WHICH 16-byte piece of its row a lane fetches: piece p of row r is stored at
 // position p ^ swz(r), swz(r) = (r / rows per 256 bytes) % pieces per row, which makes the 16 lanes that read the
@@ -83,6 +86,7 @@ struct LinCfg {
 typedef LinCfg<128, 128, 64, 2, 2, 2, 2> LinSmall;
 typedef LinCfg<256, 256, 32, 4, 1, 2, 2> LinBig;      // four waves, 128 x 128 outputs each
 typedef LinCfg<256, 256, 64, 2, 1, 2, 4> LinBig8;     // eight waves, 128 tokens x 64 outputs each: two waves per SIMD
+typedef LinCfg<64, 64, 128, 4, 1, 2, 2> LinTiny;      // four waves of one 32 x 32 tile each, three k steps of 128 in flight
 
 // The loads of one wave for one stage: 1 KiB each, XL of its quarter of the x tile, then WL of the w tile.
 template <typename CFG>
@@ -354,10 +358,13 @@ int chip_cus_linear() {
 
 // Which tile shape a problem gets: the estimated time of each shape is its number of rounds of workgroups over the
 // chip times the work of one workgroup over the shape's measured rate (relative figures).
-int choose_linear_shape(int64_t T, int32_t N) {
+int choose_linear_shape(int64_t T, int32_t N, int32_t K) {
     const int forced = g_linear_shape.load();
-    if (forced >= 0) return forced;
+    if (forced >= 0) return (forced == 3 && K % 128 != 0) ? 0 : forced;      // shape 3 walks k in steps of 128
     const double cus = (double)chip_cus_linear();
+    // at most two rounds of 64 x 64 tiles, one per compute unit (measured, shape 3 against shape 0: 512 x 2048 11 against 17 us,
+    // 512 x 2560 19 against 23, 1024 x 2048 19 against 23; 256 x 8224, three rounds, 32 against 23)
+    if (K % 128 == 0 && (double)((T + 63) / 64) * (double)((N + 63) / 64) <= 2.0 * cus) return 3;
     const struct { int id, bm, bn, per_cu; double rate; } shapes[2] = {{0, 128, 128, 2, 0.34}, {2, 256, 256, 1, 0.53}};
     int best = 0;
     double best_t = 0;
@@ -398,9 +405,10 @@ int32_t linear_launch(LinearArgs& a, int32_t out_dtype, hipStream_t stream) {
     a.tiles_n = 0;
     const bool bf = out_dtype == GDN_BF16;
     hipError_t e;
-    switch (choose_linear_shape(a.T, a.N)) {
+    switch (choose_linear_shape(a.T, a.N, a.K)) {
         case 1: e = bf ? launch_linear<LinBig, true>(a, stream) : launch_linear<LinBig, false>(a, stream); break;
         case 2: e = bf ? launch_linear<LinBig8, true>(a, stream) : launch_linear<LinBig8, false>(a, stream); break;
+        case 3: e = bf ? launch_linear<LinTiny, true>(a, stream) : launch_linear<LinTiny, false>(a, stream); break;
         default: e = bf ? launch_linear<LinSmall, true>(a, stream) : launch_linear<LinSmall, false>(a, stream); break;
     }
     return hip_err(e);
@@ -457,5 +465,5 @@ extern "C" int32_t gdn_linear_split(const void* x, int64_t ldx, const void* w, i
 }
 
 extern "C" int32_t gdn_linear_tune(int32_t shape) {
-    return g_linear_shape.exchange(shape < 0 || shape > 2 ? -1 : shape);
+    return g_linear_shape.exchange(shape < 0 || shape > 3 ? -1 : shape);
 }

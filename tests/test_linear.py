@@ -158,7 +158,7 @@ def run_gpu(x, w, b, out, ldy=None, col0=0):
     (515, 2048, 2048, True, "f32"),            # the out-projection
     (64, 131, 192, True, "bf16"),              # an output count that is no multiple of 4 is only legal with ldy % 4 == 0
 ])
-@pytest.mark.parametrize("shape", [0, 1, 2, -1])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, -1])
 def test_linear_against_the_definition(T, N, K, bias, out, shape):
     x, w, b = draw(T * 7 + N * 3 + K, T, N, K, bias)
     ref = lo.linear(x, w, b)
@@ -185,7 +185,7 @@ def test_output_may_be_a_column_slice_of_a_wider_buffer():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("shape", [0, 2])
+@pytest.mark.parametrize("shape", [0, 2, 3])
 @pytest.mark.parametrize("out", ["bf16", "f32"])
 def test_split_outputs_equal_the_whole_projection(shape, out):
     """The in-projection of a layer in one launch: [conv input | z | a | b] to four tensors of their own (the last boundary
