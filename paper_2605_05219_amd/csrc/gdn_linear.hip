@@ -196,13 +196,28 @@ gdn_linear_kernel(LinearArgs a) {
         const int next_stage = stage + 1 == STAGES ? 0 : stage + 1;
 #pragma unroll
         for (int kk = 0; kk + 1 < KK; ++kk) {
-            // the fragments of k step kk + 1 are requested BEFORE the matrix instructions of k step kk are issued (pinned: left
-            // to itself the scheduler reads them into the registers the matrix instructions have just used, behind them, and
-            // waits out the LDS latency with the matrix pipe idle)
-            read_frags(stage, kk + 1, (kk & 1) ^ 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mma_all(kk & 1);
-            __builtin_amdgcn_sched_barrier(0);
+            // The fragments of k step kk + 1 go into the other register set while the matrix instructions of k step kk are
+            // issued, one read behind every matrix instruction or two, pinned in that order: left to itself the scheduler
+            // reads them into the registers the matrix instructions have just used, behind them, and waits out the LDS
+            // latency with the matrix pipe idle; and a burst of reads in front keeps the issue port from the matrix pipe.
+            const int rs = (kk & 1) ^ 1, ms = kk & 1;
+            const char* xs = smem + stage * CFG::STAGE_BYTES;
+            const char* ws = xs + CFG::X_BYTES;
+            const int pos = ((2 * (kk + 1) + g) ^ sw) * 16;
+            constexpr int NM = TI * TJ, NR = TI + TJ;
+            constexpr int SLOTS = NM < NR ? NM : NR;
+#pragma unroll
+            for (int i = 0; i < SLOTS; ++i) {
+#pragma unroll
+                for (int q = i * NM / SLOTS; q < (i + 1) * NM / SLOTS; ++q)
+                    acc[q / TI][q % TI] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ms][q / TI], xf[ms][q % TI], acc[q / TI][q % TI], 0, 0, 0);
+#pragma unroll
+                for (int r = i * NR / SLOTS; r < (i + 1) * NR / SLOTS; ++r) {
+                    if (r < TI) xf[rs][r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xs + xrow + 32 * r * RB + pos));
+                    else wf[rs][r - TI] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(ws + wrow + 32 * (r - TI) * RB + pos));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         // (the matrix instructions above stay above: left to itself the scheduler sinks them below the barrier, and the
         // fragment reads and the barrier are then waited for with the matrix pipe idle)
