@@ -2,7 +2,8 @@
 // one chain (request, layer, value head) in ONE workgroup, chunk after chunk, the chunk
 // operands never leaving the compute unit.  HBM sees q, k, v, the gates, o and the states,
 // nothing else.  A chain's chunks are serial, so the kernel only pays when chains are plentiful
-// and none is so long that it outlasts the rest (the host decides).
+// and none is so long that it outlasts the rest (the host decides).  The grid is persistent (one to three workgroups per
+// compute unit); the chains come longest first and are taken in turn by whichever workgroup is free (see the items).
 //
 // Per 64-token chunk, with g the running sum of log a, gam = exp(g), L_ij = b_i exp(g_i - g_j)(k_i.k_j)
 // for j < i, the chunk-local form of the gated delta rule is
@@ -41,6 +42,7 @@
 //            partner half stays zero from the start of the kernel
 //   Tf[w]    fp32 [16][20]: a wave's T_aa on its way from the accumulator layout to its transpose
 //   g, b, gam, dec, and the factors of the decay between blocks (s, r_c; see the gates): fp32 [64] each
+//   one word: the chain the workgroup holds in reserve, on its way from the wave that drew it to the others
 #pragma once
 #include "gdn_prep_kernel.h"
 #include "gdn_recur_kernel.h"
