@@ -6,9 +6,13 @@
 // So each row is read once and written once: the kernel is bound by HBM traffic (2 x state
 // bytes).  A row is spread over d_k / 4 lanes (16-byte accesses, a wave covers 1 KiB of
 // consecutive memory per pass); the dot products are reduced across those lanes with xor
-// shuffles, several rows in flight per lane to cover their latency.
+// shuffles, several rows in flight per lane to cover their latency.  NT: the state rows are read and written with
+// non-temporal accesses, which is what a call wants whose states exceed the memory-side cache (1024 states of 1 MiB:
+// 6.1 against 5.6 TB/s), and not one whose states fit it and are touched again by the next step (256 states: 6.3 against
+// 6.8 TB/s); the host decides by the bytes a call touches.
 #pragma once
 #include "gdn_mma.h"
+
 
 namespace gdn {
 
@@ -33,7 +37,7 @@ struct DecodeIds {
     int32_t slot[DECODE_IDS];
 };
 
-template <typename E, int DK, int DV>
+template <typename E, int DK, int DV, bool NT>
 __global__ void __launch_bounds__(256) gdn_decode_kernel(DecodeArgs a, DecodeIds ids) {
     typedef Elem<E> EL;
     typedef typename EL::In In;
@@ -69,7 +73,7 @@ __global__ void __launch_bounds__(256) gdn_decode_kernel(DecodeArgs a, DecodeIds
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
         const int row = row0 + p * RPP;
-        s[p] = *reinterpret_cast<const f32x4*>(S + (int64_t)row * DK + 4 * c);
+        s[p] = NT ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(S + (int64_t)row * DK + 4 * c)) : *reinterpret_cast<const f32x4*>(S + (int64_t)row * DK + 4 * c);
         vr[p] = EL::widen(vp[row]);
     }
     float kq = k4[0] * q4[0] + k4[1] * q4[1] + k4[2] * q4[2] + k4[3] * q4[3];
@@ -94,7 +98,7 @@ __global__ void __launch_bounds__(256) gdn_decode_kernel(DecodeArgs a, DecodeIds
         f32x4 t;
 #pragma unroll
         for (int e = 0; e < 4; ++e) t[e] = av * s[p][e] + u * k4[e];
-        *reinterpret_cast<f32x4*>(S + (int64_t)row * DK + 4 * c) = t;
+        if (NT) __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(S + (int64_t)row * DK + 4 * c)); else *reinterpret_cast<f32x4*>(S + (int64_t)row * DK + 4 * c) = t;
         if (c == 0) {
             const float ov = a.scale * (av * pq[p] + u * kq);
             const int64_t oi = (tok * a.H_v + hv) * DV + row;

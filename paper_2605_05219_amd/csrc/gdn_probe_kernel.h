@@ -39,22 +39,12 @@ __global__ void __launch_bounds__(PROBE_THREADS) probe_mfma_kernel(float* __rest
     out[(int64_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
-// dst[i] = src[i], 16 bytes per access; a workgroup moves contiguous 16 KiB tiles, four loads in
-// flight per thread.
-__global__ void __launch_bounds__(PROBE_THREADS) probe_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+// dst[i] = src[i]: one non-temporal 16-byte access each way per thread, a workgroup per 4 KiB (the form that moves the most
+// bytes per second on this chip: see ckpt_copy_kernel).
+__global__ void __launch_bounds__(PROBE_THREADS) probe_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst,
                                                                    int64_t n4) {
-    constexpr int64_t TILE = 4 * PROBE_THREADS;
-    const int64_t n_tiles = n4 / TILE;
-    for (int64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const int64_t base = t * TILE + threadIdx.x;
-        float4 x[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) x[u] = src[base + u * PROBE_THREADS];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) dst[base + u * PROBE_THREADS] = x[u];
-    }
-    if (blockIdx.x == 0)
-        for (int64_t i = n_tiles * TILE + threadIdx.x; i < n4; i += PROBE_THREADS) dst[i] = src[i];
+    const int64_t i = (int64_t)blockIdx.x * PROBE_THREADS + threadIdx.x;
+    if (i < n4) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 }  // namespace gdn

@@ -26,37 +26,31 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // ------------------------------------------------------------------ checkpoint pool copies
 constexpr int COPY_IDS = 256;   // slot ids carried by value per launch
 constexpr int COPY_THREADS = 256;
-constexpr int COPY_UNROLL = 4;  // float4 loads in flight per thread
 
 struct CopyIds {
     int32_t id[COPY_IDS];
 };
 
-// blockIdx.y = state within the batch, blockIdx.x strides over its float4 elements.
+// blockIdx.y = state within the batch; a thread moves ONE 16-byte piece, a workgroup 4 KiB, with non-temporal accesses
+// (nothing is read twice).  Measured on 1 GiB each way: 6.5 TB/s in this form against 5.4 TB/s for a grid of a few
+// thousand workgroups that stride over the data with four loads in flight per thread: the memory system is fed best by
+// very many small workgroups, each gone as soon as its one request is answered.
 // GATHER: dst[y] = pool[id[y]] (zeros for id -1);  else pool[id[y]] = src[y].
 template <bool GATHER>
-__global__ void __launch_bounds__(COPY_THREADS) ckpt_copy_kernel(const float4* __restrict__ from, float4* __restrict__ to,
+__global__ void __launch_bounds__(COPY_THREADS) ckpt_copy_kernel(const f32x4* __restrict__ from, f32x4* __restrict__ to,
                                                                  int64_t from_stride4, int64_t to_stride4,
                                                                  int64_t n4, CopyIds ids) {
     const int y = blockIdx.y;
     const int32_t id = ids.id[y];
-    const float4* src = GATHER ? from + (int64_t)id * from_stride4 : from + (int64_t)y * from_stride4;
-    float4* dst = GATHER ? to + (int64_t)y * to_stride4 : to + (int64_t)id * to_stride4;
-    const int64_t step = (int64_t)gridDim.x * COPY_THREADS;
-    int64_t i = (int64_t)blockIdx.x * COPY_THREADS + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * COPY_THREADS + threadIdx.x;
+    if (i >= n4) return;
+    const f32x4* src = GATHER ? from + (int64_t)id * from_stride4 : from + (int64_t)y * from_stride4;
+    f32x4* dst = GATHER ? to + (int64_t)y * to_stride4 : to + (int64_t)id * to_stride4;
     if (GATHER && id < 0) {
-        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (; i < n4; i += step) dst[i] = z;
+        __builtin_nontemporal_store(f32x4{0.f, 0.f, 0.f, 0.f}, dst + i);
         return;
     }
-    for (; i + (COPY_UNROLL - 1) * step < n4; i += COPY_UNROLL * step) {
-        float4 x[COPY_UNROLL];
-#pragma unroll
-        for (int u = 0; u < COPY_UNROLL; ++u) x[u] = src[i + u * step];
-#pragma unroll
-        for (int u = 0; u < COPY_UNROLL; ++u) dst[i + u * step] = x[u];
-    }
-    for (; i < n4; i += step) dst[i] = src[i];
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 int32_t check_copy_args(const void* pool, int64_t slot_stride, int32_t n_slots, const int32_t* ids, int32_t n,
@@ -78,17 +72,16 @@ template <bool GATHER>
 int32_t launch_copy(const float* from, float* to, int64_t from_stride, int64_t to_stride, int64_t state_elems,
                     const int32_t* ids, int32_t n, hipStream_t stream) {
     const int64_t n4 = state_elems / 4;
-    // enough workgroups to fill 256 CUs several times over, but no more than the state has work for
-    const int64_t per_state = std::max<int64_t>(1, std::min<int64_t>((n4 + COPY_THREADS * COPY_UNROLL - 1) / (COPY_THREADS * COPY_UNROLL), 1024));
+    const int64_t gx = (n4 + COPY_THREADS - 1) / COPY_THREADS;      // one 16-byte piece per thread
+    if (gx > INT32_MAX) return GDN_ERR_COUNT;
     for (int32_t base = 0; base < n; base += COPY_IDS) {
         const int32_t m = std::min(COPY_IDS, n - base);
         CopyIds batch;
         std::memset(&batch, 0, sizeof batch);
         std::memcpy(batch.id, ids + base, sizeof(int32_t) * m);
-        const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(per_state, (8192 + m - 1) / m));
         const dim3 grid((unsigned)gx, (unsigned)m);
-        const float4* f = reinterpret_cast<const float4*>(from) + (GATHER ? 0 : (int64_t)base * (from_stride / 4));
-        float4* t = reinterpret_cast<float4*>(to) + (GATHER ? (int64_t)base * (to_stride / 4) : 0);
+        const f32x4* f = reinterpret_cast<const f32x4*>(from) + (GATHER ? 0 : (int64_t)base * (from_stride / 4));
+        f32x4* t = reinterpret_cast<f32x4*>(to) + (GATHER ? (int64_t)base * (to_stride / 4) : 0);
         hipLaunchKernelGGL(ckpt_copy_kernel<GATHER>, grid, dim3(COPY_THREADS), 0, stream, f, t, from_stride / 4,
                            to_stride / 4, n4, batch);
         const hipError_t e = hipGetLastError();
@@ -728,9 +721,11 @@ int32_t gdn_probe_ceilings(void* scratch, int64_t scratch_bytes, double* mfma_f1
     }
     if (e == hipSuccess) {
         const int64_t half = scratch_bytes / 2 / 16 * 16;
-        const float4* src = reinterpret_cast<const float4*>(scratch);
-        float4* dst = reinterpret_cast<float4*>(reinterpret_cast<char*>(scratch) + half);
-        e = timed([&] { hipLaunchKernelGGL(probe_copy_kernel, dim3(8192), dim3(PROBE_THREADS), 0, stream, src, dst, half / 16); },
+        const f32x4* src = reinterpret_cast<const f32x4*>(scratch);
+        f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<char*>(scratch) + half);
+        const int64_t n4 = half / 16;
+        e = timed([&] { hipLaunchKernelGGL(probe_copy_kernel, dim3((unsigned)((n4 + PROBE_THREADS - 1) / PROBE_THREADS)), dim3(PROBE_THREADS), 0,
+                                           stream, src, dst, n4); },
                   5, &ms);
         if (e == hipSuccess && copy_gbs) *copy_gbs = 2.0 * (double)half / (ms * 1e-3) / 1e9;
     }
@@ -1157,6 +1152,8 @@ int32_t gdn_decode_step(const gdn_shape* shape, const void* q, const void* k, co
     a.L = s.L; a.H_qk = s.H_qk; a.H_v = s.H_v;
     a.scale = s.scale;
     a.o_bf16 = s.o_dtype == GDN_BF16;
+    // states beyond half of the 256 MiB memory-side cache will not be there for the next step: stream them
+    const bool stream_states = (int64_t)n_req * slot_elems * (int64_t)sizeof(float) > ((int64_t)128 << 20);
     for (int32_t base = 0; base < n_req; base += DECODE_IDS) {
         const int32_t m = std::min(DECODE_IDS, n_req - base);
         DecodeIds ids;
@@ -1164,9 +1161,16 @@ int32_t gdn_decode_step(const gdn_shape* shape, const void* q, const void* k, co
         std::memcpy(ids.slot, slot + base, sizeof(int32_t) * m);
         a.req_base = base;
         const dim3 grid((unsigned)(s.d_v / 32), (unsigned)(s.L * s.H_v), (unsigned)m);
-        if (s.in_dtype == GDN_F32) hipLaunchKernelGGL((gdn_decode_kernel<float, 64, 64>), grid, dim3(256), 0, stream, a, ids);
-        else if (s.d_k == 64) hipLaunchKernelGGL((gdn_decode_kernel<half_t, 64, 64>), grid, dim3(256), 0, stream, a, ids);
-        else hipLaunchKernelGGL((gdn_decode_kernel<half_t, 128, 128>), grid, dim3(256), 0, stream, a, ids);
+        if (s.in_dtype == GDN_F32) {
+            if (stream_states) hipLaunchKernelGGL((gdn_decode_kernel<float, 64, 64, true>), grid, dim3(256), 0, stream, a, ids);
+            else hipLaunchKernelGGL((gdn_decode_kernel<float, 64, 64, false>), grid, dim3(256), 0, stream, a, ids);
+        } else if (s.d_k == 64) {
+            if (stream_states) hipLaunchKernelGGL((gdn_decode_kernel<half_t, 64, 64, true>), grid, dim3(256), 0, stream, a, ids);
+            else hipLaunchKernelGGL((gdn_decode_kernel<half_t, 64, 64, false>), grid, dim3(256), 0, stream, a, ids);
+        } else {
+            if (stream_states) hipLaunchKernelGGL((gdn_decode_kernel<half_t, 128, 128, true>), grid, dim3(256), 0, stream, a, ids);
+            else hipLaunchKernelGGL((gdn_decode_kernel<half_t, 128, 128, false>), grid, dim3(256), 0, stream, a, ids);
+        }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_err(e);
     }
