@@ -67,6 +67,23 @@ __device__ __forceinline__ F8 load8(const float* p) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
     return F8{{a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w}};
 }
+// The same for data that is read once (non-temporal loads).
+typedef uint32_t lu32x4 __attribute__((ext_vector_type(4)));
+typedef float lf32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ F8 load8_once(const uint16_t* p) {
+    const lu32x4 r = __builtin_nontemporal_load(reinterpret_cast<const lu32x4*>(p));
+    F8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o.f[2 * i] = __uint_as_float(r[i] << 16);
+        o.f[2 * i + 1] = __uint_as_float(r[i] & 0xffff0000u);
+    }
+    return o;
+}
+__device__ __forceinline__ F8 load8_once(const float* p) {
+    const lf32x4 a = __builtin_nontemporal_load(reinterpret_cast<const lf32x4*>(p)), b = __builtin_nontemporal_load(reinterpret_cast<const lf32x4*>(p) + 1);
+    return F8{{a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]}};
+}
 // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -299,8 +316,8 @@ __global__ void __launch_bounds__(LAYER_THREADS) gdn_layer_output_kernel(LayerOu
     if (gi >= a.n_groups) return;   // whole heads leave together
     const int c0 = (int)(gi % (a.d_v / 8)) * 8;
     const int64_t lo = (int64_t)blockIdx.y * a.ls_tok;   // this block's layer
-    const F8 o = load8(reinterpret_cast<const O*>(a.o) + lo + gi * 8);
-    const F8 z = load8(reinterpret_cast<const In*>(a.z) + lo + gi * 8);
+    const F8 o = load8_once(reinterpret_cast<const O*>(a.o) + lo + gi * 8);   // o and z are not read again
+    const F8 z = load8_once(reinterpret_cast<const In*>(a.z) + lo + gi * 8);
     const F8 w = load8(a.weight + (int64_t)blockIdx.y * a.d_v + c0);
     float ss = 0.f;
 #pragma unroll
