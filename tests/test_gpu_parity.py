@@ -375,7 +375,8 @@ def decode_streams(rng, L, n_req, H_qk, H_v, d, dtype, gate_mode):
     (128, 2, 2, 1, "bf16", 1), (128, 2, 2, 1, "bf16", 5), (128, 2, 2, 1, "bf16", 300),      # 300: two launches
     (64, 2, 4, 2, "bf16", 1), (64, 2, 4, 2, "bf16", 5), (64, 2, 4, 2, "bf16", 300),
     (64, 2, 2, 1, "f32", 1), (64, 2, 2, 1, "f32", 5), (64, 2, 2, 1, "f32", 300),
-    (128, 4, 8, 1, "bf16", 1), (128, 4, 8, 1, "bf16", 5)])
+    (128, 4, 8, 1, "bf16", 1), (128, 4, 8, 1, "bf16", 5),
+    (128, 16, 16, 1, "bf16", 140), (64, 16, 32, 1, "f32", 270), (64, 8, 16, 2, "bf16", 270)])   # > 128 MiB of states: streamed (non-temporal) rows
 def test_decode_step_matches_the_token_loop(d, H_qk, H_v, L, dtype, n_req):
     """Two decode steps in a row (the second reads the states the first wrote in place) against
     the oracle's token loop run over both tokens; fp32 arithmetic on exactly widened inputs,
